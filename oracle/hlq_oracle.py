@@ -1,0 +1,253 @@
+"""ctypes front-end of ``hlq_oracle.c`` -- TEST INFRASTRUCTURE, not product code.
+
+Every function takes and returns numpy arrays (fp32 inputs; bf16 data is passed
+widened to fp32, which is exact) and calls straight into the C file next to it.
+Section/equation references are those of arXiv 2406.15102.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hlq_oracle.c")
+_LIB = os.path.join(_HERE, "libhlq_oracle.so")
+
+__all__ = [
+    "build", "num_threads", "hadamard", "coeff_f32", "coeff_f64", "transform_rows",
+    "transform_cols", "stream_key", "rand_word", "rand_byte", "quantize_one", "quantize_rows",
+    "int_gemm_nt", "dequant", "hla_f32", "hla_f64", "round_bf16", "gemm_nt_f64",
+    "linear_backward",
+]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP over independent rows, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"]
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        lib = C.CDLL(build())
+        i8p, f32p, f64p, i32p = (C.POINTER(C.c_int8), C.POINTER(C.c_float), C.POINTER(C.c_double),
+                                 C.POINTER(C.c_int32))
+        lib.hlqo_num_threads.restype = C.c_int
+        lib.hlqo_hadamard.argtypes = [C.c_int, i8p]
+        lib.hlqo_coeff_f32.argtypes = [C.c_int, f32p, C.c_long, C.c_int, f32p]
+        lib.hlqo_coeff_f64.argtypes = [C.c_int, f32p, C.c_long, C.c_int, f64p]
+        lib.hlqo_transform_rows.argtypes = [f32p, C.c_long, C.c_long, C.c_int, f32p]
+        lib.hlqo_transform_cols.argtypes = [f32p, C.c_long, C.c_long, C.c_int, f32p]
+        lib.hlqo_stream_key.argtypes = [C.c_uint64, C.c_uint32]
+        lib.hlqo_stream_key.restype = C.c_uint64
+        lib.hlqo_rand_word.argtypes = [C.c_uint64, C.c_uint32]
+        lib.hlqo_rand_word.restype = C.c_uint32
+        lib.hlqo_rand_byte.argtypes = [C.c_uint64, C.c_long, C.c_long, C.c_long]
+        lib.hlqo_rand_byte.restype = C.c_uint32
+        lib.hlqo_quantize_one.argtypes = [C.c_float, C.c_float, C.c_uint32]
+        lib.hlqo_quantize_one.restype = C.c_int8
+        lib.hlqo_quantize_rows.argtypes = [f32p, C.c_long, C.c_long, C.c_uint64, C.c_uint32, i8p, f32p]
+        lib.hlqo_int_gemm_nt.argtypes = [i8p, i8p, C.c_long, C.c_long, C.c_long, i32p]
+        lib.hlqo_dequant.argtypes = [i32p, f32p, f32p, C.c_long, C.c_long, C.c_int, f64p]
+        lib.hlqo_hla_f32.argtypes = [f32p, C.c_long, C.c_long, C.c_int, C.c_int, f32p]
+        lib.hlqo_hla_f64.argtypes = [f32p, C.c_long, C.c_long, C.c_int, C.c_int, f64p]
+        lib.hlqo_round_bf16.argtypes = [C.c_float]
+        lib.hlqo_round_bf16.restype = C.c_float
+        lib.hlqo_round_bf16_array.argtypes = [f32p, C.c_long, f32p]
+        lib.hlqo_round_bf16_array.restype = None
+        lib.hlqo_gemm_nt_f64.argtypes = [f32p, f32p, C.c_long, C.c_long, C.c_long, C.c_double, f64p]
+        lib.hlqo_linear_backward.argtypes = [f32p, f32p, f32p, C.c_long, C.c_long, C.c_long, C.c_int,
+                                             C.c_int, C.c_uint64, f64p, f64p, i8p, f32p, i8p, f32p,
+                                             i32p, f32p, f32p]
+        _lib = lib
+    return _lib
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(C.POINTER(ct)) if a is not None else None
+
+
+def _f32(a):
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _i8(a):
+    return np.ascontiguousarray(a, dtype=np.int8)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise ValueError("%s: oracle rejected the arguments (rc=%d)" % (what, rc))
+
+
+def num_threads() -> int:
+    return int(_L().hlqo_num_threads())
+
+
+def hadamard(B: int) -> np.ndarray:
+    """+-1 Sylvester matrix of order B (Eq. 2 without the per-level 1/sqrt 2)."""
+    H = np.zeros((B, B), dtype=np.int8)
+    _check(_L().hlqo_hadamard(B, _p(H, C.c_int8)), "hadamard")
+    return H
+
+
+def coeff_f32(v, B: int, nout: int | None = None) -> np.ndarray:
+    v = _f32(v)
+    nout = B if nout is None else nout
+    c = np.zeros(nout, dtype=np.float32)
+    _check(_L().hlqo_coeff_f32(B, _p(v, C.c_float), 1, nout, _p(c, C.c_float)), "coeff_f32")
+    return c
+
+
+def coeff_f64(v, B: int, nout: int | None = None) -> np.ndarray:
+    v = _f32(v)
+    nout = B if nout is None else nout
+    c = np.zeros(nout, dtype=np.float64)
+    _check(_L().hlqo_coeff_f64(B, _p(v, C.c_float), 1, nout, _p(c, C.c_double)), "coeff_f64")
+    return c
+
+
+def transform_rows(G, B: int) -> np.ndarray:
+    """G . H_O : block-diagonal transform along the contiguous (out-feature) axis."""
+    G = _f32(G)
+    N, O = G.shape
+    out = np.empty_like(G)
+    _check(_L().hlqo_transform_rows(_p(G, C.c_float), N, O, B, _p(out, C.c_float)), "transform_rows")
+    return out
+
+
+def transform_cols(W, B: int) -> np.ndarray:
+    """(H_O^T . W)^T : transform along W's row (out-feature) axis, returned as [d_in, d_out]."""
+    W = _f32(W)
+    O, I = W.shape
+    out = np.empty((I, O), dtype=np.float32)
+    _check(_L().hlqo_transform_cols(_p(W, C.c_float), O, I, B, _p(out, C.c_float)), "transform_cols")
+    return out
+
+
+def stream_key(seed: int, tensor: int) -> int:
+    return int(_L().hlqo_stream_key(seed, tensor))
+
+
+def rand_word(key: int, counter: int) -> int:
+    return int(_L().hlqo_rand_word(key, counter))
+
+
+def rand_byte(key: int, row: int, pos: int, K: int) -> int:
+    return int(_L().hlqo_rand_byte(key, row, pos, K))
+
+
+def quantize_one(x: float, inv: float, byte: int) -> int:
+    return int(_L().hlqo_quantize_one(float(np.float32(x)), float(np.float32(inv)), byte))
+
+
+def quantize_rows(Cm, seed: int, tensor: int):
+    """4-bit stochastic absmax quantiser, one scale per row -> (codes int8, scales fp32)."""
+    Cm = _f32(Cm)
+    rows, K = Cm.shape
+    q = np.empty((rows, K), dtype=np.int8)
+    s = np.empty(rows, dtype=np.float32)
+    _check(_L().hlqo_quantize_rows(_p(Cm, C.c_float), rows, K, seed, tensor, _p(q, C.c_int8),
+                                   _p(s, C.c_float)), "quantize_rows")
+    return q, s
+
+
+def int_gemm_nt(A, Bm) -> np.ndarray:
+    A, Bm = _i8(A), _i8(Bm)
+    M, K = A.shape
+    Nn, K2 = Bm.shape
+    assert K == K2
+    acc = np.empty((M, Nn), dtype=np.int32)
+    _check(_L().hlqo_int_gemm_nt(_p(A, C.c_int8), _p(Bm, C.c_int8), M, Nn, K, _p(acc, C.c_int32)),
+           "int_gemm_nt")
+    return acc
+
+
+def dequant(acc, sA, sB, B: int) -> np.ndarray:
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    sA, sB = _f32(sA), _f32(sB)
+    M, Nn = acc.shape
+    out = np.empty((M, Nn), dtype=np.float64)
+    _check(_L().hlqo_dequant(_p(acc, C.c_int32), _p(sA, C.c_float), _p(sB, C.c_float), M, Nn, B,
+                             _p(out, C.c_double)), "dequant")
+    return out
+
+
+def hla_f32(T, B: int, r: int) -> np.ndarray:
+    """First r Hadamard coefficients of every block of B tokens -> [D, N/B*r] fp32."""
+    T = _f32(T)
+    N, D = T.shape
+    out = np.empty((D, N // B * r), dtype=np.float32)
+    _check(_L().hlqo_hla_f32(_p(T, C.c_float), N, D, B, r, _p(out, C.c_float)), "hla_f32")
+    return out
+
+
+def hla_f64(T, B: int, r: int) -> np.ndarray:
+    T = _f32(T)
+    N, D = T.shape
+    out = np.empty((D, N // B * r), dtype=np.float64)
+    _check(_L().hlqo_hla_f64(_p(T, C.c_float), N, D, B, r, _p(out, C.c_double)), "hla_f64")
+    return out
+
+
+def round_bf16(x) -> np.ndarray:
+    """Round fp32 values to the nearest bfloat16 (ties to even), returned widened to fp32."""
+    x = _f32(x)
+    y = np.empty_like(x)
+    _L().hlqo_round_bf16_array(_p(x, C.c_float), x.size, _p(y, C.c_float))
+    return y
+
+
+def gemm_nt_f64(A, Bm, alpha: float = 1.0) -> np.ndarray:
+    A, Bm = _f32(A), _f32(Bm)
+    M, K = A.shape
+    Nn, K2 = Bm.shape
+    assert K == K2
+    out = np.empty((M, Nn), dtype=np.float64)
+    _check(_L().hlqo_gemm_nt_f64(_p(A, C.c_float), _p(Bm, C.c_float), M, Nn, K, alpha,
+                                 _p(out, C.c_double)), "gemm_nt_f64")
+    return out
+
+
+def linear_backward(G, X, W, B: int, r: int, seed: int, want_dX: bool = True, want_dW: bool = True,
+                    intermediates: bool = False):
+    """The whole HLQ backward pass (Sec. 6.1, both six-stage lists) -> dict of fp64/int arrays."""
+    G, X, W = _f32(G), _f32(X), _f32(W)
+    N, O = G.shape
+    N2, I = X.shape
+    O2, I2 = W.shape
+    assert N == N2 and O == O2 and I == I2
+    Kc = N // B * r
+    out = {}
+    dX = np.empty((N, I), dtype=np.float64) if want_dX else None
+    dW = np.empty((O, I), dtype=np.float64) if want_dW else None
+    Gq = sG = Wq = sW = acc = gh = xh = None
+    if intermediates and want_dX:
+        Gq = np.empty((N, O), dtype=np.int8)
+        sG = np.empty(N, dtype=np.float32)
+        Wq = np.empty((I, O), dtype=np.int8)
+        sW = np.empty(I, dtype=np.float32)
+        acc = np.empty((N, I), dtype=np.int32)
+    if intermediates and want_dW:
+        gh = np.empty((O, Kc), dtype=np.float32)
+        xh = np.empty((I, Kc), dtype=np.float32)
+    rc = _L().hlqo_linear_backward(
+        _p(G, C.c_float), _p(X, C.c_float), _p(W, C.c_float), N, I, O, B, r, seed,
+        _p(dX, C.c_double), _p(dW, C.c_double), _p(Gq, C.c_int8), _p(sG, C.c_float),
+        _p(Wq, C.c_int8), _p(sW, C.c_float), _p(acc, C.c_int32), _p(gh, C.c_float),
+        _p(xh, C.c_float))
+    _check(rc, "linear_backward")
+    out.update(dX=dX, dW=dW, Gq=Gq, sG=sG, Wq=Wq, sW=sW, acc=acc, GhatT=gh, XhatT=xh)
+    return out

@@ -1,0 +1,104 @@
+"""Seeded synthetic inputs shaped like the layers HLQ (arXiv 2406.15102) is applied to.
+
+This module only draws random tensors; it contains none of the method's
+arithmetic.  Both the HIP path and the CPU oracle are fed from here so that
+they see the same bits.  The paper trains CNNs and ViTs on image datasets
+(Sec. 7); those are not needed to exercise one layer's backward pass, so each
+workload below is a stand-in with the layer's shape and a value distribution
+chosen to stress what the method is for: outlier channels in X, per-token
+spread in the output gradient, post-ReLU sparsity, heavy tails.
+
+Every second distribution argument is a standard deviation.  Values are drawn
+in fp32 with ``numpy.random.Generator(PCG64(seed))``, ``seed = 1000*id + k``
+(k: 0 = X, 1 = W, 2 = G, 3 = auxiliary choices), and rounded once to bf16 for
+the bf16 workloads, so the tensors handed out are exactly representable in the
+dtype they are labelled with.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+
+import numpy as np
+import torch
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    id: int
+    N: int          # tokens (batch x sequence, or batch x spatial positions)
+    d_in: int
+    d_out: int
+    B: int          # Hadamard block order
+    r: int          # kept bases per block
+    dtype: str      # "bf16" | "f32"
+    seed: int = 0   # stochastic-rounding seed handed to the backward call
+    desc: str = ""
+
+
+WORKLOADS = {
+    "c1": Workload("c1", 1, 256, 256, 256, 16, 8, "f32", 0,
+                   "small linear layer; X~N(0,1), W~N(0,.02), G~N(0,1e-3)"),
+    "c2": Workload("c2", 2, 64 * 197, 768, 3072, 16, 8, "bf16", 0,
+                   "ViT-B/16 MLP fc1; 2% of X channels x20; G per-token lognormal(0,.5) spread"),
+    "c3": Workload("c3", 3, 64 * 14 * 14, 2304, 256, 16, 8, "bf16", 0,
+                   "ResNet-50 stage-3 3x3 conv as im2col GEMM; X post-ReLU; W Kaiming-normal"),
+    "c4": Workload("c4", 4, 2 * 2048, 4096, 11008, 16, 8, "bf16", 0,
+                   "LLaMA-7B MLP up-proj; 0.5% of X channels x50; G per-token lognormal(0,1) spread"),
+    "c4_b32": Workload("c4_b32", 4, 2 * 2048, 4096, 11008, 32, 16, "bf16", 0, "c4 with B=32, r=16"),
+    "c4_b64": Workload("c4_b64", 4, 2 * 2048, 4096, 11008, 64, 32, "bf16", 0, "c4 with B=64, r=32"),
+    "c5_r4": Workload("c5_r4", 5, 8192, 28672, 8192, 32, 4, "bf16", 0,
+                      "70B-shaped MLP down-proj, one GPU's share; X Student-t(4)"),
+    "c5_r8": Workload("c5_r8", 5, 8192, 28672, 8192, 32, 8, "bf16", 0, "c5 with r=8"),
+    "c5_r16": Workload("c5_r16", 5, 8192, 28672, 8192, 32, 16, "bf16", 0, "c5 with r=16"),
+}
+
+
+def scaled(w: Workload, N: int | None = None, d_in: int | None = None, d_out: int | None = None,
+           **kw) -> Workload:
+    """Same recipe at another size (for parity cases the oracle finishes in seconds)."""
+    return replace(w, N=N or w.N, d_in=d_in or w.d_in, d_out=d_out or w.d_out, **kw)
+
+
+def _normal(rng, shape, std):
+    return rng.standard_normal(shape, dtype=np.float32) * np.float32(std)
+
+
+def generate(w: Workload, want=("X", "W", "G")):
+    """Return {"X": [N,d_in], "W": [d_out,d_in], "G": [N,d_out]} as CPU torch tensors of w.dtype."""
+    out = {}
+    base = 1000 * w.id
+    aux = np.random.Generator(np.random.PCG64(base + 3))
+    if "X" in want:
+        rng = np.random.Generator(np.random.PCG64(base + 0))
+        if w.id == 3:
+            X = np.maximum(_normal(rng, (w.N, w.d_in), 1.0), np.float32(0))
+        elif w.id == 5:
+            X = rng.standard_t(4.0, size=(w.N, w.d_in)).astype(np.float32)
+        else:
+            X = _normal(rng, (w.N, w.d_in), 1.0)
+            if w.id in (2, 4):
+                frac, gain = (0.02, 20.0) if w.id == 2 else (0.005, 50.0)
+                n_out = max(1, int(round(frac * w.d_in)))
+                ch = aux.choice(w.d_in, size=n_out, replace=False)
+                X[:, ch] *= np.float32(gain)
+        out["X"] = X
+    if "W" in want:
+        rng = np.random.Generator(np.random.PCG64(base + 1))
+        std = {1: 0.02, 2: 0.02, 3: float(np.sqrt(2.0 / w.d_in)), 4: 0.02, 5: 0.01}[w.id]
+        out["W"] = _normal(rng, (w.d_out, w.d_in), std)
+    if "G" in want:
+        rng = np.random.Generator(np.random.PCG64(base + 2))
+        std = {1: 1e-3, 2: 1e-3, 3: 1e-3, 4: 1e-4, 5: 1e-4}[w.id]
+        G = _normal(rng, (w.N, w.d_out), std)
+        if w.id in (2, 4):
+            sigma = 0.5 if w.id == 2 else 1.0
+            G *= np.exp(np.float32(sigma) * rng.standard_normal((w.N, 1), dtype=np.float32))
+        out["G"] = G
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    return {k: torch.from_numpy(v).to(tdt) for k, v in out.items()}
+
+
+def as_f32_numpy(t: torch.Tensor) -> np.ndarray:
+    """Widen (exactly) to fp32 numpy, the form the CPU oracle takes."""
+    return t.detach().to("cpu", torch.float32).contiguous().numpy()

@@ -1,0 +1,180 @@
+"""Pins for the oracle's random stream and 4-bit stochastic quantiser (CPU only)."""
+import numpy as np
+import pytest
+
+import oracle
+
+M32 = (1 << 32) - 1
+
+# First five outputs of the SplitMix64 generator seeded with 1234567, as published with the
+# algorithm's reference implementation (Vigna, splitmix64.c, public domain; the same five values
+# are the check values of the "Pseudo-random numbers/Splitmix64" task on Rosetta Code).
+SPLITMIX64_SEED_1234567 = [
+    6457827717110365317,
+    3203168211198807973,
+    9817491932198370423,
+    4593380528125082431,
+    16408922859458223821,
+]
+
+
+def test_stream_key_is_splitmix64():
+    # key(seed, t) is defined as output number t+1 of SplitMix64 started at `seed`
+    for t, want in enumerate(SPLITMIX64_SEED_1234567):
+        assert oracle.stream_key(1234567, t) == want
+    assert oracle.stream_key(0, 0) != oracle.stream_key(0, 1)
+
+
+def _unmix(y, key):
+    """Inverse of the word mixer, from the modular inverses of its multipliers: if this undoes
+    rand_word for every probe, the mixer is the bijection of the counter it is documented to be
+    (distinct counters can never share a word)."""
+    k0, k1 = key & M32, key >> 32
+    inv1 = pow(0x7FEB352D, -1, 1 << 32)
+    inv2 = pow(0x846CA68B, -1, 1 << 32)
+    x = y
+    x ^= x >> 16
+    x = (x * inv2) & M32
+    x ^= k1
+    x ^= (x >> 15) ^ (x >> 30)
+    x = (x * inv1) & M32
+    x ^= x >> 16
+    return x ^ k0
+
+
+def test_rand_word_is_a_keyed_bijection():
+    rng = np.random.default_rng(0)
+    for key in (0, oracle.stream_key(0, 0), oracle.stream_key(0, 1), (1 << 64) - 1):
+        for c in [0, 1, 2, M32, 0x80000000] + [int(x) for x in rng.integers(0, 1 << 32, 200)]:
+            assert _unmix(oracle.rand_word(key, c), key) == c
+
+
+def test_rand_word_avalanche():
+    # flipping any one counter bit flips every output bit with probability ~1/2
+    rng = np.random.default_rng(1)
+    key = oracle.stream_key(0, 0)
+    n = 4000
+    cs = rng.integers(0, 1 << 32, n, dtype=np.uint64)
+    base = np.array([oracle.rand_word(key, int(c)) for c in cs], dtype=np.uint64)
+    worst = 0.0
+    for bit in range(32):
+        fl = np.array([oracle.rand_word(key, int(c) ^ (1 << bit)) for c in cs], dtype=np.uint64)
+        d = base ^ fl
+        for ob in range(32):
+            p = np.mean((d >> np.uint64(ob)) & np.uint64(1))
+            worst = max(worst, abs(p - 0.5))
+    assert worst < 0.05  # ~6 sigma for n = 4000
+
+
+def test_rand_word_sequential_counters_look_uniform():
+    # the quantiser walks consecutive counters; bytes of consecutive words must be uniform
+    # (chi-square over 256 bins) and adjacent words uncorrelated
+    key = oracle.stream_key(0, 1)
+    n = 1 << 15
+    w = np.array([oracle.rand_word(key, c) for c in range(n)], dtype=np.uint64)
+    for sh in (0, 8, 16, 24):
+        b = ((w >> np.uint64(sh)) & np.uint64(0xFF)).astype(np.int64)
+        counts = np.bincount(b, minlength=256)
+        chi2 = np.sum((counts - n / 256) ** 2 / (n / 256))
+        assert chi2 < 255 + 6 * np.sqrt(2 * 255)
+    u = (w & np.uint64(0xFF)).astype(np.float64)
+    assert abs(np.corrcoef(u[:-1], u[1:])[0, 1]) < 0.03
+    # streams of the two operands differ
+    w0 = np.array([oracle.rand_word(oracle.stream_key(0, 0), c) for c in range(256)], dtype=np.uint64)
+    assert np.mean(w0 == w[:256]) < 0.05
+
+
+def test_rand_byte_indexing():
+    key = oracle.stream_key(3, 0)
+    K = 24
+    for row, pos in [(0, 0), (0, 3), (0, 4), (5, 17), (9, 23)]:
+        word = oracle.rand_word(key, row * (K // 4) + pos // 4)
+        assert oracle.rand_byte(key, row, pos, K) == (word >> (8 * (pos % 4))) & 0xFF
+
+
+def test_quantize_one_is_stochastic_rounding():
+    # exact integers are reproduced whatever the random byte is
+    for k in range(-7, 8):
+        for byte in (0, 1, 127, 128, 255):
+            assert oracle.quantize_one(float(k), 1.0, byte) == k
+    # a value with fraction f goes up for exactly the bytes with u >= 1 - f: monotone in the byte,
+    # and the number of "up" bytes is 256*f (+-1 for the half-step offset): unbiased to 2^-9
+    for x in (0.25, 2.5, -3.125, 6.9, -6.9, 0.001):
+        codes = [oracle.quantize_one(x, 1.0, b) for b in range(256)]
+        assert all(codes[i] <= codes[i + 1] for i in range(255))
+        lo = int(np.floor(x))
+        assert set(codes) <= {lo, lo + 1}
+        ups = sum(c == lo + 1 for c in codes)
+        assert abs(ups - 256 * (x - lo)) <= 1
+    # clamp: out-of-range inputs saturate at +-7
+    assert oracle.quantize_one(100.0, 1.0, 0) == 7
+    assert oracle.quantize_one(-100.0, 1.0, 255) == -7
+
+
+@pytest.mark.parametrize("tensor", [0, 1])
+def test_quantize_rows_invariants(tensor):
+    rng = np.random.default_rng(2)
+    rows, K = 40, 96
+    Cm = (rng.standard_normal((rows, K)) * np.exp(rng.standard_normal((rows, 1)) * 3)).astype(np.float32)
+    Cm[7] = 0.0                      # a zero row
+    Cm[8] = 0.0
+    Cm[8, 5] = -2.5                  # a single non-zero
+    q, s = oracle.quantize_rows(Cm, seed=11, tensor=tensor)
+    assert q.dtype == np.int8 and np.max(np.abs(q)) <= 7
+    a = np.max(np.abs(Cm), axis=1)
+    assert np.array_equal(s, (a / np.float32(7.0)).astype(np.float32))   # scale = absmax/7
+    assert not q[7].any() and s[7] == 0.0
+    assert q[8, 5] == -7 and np.count_nonzero(q[8]) <= K
+    nz = a > 0
+    # the absmax element always lands on +-7 ...
+    assert np.all(np.max(np.abs(q[nz]), axis=1) == 7)
+    idx = np.argmax(np.abs(Cm), axis=1)
+    assert np.all(q[np.arange(rows), idx][nz] == (7 * np.sign(Cm[np.arange(rows), idx]))[nz])
+    # ... and every element is within one step of its value (stochastic rounding never moves further)
+    err = np.abs(q.astype(np.float64) * s[:, None].astype(np.float64) - Cm.astype(np.float64))
+    assert np.all(err[nz] < s[nz, None] * (1 + 1e-6))
+    # codes are exactly floor(x*inv + u) with the stream's byte: recompute a few by hand in numpy
+    key = oracle.stream_key(11, tensor)
+    for (rw, k) in [(0, 0), (3, 17), (39, 95), (20, 50)]:
+        inv = np.float32(7.0) / a[rw]
+        u = (oracle.rand_byte(key, rw, k, K) + 0.5) / 256.0
+        t = np.float64(Cm[rw, k]) * np.float64(inv) + u     # exact in fp64, then one fp32 rounding
+        assert q[rw, k] == int(np.clip(np.floor(np.float32(t)), -7, 7))
+
+
+def test_quantizer_is_unbiased_over_seeds():
+    # Sec. 6.1: the quantiser must be an unbiased estimator; the mean over S seeds of the
+    # dequantised codes converges to the input like 1/sqrt(S)
+    rng = np.random.default_rng(3)
+    rows, K = 8, 64
+    Cm = rng.standard_normal((rows, K)).astype(np.float32)
+    errs = []
+    for S in (4, 64, 1024):
+        acc = np.zeros((rows, K))
+        for seed in range(S):
+            q, s = oracle.quantize_rows(Cm, seed=seed, tensor=0)
+            acc += q.astype(np.float64) * s[:, None]
+        errs.append(np.sqrt(np.mean((acc / S - Cm) ** 2)))
+    step = np.mean(np.max(np.abs(Cm), axis=1) / 7)
+    assert errs[0] < 0.5 * step                       # S=4: below the deterministic-rounding error
+    assert errs[1] < errs[0] / 2.5 and errs[2] < errs[1] / 2.5
+    assert errs[2] < 0.02 * step                      # no bias floor visible at S = 1024
+
+
+def test_clamp_never_engages_on_quantize_rows():
+    # t = x*inv + u lies in (-7, 8) by construction, so floor(t) is already in [-7, 7];
+    # the clamp of the definition is a guard, not a behaviour (checked on adversarial rows)
+    rng = np.random.default_rng(4)
+    Cm = rng.standard_normal((64, 64)).astype(np.float32)
+    Cm[:, 0] = np.max(np.abs(Cm), axis=1) * np.where(rng.random(64) < 0.5, -1, 1)  # ties at +-absmax
+    Cm[:, 1] = -Cm[:, 0]
+    for seed in range(8):
+        q, s = oracle.quantize_rows(Cm, seed=seed, tensor=1)
+        a = np.max(np.abs(Cm), axis=1)
+        inv = (np.float32(7.0) / a).astype(np.float32)
+        key = oracle.stream_key(seed, 1)
+        for rw in range(0, 64, 7):
+            for k in (0, 1):
+                u = (oracle.rand_byte(key, rw, k, 64) + 0.5) / 256.0
+                t = np.float32(np.float64(Cm[rw, k]) * np.float64(inv[rw]) + u)
+                assert -7.0 <= np.floor(t) <= 7.0
