@@ -1,0 +1,161 @@
+/*
+ * hlq.h -- C ABI of the MI355X (gfx950) HLQ backward-pass library.
+ *
+ * HLQ = Hadamard Low-rank Quantization (arXiv 2406.15102): the backward pass of a linear
+ * (or im2col'd convolution) layer y = x w^T (Sec. 3.1, Eq. 1) computed as
+ *
+ *   dX = Q(G H_O) . Q(H_O^T W)          activation gradient, Sec. 5.1 and the six g_x stages of Sec. 6.1
+ *   dW = (G^T H_L^T)(H_L X), r of B      weight gradient, Sec. 4 / 5.1 and stages 1, 3, 5 of the six
+ *        bases kept per token block      g_w stages of Sec. 6.1 (operands kept in bf16, not int8)
+ *
+ * with the block-diagonal Walsh-Hadamard transform of Sec. 3.2 and the 4-bit stochastic
+ * quantiser of Sec. 5.1 / 6.1.
+ *
+ * Notation (paper -> here): tokens B*L -> N; I -> d_in; O -> d_out; Hadamard order n -> B;
+ * kept bases r -> r.  G = g_y as [N, d_out], X = x as [N, d_in], W = w as [d_out, d_in].
+ *
+ * General conventions
+ *   - Every tensor argument is a DEVICE pointer to a dense row-major array owned by the caller,
+ *     16-byte aligned; the library reads inputs, writes outputs, keeps no reference after return.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it; no call synchronises the device.  Except where noted, no call allocates.
+ *   - `dtype` selects the element type of G, X, W and of dX, dW: HLQ_BF16 or HLQ_F32.
+ *     Arithmetic is fp32 (transforms, scales), int8 x int8 -> int32 (dX product) and
+ *     bf16 x bf16 -> fp32 (dW product) whatever the dtype.
+ *   - Every function returns an hlq_status.  On any status other than HLQ_OK nothing has been
+ *     enqueued and no output byte is written (HLQ_ERR_LAUNCH excepted: an earlier kernel of the
+ *     same call may already be queued).
+ *   - Same inputs and seed give bit-identical outputs on every call.
+ *
+ * Shape rules (violations give the listed status)
+ *   B in {16, 32, 64}                               HLQ_ERR_BLOCK
+ *   r a power of two, 1 <= r <= B                   HLQ_ERR_RANK
+ *   N > 0, N % B == 0; d_out > 0, d_out % B == 0, d_out <= 65536;
+ *   d_in > 0, d_in % 8 == 0; (N / B * r) % 8 == 0;
+ *   N * d_out / 4 < 2^32 and d_in * d_out / 4 < 2^32 (random-stream counters)     HLQ_ERR_SHAPE
+ */
+#ifndef HLQ_H_
+#define HLQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum hlq_status {
+    HLQ_OK = 0,
+    HLQ_ERR_NULL = 1,      /* a required pointer is NULL */
+    HLQ_ERR_SHAPE = 2,     /* a size breaks the shape rules above */
+    HLQ_ERR_BLOCK = 3,     /* B not in {16, 32, 64} */
+    HLQ_ERR_RANK = 4,      /* r not a power of two in [1, B] */
+    HLQ_ERR_DTYPE = 5,     /* dtype not HLQ_BF16 / HLQ_F32 */
+    HLQ_ERR_WORKSPACE = 6, /* workspace too small, misaligned, or could not be allocated */
+    HLQ_ERR_LAUNCH = 7     /* the HIP runtime refused a launch */
+} hlq_status;
+
+typedef enum hlq_dtype { HLQ_BF16 = 0, HLQ_F32 = 1 } hlq_dtype;
+
+/* Human-readable name of a status (static string, never NULL). */
+const char *hlq_status_str(int status);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int hlq_version(void);
+
+/*
+ * Bytes of device scratch hlq_linear_backward_ex needs for this problem (quantised operands,
+ * scales, partial column maxima, HLA-compressed operands).  Returns 0 if the shape is invalid.
+ * `x_is_compressed` != 0 sizes it for a call that passes XhatT instead of X.
+ */
+size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r, int x_is_compressed);
+
+/*
+ * The whole backward pass of one layer for bf16 tensors (both stage lists of Sec. 6.1):
+ *   dX [N, d_in]     = dequant( Q4(G H) . Q4(H^T W) )        stages 1-6 of the g_x list
+ *   dW [d_out, d_in] = (1/B) . HLA_r(G)^T . HLA_r(X)          stages 1, 3, 5 of the g_w list
+ * `seed` selects the stochastic-rounding stream (same seed -> same bits).
+ * Scratch memory is owned by the library: it is allocated with hipMalloc on the first call on a
+ * device and again only when a later call needs more (such a call synchronises that allocation;
+ * it must not run under stream capture).  Use hlq_linear_backward_ex with a caller workspace for
+ * a call that never allocates.  Calls that share the library workspace must not overlap on one
+ * device.
+ */
+int hlq_linear_backward(const void *G, const void *X, const void *W, int64_t N, int64_t d_in,
+                        int64_t d_out, int B, int r, uint64_t seed, void *dX, void *dW, void *stream);
+
+/*
+ * As above with every option spelled out.
+ *   X      [N, d_in] or NULL;  XhatT [d_in, N/B*r] bf16 or NULL: exactly one of the two when dW is
+ *          wanted.  XhatT is what hlq_compress_act stored at forward time (ACBP, Sec. 6.1).
+ *   dX, dW either may be NULL to skip that half (X/XhatT may then be NULL when dW is NULL, and
+ *          W may be NULL when dX is NULL).
+ *   workspace  device memory of at least hlq_workspace_bytes(...) bytes, 256-byte aligned, or
+ *          NULL to use the library-owned workspace described above.
+ */
+int hlq_linear_backward_ex(const void *G, const void *X, const void *XhatT, const void *W, int64_t N,
+                           int64_t d_in, int64_t d_out, int B, int r, uint64_t seed, int dtype,
+                           void *dX, void *dW, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Activation compression for backward propagation (ACBP, Sec. 6.1): stage 1 of the g_w list
+ * applied to X at forward time.  For token block b and feature j,
+ *   XhatT[j, b*r + k] = bf16( sum_n H[k][n] X[b*B + n, j] ),  k < r,
+ * H the +-1 natural-order Walsh-Hadamard matrix of order B (Sec. 3.2), i.e. the first r of every
+ * B coefficients, stored [d_in, N/B*r] bf16 with the compressed token axis contiguous.
+ */
+int hlq_compress_act(const void *X, int64_t N, int64_t d_in, int B, int r, int dtype, void *XhatT,
+                     void *stream);
+
+/* ---- stage entry points (the steps above one by one; also what the parity tests probe) ---- */
+
+/*
+ * Stages 1-2 of the g_x list: block Hadamard transform of every row of G along d_out, then
+ * 4-bit stochastic quantisation with one absmax scale per row.
+ *   Gq [N, d_out] int8, codes in [-7, 7];  sG [N] fp32, sG[n] = max|coef|/7.
+ *   coeff: NULL, or [N, d_out] fp32 receiving the transformed values (unnormalised H).
+ */
+int hlq_quantize_g(const void *G, int64_t N, int64_t d_out, int B, uint64_t seed, int dtype,
+                   int8_t *Gq, float *sG, float *coeff, void *stream);
+
+/*
+ * Stages 3-4 of the g_x list: H^T W (blocks of B consecutive rows of W are mixed), quantised
+ * with one scale per in-feature and stored transposed, reduction axis contiguous:
+ *   WqT [d_in, d_out] int8;  sW [d_in] fp32;  coeffT: NULL or [d_in, d_out] fp32.
+ *   workspace: >= hlq_quantize_w_workspace_bytes(d_out, d_in) bytes of device scratch (256-aligned).
+ */
+size_t hlq_quantize_w_workspace_bytes(int64_t d_out, int64_t d_in);
+int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t seed, int dtype,
+                   int8_t *WqT, float *sW, float *coeffT, void *workspace, size_t workspace_bytes,
+                   void *stream);
+
+/*
+ * Stages 5-6 of the g_x list: C[m, n] = alpha * sA[m] * sB[n] * sum_k A[m,k] * Bm[n,k], the sum
+ * exact in int32 (int8 MFMA).  A [M, K] int8, Bm [Nn, K] int8, K % 16 == 0, Nn % 4 == 0.
+ *   out_dtype HLQ_BF16 / HLQ_F32 selects the type of C [M, Nn]; C may be NULL.
+ *   acc: NULL or [M, Nn] int32 receiving the raw accumulators.  sA, sB may be NULL (= all ones).
+ */
+int hlq_int8_gemm_nt(const int8_t *A, const int8_t *Bm, int64_t M, int64_t Nn, int64_t K,
+                     const float *sA, const float *sB, float alpha, int out_dtype, void *C,
+                     int32_t *acc, void *stream);
+
+/*
+ * Stages 1 and 3 of the g_w list for any [N, D] tensor T (G or X): the projection described at
+ * hlq_compress_act.  ThatT [D, N/B*r] bf16;  coeffT: NULL or [D, N/B*r] fp32 receiving the
+ * coefficients before rounding to bf16.
+ */
+int hlq_hla_project(const void *T, int64_t N, int64_t D, int B, int r, int dtype, void *ThatT,
+                    float *coeffT, void *stream);
+
+/*
+ * Stage 5 of the g_w list: C[m, n] = alpha * sum_k A[m,k] * Bm[n,k], bf16 inputs, fp32
+ * accumulation (bf16 MFMA).  A [M, K], Bm [Nn, K] bf16, K % 8 == 0, Nn % 4 == 0; C [M, Nn] of
+ * out_dtype.
+ */
+int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64_t K, float alpha,
+                     int out_dtype, void *C, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HLQ_H_ */

@@ -1,0 +1,177 @@
+"""ctypes binding of ``libhlq.so`` -- argument marshalling only.
+
+Each function has the name and argument order of its C entry point in ``include/hlq.h``;
+tensors are torch CUDA (ROCm) tensors whose ``data_ptr()`` is handed over together with the
+current torch stream.  Nothing is computed here, and there is no fallback: if the HIP library
+has not been built, importing the entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhlq.so")
+
+HLQ_BF16, HLQ_F32 = 0, 1
+HLQ_OK = 0
+
+_EXPORTS = {
+    "hlq_status_str": (C.c_char_p, [C.c_int]),
+    "hlq_version": (C.c_int, []),
+    "hlq_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int]),
+    "hlq_linear_backward": (C.c_int, [C.c_void_p] * 3 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64]
+                            + [C.c_void_p] * 3),
+    "hlq_linear_backward_ex": (C.c_int, [C.c_void_p] * 4 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64, C.c_int]
+                               + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]),
+    "hlq_compress_act": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                   C.c_void_p]),
+    "hlq_quantize_g": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_uint64, C.c_int, C.c_void_p,
+                                 C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hlq_quantize_w_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64]),
+    "hlq_quantize_w": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_uint64, C.c_int, C.c_void_p,
+                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "hlq_int8_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                   C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "hlq_hla_project": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                  C.c_void_p, C.c_void_p]),
+    "hlq_bf16_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_float, C.c_int,
+                                   C.c_void_p, C.c_void_p]),
+}
+
+_lib = None
+
+
+class HlqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, lib().hlq_status_str(status).decode()))
+
+
+def exported_symbols():
+    """Names every build of the library must export (one per declaration in hlq.h)."""
+    return sorted(_EXPORTS)
+
+
+def lib() -> C.CDLL:
+    """Load the HIP library; raises if it has not been built (there is no other code path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "HIP library %s not built: run `python -m paper_2406_15102_amd.build` "
+                "(there is no CPU fallback)" % LIB_PATH)
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in _EXPORTS.items():
+            fn = getattr(l, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = l
+    return _lib
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return HLQ_BF16
+    if t.dtype == torch.float32:
+        return HLQ_F32
+    raise TypeError("tensor dtype must be bfloat16 or float32, got %s" % t.dtype)
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("tensor must live on the GPU")
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous (dense row-major)")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("expected %s, got %s" % (dtype, t.dtype))
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != HLQ_OK:
+        raise HlqError(status, where)
+
+
+def hlq_version() -> int:
+    return int(lib().hlq_version())
+
+
+def hlq_status_str(status: int) -> str:
+    return lib().hlq_status_str(status).decode()
+
+
+def hlq_workspace_bytes(N, d_in, d_out, B, r, x_is_compressed=False) -> int:
+    return int(lib().hlq_workspace_bytes(N, d_in, d_out, B, r, int(bool(x_is_compressed))))
+
+
+def hlq_linear_backward(G, X, W, B, r, seed, dX, dW):
+    """dX, dW <- HLQ backward of one bf16 layer (library-owned workspace)."""
+    N, d_out = G.shape
+    d_in = W.shape[1]
+    for t in (G, X, W, dX, dW):
+        _ptr(t, torch.bfloat16)
+    assert X.shape == (N, d_in) and W.shape == (d_out, d_in) and dX.shape == (N, d_in) and dW.shape == (d_out, d_in)
+    _check(lib().hlq_linear_backward(_ptr(G), _ptr(X), _ptr(W), N, d_in, d_out, B, r, seed, _ptr(dX), _ptr(dW),
+                                     _stream()), "hlq_linear_backward")
+
+
+def hlq_linear_backward_ex(G, X, XhatT, W, N, d_in, d_out, B, r, seed, dX, dW, workspace=None):
+    """Full-option call; any of X / XhatT / W / dX / dW may be None as hlq.h allows."""
+    dt = _dt(G)
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (_ptr(workspace), workspace.numel() * workspace.element_size())
+    _check(lib().hlq_linear_backward_ex(_ptr(G), _ptr(X), _ptr(XhatT), _ptr(W), N, d_in, d_out, B, r, seed, dt,
+                                        _ptr(dX), _ptr(dW), ws_ptr, ws_bytes, _stream()), "hlq_linear_backward_ex")
+
+
+def hlq_compress_act(X, B, r, XhatT):
+    N, d_in = X.shape
+    _check(lib().hlq_compress_act(_ptr(X), N, d_in, B, r, _dt(X), _ptr(XhatT, torch.bfloat16), _stream()),
+           "hlq_compress_act")
+
+
+def hlq_quantize_g(G, B, seed, Gq, sG, coeff=None):
+    N, d_out = G.shape
+    _check(lib().hlq_quantize_g(_ptr(G), N, d_out, B, seed, _dt(G), _ptr(Gq, torch.int8), _ptr(sG, torch.float32),
+                                _ptr(coeff, torch.float32), _stream()), "hlq_quantize_g")
+
+
+def hlq_quantize_w_workspace_bytes(d_out, d_in) -> int:
+    return int(lib().hlq_quantize_w_workspace_bytes(d_out, d_in))
+
+
+def hlq_quantize_w(W, B, seed, WqT, sW, workspace, coeffT=None):
+    d_out, d_in = W.shape
+    _check(lib().hlq_quantize_w(_ptr(W), d_out, d_in, B, seed, _dt(W), _ptr(WqT, torch.int8), _ptr(sW, torch.float32),
+                                _ptr(coeffT, torch.float32), _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream()), "hlq_quantize_w")
+
+
+def hlq_int8_gemm_nt(A, Bm, sA, sB, alpha, C_out=None, acc=None):
+    M, K = A.shape
+    Nn = Bm.shape[0]
+    out_dt = _dt(C_out) if C_out is not None else HLQ_F32
+    _check(lib().hlq_int8_gemm_nt(_ptr(A, torch.int8), _ptr(Bm, torch.int8), M, Nn, K, _ptr(sA, torch.float32),
+                                  _ptr(sB, torch.float32), float(alpha), out_dt, _ptr(C_out), _ptr(acc, torch.int32),
+                                  _stream()), "hlq_int8_gemm_nt")
+
+
+def hlq_hla_project(T, B, r, ThatT, coeffT=None):
+    N, D = T.shape
+    _check(lib().hlq_hla_project(_ptr(T), N, D, B, r, _dt(T), _ptr(ThatT, torch.bfloat16),
+                                 _ptr(coeffT, torch.float32), _stream()), "hlq_hla_project")
+
+
+def hlq_bf16_gemm_nt(A, Bm, alpha, C_out):
+    M, K = A.shape
+    Nn = Bm.shape[0]
+    _check(lib().hlq_bf16_gemm_nt(_ptr(A, torch.bfloat16), _ptr(Bm, torch.bfloat16), M, Nn, K, float(alpha),
+                                  _dt(C_out), _ptr(C_out), _stream()), "hlq_bf16_gemm_nt")

@@ -1,0 +1,308 @@
+// C ABI of the library (declared in hlq.h): argument validation, workspace carving, stream-key
+// derivation and the launch sequence of the HLQ backward pass (arXiv 2406.15102, Sec. 6.1).
+#include "hlq.h"
+#include "hlq_kernels.hpp"
+
+#include <mutex>
+
+namespace {
+
+inline size_t up256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+inline bool is_pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Stream key for (seed, tensor): output number tensor+1 of SplitMix64 started at `seed`;
+// tensor 0 = the G operand, 1 = the W operand.  Low half keys the counter, high half the mixer.
+inline uint64_t stream_key(uint64_t seed, uint32_t tensor)
+{
+    uint64_t z = seed + (static_cast<uint64_t>(tensor) + 1u) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+int check_block(int B) { return (B == 16 || B == 32 || B == 64) ? HLQ_OK : HLQ_ERR_BLOCK; }
+int check_rank(int B, int r) { return (r >= 1 && r <= B && is_pow2(r)) ? HLQ_OK : HLQ_ERR_RANK; }
+int check_dtype(int dt) { return (dt == HLQ_BF16 || dt == HLQ_F32) ? HLQ_OK : HLQ_ERR_DTYPE; }
+
+// rows x K operand of the quantiser: K a multiple of B, K <= 65536 for the row kernel,
+// rows*K/4 random words addressable by a 32-bit counter
+int check_quant_shape(int64_t rows, int64_t K, int B)
+{
+    if (rows <= 0 || K <= 0 || K % B != 0 || K > 65536) return HLQ_ERR_SHAPE;
+    if (rows > (int64_t(1) << 31) - 1) return HLQ_ERR_SHAPE;
+    if (rows * (K / 4) >= (int64_t(1) << 32)) return HLQ_ERR_SHAPE;
+    return HLQ_OK;
+}
+
+int check_hla_shape(int64_t N, int64_t D, int B, int r)
+{
+    if (N <= 0 || D <= 0 || N % B != 0 || D % 8 != 0 || D > (int64_t(1) << 30)) return HLQ_ERR_SHAPE;
+    const int64_t Kc = N / B * r;
+    if (Kc % 8 != 0 || Kc > (int64_t(1) << 30)) return HLQ_ERR_SHAPE;
+    int nbw = 32 / r < 1 ? 1 : 32 / r;
+    if ((N / B + 4 * nbw - 1) / (4 * nbw) > 65535) return HLQ_ERR_SHAPE;
+    return HLQ_OK;
+}
+
+int check_gemm_shape(int64_t M, int64_t Nn, int64_t K, int kmult)
+{
+    if (M <= 0 || Nn <= 0 || K <= 0 || K % kmult != 0 || Nn % 4 != 0) return HLQ_ERR_SHAPE;
+    if (M > (int64_t(1) << 30) || Nn > (int64_t(1) << 30) || K > (int64_t(1) << 30)) return HLQ_ERR_SHAPE;
+    if (((M + 127) / 128) * ((Nn + 127) / 128) > (int64_t(1) << 30)) return HLQ_ERR_SHAPE;
+    return HLQ_OK;
+}
+
+int check_backward_shape(int64_t N, int64_t d_in, int64_t d_out, int B, int r)
+{
+    int rc;
+    if ((rc = check_block(B)) != HLQ_OK) return rc;
+    if ((rc = check_rank(B, r)) != HLQ_OK) return rc;
+    if (N <= 0 || d_in <= 0 || d_out <= 0) return HLQ_ERR_SHAPE;
+    if (d_in % 8 != 0) return HLQ_ERR_SHAPE;
+    if ((rc = check_quant_shape(N, d_out, B)) != HLQ_OK) return rc;
+    if ((rc = check_quant_shape(d_in, d_out, B)) != HLQ_OK) return rc;
+    if ((rc = check_hla_shape(N, d_in, B, r)) != HLQ_OK) return rc;
+    if ((rc = check_hla_shape(N, d_out, B, r)) != HLQ_OK) return rc;
+    if ((rc = check_gemm_shape(N, d_in, d_out, 16)) != HLQ_OK) return rc;
+    if ((rc = check_gemm_shape(d_out, d_in, N / B * r, 8)) != HLQ_OK) return rc;
+    return HLQ_OK;
+}
+
+// Carving of the backward workspace.
+struct Layout {
+    size_t Gq, sG, Wq, sW, wws, GhatT, XhatT, total;
+};
+
+Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_is_compressed)
+{
+    Layout L;
+    const size_t Kc = static_cast<size_t>(N / B * r);
+    size_t off = 0;
+    L.Gq = off;    off += up256(static_cast<size_t>(N) * d_out);
+    L.sG = off;    off += up256(static_cast<size_t>(N) * 4);
+    L.Wq = off;    off += up256(static_cast<size_t>(d_in) * d_out);
+    L.sW = off;    off += up256(static_cast<size_t>(d_in) * 4);
+    L.wws = off;   off += up256(hlq::quant_cols_ws_bytes(d_out, d_in));
+    L.GhatT = off; off += up256(static_cast<size_t>(d_out) * Kc * 2);
+    L.XhatT = off; off += x_is_compressed ? 0 : up256(static_cast<size_t>(d_in) * Kc * 2);
+    L.total = off;
+    return L;
+}
+
+// Library-owned workspace, one per device, grown on demand.
+constexpr int kMaxDevices = 64;
+std::mutex g_ws_mutex;
+void *g_ws_ptr[kMaxDevices] = {nullptr};
+size_t g_ws_bytes[kMaxDevices] = {0};
+
+int own_workspace(size_t bytes, void **out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HLQ_ERR_WORKSPACE;
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (g_ws_bytes[dev] < bytes) {
+        if (g_ws_ptr[dev]) {
+            // earlier calls may still be running on the old buffer
+            if (hipDeviceSynchronize() != hipSuccess) return HLQ_ERR_WORKSPACE;
+            (void)hipFree(g_ws_ptr[dev]);
+            g_ws_ptr[dev] = nullptr;
+            g_ws_bytes[dev] = 0;
+        }
+        void *p = nullptr;
+        if (hipMalloc(&p, bytes) != hipSuccess) {
+            (void)hipGetLastError();
+            return HLQ_ERR_WORKSPACE;
+        }
+        g_ws_ptr[dev] = p;
+        g_ws_bytes[dev] = bytes;
+    }
+    *out = g_ws_ptr[dev];
+    return HLQ_OK;
+}
+
+inline int launch_rc(hipError_t e) { return e == hipSuccess ? HLQ_OK : HLQ_ERR_LAUNCH; }
+
+}  // namespace
+
+extern "C" {
+
+const char *hlq_status_str(int status)
+{
+    switch (status) {
+        case HLQ_OK: return "HLQ_OK";
+        case HLQ_ERR_NULL: return "HLQ_ERR_NULL: a required pointer is NULL";
+        case HLQ_ERR_SHAPE: return "HLQ_ERR_SHAPE: a size breaks the shape rules";
+        case HLQ_ERR_BLOCK: return "HLQ_ERR_BLOCK: B must be 16, 32 or 64";
+        case HLQ_ERR_RANK: return "HLQ_ERR_RANK: r must be a power of two in [1, B]";
+        case HLQ_ERR_DTYPE: return "HLQ_ERR_DTYPE: dtype must be HLQ_BF16 or HLQ_F32";
+        case HLQ_ERR_WORKSPACE: return "HLQ_ERR_WORKSPACE: workspace too small, misaligned or not allocatable";
+        case HLQ_ERR_LAUNCH: return "HLQ_ERR_LAUNCH: the HIP runtime refused a launch";
+    }
+    return "HLQ: unknown status";
+}
+
+int hlq_version(void) { return 100; }
+
+size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r, int x_is_compressed)
+{
+    if (check_backward_shape(N, d_in, d_out, B, r) != HLQ_OK) return 0;
+    return make_layout(N, d_in, d_out, B, r, x_is_compressed != 0).total;
+}
+
+int hlq_quantize_g(const void *G, int64_t N, int64_t d_out, int B, uint64_t seed, int dtype, int8_t *Gq,
+                   float *sG, float *coeff, void *stream)
+{
+    int rc;
+    if (!G || !Gq || !sG) return HLQ_ERR_NULL;
+    if ((rc = check_block(B)) != HLQ_OK) return rc;
+    if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if ((rc = check_quant_shape(N, d_out, B)) != HLQ_OK) return rc;
+    if (!aligned(G, 16) || !aligned(Gq, 8) || (coeff && !aligned(coeff, 16))) return HLQ_ERR_SHAPE;
+    const uint64_t key = stream_key(seed, 0);
+    return launch_rc(hlq::launch_quant_rows(G, N, static_cast<int>(d_out), B, dtype == HLQ_F32,
+                                            static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32), Gq, sG,
+                                            coeff, static_cast<hipStream_t>(stream)));
+}
+
+size_t hlq_quantize_w_workspace_bytes(int64_t d_out, int64_t d_in)
+{
+    if (d_out <= 0 || d_in <= 0) return 0;
+    return hlq::quant_cols_ws_bytes(d_out, d_in);
+}
+
+int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t seed, int dtype, int8_t *WqT,
+                   float *sW, float *coeffT, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc;
+    if (!W || !WqT || !sW || !workspace) return HLQ_ERR_NULL;
+    if ((rc = check_block(B)) != HLQ_OK) return rc;
+    if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if (d_in <= 0 || d_in % 8 != 0) return HLQ_ERR_SHAPE;
+    if ((rc = check_quant_shape(d_in, d_out, B)) != HLQ_OK) return rc;
+    if (!aligned(W, 16) || !aligned(WqT, 16) || (coeffT && !aligned(coeffT, 16))) return HLQ_ERR_SHAPE;
+    if (!aligned(workspace, 256) || workspace_bytes < hlq::quant_cols_ws_bytes(d_out, d_in)) return HLQ_ERR_WORKSPACE;
+    const uint64_t key = stream_key(seed, 1);
+    return launch_rc(hlq::launch_quant_cols(W, static_cast<int>(d_out), static_cast<int>(d_in), B, dtype == HLQ_F32,
+                                            static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32), WqT, sW,
+                                            coeffT, workspace, static_cast<hipStream_t>(stream)));
+}
+
+int hlq_int8_gemm_nt(const int8_t *A, const int8_t *Bm, int64_t M, int64_t Nn, int64_t K, const float *sA,
+                     const float *sB, float alpha, int out_dtype, void *C, int32_t *acc, void *stream)
+{
+    int rc;
+    if (!A || !Bm || (!C && !acc)) return HLQ_ERR_NULL;
+    if ((rc = check_dtype(out_dtype)) != HLQ_OK) return rc;
+    if ((rc = check_gemm_shape(M, Nn, K, 16)) != HLQ_OK) return rc;
+    if (!aligned(A, 16) || !aligned(Bm, 16) || (C && !aligned(C, 16)) || (acc && !aligned(acc, 16)) ||
+        (sB && !aligned(sB, 16)))
+        return HLQ_ERR_SHAPE;
+    hlq::GemmArgs a{A, Bm, static_cast<int>(M), static_cast<int>(Nn), static_cast<int>(K), sA, sB, alpha, C,
+                    out_dtype == HLQ_F32, acc};
+    return launch_rc(hlq::launch_gemm_nt(0, a, static_cast<hipStream_t>(stream)));
+}
+
+int hlq_hla_project(const void *T, int64_t N, int64_t D, int B, int r, int dtype, void *ThatT, float *coeffT,
+                    void *stream)
+{
+    int rc;
+    if (!T || !ThatT) return HLQ_ERR_NULL;
+    if ((rc = check_block(B)) != HLQ_OK) return rc;
+    if ((rc = check_rank(B, r)) != HLQ_OK) return rc;
+    if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if ((rc = check_hla_shape(N, D, B, r)) != HLQ_OK) return rc;
+    if (!aligned(T, 16) || !aligned(ThatT, 16) || (coeffT && !aligned(coeffT, 16))) return HLQ_ERR_SHAPE;
+    return launch_rc(hlq::launch_hla(T, N, static_cast<int>(D), B, r, dtype == HLQ_F32,
+                                     static_cast<uint16_t *>(ThatT), coeffT, static_cast<hipStream_t>(stream)));
+}
+
+int hlq_compress_act(const void *X, int64_t N, int64_t d_in, int B, int r, int dtype, void *XhatT, void *stream)
+{
+    return hlq_hla_project(X, N, d_in, B, r, dtype, XhatT, nullptr, stream);
+}
+
+int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64_t K, float alpha, int out_dtype,
+                     void *C, void *stream)
+{
+    int rc;
+    if (!A || !Bm || !C) return HLQ_ERR_NULL;
+    if ((rc = check_dtype(out_dtype)) != HLQ_OK) return rc;
+    if ((rc = check_gemm_shape(M, Nn, K, 8)) != HLQ_OK) return rc;
+    if (!aligned(A, 16) || !aligned(Bm, 16) || !aligned(C, 16)) return HLQ_ERR_SHAPE;
+    hlq::GemmArgs a{A, Bm, static_cast<int>(M), static_cast<int>(Nn), static_cast<int>(K), nullptr, nullptr, alpha, C,
+                    out_dtype == HLQ_F32, nullptr};
+    return launch_rc(hlq::launch_gemm_nt(1, a, static_cast<hipStream_t>(stream)));
+}
+
+int hlq_linear_backward_ex(const void *G, const void *X, const void *XhatT, const void *W, int64_t N, int64_t d_in,
+                           int64_t d_out, int B, int r, uint64_t seed, int dtype, void *dX, void *dW,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc;
+    if ((rc = check_backward_shape(N, d_in, d_out, B, r)) != HLQ_OK) return rc;
+    if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if (!G || (!dX && !dW)) return HLQ_ERR_NULL;
+    if (dX && !W) return HLQ_ERR_NULL;
+    if (dW && ((X == nullptr) == (XhatT == nullptr))) return HLQ_ERR_NULL;   // exactly one of the two
+    if (!aligned(G, 16) || (X && !aligned(X, 16)) || (XhatT && !aligned(XhatT, 16)) || (W && !aligned(W, 16)) ||
+        (dX && !aligned(dX, 16)) || (dW && !aligned(dW, 16)))
+        return HLQ_ERR_SHAPE;
+
+    const bool xc = (XhatT != nullptr);
+    const Layout L = make_layout(N, d_in, d_out, B, r, xc);
+    char *ws = static_cast<char *>(workspace);
+    if (ws) {
+        if (!aligned(ws, 256) || workspace_bytes < L.total) return HLQ_ERR_WORKSPACE;
+    } else {
+        void *p = nullptr;
+        if ((rc = own_workspace(L.total, &p)) != HLQ_OK) return rc;
+        ws = static_cast<char *>(p);
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool f32 = dtype == HLQ_F32;
+    const int O = static_cast<int>(d_out), I = static_cast<int>(d_in);
+    const int Kc = static_cast<int>(N / B * r);
+    const float invB = 1.0f / static_cast<float>(B);
+
+    if (dX) {
+        int8_t *Gq = reinterpret_cast<int8_t *>(ws + L.Gq);
+        float *sG = reinterpret_cast<float *>(ws + L.sG);
+        int8_t *Wq = reinterpret_cast<int8_t *>(ws + L.Wq);
+        float *sW = reinterpret_cast<float *>(ws + L.sW);
+        const uint64_t kg = stream_key(seed, 0), kw = stream_key(seed, 1);
+        // stages 1-2: Q4(G H)
+        if ((rc = launch_rc(hlq::launch_quant_rows(G, N, O, B, f32, static_cast<uint32_t>(kg),
+                                                   static_cast<uint32_t>(kg >> 32), Gq, sG, nullptr, st))) != HLQ_OK)
+            return rc;
+        // stages 3-4: Q4(H^T W), transposed
+        if ((rc = launch_rc(hlq::launch_quant_cols(W, O, I, B, f32, static_cast<uint32_t>(kw),
+                                                   static_cast<uint32_t>(kw >> 32), Wq, sW, nullptr, ws + L.wws, st))) != HLQ_OK)
+            return rc;
+        // stages 5-6: integer product and dequantisation (1/B undoes H H^T = B I)
+        hlq::GemmArgs a{Gq, Wq, static_cast<int>(N), I, O, sG, sW, invB, dX, f32, nullptr};
+        if ((rc = launch_rc(hlq::launch_gemm_nt(0, a, st))) != HLQ_OK) return rc;
+    }
+    if (dW) {
+        uint16_t *Gh = reinterpret_cast<uint16_t *>(ws + L.GhatT);
+        const void *Xh = XhatT;
+        if (!xc) {
+            uint16_t *xh = reinterpret_cast<uint16_t *>(ws + L.XhatT);
+            if ((rc = launch_rc(hlq::launch_hla(X, N, I, B, r, f32, xh, nullptr, st))) != HLQ_OK) return rc;
+            Xh = xh;
+        }
+        if ((rc = launch_rc(hlq::launch_hla(G, N, O, B, r, f32, Gh, nullptr, st))) != HLQ_OK) return rc;
+        hlq::GemmArgs a{Gh, Xh, O, I, Kc, nullptr, nullptr, invB, dW, f32, nullptr};
+        if ((rc = launch_rc(hlq::launch_gemm_nt(1, a, st))) != HLQ_OK) return rc;
+    }
+    return HLQ_OK;
+}
+
+int hlq_linear_backward(const void *G, const void *X, const void *W, int64_t N, int64_t d_in, int64_t d_out, int B,
+                        int r, uint64_t seed, void *dX, void *dW, void *stream)
+{
+    if (!G || !X || !W || !dX || !dW) return HLQ_ERR_NULL;
+    return hlq_linear_backward_ex(G, X, nullptr, W, N, d_in, d_out, B, r, seed, HLQ_BF16, dX, dW, nullptr, 0, stream);
+}
+
+}  // extern "C"

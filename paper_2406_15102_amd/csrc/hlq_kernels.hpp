@@ -1,0 +1,39 @@
+// Host-side launchers of the gfx950 kernels.  Every launcher only enqueues work on `st`; shapes
+// have been validated by the caller (hlq_api.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace hlq {
+
+// K1: rows of G -> 4-bit codes + per-row scales (and optionally the fp32 coefficients).
+hipError_t launch_quant_rows(const void *G, int64_t N, int O, int B, bool is_f32, uint32_t k0, uint32_t k1,
+                             int8_t *Gq, float *sG, float *coeff, hipStream_t st);
+
+// K1T: W [O, I] -> WqT [I, O] codes + per-in-feature scales.  `ws` holds the partial column
+// maxima and the reciprocal scales: quant_cols_ws_bytes(O, I) bytes.
+size_t quant_cols_ws_bytes(int64_t O, int64_t I);
+hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
+                             int8_t *WqT, float *sW, float *coeffT, void *ws, hipStream_t st);
+
+// K3: token-axis Hadamard low-rank projection, T [N, D] -> ThatT [D, N/B*r] bf16.
+hipError_t launch_hla(const void *T, int64_t N, int D, int B, int r, bool is_f32, uint16_t *ThatT,
+                      float *coeffT, hipStream_t st);
+
+// K2 / K4: C = alpha * sA (x) sB * (A . Bm^T).  kind 0: int8 operands, int32 accumulate;
+// kind 1: bf16 operands, fp32 accumulate.  K in elements.
+struct GemmArgs {
+    const void *A;
+    const void *Bm;
+    int M, N, K;
+    const float *sA;
+    const float *sB;
+    float alpha;
+    void *C;          // bf16 or fp32 [M, N], may be null
+    bool c_is_f32;
+    int32_t *acc;     // raw int32 accumulators (int8 kind only), may be null
+};
+hipError_t launch_gemm_nt(int kind, const GemmArgs &a, hipStream_t st);
+
+}  // namespace hlq

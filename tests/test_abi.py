@@ -1,0 +1,105 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol hlq.h declares, and
+rejects bad arguments with the documented status before touching the GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2406_15102_amd as hlq
+from paper_2406_15102_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "hlq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hlq_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    declared = _declared_symbols()
+    assert "hlq_linear_backward" in declared and "hlq_compress_act" in declared
+    l = hlq.lib()
+    for name in declared:
+        assert hasattr(l, name), "libhlq.so does not export %s" % name
+    assert declared == binding.exported_symbols()
+
+
+def test_version_and_status_strings():
+    assert hlq.hlq_version() >= 100
+    assert hlq.hlq_status_str(0) == "HLQ_OK"
+    for code, word in [(1, "NULL"), (2, "SHAPE"), (3, "BLOCK"), (4, "RANK"), (5, "DTYPE"), (6, "WORKSPACE"),
+                       (7, "LAUNCH")]:
+        assert word in hlq.hlq_status_str(code)
+    assert "unknown" in hlq.hlq_status_str(99)
+
+
+def test_workspace_bytes():
+    n = hlq.hlq_workspace_bytes(4096, 4096, 11008, 16, 8)
+    # codes of G and W, bf16 compressed G and X, plus small vectors
+    assert n >= 4096 * 11008 * 2 + (11008 + 4096) * 2048 * 2
+    assert hlq.hlq_workspace_bytes(4096, 4096, 11008, 16, 8, True) < n
+    assert hlq.hlq_workspace_bytes(4096, 4096, 11000, 16, 8) == 0      # d_out % B
+    assert hlq.hlq_workspace_bytes(4096, 4096, 11008, 24, 8) == 0      # bad block
+    assert hlq.hlq_quantize_w_workspace_bytes(11008, 4096) > 0
+
+
+FAKE = C.c_void_p(0x10000)   # non-null, 16-aligned; never dereferenced because validation fails first
+
+
+def _bw(G=FAKE, X=FAKE, W=FAKE, N=256, d_in=256, d_out=256, B=16, r=8, dX=FAKE, dW=FAKE):
+    return hlq.lib().hlq_linear_backward(G, X, W, N, d_in, d_out, B, r, 0, dX, dW, None)
+
+
+def test_linear_backward_rejects_bad_arguments_without_a_gpu():
+    assert _bw(G=None) == 1 and _bw(dX=None) == 1 and _bw(W=None) == 1
+    assert _bw(B=8) == 3 and _bw(B=48) == 3 and _bw(B=128) == 3
+    assert _bw(r=0) == 4 and _bw(r=3) == 4 and _bw(r=32) == 4
+    assert _bw(N=0) == 2 and _bw(N=250) == 2            # empty / not a multiple of B
+    assert _bw(d_out=250) == 2 and _bw(d_out=65536 + 64) == 2
+    assert _bw(d_in=100) == 2                            # d_in % 8
+    assert _bw(N=16, r=1) == 2                           # compressed token axis not a multiple of 8
+    assert _bw(N=1 << 22, d_out=4096) == 2               # random-stream counter would overflow
+
+
+def test_ex_rejects_bad_arguments_without_a_gpu():
+    f = hlq.lib().hlq_linear_backward_ex
+    ok = dict(N=256, d_in=256, d_out=256, B=16, r=8)
+
+    def call(G=FAKE, X=FAKE, Xh=None, W=FAKE, dt=0, dX=FAKE, dW=FAKE, ws=FAKE, wsb=1 << 30, **kw):
+        a = dict(ok, **kw)
+        return f(G, X, Xh, W, a["N"], a["d_in"], a["d_out"], a["B"], a["r"], 0, dt, dX, dW, ws, wsb, None)
+
+    assert call(dt=7) == 5
+    assert call(X=FAKE, Xh=FAKE) == 1 and call(X=None, Xh=None) == 1     # exactly one of X / XhatT
+    assert call(dX=None, dW=None) == 1
+    assert call(wsb=1000) == 6                                            # workspace too small
+    assert call(ws=C.c_void_p(0x10010)) == 6                              # workspace misaligned
+    assert call(G=C.c_void_p(0x10004)) == 2                               # tensor misaligned
+
+
+def test_stage_entry_points_reject_bad_arguments_without_a_gpu():
+    l = hlq.lib()
+    assert l.hlq_quantize_g(None, 16, 256, 16, 0, 0, FAKE, FAKE, None, None) == 1
+    assert l.hlq_quantize_g(FAKE, 16, 250, 16, 0, 0, FAKE, FAKE, None, None) == 2
+    assert l.hlq_quantize_g(FAKE, 16, 256, 20, 0, 0, FAKE, FAKE, None, None) == 3
+    assert l.hlq_quantize_g(FAKE, 16, 256, 16, 0, 9, FAKE, FAKE, None, None) == 5
+    assert l.hlq_quantize_w(FAKE, 256, 256, 16, 0, 0, FAKE, FAKE, None, None, 0, None) == 1
+    assert l.hlq_quantize_w(FAKE, 256, 256, 16, 0, 0, FAKE, FAKE, None, FAKE, 16, None) == 6
+    assert l.hlq_quantize_w(FAKE, 256, 100, 16, 0, 0, FAKE, FAKE, None, FAKE, 1 << 20, None) == 2
+    assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 64, 40, None, None, 1.0, 1, FAKE, None, None) == 2   # K % 16
+    assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 62, 64, None, None, 1.0, 1, FAKE, None, None) == 2   # Nn % 4
+    assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 64, 64, None, None, 1.0, 1, None, None, None) == 1
+    assert l.hlq_hla_project(FAKE, 250, 64, 16, 8, 0, FAKE, None, None) == 2
+    assert l.hlq_hla_project(FAKE, 256, 64, 16, 5, 0, FAKE, None, None) == 4
+    assert l.hlq_compress_act(FAKE, 256, 64, 16, 8, 0, None, None) == 1
+    assert l.hlq_bf16_gemm_nt(FAKE, FAKE, 64, 64, 36, 1.0, 0, FAKE, None) == 2                     # K % 8
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    t = torch.zeros(16, 256, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        hlq.hlq_quantize_g(t, 16, 0, torch.zeros(16, 256, dtype=torch.int8), torch.zeros(16))
