@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the HLQ backward pass (arXiv 2406.15102, Sec. 6.1) on one MI355X.
+
+A step is one whole backward pass of one layer -- Hadamard transform + 4-bit quantisation of G and
+of W, int8 product + dequantisation (dX), token-axis low-rank projection of G and X, bf16 product
+(dW) -- on synthetic inputs already resident in HBM, through the C ABI with a caller-owned
+workspace (nothing is allocated in the timed region).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_I8_TOPS = 5000.0
+PEAK_BF16_TFLOPS = 2500.0
+
+
+def _event_time_us(fn, iters, torch):
+    """Average duration of fn() in microseconds, HIP events on the current (= launch) stream."""
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) * 1000.0 / iters
+
+
+def cpu_baseline(w, t, budget_tokens):
+    """The CPU oracle, as it stands, timed on this host: the W stages in full (they do not depend on
+    the token count), the token-dependent stages on the first `budget_tokens` tokens, scaled up."""
+    import numpy as np
+
+    import oracle
+    from paper_2406_15102_amd import workloads as wl
+
+    G = wl.as_f32_numpy(t["G"][:budget_tokens])
+    X = wl.as_f32_numpy(t["X"][:budget_tokens])
+    W = wl.as_f32_numpy(t["W"])
+    t0 = time.perf_counter()
+    Wq, sW = oracle.quantize_rows(oracle.transform_cols(W, w.B), w.seed, 1)
+    t_w = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    Gq, sG = oracle.quantize_rows(oracle.transform_rows(G, w.B), w.seed, 0)
+    acc = oracle.int_gemm_nt(Gq, Wq)
+    oracle.dequant(acc, sG, sW, w.B)
+    gh = oracle.round_bf16(oracle.hla_f32(G, w.B, w.r))
+    xh = oracle.round_bf16(oracle.hla_f32(X, w.B, w.r))
+    oracle.gemm_nt_f64(gh, xh, 1.0 / w.B)
+    t_tok = time.perf_counter() - t0
+    total_s = t_w + t_tok * (w.N / budget_tokens)
+    return {
+        "value": total_s * 1e6, "unit": "us", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "W transform+quantise in full (%.1f s); token-dependent stages on the first %d of %d tokens "
+                  "(%.1f s), scaled x%g; extrapolated" % (t_w, budget_tokens, w.N, t_tok, w.N / budget_tokens),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c4")
+    ap.add_argument("--cpu-tokens", type=int, default=2048, help="tokens of the CPU-oracle sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import torch
+
+    import paper_2406_15102_amd as hlq
+    from paper_2406_15102_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    hlq.lib()  # fail loudly if the HIP library is missing
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = wl.WORKLOADS[args.workload]
+    t = wl.generate(w)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    G, X, W = (t[k].to(dev).contiguous() for k in ("G", "X", "W"))
+    N, I, O, B, r = w.N, w.d_in, w.d_out, w.B, w.r
+    Kc = N // B * r
+    dX = torch.empty((N, I), dtype=tdt, device=dev)
+    dW = torch.empty((O, I), dtype=tdt, device=dev)
+    ws = torch.empty(hlq.hlq_workspace_bytes(N, I, O, B, r), dtype=torch.uint8, device=dev)
+
+    def step():
+        hlq.hlq_linear_backward_ex(G, X, None, W, N, I, O, B, r, w.seed, dX, dW, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    wall_us = (time.perf_counter() - t0) * 1e6 / args.steps
+    hlq_us = _event_time_us(step, args.steps, torch)
+
+    # ---- the same path with the weight codes taken as cached (W quantised once per optimiser step) ----
+    # ---- and kernel by kernel through the stage entry points, HIP events on the launch stream ----------
+    Gq = torch.empty((N, O), dtype=torch.int8, device=dev)
+    sG = torch.empty(N, dtype=torch.float32, device=dev)
+    WqT = torch.empty((I, O), dtype=torch.int8, device=dev)
+    sW = torch.empty(I, dtype=torch.float32, device=dev)
+    wws = torch.empty(hlq.hlq_quantize_w_workspace_bytes(O, I), dtype=torch.uint8, device=dev)
+    GhT = torch.empty((O, Kc), dtype=torch.bfloat16, device=dev)
+    XhT = torch.empty((I, Kc), dtype=torch.bfloat16, device=dev)
+    stages = {
+        "quantize_g": lambda: hlq.hlq_quantize_g(G, B, w.seed, Gq, sG),
+        "quantize_w": lambda: hlq.hlq_quantize_w(W, B, w.seed, WqT, sW, wws),
+        "int8_gemm": lambda: hlq.hlq_int8_gemm_nt(Gq, WqT, sG, sW, 1.0 / B, dX),
+        "hla_g": lambda: hlq.hlq_hla_project(G, B, r, GhT),
+        "hla_x": lambda: hlq.hlq_hla_project(X, B, r, XhT),
+        "bf16_gemm": lambda: hlq.hlq_bf16_gemm_nt(GhT, XhT, 1.0 / B, dW),
+    }
+    e = 2 if w.dtype == "bf16" else 4
+    work = {  # algorithmic bytes / ops per launch
+        "quantize_g": ("hbm", N * O * (e + 1) + 4 * N),
+        "quantize_w": ("hbm", O * I * (e + 1) + 4 * I),
+        "int8_gemm": ("mfma_i8", 2.0 * N * I * O),
+        "hla_g": ("hbm", N * O * e + 2 * Kc * O),
+        "hla_x": ("hbm", N * I * e + 2 * Kc * I),
+        "bf16_gemm": ("mfma_bf16", 2.0 * O * I * Kc),
+    }
+    kernels = {}
+    for name, fn in stages.items():
+        for _ in range(3):
+            fn()
+        us = _event_time_us(fn, max(10, args.steps // 2), torch)
+        kind, amount = work[name]
+        if kind == "hbm":
+            ach, peak, unit = amount / us / 1e3, PEAK_HBM_GBS, "GB/s"
+        elif kind == "mfma_i8":
+            ach, peak, unit = amount / us / 1e6, PEAK_I8_TOPS, "TFLOP/s"
+        else:
+            ach, peak, unit = amount / us / 1e6, PEAK_BF16_TFLOPS, "TFLOP/s"
+        kernels[name] = {"us": round(us, 2), "bound": kind, "achieved": round(ach, 1), "peak": peak, "unit": unit,
+                         "frac": round(ach / peak, 4)}
+
+    # ---- dense bf16 backward on the same GPU (comparator, not part of the library) ----
+    def dense():
+        torch.matmul(G, W, out=dXd)
+        torch.matmul(G.t(), X, out=dWd)
+
+    dXd = torch.empty_like(dX)
+    dWd = torch.empty_like(dW)
+    for _ in range(5):
+        dense()
+    dense_us = _event_time_us(dense, args.steps, torch)
+
+    dom = "int8_gemm"
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
+        except Exception:
+            traffic = None
+    roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["achieved"], "peak": PEAK_I8_TOPS,
+                "unit": "TFLOP/s", "frac": kernels[dom]["frac"], "traffic": traffic,
+                "note": "int8 MFMA ops (2*N*d_in*d_out per launch) over the HIP-event average of %s launches"
+                        % max(10, args.steps // 2)}
+
+    cpu = None
+    if args.cpu_tokens > 0:
+        cpu = cpu_baseline(w, t, min(w.N, max(w.B, args.cpu_tokens // w.B * w.B)))
+
+    out = {
+        "metric": "hlq_backward_dX_dW_latency", "value": round(hlq_us, 2), "unit": "us", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(hlq_us / 1e3, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "i8 (dX product, 4-bit codes) + bf16 (dW product), fp32 transforms", "data": "synthetic",
+        "config": {"workload": "%s: %s" % (w.name, w.desc), "N": N, "d_in": I, "d_out": O, "B": B, "r": r,
+                   "io_dtype": w.dtype, "includes": "W quantisation counted every step"},
+        "wall_us_per_step": round(wall_us, 2),
+        "dense_bf16_backward_us": round(dense_us, 2),
+        "speedup_vs_dense_bf16": round(dense_us / hlq_us, 3),
+        "kernels": kernels,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
