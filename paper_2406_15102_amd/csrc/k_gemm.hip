@@ -7,13 +7,20 @@
 // operands, and both MFMA shapes consume 16 B per lane and operand for a 32-byte slice of k, so one
 // kernel template written in bytes serves the two.
 //
-// Tiling: a workgroup of 4 wavefronts (2 x 2) owns a (64*WM) x (64*WN) tile of C; each wavefront
-// a (32*WM) x (32*WN) sub-tile held as WM x WN MFMA accumulators.  k advances 64 B per step through
-// a double-buffered LDS tile; global loads for step t+1 are issued before the MFMAs of step t.
-// LDS rows are 64 B (four 16-B chunks) with the chunk index xor-swizzled by the row so that the
-// ds_read_b128 of 32 consecutive rows and the ds_write_b128 of the staging pass spread over all banks.
+// Tiling: a workgroup of 4 wavefronts (2 x 2), one per SIMD, owns a (64*WM) x (64*WN) tile of C;
+// each wavefront a (32*WM) x (32*WN) sub-tile held as WM x WN MFMA accumulators (AGPRs).  That is
+// the shape with the least LDS traffic per MFMA, which is what bounds a 256 x 256 tile.
+//
+// Pipeline: k advances KCH*16 bytes per step through two LDS stages.  Within a step the wavefront
+// runs KCH/2 sub-steps of WM*WN MFMAs; the operand fragments of sub-step s+1 are read from LDS
+// while the MFMAs of sub-step s execute, global loads run two steps ahead of the MFMAs in
+// registers, and the single workgroup barrier of a step waits on LDS traffic only, so neither
+// LDS nor global latency is exposed to the one wavefront a SIMD has.
+// LDS rows hold KCH 16-byte chunks; the chunk index is xor-swizzled with the row so that both
+// the fragment reads (32 consecutive rows, one chunk) and the staging writes spread over all banks.
 // The MFMA's A operand is fed from Bm and its B operand from A, which leaves each lane with four
-// consecutive n for one m: C is written in 8- or 16-byte pieces.
+// consecutive n for one m.  The epilogue scales the accumulators, stages each 32-row slab of the
+// wavefront's sub-tile in LDS and writes C in full 16-byte, row-contiguous pieces.
 // Workgroup ids are remapped so that each XCD (ids congruent mod 8) works on a compact patch of
 // tiles and re-uses operand rows in its own L2.
 #include "hlq_device.hpp"
@@ -22,9 +29,11 @@
 namespace hlq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // one 16-B chunk (a first-class vector: stays in registers)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // one 16-B chunk (first-class vector: stays in registers)
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 template <int KIND> struct Mma;
@@ -61,19 +70,39 @@ struct GemmDev {
     int tiles_m, tiles_n;
 };
 
-// position of 16-B chunk c of LDS row `row` (4 chunks per row)
+// position of 16-byte chunk c of LDS row `row` (KCH chunks per row)
+template <int KCH>
 __device__ __forceinline__ int lds_chunk(int row, int c)
 {
-    const int f = (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1);
-    return row * 4 + (c ^ f);
+    if (KCH == 8) return row * 8 + (c ^ ((row & 7) ^ ((row >> 3) & 1)));
+    return row * 4 + (c ^ ((((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1)));
 }
 
-template <int KIND, int WM, int WN>
+// Workgroup barrier that waits for this wavefront's LDS traffic only (global loads stay in flight).
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+// Orders this wavefront's own LDS writes before its later LDS reads (and the reverse).
+__device__ __forceinline__ void lds_wave_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
+}
+
+template <int KIND, int WM, int WN, int KCH, bool TAIL>
 __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
     constexpr int GROUP = 4;
-    __shared__ u32x4 lds[2][(BM + BN) * 4];
+    constexpr int NS = KCH / 2;                 // MFMA sub-steps (32 B of k) per step
+    constexpr int RPP = 256 / KCH;              // tile rows staged per pass of the workgroup
+    constexpr int PA = BM / RPP, PB = BN / RPP; // passes per operand
+    constexpr int STAGE = (BM + BN) * KCH;      // 16-B chunks per LDS stage
+    extern __shared__ u32x4 lds[];              // 2 * STAGE chunks
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_m = wave >> 1, wave_n = wave & 1;
@@ -97,23 +126,22 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
     const int m0 = tm * BM, n0 = tn * BN;
 
     // ---- staging assignment: thread -> (row, chunk); addresses = uniform tile base + 32-bit offset ----
-    const int lc = tid & 3;       // 16-B chunk within the 64-B k step
-    const int lr = tid >> 2;      // row 0..63 (+64 i)
+    // Rows past the end of an operand are redirected to the tile's first row: they only feed
+    // accumulators that the epilogue never stores, so the main loop needs no row predicate.
+    const int lc = tid % KCH;     // 16-B chunk within the k step
+    const int lr = tid / KCH;     // row 0..RPP-1 (+RPP i)
     const char *baseA = g.A + static_cast<int64_t>(m0) * g.Kb;
     const char *baseB = g.Bm + static_cast<int64_t>(n0) * g.Kb;
-    uint32_t offa[WM], offb[WN];
-    bool oka[WM], okb[WN];
+    uint32_t offa[PA], offb[PB];
 #pragma unroll
-    for (int i = 0; i < WM; ++i) {
-        const int row = lr + 64 * i;
-        oka[i] = m0 + row < g.M;
-        offa[i] = static_cast<uint32_t>(oka[i] ? row : 0) * static_cast<uint32_t>(g.Kb) + lc * 16;
+    for (int i = 0; i < PA; ++i) {
+        const int row = lr + RPP * i;
+        offa[i] = static_cast<uint32_t>(m0 + row < g.M ? row : 0) * static_cast<uint32_t>(g.Kb);
     }
 #pragma unroll
-    for (int j = 0; j < WN; ++j) {
-        const int row = lr + 64 * j;
-        okb[j] = n0 + row < g.N;
-        offb[j] = static_cast<uint32_t>(okb[j] ? row : 0) * static_cast<uint32_t>(g.Kb) + lc * 16;
+    for (int j = 0; j < PB; ++j) {
+        const int row = lr + RPP * j;
+        offb[j] = static_cast<uint32_t>(n0 + row < g.N ? row : 0) * static_cast<uint32_t>(g.Kb);
     }
 
     typename Mma<KIND>::acc_t acc[WM][WN];
@@ -122,103 +150,251 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
 #pragma unroll
         for (int j = 0; j < WN; ++j) acc[i][j] = Mma<KIND>::zero();
 
-    u32x4 ra[WM], rb[WN];
+    u32x4 ra[PA], rb[PB];
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    const int nk = (g.Kb + 63) >> 6;
+    const int nk = (g.Kb + KCH * 16 - 1) / (KCH * 16);
 
-#define HLQ_LOAD_GLOBAL(KT)                                                                                   \
+    // Step KT of k into registers (A rows, then Bm rows).  With a ragged last step (TAIL) chunks
+    // past the end of the row are read from the row's last chunk instead (in bounds) and replaced
+    // by zeros.
+#define HLQ_KOFS(KT)                                                                                          \
+        const int kpos = (KT) * (KCH * 16) + lc * 16;                                                         \
+        const bool kok = !TAIL || kpos < g.Kb;                                                                \
+        const uint32_t kofs = static_cast<uint32_t>(kok ? kpos : g.Kb - 16);
+#define HLQ_LOAD_GLOBAL_A(KT)                                                                                 \
     {                                                                                                         \
-        const uint32_t kofs = static_cast<uint32_t>(KT) * 64u;                                                \
-        const bool kok = static_cast<int>(kofs) + lc * 16 < g.Kb;                                             \
-        _Pragma("unroll") for (int i = 0; i < WM; ++i)                                                        \
-            ra[i] = (oka[i] && kok) ? *reinterpret_cast<const u32x4 *>(baseA + (offa[i] + kofs)) : zero4;     \
-        _Pragma("unroll") for (int j = 0; j < WN; ++j)                                                        \
-            rb[j] = (okb[j] && kok) ? *reinterpret_cast<const u32x4 *>(baseB + (offb[j] + kofs)) : zero4;     \
+        HLQ_KOFS(KT)                                                                                          \
+        _Pragma("unroll") for (int i = 0; i < PA; ++i) {                                                      \
+            ra[i] = *reinterpret_cast<const u32x4 *>(baseA + (offa[i] + kofs));                               \
+            if (TAIL) ra[i] = kok ? ra[i] : zero4;                                                            \
+        }                                                                                                     \
     }
-#define HLQ_STORE_LDS(STAGE)                                                                                  \
+#define HLQ_LOAD_GLOBAL_B(KT)                                                                                 \
     {                                                                                                         \
-        _Pragma("unroll") for (int i = 0; i < WM; ++i) lds[STAGE][lds_chunk(lr + 64 * i, lc)] = ra[i];        \
-        _Pragma("unroll") for (int j = 0; j < WN; ++j) lds[STAGE][BM * 4 + lds_chunk(lr + 64 * j, lc)] = rb[j]; \
+        HLQ_KOFS(KT)                                                                                          \
+        _Pragma("unroll") for (int j = 0; j < PB; ++j) {                                                      \
+            rb[j] = *reinterpret_cast<const u32x4 *>(baseB + (offb[j] + kofs));                               \
+            if (TAIL) rb[j] = kok ? rb[j] : zero4;                                                            \
+        }                                                                                                     \
     }
-
-    HLQ_LOAD_GLOBAL(0)
-    HLQ_STORE_LDS(0)
-    __syncthreads();
+#define HLQ_STORE_LDS_A(STG)                                                                                  \
+    {                                                                                                         \
+        u32x4 *s_ = lds + (STG) * STAGE;                                                                      \
+        _Pragma("unroll") for (int i = 0; i < PA; ++i) s_[lds_chunk<KCH>(lr + RPP * i, lc)] = ra[i];          \
+    }
+#define HLQ_STORE_LDS_B(STG)                                                                                  \
+    {                                                                                                         \
+        u32x4 *s_ = lds + (STG) * STAGE;                                                                      \
+        _Pragma("unroll") for (int j = 0; j < PB; ++j) s_[BM * KCH + lds_chunk<KCH>(lr + RPP * j, lc)] = rb[j]; \
+    }
 
     const int fr = lane & 31;   // row within a 32-row MFMA operand
     const int fh = lane >> 5;   // which 16-B half of the 32-B k slice
+    u32x4 fa[2][WM], fb[2][WN];
+
+#define HLQ_READ_FRAGS(BUF, STG, KS)                                                                          \
+    {                                                                                                         \
+        const u32x4 *s_ = lds + (STG) * STAGE;                                                                \
+        _Pragma("unroll") for (int i = 0; i < WM; ++i)                                                        \
+            fa[BUF][i] = s_[lds_chunk<KCH>(wave_m * (32 * WM) + i * 32 + fr, (KS) * 2 + fh)];                 \
+        _Pragma("unroll") for (int j = 0; j < WN; ++j)                                                        \
+            fb[BUF][j] = s_[BM * KCH + lds_chunk<KCH>(wave_n * (32 * WN) + j * 32 + fr, (KS) * 2 + fh)];      \
+    }
+
+    // The loop body is branch-free: past the end, steps are clamped to the last one, whose data is
+    // loaded, published and fetched again but never multiplied.
+    //
+    // Step kt, sub-step ks:
+    //   every ks     read the fragments of the next sub-step (the next step's first one for the
+    //                last ks, from the other LDS stage) under this sub-step's MFMAs
+    //   ks = 0       publish the A rows of step kt+1 (in registers since step kt-1), then load
+    //                the A rows of step kt+2 into the same registers
+    //   ks = 1       the same for the Bm rows
+    //   ks = NS-2    barrier at its end: step kt+1 is complete in LDS, and every wavefront has
+    //                finished reading the stage that step kt+2 will overwrite
+    HLQ_LOAD_GLOBAL_A(0)
+    HLQ_LOAD_GLOBAL_B(0)
+    HLQ_STORE_LDS_A(0)
+    HLQ_STORE_LDS_B(0)
+    HLQ_LOAD_GLOBAL_A(nk > 1 ? 1 : 0)
+    HLQ_LOAD_GLOBAL_B(nk > 1 ? 1 : 0)
+    lds_barrier();
+    HLQ_READ_FRAGS(0, 0, 0)
+
+    static_assert(NS == 4, "the staging schedule below is written for four sub-steps per step");
+    constexpr int MPR = (WM * WN) / (WM + WN);   // MFMAs per fragment read
 
     for (int kt = 0; kt < nk; ++kt) {
         const int stage = kt & 1;
-        if (kt + 1 < nk) HLQ_LOAD_GLOBAL(kt + 1)
+        const int kt2 = kt + 2 < nk ? kt + 2 : nk - 1;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            u32x4 fa[WM], fb[WN];
+        for (int ks = 0; ks < NS; ++ks) {
+            const int cur = ks & 1;
+            if (ks < NS - 1) {
+                HLQ_READ_FRAGS(cur ^ 1, stage, ks + 1)
+            } else {
+                HLQ_READ_FRAGS(cur ^ 1, stage ^ 1, 0)
+            }
 #pragma unroll
             for (int i = 0; i < WM; ++i)
-                fa[i] = lds[stage][lds_chunk(wave_m * (32 * WM) + i * 32 + fr, ks * 2 + fh)];
 #pragma unroll
-            for (int j = 0; j < WN; ++j)
-                fb[j] = lds[stage][BM * 4 + lds_chunk(wave_n * (32 * WN) + j * 32 + fr, ks * 2 + fh)];
+                for (int j = 0; j < WN; ++j) acc[i][j] = Mma<KIND>::mma(fb[cur][j], fa[cur][i], acc[i][j]);
+            if (ks == 0) {
+                HLQ_STORE_LDS_A(stage ^ 1)
+                HLQ_LOAD_GLOBAL_A(kt2)
+            }
+            if (ks == 1) {
+                HLQ_STORE_LDS_B(stage ^ 1)
+                HLQ_LOAD_GLOBAL_B(kt2)
+            }
+            // Issue order within the sub-step.  LDS writes may not pass the fragment reads (same
+            // array), so a staging sub-step threads its reads between the first half of the MFMAs
+            // and its LDS writes + global loads between the second half.
+            if (ks < 2) {
 #pragma unroll
-            for (int i = 0; i < WM; ++i)
-#pragma unroll
-                for (int j = 0; j < WN; ++j) acc[i][j] = Mma<KIND>::mma(fb[j], fa[i], acc[i][j]);
-        }
-        if (kt + 1 < nk) HLQ_STORE_LDS(stage ^ 1)
-        __syncthreads();
-    }
-#undef HLQ_LOAD_GLOBAL
-#undef HLQ_STORE_LDS
-
-    // ---- epilogue: lane holds, per accumulator group vg, C[m][n .. n+3] ----
-#pragma unroll
-    for (int i = 0; i < WM; ++i) {
-        const int m = m0 + wave_m * (32 * WM) + i * 32 + fr;
-        if (m >= g.M) continue;
-        const float sa = (g.sA ? g.sA[m] : 1.0f);
-#pragma unroll
-        for (int j = 0; j < WN; ++j) {
-#pragma unroll
-            for (int vg = 0; vg < 4; ++vg) {
-                const int n = n0 + wave_n * (32 * WN) + j * 32 + vg * 8 + fh * 4;
-                if (n >= g.N) continue;
-                const int64_t off = static_cast<int64_t>(m) * g.N + n;
-                if (KIND == 0 && g.acc) {
-                    int4 raw;
-                    raw.x = static_cast<int>(acc[i][j][vg * 4 + 0]);
-                    raw.y = static_cast<int>(acc[i][j][vg * 4 + 1]);
-                    raw.z = static_cast<int>(acc[i][j][vg * 4 + 2]);
-                    raw.w = static_cast<int>(acc[i][j][vg * 4 + 3]);
-                    *reinterpret_cast<int4 *>(g.acc + off) = raw;
+                for (int q = 0; q < (WM * WN) / 2; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2 * (WM + WN) / (WM * WN), 0);   // fragment reads
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           // one MFMA
                 }
-                if (g.C) {
-                    float o[4];
-                    if (g.sB) {
-                        const float4 sb = *reinterpret_cast<const float4 *>(g.sB + n);
-                        o[0] = sb.x; o[1] = sb.y; o[2] = sb.z; o[3] = sb.w;
-                    } else {
-                        o[0] = o[1] = o[2] = o[3] = 1.0f;
-                    }
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        o[e] = Mma<KIND>::to_float(acc[i][j][vg * 4 + e]) * (sa * o[e]) * g.alpha;
-                    if (g.c_is_f32) {
-                        *reinterpret_cast<float4 *>(static_cast<float *>(g.C) + off) = make_float4(o[0], o[1], o[2], o[3]);
-                    } else {
-                        uint2 p;
-                        p.x = pack_bf16(o[0], o[1]);
-                        p.y = pack_bf16(o[2], o[3]);
-                        *reinterpret_cast<uint2 *>(static_cast<bf16_t *>(g.C) + off) = p;
-                    }
+                for (int q = 0; q < (WM * WN) / 2; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x200, 2 * PA / (WM * WN), 0);          // LDS writes
+                    __builtin_amdgcn_sched_group_barrier(0x020, 2 * PA / (WM * WN), 0);          // global loads
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < WM + WN; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
                 }
             }
+            if (ks == NS - 2) lds_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+#undef HLQ_KOFS
+#undef HLQ_LOAD_GLOBAL_A
+#undef HLQ_LOAD_GLOBAL_B
+#undef HLQ_STORE_LDS_A
+#undef HLQ_STORE_LDS_B
+#undef HLQ_READ_FRAGS
+
+    // ---- epilogue ----
+    // Lane holds, per accumulator (i, j) and register group vg, C[m][n .. n+3] with
+    // m = 32 i + (lane & 31), n = 32 j + 8 vg + 4 (lane >> 5) inside the wavefront's sub-tile.
+    __syncthreads();   // all fragment reads are done: LDS is free for staging C
+    const int wm0 = m0 + wave_m * (32 * WM), wn0 = n0 + wave_n * (32 * WN);
+    constexpr int COLS = 32 * WN;
+
+    if (KIND == 0 && g.acc) {
+        // raw int32 accumulators (parity export): direct 16-byte stores
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            const int m = wm0 + i * 32 + fr;
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    const int n = wn0 + j * 32 + vg * 8 + fh * 4;
+                    if (m < g.M && n < g.N) {
+                        int4 raw;
+                        raw.x = static_cast<int>(acc[i][j][vg * 4 + 0]);
+                        raw.y = static_cast<int>(acc[i][j][vg * 4 + 1]);
+                        raw.z = static_cast<int>(acc[i][j][vg * 4 + 2]);
+                        raw.w = static_cast<int>(acc[i][j][vg * 4 + 3]);
+                        *reinterpret_cast<int4 *>(g.acc + static_cast<int64_t>(m) * g.N + n) = raw;
+                    }
+                }
+        }
+    }
+    if (!g.C) return;
+
+    // per-lane column scales sB[n] for the columns this lane owns
+    float sbn[WN][4][4];
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int vg = 0; vg < 4; ++vg) {
+            const int n = wn0 + j * 32 + vg * 8 + fh * 4;
+            f32x4 s = {1.0f, 1.0f, 1.0f, 1.0f};
+            if (g.sB && n < g.N) s = *reinterpret_cast<const f32x4 *>(g.sB + n);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sbn[j][vg][e] = s[e];
+        }
+
+    char *stg = reinterpret_cast<char *>(lds) + wave * (32 * COLS * 4 + 32 * 16);   // wavefront-private slab
+    if (g.c_is_f32) {
+        constexpr int PITCH = COLS * 4 + 16;     // bytes per staged row (+16: rows start on different banks)
+        constexpr int LPR = COLS / 4;            // lanes per row (16-byte pieces)
+        constexpr int RPI = 64 / LPR;            // rows per instruction
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            const int mrow = wm0 + i * 32 + fr;
+            const float sa = (g.sA && mrow < g.M) ? g.sA[mrow] : 1.0f;
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    f32x4 o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        o[e] = Mma<KIND>::to_float(acc[i][j][vg * 4 + e]) * (sa * sbn[j][vg][e]) * g.alpha;
+                    *reinterpret_cast<f32x4 *>(stg + fr * PITCH + (j * 32 + vg * 8 + fh * 4) * 4) = o;
+                }
+            lds_wave_fence();
+#pragma unroll
+            for (int p = 0; p < 32 / RPI; ++p) {
+                const int rr = p * RPI + lane / LPR, cc = (lane % LPR) * 4;
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(stg + rr * PITCH + cc * 4);
+                const int m = wm0 + i * 32 + rr, n = wn0 + cc;
+                if (m < g.M && n < g.N)
+                    *reinterpret_cast<f32x4 *>(static_cast<float *>(g.C) + static_cast<int64_t>(m) * g.N + n) = v;
+            }
+            lds_wave_fence();
+        }
+    } else {
+        constexpr int PITCH = COLS * 2 + 16;
+        constexpr int LPR = COLS / 8;            // lanes per row (16-byte pieces of 8 bf16)
+        constexpr int RPI = 64 / LPR;
+        const bool wide = (g.N & 7) == 0;
+#pragma unroll
+        for (int i = 0; i < WM; ++i) {
+            const int mrow = wm0 + i * 32 + fr;
+            const float sa = (g.sA && mrow < g.M) ? g.sA[mrow] : 1.0f;
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+#pragma unroll
+                for (int vg = 0; vg < 4; ++vg) {
+                    float o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        o[e] = Mma<KIND>::to_float(acc[i][j][vg * 4 + e]) * (sa * sbn[j][vg][e]) * g.alpha;
+                    u32x2 p = {pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+                    *reinterpret_cast<u32x2 *>(stg + fr * PITCH + (j * 32 + vg * 8 + fh * 4) * 2) = p;
+                }
+            lds_wave_fence();
+#pragma unroll
+            for (int p = 0; p < 32 / RPI; ++p) {
+                const int rr = p * RPI + lane / LPR, cc = (lane % LPR) * 8;
+                const int m = wm0 + i * 32 + rr, n = wn0 + cc;
+                bf16_t *dst = static_cast<bf16_t *>(g.C) + static_cast<int64_t>(m) * g.N + n;
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(stg + rr * PITCH + cc * 2);
+                if (wide) {                        // rows of C are 16-byte aligned
+                    if (m < g.M && n < g.N) *reinterpret_cast<u32x4 *>(dst) = v;
+                } else if (m < g.M) {              // N % 8 == 4: 8-byte pieces, the last one of a row may be missing
+                    const u32x2 lo = {v[0], v[1]}, hi = {v[2], v[3]};
+                    if (n < g.N) *reinterpret_cast<u32x2 *>(dst) = lo;
+                    if (n + 4 < g.N) *reinterpret_cast<u32x2 *>(dst + 4) = hi;
+                }
+            }
+            lds_wave_fence();
         }
     }
 }
 
-template <int KIND, int WM, int WN>
-static hipError_t launch_t(const GemmArgs &a, hipStream_t st)
+template <int KIND, int WM, int WN, int KCH, bool TAIL>
+static hipError_t launch_tt(const GemmArgs &a, hipStream_t st)
 {
     GemmDev g;
     g.A = static_cast<const char *>(a.A);
@@ -234,8 +410,25 @@ static hipError_t launch_t(const GemmArgs &a, hipStream_t st)
     g.acc = a.acc;
     g.tiles_m = (a.M + 64 * WM - 1) / (64 * WM);
     g.tiles_n = (a.N + 64 * WN - 1) / (64 * WN);
-    hipLaunchKernelGGL((k_gemm_nt<KIND, WM, WN>), dim3(g.tiles_m * g.tiles_n), dim3(256), 0, st, g);
+    constexpr size_t main_bytes = 2u * (64 * WM + 64 * WN) * KCH * 16u;
+    constexpr size_t epi_bytes = 4u * (32u * (32 * WN) * 4u + 32u * 16u);
+    constexpr size_t lds_bytes = main_bytes > epi_bytes ? main_bytes : epi_bytes;
+    static bool attr_set = false;     // raising the dynamic-LDS limit is idempotent; racing callers set the same value
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_nt<KIND, WM, WN, KCH, TAIL>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_gemm_nt<KIND, WM, WN, KCH, TAIL>), dim3(g.tiles_m * g.tiles_n), dim3(256), lds_bytes, st, g);
     return hipGetLastError();
+}
+
+template <int KIND, int WM, int WN, int KCH>
+static hipError_t launch_t(const GemmArgs &a, hipStream_t st)
+{
+    const int Kb = KIND == 0 ? a.K : 2 * a.K;
+    return (Kb % (KCH * 16) == 0) ? launch_tt<KIND, WM, WN, KCH, false>(a, st) : launch_tt<KIND, WM, WN, KCH, true>(a, st);
 }
 
 hipError_t launch_gemm_nt(int kind, const GemmArgs &a, hipStream_t st)
@@ -243,8 +436,8 @@ hipError_t launch_gemm_nt(int kind, const GemmArgs &a, hipStream_t st)
     // 256 x 256 tiles when they still give every compute unit work, else 128 x 128
     const int64_t big_tiles = static_cast<int64_t>((a.M + 255) / 256) * ((a.N + 255) / 256);
     const bool big = big_tiles >= 200;
-    if (kind == 0) return big ? launch_t<0, 4, 4>(a, st) : launch_t<0, 2, 2>(a, st);
-    return big ? launch_t<1, 4, 4>(a, st) : launch_t<1, 2, 2>(a, st);
+    if (kind == 0) return big ? launch_t<0, 4, 4, 8>(a, st) : launch_t<0, 2, 2, 8>(a, st);
+    return big ? launch_t<1, 4, 4, 8>(a, st) : launch_t<1, 2, 2, 8>(a, st);
 }
 
 }  // namespace hlq
