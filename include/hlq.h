@@ -155,6 +155,15 @@ int hlq_hla_project(const void *T, int64_t N, int64_t D, int B, int r, int dtype
 int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64_t K, float alpha,
                      int out_dtype, void *C, void *stream);
 
+/*
+ * Diagnostic, not part of the backward pass: `blocks` workgroups of four wavefronts each issue
+ * iters * 8 independent 32x32 MFMAs from registers (kind 0: int8, K = 32, 65536 ops each;
+ * kind 1: bf16, K = 16, 32768 flops each).  Timing it gives the MFMA rate the chip sustains at
+ * its running clock, the practical ceiling for the two matrix products of Sec. 6.1.
+ * sink: one device float (never written in practice; keeps the loop alive).
+ */
+int hlq_mfma_probe(int kind, int blocks, int iters, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -5,6 +5,6 @@
 from . import workloads  # noqa: F401
 from .binding import (  # noqa: F401
     HLQ_BF16, HLQ_F32, HlqError, exported_symbols, hlq_bf16_gemm_nt, hlq_compress_act, hlq_hla_project,
-    hlq_int8_gemm_nt, hlq_linear_backward, hlq_linear_backward_ex, hlq_quantize_g, hlq_quantize_w,
+    hlq_int8_gemm_nt, hlq_linear_backward, hlq_mfma_probe, hlq_linear_backward_ex, hlq_quantize_g, hlq_quantize_w,
     hlq_quantize_w_workspace_bytes, hlq_status_str, hlq_version, hlq_workspace_bytes, lib,
 )

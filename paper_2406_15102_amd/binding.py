@@ -39,6 +39,7 @@ _EXPORTS = {
                                   C.c_void_p, C.c_void_p]),
     "hlq_bf16_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_float, C.c_int,
                                    C.c_void_p, C.c_void_p]),
+    "hlq_mfma_probe": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
 }
 
 _lib = None
@@ -175,3 +176,7 @@ def hlq_bf16_gemm_nt(A, Bm, alpha, C_out):
     Nn = Bm.shape[0]
     _check(lib().hlq_bf16_gemm_nt(_ptr(A, torch.bfloat16), _ptr(Bm, torch.bfloat16), M, Nn, K, float(alpha),
                                   _dt(C_out), _ptr(C_out), _stream()), "hlq_bf16_gemm_nt")
+
+
+def hlq_mfma_probe(kind, blocks, iters, sink):
+    _check(lib().hlq_mfma_probe(kind, blocks, iters, _ptr(sink, torch.float32), _stream()), "hlq_mfma_probe")

@@ -235,6 +235,13 @@ int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64
     return launch_rc(hlq::launch_gemm_nt(1, a, static_cast<hipStream_t>(stream)));
 }
 
+int hlq_mfma_probe(int kind, int blocks, int iters, float *sink, void *stream)
+{
+    if (!sink) return HLQ_ERR_NULL;
+    if ((kind != 0 && kind != 1) || blocks <= 0 || blocks > (1 << 20) || iters <= 0) return HLQ_ERR_SHAPE;
+    return launch_rc(hlq::launch_mfma_probe(kind, blocks, iters, sink, static_cast<hipStream_t>(stream)));
+}
+
 int hlq_linear_backward_ex(const void *G, const void *X, const void *XhatT, const void *W, int64_t N, int64_t d_in,
                            int64_t d_out, int B, int r, uint64_t seed, int dtype, void *dX, void *dW,
                            void *workspace, size_t workspace_bytes, void *stream)

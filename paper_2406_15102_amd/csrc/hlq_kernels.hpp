@@ -36,4 +36,8 @@ struct GemmArgs {
 };
 hipError_t launch_gemm_nt(int kind, const GemmArgs &a, hipStream_t st);
 
+// Diagnostic: `blocks` workgroups of 4 wavefronts each run `iters` x 8 independent 32x32 MFMAs
+// (kind 0: i8, K = 32; kind 1: bf16, K = 16) from registers.
+hipError_t launch_mfma_probe(int kind, int blocks, int iters, float *sink, hipStream_t st);
+
 }  // namespace hlq

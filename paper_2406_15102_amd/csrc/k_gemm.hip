@@ -93,7 +93,134 @@ __device__ __forceinline__ void lds_wave_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
 }
 
-template <int KIND, int WM, int WN, int KCH, bool TAIL>
+// ---- epilogue helpers ------------------------------------------------------------------------
+// After the MFMAs a lane holds, per accumulator (i, j) and register group vg, C[m][n .. n+3] with
+// m = 32 i + (lane & 31), n = 32 j + 8 vg + 4 (lane >> 5) inside the wavefront's sub-tile.
+// One wavefront per SIMD means every instruction of the epilogue is exposed, so it is kept short:
+// two multiplies per value, no predicates on interior tiles.
+
+template <int WN> struct EpiSlab {
+    static constexpr int COLS = 32 * WN;
+    static constexpr int PITCH_F32 = COLS * 4 + 16;   // +16 B: consecutive rows start on different banks
+    static constexpr int PITCH_BF16 = COLS * 2 + 16;
+    static constexpr int BYTES = 32 * PITCH_F32;      // one 32-row slab per wavefront
+};
+
+// raw int32 accumulators (parity export): direct 16-byte stores
+template <int KIND, int WM, int WN, bool GUARD>
+__device__ __forceinline__ void store_raw(typename Mma<KIND>::acc_t (&acc)[WM][WN], int32_t *out, int M, int N,
+                                          int wm0, int wn0, int lane)
+{
+    struct { int32_t *acc; int M, N; } g = {out, M, N};
+    const int fr = lane & 31, fh = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+        const int m = wm0 + i * 32 + fr;
+        int32_t *row = g.acc + static_cast<int64_t>(m) * g.N + wn0 + fh * 4;
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) {
+                const int nl = j * 32 + vg * 8;
+                if (!GUARD || (m < g.M && wn0 + nl + fh * 4 < g.N)) {
+                    v4i raw = {static_cast<int>(acc[i][j][vg * 4 + 0]), static_cast<int>(acc[i][j][vg * 4 + 1]),
+                               static_cast<int>(acc[i][j][vg * 4 + 2]), static_cast<int>(acc[i][j][vg * 4 + 3])};
+                    *reinterpret_cast<v4i *>(row + nl) = raw;
+                }
+            }
+    }
+}
+
+// C = alpha * sA[m] * sB[n] * acc, staged per 32-row slab through LDS so that global stores are
+// 16-byte, row-contiguous pieces (a full 256-byte row segment per 16 or 8 lanes).
+template <int KIND, int WM, int WN, bool F32, bool GUARD>
+__device__ __forceinline__ void store_scaled(typename Mma<KIND>::acc_t (&acc)[WM][WN], void *Cout, int M, int N,
+                                             const float *sA, const float *sB, float alpha, int wm0, int wn0,
+                                             int lane, char *slab)
+{
+    struct { void *C; int M, N; const float *sA, *sB; float alpha; } g = {Cout, M, N, sA, sB, alpha};
+    constexpr int COLS = EpiSlab<WN>::COLS;
+    constexpr int PITCH = F32 ? EpiSlab<WN>::PITCH_F32 : EpiSlab<WN>::PITCH_BF16;
+    constexpr int EPL = F32 ? 4 : 8;              // elements per 16-byte piece
+    constexpr int LPR = COLS / EPL;               // lanes per row
+    constexpr int RPI = 64 / LPR;                 // rows per store instruction
+    const int fr = lane & 31, fh = lane >> 5;
+
+    // column factors alpha * sB[n] for the 16 WN columns this lane owns (columns past the edge
+    // read sB[0..3]: their products are never stored)
+    f32x4 cs[WN][4];
+    if (g.sB) {
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) {
+                int n = wn0 + j * 32 + vg * 8 + fh * 4;
+                if (GUARD) n = n < g.N ? n : 0;
+                cs[j][vg] = *reinterpret_cast<const f32x4 *>(g.sB + n) * g.alpha;
+            }
+    } else {
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) cs[j][vg] = f32x4{g.alpha, g.alpha, g.alpha, g.alpha};
+    }
+    float sa[WM];
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+        int m = wm0 + i * 32 + fr;
+        if (GUARD) m = m < g.M ? m : 0;
+        sa[i] = g.sA ? g.sA[m] : 1.0f;
+    }
+
+    const int rr0 = lane / LPR, cc = (lane % LPR) * EPL;
+    char *wr = slab + fr * PITCH + fh * 4 * (F32 ? 4 : 2);
+    const char *rd = slab + rr0 * PITCH + cc * (F32 ? 4 : 2);
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+            for (int vg = 0; vg < 4; ++vg) {
+                f32x4 o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = Mma<KIND>::to_float(acc[i][j][vg * 4 + e]) * (sa[i] * cs[j][vg][e]);
+                if (F32) {
+                    *reinterpret_cast<f32x4 *>(wr + (j * 32 + vg * 8) * 4) = o;
+                } else {
+                    u32x2 p = {pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+                    *reinterpret_cast<u32x2 *>(wr + (j * 32 + vg * 8) * 2) = p;
+                }
+            }
+        lds_wave_fence();
+        u32x4 v[32 / RPI];
+#pragma unroll
+        for (int p = 0; p < 32 / RPI; ++p) v[p] = *reinterpret_cast<const u32x4 *>(rd + p * RPI * PITCH);
+        const int mbase = wm0 + i * 32 + rr0;
+        char *dst = static_cast<char *>(g.C) + (static_cast<int64_t>(mbase) * g.N + wn0 + cc) * (F32 ? 4 : 2);
+        const int64_t step = static_cast<int64_t>(RPI) * g.N * (F32 ? 4 : 2);
+#pragma unroll
+        for (int p = 0; p < 32 / RPI; ++p) {
+            if (!GUARD) {
+                *reinterpret_cast<u32x4 *>(dst + p * step) = v[p];
+            } else {
+                const int m = mbase + p * RPI, n = wn0 + cc;
+                if (m < g.M) {
+                    if (F32 || (g.N & 7) == 0) {
+                        if (n < g.N) *reinterpret_cast<u32x4 *>(dst + p * step) = v[p];
+                    } else {   // bf16 rows that are only 8-byte aligned: two halves, the last may be missing
+                        const u32x2 lo = {v[p][0], v[p][1]}, hi = {v[p][2], v[p][3]};
+                        if (n < g.N) *reinterpret_cast<u32x2 *>(dst + p * step) = lo;
+                        if (n + 4 < g.N) *reinterpret_cast<u32x2 *>(dst + p * step + 8) = hi;
+                    }
+                }
+            }
+        }
+        lds_wave_fence();
+    }
+}
+
+// OUT: 0 = C in bf16, 1 = C in fp32, 2 = raw int32 accumulators (parity export)
+template <int KIND, int WM, int WN, int KCH, bool TAIL, int OUT>
 __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
 {
     constexpr int BM = 64 * WM, BN = 64 * WN;
@@ -281,119 +408,21 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
 #undef HLQ_READ_FRAGS
 
     // ---- epilogue ----
-    // Lane holds, per accumulator (i, j) and register group vg, C[m][n .. n+3] with
-    // m = 32 i + (lane & 31), n = 32 j + 8 vg + 4 (lane >> 5) inside the wavefront's sub-tile.
     __syncthreads();   // all fragment reads are done: LDS is free for staging C
     const int wm0 = m0 + wave_m * (32 * WM), wn0 = n0 + wave_n * (32 * WN);
-    constexpr int COLS = 32 * WN;
-
-    if (KIND == 0 && g.acc) {
-        // raw int32 accumulators (parity export): direct 16-byte stores
-#pragma unroll
-        for (int i = 0; i < WM; ++i) {
-            const int m = wm0 + i * 32 + fr;
-#pragma unroll
-            for (int j = 0; j < WN; ++j)
-#pragma unroll
-                for (int vg = 0; vg < 4; ++vg) {
-                    const int n = wn0 + j * 32 + vg * 8 + fh * 4;
-                    if (m < g.M && n < g.N) {
-                        int4 raw;
-                        raw.x = static_cast<int>(acc[i][j][vg * 4 + 0]);
-                        raw.y = static_cast<int>(acc[i][j][vg * 4 + 1]);
-                        raw.z = static_cast<int>(acc[i][j][vg * 4 + 2]);
-                        raw.w = static_cast<int>(acc[i][j][vg * 4 + 3]);
-                        *reinterpret_cast<int4 *>(g.acc + static_cast<int64_t>(m) * g.N + n) = raw;
-                    }
-                }
-        }
-    }
-    if (!g.C) return;
-
-    // per-lane column scales sB[n] for the columns this lane owns
-    float sbn[WN][4][4];
-#pragma unroll
-    for (int j = 0; j < WN; ++j)
-#pragma unroll
-        for (int vg = 0; vg < 4; ++vg) {
-            const int n = wn0 + j * 32 + vg * 8 + fh * 4;
-            f32x4 s = {1.0f, 1.0f, 1.0f, 1.0f};
-            if (g.sB && n < g.N) s = *reinterpret_cast<const f32x4 *>(g.sB + n);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) sbn[j][vg][e] = s[e];
-        }
-
-    char *stg = reinterpret_cast<char *>(lds) + wave * (32 * COLS * 4 + 32 * 16);   // wavefront-private slab
-    if (g.c_is_f32) {
-        constexpr int PITCH = COLS * 4 + 16;     // bytes per staged row (+16: rows start on different banks)
-        constexpr int LPR = COLS / 4;            // lanes per row (16-byte pieces)
-        constexpr int RPI = 64 / LPR;            // rows per instruction
-#pragma unroll
-        for (int i = 0; i < WM; ++i) {
-            const int mrow = wm0 + i * 32 + fr;
-            const float sa = (g.sA && mrow < g.M) ? g.sA[mrow] : 1.0f;
-#pragma unroll
-            for (int j = 0; j < WN; ++j)
-#pragma unroll
-                for (int vg = 0; vg < 4; ++vg) {
-                    f32x4 o;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        o[e] = Mma<KIND>::to_float(acc[i][j][vg * 4 + e]) * (sa * sbn[j][vg][e]) * g.alpha;
-                    *reinterpret_cast<f32x4 *>(stg + fr * PITCH + (j * 32 + vg * 8 + fh * 4) * 4) = o;
-                }
-            lds_wave_fence();
-#pragma unroll
-            for (int p = 0; p < 32 / RPI; ++p) {
-                const int rr = p * RPI + lane / LPR, cc = (lane % LPR) * 4;
-                const f32x4 v = *reinterpret_cast<const f32x4 *>(stg + rr * PITCH + cc * 4);
-                const int m = wm0 + i * 32 + rr, n = wn0 + cc;
-                if (m < g.M && n < g.N)
-                    *reinterpret_cast<f32x4 *>(static_cast<float *>(g.C) + static_cast<int64_t>(m) * g.N + n) = v;
-            }
-            lds_wave_fence();
-        }
+    char *slab = reinterpret_cast<char *>(lds) + wave * EpiSlab<WN>::BYTES;   // wavefront-private
+    // one uniform test selects straight-line code without per-store predicates for interior tiles
+    const bool interior = (m0 + BM <= g.M) && (n0 + BN <= g.N) && ((g.N & 7) == 0);
+    if (OUT == 2) {
+        if (interior) store_raw<KIND, WM, WN, false>(acc, g.acc, g.M, g.N, wm0, wn0, lane);
+        else store_raw<KIND, WM, WN, true>(acc, g.acc, g.M, g.N, wm0, wn0, lane);
     } else {
-        constexpr int PITCH = COLS * 2 + 16;
-        constexpr int LPR = COLS / 8;            // lanes per row (16-byte pieces of 8 bf16)
-        constexpr int RPI = 64 / LPR;
-        const bool wide = (g.N & 7) == 0;
-#pragma unroll
-        for (int i = 0; i < WM; ++i) {
-            const int mrow = wm0 + i * 32 + fr;
-            const float sa = (g.sA && mrow < g.M) ? g.sA[mrow] : 1.0f;
-#pragma unroll
-            for (int j = 0; j < WN; ++j)
-#pragma unroll
-                for (int vg = 0; vg < 4; ++vg) {
-                    float o[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        o[e] = Mma<KIND>::to_float(acc[i][j][vg * 4 + e]) * (sa * sbn[j][vg][e]) * g.alpha;
-                    u32x2 p = {pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
-                    *reinterpret_cast<u32x2 *>(stg + fr * PITCH + (j * 32 + vg * 8 + fh * 4) * 2) = p;
-                }
-            lds_wave_fence();
-#pragma unroll
-            for (int p = 0; p < 32 / RPI; ++p) {
-                const int rr = p * RPI + lane / LPR, cc = (lane % LPR) * 8;
-                const int m = wm0 + i * 32 + rr, n = wn0 + cc;
-                bf16_t *dst = static_cast<bf16_t *>(g.C) + static_cast<int64_t>(m) * g.N + n;
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(stg + rr * PITCH + cc * 2);
-                if (wide) {                        // rows of C are 16-byte aligned
-                    if (m < g.M && n < g.N) *reinterpret_cast<u32x4 *>(dst) = v;
-                } else if (m < g.M) {              // N % 8 == 4: 8-byte pieces, the last one of a row may be missing
-                    const u32x2 lo = {v[0], v[1]}, hi = {v[2], v[3]};
-                    if (n < g.N) *reinterpret_cast<u32x2 *>(dst) = lo;
-                    if (n + 4 < g.N) *reinterpret_cast<u32x2 *>(dst + 4) = hi;
-                }
-            }
-            lds_wave_fence();
-        }
+        if (interior) store_scaled<KIND, WM, WN, OUT == 1, false>(acc, g.C, g.M, g.N, g.sA, g.sB, g.alpha, wm0, wn0, lane, slab);
+        else store_scaled<KIND, WM, WN, OUT == 1, true>(acc, g.C, g.M, g.N, g.sA, g.sB, g.alpha, wm0, wn0, lane, slab);
     }
 }
 
-template <int KIND, int WM, int WN, int KCH, bool TAIL>
+template <int KIND, int WM, int WN, int KCH, bool TAIL, int OUT>
 static hipError_t launch_tt(const GemmArgs &a, hipStream_t st)
 {
     GemmDev g;
@@ -411,24 +440,36 @@ static hipError_t launch_tt(const GemmArgs &a, hipStream_t st)
     g.tiles_m = (a.M + 64 * WM - 1) / (64 * WM);
     g.tiles_n = (a.N + 64 * WN - 1) / (64 * WN);
     constexpr size_t main_bytes = 2u * (64 * WM + 64 * WN) * KCH * 16u;
-    constexpr size_t epi_bytes = 4u * (32u * (32 * WN) * 4u + 32u * 16u);
+    constexpr size_t epi_bytes = 4u * EpiSlab<WN>::BYTES;
     constexpr size_t lds_bytes = main_bytes > epi_bytes ? main_bytes : epi_bytes;
     static bool attr_set = false;     // raising the dynamic-LDS limit is idempotent; racing callers set the same value
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_nt<KIND, WM, WN, KCH, TAIL>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_nt<KIND, WM, WN, KCH, TAIL, OUT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_gemm_nt<KIND, WM, WN, KCH, TAIL>), dim3(g.tiles_m * g.tiles_n), dim3(256), lds_bytes, st, g);
+    hipLaunchKernelGGL((k_gemm_nt<KIND, WM, WN, KCH, TAIL, OUT>), dim3(g.tiles_m * g.tiles_n), dim3(256), lds_bytes, st, g);
     return hipGetLastError();
+}
+
+template <int KIND, int WM, int WN, int KCH, int OUT>
+static hipError_t launch_o(const GemmArgs &a, hipStream_t st)
+{
+    const int Kb = KIND == 0 ? a.K : 2 * a.K;
+    return (Kb % (KCH * 16) == 0) ? launch_tt<KIND, WM, WN, KCH, false, OUT>(a, st)
+                                  : launch_tt<KIND, WM, WN, KCH, true, OUT>(a, st);
 }
 
 template <int KIND, int WM, int WN, int KCH>
 static hipError_t launch_t(const GemmArgs &a, hipStream_t st)
 {
-    const int Kb = KIND == 0 ? a.K : 2 * a.K;
-    return (Kb % (KCH * 16) == 0) ? launch_tt<KIND, WM, WN, KCH, false>(a, st) : launch_tt<KIND, WM, WN, KCH, true>(a, st);
+    // the raw accumulators and the scaled output are separate launches of the same product
+    if (KIND == 0 && a.acc) {
+        hipError_t e = launch_o<0, WM, WN, KCH, 2>(a, st);
+        if (e != hipSuccess || !a.C) return e;
+    }
+    return a.c_is_f32 ? launch_o<KIND, WM, WN, KCH, 1>(a, st) : launch_o<KIND, WM, WN, KCH, 0>(a, st);
 }
 
 hipError_t launch_gemm_nt(int kind, const GemmArgs &a, hipStream_t st)
