@@ -40,8 +40,7 @@ int check_hla_shape(int64_t N, int64_t D, int B, int r)
     if (N <= 0 || D <= 0 || N % B != 0 || D % 8 != 0 || D > (int64_t(1) << 30)) return HLQ_ERR_SHAPE;
     const int64_t Kc = N / B * r;
     if (Kc % 8 != 0 || Kc > (int64_t(1) << 30)) return HLQ_ERR_SHAPE;
-    int nbw = 32 / r < 1 ? 1 : 32 / r;
-    if ((N / B + 4 * nbw - 1) / (4 * nbw) > 65535) return HLQ_ERR_SHAPE;
+    if ((N / B + 3) / 4 > 65535) return HLQ_ERR_SHAPE;   // token-block groups are the grid's y axis
     return HLQ_OK;
 }
 
