@@ -163,6 +163,14 @@ def main():
         dense()
     dense_us = _event_time_us(dense, args.steps, torch)
 
+    # ---- a plain copy of known size: the yardstick that scales the profiler's FETCH_SIZE / WRITE_SIZE ----
+    calib_src = torch.empty(1 << 28, dtype=torch.uint8, device=dev)
+    calib_dst = torch.empty_like(calib_src)
+    for _ in range(3):
+        calib_dst.copy_(calib_src)
+    copy_us = _event_time_us(lambda: calib_dst.copy_(calib_src), 10, torch)
+    del calib_src, calib_dst
+
     dom = "int8_gemm"
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -191,6 +199,7 @@ def main():
         "dense_bf16_backward_us": round(dense_us, 2),
         "speedup_vs_dense_bf16": round(dense_us / hlq_us, 3),
         "kernels": kernels,
+        "copy_256MiB": {"us": round(copy_us, 2), "GB/s": round(2 * (1 << 28) / copy_us / 1e3, 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -223,25 +223,35 @@ int8_t hlqo_quantize_one(float x, float inv, uint32_t byte)
     return (int8_t)q;
 }
 
-int hlqo_quantize_rows(const float *C, long rows, long K, uint64_t seed, uint32_t tensor,
-                       int8_t *q /* [rows,K] */, float *scale /* [rows] */)
+/* Quantise `rows` rows of C; row_ids[i] (or i when row_ids is NULL) is the row's index in the   */
+/* full operand, which is what addresses its random bytes: a subset of rows gets the same codes */
+/* it has inside the full matrix.                                                               */
+int hlqo_quantize_rows_at(const float *C, long rows, long K, uint64_t seed, uint32_t tensor,
+                          const long *row_ids, int8_t *q /* [rows,K] */, float *scale /* [rows] */)
 {
     if (K % 4) return -1;
     uint64_t key = hlqo_stream_key(seed, tensor);
 #pragma omp parallel for schedule(static)
-    for (long row = 0; row < rows; ++row) {
-        const float *c = C + row * K;
+    for (long i = 0; i < rows; ++i) {
+        const long row = row_ids ? row_ids[i] : i;
+        const float *c = C + i * K;
         float a = 0.0f;
         for (long k = 0; k < K; ++k) {
             float m = fabsf(c[k]);
             if (m > a) a = m;
         }
         float inv = (a > 0.0f) ? 7.0f / a : 0.0f;
-        scale[row] = a / 7.0f;
+        scale[i] = a / 7.0f;
         for (long k = 0; k < K; ++k)
-            q[row * K + k] = hlqo_quantize_one(c[k], inv, hlqo_rand_byte(key, row, k, K));
+            q[i * K + k] = hlqo_quantize_one(c[k], inv, hlqo_rand_byte(key, row, k, K));
     }
     return 0;
+}
+
+int hlqo_quantize_rows(const float *C, long rows, long K, uint64_t seed, uint32_t tensor,
+                       int8_t *q /* [rows,K] */, float *scale /* [rows] */)
+{
+    return hlqo_quantize_rows_at(C, rows, K, seed, tensor, NULL, q, scale);
 }
 
 /* ------------------------------------------------------------------------- */

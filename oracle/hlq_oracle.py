@@ -59,6 +59,8 @@ def _L():
         lib.hlqo_quantize_one.argtypes = [C.c_float, C.c_float, C.c_uint32]
         lib.hlqo_quantize_one.restype = C.c_int8
         lib.hlqo_quantize_rows.argtypes = [f32p, C.c_long, C.c_long, C.c_uint64, C.c_uint32, i8p, f32p]
+        lib.hlqo_quantize_rows_at.argtypes = [f32p, C.c_long, C.c_long, C.c_uint64, C.c_uint32,
+                                              C.POINTER(C.c_long), i8p, f32p]
         lib.hlqo_int_gemm_nt.argtypes = [i8p, i8p, C.c_long, C.c_long, C.c_long, i32p]
         lib.hlqo_dequant.argtypes = [i32p, f32p, f32p, C.c_long, C.c_long, C.c_int, f64p]
         lib.hlqo_hla_f32.argtypes = [f32p, C.c_long, C.c_long, C.c_int, C.c_int, f32p]
@@ -153,14 +155,22 @@ def quantize_one(x: float, inv: float, byte: int) -> int:
     return int(_L().hlqo_quantize_one(float(np.float32(x)), float(np.float32(inv)), byte))
 
 
-def quantize_rows(Cm, seed: int, tensor: int):
-    """4-bit stochastic absmax quantiser, one scale per row -> (codes int8, scales fp32)."""
+def quantize_rows(Cm, seed: int, tensor: int, row_ids=None):
+    """4-bit stochastic absmax quantiser, one scale per row -> (codes int8, scales fp32).
+
+    row_ids: indices of the given rows inside the full operand (they address the random bytes);
+    default 0..rows-1."""
     Cm = _f32(Cm)
     rows, K = Cm.shape
     q = np.empty((rows, K), dtype=np.int8)
     s = np.empty(rows, dtype=np.float32)
-    _check(_L().hlqo_quantize_rows(_p(Cm, C.c_float), rows, K, seed, tensor, _p(q, C.c_int8),
-                                   _p(s, C.c_float)), "quantize_rows")
+    ids = None
+    if row_ids is not None:
+        ids = np.ascontiguousarray(row_ids, dtype=np.int64)
+        assert ids.shape == (rows,) and C.sizeof(C.c_long) == 8
+    _check(_L().hlqo_quantize_rows_at(_p(Cm, C.c_float), rows, K, seed, tensor,
+                                      ids.ctypes.data_as(C.POINTER(C.c_long)) if ids is not None else None,
+                                      _p(q, C.c_int8), _p(s, C.c_float)), "quantize_rows")
     return q, s
 
 

@@ -178,3 +178,15 @@ def test_clamp_never_engages_on_quantize_rows():
                 u = (oracle.rand_byte(key, rw, k, 64) + 0.5) / 256.0
                 t = np.float32(np.float64(Cm[rw, k]) * np.float64(inv[rw]) + u)
                 assert -7.0 <= np.floor(t) <= 7.0
+
+
+def test_quantize_rows_subset_matches_full():
+    # a subset of rows, addressed by its indices in the full operand, gets the codes it has there
+    rng = np.random.default_rng(5)
+    Cm = rng.standard_normal((32, 48)).astype(np.float32)
+    q, s = oracle.quantize_rows(Cm, seed=9, tensor=0)
+    ids = np.array([3, 0, 31, 17])
+    q2, s2 = oracle.quantize_rows(Cm[ids], seed=9, tensor=0, row_ids=ids)
+    assert np.array_equal(q2, q[ids]) and np.array_equal(s2, s[ids])
+    q3, _ = oracle.quantize_rows(Cm[ids], seed=9, tensor=0)
+    assert not np.array_equal(q3, q[ids])       # the row index really selects the random bytes
