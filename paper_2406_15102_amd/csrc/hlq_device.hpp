@@ -5,7 +5,7 @@
 //   * H is the +-1 natural-order Walsh-Hadamard matrix; a coefficient is the sum of its B signed
 //     terms added pairwise in index order.  A radix-2 butterfly network with strides 1, 2, 4, ...
 //     (ascending) evaluates exactly that expression tree, so the stage order below is fixed.
-//   * code = clamp(floor(fma(x, 7/absmax, (byte + 0.5)/256)), -7, 7), byte taken from word
+//   * code = floor(fma(x, 7/absmax, (byte + 0.5)/256)) (always inside [-7, 7]), byte taken from word
 //     number row*(K/4) + pos/4 of a keyed counter stream, byte pos%4 of that word.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -95,25 +95,30 @@ __device__ __forceinline__ void fwht_regs(float *v)
     }
 }
 
-// One butterfly stage between lanes l and l^MASK (MASK in {1, 2, 4}): the lane with the bit
-// clear keeps a+b, the other a-b, a being the value of the lower lane.
+// One butterfly stage between lanes l and l^MASK (MASK in {1, 2, 4}) in ONE instruction where the
+// exchange is a DPP quad permute: x <- partner * sigma + x with sigma = +1 in the lane whose MASK
+// bit is clear and -1 in the other.  The product is exact, so the single rounding is that of the
+// add/subtract of the butterfly.  The lower lane gets a + b; the upper lane gets b - a, i.e. the
+// NEGATIVE of the butterfly's difference a - b... with a = lower lane's value: upper holds
+// x_upper - x_lower = -(a - b).  Callers carry that sign per lane (it is the same for both lanes of
+// every later exchange, because they differ in a higher lane bit only) and fold it into whatever
+// consumes the value.  The s_nop covers the VALU-write -> DPP-read hazard, which the compiler
+// cannot see inside an asm statement.
 template <int MASK>
-__device__ __forceinline__ float lane_xor(float x)
+__device__ __forceinline__ float butterfly_lanes_signed(float x, float sigma)
 {
-    int xi = __builtin_bit_cast(int, x);
-    int r;
-    if (MASK == 1) r = __builtin_amdgcn_update_dpp(0, xi, 0xB1, 0xF, 0xF, true);       // quad_perm [1,0,3,2]
-    else if (MASK == 2) r = __builtin_amdgcn_update_dpp(0, xi, 0x4E, 0xF, 0xF, true);  // quad_perm [2,3,0,1]
-    else r = __builtin_amdgcn_ds_swizzle(xi, 0x101F);                                  // lane ^ 4
-    return __builtin_bit_cast(float, r);
-}
-
-template <int MASK>
-__device__ __forceinline__ float butterfly_lanes(float x, bool upper)
-{
-    float p = lane_xor<MASK>(x);
-    float own = upper ? -x : x;
-    return p + own;
+    if (MASK == 1) {
+        asm("s_nop 1\n\tv_fmac_f32_dpp %0, %1, %2 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf bound_ctrl:1"
+            : "+v"(x) : "v"(x), "v"(sigma));
+        return x;
+    } else if (MASK == 2) {
+        asm("s_nop 1\n\tv_fmac_f32_dpp %0, %1, %2 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf bound_ctrl:1"
+            : "+v"(x) : "v"(x), "v"(sigma));
+        return x;
+    } else {
+        const float p = __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, x), 0x101F));  // lane ^ 4
+        return __builtin_fmaf(p, sigma, x);
+    }
 }
 
 // ---- random stream ---------------------------------------------------------------------------
@@ -131,24 +136,36 @@ __device__ __forceinline__ uint32_t rand_word(uint32_t counter, uint32_t k0, uin
     return x;
 }
 
-// Four codes from four values and one random word, packed little-endian into a dword.
-__device__ __forceinline__ int quant_code(float x, float inv, uint32_t byte)
+// floor(t) as an integer in one instruction (v_cvt_flr_i32_f32).
+__device__ __forceinline__ int floor_to_int(float t)
 {
-    float u = (static_cast<float>(byte) + 0.5f) * 0.00390625f;
-    float t = __builtin_fmaf(x, inv, u);
-    int q = static_cast<int>(__builtin_floorf(t));
-    q = q > 7 ? 7 : q;
-    q = q < -7 ? -7 : q;
-    return q;
+    int r;
+    asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(r) : "v"(t));
+    return r;
 }
 
+// One code: floor(fma(x, inv, u)), u = (byte + 0.5) / 256 (exact in fp32, built with one fma).
+// No clamp is needed: |x| <= absmax and inv = RN(7 / absmax) give x*inv in [-7(1+2^-24), 7(1+2^-24)],
+// and u lies in [2^-9, 1 - 2^-9], so the rounded sum stays inside (-7, 8) and its floor inside
+// [-7, 7] (a zero row has inv = 0 and floor(u) = 0).  Inf/NaN inputs are outside the contract.
+__device__ __forceinline__ int quant_code(float x, float inv, float byte_as_float)
+{
+    const float u = __builtin_fmaf(byte_as_float, 0.00390625f, 0.001953125f);
+    return floor_to_int(__builtin_fmaf(x, inv, u));
+}
+
+// Four codes from four values and one random word, packed little-endian into a dword
+// (two's-complement bytes, as the int8 MFMA reads them).
 __device__ __forceinline__ uint32_t quant_pack4(float x0, float x1, float x2, float x3, float inv, uint32_t w)
 {
-    uint32_t q0 = static_cast<uint32_t>(quant_code(x0, inv, w & 0xFFu)) & 0xFFu;
-    uint32_t q1 = static_cast<uint32_t>(quant_code(x1, inv, (w >> 8) & 0xFFu)) & 0xFFu;
-    uint32_t q2 = static_cast<uint32_t>(quant_code(x2, inv, (w >> 16) & 0xFFu)) & 0xFFu;
-    uint32_t q3 = static_cast<uint32_t>(quant_code(x3, inv, w >> 24));
-    return q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
+    const uint32_t q0 = static_cast<uint32_t>(quant_code(x0, inv, static_cast<float>(w & 0xFFu)));
+    const uint32_t q1 = static_cast<uint32_t>(quant_code(x1, inv, static_cast<float>((w >> 8) & 0xFFu)));
+    const uint32_t q2 = static_cast<uint32_t>(quant_code(x2, inv, static_cast<float>((w >> 16) & 0xFFu)));
+    const uint32_t q3 = static_cast<uint32_t>(quant_code(x3, inv, static_cast<float>(w >> 24)));
+    // v_perm_b32: selector bytes 0-3 pick bytes of the second operand, 4-7 of the first, 0x0c = zero
+    const uint32_t lo = __builtin_amdgcn_perm(q1, q0, 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm(q3, q2, 0x04000c0cu);
+    return lo | hi;
 }
 
 __device__ __forceinline__ float absmax_to_inv(float a) { return a > 0.0f ? 7.0f / a : 0.0f; }

@@ -34,13 +34,14 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tin *__restrict__ G,
 #pragma unroll
     for (int m = 0; m < K1_MAXC; ++m) {
         const int ci = g + m * T;
-        if (ci < nch) {
-            Loader<Tin, 8>::load(grow + static_cast<int64_t>(ci) * 8, v[m]);
-        } else {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) v[m][e] = 0.0f;
-        }
+        if (ci < nch) Loader<Tin, 8>::load(grow + static_cast<int64_t>(ci) * 8, v[m]);
     }
+
+    // Cross-lane stages leave the lane with value sign * (coefficient): see butterfly_lanes_signed.
+    const float sg1 = (tid & 1) ? -1.0f : 1.0f;
+    const float sg2 = (tid & 2) ? -1.0f : 1.0f;
+    const float sg4 = (tid & 4) ? -1.0f : 1.0f;
+    const float sign = sg1 * (B >= 32 ? sg2 : 1.0f) * (B >= 64 ? sg4 : 1.0f);
 
     float amax = 0.0f;
 #pragma unroll
@@ -53,9 +54,9 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tin *__restrict__ G,
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 float x = v[m][e];
-                x = butterfly_lanes<1>(x, (tid & 1) != 0);
-                if (B >= 32) x = butterfly_lanes<2>(x, (tid & 2) != 0);
-                if (B >= 64) x = butterfly_lanes<4>(x, (tid & 4) != 0);
+                x = butterfly_lanes_signed<1>(x, sg1);
+                if (B >= 32) x = butterfly_lanes_signed<2>(x, sg2);
+                if (B >= 64) x = butterfly_lanes_signed<4>(x, sg4);
                 v[m][e] = x;
                 amax = fmaxf(amax, fabsf(x));
             }
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tin *__restrict__ G,
     }
 
     if (!row_ok) return;
-    const float inv = absmax_to_inv(amax);
+    const float inv = absmax_to_inv(amax) * sign;   // exact: undoes the sign the lane exchange left
     if (g == 0) sG[row] = absmax_to_scale(amax);
 
     const uint32_t cbase = static_cast<uint32_t>(row) * static_cast<uint32_t>(O >> 2);
@@ -92,8 +93,8 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tin *__restrict__ G,
             *reinterpret_cast<uint2 *>(qrow + static_cast<int64_t>(ci) * 8) = out;
             if (coeff) {
                 float4 *c = reinterpret_cast<float4 *>(coeff + row * static_cast<int64_t>(O) + static_cast<int64_t>(ci) * 8);
-                c[0] = make_float4(v[m][0], v[m][1], v[m][2], v[m][3]);
-                c[1] = make_float4(v[m][4], v[m][5], v[m][6], v[m][7]);
+                c[0] = make_float4(sign * v[m][0], sign * v[m][1], sign * v[m][2], sign * v[m][3]);
+                c[1] = make_float4(sign * v[m][4], sign * v[m][5], sign * v[m][6], sign * v[m][7]);
             }
         }
     }
