@@ -47,7 +47,8 @@ int check_hla_shape(int64_t N, int64_t D, int B, int r)
 int check_gemm_shape(int64_t M, int64_t Nn, int64_t K, int kmult)
 {
     if (M <= 0 || Nn <= 0 || K <= 0 || K % kmult != 0 || Nn % 4 != 0) return HLQ_ERR_SHAPE;
-    if (M > (int64_t(1) << 30) || Nn > (int64_t(1) << 30) || K > (int64_t(1) << 30)) return HLQ_ERR_SHAPE;
+    // 32-bit byte offsets inside a 256-row operand tile: 256 rows x (2 K) bytes must stay below 2^31
+    if (M > (int64_t(1) << 30) || Nn > (int64_t(1) << 30) || K > (int64_t(1) << 21)) return HLQ_ERR_SHAPE;
     if (((M + 127) / 128) * ((Nn + 127) / 128) > (int64_t(1) << 30)) return HLQ_ERR_SHAPE;
     return HLQ_OK;
 }
@@ -271,33 +272,42 @@ int hlq_linear_backward_ex(const void *G, const void *X, const void *XhatT, cons
     const int Kc = static_cast<int>(N / B * r);
     const float invB = 1.0f / static_cast<float>(B);
 
+    // Launch order: everything that streams G first (the second reader then finds it in the
+    // last-level cache), then X, then the two passes over W back to back, then the two products.
+    int8_t *Gq = reinterpret_cast<int8_t *>(ws + L.Gq);
+    float *sG = reinterpret_cast<float *>(ws + L.sG);
+    int8_t *Wq = reinterpret_cast<int8_t *>(ws + L.Wq);
+    float *sW = reinterpret_cast<float *>(ws + L.sW);
+    uint16_t *Gh = reinterpret_cast<uint16_t *>(ws + L.GhatT);
+    const void *Xh = XhatT;
     if (dX) {
-        int8_t *Gq = reinterpret_cast<int8_t *>(ws + L.Gq);
-        float *sG = reinterpret_cast<float *>(ws + L.sG);
-        int8_t *Wq = reinterpret_cast<int8_t *>(ws + L.Wq);
-        float *sW = reinterpret_cast<float *>(ws + L.sW);
-        const uint64_t kg = stream_key(seed, 0), kw = stream_key(seed, 1);
-        // stages 1-2: Q4(G H)
+        // g_x stages 1-2: Q4(G H)
+        const uint64_t kg = stream_key(seed, 0);
         if ((rc = launch_rc(hlq::launch_quant_rows(G, N, O, B, f32, static_cast<uint32_t>(kg),
                                                    static_cast<uint32_t>(kg >> 32), Gq, sG, nullptr, st))) != HLQ_OK)
             return rc;
-        // stages 3-4: Q4(H^T W), transposed
-        if ((rc = launch_rc(hlq::launch_quant_cols(W, O, I, B, f32, static_cast<uint32_t>(kw),
-                                                   static_cast<uint32_t>(kw >> 32), Wq, sW, nullptr, ws + L.wws, st))) != HLQ_OK)
-            return rc;
-        // stages 5-6: integer product and dequantisation (1/B undoes H H^T = B I)
-        hlq::GemmArgs a{Gq, Wq, static_cast<int>(N), I, O, sG, sW, invB, dX, f32, nullptr};
-        if ((rc = launch_rc(hlq::launch_gemm_nt(0, a, st))) != HLQ_OK) return rc;
     }
     if (dW) {
-        uint16_t *Gh = reinterpret_cast<uint16_t *>(ws + L.GhatT);
-        const void *Xh = XhatT;
+        // g_w stages 3 and 1: HLA of G and (unless it was compressed at forward time) of X
+        if ((rc = launch_rc(hlq::launch_hla(G, N, O, B, r, f32, Gh, nullptr, st))) != HLQ_OK) return rc;
         if (!xc) {
             uint16_t *xh = reinterpret_cast<uint16_t *>(ws + L.XhatT);
             if ((rc = launch_rc(hlq::launch_hla(X, N, I, B, r, f32, xh, nullptr, st))) != HLQ_OK) return rc;
             Xh = xh;
         }
-        if ((rc = launch_rc(hlq::launch_hla(G, N, O, B, r, f32, Gh, nullptr, st))) != HLQ_OK) return rc;
+    }
+    if (dX) {
+        // g_x stages 3-4: Q4(H^T W), transposed
+        const uint64_t kw = stream_key(seed, 1);
+        if ((rc = launch_rc(hlq::launch_quant_cols(W, O, I, B, f32, static_cast<uint32_t>(kw),
+                                                   static_cast<uint32_t>(kw >> 32), Wq, sW, nullptr, ws + L.wws, st))) != HLQ_OK)
+            return rc;
+        // g_x stages 5-6: integer product and dequantisation (1/B undoes H H^T = B I)
+        hlq::GemmArgs a{Gq, Wq, static_cast<int>(N), I, O, sG, sW, invB, dX, f32, nullptr};
+        if ((rc = launch_rc(hlq::launch_gemm_nt(0, a, st))) != HLQ_OK) return rc;
+    }
+    if (dW) {
+        // g_w stage 5: product over the compressed token axis
         hlq::GemmArgs a{Gh, Xh, O, I, Kc, nullptr, nullptr, invB, dW, f32, nullptr};
         if ((rc = launch_rc(hlq::launch_gemm_nt(1, a, st))) != HLQ_OK) return rc;
     }

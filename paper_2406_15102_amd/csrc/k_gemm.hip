@@ -281,18 +281,22 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     const int nk = (g.Kb + KCH * 16 - 1) / (KCH * 16);
 
-    // Step KT of k into registers (A rows, then Bm rows).  With a ragged last step (TAIL) chunks
-    // past the end of the row are read from the row's last chunk instead (in bounds) and replaced
-    // by zeros.
+    // Step KT of k into registers (A rows, then Bm rows) with raw buffer loads: the address is
+    // (tile base in the resource) + (per-thread row offset, a loop-invariant VGPR) + (k offset, an
+    // SGPR), so no vector arithmetic is spent on addresses inside the loop.  With a ragged last
+    // step (TAIL) chunks past the end of the row are read from the row's last chunk instead (in
+    // bounds) and replaced by zeros.
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(baseA), 0, 0x7FFFFFFF, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(baseB), 0, 0x7FFFFFFF, 0x00020000);
 #define HLQ_KOFS(KT)                                                                                          \
-        const int kpos = (KT) * (KCH * 16) + lc * 16;                                                         \
-        const bool kok = !TAIL || kpos < g.Kb;                                                                \
-        const uint32_t kofs = static_cast<uint32_t>(kok ? kpos : g.Kb - 16);
+        const int kuni = (KT) * (KCH * 16);               /* wave-uniform: lives in an SGPR */                \
+        const bool kok = !TAIL || kuni + lc * 16 < g.Kb;                                                      \
+        const uint32_t kfix = TAIL ? static_cast<uint32_t>(kok ? lc * 16 : g.Kb - 16 - kuni) : lc * 16u;
 #define HLQ_LOAD_GLOBAL_A(KT)                                                                                 \
     {                                                                                                         \
         HLQ_KOFS(KT)                                                                                          \
         _Pragma("unroll") for (int i = 0; i < PA; ++i) {                                                      \
-            ra[i] = *reinterpret_cast<const u32x4 *>(baseA + (offa[i] + kofs));                               \
+            ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsA, offa[i] + kfix, kuni, 0);                      \
             if (TAIL) ra[i] = kok ? ra[i] : zero4;                                                            \
         }                                                                                                     \
     }
@@ -300,32 +304,48 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
     {                                                                                                         \
         HLQ_KOFS(KT)                                                                                          \
         _Pragma("unroll") for (int j = 0; j < PB; ++j) {                                                      \
-            rb[j] = *reinterpret_cast<const u32x4 *>(baseB + (offb[j] + kofs));                               \
+            rb[j] = __builtin_amdgcn_raw_buffer_load_b128(rsB, offb[j] + kfix, kuni, 0);                      \
             if (TAIL) rb[j] = kok ? rb[j] : zero4;                                                            \
         }                                                                                                     \
     }
-#define HLQ_STORE_LDS_A(STG)                                                                                  \
-    {                                                                                                         \
-        u32x4 *s_ = lds + (STG) * STAGE;                                                                      \
-        _Pragma("unroll") for (int i = 0; i < PA; ++i) s_[lds_chunk<KCH>(lr + RPP * i, lc)] = ra[i];          \
-    }
-#define HLQ_STORE_LDS_B(STG)                                                                                  \
-    {                                                                                                         \
-        u32x4 *s_ = lds + (STG) * STAGE;                                                                      \
-        _Pragma("unroll") for (int j = 0; j < PB; ++j) s_[BM * KCH + lds_chunk<KCH>(lr + RPP * j, lc)] = rb[j]; \
-    }
-
+    // LDS addressing.  Every address is (one per-lane register) + (compile-time immediate): the
+    // swizzle only involves the low four row bits, so the i-th 32-row group is a constant 4 KB
+    // further, and the stage is a single bit (64 KB) toggled by xor once per step.  No address
+    // arithmetic is left between the MFMAs.
+    static_assert(RPP == 32 && KCH == 8, "LDS address immediates below assume 32 rows x 128 B per staging pass");
+    char *const ldsb = reinterpret_cast<char *>(lds);
+    constexpr uint32_t STAGE_BYTES = STAGE * 16u;
+    static_assert((STAGE_BYTES & (STAGE_BYTES - 1)) == 0, "stage toggling by xor needs a power-of-two stage");
     const int fr = lane & 31;   // row within a 32-row MFMA operand
     const int fh = lane >> 5;   // which 16-B half of the 32-B k slice
-    u32x4 fa[2][WM], fb[2][WN];
-
-#define HLQ_READ_FRAGS(BUF, STG, KS)                                                                          \
+    uint32_t wr_off = lds_chunk<KCH>(lr, lc) * 16u + STAGE_BYTES;   // staging writes go to the other stage
+    uint32_t rdA[NS], rdB[NS];                                      // fragment reads, current stage
+#pragma unroll
+    for (int ks = 0; ks < NS; ++ks) {
+        rdA[ks] = lds_chunk<KCH>(wave_m * (32 * WM) + fr, ks * 2 + fh) * 16u;
+        rdB[ks] = (BM * KCH + lds_chunk<KCH>(wave_n * (32 * WN) + fr, ks * 2 + fh)) * 16u;
+    }
+#define HLQ_STORE_LDS_A()                                                                                     \
     {                                                                                                         \
-        const u32x4 *s_ = lds + (STG) * STAGE;                                                                \
+        _Pragma("unroll") for (int i = 0; i < PA; ++i)                                                        \
+            *reinterpret_cast<u32x4 *>(ldsb + wr_off + i * (RPP * KCH * 16)) = ra[i];                         \
+    }
+#define HLQ_STORE_LDS_B()                                                                                     \
+    {                                                                                                         \
+        _Pragma("unroll") for (int j = 0; j < PB; ++j)                                                        \
+            *reinterpret_cast<u32x4 *>(ldsb + wr_off + (BM * KCH * 16) + j * (RPP * KCH * 16)) = rb[j];       \
+    }
+    u32x4 fa[2][WM], fb[2][WN];
+#define HLQ_READ_FRAGS(BUF, KS)                                                                               \
+    {                                                                                                         \
         _Pragma("unroll") for (int i = 0; i < WM; ++i)                                                        \
-            fa[BUF][i] = s_[lds_chunk<KCH>(wave_m * (32 * WM) + i * 32 + fr, (KS) * 2 + fh)];                 \
+            fa[BUF][i] = *reinterpret_cast<const u32x4 *>(ldsb + rdA[KS] + i * (32 * KCH * 16));              \
         _Pragma("unroll") for (int j = 0; j < WN; ++j)                                                        \
-            fb[BUF][j] = s_[BM * KCH + lds_chunk<KCH>(wave_n * (32 * WN) + j * 32 + fr, (KS) * 2 + fh)];      \
+            fb[BUF][j] = *reinterpret_cast<const u32x4 *>(ldsb + rdB[KS] + j * (32 * KCH * 16));              \
+    }
+#define HLQ_TOGGLE_STAGE()                                                                                    \
+    {                                                                                                         \
+        _Pragma("unroll") for (int ks = 0; ks < NS; ++ks) { rdA[ks] ^= STAGE_BYTES; rdB[ks] ^= STAGE_BYTES; } \
     }
 
     // The loop body is branch-free: past the end, steps are clamped to the last one, whose data is
@@ -339,40 +359,44 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
     //   ks = 1       the same for the Bm rows
     //   ks = NS-2    barrier at its end: step kt+1 is complete in LDS, and every wavefront has
     //                finished reading the stage that step kt+2 will overwrite
+    // prologue: step 0 straight into stage 0, step 1 into registers
     HLQ_LOAD_GLOBAL_A(0)
     HLQ_LOAD_GLOBAL_B(0)
-    HLQ_STORE_LDS_A(0)
-    HLQ_STORE_LDS_B(0)
+    wr_off ^= STAGE_BYTES;
+    HLQ_STORE_LDS_A()
+    HLQ_STORE_LDS_B()
+    wr_off ^= STAGE_BYTES;
     HLQ_LOAD_GLOBAL_A(nk > 1 ? 1 : 0)
     HLQ_LOAD_GLOBAL_B(nk > 1 ? 1 : 0)
     lds_barrier();
-    HLQ_READ_FRAGS(0, 0, 0)
+    HLQ_READ_FRAGS(0, 0)
 
     static_assert(NS == 4, "the staging schedule below is written for four sub-steps per step");
     constexpr int MPR = (WM * WN) / (WM + WN);   // MFMAs per fragment read
 
     for (int kt = 0; kt < nk; ++kt) {
-        const int stage = kt & 1;
         const int kt2 = kt + 2 < nk ? kt + 2 : nk - 1;
 #pragma unroll
         for (int ks = 0; ks < NS; ++ks) {
             const int cur = ks & 1;
             if (ks < NS - 1) {
-                HLQ_READ_FRAGS(cur ^ 1, stage, ks + 1)
+                HLQ_READ_FRAGS(cur ^ 1, ks + 1)
             } else {
-                HLQ_READ_FRAGS(cur ^ 1, stage ^ 1, 0)
+                HLQ_TOGGLE_STAGE()          // from here on this wavefront reads the next step's stage
+                HLQ_READ_FRAGS(cur ^ 1, 0)
             }
 #pragma unroll
             for (int i = 0; i < WM; ++i)
 #pragma unroll
                 for (int j = 0; j < WN; ++j) acc[i][j] = Mma<KIND>::mma(fb[cur][j], fa[cur][i], acc[i][j]);
             if (ks == 0) {
-                HLQ_STORE_LDS_A(stage ^ 1)
+                HLQ_STORE_LDS_A()
                 HLQ_LOAD_GLOBAL_A(kt2)
             }
             if (ks == 1) {
-                HLQ_STORE_LDS_B(stage ^ 1)
+                HLQ_STORE_LDS_B()
                 HLQ_LOAD_GLOBAL_B(kt2)
+                wr_off ^= STAGE_BYTES;
             }
             // Issue order within the sub-step.  LDS writes may not pass the fragment reads (same
             // array), so a staging sub-step threads its reads between the first half of the MFMAs
@@ -380,20 +404,20 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
             if (ks < 2) {
 #pragma unroll
                 for (int q = 0; q < (WM * WN) / 2; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x100, 2 * (WM + WN) / (WM * WN), 0);   // fragment reads
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2 * (WM + WN) / (WM * WN), 0);   // fragment reads
                 }
 #pragma unroll
                 for (int q = 0; q < (WM * WN) / 2; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                     __builtin_amdgcn_sched_group_barrier(0x200, 2 * PA / (WM * WN), 0);          // LDS writes
                     __builtin_amdgcn_sched_group_barrier(0x020, 2 * PA / (WM * WN), 0);          // global loads
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 }
             } else {
 #pragma unroll
                 for (int q = 0; q < WM + WN; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                     __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 }
             }
             if (ks == NS - 2) lds_barrier();
@@ -406,6 +430,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
 #undef HLQ_STORE_LDS_A
 #undef HLQ_STORE_LDS_B
 #undef HLQ_READ_FRAGS
+#undef HLQ_TOGGLE_STAGE
 
     // ---- epilogue ----
     __syncthreads();   // all fragment reads are done: LDS is free for staging C
