@@ -149,7 +149,9 @@ __device__ __forceinline__ void store_scaled(typename Mma<KIND>::acc_t (&acc)[WM
     // column factors alpha * sB[n] for the 16 WN columns this lane owns (columns past the edge
     // read sB[0..3]: their products are never stored)
     f32x4 cs[WN][4];
-    if (g.sB) {
+    if (KIND == 1) {
+        // unused
+    } else if (g.sB) {
 #pragma unroll
         for (int j = 0; j < WN; ++j)
 #pragma unroll
@@ -183,7 +185,10 @@ __device__ __forceinline__ void store_scaled(typename Mma<KIND>::acc_t (&acc)[WM
             for (int vg = 0; vg < 4; ++vg) {
                 f32x4 o;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o[e] = Mma<KIND>::to_float(acc[i][j][vg * 4 + e]) * (sa[i] * cs[j][vg][e]);
+                for (int e = 0; e < 4; ++e) {
+                    if (KIND == 1) o[e] = Mma<KIND>::to_float(acc[i][j][vg * 4 + e]) * g.alpha;   // no scales on the bf16 product
+                    else o[e] = Mma<KIND>::to_float(acc[i][j][vg * 4 + e]) * (sa[i] * cs[j][vg][e]);
+                }
                 if (F32) {
                     *reinterpret_cast<f32x4 *>(wr + (j * 32 + vg * 8) * 4) = o;
                 } else {

@@ -9,6 +9,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 
 template <int KIND>
 __global__ __launch_bounds__(256) void k_mfma_probe(int iters, float *sink)
@@ -27,6 +28,24 @@ __global__ __launch_bounds__(256) void k_mfma_probe(int iters, float *sink)
 #pragma unroll
         for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][15];
         if (s == 0x7fffffff) sink[0] = static_cast<float>(s);
+    } else if (KIND >= 2) {
+        // 32x32x64 f8f6f4 MFMA: KIND 2 = fp8 (e4m3), 3 = fp6 (e2m3), 4 = fp4 (e2m1) operands, unit scales
+        constexpr int FMT = KIND == 2 ? 0 : (KIND == 3 ? 2 : 4);
+        v8i a, b;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { a[e] = 0x12345678 * (lane + e + 1); b[e] = 0x9E3779B9 * (lane + 3 * e + 7); }
+        v16f acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = v16f{0.0f};
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, acc[i], FMT, FMT, 0, 127, 0, 127);
+        }
+        float s = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][15];
+        if (s == 12345.678f) sink[0] = s;
     } else {
         v8bf a, b;
 #pragma unroll
@@ -47,8 +66,13 @@ __global__ __launch_bounds__(256) void k_mfma_probe(int iters, float *sink)
 
 hipError_t launch_mfma_probe(int kind, int blocks, int iters, float *sink, hipStream_t st)
 {
-    if (kind == 0) hipLaunchKernelGGL(k_mfma_probe<0>, dim3(blocks), dim3(256), 0, st, iters, sink);
-    else hipLaunchKernelGGL(k_mfma_probe<1>, dim3(blocks), dim3(256), 0, st, iters, sink);
+    switch (kind) {
+        case 0: hipLaunchKernelGGL(k_mfma_probe<0>, dim3(blocks), dim3(256), 0, st, iters, sink); break;
+        case 1: hipLaunchKernelGGL(k_mfma_probe<1>, dim3(blocks), dim3(256), 0, st, iters, sink); break;
+        case 2: hipLaunchKernelGGL(k_mfma_probe<2>, dim3(blocks), dim3(256), 0, st, iters, sink); break;
+        case 3: hipLaunchKernelGGL(k_mfma_probe<3>, dim3(blocks), dim3(256), 0, st, iters, sink); break;
+        default: hipLaunchKernelGGL(k_mfma_probe<4>, dim3(blocks), dim3(256), 0, st, iters, sink); break;
+    }
     return hipGetLastError();
 }
 
