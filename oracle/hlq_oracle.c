@@ -170,7 +170,8 @@ int hlqo_transform_cols(const float *W, long O, long I, int B, float *WhatT /* [
 
 /* Stream key for (seed, tensor id): output number (tensor+1) of the SplitMix64 */
 /* generator (Steele, Lea, Flood 2014; Vigna's public-domain constants)         */
-/* started at state = seed.  tensor: 0 = G operand, 1 = W operand.              */
+/* started at state = seed.  tensor: 0 = G operand, 1 = W operand of the g_x     */
+/* product; 2 = projected X, 3 = projected G of the integer g_w product.         */
 uint64_t hlqo_stream_key(uint64_t seed, uint32_t tensor)
 {
     uint64_t z = seed + ((uint64_t)tensor + 1u) * 0x9E3779B97F4A7C15ull;
@@ -204,33 +205,38 @@ uint32_t hlqo_rand_byte(uint64_t key, long row, long pos, long K)
 }
 
 /* ------------------------------------------------------------------------- */
-/* 4-bit stochastic quantiser (Sec. 5.1 "4-bit stochastic min-max", Sec. 6.1): */
-/* stages 2 and 4 of the g_x path.                                             */
+/* Stochastic "min-max" quantiser (Sec. 5.1, Sec. 6.1): stages 2 and 4 of the  */
+/* g_x path with 4-bit codes (qmax = 7), and with qmax = 127 the int8          */
+/* quantiser of stages 2 and 4 of the g_w path and of the 8-bit warm-up phase  */
+/* (Sec. 7, "all quantization operators use int8 at the initial 25 epochs").   */
 /*   a     = max_k |C[row,k]|             per row                              */
-/*   inv   = 7/a (0 when a == 0),  scale = a/7                                 */
+/*   inv   = qmax/a (0 when a == 0),  scale = a/qmax                           */
 /*   u     = (byte + 0.5)/256   in (0,1), uniform                              */
-/*   q     = clamp(floor(x*inv + u), -7, 7)     x*inv+u rounded once (fma)     */
+/*   q     = clamp(floor(x*inv + u), -qmax, qmax)   x*inv+u rounded once (fma) */
 /* floor(y + u) with u uniform on (0,1) rounds y up with probability frac(y):  */
 /* the unbiased stochastic rounding the paper requires.                        */
 /* ------------------------------------------------------------------------- */
-int8_t hlqo_quantize_one(float x, float inv, uint32_t byte)
+int8_t hlqo_quantize_one_q(float x, float inv, uint32_t byte, int qmax)
 {
     float u = ((float)byte + 0.5f) * 0.00390625f;
     float t = fmaf(x, inv, u);
     int q = (int)floorf(t);
-    if (q > 7) q = 7;
-    if (q < -7) q = -7;
+    if (q > qmax) q = qmax;
+    if (q < -qmax) q = -qmax;
     return (int8_t)q;
 }
 
+int8_t hlqo_quantize_one(float x, float inv, uint32_t byte) { return hlqo_quantize_one_q(x, inv, byte, 7); }
+
 /* Quantise `rows` rows of C; row_ids[i] (or i when row_ids is NULL) is the row's index in the   */
 /* full operand, which is what addresses its random bytes: a subset of rows gets the same codes */
-/* it has inside the full matrix.                                                               */
-int hlqo_quantize_rows_at(const float *C, long rows, long K, uint64_t seed, uint32_t tensor,
-                          const long *row_ids, int8_t *q /* [rows,K] */, float *scale /* [rows] */)
+/* it has inside the full matrix.  qmax is 7 (4-bit codes) or 127 (8-bit codes).                */
+int hlqo_quantize_rows_q(const float *C, long rows, long K, uint64_t seed, uint32_t tensor,
+                         const long *row_ids, int qmax, int8_t *q /* [rows,K] */, float *scale /* [rows] */)
 {
-    if (K % 4) return -1;
+    if (K % 4 || (qmax != 7 && qmax != 127)) return -1;
     uint64_t key = hlqo_stream_key(seed, tensor);
+    const float fq = (float)qmax;
 #pragma omp parallel for schedule(static)
     for (long i = 0; i < rows; ++i) {
         const long row = row_ids ? row_ids[i] : i;
@@ -240,18 +246,24 @@ int hlqo_quantize_rows_at(const float *C, long rows, long K, uint64_t seed, uint
             float m = fabsf(c[k]);
             if (m > a) a = m;
         }
-        float inv = (a > 0.0f) ? 7.0f / a : 0.0f;
-        scale[i] = a / 7.0f;
+        float inv = (a > 0.0f) ? fq / a : 0.0f;
+        scale[i] = a / fq;
         for (long k = 0; k < K; ++k)
-            q[i * K + k] = hlqo_quantize_one(c[k], inv, hlqo_rand_byte(key, row, k, K));
+            q[i * K + k] = hlqo_quantize_one_q(c[k], inv, hlqo_rand_byte(key, row, k, K), qmax);
     }
     return 0;
+}
+
+int hlqo_quantize_rows_at(const float *C, long rows, long K, uint64_t seed, uint32_t tensor,
+                          const long *row_ids, int8_t *q, float *scale)
+{
+    return hlqo_quantize_rows_q(C, rows, K, seed, tensor, row_ids, 7, q, scale);
 }
 
 int hlqo_quantize_rows(const float *C, long rows, long K, uint64_t seed, uint32_t tensor,
                        int8_t *q /* [rows,K] */, float *scale /* [rows] */)
 {
-    return hlqo_quantize_rows_at(C, rows, K, seed, tensor, NULL, q, scale);
+    return hlqo_quantize_rows_q(C, rows, K, seed, tensor, NULL, 7, q, scale);
 }
 
 /* ------------------------------------------------------------------------- */

@@ -16,7 +16,10 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hlq_oracle.c")
 _LIB = os.path.join(_HERE, "libhlq_oracle.so")
 
+TENSOR_G, TENSOR_W, TENSOR_XHAT, TENSOR_GHAT = 0, 1, 2, 3   # random-stream ids of the four quantised operands
+
 __all__ = [
+    "TENSOR_G", "TENSOR_W", "TENSOR_XHAT", "TENSOR_GHAT", "linear_backward_mode",
     "build", "num_threads", "hadamard", "coeff_f32", "coeff_f64", "transform_rows",
     "transform_cols", "stream_key", "rand_word", "rand_byte", "quantize_one", "quantize_rows",
     "int_gemm_nt", "dequant", "hla_f32", "hla_f64", "round_bf16", "gemm_nt_f64",
@@ -59,8 +62,10 @@ def _L():
         lib.hlqo_quantize_one.argtypes = [C.c_float, C.c_float, C.c_uint32]
         lib.hlqo_quantize_one.restype = C.c_int8
         lib.hlqo_quantize_rows.argtypes = [f32p, C.c_long, C.c_long, C.c_uint64, C.c_uint32, i8p, f32p]
-        lib.hlqo_quantize_rows_at.argtypes = [f32p, C.c_long, C.c_long, C.c_uint64, C.c_uint32,
-                                              C.POINTER(C.c_long), i8p, f32p]
+        lib.hlqo_quantize_rows_q.argtypes = [f32p, C.c_long, C.c_long, C.c_uint64, C.c_uint32,
+                                             C.POINTER(C.c_long), C.c_int, i8p, f32p]
+        lib.hlqo_quantize_one_q.argtypes = [C.c_float, C.c_float, C.c_uint32, C.c_int]
+        lib.hlqo_quantize_one_q.restype = C.c_int8
         lib.hlqo_int_gemm_nt.argtypes = [i8p, i8p, C.c_long, C.c_long, C.c_long, i32p]
         lib.hlqo_dequant.argtypes = [i32p, f32p, f32p, C.c_long, C.c_long, C.c_int, f64p]
         lib.hlqo_hla_f32.argtypes = [f32p, C.c_long, C.c_long, C.c_int, C.c_int, f32p]
@@ -151,13 +156,15 @@ def rand_byte(key: int, row: int, pos: int, K: int) -> int:
     return int(_L().hlqo_rand_byte(key, row, pos, K))
 
 
-def quantize_one(x: float, inv: float, byte: int) -> int:
-    return int(_L().hlqo_quantize_one(float(np.float32(x)), float(np.float32(inv)), byte))
+def quantize_one(x: float, inv: float, byte: int, qmax: int = 7) -> int:
+    return int(_L().hlqo_quantize_one_q(float(np.float32(x)), float(np.float32(inv)), byte, qmax))
 
 
-def quantize_rows(Cm, seed: int, tensor: int, row_ids=None):
-    """4-bit stochastic absmax quantiser, one scale per row -> (codes int8, scales fp32).
+def quantize_rows(Cm, seed: int, tensor: int, row_ids=None, qmax: int = 7):
+    """Stochastic absmax quantiser, one scale per row -> (codes int8, scales fp32).
 
+    qmax = 7: the 4-bit codes of the g_x path; qmax = 127: int8 codes (g_w path, 8-bit warm-up).
+    tensor selects the random stream: 0 G, 1 W (g_x product); 2 projected X, 3 projected G (g_w).
     row_ids: indices of the given rows inside the full operand (they address the random bytes);
     default 0..rows-1."""
     Cm = _f32(Cm)
@@ -168,9 +175,9 @@ def quantize_rows(Cm, seed: int, tensor: int, row_ids=None):
     if row_ids is not None:
         ids = np.ascontiguousarray(row_ids, dtype=np.int64)
         assert ids.shape == (rows,) and C.sizeof(C.c_long) == 8
-    _check(_L().hlqo_quantize_rows_at(_p(Cm, C.c_float), rows, K, seed, tensor,
-                                      ids.ctypes.data_as(C.POINTER(C.c_long)) if ids is not None else None,
-                                      _p(q, C.c_int8), _p(s, C.c_float)), "quantize_rows")
+    _check(_L().hlqo_quantize_rows_q(_p(Cm, C.c_float), rows, K, seed, tensor,
+                                     ids.ctypes.data_as(C.POINTER(C.c_long)) if ids is not None else None,
+                                     qmax, _p(q, C.c_int8), _p(s, C.c_float)), "quantize_rows")
     return q, s
 
 
@@ -260,4 +267,35 @@ def linear_backward(G, X, W, B: int, r: int, seed: int, want_dX: bool = True, wa
         _p(xh, C.c_float))
     _check(rc, "linear_backward")
     out.update(dX=dX, dW=dW, Gq=Gq, sG=sG, Wq=Wq, sW=sW, acc=acc, GhatT=gh, XhatT=xh)
+    return out
+
+
+def linear_backward_mode(G, X, W, B: int, r: int, seed: int, gx_bits: int = 4, gw_int8: bool = False):
+    """Both stage lists of Sec. 6.1 composed stage by stage, with the two options of the method:
+
+    gx_bits = 8   the g_x codes use [-127, 127] (the int8 warm-up phase of Sec. 7) instead of 4 bits;
+    gw_int8       the g_w list in full: the HLA-projected X and G are quantised to int8 (stages 2, 4),
+                  multiplied in integers (stage 5) and dequantised (stage 6), instead of being kept
+                  in bf16.
+    Returns a dict with dX, dW (fp64) and every intermediate."""
+    G, X, W = _f32(G), _f32(X), _f32(W)
+    qx = 7 if gx_bits == 4 else 127
+    assert gx_bits in (4, 8)
+    out = {}
+    # g_x: 1. FWH(g_o) on O  2. Q  3. FWH(w) on O  4. Q  5. integer product  6. dequantise
+    Gq, sG = quantize_rows(transform_rows(G, B), seed, TENSOR_G, qmax=qx)
+    Wq, sW = quantize_rows(transform_cols(W, B), seed, TENSOR_W, qmax=qx)
+    acc = int_gemm_nt(Gq, Wq)
+    out.update(Gq=Gq, sG=sG, Wq=Wq, sW=sW, acc=acc, dX=dequant(acc, sG, sW, B))
+    # g_w: 1. HLA(x) on L  2. Q8  3. HLA(g_o^T) on L  4. Q8  5. integer product  6. dequantise
+    xh = hla_f32(X, B, r)
+    gh = hla_f32(G, B, r)
+    if gw_int8:
+        Xq, sX = quantize_rows(xh, seed, TENSOR_XHAT, qmax=127)
+        Gq2, sG2 = quantize_rows(gh, seed, TENSOR_GHAT, qmax=127)
+        accw = int_gemm_nt(Gq2, Xq)
+        out.update(XqT=Xq, sX=sX, GqT=Gq2, sGhat=sG2, accw=accw, dW=dequant(accw, sG2, sX, B))
+    else:
+        xh, gh = round_bf16(xh), round_bf16(gh)
+        out.update(XhatT=xh, GhatT=gh, dW=gemm_nt_f64(gh, xh, 1.0 / B))
     return out
