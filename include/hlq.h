@@ -111,21 +111,24 @@ int hlq_compress_act(const void *X, int64_t N, int64_t d_in, int B, int r, int d
 
 /*
  * Stages 1-2 of the g_x list: block Hadamard transform of every row of G along d_out, then
- * 4-bit stochastic quantisation with one absmax scale per row.
- *   Gq [N, d_out] int8, codes in [-7, 7];  sG [N] fp32, sG[n] = max|coef|/7.
+ * stochastic quantisation with one absmax scale per row.
+ *   bits  4: codes in [-7, 7] (the method's setting); 8: codes in [-127, 127] (the int8 warm-up
+ *         phase of Sec. 7).  Anything else: HLQ_ERR_DTYPE.
+ *   Gq [N, d_out] int8;  sG [N] fp32, sG[n] = max|coef| / qmax.
  *   coeff: NULL, or [N, d_out] fp32 receiving the transformed values (unnormalised H).
  */
-int hlq_quantize_g(const void *G, int64_t N, int64_t d_out, int B, uint64_t seed, int dtype,
+int hlq_quantize_g(const void *G, int64_t N, int64_t d_out, int B, uint64_t seed, int dtype, int bits,
                    int8_t *Gq, float *sG, float *coeff, void *stream);
 
 /*
  * Stages 3-4 of the g_x list: H^T W (blocks of B consecutive rows of W are mixed), quantised
  * with one scale per in-feature and stored transposed, reduction axis contiguous:
  *   WqT [d_in, d_out] int8;  sW [d_in] fp32;  coeffT: NULL or [d_in, d_out] fp32.
+ *   bits: 4 or 8, as for hlq_quantize_g.
  *   workspace: >= hlq_quantize_w_workspace_bytes(d_out, d_in) bytes of device scratch (256-aligned).
  */
 size_t hlq_quantize_w_workspace_bytes(int64_t d_out, int64_t d_in);
-int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t seed, int dtype,
+int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t seed, int dtype, int bits,
                    int8_t *WqT, float *sW, float *coeffT, void *workspace, size_t workspace_bytes,
                    void *stream);
 
@@ -154,6 +157,51 @@ int hlq_hla_project(const void *T, int64_t N, int64_t D, int B, int r, int dtype
  */
 int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64_t K, float alpha,
                      int out_dtype, void *C, void *stream);
+
+/* ---- the method's two options: 8-bit g_x codes, and the g_w list in integers ------------------- */
+
+/* flags of hlq_linear_backward_mode / hlq_workspace_bytes_mode */
+#define HLQ_FLAG_GX_8BIT 1 /* g_x codes in [-127, 127]: the int8 warm-up phase of Sec. 7 */
+#define HLQ_FLAG_GW_INT8 2 /* g_w list in full (Sec. 6.1): projected X and G quantised to int8
+                              (stages 2, 4), integer product (5), dequantisation (6) */
+
+/*
+ * Stages 1-2 (T = X, tensor 2) or 3-4 (T = G, tensor 3) of the g_w list: the projection described
+ * at hlq_compress_act followed by int8 stochastic quantisation (codes in [-127, 127]) with one
+ * absmax scale per feature:
+ *   TqT [D, N/B*r] int8;  sT [D] fp32;  coeffT: NULL or [D, N/B*r] fp32 (coefficients before
+ *   quantisation).  Needs r % 4 == 0 (HLQ_ERR_RANK) and (N/B*r) % 16 == 0 (HLQ_ERR_SHAPE).
+ *   tensor: 2 or 3, selects the random stream (HLQ_ERR_SHAPE otherwise).
+ *   workspace: >= hlq_hla_quantize_workspace_bytes(D) bytes of device scratch (256-aligned).
+ */
+size_t hlq_hla_quantize_workspace_bytes(int64_t D);
+int hlq_hla_quantize(const void *T, int64_t N, int64_t D, int B, int r, uint64_t seed, int tensor, int dtype,
+                     int8_t *TqT, float *sT, float *coeffT, void *workspace, size_t workspace_bytes,
+                     void *stream);
+
+/*
+ * ACBP with integer storage (Sec. 6.1: "apply stages 1 and 2 during forward propagation and store
+ * the intermediate feature map" in integers): hlq_hla_quantize on X with tensor 2.
+ * XqT [d_in, N/B*r] int8, sX [d_in] fp32: a quarter (r = B/2) of X's bf16 footprint.
+ */
+int hlq_compress_act_int8(const void *X, int64_t N, int64_t d_in, int B, int r, uint64_t seed, int dtype,
+                          int8_t *XqT, float *sX, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * hlq_linear_backward_ex with the options above.
+ *   Xc, sXc   X compressed at forward time, or NULL: bf16 XhatT (sXc NULL) without
+ *             HLQ_FLAG_GW_INT8; int8 XqT with its scales sXc [d_in] with it.  Exactly one of X and
+ *             Xc when dW is wanted.
+ *   flags     any combination of HLQ_FLAG_*; 0 = hlq_linear_backward_ex.
+ *   workspace >= hlq_workspace_bytes_mode(...) bytes, 256-aligned, or NULL for the library-owned one.
+ * HLQ_FLAG_GW_INT8 additionally needs r % 4 == 0 (HLQ_ERR_RANK) and (N/B*r) % 16 == 0.
+ */
+size_t hlq_workspace_bytes_mode(int64_t N, int64_t d_in, int64_t d_out, int B, int r, int x_is_compressed,
+                                int flags);
+int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const float *sXc, const void *W,
+                             int64_t N, int64_t d_in, int64_t d_out, int B, int r, uint64_t seed, int dtype,
+                             int flags, void *dX, void *dW, void *workspace, size_t workspace_bytes,
+                             void *stream);
 
 /*
  * Diagnostic, not part of the backward pass: `blocks` workgroups of four wavefronts each issue

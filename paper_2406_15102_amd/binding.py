@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libhlq.so")
 
 HLQ_BF16, HLQ_F32 = 0, 1
 HLQ_OK = 0
+HLQ_FLAG_GX_8BIT, HLQ_FLAG_GW_INT8 = 1, 2
 
 _EXPORTS = {
     "hlq_status_str": (C.c_char_p, [C.c_int]),
@@ -28,11 +29,19 @@ _EXPORTS = {
                                + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]),
     "hlq_compress_act": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                    C.c_void_p]),
-    "hlq_quantize_g": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_uint64, C.c_int, C.c_void_p,
+    "hlq_quantize_g": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_uint64, C.c_int, C.c_int, C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_void_p]),
     "hlq_quantize_w_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64]),
-    "hlq_quantize_w": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_uint64, C.c_int, C.c_void_p,
+    "hlq_quantize_w": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_uint64, C.c_int, C.c_int, C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "hlq_hla_quantize_workspace_bytes": (C.c_size_t, [C.c_int64]),
+    "hlq_hla_quantize": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_uint64, C.c_int, C.c_int,
+                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "hlq_compress_act_int8": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_uint64, C.c_int,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "hlq_workspace_bytes_mode": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int]),
+    "hlq_linear_backward_mode": (C.c_int, [C.c_void_p] * 5 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64, C.c_int,
+                                           C.c_int] + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]),
     "hlq_int8_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                    C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
     "hlq_hla_project": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p,
@@ -139,9 +148,9 @@ def hlq_compress_act(X, B, r, XhatT):
            "hlq_compress_act")
 
 
-def hlq_quantize_g(G, B, seed, Gq, sG, coeff=None):
+def hlq_quantize_g(G, B, seed, Gq, sG, coeff=None, bits=4):
     N, d_out = G.shape
-    _check(lib().hlq_quantize_g(_ptr(G), N, d_out, B, seed, _dt(G), _ptr(Gq, torch.int8), _ptr(sG, torch.float32),
+    _check(lib().hlq_quantize_g(_ptr(G), N, d_out, B, seed, _dt(G), bits, _ptr(Gq, torch.int8), _ptr(sG, torch.float32),
                                 _ptr(coeff, torch.float32), _stream()), "hlq_quantize_g")
 
 
@@ -149,9 +158,9 @@ def hlq_quantize_w_workspace_bytes(d_out, d_in) -> int:
     return int(lib().hlq_quantize_w_workspace_bytes(d_out, d_in))
 
 
-def hlq_quantize_w(W, B, seed, WqT, sW, workspace, coeffT=None):
+def hlq_quantize_w(W, B, seed, WqT, sW, workspace, coeffT=None, bits=4):
     d_out, d_in = W.shape
-    _check(lib().hlq_quantize_w(_ptr(W), d_out, d_in, B, seed, _dt(W), _ptr(WqT, torch.int8), _ptr(sW, torch.float32),
+    _check(lib().hlq_quantize_w(_ptr(W), d_out, d_in, B, seed, _dt(W), bits, _ptr(WqT, torch.int8), _ptr(sW, torch.float32),
                                 _ptr(coeffT, torch.float32), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream()), "hlq_quantize_w")
 
@@ -180,3 +189,37 @@ def hlq_bf16_gemm_nt(A, Bm, alpha, C_out):
 
 def hlq_mfma_probe(kind, blocks, iters, sink):
     _check(lib().hlq_mfma_probe(kind, blocks, iters, _ptr(sink, torch.float32), _stream()), "hlq_mfma_probe")
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size()
+
+
+def hlq_hla_quantize_workspace_bytes(D) -> int:
+    return int(lib().hlq_hla_quantize_workspace_bytes(D))
+
+
+def hlq_hla_quantize(T, B, r, seed, tensor, TqT, sT, workspace, coeffT=None):
+    N, D = T.shape
+    _check(lib().hlq_hla_quantize(_ptr(T), N, D, B, r, seed, tensor, _dt(T), _ptr(TqT, torch.int8),
+                                  _ptr(sT, torch.float32), _ptr(coeffT, torch.float32), _ptr(workspace),
+                                  _nbytes(workspace), _stream()), "hlq_hla_quantize")
+
+
+def hlq_compress_act_int8(X, B, r, seed, XqT, sX, workspace):
+    N, d_in = X.shape
+    _check(lib().hlq_compress_act_int8(_ptr(X), N, d_in, B, r, seed, _dt(X), _ptr(XqT, torch.int8),
+                                       _ptr(sX, torch.float32), _ptr(workspace), _nbytes(workspace), _stream()),
+           "hlq_compress_act_int8")
+
+
+def hlq_workspace_bytes_mode(N, d_in, d_out, B, r, x_is_compressed=False, flags=0) -> int:
+    return int(lib().hlq_workspace_bytes_mode(N, d_in, d_out, B, r, int(bool(x_is_compressed)), flags))
+
+
+def hlq_linear_backward_mode(G, X, Xc, sXc, W, N, d_in, d_out, B, r, seed, flags, dX, dW, workspace=None):
+    """hlq_linear_backward_ex with HLQ_FLAG_GX_8BIT / HLQ_FLAG_GW_INT8."""
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (_ptr(workspace), _nbytes(workspace))
+    _check(lib().hlq_linear_backward_mode(_ptr(G), _ptr(X), _ptr(Xc), _ptr(sXc, torch.float32), _ptr(W), N, d_in,
+                                          d_out, B, r, seed, _dt(G), flags, _ptr(dX), _ptr(dW), ws_ptr, ws_bytes,
+                                          _stream()), "hlq_linear_backward_mode")

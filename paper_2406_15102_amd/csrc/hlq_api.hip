@@ -69,26 +69,45 @@ int check_backward_shape(int64_t N, int64_t d_in, int64_t d_out, int B, int r)
     return HLQ_OK;
 }
 
-// Carving of the backward workspace.
+// Carving of the backward workspace.  With HLQ_FLAG_GW_INT8 the compressed operands are int8
+// codes with one scale per feature plus one word of column maximum per feature.
 struct Layout {
-    size_t Gq, sG, Wq, sW, wws, GhatT, XhatT, total;
+    size_t Gq, sG, Wq, sW, wws, GhatT, sGhat, XhatT, sXhat, hws, total;
 };
 
-Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_is_compressed)
+Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_is_compressed, int flags)
 {
     Layout L;
     const size_t Kc = static_cast<size_t>(N / B * r);
+    const bool gwi = (flags & HLQ_FLAG_GW_INT8) != 0;
+    const size_t esz = gwi ? 1 : 2;
     size_t off = 0;
     L.Gq = off;    off += up256(static_cast<size_t>(N) * d_out);
     L.sG = off;    off += up256(static_cast<size_t>(N) * 4);
     L.Wq = off;    off += up256(static_cast<size_t>(d_in) * d_out);
     L.sW = off;    off += up256(static_cast<size_t>(d_in) * 4);
     L.wws = off;   off += up256(hlq::quant_cols_ws_bytes(d_out, d_in));
-    L.GhatT = off; off += up256(static_cast<size_t>(d_out) * Kc * 2);
-    L.XhatT = off; off += x_is_compressed ? 0 : up256(static_cast<size_t>(d_in) * Kc * 2);
+    L.GhatT = off; off += up256(static_cast<size_t>(d_out) * Kc * esz);
+    L.sGhat = off; off += gwi ? up256(static_cast<size_t>(d_out) * 4) : 0;
+    L.XhatT = off; off += x_is_compressed ? 0 : up256(static_cast<size_t>(d_in) * Kc * esz);
+    L.sXhat = off; off += (gwi && !x_is_compressed) ? up256(static_cast<size_t>(d_in) * 4) : 0;
+    L.hws = off;   off += gwi ? up256(hlq::hla_quant_ws_bytes(d_out > d_in ? d_out : d_in)) : 0;
     L.total = off;
     return L;
 }
+
+int check_flags(int flags, int r, int64_t N, int B)
+{
+    if (flags & ~(HLQ_FLAG_GX_8BIT | HLQ_FLAG_GW_INT8)) return HLQ_ERR_SHAPE;
+    if (flags & HLQ_FLAG_GW_INT8) {
+        if (r % 4 != 0) return HLQ_ERR_RANK;
+        if ((N / B * r) % 16 != 0) return HLQ_ERR_SHAPE;
+    }
+    return HLQ_OK;
+}
+
+inline bool bits_ok(int bits) { return bits == 4 || bits == 8; }
+inline float bits_qmax(int bits) { return bits == 8 ? 127.0f : 7.0f; }
 
 // Library-owned workspace, one per device, grown on demand.
 constexpr int kMaxDevices = 64;
@@ -147,22 +166,29 @@ int hlq_version(void) { return 100; }
 size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r, int x_is_compressed)
 {
     if (check_backward_shape(N, d_in, d_out, B, r) != HLQ_OK) return 0;
-    return make_layout(N, d_in, d_out, B, r, x_is_compressed != 0).total;
+    return make_layout(N, d_in, d_out, B, r, x_is_compressed != 0, 0).total;
 }
 
-int hlq_quantize_g(const void *G, int64_t N, int64_t d_out, int B, uint64_t seed, int dtype, int8_t *Gq,
+size_t hlq_workspace_bytes_mode(int64_t N, int64_t d_in, int64_t d_out, int B, int r, int x_is_compressed, int flags)
+{
+    if (check_backward_shape(N, d_in, d_out, B, r) != HLQ_OK || check_flags(flags, r, N, B) != HLQ_OK) return 0;
+    return make_layout(N, d_in, d_out, B, r, x_is_compressed != 0, flags).total;
+}
+
+int hlq_quantize_g(const void *G, int64_t N, int64_t d_out, int B, uint64_t seed, int dtype, int bits, int8_t *Gq,
                    float *sG, float *coeff, void *stream)
 {
     int rc;
     if (!G || !Gq || !sG) return HLQ_ERR_NULL;
     if ((rc = check_block(B)) != HLQ_OK) return rc;
     if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if (!bits_ok(bits)) return HLQ_ERR_DTYPE;
     if ((rc = check_quant_shape(N, d_out, B)) != HLQ_OK) return rc;
     if (!aligned(G, 16) || !aligned(Gq, 8) || (coeff && !aligned(coeff, 16))) return HLQ_ERR_SHAPE;
     const uint64_t key = stream_key(seed, 0);
     return launch_rc(hlq::launch_quant_rows(G, N, static_cast<int>(d_out), B, dtype == HLQ_F32,
-                                            static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32), Gq, sG,
-                                            coeff, static_cast<hipStream_t>(stream)));
+                                            static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32),
+                                            bits_qmax(bits), Gq, sG, coeff, static_cast<hipStream_t>(stream)));
 }
 
 size_t hlq_quantize_w_workspace_bytes(int64_t d_out, int64_t d_in)
@@ -171,21 +197,23 @@ size_t hlq_quantize_w_workspace_bytes(int64_t d_out, int64_t d_in)
     return hlq::quant_cols_ws_bytes(d_out, d_in);
 }
 
-int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t seed, int dtype, int8_t *WqT,
+int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t seed, int dtype, int bits, int8_t *WqT,
                    float *sW, float *coeffT, void *workspace, size_t workspace_bytes, void *stream)
 {
     int rc;
     if (!W || !WqT || !sW || !workspace) return HLQ_ERR_NULL;
     if ((rc = check_block(B)) != HLQ_OK) return rc;
     if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if (!bits_ok(bits)) return HLQ_ERR_DTYPE;
     if (d_in <= 0 || d_in % 8 != 0) return HLQ_ERR_SHAPE;
     if ((rc = check_quant_shape(d_in, d_out, B)) != HLQ_OK) return rc;
     if (!aligned(W, 16) || !aligned(WqT, 16) || (coeffT && !aligned(coeffT, 16))) return HLQ_ERR_SHAPE;
     if (!aligned(workspace, 256) || workspace_bytes < hlq::quant_cols_ws_bytes(d_out, d_in)) return HLQ_ERR_WORKSPACE;
     const uint64_t key = stream_key(seed, 1);
     return launch_rc(hlq::launch_quant_cols(W, static_cast<int>(d_out), static_cast<int>(d_in), B, dtype == HLQ_F32,
-                                            static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32), WqT, sW,
-                                            coeffT, workspace, static_cast<hipStream_t>(stream)));
+                                            static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32),
+                                            bits_qmax(bits), WqT, sW, coeffT, workspace,
+                                            static_cast<hipStream_t>(stream)));
 }
 
 int hlq_int8_gemm_nt(const int8_t *A, const int8_t *Bm, int64_t M, int64_t Nn, int64_t K, const float *sA,
@@ -242,22 +270,57 @@ int hlq_mfma_probe(int kind, int blocks, int iters, float *sink, void *stream)
     return launch_rc(hlq::launch_mfma_probe(kind, blocks, iters, sink, static_cast<hipStream_t>(stream)));
 }
 
-int hlq_linear_backward_ex(const void *G, const void *X, const void *XhatT, const void *W, int64_t N, int64_t d_in,
-                           int64_t d_out, int B, int r, uint64_t seed, int dtype, void *dX, void *dW,
-                           void *workspace, size_t workspace_bytes, void *stream)
+size_t hlq_hla_quantize_workspace_bytes(int64_t D) { return D > 0 ? hlq::hla_quant_ws_bytes(D) : 0; }
+
+int hlq_hla_quantize(const void *T, int64_t N, int64_t D, int B, int r, uint64_t seed, int tensor, int dtype,
+                     int8_t *TqT, float *sT, float *coeffT, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc;
+    if (!T || !TqT || !sT || !workspace) return HLQ_ERR_NULL;
+    if ((rc = check_block(B)) != HLQ_OK) return rc;
+    if ((rc = check_rank(B, r)) != HLQ_OK) return rc;
+    if (r % 4 != 0) return HLQ_ERR_RANK;
+    if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if ((rc = check_hla_shape(N, D, B, r)) != HLQ_OK) return rc;
+    if (tensor != 2 && tensor != 3) return HLQ_ERR_SHAPE;
+    const int64_t Kc = N / B * r;
+    if (Kc % 16 != 0 || D * (Kc / 4) >= (int64_t(1) << 32)) return HLQ_ERR_SHAPE;
+    if (!aligned(T, 16) || !aligned(TqT, 16) || (coeffT && !aligned(coeffT, 16))) return HLQ_ERR_SHAPE;
+    if (!aligned(workspace, 256) || workspace_bytes < hlq::hla_quant_ws_bytes(D)) return HLQ_ERR_WORKSPACE;
+    const uint64_t key = stream_key(seed, static_cast<uint32_t>(tensor));
+    return launch_rc(hlq::launch_hla_quant(T, N, static_cast<int>(D), B, r, dtype == HLQ_F32,
+                                           static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32), TqT, sT,
+                                           coeffT, workspace, static_cast<hipStream_t>(stream)));
+}
+
+int hlq_compress_act_int8(const void *X, int64_t N, int64_t d_in, int B, int r, uint64_t seed, int dtype,
+                          int8_t *XqT, float *sX, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return hlq_hla_quantize(X, N, d_in, B, r, seed, 2, dtype, XqT, sX, nullptr, workspace, workspace_bytes, stream);
+}
+
+int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const float *sXc, const void *W, int64_t N,
+                             int64_t d_in, int64_t d_out, int B, int r, uint64_t seed, int dtype, int flags, void *dX,
+                             void *dW, void *workspace, size_t workspace_bytes, void *stream)
 {
     int rc;
     if ((rc = check_backward_shape(N, d_in, d_out, B, r)) != HLQ_OK) return rc;
     if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if ((rc = check_flags(flags, r, N, B)) != HLQ_OK) return rc;
+    const bool gwi = (flags & HLQ_FLAG_GW_INT8) != 0;
+    const float qmax = (flags & HLQ_FLAG_GX_8BIT) ? 127.0f : 7.0f;
     if (!G || (!dX && !dW)) return HLQ_ERR_NULL;
     if (dX && !W) return HLQ_ERR_NULL;
-    if (dW && ((X == nullptr) == (XhatT == nullptr))) return HLQ_ERR_NULL;   // exactly one of the two
-    if (!aligned(G, 16) || (X && !aligned(X, 16)) || (XhatT && !aligned(XhatT, 16)) || (W && !aligned(W, 16)) ||
-        (dX && !aligned(dX, 16)) || (dW && !aligned(dW, 16)))
+    if (dW && ((X == nullptr) == (Xc == nullptr))) return HLQ_ERR_NULL;   // exactly one of the two
+    if (dW && Xc && (gwi != (sXc != nullptr))) return HLQ_ERR_NULL;       // int8 codes come with their scales
+    if (!aligned(G, 16) || (X && !aligned(X, 16)) || (Xc && !aligned(Xc, 16)) || (sXc && !aligned(sXc, 16)) ||
+        (W && !aligned(W, 16)) || (dX && !aligned(dX, 16)) || (dW && !aligned(dW, 16)))
+        return HLQ_ERR_SHAPE;
+    if (gwi && static_cast<int64_t>(d_out > d_in ? d_out : d_in) * (N / B * r / 4) >= (int64_t(1) << 32))
         return HLQ_ERR_SHAPE;
 
-    const bool xc = (XhatT != nullptr);
-    const Layout L = make_layout(N, d_in, d_out, B, r, xc);
+    const bool xc = (Xc != nullptr);
+    const Layout L = make_layout(N, d_in, d_out, B, r, xc, flags);
     char *ws = static_cast<char *>(workspace);
     if (ws) {
         if (!aligned(ws, 256) || workspace_bytes < L.total) return HLQ_ERR_WORKSPACE;
@@ -278,40 +341,74 @@ int hlq_linear_backward_ex(const void *G, const void *X, const void *XhatT, cons
     float *sG = reinterpret_cast<float *>(ws + L.sG);
     int8_t *Wq = reinterpret_cast<int8_t *>(ws + L.Wq);
     float *sW = reinterpret_cast<float *>(ws + L.sW);
-    uint16_t *Gh = reinterpret_cast<uint16_t *>(ws + L.GhatT);
-    const void *Xh = XhatT;
+    void *Gh = ws + L.GhatT;
+    float *sGh = reinterpret_cast<float *>(ws + L.sGhat);
+    const void *Xh = Xc;
+    const float *sXh = sXc;
     if (dX) {
-        // g_x stages 1-2: Q4(G H)
+        // g_x stages 1-2: Q(G H)
         const uint64_t kg = stream_key(seed, 0);
         if ((rc = launch_rc(hlq::launch_quant_rows(G, N, O, B, f32, static_cast<uint32_t>(kg),
-                                                   static_cast<uint32_t>(kg >> 32), Gq, sG, nullptr, st))) != HLQ_OK)
+                                                   static_cast<uint32_t>(kg >> 32), qmax, Gq, sG, nullptr, st))) != HLQ_OK)
             return rc;
     }
-    if (dW) {
-        // g_w stages 3 and 1: HLA of G and (unless it was compressed at forward time) of X
-        if ((rc = launch_rc(hlq::launch_hla(G, N, O, B, r, f32, Gh, nullptr, st))) != HLQ_OK) return rc;
+    if (dW && !gwi) {
+        // g_w stages 3 and 1 kept in bf16: HLA of G and (unless it was compressed at forward time) of X
+        if ((rc = launch_rc(hlq::launch_hla(G, N, O, B, r, f32, static_cast<uint16_t *>(Gh), nullptr, st))) != HLQ_OK) return rc;
         if (!xc) {
             uint16_t *xh = reinterpret_cast<uint16_t *>(ws + L.XhatT);
             if ((rc = launch_rc(hlq::launch_hla(X, N, I, B, r, f32, xh, nullptr, st))) != HLQ_OK) return rc;
             Xh = xh;
         }
     }
+    if (dW && gwi) {
+        // g_w stages 3-4 and 1-2: HLA + int8 quantisation of G (stream 3) and of X (stream 2)
+        const uint64_t k3 = stream_key(seed, 3), k2 = stream_key(seed, 2);
+        if ((rc = launch_rc(hlq::launch_hla_quant(G, N, O, B, r, f32, static_cast<uint32_t>(k3),
+                                                  static_cast<uint32_t>(k3 >> 32), static_cast<int8_t *>(Gh), sGh,
+                                                  nullptr, ws + L.hws, st))) != HLQ_OK)
+            return rc;
+        if (!xc) {
+            int8_t *xq = reinterpret_cast<int8_t *>(ws + L.XhatT);
+            float *sx = reinterpret_cast<float *>(ws + L.sXhat);
+            if ((rc = launch_rc(hlq::launch_hla_quant(X, N, I, B, r, f32, static_cast<uint32_t>(k2),
+                                                      static_cast<uint32_t>(k2 >> 32), xq, sx, nullptr, ws + L.hws,
+                                                      st))) != HLQ_OK)
+                return rc;
+            Xh = xq;
+            sXh = sx;
+        }
+    }
     if (dX) {
-        // g_x stages 3-4: Q4(H^T W), transposed
+        // g_x stages 3-4: Q(H^T W), transposed
         const uint64_t kw = stream_key(seed, 1);
         if ((rc = launch_rc(hlq::launch_quant_cols(W, O, I, B, f32, static_cast<uint32_t>(kw),
-                                                   static_cast<uint32_t>(kw >> 32), Wq, sW, nullptr, ws + L.wws, st))) != HLQ_OK)
+                                                   static_cast<uint32_t>(kw >> 32), qmax, Wq, sW, nullptr, ws + L.wws,
+                                                   st))) != HLQ_OK)
             return rc;
         // g_x stages 5-6: integer product and dequantisation (1/B undoes H H^T = B I)
         hlq::GemmArgs a{Gq, Wq, static_cast<int>(N), I, O, sG, sW, invB, dX, f32, nullptr};
         if ((rc = launch_rc(hlq::launch_gemm_nt(0, a, st))) != HLQ_OK) return rc;
     }
     if (dW) {
-        // g_w stage 5: product over the compressed token axis
-        hlq::GemmArgs a{Gh, Xh, O, I, Kc, nullptr, nullptr, invB, dW, f32, nullptr};
-        if ((rc = launch_rc(hlq::launch_gemm_nt(1, a, st))) != HLQ_OK) return rc;
+        // g_w stage 5 (and 6): product over the compressed token axis
+        if (gwi) {
+            hlq::GemmArgs a{Gh, Xh, O, I, Kc, sGh, sXh, invB, dW, f32, nullptr};
+            if ((rc = launch_rc(hlq::launch_gemm_nt(0, a, st))) != HLQ_OK) return rc;
+        } else {
+            hlq::GemmArgs a{Gh, Xh, O, I, Kc, nullptr, nullptr, invB, dW, f32, nullptr};
+            if ((rc = launch_rc(hlq::launch_gemm_nt(1, a, st))) != HLQ_OK) return rc;
+        }
     }
     return HLQ_OK;
+}
+
+int hlq_linear_backward_ex(const void *G, const void *X, const void *XhatT, const void *W, int64_t N, int64_t d_in,
+                           int64_t d_out, int B, int r, uint64_t seed, int dtype, void *dX, void *dW,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    return hlq_linear_backward_mode(G, X, XhatT, nullptr, W, N, d_in, d_out, B, r, seed, dtype, 0, dX, dW, workspace,
+                                    workspace_bytes, stream);
 }
 
 int hlq_linear_backward(const void *G, const void *X, const void *W, int64_t N, int64_t d_in, int64_t d_out, int B,

@@ -5,7 +5,8 @@
 //   * H is the +-1 natural-order Walsh-Hadamard matrix; a coefficient is the sum of its B signed
 //     terms added pairwise in index order.  A radix-2 butterfly network with strides 1, 2, 4, ...
 //     (ascending) evaluates exactly that expression tree, so the stage order below is fixed.
-//   * code = floor(fma(x, 7/absmax, (byte + 0.5)/256)) (always inside [-7, 7]), byte taken from word
+//   * code = floor(fma(x, qmax/absmax, (byte + 0.5)/256)) (always inside [-qmax, qmax]; qmax = 7
+//     or 127), byte taken from word
 //     number row*(K/4) + pos/4 of a keyed counter stream, byte pos%4 of that word.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -145,9 +146,10 @@ __device__ __forceinline__ int floor_to_int(float t)
 }
 
 // One code: floor(fma(x, inv, u)), u = (byte + 0.5) / 256 (exact in fp32, built with one fma).
-// No clamp is needed: |x| <= absmax and inv = RN(7 / absmax) give x*inv in [-7(1+2^-24), 7(1+2^-24)],
-// and u lies in [2^-9, 1 - 2^-9], so the rounded sum stays inside (-7, 8) and its floor inside
-// [-7, 7] (a zero row has inv = 0 and floor(u) = 0).  Inf/NaN inputs are outside the contract.
+// No clamp is needed: |x| <= absmax and inv = RN(qmax / absmax) give |x*inv| <= qmax (1 + 2^-24),
+// and u lies in [2^-9, 1 - 2^-9], so the rounded sum stays inside (-qmax, qmax + 1) and its floor
+// inside [-qmax, qmax] (a zero row has inv = 0 and floor(u) = 0).  Inf/NaN inputs are outside the
+// contract.
 __device__ __forceinline__ int quant_code(float x, float inv, float byte_as_float)
 {
     const float u = __builtin_fmaf(byte_as_float, 0.00390625f, 0.001953125f);
@@ -168,7 +170,8 @@ __device__ __forceinline__ uint32_t quant_pack4(float x0, float x1, float x2, fl
     return lo | hi;
 }
 
-__device__ __forceinline__ float absmax_to_inv(float a) { return a > 0.0f ? 7.0f / a : 0.0f; }
-__device__ __forceinline__ float absmax_to_scale(float a) { return a / 7.0f; }
+// qmax = 7 for 4-bit codes, 127 for 8-bit codes (int8 warm-up phase, integer g_w path).
+__device__ __forceinline__ float absmax_to_inv(float a, float qmax) { return a > 0.0f ? qmax / a : 0.0f; }
+__device__ __forceinline__ float absmax_to_scale(float a, float qmax) { return a / qmax; }
 
 }  // namespace hlq

@@ -9,17 +9,24 @@ namespace hlq {
 
 // K1: rows of G -> 4-bit codes + per-row scales (and optionally the fp32 coefficients).
 hipError_t launch_quant_rows(const void *G, int64_t N, int O, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                             int8_t *Gq, float *sG, float *coeff, hipStream_t st);
+                             float qmax, int8_t *Gq, float *sG, float *coeff, hipStream_t st);
 
 // K1T: W [O, I] -> WqT [I, O] codes + per-in-feature scales.  `ws` holds the partial column
 // maxima and the reciprocal scales: quant_cols_ws_bytes(O, I) bytes.
 size_t quant_cols_ws_bytes(int64_t O, int64_t I);
 hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                             int8_t *WqT, float *sW, float *coeffT, void *ws, hipStream_t st);
+                             float qmax, int8_t *WqT, float *sW, float *coeffT, void *ws, hipStream_t st);
 
 // K3: token-axis Hadamard low-rank projection, T [N, D] -> ThatT [D, N/B*r] bf16.
 hipError_t launch_hla(const void *T, int64_t N, int D, int B, int r, bool is_f32, uint16_t *ThatT,
                       float *coeffT, hipStream_t st);
+
+// K3q: token-axis projection followed by int8 quantisation with one scale per feature (stages
+// 1-2 / 3-4 of the g_w list): T [N, D] -> TqT [D, N/B*r] int8 + sT [D].  `ws` holds D words of
+// column maxima: hla_quant_ws_bytes(D) bytes.  Needs r % 4 == 0.
+size_t hla_quant_ws_bytes(int64_t D);
+hipError_t launch_hla_quant(const void *T, int64_t N, int D, int B, int r, bool is_f32, uint32_t k0, uint32_t k1,
+                            int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st);
 
 // K2 / K4: C = alpha * sA (x) sB * (A . Bm^T).  kind 0: int8 operands, int32 accumulate;
 // kind 1: bf16 operands, fp32 accumulate.  K in elements.

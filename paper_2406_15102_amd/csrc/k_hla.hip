@@ -92,4 +92,128 @@ hipError_t launch_hla(const void *T, int64_t N, int D, int B, int r, bool is_f32
     return hipErrorInvalidValue;
 }
 
+// ---- integer g_w path: projection + int8 quantisation (stages 1-2 and 3-4 of the g_w list) ----
+// One scale per feature (= per row of the reduction-contiguous output TqT [D, N/B*r]), so the
+// absmax spans the whole token axis: two passes over T, as for the weight operand of the g_x path.
+//   zero    amax[D] = 0
+//   pass 1  transform, max |coefficient| over the kept r per column, LDS across the workgroup's
+//           four token blocks, one atomic max (on the bit pattern of a non-negative float) per column
+//   pass 2  transform again, quantise the kept coefficients with qmax = 127, write r codes per
+//           column and token block
+__global__ __launch_bounds__(256) void k_hla_fill_u32(uint32_t *p, int n, uint32_t value)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = value;
+}
+
+template <typename Tin, int B>
+__global__ __launch_bounds__(256) void k_hla_absmax(const Tin *__restrict__ T, int64_t N, int D, int r,
+                                                    uint32_t *__restrict__ amax_bits)
+{
+    constexpr int CPL = 128 / B;
+    __shared__ float s_max[4][64 * CPL];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int col0 = (blockIdx.x * 64 + lane) * CPL;
+    const int64_t nblk = N / B;
+    const int64_t blk = static_cast<int64_t>(blockIdx.y) * 4 + wave;
+    float cmax[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) cmax[c] = 0.0f;
+    if (col0 < D && blk < nblk) {
+        float v[B * CPL];
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+            Loader<Tin, CPL>::load(T + (blk * B + j) * static_cast<int64_t>(D) + col0, v + j * CPL);
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+            fwht_regs<B, CPL>(v + c);
+#pragma unroll
+            for (int k = 0; k < B; ++k)
+                if (k < r) cmax[c] = fmaxf(cmax[c], fabsf(v[k * CPL + c]));
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) s_max[wave][lane * CPL + c] = cmax[c];
+    __syncthreads();
+    for (int idx = tid; idx < 64 * CPL; idx += 256) {
+        const float m = fmaxf(fmaxf(s_max[0][idx], s_max[1][idx]), fmaxf(s_max[2][idx], s_max[3][idx]));
+        const int col = blockIdx.x * 64 * CPL + idx;
+        if (col < D && m > 0.0f) atomicMax(amax_bits + col, __float_as_uint(m));
+    }
+}
+
+template <typename Tin, int B>
+__global__ __launch_bounds__(256) void k_hla_quantize(const Tin *__restrict__ T, int64_t N, int D, int r,
+                                                      const uint32_t *__restrict__ amax_bits, uint32_t k0,
+                                                      uint32_t k1, int8_t *__restrict__ TqT, float *__restrict__ sT,
+                                                      float *__restrict__ coeffT)
+{
+    constexpr int CPL = 128 / B;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int col0 = (blockIdx.x * 64 + lane) * CPL;
+    const int64_t nblk = N / B;
+    const int64_t Kc = nblk * r;
+    const int64_t blk = static_cast<int64_t>(blockIdx.y) * 4 + wave;
+    if (col0 >= D || blk >= nblk) return;
+
+    float v[B * CPL];
+#pragma unroll
+    for (int j = 0; j < B; ++j)
+        Loader<Tin, CPL>::load(T + (blk * B + j) * static_cast<int64_t>(D) + col0, v + j * CPL);
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        fwht_regs<B, CPL>(v + c);
+        const float a = __uint_as_float(amax_bits[col0 + c]);
+        const float inv = absmax_to_inv(a, 127.0f);
+        if (blk == 0) sT[col0 + c] = absmax_to_scale(a, 127.0f);
+        const int64_t o = static_cast<int64_t>(col0 + c) * Kc + blk * r;          // r % 4 == 0
+        const uint32_t cnt = static_cast<uint32_t>(col0 + c) * static_cast<uint32_t>(Kc >> 2) +
+                             static_cast<uint32_t>((blk * r) >> 2);
+#pragma unroll
+        for (int k = 0; k < B; k += 4) {
+            if (k < r) {
+                const uint32_t w = rand_word(cnt + (k >> 2), k0, k1);
+                *reinterpret_cast<uint32_t *>(TqT + o + k) =
+                    quant_pack4(v[(k + 0) * CPL + c], v[(k + 1) * CPL + c], v[(k + 2) * CPL + c], v[(k + 3) * CPL + c], inv, w);
+                if (coeffT)
+                    *reinterpret_cast<float4 *>(coeffT + o + k) =
+                        make_float4(v[(k + 0) * CPL + c], v[(k + 1) * CPL + c], v[(k + 2) * CPL + c], v[(k + 3) * CPL + c]);
+            }
+        }
+    }
+}
+
+size_t hla_quant_ws_bytes(int64_t D) { return (static_cast<size_t>(D) * 4 + 255) & ~static_cast<size_t>(255); }
+
+template <typename Tin, int B>
+static hipError_t launch_hla_quant_t(const void *T, int64_t N, int D, int r, uint32_t k0, uint32_t k1, int8_t *TqT,
+                                     float *sT, float *coeffT, void *ws, hipStream_t st)
+{
+    constexpr int CPL = 128 / B;
+    const int64_t nblk = N / B;
+    uint32_t *amax = static_cast<uint32_t *>(ws);
+    const Tin *t = static_cast<const Tin *>(T);
+    dim3 grid((D + 64 * CPL - 1) / (64 * CPL), static_cast<unsigned>((nblk + 3) / 4));
+    hipLaunchKernelGGL(k_hla_fill_u32, dim3((D + 255) / 256), dim3(256), 0, st, amax, D, 0u);
+    hipLaunchKernelGGL((k_hla_absmax<Tin, B>), grid, dim3(256), 0, st, t, N, D, r, amax);
+    hipLaunchKernelGGL((k_hla_quantize<Tin, B>), grid, dim3(256), 0, st, t, N, D, r, amax, k0, k1, TqT, sT, coeffT);
+    return hipGetLastError();
+}
+
+hipError_t launch_hla_quant(const void *T, int64_t N, int D, int B, int r, bool is_f32, uint32_t k0, uint32_t k1,
+                            int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st)
+{
+#define HLQ_HLAQ_CASE(BB)                                                                              \
+    case BB:                                                                                           \
+        return is_f32 ? launch_hla_quant_t<float, BB>(T, N, D, r, k0, k1, TqT, sT, coeffT, ws, st)     \
+                      : launch_hla_quant_t<bf16_t, BB>(T, N, D, r, k0, k1, TqT, sT, coeffT, ws, st);
+    switch (B) {
+        HLQ_HLAQ_CASE(16)
+        HLQ_HLAQ_CASE(32)
+        HLQ_HLAQ_CASE(64)
+    }
+#undef HLQ_HLAQ_CASE
+    return hipErrorInvalidValue;
+}
+
 }  // namespace hlq

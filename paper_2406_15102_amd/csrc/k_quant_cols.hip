@@ -69,7 +69,7 @@ __global__ __launch_bounds__(256) void k_cols_absmax(const Tin *__restrict__ W, 
 template <typename Tin, int B>
 __global__ __launch_bounds__(256) void k_cols_quantize(const Tin *__restrict__ W, int O, int I,
                                                        const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
-                                                       int8_t *__restrict__ WqT, float *__restrict__ sW,
+                                                       float qmax, int8_t *__restrict__ WqT, float *__restrict__ sW,
                                                        float *__restrict__ coeffT)
 {
     constexpr int CPL = 128 / B;
@@ -84,8 +84,8 @@ __global__ __launch_bounds__(256) void k_cols_quantize(const Tin *__restrict__ W
 #pragma unroll
     for (int c = 0; c < CPL; ++c) {
         const float a = __uint_as_float(amax_bits[col0 + c]);
-        inv[c] = absmax_to_inv(a);
-        if (o0 == 0) sW[col0 + c] = absmax_to_scale(a);
+        inv[c] = absmax_to_inv(a, qmax);
+        if (o0 == 0) sW[col0 + c] = absmax_to_scale(a, qmax);
     }
 #pragma unroll
     for (int c = 0; c < CPL; ++c) {
@@ -121,7 +121,7 @@ size_t quant_cols_ws_bytes(int64_t /*O*/, int64_t I)
 }
 
 template <typename Tin, int B>
-static hipError_t launch_cols_t(const void *W, int O, int I, uint32_t k0, uint32_t k1, int8_t *WqT, float *sW,
+static hipError_t launch_cols_t(const void *W, int O, int I, uint32_t k0, uint32_t k1, float qmax, int8_t *WqT, float *sW,
                                 float *coeffT, void *ws, hipStream_t st)
 {
     constexpr int CPL = 128 / B;
@@ -130,17 +130,17 @@ static hipError_t launch_cols_t(const void *W, int O, int I, uint32_t k0, uint32
     dim3 grid((I + 64 * CPL - 1) / (64 * CPL), (O + 4 * B - 1) / (4 * B));
     hipLaunchKernelGGL(k_fill_u32, dim3((I + 255) / 256), dim3(256), 0, st, amax, I, 0u);
     hipLaunchKernelGGL((k_cols_absmax<Tin, B>), grid, dim3(256), 0, st, w, O, I, amax);
-    hipLaunchKernelGGL((k_cols_quantize<Tin, B>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, WqT, sW, coeffT);
+    hipLaunchKernelGGL((k_cols_quantize<Tin, B>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, coeffT);
     return hipGetLastError();
 }
 
 hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                             int8_t *WqT, float *sW, float *coeffT, void *ws, hipStream_t st)
+                             float qmax, int8_t *WqT, float *sW, float *coeffT, void *ws, hipStream_t st)
 {
 #define HLQ_COLS_CASE(BB)                                                                            \
     case BB:                                                                                         \
-        return is_f32 ? launch_cols_t<float, BB>(W, O, I, k0, k1, WqT, sW, coeffT, ws, st)           \
-                      : launch_cols_t<bf16_t, BB>(W, O, I, k0, k1, WqT, sW, coeffT, ws, st);
+        return is_f32 ? launch_cols_t<float, BB>(W, O, I, k0, k1, qmax, WqT, sW, coeffT, ws, st)           \
+                      : launch_cols_t<bf16_t, BB>(W, O, I, k0, k1, qmax, WqT, sW, coeffT, ws, st);
     switch (B) {
         HLQ_COLS_CASE(16)
         HLQ_COLS_CASE(32)

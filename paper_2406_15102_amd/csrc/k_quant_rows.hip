@@ -17,7 +17,7 @@ constexpr int K1_MAXC = 8;  // chunks of 8 elements per lane
 
 template <typename Tin, int B, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tin *__restrict__ G, int64_t N, int O, int T,
-                                                      uint32_t k0, uint32_t k1, int8_t *__restrict__ Gq,
+                                                      uint32_t k0, uint32_t k1, float qmax, int8_t *__restrict__ Gq,
                                                       float *__restrict__ sG, float *__restrict__ coeff)
 {
     __shared__ float s_red[BLOCK / 64];
@@ -76,8 +76,8 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tin *__restrict__ G,
     }
 
     if (!row_ok) return;
-    const float inv = absmax_to_inv(amax) * sign;   // exact: undoes the sign the lane exchange left
-    if (g == 0) sG[row] = absmax_to_scale(amax);
+    const float inv = absmax_to_inv(amax, qmax) * sign;   // exact: undoes the sign the lane exchange left
+    if (g == 0) sG[row] = absmax_to_scale(amax, qmax);
 
     const uint32_t cbase = static_cast<uint32_t>(row) * static_cast<uint32_t>(O >> 2);
     int8_t *qrow = Gq + row * static_cast<int64_t>(O);
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tin *__restrict__ G,
 }
 
 template <typename Tin, int B>
-static hipError_t launch_rows_t(const void *G, int64_t N, int O, uint32_t k0, uint32_t k1, int8_t *Gq,
+static hipError_t launch_rows_t(const void *G, int64_t N, int O, uint32_t k0, uint32_t k1, float qmax, int8_t *Gq,
                                 float *sG, float *coeff, hipStream_t st)
 {
     const int nch = O / 8;
@@ -113,22 +113,22 @@ static hipError_t launch_rows_t(const void *G, int64_t N, int O, uint32_t k0, ui
         while (T < 64 && nch / T > 4) T *= 2;
         const int rows_per_block = 256 / T;
         const unsigned grid = static_cast<unsigned>((N + rows_per_block - 1) / rows_per_block);
-        hipLaunchKernelGGL((k_quant_rows<Tin, B, 256>), dim3(grid), dim3(256), 0, st, g, N, O, T, k0, k1, Gq, sG, coeff);
+        hipLaunchKernelGGL((k_quant_rows<Tin, B, 256>), dim3(grid), dim3(256), 0, st, g, N, O, T, k0, k1, qmax, Gq, sG, coeff);
     } else if (nch <= K1_MAXC * 256) {
-        hipLaunchKernelGGL((k_quant_rows<Tin, B, 256>), dim3(static_cast<unsigned>(N)), dim3(256), 0, st, g, N, O, 256, k0, k1, Gq, sG, coeff);
+        hipLaunchKernelGGL((k_quant_rows<Tin, B, 256>), dim3(static_cast<unsigned>(N)), dim3(256), 0, st, g, N, O, 256, k0, k1, qmax, Gq, sG, coeff);
     } else {
-        hipLaunchKernelGGL((k_quant_rows<Tin, B, 1024>), dim3(static_cast<unsigned>(N)), dim3(1024), 0, st, g, N, O, 1024, k0, k1, Gq, sG, coeff);
+        hipLaunchKernelGGL((k_quant_rows<Tin, B, 1024>), dim3(static_cast<unsigned>(N)), dim3(1024), 0, st, g, N, O, 1024, k0, k1, qmax, Gq, sG, coeff);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_quant_rows(const void *G, int64_t N, int O, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                             int8_t *Gq, float *sG, float *coeff, hipStream_t st)
+                             float qmax, int8_t *Gq, float *sG, float *coeff, hipStream_t st)
 {
 #define HLQ_ROWS_CASE(BB)                                                                           \
     case BB:                                                                                        \
-        return is_f32 ? launch_rows_t<float, BB>(G, N, O, k0, k1, Gq, sG, coeff, st)                \
-                      : launch_rows_t<bf16_t, BB>(G, N, O, k0, k1, Gq, sG, coeff, st);
+        return is_f32 ? launch_rows_t<float, BB>(G, N, O, k0, k1, qmax, Gq, sG, coeff, st)                \
+                      : launch_rows_t<bf16_t, BB>(G, N, O, k0, k1, qmax, Gq, sG, coeff, st);
     switch (B) {
         HLQ_ROWS_CASE(16)
         HLQ_ROWS_CASE(32)

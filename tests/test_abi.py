@@ -82,13 +82,14 @@ def test_ex_rejects_bad_arguments_without_a_gpu():
 
 def test_stage_entry_points_reject_bad_arguments_without_a_gpu():
     l = hlq.lib()
-    assert l.hlq_quantize_g(None, 16, 256, 16, 0, 0, FAKE, FAKE, None, None) == 1
-    assert l.hlq_quantize_g(FAKE, 16, 250, 16, 0, 0, FAKE, FAKE, None, None) == 2
-    assert l.hlq_quantize_g(FAKE, 16, 256, 20, 0, 0, FAKE, FAKE, None, None) == 3
-    assert l.hlq_quantize_g(FAKE, 16, 256, 16, 0, 9, FAKE, FAKE, None, None) == 5
-    assert l.hlq_quantize_w(FAKE, 256, 256, 16, 0, 0, FAKE, FAKE, None, None, 0, None) == 1
-    assert l.hlq_quantize_w(FAKE, 256, 256, 16, 0, 0, FAKE, FAKE, None, FAKE, 16, None) == 6
-    assert l.hlq_quantize_w(FAKE, 256, 100, 16, 0, 0, FAKE, FAKE, None, FAKE, 1 << 20, None) == 2
+    assert l.hlq_quantize_g(None, 16, 256, 16, 0, 0, 4, FAKE, FAKE, None, None) == 1
+    assert l.hlq_quantize_g(FAKE, 16, 250, 16, 0, 0, 4, FAKE, FAKE, None, None) == 2
+    assert l.hlq_quantize_g(FAKE, 16, 256, 20, 0, 0, 4, FAKE, FAKE, None, None) == 3
+    assert l.hlq_quantize_g(FAKE, 16, 256, 16, 0, 9, 4, FAKE, FAKE, None, None) == 5
+    assert l.hlq_quantize_g(FAKE, 16, 256, 16, 0, 0, 5, FAKE, FAKE, None, None) == 5      # bits must be 4 or 8
+    assert l.hlq_quantize_w(FAKE, 256, 256, 16, 0, 0, 4, FAKE, FAKE, None, None, 0, None) == 1
+    assert l.hlq_quantize_w(FAKE, 256, 256, 16, 0, 0, 4, FAKE, FAKE, None, FAKE, 16, None) == 6
+    assert l.hlq_quantize_w(FAKE, 256, 100, 16, 0, 0, 4, FAKE, FAKE, None, FAKE, 1 << 20, None) == 2
     assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 64, 40, None, None, 1.0, 1, FAKE, None, None) == 2   # K % 16
     assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 62, 64, None, None, 1.0, 1, FAKE, None, None) == 2   # Nn % 4
     assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 64, 64, None, None, 1.0, 1, None, None, None) == 1
@@ -96,6 +97,29 @@ def test_stage_entry_points_reject_bad_arguments_without_a_gpu():
     assert l.hlq_hla_project(FAKE, 256, 64, 16, 5, 0, FAKE, None, None) == 4
     assert l.hlq_compress_act(FAKE, 256, 64, 16, 8, 0, None, None) == 1
     assert l.hlq_bf16_gemm_nt(FAKE, FAKE, 64, 64, 36, 1.0, 0, FAKE, None) == 2                     # K % 8
+    W256 = C.c_void_p(0x10000)
+    assert l.hlq_hla_quantize(FAKE, 256, 64, 16, 2, 0, 2, 0, FAKE, FAKE, None, W256, 1 << 20, None) == 4   # r % 4
+    assert l.hlq_hla_quantize(FAKE, 256, 64, 16, 8, 0, 1, 0, FAKE, FAKE, None, W256, 1 << 20, None) == 2   # stream id
+    assert l.hlq_hla_quantize(FAKE, 16, 64, 16, 8, 0, 2, 0, FAKE, FAKE, None, W256, 1 << 20, None) == 2    # Kc % 16
+    assert l.hlq_hla_quantize(FAKE, 256, 64, 16, 8, 0, 2, 0, FAKE, FAKE, None, W256, 16, None) == 6
+    assert l.hlq_compress_act_int8(FAKE, 256, 64, 16, 8, 0, 0, None, FAKE, W256, 1 << 20, None) == 1
+
+
+def test_mode_entry_point_rejects_bad_arguments_without_a_gpu():
+    f = hlq.lib().hlq_linear_backward_mode
+
+    def call(X=FAKE, Xc=None, sXc=None, flags=0, N=256, r=8, wsb=1 << 30):
+        return f(FAKE, X, Xc, sXc, FAKE, N, 256, 256, 16, r, 0, 0, flags, FAKE, FAKE, FAKE, wsb, None)
+
+    assert call(flags=8) == 2                                   # unknown flag
+    assert call(flags=2, r=2) == 4                              # integer g_w path needs r % 4 == 0
+    assert call(flags=2, N=16, r=8) == 2                        # compressed token axis % 16
+    assert call(X=None, Xc=FAKE, sXc=None, flags=2) == 1        # int8 codes need their scales
+    assert call(X=None, Xc=FAKE, sXc=FAKE, flags=0) == 1        # bf16 XhatT takes no scales
+    assert call(flags=2, wsb=1000) == 6
+    assert hlq.hlq_workspace_bytes_mode(4096, 4096, 11008, 16, 8, False, 2) < hlq.hlq_workspace_bytes(4096, 4096, 11008, 16, 8)
+    assert hlq.hlq_workspace_bytes_mode(4096, 4096, 11008, 16, 8, False, 0) == hlq.hlq_workspace_bytes(4096, 4096, 11008, 16, 8)
+    assert hlq.hlq_workspace_bytes_mode(4096, 4096, 11008, 16, 2, False, 2) == 0
 
 
 def test_binding_refuses_cpu_tensors():
