@@ -152,6 +152,19 @@ def main():
         kernels[name] = {"us": round(us, 2), "bound": kind, "achieved": round(ach, 1), "peak": peak, "unit": unit,
                          "frac": round(ach / peak, 4)}
 
+    # ---- the method's options, whole path (extra figures; `value` stays the default path) ----
+    modes = {}
+    for label, flags in (("gw_int8", hlq.HLQ_FLAG_GW_INT8), ("gx_8bit", hlq.HLQ_FLAG_GX_8BIT),
+                         ("gx_8bit+gw_int8", hlq.HLQ_FLAG_GX_8BIT | hlq.HLQ_FLAG_GW_INT8)):
+        need = hlq.hlq_workspace_bytes_mode(N, I, O, B, r, False, flags)
+        if need == 0 or need > ws.numel():
+            continue
+        fn = lambda: hlq.hlq_linear_backward_mode(G, X, None, None, W, N, I, O, B, r, w.seed, flags, dX, dW, ws)
+        for _ in range(3):
+            fn()
+        modes[label] = {"us": round(_event_time_us(fn, max(10, args.steps // 2), torch), 2)}
+    step()   # leave dX / dW as the default path computes them
+
     # ---- dense bf16 backward on the same GPU (comparator, not part of the library) ----
     def dense():
         torch.matmul(G, W, out=dXd)
@@ -199,6 +212,7 @@ def main():
         "dense_bf16_backward_us": round(dense_us, 2),
         "speedup_vs_dense_bf16": round(dense_us / hlq_us, 3),
         "kernels": kernels,
+        "modes_us": modes,
         "copy_256MiB": {"us": round(copy_us, 2), "GB/s": round(2 * (1 << 28) / copy_us / 1e3, 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,
