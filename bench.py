@@ -120,13 +120,15 @@ def main():
     wws = torch.empty(hlq.hlq_quantize_w_workspace_bytes(O, I), dtype=torch.uint8, device=dev)
     GhT = torch.empty((O, Kc), dtype=torch.bfloat16, device=dev)
     XhT = torch.empty((I, Kc), dtype=torch.bfloat16, device=dev)
+    gws = torch.empty(max(16, hlq.hlq_gemm_workspace_bytes(0, N, I, O), hlq.hlq_gemm_workspace_bytes(1, O, I, Kc)),
+                      dtype=torch.uint8, device=dev)   # split-K scratch, as the whole path has it
     stages = {
         "quantize_g": lambda: hlq.hlq_quantize_g(G, B, w.seed, Gq, sG),
         "quantize_w": lambda: hlq.hlq_quantize_w(W, B, w.seed, WqT, sW, wws),
-        "int8_gemm": lambda: hlq.hlq_int8_gemm_nt(Gq, WqT, sG, sW, 1.0 / B, dX),
+        "int8_gemm": lambda: hlq.hlq_int8_gemm_nt(Gq, WqT, sG, sW, 1.0 / B, dX, None, gws),
         "hla_g": lambda: hlq.hlq_hla_project(G, B, r, GhT),
         "hla_x": lambda: hlq.hlq_hla_project(X, B, r, XhT),
-        "bf16_gemm": lambda: hlq.hlq_bf16_gemm_nt(GhT, XhT, 1.0 / B, dW),
+        "bf16_gemm": lambda: hlq.hlq_bf16_gemm_nt(GhT, XhT, 1.0 / B, dW, gws),
     }
     e = 2 if w.dtype == "bf16" else 4
     work = {  # algorithmic bytes / ops per launch

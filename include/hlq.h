@@ -137,10 +137,16 @@ int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t s
  * exact in int32 (int8 MFMA).  A [M, K] int8, Bm [Nn, K] int8, K % 16 == 0, Nn % 4 == 0.
  *   out_dtype HLQ_BF16 / HLQ_F32 selects the type of C [M, Nn]; C may be NULL.
  *   acc: NULL or [M, Nn] int32 receiving the raw accumulators.  sA, sB may be NULL (= all ones).
+ *   workspace: NULL, or device scratch (16-byte aligned) of hlq_gemm_workspace_bytes(0, M, Nn, K)
+ *   bytes or more.  With it, shapes with few output tiles and a long reduction are computed as
+ *   several partial products over ranges of k, summed in a fixed order (integers: exactly) by a
+ *   second kernel; without it, or when it is too small, k is never split.  Same result either way
+ *   for the int8 product; for the bf16 product the fp32 summation order differs.
  */
+size_t hlq_gemm_workspace_bytes(int kind /* 0 int8, 1 bf16 */, int64_t M, int64_t Nn, int64_t K);
 int hlq_int8_gemm_nt(const int8_t *A, const int8_t *Bm, int64_t M, int64_t Nn, int64_t K,
                      const float *sA, const float *sB, float alpha, int out_dtype, void *C,
-                     int32_t *acc, void *stream);
+                     int32_t *acc, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Stages 1 and 3 of the g_w list for any [N, D] tensor T (G or X): the projection described at
@@ -153,10 +159,10 @@ int hlq_hla_project(const void *T, int64_t N, int64_t D, int B, int r, int dtype
 /*
  * Stage 5 of the g_w list: C[m, n] = alpha * sum_k A[m,k] * Bm[n,k], bf16 inputs, fp32
  * accumulation (bf16 MFMA).  A [M, K], Bm [Nn, K] bf16, K % 8 == 0, Nn % 4 == 0; C [M, Nn] of
- * out_dtype.
+ * out_dtype.  workspace: as for hlq_int8_gemm_nt (kind 1).
  */
 int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64_t K, float alpha,
-                     int out_dtype, void *C, void *stream);
+                     int out_dtype, void *C, void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- the method's two options: 8-bit g_x codes, and the g_w list in integers ------------------- */
 

@@ -43,11 +43,12 @@ _EXPORTS = {
     "hlq_linear_backward_mode": (C.c_int, [C.c_void_p] * 5 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64, C.c_int,
                                            C.c_int] + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]),
     "hlq_int8_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
-                                   C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]),
+                                   C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "hlq_gemm_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int64, C.c_int64, C.c_int64]),
     "hlq_hla_project": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                   C.c_void_p, C.c_void_p]),
     "hlq_bf16_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_float, C.c_int,
-                                   C.c_void_p, C.c_void_p]),
+                                   C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hlq_mfma_probe": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
 }
 
@@ -165,13 +166,22 @@ def hlq_quantize_w(W, B, seed, WqT, sW, workspace, coeffT=None, bits=4):
                                 workspace.numel() * workspace.element_size(), _stream()), "hlq_quantize_w")
 
 
-def hlq_int8_gemm_nt(A, Bm, sA, sB, alpha, C_out=None, acc=None):
+def _ws(workspace):
+    return (None, 0) if workspace is None else (_ptr(workspace), workspace.numel() * workspace.element_size())
+
+
+def hlq_gemm_workspace_bytes(kind, M, Nn, K) -> int:
+    return int(lib().hlq_gemm_workspace_bytes(kind, M, Nn, K))
+
+
+def hlq_int8_gemm_nt(A, Bm, sA, sB, alpha, C_out=None, acc=None, workspace=None):
     M, K = A.shape
     Nn = Bm.shape[0]
     out_dt = _dt(C_out) if C_out is not None else HLQ_F32
+    wp, wb = _ws(workspace)
     _check(lib().hlq_int8_gemm_nt(_ptr(A, torch.int8), _ptr(Bm, torch.int8), M, Nn, K, _ptr(sA, torch.float32),
                                   _ptr(sB, torch.float32), float(alpha), out_dt, _ptr(C_out), _ptr(acc, torch.int32),
-                                  _stream()), "hlq_int8_gemm_nt")
+                                  wp, wb, _stream()), "hlq_int8_gemm_nt")
 
 
 def hlq_hla_project(T, B, r, ThatT, coeffT=None):
@@ -180,11 +190,12 @@ def hlq_hla_project(T, B, r, ThatT, coeffT=None):
                                  _ptr(coeffT, torch.float32), _stream()), "hlq_hla_project")
 
 
-def hlq_bf16_gemm_nt(A, Bm, alpha, C_out):
+def hlq_bf16_gemm_nt(A, Bm, alpha, C_out, workspace=None):
     M, K = A.shape
     Nn = Bm.shape[0]
+    wp, wb = _ws(workspace)
     _check(lib().hlq_bf16_gemm_nt(_ptr(A, torch.bfloat16), _ptr(Bm, torch.bfloat16), M, Nn, K, float(alpha),
-                                  _dt(C_out), _ptr(C_out), _stream()), "hlq_bf16_gemm_nt")
+                                  _dt(C_out), _ptr(C_out), wp, wb, _stream()), "hlq_bf16_gemm_nt")
 
 
 def hlq_mfma_probe(kind, blocks, iters, sink):

@@ -72,7 +72,7 @@ int check_backward_shape(int64_t N, int64_t d_in, int64_t d_out, int B, int r)
 // Carving of the backward workspace.  With HLQ_FLAG_GW_INT8 the compressed operands are int8
 // codes with one scale per feature plus one word of column maximum per feature.
 struct Layout {
-    size_t Gq, sG, Wq, sW, wws, GhatT, sGhat, XhatT, sXhat, hws, total;
+    size_t Gq, sG, Wq, sW, wws, GhatT, sGhat, XhatT, sXhat, hws, gws, gws_bytes, total;
 };
 
 Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_is_compressed, int flags)
@@ -92,6 +92,11 @@ Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_
     L.XhatT = off; off += x_is_compressed ? 0 : up256(static_cast<size_t>(d_in) * Kc * esz);
     L.sXhat = off; off += (gwi && !x_is_compressed) ? up256(static_cast<size_t>(d_in) * 4) : 0;
     L.hws = off;   off += gwi ? up256(hlq::hla_quant_ws_bytes(d_out > d_in ? d_out : d_in)) : 0;
+    // split-K partial sums of whichever product wants them (the two products run one after the other)
+    const size_t g1 = hlq::gemm_ws_bytes(0, static_cast<int>(N), static_cast<int>(d_in), static_cast<int>(d_out));
+    const size_t g2 = hlq::gemm_ws_bytes(gwi ? 0 : 1, static_cast<int>(d_out), static_cast<int>(d_in), static_cast<int>(Kc));
+    L.gws_bytes = g1 > g2 ? g1 : g2;
+    L.gws = off;   off += up256(L.gws_bytes);
     L.total = off;
     return L;
 }
@@ -216,8 +221,15 @@ int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t s
                                             static_cast<hipStream_t>(stream)));
 }
 
+size_t hlq_gemm_workspace_bytes(int kind, int64_t M, int64_t Nn, int64_t K)
+{
+    if ((kind != 0 && kind != 1) || check_gemm_shape(M, Nn, K, kind == 0 ? 16 : 8) != HLQ_OK) return 0;
+    return hlq::gemm_ws_bytes(kind, static_cast<int>(M), static_cast<int>(Nn), static_cast<int>(K));
+}
+
 int hlq_int8_gemm_nt(const int8_t *A, const int8_t *Bm, int64_t M, int64_t Nn, int64_t K, const float *sA,
-                     const float *sB, float alpha, int out_dtype, void *C, int32_t *acc, void *stream)
+                     const float *sB, float alpha, int out_dtype, void *C, int32_t *acc, void *workspace,
+                     size_t workspace_bytes, void *stream)
 {
     int rc;
     if (!A || !Bm || (!C && !acc)) return HLQ_ERR_NULL;
@@ -226,8 +238,9 @@ int hlq_int8_gemm_nt(const int8_t *A, const int8_t *Bm, int64_t M, int64_t Nn, i
     if (!aligned(A, 16) || !aligned(Bm, 16) || (C && !aligned(C, 16)) || (acc && !aligned(acc, 16)) ||
         (sB && !aligned(sB, 16)))
         return HLQ_ERR_SHAPE;
+    if (workspace && !aligned(workspace, 16)) return HLQ_ERR_WORKSPACE;
     hlq::GemmArgs a{A, Bm, static_cast<int>(M), static_cast<int>(Nn), static_cast<int>(K), sA, sB, alpha, C,
-                    out_dtype == HLQ_F32, acc};
+                    out_dtype == HLQ_F32, acc, workspace, workspace_bytes};
     return launch_rc(hlq::launch_gemm_nt(0, a, static_cast<hipStream_t>(stream)));
 }
 
@@ -251,15 +264,16 @@ int hlq_compress_act(const void *X, int64_t N, int64_t d_in, int B, int r, int d
 }
 
 int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64_t K, float alpha, int out_dtype,
-                     void *C, void *stream)
+                     void *C, void *workspace, size_t workspace_bytes, void *stream)
 {
     int rc;
     if (!A || !Bm || !C) return HLQ_ERR_NULL;
     if ((rc = check_dtype(out_dtype)) != HLQ_OK) return rc;
     if ((rc = check_gemm_shape(M, Nn, K, 8)) != HLQ_OK) return rc;
     if (!aligned(A, 16) || !aligned(Bm, 16) || !aligned(C, 16)) return HLQ_ERR_SHAPE;
+    if (workspace && !aligned(workspace, 16)) return HLQ_ERR_WORKSPACE;
     hlq::GemmArgs a{A, Bm, static_cast<int>(M), static_cast<int>(Nn), static_cast<int>(K), nullptr, nullptr, alpha, C,
-                    out_dtype == HLQ_F32, nullptr};
+                    out_dtype == HLQ_F32, nullptr, workspace, workspace_bytes};
     return launch_rc(hlq::launch_gemm_nt(1, a, static_cast<hipStream_t>(stream)));
 }
 
@@ -387,16 +401,16 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
                                                    st))) != HLQ_OK)
             return rc;
         // g_x stages 5-6: integer product and dequantisation (1/B undoes H H^T = B I)
-        hlq::GemmArgs a{Gq, Wq, static_cast<int>(N), I, O, sG, sW, invB, dX, f32, nullptr};
+        hlq::GemmArgs a{Gq, Wq, static_cast<int>(N), I, O, sG, sW, invB, dX, f32, nullptr, ws + L.gws, L.gws_bytes};
         if ((rc = launch_rc(hlq::launch_gemm_nt(0, a, st))) != HLQ_OK) return rc;
     }
     if (dW) {
         // g_w stage 5 (and 6): product over the compressed token axis
         if (gwi) {
-            hlq::GemmArgs a{Gh, Xh, O, I, Kc, sGh, sXh, invB, dW, f32, nullptr};
+            hlq::GemmArgs a{Gh, Xh, O, I, Kc, sGh, sXh, invB, dW, f32, nullptr, ws + L.gws, L.gws_bytes};
             if ((rc = launch_rc(hlq::launch_gemm_nt(0, a, st))) != HLQ_OK) return rc;
         } else {
-            hlq::GemmArgs a{Gh, Xh, O, I, Kc, nullptr, nullptr, invB, dW, f32, nullptr};
+            hlq::GemmArgs a{Gh, Xh, O, I, Kc, nullptr, nullptr, invB, dW, f32, nullptr, ws + L.gws, L.gws_bytes};
             if ((rc = launch_rc(hlq::launch_gemm_nt(1, a, st))) != HLQ_OK) return rc;
         }
     }

@@ -40,8 +40,13 @@ struct GemmArgs {
     void *C;          // bf16 or fp32 [M, N], may be null
     bool c_is_f32;
     int32_t *acc;     // raw int32 accumulators (int8 kind only), may be null
+    void *ws;         // device scratch for split-K partial sums, may be null (then k is never split)
+    size_t ws_bytes;
 };
 hipError_t launch_gemm_nt(int kind, const GemmArgs &a, hipStream_t st);
+// Scratch that lets launch_gemm_nt split k whenever that is the faster plan for this shape
+// (few output tiles, long reduction); 0 if the plan does not split.
+size_t gemm_ws_bytes(int kind, int M, int N, int K);
 
 // Diagnostic: `blocks` workgroups of 4 wavefronts each run `iters` x 8 independent 32x32 MFMAs
 // (kind 0: i8, K = 32; kind 1: bf16, K = 16) from registers.

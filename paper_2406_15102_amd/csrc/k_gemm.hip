@@ -68,6 +68,8 @@ struct GemmDev {
     int c_is_f32;
     int32_t *acc;
     int tiles_m, tiles_n;
+    int splits;        // split-K: this many workgroups share a tile, each a contiguous range of k steps
+    int32_t *partial;  // [splits][M][N] raw 32-bit accumulators (OUT == 3)
 };
 
 // position of 16-byte chunk c of LDS row `row` (KCH chunks per row)
@@ -106,7 +108,11 @@ template <int WN> struct EpiSlab {
     static constexpr int BYTES = 32 * PITCH_F32;      // one 32-row slab per wavefront
 };
 
-// raw int32 accumulators (parity export): direct 16-byte stores
+__device__ __forceinline__ int raw_bits(int v) { return v; }
+__device__ __forceinline__ int raw_bits(float v) { return __builtin_bit_cast(int, v); }
+
+// raw 32-bit accumulators (int32, or fp32 bit patterns): the parity export and the split-K
+// partial results; direct 16-byte stores
 template <int KIND, int WM, int WN, bool GUARD>
 __device__ __forceinline__ void store_raw(typename Mma<KIND>::acc_t (&acc)[WM][WN], int32_t *out, int M, int N,
                                           int wm0, int wn0, int lane)
@@ -123,8 +129,8 @@ __device__ __forceinline__ void store_raw(typename Mma<KIND>::acc_t (&acc)[WM][W
             for (int vg = 0; vg < 4; ++vg) {
                 const int nl = j * 32 + vg * 8;
                 if (!GUARD || (m < g.M && wn0 + nl + fh * 4 < g.N)) {
-                    v4i raw = {static_cast<int>(acc[i][j][vg * 4 + 0]), static_cast<int>(acc[i][j][vg * 4 + 1]),
-                               static_cast<int>(acc[i][j][vg * 4 + 2]), static_cast<int>(acc[i][j][vg * 4 + 3])};
+                    v4i raw = {raw_bits(acc[i][j][vg * 4 + 0]), raw_bits(acc[i][j][vg * 4 + 1]),
+                               raw_bits(acc[i][j][vg * 4 + 2]), raw_bits(acc[i][j][vg * 4 + 3])};
                     *reinterpret_cast<v4i *>(row + nl) = raw;
                 }
             }
@@ -224,7 +230,8 @@ __device__ __forceinline__ void store_scaled(typename Mma<KIND>::acc_t (&acc)[WM
     }
 }
 
-// OUT: 0 = C in bf16, 1 = C in fp32, 2 = raw int32 accumulators (parity export)
+// OUT: 0 = C in bf16, 1 = C in fp32, 2 = raw int32 accumulators (parity export),
+//      3 = raw 32-bit partial accumulators of this workgroup's k range (split-K)
 template <int KIND, int WM, int WN, int KCH, bool TAIL, int OUT>
 __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
 {
@@ -243,7 +250,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
     int tm, tn;
     {
         const int nb = g.tiles_m * g.tiles_n;
-        const int pid = blockIdx.x;
+        const int pid = blockIdx.x % nb;           // blockIdx.x / nb is the k split
         const int xcd = pid & 7, idx = pid >> 3;
         const int per = nb >> 3, rem = nb & 7;
         const int logical = xcd * per + (xcd < rem ? xcd : rem) + idx;
@@ -283,18 +290,23 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
         for (int j = 0; j < WN; ++j) acc[i][j] = Mma<KIND>::zero();
 
     u32x4 ra[PA], rb[PB];
+    bool keepA = true, keepB = true;   // TAIL: whether this thread's chunk of the step in ra / rb lies inside the row
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    const int nk = (g.Kb + KCH * 16 - 1) / (KCH * 16);
+    // k steps of this workgroup: all of them, or the split's share [kbeg, kbeg + nk)
+    const int nk_all = (g.Kb + KCH * 16 - 1) / (KCH * 16);
+    const int split = blockIdx.x / (g.tiles_m * g.tiles_n);
+    const int kbeg = static_cast<int>(static_cast<int64_t>(nk_all) * split / g.splits);
+    const int nk = static_cast<int>(static_cast<int64_t>(nk_all) * (split + 1) / g.splits) - kbeg;
 
     // Step KT of k into registers (A rows, then Bm rows) with raw buffer loads: the address is
     // (tile base in the resource) + (per-thread row offset, a loop-invariant VGPR) + (k offset, an
     // SGPR), so no vector arithmetic is spent on addresses inside the loop.  With a ragged last
     // step (TAIL) chunks past the end of the row are read from the row's last chunk instead (in
-    // bounds) and replaced by zeros.
+    // bounds) and replaced by zeros when the registers are written to LDS.
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(baseA), 0, 0x7FFFFFFF, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(baseB), 0, 0x7FFFFFFF, 0x00020000);
 #define HLQ_KOFS(KT)                                                                                          \
-        const int kuni = (KT) * (KCH * 16);               /* wave-uniform: lives in an SGPR */                \
+        const int kuni = (kbeg + (KT)) * (KCH * 16);      /* wave-uniform: lives in an SGPR */                \
         const bool kok = !TAIL || kuni + lc * 16 < g.Kb;                                                      \
         const uint32_t kfix = TAIL ? static_cast<uint32_t>(kok ? lc * 16 : g.Kb - 16 - kuni) : lc * 16u;
 #define HLQ_LOAD_GLOBAL_A(KT)                                                                                 \
@@ -302,16 +314,16 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
         HLQ_KOFS(KT)                                                                                          \
         _Pragma("unroll") for (int i = 0; i < PA; ++i) {                                                      \
             ra[i] = __builtin_amdgcn_raw_buffer_load_b128(rsA, offa[i] + kfix, kuni, 0);                      \
-            if (TAIL) ra[i] = kok ? ra[i] : zero4;                                                            \
         }                                                                                                     \
+        keepA = kok;   /* applied when the registers are published, not here: no wait on the load */          \
     }
 #define HLQ_LOAD_GLOBAL_B(KT)                                                                                 \
     {                                                                                                         \
         HLQ_KOFS(KT)                                                                                          \
         _Pragma("unroll") for (int j = 0; j < PB; ++j) {                                                      \
             rb[j] = __builtin_amdgcn_raw_buffer_load_b128(rsB, offb[j] + kfix, kuni, 0);                      \
-            if (TAIL) rb[j] = kok ? rb[j] : zero4;                                                            \
         }                                                                                                     \
+        keepB = kok;                                                                                          \
     }
     // LDS addressing.  Every address is (one per-lane register) + (compile-time immediate): the
     // swizzle only involves the low four row bits, so the i-th 32-row group is a constant 4 KB
@@ -333,12 +345,13 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
 #define HLQ_STORE_LDS_A()                                                                                     \
     {                                                                                                         \
         _Pragma("unroll") for (int i = 0; i < PA; ++i)                                                        \
-            *reinterpret_cast<u32x4 *>(ldsb + wr_off + i * (RPP * KCH * 16)) = ra[i];                         \
+            *reinterpret_cast<u32x4 *>(ldsb + wr_off + i * (RPP * KCH * 16)) = (!TAIL || keepA) ? ra[i] : zero4; \
     }
 #define HLQ_STORE_LDS_B()                                                                                     \
     {                                                                                                         \
         _Pragma("unroll") for (int j = 0; j < PB; ++j)                                                        \
-            *reinterpret_cast<u32x4 *>(ldsb + wr_off + (BM * KCH * 16) + j * (RPP * KCH * 16)) = rb[j];       \
+            *reinterpret_cast<u32x4 *>(ldsb + wr_off + (BM * KCH * 16) + j * (RPP * KCH * 16)) =              \
+                (!TAIL || keepB) ? rb[j] : zero4;                                                             \
     }
     u32x4 fa[2][WM], fb[2][WN];
 #define HLQ_READ_FRAGS(BUF, KS)                                                                               \
@@ -446,14 +459,88 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
     if (OUT == 2) {
         if (interior) store_raw<KIND, WM, WN, false>(acc, g.acc, g.M, g.N, wm0, wn0, lane);
         else store_raw<KIND, WM, WN, true>(acc, g.acc, g.M, g.N, wm0, wn0, lane);
+    } else if (OUT == 3) {
+        int32_t *part = g.partial + static_cast<int64_t>(split) * g.M * g.N;
+        if (interior) store_raw<KIND, WM, WN, false>(acc, part, g.M, g.N, wm0, wn0, lane);
+        else store_raw<KIND, WM, WN, true>(acc, part, g.M, g.N, wm0, wn0, lane);
     } else {
         if (interior) store_scaled<KIND, WM, WN, OUT == 1, false>(acc, g.C, g.M, g.N, g.sA, g.sB, g.alpha, wm0, wn0, lane, slab);
         else store_scaled<KIND, WM, WN, OUT == 1, true>(acc, g.C, g.M, g.N, g.sA, g.sB, g.alpha, wm0, wn0, lane, slab);
     }
 }
 
+// ---- split-K: sum of the partial accumulators, then the same scaling as the direct epilogue -------
+// Partials are summed in split order (integers exactly, floats in a fixed order): deterministic.
+template <int KIND, bool F32>
+__global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t *__restrict__ partial, int splits, int M, int N,
+                                                       const float *__restrict__ sA, const float *__restrict__ sB,
+                                                       float alpha, void *__restrict__ C)
+{
+    const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
+    const int64_t total = static_cast<int64_t>(M) * N;
+    if (e >= total) return;
+    const int m = static_cast<int>(e / N), n = static_cast<int>(e % N);
+    f32x4 o;
+    if (KIND == 0) {
+        v4i sum = {0, 0, 0, 0};
+        for (int z = 0; z < splits; ++z) sum += *reinterpret_cast<const v4i *>(partial + z * total + e);
+        const float sa = sA ? sA[m] : 1.0f;
+        f32x4 cs = {alpha, alpha, alpha, alpha};
+        if (sB) cs = *reinterpret_cast<const f32x4 *>(sB + n) * alpha;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = static_cast<float>(sum[k]) * (sa * cs[k]);
+    } else {
+        f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (int z = 0; z < splits; ++z) sum += *reinterpret_cast<const f32x4 *>(partial + z * total + e);
+        o = sum * alpha;
+    }
+    if (F32) {
+        *reinterpret_cast<f32x4 *>(static_cast<float *>(C) + e) = o;
+    } else {
+        u32x2 p = {pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+        *reinterpret_cast<u32x2 *>(static_cast<bf16_t *>(C) + e) = p;
+    }
+}
+
+// Plan: tile size and number of k splits, from a small cost model (microseconds) fitted to
+// measurements on MI355X: a 256-tile step (128 B of k) costs ~1.6 us and a tile ~12 us of fixed
+// prologue/epilogue, one workgroup per compute unit; a 128-tile step ~0.45 us, ~6 us fixed, two
+// workgroups per compute unit; the split-K partials cost their HBM round trip plus a launch.
+struct GemmPlan {
+    bool big;
+    int splits;
+};
+
+static GemmPlan plan_gemm(int M, int N, int Kb, size_t ws_bytes, bool allow_split)
+{
+    const int nk = (Kb + 127) / 128;
+    const double mn = static_cast<double>(M) * N;
+    GemmPlan best{true, 1};
+    double best_t = 1e30;
+    for (int big = 1; big >= 0; --big) {
+        const int tile = big ? 256 : 128;
+        const double tiles = static_cast<double>((M + tile - 1) / tile) * ((N + tile - 1) / tile);
+        const double slots = big ? 256.0 : 512.0, step = big ? 1.6 : 0.45, fixed = big ? 12.0 : 6.0;
+        for (int S = 1; S <= 16; ++S) {
+            if (S > 1 && (!allow_split || S > nk || static_cast<double>(S) * mn * 4.0 > static_cast<double>(ws_bytes))) break;
+            const double rounds = __builtin_ceil(tiles * S / slots);
+            double t = rounds * (__builtin_ceil(static_cast<double>(nk) / S) * step + fixed);
+            if (S > 1) t += 2.0 * S * mn * 4.0 / 5.0e6 + 4.0;
+            if (t < best_t) { best_t = t; best = GemmPlan{big != 0, S}; }
+        }
+    }
+    return best;
+}
+
+size_t gemm_ws_bytes(int kind, int M, int N, int K)
+{
+    const int Kb = kind == 0 ? K : 2 * K;
+    const GemmPlan p = plan_gemm(M, N, Kb, ~static_cast<size_t>(0), true);
+    return p.splits > 1 ? static_cast<size_t>(p.splits) * M * N * 4 : 0;
+}
+
 template <int KIND, int WM, int WN, int KCH, bool TAIL, int OUT>
-static hipError_t launch_tt(const GemmArgs &a, hipStream_t st)
+static hipError_t launch_tt(const GemmArgs &a, int splits, hipStream_t st)
 {
     GemmDev g;
     g.A = static_cast<const char *>(a.A);
@@ -469,6 +556,8 @@ static hipError_t launch_tt(const GemmArgs &a, hipStream_t st)
     g.acc = a.acc;
     g.tiles_m = (a.M + 64 * WM - 1) / (64 * WM);
     g.tiles_n = (a.N + 64 * WN - 1) / (64 * WN);
+    g.splits = splits;
+    g.partial = static_cast<int32_t *>(a.ws);
     constexpr size_t main_bytes = 2u * (64 * WM + 64 * WN) * KCH * 16u;
     constexpr size_t epi_bytes = 4u * EpiSlab<WN>::BYTES;
     constexpr size_t lds_bytes = main_bytes > epi_bytes ? main_bytes : epi_bytes;
@@ -479,36 +568,48 @@ static hipError_t launch_tt(const GemmArgs &a, hipStream_t st)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_gemm_nt<KIND, WM, WN, KCH, TAIL, OUT>), dim3(g.tiles_m * g.tiles_n), dim3(256), lds_bytes, st, g);
+    hipLaunchKernelGGL((k_gemm_nt<KIND, WM, WN, KCH, TAIL, OUT>), dim3(g.tiles_m * g.tiles_n * splits), dim3(256), lds_bytes, st, g);
     return hipGetLastError();
 }
 
 template <int KIND, int WM, int WN, int KCH, int OUT>
-static hipError_t launch_o(const GemmArgs &a, hipStream_t st)
+static hipError_t launch_o(const GemmArgs &a, int splits, hipStream_t st)
 {
     const int Kb = KIND == 0 ? a.K : 2 * a.K;
-    return (Kb % (KCH * 16) == 0) ? launch_tt<KIND, WM, WN, KCH, false, OUT>(a, st)
-                                  : launch_tt<KIND, WM, WN, KCH, true, OUT>(a, st);
+    return (Kb % (KCH * 16) == 0) ? launch_tt<KIND, WM, WN, KCH, false, OUT>(a, splits, st)
+                                  : launch_tt<KIND, WM, WN, KCH, true, OUT>(a, splits, st);
 }
 
 template <int KIND, int WM, int WN, int KCH>
-static hipError_t launch_t(const GemmArgs &a, hipStream_t st)
+static hipError_t launch_t(const GemmArgs &a, int splits, hipStream_t st)
 {
     // the raw accumulators and the scaled output are separate launches of the same product
     if (KIND == 0 && a.acc) {
-        hipError_t e = launch_o<0, WM, WN, KCH, 2>(a, st);
+        hipError_t e = launch_o<0, WM, WN, KCH, 2>(a, 1, st);
         if (e != hipSuccess || !a.C) return e;
     }
-    return a.c_is_f32 ? launch_o<KIND, WM, WN, KCH, 1>(a, st) : launch_o<KIND, WM, WN, KCH, 0>(a, st);
+    if (splits > 1) {
+        hipError_t e = launch_o<KIND, WM, WN, KCH, 3>(a, splits, st);
+        if (e != hipSuccess) return e;
+        const int64_t quads = (static_cast<int64_t>(a.M) * a.N + 3) / 4;
+        const unsigned grid = static_cast<unsigned>((quads + 255) / 256);
+        const int32_t *part = static_cast<const int32_t *>(a.ws);
+        if (a.c_is_f32)
+            hipLaunchKernelGGL((k_splitk_reduce<KIND, true>), dim3(grid), dim3(256), 0, st, part, splits, a.M, a.N, a.sA, a.sB, a.alpha, a.C);
+        else
+            hipLaunchKernelGGL((k_splitk_reduce<KIND, false>), dim3(grid), dim3(256), 0, st, part, splits, a.M, a.N, a.sA, a.sB, a.alpha, a.C);
+        return hipGetLastError();
+    }
+    return a.c_is_f32 ? launch_o<KIND, WM, WN, KCH, 1>(a, 1, st) : launch_o<KIND, WM, WN, KCH, 0>(a, 1, st);
 }
 
 hipError_t launch_gemm_nt(int kind, const GemmArgs &a, hipStream_t st)
 {
-    // 256 x 256 tiles when they still give every compute unit work, else 128 x 128
-    const int64_t big_tiles = static_cast<int64_t>((a.M + 255) / 256) * ((a.N + 255) / 256);
-    const bool big = big_tiles >= 200;
-    if (kind == 0) return big ? launch_t<0, 4, 4, 8>(a, st) : launch_t<0, 2, 2, 8>(a, st);
-    return big ? launch_t<1, 4, 4, 8>(a, st) : launch_t<1, 2, 2, 8>(a, st);
+    const int Kb = kind == 0 ? a.K : 2 * a.K;
+    const bool can_split = a.ws != nullptr && a.C != nullptr && (reinterpret_cast<uintptr_t>(a.ws) & 15) == 0;
+    const GemmPlan p = plan_gemm(a.M, a.N, Kb, a.ws_bytes, can_split);
+    if (kind == 0) return p.big ? launch_t<0, 4, 4, 8>(a, p.splits, st) : launch_t<0, 2, 2, 8>(a, p.splits, st);
+    return p.big ? launch_t<1, 4, 4, 8>(a, p.splits, st) : launch_t<1, 2, 2, 8>(a, p.splits, st);
 }
 
 }  // namespace hlq

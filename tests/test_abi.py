@@ -90,13 +90,13 @@ def test_stage_entry_points_reject_bad_arguments_without_a_gpu():
     assert l.hlq_quantize_w(FAKE, 256, 256, 16, 0, 0, 4, FAKE, FAKE, None, None, 0, None) == 1
     assert l.hlq_quantize_w(FAKE, 256, 256, 16, 0, 0, 4, FAKE, FAKE, None, FAKE, 16, None) == 6
     assert l.hlq_quantize_w(FAKE, 256, 100, 16, 0, 0, 4, FAKE, FAKE, None, FAKE, 1 << 20, None) == 2
-    assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 64, 40, None, None, 1.0, 1, FAKE, None, None) == 2   # K % 16
-    assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 62, 64, None, None, 1.0, 1, FAKE, None, None) == 2   # Nn % 4
-    assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 64, 64, None, None, 1.0, 1, None, None, None) == 1
+    assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 64, 40, None, None, 1.0, 1, FAKE, None, None, 0, None) == 2   # K % 16
+    assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 62, 64, None, None, 1.0, 1, FAKE, None, None, 0, None) == 2   # Nn % 4
+    assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 64, 64, None, None, 1.0, 1, None, None, None, 0, None) == 1
     assert l.hlq_hla_project(FAKE, 250, 64, 16, 8, 0, FAKE, None, None) == 2
     assert l.hlq_hla_project(FAKE, 256, 64, 16, 5, 0, FAKE, None, None) == 4
     assert l.hlq_compress_act(FAKE, 256, 64, 16, 8, 0, None, None) == 1
-    assert l.hlq_bf16_gemm_nt(FAKE, FAKE, 64, 64, 36, 1.0, 0, FAKE, None) == 2                     # K % 8
+    assert l.hlq_bf16_gemm_nt(FAKE, FAKE, 64, 64, 36, 1.0, 0, FAKE, None, 0, None) == 2                     # K % 8
     W256 = C.c_void_p(0x10000)
     assert l.hlq_hla_quantize(FAKE, 256, 64, 16, 2, 0, 2, 0, FAKE, FAKE, None, W256, 1 << 20, None) == 4   # r % 4
     assert l.hlq_hla_quantize(FAKE, 256, 64, 16, 8, 0, 1, 0, FAKE, FAKE, None, W256, 1 << 20, None) == 2   # stream id

@@ -145,6 +145,7 @@ def _codes(shape, seed):
 
 
 GEMM_I8_CASES = [
+    (768, 520, 3072),       # few tiles, long reduction: split over k when scratch is given
     (256, 256, 256),        # config 1
     (300, 260, 320),        # ragged M and Nn (128-tiles), K a multiple of 64
     (130, 132, 592),        # K = 9*64 + 16: ragged last k step
@@ -170,6 +171,16 @@ def test_int8_gemm_accumulators_bit_exact(M, Nn, K):
     outb = torch.empty((M, Nn), dtype=torch.bfloat16, device=DEV)
     hlq.hlq_int8_gemm_nt(dev(A), dev(Bm), dev(sA), dev(sB), 1.0 / 16, outb, None)
     assert row_rel_err(outb.float().cpu().numpy(), want, True) < TOL_OUT
+    # with scratch the reduction may be split over several workgroups per tile: integer partial
+    # sums are exact, so the result has to be the same bits
+    need = hlq.hlq_gemm_workspace_bytes(0, M, Nn, K)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=DEV)
+    out2 = torch.empty_like(out)
+    hlq.hlq_int8_gemm_nt(dev(A), dev(Bm), dev(sA), dev(sB), 1.0 / 16, out2, None, ws)
+    assert torch.equal(out, out2)
+    outb2 = torch.empty_like(outb)
+    hlq.hlq_int8_gemm_nt(dev(A), dev(Bm), dev(sA), dev(sB), 1.0 / 16, outb2, None, ws)
+    assert torch.equal(outb, outb2)
 
 
 def test_int8_gemm_large_tile_variant_sampled():
@@ -235,7 +246,7 @@ def test_hla_project(N, D, B, r, dtype):
 # --------------------------------------------------------------------------------------------
 # K4: bf16 MFMA product
 # --------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("M,Nn,K", [(256, 256, 128), (300, 260, 104), (1030, 520, 6304), (64, 8, 8)])
+@pytest.mark.parametrize("M,Nn,K", [(256, 256, 128), (300, 260, 104), (1030, 520, 6304), (64, 8, 8), (768, 264, 6272)])
 def test_bf16_gemm(M, Nn, K):
     A = rand_tensor((M, K), torch.bfloat16, seed=M + K)
     Bm = rand_tensor((Nn, K), torch.bfloat16, seed=Nn + K + 1)
@@ -247,6 +258,14 @@ def test_bf16_gemm(M, Nn, K):
     out16 = torch.empty((M, Nn), dtype=torch.bfloat16, device=DEV)
     hlq.hlq_bf16_gemm_nt(dev(A), dev(Bm), 0.0625, out16)
     assert row_rel_err(out16.float().cpu().numpy(), ref, True) < TOL_OUT
+    # split over k when scratch is given (fp32 partial sums added in a fixed order)
+    ws = torch.empty(max(hlq.hlq_gemm_workspace_bytes(1, M, Nn, K), 16), dtype=torch.uint8, device=DEV)
+    out32s = torch.empty_like(out32)
+    hlq.hlq_bf16_gemm_nt(dev(A), dev(Bm), 0.0625, out32s, ws)
+    assert row_rel_err(out32s.cpu().numpy(), ref) < 1e-5
+    out32t = torch.empty_like(out32)
+    hlq.hlq_bf16_gemm_nt(dev(A), dev(Bm), 0.0625, out32t, ws)
+    assert torch.equal(out32s, out32t)          # deterministic
 
 
 def test_bf16_gemm_large_tile_variant_sampled():
