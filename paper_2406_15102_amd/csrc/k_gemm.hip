@@ -504,8 +504,8 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t *__restrict
 
 // Plan: tile size and number of k splits, from a small cost model (microseconds) fitted to
 // measurements on MI355X: a 256-tile step (128 B of k) costs ~1.6 us and a tile ~12 us of fixed
-// prologue/epilogue, one workgroup per compute unit; a 128-tile step ~0.45 us, ~6 us fixed, two
-// workgroups per compute unit; the split-K partials cost their HBM round trip plus a launch.
+// prologue/epilogue, one workgroup per compute unit; a 128-tile step ~0.5 us alone on its compute
+// unit and ~0.95 us when two share it, ~6 us fixed; the split-K partials cost their HBM round trip plus a launch.
 struct GemmPlan {
     bool big;
     int splits;
@@ -520,8 +520,10 @@ static GemmPlan plan_gemm(int M, int N, int Kb, size_t ws_bytes, bool allow_spli
     for (int big = 1; big >= 0; --big) {
         const int tile = big ? 256 : 128;
         const double tiles = static_cast<double>((M + tile - 1) / tile) * ((N + tile - 1) / tile);
-        const double slots = big ? 256.0 : 512.0, step = big ? 1.6 : 0.45, fixed = big ? 12.0 : 6.0;
+        const double slots = big ? 256.0 : 512.0, fixed = big ? 12.0 : 6.0;
         for (int S = 1; S <= 16; ++S) {
+            // two co-resident 128-tile workgroups share a compute unit's LDS and power: slower steps
+            const double step = big ? 1.6 : (tiles * S > 256.0 ? 0.95 : 0.5);
             if (S > 1 && (!allow_split || S > nk || static_cast<double>(S) * mn * 4.0 > static_cast<double>(ws_bytes))) break;
             const double rounds = __builtin_ceil(tiles * S / slots);
             double t = rounds * (__builtin_ceil(static_cast<double>(nk) / S) * step + fixed);
