@@ -355,11 +355,13 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
     }
     u32x4 fa[2][WM], fb[2][WN];
 #define HLQ_READ_FRAGS(BUF, KS)                                                                               \
-    {                                                                                                         \
-        _Pragma("unroll") for (int i = 0; i < WM; ++i)                                                        \
-            fa[BUF][i] = *reinterpret_cast<const u32x4 *>(ldsb + rdA[KS] + i * (32 * KCH * 16));              \
-        _Pragma("unroll") for (int j = 0; j < WN; ++j)                                                        \
+    {   /* in the order the MFMAs consume them: fa[0] with every fb[j] first */                               \
+        fb[BUF][0] = *reinterpret_cast<const u32x4 *>(ldsb + rdB[KS]);                                        \
+        fa[BUF][0] = *reinterpret_cast<const u32x4 *>(ldsb + rdA[KS]);                                        \
+        _Pragma("unroll") for (int j = 1; j < WN; ++j)                                                        \
             fb[BUF][j] = *reinterpret_cast<const u32x4 *>(ldsb + rdB[KS] + j * (32 * KCH * 16));              \
+        _Pragma("unroll") for (int i = 1; i < WM; ++i)                                                        \
+            fa[BUF][i] = *reinterpret_cast<const u32x4 *>(ldsb + rdA[KS] + i * (32 * KCH * 16));              \
     }
 #define HLQ_TOGGLE_STAGE()                                                                                    \
     {                                                                                                         \
@@ -390,7 +392,6 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
     HLQ_READ_FRAGS(0, 0)
 
     static_assert(NS == 4, "the staging schedule below is written for four sub-steps per step");
-    constexpr int MPR = (WM * WN) / (WM + WN);   // MFMAs per fragment read
 
     for (int kt = 0; kt < nk; ++kt) {
         const int kt2 = kt + 2 < nk ? kt + 2 : nk - 1;
@@ -416,30 +417,29 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
                 HLQ_LOAD_GLOBAL_B(kt2)
                 wr_off ^= STAGE_BYTES;
             }
-            // Issue order within the sub-step.  LDS writes may not pass the fragment reads (same
-            // array), so a staging sub-step threads its reads between the first half of the MFMAs
-            // and its LDS writes + global loads between the second half.
-            if (ks < 2) {
+            // Issue order within the sub-step.  The fragment reads are threaded between the first
+            // half of the MFMAs, so that the last of them has a quarter of a step to return before
+            // anything waits on it (the next sub-step's first MFMA, the barrier, the loop's back
+            // edge).  LDS writes may not pass the reads (same array): a staging sub-step threads its
+            // LDS writes + global loads between the second half of the MFMAs.
 #pragma unroll
-                for (int q = 0; q < (WM * WN) / 2; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           // one MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 2 * (WM + WN) / (WM * WN), 0);   // fragment reads
-                }
+            for (int q = 0; q < (WM * WN) / 2; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 2 * (WM + WN) / (WM * WN), 0);   // fragment reads
+            }
 #pragma unroll
-                for (int q = 0; q < (WM * WN) / 2; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x200, 2 * PA / (WM * WN), 0);          // LDS writes
-                    __builtin_amdgcn_sched_group_barrier(0x020, 2 * PA / (WM * WN), 0);          // global loads
-                }
-            } else {
-#pragma unroll
-                for (int q = 0; q < WM + WN; ++q) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            for (int q = 0; q < (WM * WN) / 2; ++q) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                if (ks < 2) {
+                    __builtin_amdgcn_sched_group_barrier(0x200, 2 * PA / (WM * WN), 0);      // LDS writes
+                    __builtin_amdgcn_sched_group_barrier(0x020, 2 * PA / (WM * WN), 0);      // global loads
                 }
             }
-            if (ks == NS - 2) lds_barrier();
             __builtin_amdgcn_sched_barrier(0);
+            if (ks == NS - 2) {              // after this sub-step's last MFMA has been issued
+                lds_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     }
 #undef HLQ_KOFS
