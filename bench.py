@@ -63,7 +63,8 @@ def cpu_baseline(w, t, budget_tokens):
     return {
         "value": total_s * 1e6, "unit": "us", "cores": oracle.num_threads(), "kind": "oracle",
         "sample": "W transform+quantise in full (%.1f s); token-dependent stages on the first %d of %d tokens "
-                  "(%.1f s), scaled x%g; extrapolated" % (t_w, budget_tokens, w.N, t_tok, w.N / budget_tokens),
+                  "(%.1f s), scaled x%g%s" % (t_w, budget_tokens, w.N, t_tok, w.N / budget_tokens,
+                                              "" if budget_tokens == w.N else "; extrapolated"),
     }
 
 
@@ -73,7 +74,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c4")
-    ap.add_argument("--cpu-tokens", type=int, default=2048, help="tokens of the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--no-modes", action="store_true",
+                    help="skip the extra whole-path timings of the method's options (keeps a profile to the default path)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -139,11 +142,27 @@ def main():
         "hla_x": ("hbm", N * I * e + 2 * Kc * I),
         "bf16_gemm": ("mfma_bf16", 2.0 * O * I * Kc),
     }
-    kernels = {}
-    for name, fn in stages.items():
+    # Two timings per kernel: "us" = inside the whole sequence (events between the stage calls, the
+    # order and the thermal / cache state of the real path), "us_alone" = the same launch back to back.
+    iters = max(10, args.steps // 2)
+    names = list(stages)
+    for fn in stages.values():
         for _ in range(3):
             fn()
-        us = _event_time_us(fn, max(10, args.steps // 2), torch)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(iters)]
+    torch.cuda.synchronize()
+    for it in range(iters):
+        evs[it][0].record()
+        for k, name in enumerate(names):
+            stages[name]()
+            evs[it][k + 1].record()
+    torch.cuda.synchronize()
+    seq_us = {name: sum(evs[it][k].elapsed_time(evs[it][k + 1]) for it in range(iters)) * 1000.0 / iters
+              for k, name in enumerate(names)}
+    kernels = {}
+    for name, fn in stages.items():
+        alone = _event_time_us(fn, iters, torch)
+        us = seq_us[name]
         kind, amount = work[name]
         if kind == "hbm":
             ach, peak, unit = amount / us / 1e3, PEAK_HBM_GBS, "GB/s"
@@ -151,13 +170,14 @@ def main():
             ach, peak, unit = amount / us / 1e6, PEAK_I8_TOPS, "TFLOP/s"
         else:
             ach, peak, unit = amount / us / 1e6, PEAK_BF16_TFLOPS, "TFLOP/s"
-        kernels[name] = {"us": round(us, 2), "bound": kind, "achieved": round(ach, 1), "peak": peak, "unit": unit,
-                         "frac": round(ach / peak, 4)}
+        kernels[name] = {"us": round(us, 2), "us_alone": round(alone, 2), "bound": kind, "achieved": round(ach, 1),
+                         "peak": peak, "unit": unit, "frac": round(ach / peak, 4)}
 
     # ---- the method's options, whole path (extra figures; `value` stays the default path) ----
     modes = {}
-    for label, flags in (("gw_int8", hlq.HLQ_FLAG_GW_INT8), ("gx_8bit", hlq.HLQ_FLAG_GX_8BIT),
-                         ("gx_8bit+gw_int8", hlq.HLQ_FLAG_GX_8BIT | hlq.HLQ_FLAG_GW_INT8)):
+    for label, flags in (() if args.no_modes else (
+            ("gw_int8", hlq.HLQ_FLAG_GW_INT8), ("gx_8bit", hlq.HLQ_FLAG_GX_8BIT),
+            ("gx_8bit+gw_int8", hlq.HLQ_FLAG_GX_8BIT | hlq.HLQ_FLAG_GW_INT8))):
         need = hlq.hlq_workspace_bytes_mode(N, I, O, B, r, False, flags)
         if need == 0 or need > ws.numel():
             continue
@@ -196,8 +216,8 @@ def main():
             traffic = None
     roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["achieved"], "peak": PEAK_I8_TOPS,
                 "unit": "TFLOP/s", "frac": kernels[dom]["frac"], "traffic": traffic,
-                "note": "int8 MFMA ops (2*N*d_in*d_out per launch) over the HIP-event average of %s launches"
-                        % max(10, args.steps // 2)}
+                "note": "int8 MFMA ops (2*N*d_in*d_out per launch) over the HIP-event average of %s launches, "
+                        "each timed inside the stage sequence of the path" % iters}
 
     cpu = None
     if args.cpu_tokens > 0:
