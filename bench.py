@@ -125,12 +125,12 @@ def main():
     XhT = torch.empty((I, Kc), dtype=torch.bfloat16, device=dev)
     gws = torch.empty(max(16, hlq.hlq_gemm_workspace_bytes(0, N, I, O), hlq.hlq_gemm_workspace_bytes(1, O, I, Kc)),
                       dtype=torch.uint8, device=dev)   # split-K scratch, as the whole path has it
-    stages = {
+    stages = {   # in the launch order of the whole path
         "quantize_g": lambda: hlq.hlq_quantize_g(G, B, w.seed, Gq, sG),
-        "quantize_w": lambda: hlq.hlq_quantize_w(W, B, w.seed, WqT, sW, wws),
-        "int8_gemm": lambda: hlq.hlq_int8_gemm_nt(Gq, WqT, sG, sW, 1.0 / B, dX, None, gws),
         "hla_g": lambda: hlq.hlq_hla_project(G, B, r, GhT),
         "hla_x": lambda: hlq.hlq_hla_project(X, B, r, XhT),
+        "quantize_w": lambda: hlq.hlq_quantize_w(W, B, w.seed, WqT, sW, wws),
+        "int8_gemm": lambda: hlq.hlq_int8_gemm_nt(Gq, WqT, sG, sW, 1.0 / B, dX, None, gws),
         "bf16_gemm": lambda: hlq.hlq_bf16_gemm_nt(GhT, XhT, 1.0 / B, dW, gws),
     }
     e = 2 if w.dtype == "bf16" else 4

@@ -109,12 +109,19 @@ int hlq_compress_act(const void *X, int64_t N, int64_t d_in, int B, int r, int d
 
 /* ---- stage entry points (the steps above one by one; also what the parity tests probe) ---- */
 
+/* `bits` of hlq_quantize_g / hlq_quantize_w */
+#define HLQ_BITS_4 4            /* codes in [-7, 7] (the method's setting), one int8 each */
+#define HLQ_BITS_8 8            /* codes in [-127, 127] (the int8 warm-up phase of Sec. 7), one int8 each */
+#define HLQ_BITS_4_PACKED 0x104 /* codes in [-7, 7], two to a byte: code 2b in the low nibble of byte b,
+                                   code 2b+1 in the high nibble, two's complement; rows of d_out/2 bytes;
+                                   needs d_out % 32 == 0.  The operand format of hlq_int4_gemm_nt. */
+
 /*
  * Stages 1-2 of the g_x list: block Hadamard transform of every row of G along d_out, then
  * stochastic quantisation with one absmax scale per row.
- *   bits  4: codes in [-7, 7] (the method's setting); 8: codes in [-127, 127] (the int8 warm-up
- *         phase of Sec. 7).  Anything else: HLQ_ERR_DTYPE.
- *   Gq [N, d_out] int8;  sG [N] fp32, sG[n] = max|coef| / qmax.
+ *   bits  one of HLQ_BITS_*; anything else: HLQ_ERR_DTYPE.  The codes are the same for HLQ_BITS_4
+ *         and HLQ_BITS_4_PACKED; only their storage differs.
+ *   Gq [N, d_out] int8 (packed: [N, d_out/2] bytes);  sG [N] fp32, sG[n] = max|coef| / qmax.
  *   coeff: NULL, or [N, d_out] fp32 receiving the transformed values (unnormalised H).
  */
 int hlq_quantize_g(const void *G, int64_t N, int64_t d_out, int B, uint64_t seed, int dtype, int bits,
@@ -123,8 +130,8 @@ int hlq_quantize_g(const void *G, int64_t N, int64_t d_out, int B, uint64_t seed
 /*
  * Stages 3-4 of the g_x list: H^T W (blocks of B consecutive rows of W are mixed), quantised
  * with one scale per in-feature and stored transposed, reduction axis contiguous:
- *   WqT [d_in, d_out] int8;  sW [d_in] fp32;  coeffT: NULL or [d_in, d_out] fp32.
- *   bits: 4 or 8, as for hlq_quantize_g.
+ *   WqT [d_in, d_out] int8 (packed: [d_in, d_out/2] bytes);  sW [d_in] fp32;  coeffT: NULL or
+ *   [d_in, d_out] fp32.  bits: as for hlq_quantize_g.
  *   workspace: >= hlq_quantize_w_workspace_bytes(d_out, d_in) bytes of device scratch (256-aligned).
  */
 size_t hlq_quantize_w_workspace_bytes(int64_t d_out, int64_t d_in);
@@ -143,10 +150,23 @@ int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t s
  *   second kernel; without it, or when it is too small, k is never split.  Same result either way
  *   for the int8 product; for the bf16 product the fp32 summation order differs.
  */
-size_t hlq_gemm_workspace_bytes(int kind /* 0 int8, 1 bf16 */, int64_t M, int64_t Nn, int64_t K);
+size_t hlq_gemm_workspace_bytes(int kind /* 0 int8, 1 bf16, 2 packed 4-bit */, int64_t M, int64_t Nn, int64_t K);
 int hlq_int8_gemm_nt(const int8_t *A, const int8_t *Bm, int64_t M, int64_t Nn, int64_t K,
                      const float *sA, const float *sB, float alpha, int out_dtype, void *C,
                      int32_t *acc, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The same product on 4-bit codes stored two to a byte (the paper's int4 operands, Sec. 6.1):
+ * byte b of a row holds code 2b in its low nibble and code 2b+1 in its high nibble, two's
+ * complement, |code| <= 7.  Half the bytes of the int8 layout in HBM, L2 and LDS; the nibbles are
+ * widened to int8 MFMA operands in registers.  C and acc equal those of hlq_int8_gemm_nt on the
+ * same codes bit for bit.
+ *   A [M, K/2 bytes], Bm [Nn, K/2 bytes]; K % 32 == 0, K <= 131072, Nn % 4 == 0.
+ *   Other arguments as for hlq_int8_gemm_nt (workspace: kind 2).
+ */
+int hlq_int4_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64_t K, const float *sA,
+                     const float *sB, float alpha, int out_dtype, void *C, int32_t *acc, void *workspace,
+                     size_t workspace_bytes, void *stream);
 
 /*
  * Stages 1 and 3 of the g_w list for any [N, D] tensor T (G or X): the projection described at
@@ -170,6 +190,9 @@ int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64
 #define HLQ_FLAG_GX_8BIT 1 /* g_x codes in [-127, 127]: the int8 warm-up phase of Sec. 7 */
 #define HLQ_FLAG_GW_INT8 2 /* g_w list in full (Sec. 6.1): projected X and G quantised to int8
                               (stages 2, 4), integer product (5), dequantisation (6) */
+#define HLQ_FLAG_GX_UNPACKED 4 /* keep the 4-bit g_x codes one per int8 between the stages.  By default
+                                  they are stored two to a byte whenever d_out % 32 == 0 (same codes, same
+                                  dX bit for bit; half the traffic). */
 
 /*
  * Stages 1-2 (T = X, tensor 2) or 3-4 (T = G, tensor 3) of the g_w list: the projection described

@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libhlq.so")
 
 HLQ_BF16, HLQ_F32 = 0, 1
 HLQ_OK = 0
-HLQ_FLAG_GX_8BIT, HLQ_FLAG_GW_INT8 = 1, 2
+HLQ_FLAG_GX_8BIT, HLQ_FLAG_GW_INT8, HLQ_FLAG_GX_UNPACKED = 1, 2, 4
+HLQ_BITS_4, HLQ_BITS_8, HLQ_BITS_4_PACKED = 4, 8, 0x104
 
 _EXPORTS = {
     "hlq_status_str": (C.c_char_p, [C.c_int]),
@@ -43,6 +44,8 @@ _EXPORTS = {
     "hlq_linear_backward_mode": (C.c_int, [C.c_void_p] * 5 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64, C.c_int,
                                            C.c_int] + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]),
     "hlq_int8_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
+                                   C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "hlq_int4_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                    C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hlq_gemm_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int64, C.c_int64, C.c_int64]),
     "hlq_hla_project": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p,
@@ -149,9 +152,15 @@ def hlq_compress_act(X, B, r, XhatT):
            "hlq_compress_act")
 
 
+def _codes_ptr(t):
+    if t.dtype not in (torch.int8, torch.uint8):
+        raise TypeError("codes must be int8 (or uint8 for packed codes), got %s" % t.dtype)
+    return _ptr(t)
+
+
 def hlq_quantize_g(G, B, seed, Gq, sG, coeff=None, bits=4):
     N, d_out = G.shape
-    _check(lib().hlq_quantize_g(_ptr(G), N, d_out, B, seed, _dt(G), bits, _ptr(Gq, torch.int8), _ptr(sG, torch.float32),
+    _check(lib().hlq_quantize_g(_ptr(G), N, d_out, B, seed, _dt(G), bits, _codes_ptr(Gq), _ptr(sG, torch.float32),
                                 _ptr(coeff, torch.float32), _stream()), "hlq_quantize_g")
 
 
@@ -161,7 +170,7 @@ def hlq_quantize_w_workspace_bytes(d_out, d_in) -> int:
 
 def hlq_quantize_w(W, B, seed, WqT, sW, workspace, coeffT=None, bits=4):
     d_out, d_in = W.shape
-    _check(lib().hlq_quantize_w(_ptr(W), d_out, d_in, B, seed, _dt(W), bits, _ptr(WqT, torch.int8), _ptr(sW, torch.float32),
+    _check(lib().hlq_quantize_w(_ptr(W), d_out, d_in, B, seed, _dt(W), bits, _codes_ptr(WqT), _ptr(sW, torch.float32),
                                 _ptr(coeffT, torch.float32), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream()), "hlq_quantize_w")
 
@@ -182,6 +191,17 @@ def hlq_int8_gemm_nt(A, Bm, sA, sB, alpha, C_out=None, acc=None, workspace=None)
     _check(lib().hlq_int8_gemm_nt(_ptr(A, torch.int8), _ptr(Bm, torch.int8), M, Nn, K, _ptr(sA, torch.float32),
                                   _ptr(sB, torch.float32), float(alpha), out_dt, _ptr(C_out), _ptr(acc, torch.int32),
                                   wp, wb, _stream()), "hlq_int8_gemm_nt")
+
+
+def hlq_int4_gemm_nt(A4, Bm4, sA, sB, alpha, C_out=None, acc=None, workspace=None):
+    """A4 [M, K/2], Bm4 [Nn, K/2] uint8: 4-bit codes, two to a byte."""
+    M, Kb = A4.shape
+    Nn = Bm4.shape[0]
+    out_dt = _dt(C_out) if C_out is not None else HLQ_F32
+    wp, wb = _ws(workspace)
+    _check(lib().hlq_int4_gemm_nt(_ptr(A4, torch.uint8), _ptr(Bm4, torch.uint8), M, Nn, 2 * Kb, _ptr(sA, torch.float32),
+                                  _ptr(sB, torch.float32), float(alpha), out_dt, _ptr(C_out), _ptr(acc, torch.int32),
+                                  wp, wb, _stream()), "hlq_int4_gemm_nt")
 
 
 def hlq_hla_project(T, B, r, ThatT, coeffT=None):

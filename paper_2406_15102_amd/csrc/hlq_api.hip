@@ -103,7 +103,7 @@ Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_
 
 int check_flags(int flags, int r, int64_t N, int B)
 {
-    if (flags & ~(HLQ_FLAG_GX_8BIT | HLQ_FLAG_GW_INT8)) return HLQ_ERR_SHAPE;
+    if (flags & ~(HLQ_FLAG_GX_8BIT | HLQ_FLAG_GW_INT8 | HLQ_FLAG_GX_UNPACKED)) return HLQ_ERR_SHAPE;
     if (flags & HLQ_FLAG_GW_INT8) {
         if (r % 4 != 0) return HLQ_ERR_RANK;
         if ((N / B * r) % 16 != 0) return HLQ_ERR_SHAPE;
@@ -111,8 +111,9 @@ int check_flags(int flags, int r, int64_t N, int B)
     return HLQ_OK;
 }
 
-inline bool bits_ok(int bits) { return bits == 4 || bits == 8; }
-inline float bits_qmax(int bits) { return bits == 8 ? 127.0f : 7.0f; }
+inline bool bits_ok(int bits) { return bits == HLQ_BITS_4 || bits == HLQ_BITS_8 || bits == HLQ_BITS_4_PACKED; }
+inline float bits_qmax(int bits) { return bits == HLQ_BITS_8 ? 127.0f : 7.0f; }
+inline bool bits_packed(int bits) { return bits == HLQ_BITS_4_PACKED; }
 
 // Library-owned workspace, one per device, grown on demand.
 constexpr int kMaxDevices = 64;
@@ -189,11 +190,13 @@ int hlq_quantize_g(const void *G, int64_t N, int64_t d_out, int B, uint64_t seed
     if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
     if (!bits_ok(bits)) return HLQ_ERR_DTYPE;
     if ((rc = check_quant_shape(N, d_out, B)) != HLQ_OK) return rc;
+    if (bits_packed(bits) && d_out % 32 != 0) return HLQ_ERR_SHAPE;   // 16-byte rows of packed codes
     if (!aligned(G, 16) || !aligned(Gq, 8) || (coeff && !aligned(coeff, 16))) return HLQ_ERR_SHAPE;
     const uint64_t key = stream_key(seed, 0);
     return launch_rc(hlq::launch_quant_rows(G, N, static_cast<int>(d_out), B, dtype == HLQ_F32,
                                             static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32),
-                                            bits_qmax(bits), Gq, sG, coeff, static_cast<hipStream_t>(stream)));
+                                            bits_qmax(bits), bits_packed(bits), Gq, sG, coeff,
+                                            static_cast<hipStream_t>(stream)));
 }
 
 size_t hlq_quantize_w_workspace_bytes(int64_t d_out, int64_t d_in)
@@ -212,18 +215,19 @@ int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t s
     if (!bits_ok(bits)) return HLQ_ERR_DTYPE;
     if (d_in <= 0 || d_in % 8 != 0) return HLQ_ERR_SHAPE;
     if ((rc = check_quant_shape(d_in, d_out, B)) != HLQ_OK) return rc;
+    if (bits_packed(bits) && d_out % 32 != 0) return HLQ_ERR_SHAPE;
     if (!aligned(W, 16) || !aligned(WqT, 16) || (coeffT && !aligned(coeffT, 16))) return HLQ_ERR_SHAPE;
     if (!aligned(workspace, 256) || workspace_bytes < hlq::quant_cols_ws_bytes(d_out, d_in)) return HLQ_ERR_WORKSPACE;
     const uint64_t key = stream_key(seed, 1);
     return launch_rc(hlq::launch_quant_cols(W, static_cast<int>(d_out), static_cast<int>(d_in), B, dtype == HLQ_F32,
                                             static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32),
-                                            bits_qmax(bits), WqT, sW, coeffT, workspace,
+                                            bits_qmax(bits), bits_packed(bits), WqT, sW, coeffT, workspace,
                                             static_cast<hipStream_t>(stream)));
 }
 
 size_t hlq_gemm_workspace_bytes(int kind, int64_t M, int64_t Nn, int64_t K)
 {
-    if ((kind != 0 && kind != 1) || check_gemm_shape(M, Nn, K, kind == 0 ? 16 : 8) != HLQ_OK) return 0;
+    if (kind < 0 || kind > 2 || check_gemm_shape(M, Nn, K, kind == 0 ? 16 : (kind == 1 ? 8 : 32)) != HLQ_OK) return 0;
     return hlq::gemm_ws_bytes(kind, static_cast<int>(M), static_cast<int>(Nn), static_cast<int>(K));
 }
 
@@ -242,6 +246,24 @@ int hlq_int8_gemm_nt(const int8_t *A, const int8_t *Bm, int64_t M, int64_t Nn, i
     hlq::GemmArgs a{A, Bm, static_cast<int>(M), static_cast<int>(Nn), static_cast<int>(K), sA, sB, alpha, C,
                     out_dtype == HLQ_F32, acc, workspace, workspace_bytes};
     return launch_rc(hlq::launch_gemm_nt(0, a, static_cast<hipStream_t>(stream)));
+}
+
+int hlq_int4_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64_t K, const float *sA,
+                     const float *sB, float alpha, int out_dtype, void *C, int32_t *acc, void *workspace,
+                     size_t workspace_bytes, void *stream)
+{
+    int rc;
+    if (!A || !Bm || (!C && !acc)) return HLQ_ERR_NULL;
+    if ((rc = check_dtype(out_dtype)) != HLQ_OK) return rc;
+    if ((rc = check_gemm_shape(M, Nn, K, 32)) != HLQ_OK) return rc;
+    if (K > 131072) return HLQ_ERR_SHAPE;   // 256 * 49 * K must fit the int32 accumulators
+    if (!aligned(A, 16) || !aligned(Bm, 16) || (C && !aligned(C, 16)) || (acc && !aligned(acc, 16)) ||
+        (sB && !aligned(sB, 16)))
+        return HLQ_ERR_SHAPE;
+    if (workspace && !aligned(workspace, 16)) return HLQ_ERR_WORKSPACE;
+    hlq::GemmArgs a{A, Bm, static_cast<int>(M), static_cast<int>(Nn), static_cast<int>(K), sA, sB, alpha, C,
+                    out_dtype == HLQ_F32, acc, workspace, workspace_bytes};
+    return launch_rc(hlq::launch_gemm_nt(2, a, static_cast<hipStream_t>(stream)));
 }
 
 int hlq_hla_project(const void *T, int64_t N, int64_t D, int B, int r, int dtype, void *ThatT, float *coeffT,
@@ -323,6 +345,8 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
     if ((rc = check_flags(flags, r, N, B)) != HLQ_OK) return rc;
     const bool gwi = (flags & HLQ_FLAG_GW_INT8) != 0;
     const float qmax = (flags & HLQ_FLAG_GX_8BIT) ? 127.0f : 7.0f;
+    // 4-bit codes travel two to a byte whenever their rows stay 16-byte aligned that way
+    const bool packed = !(flags & (HLQ_FLAG_GX_8BIT | HLQ_FLAG_GX_UNPACKED)) && d_out % 32 == 0;
     if (!G || (!dX && !dW)) return HLQ_ERR_NULL;
     if (dX && !W) return HLQ_ERR_NULL;
     if (dW && ((X == nullptr) == (Xc == nullptr))) return HLQ_ERR_NULL;   // exactly one of the two
@@ -363,7 +387,7 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
         // g_x stages 1-2: Q(G H)
         const uint64_t kg = stream_key(seed, 0);
         if ((rc = launch_rc(hlq::launch_quant_rows(G, N, O, B, f32, static_cast<uint32_t>(kg),
-                                                   static_cast<uint32_t>(kg >> 32), qmax, Gq, sG, nullptr, st))) != HLQ_OK)
+                                                   static_cast<uint32_t>(kg >> 32), qmax, packed, Gq, sG, nullptr, st))) != HLQ_OK)
             return rc;
     }
     if (dW && !gwi) {
@@ -397,12 +421,12 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
         // g_x stages 3-4: Q(H^T W), transposed
         const uint64_t kw = stream_key(seed, 1);
         if ((rc = launch_rc(hlq::launch_quant_cols(W, O, I, B, f32, static_cast<uint32_t>(kw),
-                                                   static_cast<uint32_t>(kw >> 32), qmax, Wq, sW, nullptr, ws + L.wws,
-                                                   st))) != HLQ_OK)
+                                                   static_cast<uint32_t>(kw >> 32), qmax, packed, Wq, sW, nullptr,
+                                                   ws + L.wws, st))) != HLQ_OK)
             return rc;
         // g_x stages 5-6: integer product and dequantisation (1/B undoes H H^T = B I)
         hlq::GemmArgs a{Gq, Wq, static_cast<int>(N), I, O, sG, sW, invB, dX, f32, nullptr, ws + L.gws, L.gws_bytes};
-        if ((rc = launch_rc(hlq::launch_gemm_nt(0, a, st))) != HLQ_OK) return rc;
+        if ((rc = launch_rc(hlq::launch_gemm_nt(packed ? 2 : 0, a, st))) != HLQ_OK) return rc;
     }
     if (dW) {
         // g_w stage 5 (and 6): product over the compressed token axis

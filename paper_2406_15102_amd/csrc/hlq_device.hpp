@@ -170,6 +170,16 @@ __device__ __forceinline__ uint32_t quant_pack4(float x0, float x1, float x2, fl
     return lo | hi;
 }
 
+// Eight 4-bit codes from two dwords of int8 codes (as quant_pack4 makes them), two to a byte:
+// code 2b in the low nibble of byte b, code 2b+1 in the high nibble, two's complement.
+__device__ __forceinline__ uint32_t nibble_pack8(uint32_t lo, uint32_t hi)
+{
+    // bytes (c0, c1, c2, c3) -> bits 0..7 = c0 | c1 << 4, bits 16..23 = c2 | c3 << 4
+    const uint32_t a = ((lo >> 4) & 0x00F000F0u) | (lo & 0x000F000Fu);
+    const uint32_t b = ((hi >> 4) & 0x00F000F0u) | (hi & 0x000F000Fu);
+    return __builtin_amdgcn_perm(b, a, 0x06040200u);   // bytes 0, 2 of a, then bytes 0, 2 of b
+}
+
 // qmax = 7 for 4-bit codes, 127 for 8-bit codes (int8 warm-up phase, integer g_w path).
 __device__ __forceinline__ float absmax_to_inv(float a, float qmax) { return a > 0.0f ? qmax / a : 0.0f; }
 __device__ __forceinline__ float absmax_to_scale(float a, float qmax) { return a / qmax; }

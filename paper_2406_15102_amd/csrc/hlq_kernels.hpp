@@ -7,15 +7,16 @@
 
 namespace hlq {
 
-// K1: rows of G -> 4-bit codes + per-row scales (and optionally the fp32 coefficients).
+// K1: rows of G -> codes + per-row scales (and optionally the fp32 coefficients).  `packed`
+// (4-bit codes only): two codes to a byte, O/2 bytes per row, instead of one int8 each.
 hipError_t launch_quant_rows(const void *G, int64_t N, int O, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                             float qmax, int8_t *Gq, float *sG, float *coeff, hipStream_t st);
+                             float qmax, bool packed, int8_t *Gq, float *sG, float *coeff, hipStream_t st);
 
 // K1T: W [O, I] -> WqT [I, O] codes + per-in-feature scales.  `ws` holds the partial column
 // maxima and the reciprocal scales: quant_cols_ws_bytes(O, I) bytes.
 size_t quant_cols_ws_bytes(int64_t O, int64_t I);
 hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                             float qmax, int8_t *WqT, float *sW, float *coeffT, void *ws, hipStream_t st);
+                             float qmax, bool packed, int8_t *WqT, float *sW, float *coeffT, void *ws, hipStream_t st);
 
 // K3: token-axis Hadamard low-rank projection, T [N, D] -> ThatT [D, N/B*r] bf16.
 hipError_t launch_hla(const void *T, int64_t N, int D, int B, int r, bool is_f32, uint16_t *ThatT,
@@ -44,6 +45,7 @@ struct GemmArgs {
     size_t ws_bytes;
 };
 hipError_t launch_gemm_nt(int kind, const GemmArgs &a, hipStream_t st);
+hipError_t launch_splitk_reduce(int kind, const GemmArgs &a, int splits, hipStream_t st);
 // Scratch that lets launch_gemm_nt split k whenever that is the faster plan for this shape
 // (few output tiles, long reduction); 0 if the plan does not split.
 size_t gemm_ws_bytes(int kind, int M, int N, int K);

@@ -23,212 +23,9 @@
 // wavefront's sub-tile in LDS and writes C in full 16-byte, row-contiguous pieces.
 // Workgroup ids are remapped so that each XCD (ids congruent mod 8) works on a compact patch of
 // tiles and re-uses operand rows in its own L2.
-#include "hlq_device.hpp"
-#include "hlq_kernels.hpp"
+#include "gemm_common.hpp"
 
 namespace hlq {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // one 16-B chunk (first-class vector: stays in registers)
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-
-template <int KIND> struct Mma;
-template <> struct Mma<0> {
-    typedef v16i acc_t;
-    static __device__ __forceinline__ acc_t zero() { acc_t z = {0}; return z; }
-    static __device__ __forceinline__ acc_t mma(const u32x4 &x, const u32x4 &y, acc_t c)
-    {
-        return __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(v4i, x), __builtin_bit_cast(v4i, y), c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ float to_float(int v) { return static_cast<float>(v); }
-};
-template <> struct Mma<1> {
-    typedef v16f acc_t;
-    static __device__ __forceinline__ acc_t zero() { acc_t z = {0.0f}; return z; }
-    static __device__ __forceinline__ acc_t mma(const u32x4 &x, const u32x4 &y, acc_t c)
-    {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, x), __builtin_bit_cast(v8bf, y), c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ float to_float(float v) { return v; }
-};
-
-struct GemmDev {
-    const char *A;
-    const char *Bm;
-    int M, N;
-    int Kb;            // bytes per operand row
-    const float *sA;
-    const float *sB;
-    float alpha;
-    void *C;
-    int c_is_f32;
-    int32_t *acc;
-    int tiles_m, tiles_n;
-    int splits;        // split-K: this many workgroups share a tile, each a contiguous range of k steps
-    int32_t *partial;  // [splits][M][N] raw 32-bit accumulators (OUT == 3)
-};
-
-// position of 16-byte chunk c of LDS row `row` (KCH chunks per row)
-template <int KCH>
-__device__ __forceinline__ int lds_chunk(int row, int c)
-{
-    if (KCH == 8) return row * 8 + (c ^ ((row & 7) ^ ((row >> 3) & 1)));
-    return row * 4 + (c ^ ((((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1)));
-}
-
-// Workgroup barrier that waits for this wavefront's LDS traffic only (global loads stay in flight).
-__device__ __forceinline__ void lds_barrier()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// Orders this wavefront's own LDS writes before its later LDS reads (and the reverse).
-__device__ __forceinline__ void lds_wave_fence()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront", "local");
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront", "local");
-}
-
-// ---- epilogue helpers ------------------------------------------------------------------------
-// After the MFMAs a lane holds, per accumulator (i, j) and register group vg, C[m][n .. n+3] with
-// m = 32 i + (lane & 31), n = 32 j + 8 vg + 4 (lane >> 5) inside the wavefront's sub-tile.
-// One wavefront per SIMD means every instruction of the epilogue is exposed, so it is kept short:
-// two multiplies per value, no predicates on interior tiles.
-
-template <int WN> struct EpiSlab {
-    static constexpr int COLS = 32 * WN;
-    static constexpr int PITCH_F32 = COLS * 4 + 16;   // +16 B: consecutive rows start on different banks
-    static constexpr int PITCH_BF16 = COLS * 2 + 16;
-    static constexpr int BYTES = 32 * PITCH_F32;      // one 32-row slab per wavefront
-};
-
-__device__ __forceinline__ int raw_bits(int v) { return v; }
-__device__ __forceinline__ int raw_bits(float v) { return __builtin_bit_cast(int, v); }
-
-// raw 32-bit accumulators (int32, or fp32 bit patterns): the parity export and the split-K
-// partial results; direct 16-byte stores
-template <int KIND, int WM, int WN, bool GUARD>
-__device__ __forceinline__ void store_raw(typename Mma<KIND>::acc_t (&acc)[WM][WN], int32_t *out, int M, int N,
-                                          int wm0, int wn0, int lane)
-{
-    struct { int32_t *acc; int M, N; } g = {out, M, N};
-    const int fr = lane & 31, fh = lane >> 5;
-#pragma unroll
-    for (int i = 0; i < WM; ++i) {
-        const int m = wm0 + i * 32 + fr;
-        int32_t *row = g.acc + static_cast<int64_t>(m) * g.N + wn0 + fh * 4;
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-#pragma unroll
-            for (int vg = 0; vg < 4; ++vg) {
-                const int nl = j * 32 + vg * 8;
-                if (!GUARD || (m < g.M && wn0 + nl + fh * 4 < g.N)) {
-                    v4i raw = {raw_bits(acc[i][j][vg * 4 + 0]), raw_bits(acc[i][j][vg * 4 + 1]),
-                               raw_bits(acc[i][j][vg * 4 + 2]), raw_bits(acc[i][j][vg * 4 + 3])};
-                    *reinterpret_cast<v4i *>(row + nl) = raw;
-                }
-            }
-    }
-}
-
-// C = alpha * sA[m] * sB[n] * acc, staged per 32-row slab through LDS so that global stores are
-// 16-byte, row-contiguous pieces (a full 256-byte row segment per 16 or 8 lanes).
-template <int KIND, int WM, int WN, bool F32, bool GUARD>
-__device__ __forceinline__ void store_scaled(typename Mma<KIND>::acc_t (&acc)[WM][WN], void *Cout, int M, int N,
-                                             const float *sA, const float *sB, float alpha, int wm0, int wn0,
-                                             int lane, char *slab)
-{
-    struct { void *C; int M, N; const float *sA, *sB; float alpha; } g = {Cout, M, N, sA, sB, alpha};
-    constexpr int COLS = EpiSlab<WN>::COLS;
-    constexpr int PITCH = F32 ? EpiSlab<WN>::PITCH_F32 : EpiSlab<WN>::PITCH_BF16;
-    constexpr int EPL = F32 ? 4 : 8;              // elements per 16-byte piece
-    constexpr int LPR = COLS / EPL;               // lanes per row
-    constexpr int RPI = 64 / LPR;                 // rows per store instruction
-    const int fr = lane & 31, fh = lane >> 5;
-
-    // column factors alpha * sB[n] for the 16 WN columns this lane owns (columns past the edge
-    // read sB[0..3]: their products are never stored)
-    f32x4 cs[WN][4];
-    if (KIND == 1) {
-        // unused
-    } else if (g.sB) {
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-#pragma unroll
-            for (int vg = 0; vg < 4; ++vg) {
-                int n = wn0 + j * 32 + vg * 8 + fh * 4;
-                if (GUARD) n = n < g.N ? n : 0;
-                cs[j][vg] = *reinterpret_cast<const f32x4 *>(g.sB + n) * g.alpha;
-            }
-    } else {
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-#pragma unroll
-            for (int vg = 0; vg < 4; ++vg) cs[j][vg] = f32x4{g.alpha, g.alpha, g.alpha, g.alpha};
-    }
-    float sa[WM];
-#pragma unroll
-    for (int i = 0; i < WM; ++i) {
-        int m = wm0 + i * 32 + fr;
-        if (GUARD) m = m < g.M ? m : 0;
-        sa[i] = g.sA ? g.sA[m] : 1.0f;
-    }
-
-    const int rr0 = lane / LPR, cc = (lane % LPR) * EPL;
-    char *wr = slab + fr * PITCH + fh * 4 * (F32 ? 4 : 2);
-    const char *rd = slab + rr0 * PITCH + cc * (F32 ? 4 : 2);
-#pragma unroll
-    for (int i = 0; i < WM; ++i) {
-#pragma unroll
-        for (int j = 0; j < WN; ++j)
-#pragma unroll
-            for (int vg = 0; vg < 4; ++vg) {
-                f32x4 o;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (KIND == 1) o[e] = Mma<KIND>::to_float(acc[i][j][vg * 4 + e]) * g.alpha;   // no scales on the bf16 product
-                    else o[e] = Mma<KIND>::to_float(acc[i][j][vg * 4 + e]) * (sa[i] * cs[j][vg][e]);
-                }
-                if (F32) {
-                    *reinterpret_cast<f32x4 *>(wr + (j * 32 + vg * 8) * 4) = o;
-                } else {
-                    u32x2 p = {pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
-                    *reinterpret_cast<u32x2 *>(wr + (j * 32 + vg * 8) * 2) = p;
-                }
-            }
-        lds_wave_fence();
-        u32x4 v[32 / RPI];
-#pragma unroll
-        for (int p = 0; p < 32 / RPI; ++p) v[p] = *reinterpret_cast<const u32x4 *>(rd + p * RPI * PITCH);
-        const int mbase = wm0 + i * 32 + rr0;
-        char *dst = static_cast<char *>(g.C) + (static_cast<int64_t>(mbase) * g.N + wn0 + cc) * (F32 ? 4 : 2);
-        const int64_t step = static_cast<int64_t>(RPI) * g.N * (F32 ? 4 : 2);
-#pragma unroll
-        for (int p = 0; p < 32 / RPI; ++p) {
-            if (!GUARD) {
-                *reinterpret_cast<u32x4 *>(dst + p * step) = v[p];
-            } else {
-                const int m = mbase + p * RPI, n = wn0 + cc;
-                if (m < g.M) {
-                    if (F32 || (g.N & 7) == 0) {
-                        if (n < g.N) *reinterpret_cast<u32x4 *>(dst + p * step) = v[p];
-                    } else {   // bf16 rows that are only 8-byte aligned: two halves, the last may be missing
-                        const u32x2 lo = {v[p][0], v[p][1]}, hi = {v[p][2], v[p][3]};
-                        if (n < g.N) *reinterpret_cast<u32x2 *>(dst + p * step) = lo;
-                        if (n + 4 < g.N) *reinterpret_cast<u32x2 *>(dst + p * step + 8) = hi;
-                    }
-                }
-            }
-        }
-        lds_wave_fence();
-    }
-}
 
 // OUT: 0 = C in bf16, 1 = C in fp32, 2 = raw int32 accumulators (parity export),
 //      3 = raw 32-bit partial accumulators of this workgroup's k range (split-K)
@@ -390,6 +187,13 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
     HLQ_LOAD_GLOBAL_B(nk > 1 ? 1 : 0)
     lds_barrier();
     HLQ_READ_FRAGS(0, 0)
+    u32x4 ea[2][WM][2], pb[2];    // packed codes: expanded A operands and first B operand of the coming sub-step
+    if constexpr (KIND == 2) {
+#pragma unroll
+        for (int i = 0; i < WM; ++i) Mma<2>::expand(fa[0][i], ea[0][i][0], ea[0][i][1]);
+        Mma<2>::expand(fb[0][0], pb[0], pb[1]);
+    }
+    constexpr int MPS = KIND == 2 ? 2 : 1;   // MFMAs per accumulator and sub-step
 
     static_assert(NS == 4, "the staging schedule below is written for four sub-steps per step");
 
@@ -401,13 +205,46 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
             if (ks < NS - 1) {
                 HLQ_READ_FRAGS(cur ^ 1, ks + 1)
             } else {
-                HLQ_TOGGLE_STAGE()          // from here on this wavefront reads the next step's stage
+                if (KIND != 2) HLQ_TOGGLE_STAGE()   // from here on this wavefront reads the next step's stage
                 HLQ_READ_FRAGS(cur ^ 1, 0)
             }
+            if constexpr (KIND == 2) {
+                // packed codes: every fragment expands to two MFMA operands.  The A operands of this
+                // sub-step and its first B operand were expanded under the previous sub-step's MFMAs
+                // (ea[cur], pb); the other B operands are expanded here, one ahead of their use, and
+                // so are the next sub-step's A operands: no MFMA waits for a burst of vector work.
+                u32x4 eb[2][2];
+                eb[0][0] = pb[0];
+                eb[0][1] = pb[1];
 #pragma unroll
-            for (int i = 0; i < WM; ++i)
+                for (int j = 0; j < WN; ++j) {
+                    if (j + 1 < WN) Mma<2>::expand(fb[cur][j + 1], eb[(j + 1) & 1][0], eb[(j + 1) & 1][1]);
 #pragma unroll
-                for (int j = 0; j < WN; ++j) acc[i][j] = Mma<KIND>::mma(fb[cur][j], fa[cur][i], acc[i][j]);
+                    for (int i = 0; i < WM; ++i) acc[i][j] = Mma<2>::mma(eb[j & 1][0], ea[cur][i][0], acc[i][j]);
+#pragma unroll
+                    for (int i = 0; i < WM; ++i) acc[i][j] = Mma<2>::mma(eb[j & 1][1], ea[cur][i][1], acc[i][j]);
+                }
+#pragma unroll
+                for (int i = 0; i < WM; ++i) Mma<2>::expand(fa[cur ^ 1][i], ea[cur ^ 1][i][0], ea[cur ^ 1][i][1]);
+                Mma<2>::expand(fb[cur ^ 1][0], pb[0], pb[1]);
+                if (ks == NS - 1) {
+                    // loop-carried: keep the compiler from moving these expansions to the top of the
+                    // next iteration (it would carry the packed registers over instead), where they
+                    // would stand in front of the first MFMA
+#pragma unroll
+                    for (int i = 0; i < WM; ++i) {
+                        asm("" : "+v"(ea[cur ^ 1][i][0]));
+                        asm("" : "+v"(ea[cur ^ 1][i][1]));
+                    }
+                    asm("" : "+v"(pb[0]));
+                    asm("" : "+v"(pb[1]));
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int j = 0; j < WN; ++j) acc[i][j] = Mma<KIND>::mma(fb[cur][j], fa[cur][i], acc[i][j]);
+            }
             if (ks == 0) {
                 HLQ_STORE_LDS_A()
                 HLQ_LOAD_GLOBAL_A(kt2)
@@ -422,19 +259,24 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
             // anything waits on it (the next sub-step's first MFMA, the barrier, the loop's back
             // edge).  LDS writes may not pass the reads (same array): a staging sub-step threads its
             // LDS writes + global loads between the second half of the MFMAs.
+            constexpr int VPS = KIND == 2 ? 12 * (WM + WN) / ((WM * WN) / 1) : 0;   // expansion instructions per slot
 #pragma unroll
             for (int q = 0; q < (WM * WN) / 2; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                           // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x008, MPS, 0);                         // MFMA(s)
                 __builtin_amdgcn_sched_group_barrier(0x100, 2 * (WM + WN) / (WM * WN), 0);   // fragment reads
+                if (VPS) __builtin_amdgcn_sched_group_barrier(0x002, VPS, 0);                // expansions
             }
 #pragma unroll
             for (int q = 0; q < (WM * WN) / 2; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, MPS, 0);
+                if (VPS) __builtin_amdgcn_sched_group_barrier(0x002, VPS, 0);
                 if (ks < 2) {
                     __builtin_amdgcn_sched_group_barrier(0x200, 2 * PA / (WM * WN), 0);      // LDS writes
                     __builtin_amdgcn_sched_group_barrier(0x020, 2 * PA / (WM * WN), 0);      // global loads
                 }
             }
+            // packed codes: the address toggle is moved out of the last sub-step, which is busy enough
+            if (KIND == 2 && ks == NS - 2) HLQ_TOGGLE_STAGE()
             __builtin_amdgcn_sched_barrier(0);
             if (ks == NS - 2) {              // after this sub-step's last MFMA has been issued
                 lds_barrier();
@@ -506,14 +348,19 @@ __global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t *__restrict
 // measurements on MI355X: a 256-tile step (128 B of k) costs ~1.6 us and a tile ~12 us of fixed
 // prologue/epilogue, one workgroup per compute unit; a 128-tile step ~0.5 us alone on its compute
 // unit and ~0.95 us when two share it, ~6 us fixed; the split-K partials cost their HBM round trip plus a launch.
+// bytes per operand row: int8 codes, bf16 values, nibble-packed codes
+static inline int row_bytes(int kind, int K) { return kind == 0 ? K : (kind == 1 ? 2 * K : K / 2); }
+
+constexpr double P4_STEP_SCALE = 1.8;   // measured: see the plan comment
 struct GemmPlan {
     bool big;
     int splits;
 };
 
-static GemmPlan plan_gemm(int M, int N, int Kb, size_t ws_bytes, bool allow_split)
+// `nk` = k steps of the product (128 B of k per operand row);
+// `scale` = cost of such a step relative to the byte-operand kernels.
+static GemmPlan plan_gemm(int M, int N, int nk, double scale, size_t ws_bytes, bool allow_split)
 {
-    const int nk = (Kb + 127) / 128;
     const double mn = static_cast<double>(M) * N;
     GemmPlan best{true, 1};
     double best_t = 1e30;
@@ -523,7 +370,7 @@ static GemmPlan plan_gemm(int M, int N, int Kb, size_t ws_bytes, bool allow_spli
         const double slots = big ? 256.0 : 512.0, fixed = big ? 12.0 : 6.0;
         for (int S = 1; S <= 16; ++S) {
             // two co-resident 128-tile workgroups share a compute unit's LDS and power: slower steps
-            const double step = big ? 1.6 : (tiles * S > 256.0 ? 0.95 : 0.5);
+            const double step = scale * (big ? 1.6 : (tiles * S > 256.0 ? 0.95 : 0.5));
             if (S > 1 && (!allow_split || S > nk || static_cast<double>(S) * mn * 4.0 > static_cast<double>(ws_bytes))) break;
             const double rounds = __builtin_ceil(tiles * S / slots);
             double t = rounds * (__builtin_ceil(static_cast<double>(nk) / S) * step + fixed);
@@ -534,11 +381,33 @@ static GemmPlan plan_gemm(int M, int N, int Kb, size_t ws_bytes, bool allow_spli
     return best;
 }
 
+static GemmPlan plan_for(int kind, int M, int N, int K, size_t ws_bytes, bool allow_split)
+{
+    // a step of the packed product carries twice the MFMAs of a byte-operand step
+    return plan_gemm(M, N, (row_bytes(kind, K) + 127) / 128, kind == 2 ? P4_STEP_SCALE : 1.0, ws_bytes, allow_split);
+}
+
 size_t gemm_ws_bytes(int kind, int M, int N, int K)
 {
-    const int Kb = kind == 0 ? K : 2 * K;
-    const GemmPlan p = plan_gemm(M, N, Kb, ~static_cast<size_t>(0), true);
+    const GemmPlan p = plan_for(kind, M, N, K, ~static_cast<size_t>(0), true);
     return p.splits > 1 ? static_cast<size_t>(p.splits) * M * N * 4 : 0;
+}
+
+// kind 0: int32 partials (the two integer products), kind 1: fp32 partials
+hipError_t launch_splitk_reduce(int kind, const GemmArgs &a, int splits, hipStream_t st)
+{
+    const int64_t quads = (static_cast<int64_t>(a.M) * a.N + 3) / 4;
+    const unsigned grid = static_cast<unsigned>((quads + 255) / 256);
+    const int32_t *part = static_cast<const int32_t *>(a.ws);
+#define HLQ_REDUCE(KIND, F32) \
+    hipLaunchKernelGGL((k_splitk_reduce<KIND, F32>), dim3(grid), dim3(256), 0, st, part, splits, a.M, a.N, a.sA, a.sB, a.alpha, a.C)
+    if (kind == 0) {
+        if (a.c_is_f32) HLQ_REDUCE(0, true); else HLQ_REDUCE(0, false);
+    } else {
+        if (a.c_is_f32) HLQ_REDUCE(1, true); else HLQ_REDUCE(1, false);
+    }
+#undef HLQ_REDUCE
+    return hipGetLastError();
 }
 
 template <int KIND, int WM, int WN, int KCH, bool TAIL, int OUT>
@@ -549,7 +418,7 @@ static hipError_t launch_tt(const GemmArgs &a, int splits, hipStream_t st)
     g.Bm = static_cast<const char *>(a.Bm);
     g.M = a.M;
     g.N = a.N;
-    g.Kb = KIND == 0 ? a.K : 2 * a.K;
+    g.Kb = row_bytes(KIND, a.K);
     g.sA = a.sA;
     g.sB = a.sB;
     g.alpha = a.alpha;
@@ -577,7 +446,7 @@ static hipError_t launch_tt(const GemmArgs &a, int splits, hipStream_t st)
 template <int KIND, int WM, int WN, int KCH, int OUT>
 static hipError_t launch_o(const GemmArgs &a, int splits, hipStream_t st)
 {
-    const int Kb = KIND == 0 ? a.K : 2 * a.K;
+    const int Kb = row_bytes(KIND, a.K);
     return (Kb % (KCH * 16) == 0) ? launch_tt<KIND, WM, WN, KCH, false, OUT>(a, splits, st)
                                   : launch_tt<KIND, WM, WN, KCH, true, OUT>(a, splits, st);
 }
@@ -586,31 +455,24 @@ template <int KIND, int WM, int WN, int KCH>
 static hipError_t launch_t(const GemmArgs &a, int splits, hipStream_t st)
 {
     // the raw accumulators and the scaled output are separate launches of the same product
-    if (KIND == 0 && a.acc) {
-        hipError_t e = launch_o<0, WM, WN, KCH, 2>(a, 1, st);
+    if (KIND != 1 && a.acc) {
+        hipError_t e = launch_o<KIND, WM, WN, KCH, 2>(a, 1, st);
         if (e != hipSuccess || !a.C) return e;
     }
     if (splits > 1) {
         hipError_t e = launch_o<KIND, WM, WN, KCH, 3>(a, splits, st);
         if (e != hipSuccess) return e;
-        const int64_t quads = (static_cast<int64_t>(a.M) * a.N + 3) / 4;
-        const unsigned grid = static_cast<unsigned>((quads + 255) / 256);
-        const int32_t *part = static_cast<const int32_t *>(a.ws);
-        if (a.c_is_f32)
-            hipLaunchKernelGGL((k_splitk_reduce<KIND, true>), dim3(grid), dim3(256), 0, st, part, splits, a.M, a.N, a.sA, a.sB, a.alpha, a.C);
-        else
-            hipLaunchKernelGGL((k_splitk_reduce<KIND, false>), dim3(grid), dim3(256), 0, st, part, splits, a.M, a.N, a.sA, a.sB, a.alpha, a.C);
-        return hipGetLastError();
+        return launch_splitk_reduce(KIND == 1 ? 1 : 0, a, splits, st);
     }
     return a.c_is_f32 ? launch_o<KIND, WM, WN, KCH, 1>(a, 1, st) : launch_o<KIND, WM, WN, KCH, 0>(a, 1, st);
 }
 
 hipError_t launch_gemm_nt(int kind, const GemmArgs &a, hipStream_t st)
 {
-    const int Kb = kind == 0 ? a.K : 2 * a.K;
     const bool can_split = a.ws != nullptr && a.C != nullptr && (reinterpret_cast<uintptr_t>(a.ws) & 15) == 0;
-    const GemmPlan p = plan_gemm(a.M, a.N, Kb, a.ws_bytes, can_split);
+    const GemmPlan p = plan_for(kind, a.M, a.N, a.K, a.ws_bytes, can_split);
     if (kind == 0) return p.big ? launch_t<0, 4, 4, 8>(a, p.splits, st) : launch_t<0, 2, 2, 8>(a, p.splits, st);
+    if (kind == 2) return p.big ? launch_t<2, 4, 4, 8>(a, p.splits, st) : launch_t<2, 2, 2, 8>(a, p.splits, st);
     return p.big ? launch_t<1, 4, 4, 8>(a, p.splits, st) : launch_t<1, 2, 2, 8>(a, p.splits, st);
 }
 

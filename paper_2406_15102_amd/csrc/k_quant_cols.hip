@@ -66,7 +66,8 @@ __global__ __launch_bounds__(256) void k_cols_absmax(const Tin *__restrict__ W, 
     }
 }
 
-template <typename Tin, int B>
+// PACKED: the codes are written two to a byte (4-bit codes only), O/2 bytes per row of WqT.
+template <typename Tin, int B, bool PACKED>
 __global__ __launch_bounds__(256) void k_cols_quantize(const Tin *__restrict__ W, int O, int I,
                                                        const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
                                                        float qmax, int8_t *__restrict__ WqT, float *__restrict__ sW,
@@ -103,7 +104,11 @@ __global__ __launch_bounds__(256) void k_cols_quantize(const Tin *__restrict__ W
                 out[d] = quant_pack4(v[(j + 0) * CPL + c], v[(j + 1) * CPL + c], v[(j + 2) * CPL + c],
                                      v[(j + 3) * CPL + c], inv[c], w);
             }
-            *reinterpret_cast<uint4 *>(WqT + orow + d4 * 16) = make_uint4(out[0], out[1], out[2], out[3]);
+            if (PACKED)
+                *reinterpret_cast<uint2 *>(WqT + orow / 2 + d4 * 8) =
+                    make_uint2(nibble_pack8(out[0], out[1]), nibble_pack8(out[2], out[3]));
+            else
+                *reinterpret_cast<uint4 *>(WqT + orow + d4 * 16) = make_uint4(out[0], out[1], out[2], out[3]);
         }
         if (coeffT) {
 #pragma unroll
@@ -121,8 +126,8 @@ size_t quant_cols_ws_bytes(int64_t /*O*/, int64_t I)
 }
 
 template <typename Tin, int B>
-static hipError_t launch_cols_t(const void *W, int O, int I, uint32_t k0, uint32_t k1, float qmax, int8_t *WqT, float *sW,
-                                float *coeffT, void *ws, hipStream_t st)
+static hipError_t launch_cols_t(const void *W, int O, int I, uint32_t k0, uint32_t k1, float qmax, bool packed, int8_t *WqT,
+                                float *sW, float *coeffT, void *ws, hipStream_t st)
 {
     constexpr int CPL = 128 / B;
     uint32_t *amax = static_cast<uint32_t *>(ws);
@@ -130,17 +135,20 @@ static hipError_t launch_cols_t(const void *W, int O, int I, uint32_t k0, uint32
     dim3 grid((I + 64 * CPL - 1) / (64 * CPL), (O + 4 * B - 1) / (4 * B));
     hipLaunchKernelGGL(k_fill_u32, dim3((I + 255) / 256), dim3(256), 0, st, amax, I, 0u);
     hipLaunchKernelGGL((k_cols_absmax<Tin, B>), grid, dim3(256), 0, st, w, O, I, amax);
-    hipLaunchKernelGGL((k_cols_quantize<Tin, B>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, coeffT);
+    if (packed)
+        hipLaunchKernelGGL((k_cols_quantize<Tin, B, true>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, coeffT);
+    else
+        hipLaunchKernelGGL((k_cols_quantize<Tin, B, false>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, coeffT);
     return hipGetLastError();
 }
 
 hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                             float qmax, int8_t *WqT, float *sW, float *coeffT, void *ws, hipStream_t st)
+                             float qmax, bool packed, int8_t *WqT, float *sW, float *coeffT, void *ws, hipStream_t st)
 {
 #define HLQ_COLS_CASE(BB)                                                                            \
     case BB:                                                                                         \
-        return is_f32 ? launch_cols_t<float, BB>(W, O, I, k0, k1, qmax, WqT, sW, coeffT, ws, st)           \
-                      : launch_cols_t<bf16_t, BB>(W, O, I, k0, k1, qmax, WqT, sW, coeffT, ws, st);
+        return is_f32 ? launch_cols_t<float, BB>(W, O, I, k0, k1, qmax, packed, WqT, sW, coeffT, ws, st)           \
+                      : launch_cols_t<bf16_t, BB>(W, O, I, k0, k1, qmax, packed, WqT, sW, coeffT, ws, st);
     switch (B) {
         HLQ_COLS_CASE(16)
         HLQ_COLS_CASE(32)

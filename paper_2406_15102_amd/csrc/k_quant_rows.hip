@@ -15,7 +15,8 @@ namespace hlq {
 
 constexpr int K1_MAXC = 8;  // chunks of 8 elements per lane
 
-template <typename Tin, int B, int BLOCK>
+// PACKED: the codes are written two to a byte (4-bit codes only), O/2 bytes per row.
+template <typename Tin, int B, int BLOCK, bool PACKED>
 __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tin *__restrict__ G, int64_t N, int O, int T,
                                                       uint32_t k0, uint32_t k1, float qmax, int8_t *__restrict__ Gq,
                                                       float *__restrict__ sG, float *__restrict__ coeff)
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tin *__restrict__ G,
     if (g == 0) sG[row] = absmax_to_scale(amax, qmax);
 
     const uint32_t cbase = static_cast<uint32_t>(row) * static_cast<uint32_t>(O >> 2);
-    int8_t *qrow = Gq + row * static_cast<int64_t>(O);
+    int8_t *qrow = Gq + row * static_cast<int64_t>(PACKED ? O / 2 : O);
 #pragma unroll
     for (int m = 0; m < K1_MAXC; ++m) {
         const int ci = g + m * T;
@@ -90,7 +91,8 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tin *__restrict__ G,
             uint2 out;
             out.x = quant_pack4(v[m][0], v[m][1], v[m][2], v[m][3], inv, w0);
             out.y = quant_pack4(v[m][4], v[m][5], v[m][6], v[m][7], inv, w1);
-            *reinterpret_cast<uint2 *>(qrow + static_cast<int64_t>(ci) * 8) = out;
+            if (PACKED) *reinterpret_cast<uint32_t *>(qrow + static_cast<int64_t>(ci) * 4) = nibble_pack8(out.x, out.y);
+            else *reinterpret_cast<uint2 *>(qrow + static_cast<int64_t>(ci) * 8) = out;
             if (coeff) {
                 float4 *c = reinterpret_cast<float4 *>(coeff + row * static_cast<int64_t>(O) + static_cast<int64_t>(ci) * 8);
                 c[0] = make_float4(sign * v[m][0], sign * v[m][1], sign * v[m][2], sign * v[m][3]);
@@ -100,7 +102,7 @@ __global__ __launch_bounds__(BLOCK) void k_quant_rows(const Tin *__restrict__ G,
     }
 }
 
-template <typename Tin, int B>
+template <typename Tin, int B, bool PACKED>
 static hipError_t launch_rows_t(const void *G, int64_t N, int O, uint32_t k0, uint32_t k1, float qmax, int8_t *Gq,
                                 float *sG, float *coeff, hipStream_t st)
 {
@@ -113,22 +115,25 @@ static hipError_t launch_rows_t(const void *G, int64_t N, int O, uint32_t k0, ui
         while (T < 64 && nch / T > 4) T *= 2;
         const int rows_per_block = 256 / T;
         const unsigned grid = static_cast<unsigned>((N + rows_per_block - 1) / rows_per_block);
-        hipLaunchKernelGGL((k_quant_rows<Tin, B, 256>), dim3(grid), dim3(256), 0, st, g, N, O, T, k0, k1, qmax, Gq, sG, coeff);
+        hipLaunchKernelGGL((k_quant_rows<Tin, B, 256, PACKED>), dim3(grid), dim3(256), 0, st, g, N, O, T, k0, k1, qmax, Gq, sG, coeff);
     } else if (nch <= K1_MAXC * 256) {
-        hipLaunchKernelGGL((k_quant_rows<Tin, B, 256>), dim3(static_cast<unsigned>(N)), dim3(256), 0, st, g, N, O, 256, k0, k1, qmax, Gq, sG, coeff);
+        hipLaunchKernelGGL((k_quant_rows<Tin, B, 256, PACKED>), dim3(static_cast<unsigned>(N)), dim3(256), 0, st, g, N, O, 256, k0, k1, qmax, Gq, sG, coeff);
     } else {
-        hipLaunchKernelGGL((k_quant_rows<Tin, B, 1024>), dim3(static_cast<unsigned>(N)), dim3(1024), 0, st, g, N, O, 1024, k0, k1, qmax, Gq, sG, coeff);
+        hipLaunchKernelGGL((k_quant_rows<Tin, B, 1024, PACKED>), dim3(static_cast<unsigned>(N)), dim3(1024), 0, st, g, N, O, 1024, k0, k1, qmax, Gq, sG, coeff);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_quant_rows(const void *G, int64_t N, int O, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                             float qmax, int8_t *Gq, float *sG, float *coeff, hipStream_t st)
+                             float qmax, bool packed, int8_t *Gq, float *sG, float *coeff, hipStream_t st)
 {
-#define HLQ_ROWS_CASE(BB)                                                                           \
-    case BB:                                                                                        \
-        return is_f32 ? launch_rows_t<float, BB>(G, N, O, k0, k1, qmax, Gq, sG, coeff, st)                \
-                      : launch_rows_t<bf16_t, BB>(G, N, O, k0, k1, qmax, Gq, sG, coeff, st);
+#define HLQ_ROWS_CASE(BB)                                                                                  \
+    case BB:                                                                                               \
+        if (packed)                                                                                        \
+            return is_f32 ? launch_rows_t<float, BB, true>(G, N, O, k0, k1, qmax, Gq, sG, coeff, st)       \
+                          : launch_rows_t<bf16_t, BB, true>(G, N, O, k0, k1, qmax, Gq, sG, coeff, st);     \
+        return is_f32 ? launch_rows_t<float, BB, false>(G, N, O, k0, k1, qmax, Gq, sG, coeff, st)          \
+                      : launch_rows_t<bf16_t, BB, false>(G, N, O, k0, k1, qmax, Gq, sG, coeff, st);
     switch (B) {
         HLQ_ROWS_CASE(16)
         HLQ_ROWS_CASE(32)
