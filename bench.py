@@ -116,27 +116,33 @@ def main():
 
     # ---- the same path with the weight codes taken as cached (W quantised once per optimiser step) ----
     # ---- and kernel by kernel through the stage entry points, HIP events on the launch stream ----------
-    Gq = torch.empty((N, O), dtype=torch.int8, device=dev)
+    packed = O % 32 == 0          # the whole path stores the 4-bit codes two to a byte then
+    cb = O // 2 if packed else O
+    qbits = hlq.HLQ_BITS_4_PACKED if packed else hlq.HLQ_BITS_4
+    Gq = torch.empty((N, cb), dtype=torch.uint8 if packed else torch.int8, device=dev)
     sG = torch.empty(N, dtype=torch.float32, device=dev)
-    WqT = torch.empty((I, O), dtype=torch.int8, device=dev)
+    WqT = torch.empty((I, cb), dtype=torch.uint8 if packed else torch.int8, device=dev)
     sW = torch.empty(I, dtype=torch.float32, device=dev)
     wws = torch.empty(hlq.hlq_quantize_w_workspace_bytes(O, I), dtype=torch.uint8, device=dev)
     GhT = torch.empty((O, Kc), dtype=torch.bfloat16, device=dev)
     XhT = torch.empty((I, Kc), dtype=torch.bfloat16, device=dev)
-    gws = torch.empty(max(16, hlq.hlq_gemm_workspace_bytes(0, N, I, O), hlq.hlq_gemm_workspace_bytes(1, O, I, Kc)),
+    gws = torch.empty(max(16, hlq.hlq_gemm_workspace_bytes(2 if packed else 0, N, I, O),
+                          hlq.hlq_gemm_workspace_bytes(1, O, I, Kc)),
                       dtype=torch.uint8, device=dev)   # split-K scratch, as the whole path has it
     stages = {   # in the launch order of the whole path
-        "quantize_g": lambda: hlq.hlq_quantize_g(G, B, w.seed, Gq, sG),
+        "quantize_g": lambda: hlq.hlq_quantize_g(G, B, w.seed, Gq, sG, None, qbits),
         "hla_g": lambda: hlq.hlq_hla_project(G, B, r, GhT),
         "hla_x": lambda: hlq.hlq_hla_project(X, B, r, XhT),
-        "quantize_w": lambda: hlq.hlq_quantize_w(W, B, w.seed, WqT, sW, wws),
-        "int8_gemm": lambda: hlq.hlq_int8_gemm_nt(Gq, WqT, sG, sW, 1.0 / B, dX, None, gws),
+        "quantize_w": lambda: hlq.hlq_quantize_w(W, B, w.seed, WqT, sW, wws, None, qbits),
+        "int8_gemm": lambda: (hlq.hlq_int4_gemm_nt if packed else hlq.hlq_int8_gemm_nt)(
+            Gq, WqT, sG, sW, 1.0 / B, dX, None, gws),
         "bf16_gemm": lambda: hlq.hlq_bf16_gemm_nt(GhT, XhT, 1.0 / B, dW, gws),
     }
     e = 2 if w.dtype == "bf16" else 4
+    cbytes = 0.5 if packed else 1.0          # bytes per stored code
     work = {  # algorithmic bytes / ops per launch
-        "quantize_g": ("hbm", N * O * (e + 1) + 4 * N),
-        "quantize_w": ("hbm", O * I * (e + 1) + 4 * I),
+        "quantize_g": ("hbm", N * O * (e + cbytes) + 4 * N),
+        "quantize_w": ("hbm", O * I * (e + cbytes) + 4 * I),
         "int8_gemm": ("mfma_i8", 2.0 * N * I * O),
         "hla_g": ("hbm", N * O * e + 2 * Kc * O),
         "hla_x": ("hbm", N * I * e + 2 * Kc * I),
@@ -227,9 +233,10 @@ def main():
         "metric": "hlq_backward_dX_dW_latency", "value": round(hlq_us, 2), "unit": "us", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(hlq_us / 1e3, 5),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "i8 (dX product, 4-bit codes) + bf16 (dW product), fp32 transforms", "data": "synthetic",
+        "dtype": "i8 MFMA (dX product, 4-bit codes) + bf16 (dW product), fp32 transforms", "data": "synthetic",
         "config": {"workload": "%s: %s" % (w.name, w.desc), "N": N, "d_in": I, "d_out": O, "B": B, "r": r,
-                   "io_dtype": w.dtype, "includes": "W quantisation counted every step"},
+                   "io_dtype": w.dtype, "includes": "W quantisation counted every step",
+                   "code_storage": "4-bit, two per byte" if packed else "int8"},
         "wall_us_per_step": round(wall_us, 2),
         "dense_bf16_backward_us": round(dense_us, 2),
         "speedup_vs_dense_bf16": round(dense_us / hlq_us, 3),

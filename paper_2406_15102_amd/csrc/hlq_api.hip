@@ -383,14 +383,28 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
     float *sGh = reinterpret_cast<float *>(ws + L.sGhat);
     const void *Xh = Xc;
     const float *sXh = sXc;
-    if (dX) {
+    // The transforms that depend on nothing share two launches when the shapes allow (k_front.hip);
+    // the integer g_w list and very long rows of G keep one launch per stage.
+    const bool fused = !gwi && hlq::front_fusable(O, B);
+    const uint64_t kg = stream_key(seed, 0);
+    if (fused) {
+        uint16_t *xh = xc ? nullptr : reinterpret_cast<uint16_t *>(ws + L.XhatT);
+        const hlq::FrontRows jr = hlq::front_rows(dX ? G : nullptr, N, O, B, static_cast<uint32_t>(kg),
+                                                  static_cast<uint32_t>(kg >> 32), qmax, Gq, sG);
+        const hlq::FrontHla jx = hlq::front_hla(dW && !xc ? X : nullptr, N, I, B, r, xh);
+        const hlq::FrontFill jf{reinterpret_cast<uint32_t *>(ws + L.wws), dX ? I : 0};
+        const hlq::FrontHla jg = hlq::front_hla(dW ? G : nullptr, N, O, B, r, static_cast<uint16_t *>(Gh));
+        const hlq::FrontAbsmax jw = hlq::front_absmax(dX ? W : nullptr, O, I, B, reinterpret_cast<uint32_t *>(ws + L.wws));
+        if ((rc = launch_rc(hlq::launch_front(jr, jx, jf, jg, jw, B, f32, packed, st))) != HLQ_OK) return rc;
+        if (dW && !xc) Xh = xh;
+    }
+    if (dX && !fused) {
         // g_x stages 1-2: Q(G H)
-        const uint64_t kg = stream_key(seed, 0);
         if ((rc = launch_rc(hlq::launch_quant_rows(G, N, O, B, f32, static_cast<uint32_t>(kg),
                                                    static_cast<uint32_t>(kg >> 32), qmax, packed, Gq, sG, nullptr, st))) != HLQ_OK)
             return rc;
     }
-    if (dW && !gwi) {
+    if (dW && !gwi && !fused) {
         // g_w stages 3 and 1 kept in bf16: HLA of G and (unless it was compressed at forward time) of X
         if ((rc = launch_rc(hlq::launch_hla(G, N, O, B, r, f32, static_cast<uint16_t *>(Gh), nullptr, st))) != HLQ_OK) return rc;
         if (!xc) {
@@ -420,10 +434,15 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
     if (dX) {
         // g_x stages 3-4: Q(H^T W), transposed
         const uint64_t kw = stream_key(seed, 1);
-        if ((rc = launch_rc(hlq::launch_quant_cols(W, O, I, B, f32, static_cast<uint32_t>(kw),
-                                                   static_cast<uint32_t>(kw >> 32), qmax, packed, Wq, sW, nullptr,
-                                                   ws + L.wws, st))) != HLQ_OK)
-            return rc;
+        if (fused)   // pass 1 ran in the second front launch
+            rc = launch_rc(hlq::launch_quant_cols_pass2(W, O, I, B, f32, static_cast<uint32_t>(kw),
+                                                        static_cast<uint32_t>(kw >> 32), qmax, packed, Wq, sW,
+                                                        ws + L.wws, st));
+        else
+            rc = launch_rc(hlq::launch_quant_cols(W, O, I, B, f32, static_cast<uint32_t>(kw),
+                                                  static_cast<uint32_t>(kw >> 32), qmax, packed, Wq, sW, nullptr,
+                                                  ws + L.wws, st));
+        if (rc != HLQ_OK) return rc;
         // g_x stages 5-6: integer product and dequantisation (1/B undoes H H^T = B I)
         hlq::GemmArgs a{Gq, Wq, static_cast<int>(N), I, O, sG, sW, invB, dX, f32, nullptr, ws + L.gws, L.gws_bytes};
         if ((rc = launch_rc(hlq::launch_gemm_nt(packed ? 2 : 0, a, st))) != HLQ_OK) return rc;

@@ -18,6 +18,47 @@ size_t quant_cols_ws_bytes(int64_t O, int64_t I);
 hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
                              float qmax, bool packed, int8_t *WqT, float *sW, float *coeffT, void *ws, hipStream_t st);
 
+// K1T split in its two passes, for callers that run pass 1 elsewhere (the fused front launches):
+// pass 2 alone, reading the column maxima pass 1 left in `ws`.
+hipError_t launch_quant_cols_pass2(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
+                                   float qmax, bool packed, int8_t *WqT, float *sW, const void *ws, hipStream_t st);
+
+// The independent transforms of one backward pass in two launches (k_front.hip).  A job with a
+// null tensor is empty.
+struct FrontRows {   // K1 on G, 256-thread variant
+    const void *G;
+    int64_t N;
+    int O, T;
+    uint32_t k0, k1;
+    float qmax;
+    int8_t *Gq;
+    float *sG;
+    int blocks;
+};
+struct FrontHla {    // K3 on one tensor
+    const void *T;
+    int64_t N;
+    int D, r;
+    uint16_t *out;
+    int gx, gy;
+};
+struct FrontFill {   // n words at p := 0
+    uint32_t *p;
+    int n;
+};
+struct FrontAbsmax { // pass 1 of K1T
+    const void *W;
+    int O, I;
+    uint32_t *amax;
+    int gx, gy;
+};
+bool front_fusable(int O, int B);
+FrontRows front_rows(const void *G, int64_t N, int O, int B, uint32_t k0, uint32_t k1, float qmax, int8_t *Gq, float *sG);
+FrontHla front_hla(const void *T, int64_t N, int D, int B, int r, uint16_t *out);
+FrontAbsmax front_absmax(const void *W, int O, int I, int B, uint32_t *amax);
+hipError_t launch_front(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
+                        const FrontAbsmax &jw, int B, bool is_f32, bool packed, hipStream_t st);
+
 // K3: token-axis Hadamard low-rank projection, T [N, D] -> ThatT [D, N/B*r] bf16.
 hipError_t launch_hla(const void *T, int64_t N, int D, int B, int r, bool is_f32, uint16_t *ThatT,
                       float *coeffT, hipStream_t st);

@@ -1,0 +1,115 @@
+// The transforms of one backward pass, launched together.  Stages 1-2 of the g_x list (K1 on G),
+// stages 1 and 3 of the g_w list (K3 on X and on G) and the first pass of stages 3-4 of the g_x
+// list (column maxima of H^T W) do not depend on one another (arXiv 2406.15102, Sec. 6.1), and each
+// costs a few tens of microseconds, of which four to five are the fixed price of a launch that
+// waits for its predecessor to drain.  Two launches carry them instead of six:
+//   front A   K1(G)  |  K3(X)  |  zeroing of the column maxima
+//   front B   K3(G)  |  column maxima of H^T W      (needs the zeroing; G is re-read while the
+//                                                    last-level cache still holds it)
+// A workgroup looks up its job from its index (jobs occupy consecutive index ranges, a job may be
+// empty) and runs the same device body as the stand-alone kernel of that stage.
+#include "hla_body.hpp"
+#include "hlq_kernels.hpp"
+#include "quant_cols_body.hpp"
+#include "quant_rows_body.hpp"
+
+namespace hlq {
+
+template <typename Tin, int B, bool PACKED>
+__global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, FrontFill jf)
+{
+    int b = blockIdx.x;
+    if (b < jr.blocks) {
+        quant_rows_body<Tin, B, 256, PACKED>(static_cast<const Tin *>(jr.G), jr.N, jr.O, jr.T, jr.k0, jr.k1, jr.qmax, jr.Gq,
+                                             jr.sG, nullptr, b);
+        return;
+    }
+    b -= jr.blocks;
+    if (b < jx.gx * jx.gy) {
+        hla_body<Tin, B>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, b % jx.gx, b / jx.gx);
+        return;
+    }
+    b -= jx.gx * jx.gy;
+    const int i = b * 256 + threadIdx.x;
+    if (i < jf.n) jf.p[i] = 0u;
+}
+
+template <typename Tin, int B>
+__global__ __launch_bounds__(256) void k_front_b(FrontHla jg, FrontAbsmax jw)
+{
+    int b = blockIdx.x;
+    if (b < jg.gx * jg.gy) {
+        hla_body<Tin, B>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.out, nullptr, b % jg.gx, b / jg.gx);
+        return;
+    }
+    b -= jg.gx * jg.gy;
+    cols_absmax_body<Tin, B>(static_cast<const Tin *>(jw.W), jw.O, jw.I, jw.amax, b % jw.gx, b / jw.gx);
+}
+
+bool front_fusable(int O, int B)
+{
+    const int T = quant_rows_lanes(O, B);
+    return T > 0;   // rows that need the 1024-thread K1 keep their own launch
+}
+
+FrontRows front_rows(const void *G, int64_t N, int O, int B, uint32_t k0, uint32_t k1, float qmax, int8_t *Gq, float *sG)
+{
+    FrontRows j{G, N, O, 0, k0, k1, qmax, Gq, sG, 0};
+    if (!G) return j;
+    j.T = quant_rows_lanes(O, B);
+    const int rows_per_block = 256 / j.T;     // T == 256: one row per workgroup
+    j.blocks = static_cast<int>((N + rows_per_block - 1) / rows_per_block);
+    return j;
+}
+
+FrontHla front_hla(const void *T, int64_t N, int D, int B, int r, uint16_t *out)
+{
+    FrontHla j{T, N, D, r, out, 0, 0};
+    if (!T) return j;
+    const int cpl = 128 / B;
+    j.gx = (D + 64 * cpl - 1) / (64 * cpl);
+    j.gy = static_cast<int>((N / B + 3) / 4);
+    return j;
+}
+
+FrontAbsmax front_absmax(const void *W, int O, int I, int B, uint32_t *amax)
+{
+    FrontAbsmax j{W, O, I, amax, 0, 0};
+    if (!W) return j;
+    const int cpl = 128 / B;
+    j.gx = (I + 64 * cpl - 1) / (64 * cpl);
+    j.gy = (O + 4 * B - 1) / (4 * B);
+    return j;
+}
+
+template <typename Tin, int B>
+static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
+                                 const FrontAbsmax &jw, bool packed, hipStream_t st)
+{
+    const int na = jr.blocks + jx.gx * jx.gy + (jf.n + 255) / 256;
+    if (na > 0) {
+        if (packed) hipLaunchKernelGGL((k_front_a<Tin, B, true>), dim3(na), dim3(256), 0, st, jr, jx, jf);
+        else hipLaunchKernelGGL((k_front_a<Tin, B, false>), dim3(na), dim3(256), 0, st, jr, jx, jf);
+    }
+    const int nb = jg.gx * jg.gy + jw.gx * jw.gy;
+    if (nb > 0) hipLaunchKernelGGL((k_front_b<Tin, B>), dim3(nb), dim3(256), 0, st, jg, jw);
+    return hipGetLastError();
+}
+
+hipError_t launch_front(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
+                        const FrontAbsmax &jw, int B, bool is_f32, bool packed, hipStream_t st)
+{
+#define HLQ_FRONT_CASE(BB)                                                                   \
+    case BB:                                                                                 \
+        return is_f32 ? launch_front_t<float, BB>(jr, jx, jf, jg, jw, packed, st)            \
+                      : launch_front_t<bf16_t, BB>(jr, jx, jf, jg, jw, packed, st);
+    switch (B) {
+        HLQ_FRONT_CASE(16)
+        HLQ_FRONT_CASE(32)
+        HLQ_FRONT_CASE(64)
+    }
+#undef HLQ_FRONT_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace hlq

@@ -11,7 +11,7 @@
 // wavefront is one (B tokens) x (64*CPL features) unit of work, a workgroup four consecutive
 // token blocks (their outputs are adjacent: 4*r contiguous values per feature).
 // T is read once (2 B/element), r/B of it is written back as bf16.
-#include "hlq_device.hpp"
+#include "hla_body.hpp"
 #include "hlq_kernels.hpp"
 
 namespace hlq {
@@ -20,50 +20,7 @@ template <typename Tin, int B>
 __global__ __launch_bounds__(256) void k_hla(const Tin *__restrict__ T, int64_t N, int D, int r,
                                              bf16_t *__restrict__ ThatT, float *__restrict__ coeffT)
 {
-    constexpr int CPL = 128 / B;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int col0 = (blockIdx.x * 64 + lane) * CPL;
-    const int64_t nblk = N / B;
-    const int64_t Kc = nblk * r;
-    const int64_t blk = static_cast<int64_t>(blockIdx.y) * 4 + wave;
-    if (col0 >= D || blk >= nblk) return;
-
-    float v[B * CPL];
-#pragma unroll
-    for (int j = 0; j < B; ++j)
-        Loader<Tin, CPL>::load(T + (blk * B + j) * static_cast<int64_t>(D) + col0, v + j * CPL);
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-        fwht_regs<B, CPL>(v + c);
-        const int64_t o = static_cast<int64_t>(col0 + c) * Kc + blk * r;
-        if (r >= 8) {
-#pragma unroll
-            for (int k = 0; k < B; k += 8) {
-                if (k < r) {
-                    uint4 p;
-                    p.x = pack_bf16(v[(k + 0) * CPL + c], v[(k + 1) * CPL + c]);
-                    p.y = pack_bf16(v[(k + 2) * CPL + c], v[(k + 3) * CPL + c]);
-                    p.z = pack_bf16(v[(k + 4) * CPL + c], v[(k + 5) * CPL + c]);
-                    p.w = pack_bf16(v[(k + 6) * CPL + c], v[(k + 7) * CPL + c]);
-                    *reinterpret_cast<uint4 *>(ThatT + o + k) = p;
-                }
-            }
-        } else if (r == 4) {
-            uint2 p;
-            p.x = pack_bf16(v[0 * CPL + c], v[1 * CPL + c]);
-            p.y = pack_bf16(v[2 * CPL + c], v[3 * CPL + c]);
-            *reinterpret_cast<uint2 *>(ThatT + o) = p;
-        } else if (r == 2) {
-            *reinterpret_cast<uint32_t *>(ThatT + o) = pack_bf16(v[0 * CPL + c], v[1 * CPL + c]);
-        } else {
-            ThatT[o] = static_cast<bf16_t>(pack_bf16(v[c], 0.0f) & 0xFFFFu);
-        }
-        if (coeffT) {
-#pragma unroll
-            for (int k = 0; k < B; ++k)
-                if (k < r) coeffT[o + k] = v[k * CPL + c];
-        }
-    }
+    hla_body<Tin, B>(T, N, D, r, ThatT, coeffT, blockIdx.x, blockIdx.y);
 }
 
 template <typename Tin, int B>

@@ -15,17 +15,10 @@
 //           whose bit patterns order like unsigned integers: the result is deterministic.
 //   pass 2  transform again, quantise, write B codes per column and wavefront (contiguous in
 //           d_out; the four wavefronts of a workgroup complete 4*B contiguous bytes per column).
-#include "hlq_device.hpp"
+#include "quant_cols_body.hpp"
 #include "hlq_kernels.hpp"
 
 namespace hlq {
-
-template <typename Tin, int B, int CPL>
-__device__ __forceinline__ void load_row_block(const Tin *base, int64_t pitch, float *v)
-{
-#pragma unroll
-    for (int j = 0; j < B; ++j) Loader<Tin, CPL>::load(base + j * pitch, v + j * CPL);
-}
 
 __global__ __launch_bounds__(256) void k_fill_u32(uint32_t *p, int n, uint32_t value)
 {
@@ -37,33 +30,7 @@ template <typename Tin, int B>
 __global__ __launch_bounds__(256) void k_cols_absmax(const Tin *__restrict__ W, int O, int I,
                                                      uint32_t *__restrict__ amax_bits)
 {
-    constexpr int CPL = 128 / B;
-    __shared__ float s_max[4][64 * CPL];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int col0 = (blockIdx.x * 64 + lane) * CPL;
-    const int o0 = (blockIdx.y * 4 + wave) * B;
-    float cmax[CPL];
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) cmax[c] = 0.0f;
-
-    if (col0 < I && o0 < O) {
-        float v[B * CPL];
-        load_row_block<Tin, B, CPL>(W + static_cast<int64_t>(o0) * I + col0, I, v);
-#pragma unroll
-        for (int c = 0; c < CPL; ++c) {
-            fwht_regs<B, CPL>(v + c);
-#pragma unroll
-            for (int j = 0; j < B; ++j) cmax[c] = fmaxf(cmax[c], fabsf(v[j * CPL + c]));
-        }
-    }
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) s_max[wave][lane * CPL + c] = cmax[c];
-    __syncthreads();
-    for (int idx = tid; idx < 64 * CPL; idx += 256) {
-        const float m = fmaxf(fmaxf(s_max[0][idx], s_max[1][idx]), fmaxf(s_max[2][idx], s_max[3][idx]));
-        const int col = blockIdx.x * 64 * CPL + idx;
-        if (col < I && m > 0.0f) atomicMax(amax_bits + col, __float_as_uint(m));
-    }
+    cols_absmax_body<Tin, B>(W, O, I, amax_bits, blockIdx.x, blockIdx.y);
 }
 
 // PACKED: the codes are written two to a byte (4-bit codes only), O/2 bytes per row of WqT.
@@ -140,6 +107,37 @@ static hipError_t launch_cols_t(const void *W, int O, int I, uint32_t k0, uint32
     else
         hipLaunchKernelGGL((k_cols_quantize<Tin, B, false>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, coeffT);
     return hipGetLastError();
+}
+
+template <typename Tin, int B>
+static hipError_t launch_cols_pass2_t(const void *W, int O, int I, uint32_t k0, uint32_t k1, float qmax, bool packed,
+                                      int8_t *WqT, float *sW, const void *ws, hipStream_t st)
+{
+    constexpr int CPL = 128 / B;
+    const uint32_t *amax = static_cast<const uint32_t *>(ws);
+    const Tin *w = static_cast<const Tin *>(W);
+    dim3 grid((I + 64 * CPL - 1) / (64 * CPL), (O + 4 * B - 1) / (4 * B));
+    if (packed)
+        hipLaunchKernelGGL((k_cols_quantize<Tin, B, true>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, nullptr);
+    else
+        hipLaunchKernelGGL((k_cols_quantize<Tin, B, false>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, nullptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_quant_cols_pass2(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
+                                   float qmax, bool packed, int8_t *WqT, float *sW, const void *ws, hipStream_t st)
+{
+#define HLQ_COLS2_CASE(BB)                                                                                   \
+    case BB:                                                                                                 \
+        return is_f32 ? launch_cols_pass2_t<float, BB>(W, O, I, k0, k1, qmax, packed, WqT, sW, ws, st)       \
+                      : launch_cols_pass2_t<bf16_t, BB>(W, O, I, k0, k1, qmax, packed, WqT, sW, ws, st);
+    switch (B) {
+        HLQ_COLS2_CASE(16)
+        HLQ_COLS2_CASE(32)
+        HLQ_COLS2_CASE(64)
+    }
+#undef HLQ_COLS2_CASE
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
