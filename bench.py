@@ -191,6 +191,13 @@ def main():
         for _ in range(3):
             fn()
         modes[label] = {"us": round(_event_time_us(fn, max(10, args.steps // 2), torch), 2)}
+    # ---- the default path with the weight codes handed over (quantised once per optimiser step) ----
+    assert hlq.hlq_weight_code_bits(O, 0) == qbits
+    hlq.hlq_quantize_w(W, B, w.seed, WqT, sW, wws, None, qbits)
+    cached = lambda: hlq.hlq_linear_backward_cached(G, X, None, None, WqT, sW, N, I, O, B, r, w.seed, 0, dX, dW, ws)
+    for _ in range(3):
+        cached()
+    cached_us = _event_time_us(cached, max(10, args.steps // 2), torch)
     step()   # leave dX / dW as the default path computes them
 
     # ---- dense bf16 backward on the same GPU (comparator, not part of the library) ----
@@ -242,6 +249,7 @@ def main():
         "speedup_vs_dense_bf16": round(dense_us / hlq_us, 3),
         "kernels": kernels,
         "modes_us": modes,
+        "cached_weight_codes_us": round(cached_us, 2),
         "copy_256MiB": {"us": round(copy_us, 2), "GB/s": round(2 * (1 << 28) / copy_us / 1e3, 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,

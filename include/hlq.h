@@ -233,6 +233,21 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
                              void *stream);
 
 /*
+ * The same with the weight operand quantised beforehand: the weight changes once per optimiser
+ * step, its codes can serve every micro-batch in between (same seed => the codes the path itself
+ * would compute, so the results are those of hlq_linear_backward_mode bit for bit).
+ *   WqT, sW   as written by hlq_quantize_w(W, ..., seed, ..., bits = hlq_weight_code_bits(d_out, flags)):
+ *             that helper returns the HLQ_BITS_* value (storage included) this path expects for
+ *             the given flags.  Ignored (may be NULL) when dX is NULL.
+ *   Other arguments, workspace and errors as for hlq_linear_backward_mode.
+ */
+int hlq_weight_code_bits(int64_t d_out, int flags);
+int hlq_linear_backward_cached(const void *G, const void *X, const void *Xc, const float *sXc, const void *WqT,
+                               const float *sW, int64_t N, int64_t d_in, int64_t d_out, int B, int r,
+                               uint64_t seed, int dtype, int flags, void *dX, void *dW, void *workspace,
+                               size_t workspace_bytes, void *stream);
+
+/*
  * Diagnostic, not part of the backward pass: `blocks` workgroups of four wavefronts each issue
  * iters * 8 independent 32x32 MFMAs from registers (kind 0: int8, K = 32, 65536 ops each;
  * kind 1: bf16, K = 16, 32768 flops each).  Timing it gives the MFMA rate the chip sustains at

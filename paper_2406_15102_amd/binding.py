@@ -43,6 +43,9 @@ _EXPORTS = {
     "hlq_workspace_bytes_mode": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int]),
     "hlq_linear_backward_mode": (C.c_int, [C.c_void_p] * 5 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64, C.c_int,
                                            C.c_int] + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]),
+    "hlq_weight_code_bits": (C.c_int, [C.c_int64, C.c_int]),
+    "hlq_linear_backward_cached": (C.c_int, [C.c_void_p] * 6 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64, C.c_int,
+                                             C.c_int] + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]),
     "hlq_int8_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
                                    C.c_float, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hlq_int4_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_void_p,
@@ -254,3 +257,16 @@ def hlq_linear_backward_mode(G, X, Xc, sXc, W, N, d_in, d_out, B, r, seed, flags
     _check(lib().hlq_linear_backward_mode(_ptr(G), _ptr(X), _ptr(Xc), _ptr(sXc, torch.float32), _ptr(W), N, d_in,
                                           d_out, B, r, seed, _dt(G), flags, _ptr(dX), _ptr(dW), ws_ptr, ws_bytes,
                                           _stream()), "hlq_linear_backward_mode")
+
+
+def hlq_weight_code_bits(d_out, flags) -> int:
+    return int(lib().hlq_weight_code_bits(d_out, flags))
+
+
+def hlq_linear_backward_cached(G, X, Xc, sXc, WqT, sW, N, d_in, d_out, B, r, seed, flags, dX, dW, workspace=None):
+    """hlq_linear_backward_mode with the weight codes of hlq_quantize_w handed over."""
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (_ptr(workspace), _nbytes(workspace))
+    _check(lib().hlq_linear_backward_cached(_ptr(G), _ptr(X), _ptr(Xc), _ptr(sXc, torch.float32), _ptr(WqT),
+                                            _ptr(sW, torch.float32), N, d_in, d_out, B, r, seed, _dt(G), flags,
+                                            _ptr(dX), _ptr(dW), ws_ptr, ws_bytes, _stream()),
+           "hlq_linear_backward_cached")

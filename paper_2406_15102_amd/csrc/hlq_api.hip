@@ -335,9 +335,11 @@ int hlq_compress_act_int8(const void *X, int64_t N, int64_t d_in, int B, int r, 
     return hlq_hla_quantize(X, N, d_in, B, r, seed, 2, dtype, XqT, sX, nullptr, workspace, workspace_bytes, stream);
 }
 
-int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const float *sXc, const void *W, int64_t N,
-                             int64_t d_in, int64_t d_out, int B, int r, uint64_t seed, int dtype, int flags, void *dX,
-                             void *dW, void *workspace, size_t workspace_bytes, void *stream)
+// The whole path.  Either W (quantised here, every call) or its codes and scales as hlq_quantize_w
+// left them (Wc, sWc): the weight changes once per optimiser step, not once per micro-batch.
+static int backward_impl(const void *G, const void *X, const void *Xc, const float *sXc, const void *W, const void *Wc,
+                         const float *sWc, int64_t N, int64_t d_in, int64_t d_out, int B, int r, uint64_t seed, int dtype,
+                         int flags, void *dX, void *dW, void *workspace, size_t workspace_bytes, void *stream)
 {
     int rc;
     if ((rc = check_backward_shape(N, d_in, d_out, B, r)) != HLQ_OK) return rc;
@@ -348,7 +350,8 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
     // 4-bit codes travel two to a byte whenever their rows stay 16-byte aligned that way
     const bool packed = !(flags & (HLQ_FLAG_GX_8BIT | HLQ_FLAG_GX_UNPACKED)) && d_out % 32 == 0;
     if (!G || (!dX && !dW)) return HLQ_ERR_NULL;
-    if (dX && !W) return HLQ_ERR_NULL;
+    if (dX && !W && !(Wc && sWc)) return HLQ_ERR_NULL;
+    if (Wc && (!aligned(Wc, 16) || !aligned(sWc, 16))) return HLQ_ERR_SHAPE;
     if (dW && ((X == nullptr) == (Xc == nullptr))) return HLQ_ERR_NULL;   // exactly one of the two
     if (dW && Xc && (gwi != (sXc != nullptr))) return HLQ_ERR_NULL;       // int8 codes come with their scales
     if (!aligned(G, 16) || (X && !aligned(X, 16)) || (Xc && !aligned(Xc, 16)) || (sXc && !aligned(sXc, 16)) ||
@@ -377,8 +380,9 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
     // last-level cache), then X, then the two passes over W back to back, then the two products.
     int8_t *Gq = reinterpret_cast<int8_t *>(ws + L.Gq);
     float *sG = reinterpret_cast<float *>(ws + L.sG);
-    int8_t *Wq = reinterpret_cast<int8_t *>(ws + L.Wq);
-    float *sW = reinterpret_cast<float *>(ws + L.sW);
+    const bool wc = (Wc != nullptr);
+    const int8_t *Wq = wc ? static_cast<const int8_t *>(Wc) : reinterpret_cast<const int8_t *>(ws + L.Wq);
+    const float *sW = wc ? sWc : reinterpret_cast<const float *>(ws + L.sW);
     void *Gh = ws + L.GhatT;
     float *sGh = reinterpret_cast<float *>(ws + L.sGhat);
     const void *Xh = Xc;
@@ -392,9 +396,9 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
         const hlq::FrontRows jr = hlq::front_rows(dX ? G : nullptr, N, O, B, static_cast<uint32_t>(kg),
                                                   static_cast<uint32_t>(kg >> 32), qmax, Gq, sG);
         const hlq::FrontHla jx = hlq::front_hla(dW && !xc ? X : nullptr, N, I, B, r, xh);
-        const hlq::FrontFill jf{reinterpret_cast<uint32_t *>(ws + L.wws), dX ? I : 0};
+        const hlq::FrontFill jf{reinterpret_cast<uint32_t *>(ws + L.wws), dX && !wc ? I : 0};
         const hlq::FrontHla jg = hlq::front_hla(dW ? G : nullptr, N, O, B, r, static_cast<uint16_t *>(Gh));
-        const hlq::FrontAbsmax jw = hlq::front_absmax(dX ? W : nullptr, O, I, B, reinterpret_cast<uint32_t *>(ws + L.wws));
+        const hlq::FrontAbsmax jw = hlq::front_absmax(dX && !wc ? W : nullptr, O, I, B, reinterpret_cast<uint32_t *>(ws + L.wws));
         if ((rc = launch_rc(hlq::launch_front(jr, jx, jf, jg, jw, B, f32, packed, st))) != HLQ_OK) return rc;
         if (dW && !xc) Xh = xh;
     }
@@ -434,13 +438,17 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
     if (dX) {
         // g_x stages 3-4: Q(H^T W), transposed
         const uint64_t kw = stream_key(seed, 1);
-        if (fused)   // pass 1 ran in the second front launch
+        int8_t *wq = reinterpret_cast<int8_t *>(ws + L.Wq);
+        float *sw = reinterpret_cast<float *>(ws + L.sW);
+        if (wc)      // codes handed over by the caller
+            rc = HLQ_OK;
+        else if (fused)   // pass 1 ran in the second front launch
             rc = launch_rc(hlq::launch_quant_cols_pass2(W, O, I, B, f32, static_cast<uint32_t>(kw),
-                                                        static_cast<uint32_t>(kw >> 32), qmax, packed, Wq, sW,
+                                                        static_cast<uint32_t>(kw >> 32), qmax, packed, wq, sw,
                                                         ws + L.wws, st));
         else
             rc = launch_rc(hlq::launch_quant_cols(W, O, I, B, f32, static_cast<uint32_t>(kw),
-                                                  static_cast<uint32_t>(kw >> 32), qmax, packed, Wq, sW, nullptr,
+                                                  static_cast<uint32_t>(kw >> 32), qmax, packed, wq, sw, nullptr,
                                                   ws + L.wws, st));
         if (rc != HLQ_OK) return rc;
         // g_x stages 5-6: integer product and dequantisation (1/B undoes H H^T = B I)
@@ -458,6 +466,30 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
         }
     }
     return HLQ_OK;
+}
+
+int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const float *sXc, const void *W, int64_t N,
+                             int64_t d_in, int64_t d_out, int B, int r, uint64_t seed, int dtype, int flags, void *dX,
+                             void *dW, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return backward_impl(G, X, Xc, sXc, W, nullptr, nullptr, N, d_in, d_out, B, r, seed, dtype, flags, dX, dW, workspace,
+                         workspace_bytes, stream);
+}
+
+int hlq_weight_code_bits(int64_t d_out, int flags)
+{
+    if (flags & HLQ_FLAG_GX_8BIT) return HLQ_BITS_8;
+    return (!(flags & HLQ_FLAG_GX_UNPACKED) && d_out % 32 == 0) ? HLQ_BITS_4_PACKED : HLQ_BITS_4;
+}
+
+int hlq_linear_backward_cached(const void *G, const void *X, const void *Xc, const float *sXc, const void *WqT,
+                               const float *sW, int64_t N, int64_t d_in, int64_t d_out, int B, int r, uint64_t seed,
+                               int dtype, int flags, void *dX, void *dW, void *workspace, size_t workspace_bytes,
+                               void *stream)
+{
+    if (dX && (!WqT || !sW)) return HLQ_ERR_NULL;
+    return backward_impl(G, X, Xc, sXc, nullptr, dX ? WqT : nullptr, dX ? sW : nullptr, N, d_in, d_out, B, r, seed, dtype,
+                         flags, dX, dW, workspace, workspace_bytes, stream);
 }
 
 int hlq_linear_backward_ex(const void *G, const void *X, const void *XhatT, const void *W, int64_t N, int64_t d_in,

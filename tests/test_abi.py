@@ -132,3 +132,20 @@ def test_binding_refuses_cpu_tensors():
     t = torch.zeros(16, 256, dtype=torch.bfloat16)
     with pytest.raises(ValueError):
         hlq.hlq_quantize_g(t, 16, 0, torch.zeros(16, 256, dtype=torch.int8), torch.zeros(16))
+
+
+def test_cached_weight_entry_point_without_a_gpu():
+    l = hlq.lib()
+    assert l.hlq_weight_code_bits(256, 0) == 0x104 and l.hlq_weight_code_bits(48, 0) == 4
+    assert l.hlq_weight_code_bits(256, 1) == 8 and l.hlq_weight_code_bits(256, 4) == 4
+    f = l.hlq_linear_backward_cached
+
+    def call(WqT=FAKE, sW=FAKE, dX=FAKE, dW=FAKE, **kw):
+        a = dict(N=256, d_in=256, d_out=256, B=16, r=8, flags=0)
+        a.update(kw)
+        return f(FAKE, FAKE, None, None, WqT, sW, a["N"], a["d_in"], a["d_out"], a["B"], a["r"], 0, 0, a["flags"], dX, dW,
+                 FAKE, 1 << 30, None)
+
+    assert call(WqT=None) == 1 and call(sW=None) == 1            # dX wanted: the codes and their scales are needed
+    assert call(WqT=C.c_void_p(0x10004)) == 2                    # misaligned codes
+    assert call(d_out=250) == 2 and call(B=20) == 3 and call(flags=64) == 2

@@ -129,3 +129,33 @@ def test_backward_packed_equals_unpacked(w):
         torch.cuda.synchronize()
         out.append((dX, dW))
     assert torch.equal(out[0][0], out[1][0]) and torch.equal(out[0][1], out[1][1])
+
+
+@pytest.mark.parametrize("flags", [0, hlq.HLQ_FLAG_GX_UNPACKED, hlq.HLQ_FLAG_GX_8BIT, hlq.HLQ_FLAG_GW_INT8])
+@pytest.mark.parametrize("w", SMALL[:3], ids=lambda w: "%s_N%d_O%d" % (w.name, w.N, w.d_out))
+def test_backward_with_cached_weight_codes(w, flags):
+    """Weight quantised once by its stage entry point, then handed to the path: same bits as the
+    path that quantises it itself (same seed, same codes)."""
+    t = wl.generate(w)
+    G, X, W = dev(t["G"]), dev(t["X"]), dev(t["W"])
+    N, I, O, B, r = w.N, w.d_in, w.d_out, w.B, w.r
+    ws = torch.empty(hlq.hlq_workspace_bytes_mode(N, I, O, B, r, False, flags), dtype=torch.uint8, device=DEV)
+    dX0 = torch.empty((N, I), dtype=G.dtype, device=DEV)
+    dW0 = torch.empty((O, I), dtype=G.dtype, device=DEV)
+    hlq.hlq_linear_backward_mode(G, X, None, None, W, N, I, O, B, r, w.seed, flags, dX0, dW0, ws)
+    bits = hlq.hlq_weight_code_bits(O, flags)
+    assert bits == (8 if flags & hlq.HLQ_FLAG_GX_8BIT else (4 if flags & hlq.HLQ_FLAG_GX_UNPACKED else P4))
+    WqT = torch.empty((I, O // 2 if bits == P4 else O), dtype=torch.uint8, device=DEV)
+    sW = torch.empty(I, dtype=torch.float32, device=DEV)
+    wws = torch.empty(hlq.hlq_quantize_w_workspace_bytes(O, I), dtype=torch.uint8, device=DEV)
+    hlq.hlq_quantize_w(W, B, w.seed, WqT, sW, wws, None, bits)
+    ws.fill_(0x5A)                                       # nothing of the first call may be reused
+    dX1, dW1 = torch.empty_like(dX0), torch.empty_like(dW0)
+    hlq.hlq_linear_backward_cached(G, X, None, None, WqT, sW, N, I, O, B, r, w.seed, flags, dX1, dW1, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
+    # dW alone needs no weight at all
+    dW2 = torch.empty_like(dW0)
+    hlq.hlq_linear_backward_cached(G, X, None, None, None, None, N, I, O, B, r, w.seed, flags, None, dW2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dW0, dW2)
