@@ -303,28 +303,77 @@ int hlqo_dequant(const int32_t *acc, const float *sA, const float *sB, long M, l
 /* stored with the compressed token axis contiguous.  fp32 (same pairwise sum) */
 /* and fp64 versions.                                                          */
 /* ------------------------------------------------------------------------- */
-int hlqo_hla_f32(const float *T, long N, long D, int B, int r, float *ChatT /* [D, N/B*r] */)
+/* Which rows of H are "the first r".  basis 0: rows 0..r-1 as Eq. 2 numbers them (natural order).     */
+/* basis 1: the r rows of lowest SEQUENCY, in order of increasing sequency, where the sequency of a     */
+/* row is the number of sign changes along it -- the Walsh functions' analogue of frequency, which is  */
+/* what "low-frequency components" of g_w (Sec. 4) and the low-pass base selection of LBP-WHT (Sec.     */
+/* 6.1) refer to.  The rows are found from that definition: count the sign changes of every row.       */
+int hlqo_basis_rows(int B, int basis, int *rows /* [B] */)
 {
     int8_t H[HLQO_MAX_B * HLQO_MAX_B];
-    if (hlqo_hadamard(B, H) || N % B || r < 1 || r > B) return -1;
+    if (hlqo_hadamard(B, H) || (basis != 0 && basis != 1)) return -1;
+    for (int k = 0; k < B; ++k) rows[k] = -1;
+    for (int n = 0; n < B; ++n) {
+        int changes = 0;
+        for (int j = 1; j < B; ++j) changes += H[n * B + j] != H[n * B + j - 1];
+        int k = basis ? changes : n;
+        if (rows[k] != -1) return -1;   /* the sequencies of the B rows are 0..B-1, each once */
+        rows[k] = n;
+    }
+    return 0;
+}
+
+/* coefficient of one given row of H: the one-row case of coeff_f32 / coeff_f64 */
+static float coeff_row_f32(const int8_t *H, int B, int row, const float *v, long stride)
+{
+    float c;
+    coeff_f32(H + row * B, B, v, stride, 1, &c);
+    return c;
+}
+
+static double coeff_row_f64(const int8_t *H, int B, int row, const float *v, long stride)
+{
+    double c;
+    coeff_f64(H + row * B, B, v, stride, 1, &c);
+    return c;
+}
+
+int hlqo_hla_basis_f32(const float *T, long N, long D, int B, int r, int basis, float *ChatT /* [D, N/B*r] */)
+{
+    int8_t H[HLQO_MAX_B * HLQO_MAX_B];
+    int rows[HLQO_MAX_B];
+    if (hlqo_hadamard(B, H) || hlqo_basis_rows(B, basis, rows) || N % B || r < 1 || r > B) return -1;
     long Kc = N / B * r;
 #pragma omp parallel for schedule(static)
     for (long j = 0; j < D; ++j)
         for (long b = 0; b < N / B; ++b)
-            coeff_f32(H, B, T + b * B * D + j, D, r, ChatT + j * Kc + b * r);
+            for (int k = 0; k < r; ++k)
+                ChatT[j * Kc + b * r + k] = coeff_row_f32(H, B, rows[k], T + b * B * D + j, D);
     return 0;
+}
+
+int hlqo_hla_basis_f64(const float *T, long N, long D, int B, int r, int basis, double *ChatT /* [D, N/B*r] */)
+{
+    int8_t H[HLQO_MAX_B * HLQO_MAX_B];
+    int rows[HLQO_MAX_B];
+    if (hlqo_hadamard(B, H) || hlqo_basis_rows(B, basis, rows) || N % B || r < 1 || r > B) return -1;
+    long Kc = N / B * r;
+#pragma omp parallel for schedule(static)
+    for (long j = 0; j < D; ++j)
+        for (long b = 0; b < N / B; ++b)
+            for (int k = 0; k < r; ++k)
+                ChatT[j * Kc + b * r + k] = coeff_row_f64(H, B, rows[k], T + b * B * D + j, D);
+    return 0;
+}
+
+int hlqo_hla_f32(const float *T, long N, long D, int B, int r, float *ChatT /* [D, N/B*r] */)
+{
+    return hlqo_hla_basis_f32(T, N, D, B, r, 0, ChatT);
 }
 
 int hlqo_hla_f64(const float *T, long N, long D, int B, int r, double *ChatT /* [D, N/B*r] */)
 {
-    int8_t H[HLQO_MAX_B * HLQO_MAX_B];
-    if (hlqo_hadamard(B, H) || N % B || r < 1 || r > B) return -1;
-    long Kc = N / B * r;
-#pragma omp parallel for schedule(static)
-    for (long j = 0; j < D; ++j)
-        for (long b = 0; b < N / B; ++b)
-            coeff_f64(H, B, T + b * B * D + j, D, r, ChatT + j * Kc + b * r);
-    return 0;
+    return hlqo_hla_basis_f64(T, N, D, B, r, 0, ChatT);
 }
 
 /* Round an fp32 value to the nearest bfloat16 (ties to even), returned as the */

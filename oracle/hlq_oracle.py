@@ -23,7 +23,7 @@ __all__ = [
     "build", "num_threads", "hadamard", "coeff_f32", "coeff_f64", "transform_rows",
     "transform_cols", "stream_key", "rand_word", "rand_byte", "quantize_one", "quantize_rows",
     "int_gemm_nt", "dequant", "hla_f32", "hla_f64", "round_bf16", "gemm_nt_f64",
-    "linear_backward",
+    "linear_backward", "BASIS_NATURAL", "BASIS_SEQUENCY", "basis_rows",
 ]
 
 
@@ -70,6 +70,9 @@ def _L():
         lib.hlqo_dequant.argtypes = [i32p, f32p, f32p, C.c_long, C.c_long, C.c_int, f64p]
         lib.hlqo_hla_f32.argtypes = [f32p, C.c_long, C.c_long, C.c_int, C.c_int, f32p]
         lib.hlqo_hla_f64.argtypes = [f32p, C.c_long, C.c_long, C.c_int, C.c_int, f64p]
+        lib.hlqo_hla_basis_f32.argtypes = [f32p, C.c_long, C.c_long, C.c_int, C.c_int, C.c_int, f32p]
+        lib.hlqo_hla_basis_f64.argtypes = [f32p, C.c_long, C.c_long, C.c_int, C.c_int, C.c_int, f64p]
+        lib.hlqo_basis_rows.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int)]
         lib.hlqo_round_bf16.argtypes = [C.c_float]
         lib.hlqo_round_bf16.restype = C.c_float
         lib.hlqo_round_bf16_array.argtypes = [f32p, C.c_long, f32p]
@@ -202,20 +205,30 @@ def dequant(acc, sA, sB, B: int) -> np.ndarray:
     return out
 
 
-def hla_f32(T, B: int, r: int) -> np.ndarray:
-    """First r Hadamard coefficients of every block of B tokens -> [D, N/B*r] fp32."""
+BASIS_NATURAL, BASIS_SEQUENCY = 0, 1
+
+
+def basis_rows(B: int, basis: int) -> np.ndarray:
+    """Row of H kept as coefficient k: k itself (natural order), or the row with k sign changes."""
+    rows = np.empty(B, dtype=np.int32)
+    _check(_L().hlqo_basis_rows(B, basis, _p(rows, C.c_int)), "basis_rows")
+    return rows
+
+
+def hla_f32(T, B: int, r: int, basis: int = 0) -> np.ndarray:
+    """First r Hadamard coefficients (in the order of `basis`) of every block of B tokens -> [D, N/B*r] fp32."""
     T = _f32(T)
     N, D = T.shape
     out = np.empty((D, N // B * r), dtype=np.float32)
-    _check(_L().hlqo_hla_f32(_p(T, C.c_float), N, D, B, r, _p(out, C.c_float)), "hla_f32")
+    _check(_L().hlqo_hla_basis_f32(_p(T, C.c_float), N, D, B, r, basis, _p(out, C.c_float)), "hla_f32")
     return out
 
 
-def hla_f64(T, B: int, r: int) -> np.ndarray:
+def hla_f64(T, B: int, r: int, basis: int = 0) -> np.ndarray:
     T = _f32(T)
     N, D = T.shape
     out = np.empty((D, N // B * r), dtype=np.float64)
-    _check(_L().hlqo_hla_f64(_p(T, C.c_float), N, D, B, r, _p(out, C.c_double)), "hla_f64")
+    _check(_L().hlqo_hla_basis_f64(_p(T, C.c_float), N, D, B, r, basis, _p(out, C.c_double)), "hla_f64")
     return out
 
 
@@ -270,13 +283,16 @@ def linear_backward(G, X, W, B: int, r: int, seed: int, want_dX: bool = True, wa
     return out
 
 
-def linear_backward_mode(G, X, W, B: int, r: int, seed: int, gx_bits: int = 4, gw_int8: bool = False):
+def linear_backward_mode(G, X, W, B: int, r: int, seed: int, gx_bits: int = 4, gw_int8: bool = False,
+                         basis: int = 0):
     """Both stage lists of Sec. 6.1 composed stage by stage, with the two options of the method:
 
     gx_bits = 8   the g_x codes use [-127, 127] (the int8 warm-up phase of Sec. 7) instead of 4 bits;
     gw_int8       the g_w list in full: the HLA-projected X and G are quantised to int8 (stages 2, 4),
                   multiplied in integers (stage 5) and dequantised (stage 6), instead of being kept
-                  in bf16.
+                  in bf16;
+    basis         which r rows of H the g_w list keeps: 0 the first r in natural order, 1 the r of
+                  lowest sequency.
     Returns a dict with dX, dW (fp64) and every intermediate."""
     G, X, W = _f32(G), _f32(X), _f32(W)
     qx = 7 if gx_bits == 4 else 127
@@ -288,8 +304,8 @@ def linear_backward_mode(G, X, W, B: int, r: int, seed: int, gx_bits: int = 4, g
     acc = int_gemm_nt(Gq, Wq)
     out.update(Gq=Gq, sG=sG, Wq=Wq, sW=sW, acc=acc, dX=dequant(acc, sG, sW, B))
     # g_w: 1. HLA(x) on L  2. Q8  3. HLA(g_o^T) on L  4. Q8  5. integer product  6. dequantise
-    xh = hla_f32(X, B, r)
-    gh = hla_f32(G, B, r)
+    xh = hla_f32(X, B, r, basis)
+    gh = hla_f32(G, B, r, basis)
     if gw_int8:
         Xq, sX = quantize_rows(xh, seed, TENSOR_XHAT, qmax=127)
         Gq2, sG2 = quantize_rows(gh, seed, TENSOR_GHAT, qmax=127)
