@@ -177,6 +177,21 @@ int hlq_hla_project(const void *T, int64_t N, int64_t D, int B, int r, int dtype
                     float *coeffT, void *stream);
 
 /*
+ * Which r of the B coefficients "the first r" are (Sec. 6.1 follows the base selection of LBP-WHT,
+ * which the paper does not spell out; Sec. 4 speaks of the low-frequency components of g_w).
+ *   HLQ_BASIS_NATURAL   rows 0..r-1 of the matrix as Eq. 2 builds it -- what every entry point
+ *                       without a basis argument uses;
+ *   HLQ_BASIS_SEQUENCY  the r rows with the fewest sign changes, in that order (Walsh ordering):
+ *                       a true low-pass, for r = B/2^m the averages over runs of B/r tokens.
+ * Same arguments as hlq_hla_project otherwise; any other basis: HLQ_ERR_RANK.  For the forward-time
+ * stores call these with T = X (and tensor = 2 for the integer one).
+ */
+#define HLQ_BASIS_NATURAL 0
+#define HLQ_BASIS_SEQUENCY 1
+int hlq_hla_project_basis(const void *T, int64_t N, int64_t D, int B, int r, int basis, int dtype, void *ThatT,
+                          float *coeffT, void *stream);
+
+/*
  * Stage 5 of the g_w list: C[m, n] = alpha * sum_k A[m,k] * Bm[n,k], bf16 inputs, fp32
  * accumulation (bf16 MFMA).  A [M, K], Bm [Nn, K] bf16, K % 8 == 0, Nn % 4 == 0; C [M, Nn] of
  * out_dtype.  workspace: as for hlq_int8_gemm_nt (kind 1).
@@ -190,6 +205,8 @@ int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64
 #define HLQ_FLAG_GX_8BIT 1 /* g_x codes in [-127, 127]: the int8 warm-up phase of Sec. 7 */
 #define HLQ_FLAG_GW_INT8 2 /* g_w list in full (Sec. 6.1): projected X and G quantised to int8
                               (stages 2, 4), integer product (5), dequantisation (6) */
+#define HLQ_FLAG_GW_SEQUENCY 8 /* g_w list keeps the r lowest-sequency coefficients (HLQ_BASIS_SEQUENCY); a
+                                 forward-time store handed over as Xc must have been made the same way */
 #define HLQ_FLAG_GX_UNPACKED 4 /* keep the 4-bit g_x codes one per int8 between the stages.  By default
                                   they are stored two to a byte whenever d_out % 32 == 0 (same codes, same
                                   dX bit for bit; half the traffic). */
@@ -207,6 +224,9 @@ size_t hlq_hla_quantize_workspace_bytes(int64_t D);
 int hlq_hla_quantize(const void *T, int64_t N, int64_t D, int B, int r, uint64_t seed, int tensor, int dtype,
                      int8_t *TqT, float *sT, float *coeffT, void *workspace, size_t workspace_bytes,
                      void *stream);
+int hlq_hla_quantize_basis(const void *T, int64_t N, int64_t D, int B, int r, int basis, uint64_t seed, int tensor,
+                           int dtype, int8_t *TqT, float *sT, float *coeffT, void *workspace,
+                           size_t workspace_bytes, void *stream);
 
 /*
  * ACBP with integer storage (Sec. 6.1: "apply stages 1 and 2 during forward propagation and store

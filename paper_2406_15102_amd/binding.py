@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libhlq.so")
 
 HLQ_BF16, HLQ_F32 = 0, 1
 HLQ_OK = 0
-HLQ_FLAG_GX_8BIT, HLQ_FLAG_GW_INT8, HLQ_FLAG_GX_UNPACKED = 1, 2, 4
+HLQ_FLAG_GX_8BIT, HLQ_FLAG_GW_INT8, HLQ_FLAG_GX_UNPACKED, HLQ_FLAG_GW_SEQUENCY = 1, 2, 4, 8
+HLQ_BASIS_NATURAL, HLQ_BASIS_SEQUENCY = 0, 1
 HLQ_BITS_4, HLQ_BITS_8, HLQ_BITS_4_PACKED = 4, 8, 0x104
 
 _EXPORTS = {
@@ -53,6 +54,10 @@ _EXPORTS = {
     "hlq_gemm_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int64, C.c_int64, C.c_int64]),
     "hlq_hla_project": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_void_p,
                                   C.c_void_p, C.c_void_p]),
+    "hlq_hla_project_basis": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p,
+                                        C.c_void_p, C.c_void_p]),
+    "hlq_hla_quantize_basis": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_int,
+                                         C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hlq_bf16_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_float, C.c_int,
                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hlq_mfma_probe": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
@@ -270,3 +275,16 @@ def hlq_linear_backward_cached(G, X, Xc, sXc, WqT, sW, N, d_in, d_out, B, r, see
                                             _ptr(sW, torch.float32), N, d_in, d_out, B, r, seed, _dt(G), flags,
                                             _ptr(dX), _ptr(dW), ws_ptr, ws_bytes, _stream()),
            "hlq_linear_backward_cached")
+
+
+def hlq_hla_project_basis(T, B, r, basis, ThatT, coeffT=None):
+    N, D = T.shape
+    _check(lib().hlq_hla_project_basis(_ptr(T), N, D, B, r, basis, _dt(T), _ptr(ThatT, torch.bfloat16),
+                                       _ptr(coeffT, torch.float32), _stream()), "hlq_hla_project_basis")
+
+
+def hlq_hla_quantize_basis(T, B, r, basis, seed, tensor, TqT, sT, workspace, coeffT=None):
+    N, D = T.shape
+    _check(lib().hlq_hla_quantize_basis(_ptr(T), N, D, B, r, basis, seed, tensor, _dt(T), _ptr(TqT, torch.int8),
+                                        _ptr(sT, torch.float32), _ptr(coeffT, torch.float32), _ptr(workspace),
+                                        _nbytes(workspace), _stream()), "hlq_hla_quantize_basis")

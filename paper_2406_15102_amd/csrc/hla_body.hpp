@@ -5,7 +5,7 @@
 
 namespace hlq {
 
-template <typename Tin, int B>
+template <typename Tin, int B, int BASIS>
 __device__ __forceinline__ void hla_body(const Tin *__restrict__ T, int64_t N, int D, int r, bf16_t *__restrict__ ThatT,
                                          float *__restrict__ coeffT, int bx, int by)
 {
@@ -30,27 +30,27 @@ __device__ __forceinline__ void hla_body(const Tin *__restrict__ T, int64_t N, i
             for (int k = 0; k < B; k += 8) {
                 if (k < r) {
                     uint4 p;
-                    p.x = pack_bf16(v[(k + 0) * CPL + c], v[(k + 1) * CPL + c]);
-                    p.y = pack_bf16(v[(k + 2) * CPL + c], v[(k + 3) * CPL + c]);
-                    p.z = pack_bf16(v[(k + 4) * CPL + c], v[(k + 5) * CPL + c]);
-                    p.w = pack_bf16(v[(k + 6) * CPL + c], v[(k + 7) * CPL + c]);
+                    p.x = pack_bf16(v[kept_row<B, BASIS>(k + 0) * CPL + c], v[kept_row<B, BASIS>(k + 1) * CPL + c]);
+                    p.y = pack_bf16(v[kept_row<B, BASIS>(k + 2) * CPL + c], v[kept_row<B, BASIS>(k + 3) * CPL + c]);
+                    p.z = pack_bf16(v[kept_row<B, BASIS>(k + 4) * CPL + c], v[kept_row<B, BASIS>(k + 5) * CPL + c]);
+                    p.w = pack_bf16(v[kept_row<B, BASIS>(k + 6) * CPL + c], v[kept_row<B, BASIS>(k + 7) * CPL + c]);
                     *reinterpret_cast<uint4 *>(ThatT + o + k) = p;
                 }
             }
         } else if (r == 4) {
             uint2 p;
-            p.x = pack_bf16(v[0 * CPL + c], v[1 * CPL + c]);
-            p.y = pack_bf16(v[2 * CPL + c], v[3 * CPL + c]);
+            p.x = pack_bf16(v[kept_row<B, BASIS>(0) * CPL + c], v[kept_row<B, BASIS>(1) * CPL + c]);
+            p.y = pack_bf16(v[kept_row<B, BASIS>(2) * CPL + c], v[kept_row<B, BASIS>(3) * CPL + c]);
             *reinterpret_cast<uint2 *>(ThatT + o) = p;
         } else if (r == 2) {
-            *reinterpret_cast<uint32_t *>(ThatT + o) = pack_bf16(v[0 * CPL + c], v[1 * CPL + c]);
+            *reinterpret_cast<uint32_t *>(ThatT + o) = pack_bf16(v[kept_row<B, BASIS>(0) * CPL + c], v[kept_row<B, BASIS>(1) * CPL + c]);
         } else {
             ThatT[o] = static_cast<bf16_t>(pack_bf16(v[c], 0.0f) & 0xFFFFu);
         }
         if (coeffT) {
 #pragma unroll
             for (int k = 0; k < B; ++k)
-                if (k < r) coeffT[o + k] = v[k * CPL + c];
+                if (k < r) coeffT[o + k] = v[kept_row<B, BASIS>(k) * CPL + c];
         }
     }
 }

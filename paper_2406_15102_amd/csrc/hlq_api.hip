@@ -103,7 +103,7 @@ Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_
 
 int check_flags(int flags, int r, int64_t N, int B)
 {
-    if (flags & ~(HLQ_FLAG_GX_8BIT | HLQ_FLAG_GW_INT8 | HLQ_FLAG_GX_UNPACKED)) return HLQ_ERR_SHAPE;
+    if (flags & ~(HLQ_FLAG_GX_8BIT | HLQ_FLAG_GW_INT8 | HLQ_FLAG_GX_UNPACKED | HLQ_FLAG_GW_SEQUENCY)) return HLQ_ERR_SHAPE;
     if (flags & HLQ_FLAG_GW_INT8) {
         if (r % 4 != 0) return HLQ_ERR_RANK;
         if ((N / B * r) % 16 != 0) return HLQ_ERR_SHAPE;
@@ -269,14 +269,21 @@ int hlq_int4_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64
 int hlq_hla_project(const void *T, int64_t N, int64_t D, int B, int r, int dtype, void *ThatT, float *coeffT,
                     void *stream)
 {
+    return hlq_hla_project_basis(T, N, D, B, r, HLQ_BASIS_NATURAL, dtype, ThatT, coeffT, stream);
+}
+
+int hlq_hla_project_basis(const void *T, int64_t N, int64_t D, int B, int r, int basis, int dtype, void *ThatT,
+                          float *coeffT, void *stream)
+{
     int rc;
     if (!T || !ThatT) return HLQ_ERR_NULL;
+    if (basis != HLQ_BASIS_NATURAL && basis != HLQ_BASIS_SEQUENCY) return HLQ_ERR_RANK;
     if ((rc = check_block(B)) != HLQ_OK) return rc;
     if ((rc = check_rank(B, r)) != HLQ_OK) return rc;
     if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
     if ((rc = check_hla_shape(N, D, B, r)) != HLQ_OK) return rc;
     if (!aligned(T, 16) || !aligned(ThatT, 16) || (coeffT && !aligned(coeffT, 16))) return HLQ_ERR_SHAPE;
-    return launch_rc(hlq::launch_hla(T, N, static_cast<int>(D), B, r, dtype == HLQ_F32,
+    return launch_rc(hlq::launch_hla(T, N, static_cast<int>(D), B, r, basis, dtype == HLQ_F32,
                                      static_cast<uint16_t *>(ThatT), coeffT, static_cast<hipStream_t>(stream)));
 }
 
@@ -311,8 +318,17 @@ size_t hlq_hla_quantize_workspace_bytes(int64_t D) { return D > 0 ? hlq::hla_qua
 int hlq_hla_quantize(const void *T, int64_t N, int64_t D, int B, int r, uint64_t seed, int tensor, int dtype,
                      int8_t *TqT, float *sT, float *coeffT, void *workspace, size_t workspace_bytes, void *stream)
 {
+    return hlq_hla_quantize_basis(T, N, D, B, r, HLQ_BASIS_NATURAL, seed, tensor, dtype, TqT, sT, coeffT, workspace,
+                                  workspace_bytes, stream);
+}
+
+int hlq_hla_quantize_basis(const void *T, int64_t N, int64_t D, int B, int r, int basis, uint64_t seed, int tensor,
+                           int dtype, int8_t *TqT, float *sT, float *coeffT, void *workspace, size_t workspace_bytes,
+                           void *stream)
+{
     int rc;
     if (!T || !TqT || !sT || !workspace) return HLQ_ERR_NULL;
+    if (basis != HLQ_BASIS_NATURAL && basis != HLQ_BASIS_SEQUENCY) return HLQ_ERR_RANK;
     if ((rc = check_block(B)) != HLQ_OK) return rc;
     if ((rc = check_rank(B, r)) != HLQ_OK) return rc;
     if (r % 4 != 0) return HLQ_ERR_RANK;
@@ -324,7 +340,7 @@ int hlq_hla_quantize(const void *T, int64_t N, int64_t D, int B, int r, uint64_t
     if (!aligned(T, 16) || !aligned(TqT, 16) || (coeffT && !aligned(coeffT, 16))) return HLQ_ERR_SHAPE;
     if (!aligned(workspace, 256) || workspace_bytes < hlq::hla_quant_ws_bytes(D)) return HLQ_ERR_WORKSPACE;
     const uint64_t key = stream_key(seed, static_cast<uint32_t>(tensor));
-    return launch_rc(hlq::launch_hla_quant(T, N, static_cast<int>(D), B, r, dtype == HLQ_F32,
+    return launch_rc(hlq::launch_hla_quant(T, N, static_cast<int>(D), B, r, basis, dtype == HLQ_F32,
                                            static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32), TqT, sT,
                                            coeffT, workspace, static_cast<hipStream_t>(stream)));
 }
@@ -349,6 +365,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     const float qmax = (flags & HLQ_FLAG_GX_8BIT) ? 127.0f : 7.0f;
     // 4-bit codes travel two to a byte whenever their rows stay 16-byte aligned that way
     const bool packed = !(flags & (HLQ_FLAG_GX_8BIT | HLQ_FLAG_GX_UNPACKED)) && d_out % 32 == 0;
+    const int basis = (flags & HLQ_FLAG_GW_SEQUENCY) ? HLQ_BASIS_SEQUENCY : HLQ_BASIS_NATURAL;
     if (!G || (!dX && !dW)) return HLQ_ERR_NULL;
     if (dX && !W && !(Wc && sWc)) return HLQ_ERR_NULL;
     if (Wc && (!aligned(Wc, 16) || !aligned(sWc, 16))) return HLQ_ERR_SHAPE;
@@ -399,7 +416,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         const hlq::FrontFill jf{reinterpret_cast<uint32_t *>(ws + L.wws), dX && !wc ? I : 0};
         const hlq::FrontHla jg = hlq::front_hla(dW ? G : nullptr, N, O, B, r, static_cast<uint16_t *>(Gh));
         const hlq::FrontAbsmax jw = hlq::front_absmax(dX && !wc ? W : nullptr, O, I, B, reinterpret_cast<uint32_t *>(ws + L.wws));
-        if ((rc = launch_rc(hlq::launch_front(jr, jx, jf, jg, jw, B, f32, packed, st))) != HLQ_OK) return rc;
+        if ((rc = launch_rc(hlq::launch_front(jr, jx, jf, jg, jw, B, basis, f32, packed, st))) != HLQ_OK) return rc;
         if (dW && !xc) Xh = xh;
     }
     if (dX && !fused) {
@@ -410,24 +427,24 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     }
     if (dW && !gwi && !fused) {
         // g_w stages 3 and 1 kept in bf16: HLA of G and (unless it was compressed at forward time) of X
-        if ((rc = launch_rc(hlq::launch_hla(G, N, O, B, r, f32, static_cast<uint16_t *>(Gh), nullptr, st))) != HLQ_OK) return rc;
+        if ((rc = launch_rc(hlq::launch_hla(G, N, O, B, r, basis, f32, static_cast<uint16_t *>(Gh), nullptr, st))) != HLQ_OK) return rc;
         if (!xc) {
             uint16_t *xh = reinterpret_cast<uint16_t *>(ws + L.XhatT);
-            if ((rc = launch_rc(hlq::launch_hla(X, N, I, B, r, f32, xh, nullptr, st))) != HLQ_OK) return rc;
+            if ((rc = launch_rc(hlq::launch_hla(X, N, I, B, r, basis, f32, xh, nullptr, st))) != HLQ_OK) return rc;
             Xh = xh;
         }
     }
     if (dW && gwi) {
         // g_w stages 3-4 and 1-2: HLA + int8 quantisation of G (stream 3) and of X (stream 2)
         const uint64_t k3 = stream_key(seed, 3), k2 = stream_key(seed, 2);
-        if ((rc = launch_rc(hlq::launch_hla_quant(G, N, O, B, r, f32, static_cast<uint32_t>(k3),
+        if ((rc = launch_rc(hlq::launch_hla_quant(G, N, O, B, r, basis, f32, static_cast<uint32_t>(k3),
                                                   static_cast<uint32_t>(k3 >> 32), static_cast<int8_t *>(Gh), sGh,
                                                   nullptr, ws + L.hws, st))) != HLQ_OK)
             return rc;
         if (!xc) {
             int8_t *xq = reinterpret_cast<int8_t *>(ws + L.XhatT);
             float *sx = reinterpret_cast<float *>(ws + L.sXhat);
-            if ((rc = launch_rc(hlq::launch_hla_quant(X, N, I, B, r, f32, static_cast<uint32_t>(k2),
+            if ((rc = launch_rc(hlq::launch_hla_quant(X, N, I, B, r, basis, f32, static_cast<uint32_t>(k2),
                                                       static_cast<uint32_t>(k2 >> 32), xq, sx, nullptr, ws + L.hws,
                                                       st))) != HLQ_OK)
                 return rc;

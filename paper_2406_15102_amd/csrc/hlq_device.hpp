@@ -122,6 +122,20 @@ __device__ __forceinline__ float butterfly_lanes_signed(float x, float sigma)
     }
 }
 
+// Row of the natural-order Hadamard matrix kept as coefficient k of the low-rank projection.
+// BASIS 0: row k.  BASIS 1: the row with k sign changes (sequency order), which is the
+// bit-reversed Gray code of k.  Constant-folds when k is a compile-time constant.
+template <int B, int BASIS>
+__host__ __device__ constexpr int kept_row(int k)
+{
+    if (BASIS == 0) return k;
+    const int g = k ^ (k >> 1);
+    int n = 0;
+    for (int lo = 1, hi = B >> 1; lo < B; lo <<= 1, hi >>= 1)
+        if (g & lo) n |= hi;
+    return n;
+}
+
 // ---- random stream ---------------------------------------------------------------------------
 // Word `counter` of the stream keyed by (k0, k1): a keyed xorshift-multiply bijection of the
 // counter (multipliers of the public-domain "lowbias32" integer hash).

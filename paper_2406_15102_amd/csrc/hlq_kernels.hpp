@@ -57,18 +57,19 @@ FrontRows front_rows(const void *G, int64_t N, int O, int B, uint32_t k0, uint32
 FrontHla front_hla(const void *T, int64_t N, int D, int B, int r, uint16_t *out);
 FrontAbsmax front_absmax(const void *W, int O, int I, int B, uint32_t *amax);
 hipError_t launch_front(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
-                        const FrontAbsmax &jw, int B, bool is_f32, bool packed, hipStream_t st);
+                        const FrontAbsmax &jw, int B, int basis, bool is_f32, bool packed, hipStream_t st);
 
 // K3: token-axis Hadamard low-rank projection, T [N, D] -> ThatT [D, N/B*r] bf16.
-hipError_t launch_hla(const void *T, int64_t N, int D, int B, int r, bool is_f32, uint16_t *ThatT,
+// basis: which r rows of the order-B matrix are kept, 0 = rows 0..r-1, 1 = the r of lowest sequency.
+hipError_t launch_hla(const void *T, int64_t N, int D, int B, int r, int basis, bool is_f32, uint16_t *ThatT,
                       float *coeffT, hipStream_t st);
 
 // K3q: token-axis projection followed by int8 quantisation with one scale per feature (stages
 // 1-2 / 3-4 of the g_w list): T [N, D] -> TqT [D, N/B*r] int8 + sT [D].  `ws` holds D words of
 // column maxima: hla_quant_ws_bytes(D) bytes.  Needs r % 4 == 0.
 size_t hla_quant_ws_bytes(int64_t D);
-hipError_t launch_hla_quant(const void *T, int64_t N, int D, int B, int r, bool is_f32, uint32_t k0, uint32_t k1,
-                            int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st);
+hipError_t launch_hla_quant(const void *T, int64_t N, int D, int B, int r, int basis, bool is_f32, uint32_t k0,
+                            uint32_t k1, int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st);
 
 // K2 / K4: C = alpha * sA (x) sB * (A . Bm^T).  kind 0: int8 operands, int32 accumulate;
 // kind 1: bf16 operands, fp32 accumulate.  K in elements.

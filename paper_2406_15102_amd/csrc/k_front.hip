@@ -15,7 +15,7 @@
 
 namespace hlq {
 
-template <typename Tin, int B, bool PACKED>
+template <typename Tin, int B, bool PACKED, int BASIS>
 __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, FrontFill jf)
 {
     int b = blockIdx.x;
@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
     }
     b -= jr.blocks;
     if (b < jx.gx * jx.gy) {
-        hla_body<Tin, B>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, b % jx.gx, b / jx.gx);
+        hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, b % jx.gx, b / jx.gx);
         return;
     }
     b -= jx.gx * jx.gy;
@@ -34,12 +34,12 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
     if (i < jf.n) jf.p[i] = 0u;
 }
 
-template <typename Tin, int B>
+template <typename Tin, int B, int BASIS>
 __global__ __launch_bounds__(256) void k_front_b(FrontHla jg, FrontAbsmax jw)
 {
     int b = blockIdx.x;
     if (b < jg.gx * jg.gy) {
-        hla_body<Tin, B>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.out, nullptr, b % jg.gx, b / jg.gx);
+        hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.out, nullptr, b % jg.gx, b / jg.gx);
         return;
     }
     b -= jg.gx * jg.gy;
@@ -82,27 +82,30 @@ FrontAbsmax front_absmax(const void *W, int O, int I, int B, uint32_t *amax)
     return j;
 }
 
-template <typename Tin, int B>
+template <typename Tin, int B, int BASIS>
 static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
                                  const FrontAbsmax &jw, bool packed, hipStream_t st)
 {
     const int na = jr.blocks + jx.gx * jx.gy + (jf.n + 255) / 256;
     if (na > 0) {
-        if (packed) hipLaunchKernelGGL((k_front_a<Tin, B, true>), dim3(na), dim3(256), 0, st, jr, jx, jf);
-        else hipLaunchKernelGGL((k_front_a<Tin, B, false>), dim3(na), dim3(256), 0, st, jr, jx, jf);
+        if (packed) hipLaunchKernelGGL((k_front_a<Tin, B, true, BASIS>), dim3(na), dim3(256), 0, st, jr, jx, jf);
+        else hipLaunchKernelGGL((k_front_a<Tin, B, false, BASIS>), dim3(na), dim3(256), 0, st, jr, jx, jf);
     }
     const int nb = jg.gx * jg.gy + jw.gx * jw.gy;
-    if (nb > 0) hipLaunchKernelGGL((k_front_b<Tin, B>), dim3(nb), dim3(256), 0, st, jg, jw);
+    if (nb > 0) hipLaunchKernelGGL((k_front_b<Tin, B, BASIS>), dim3(nb), dim3(256), 0, st, jg, jw);
     return hipGetLastError();
 }
 
 hipError_t launch_front(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
-                        const FrontAbsmax &jw, int B, bool is_f32, bool packed, hipStream_t st)
+                        const FrontAbsmax &jw, int B, int basis, bool is_f32, bool packed, hipStream_t st)
 {
-#define HLQ_FRONT_CASE(BB)                                                                   \
-    case BB:                                                                                 \
-        return is_f32 ? launch_front_t<float, BB>(jr, jx, jf, jg, jw, packed, st)            \
-                      : launch_front_t<bf16_t, BB>(jr, jx, jf, jg, jw, packed, st);
+#define HLQ_FRONT_CASE(BB)                                                                      \
+    case BB:                                                                                    \
+        if (basis)                                                                              \
+            return is_f32 ? launch_front_t<float, BB, 1>(jr, jx, jf, jg, jw, packed, st)        \
+                          : launch_front_t<bf16_t, BB, 1>(jr, jx, jf, jg, jw, packed, st);      \
+        return is_f32 ? launch_front_t<float, BB, 0>(jr, jx, jf, jg, jw, packed, st)            \
+                      : launch_front_t<bf16_t, BB, 0>(jr, jx, jf, jg, jw, packed, st);
     switch (B) {
         HLQ_FRONT_CASE(16)
         HLQ_FRONT_CASE(32)

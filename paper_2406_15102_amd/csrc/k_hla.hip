@@ -16,30 +16,33 @@
 
 namespace hlq {
 
-template <typename Tin, int B>
+template <typename Tin, int B, int BASIS>
 __global__ __launch_bounds__(256) void k_hla(const Tin *__restrict__ T, int64_t N, int D, int r,
                                              bf16_t *__restrict__ ThatT, float *__restrict__ coeffT)
 {
-    hla_body<Tin, B>(T, N, D, r, ThatT, coeffT, blockIdx.x, blockIdx.y);
+    hla_body<Tin, B, BASIS>(T, N, D, r, ThatT, coeffT, blockIdx.x, blockIdx.y);
 }
 
 template <typename Tin, int B>
-static hipError_t launch_hla_t(const void *T, int64_t N, int D, int r, bf16_t *ThatT, float *coeffT, hipStream_t st)
+static hipError_t launch_hla_t(const void *T, int64_t N, int D, int r, int basis, bf16_t *ThatT, float *coeffT, hipStream_t st)
 {
     constexpr int CPL = 128 / B;
     const int64_t nblk = N / B;
     dim3 grid((D + 64 * CPL - 1) / (64 * CPL), static_cast<unsigned>((nblk + 3) / 4));
-    hipLaunchKernelGGL((k_hla<Tin, B>), grid, dim3(256), 0, st, static_cast<const Tin *>(T), N, D, r, ThatT, coeffT);
+    if (basis)
+        hipLaunchKernelGGL((k_hla<Tin, B, 1>), grid, dim3(256), 0, st, static_cast<const Tin *>(T), N, D, r, ThatT, coeffT);
+    else
+        hipLaunchKernelGGL((k_hla<Tin, B, 0>), grid, dim3(256), 0, st, static_cast<const Tin *>(T), N, D, r, ThatT, coeffT);
     return hipGetLastError();
 }
 
-hipError_t launch_hla(const void *T, int64_t N, int D, int B, int r, bool is_f32, uint16_t *ThatT, float *coeffT,
-                      hipStream_t st)
+hipError_t launch_hla(const void *T, int64_t N, int D, int B, int r, int basis, bool is_f32, uint16_t *ThatT,
+                      float *coeffT, hipStream_t st)
 {
 #define HLQ_HLA_CASE(BB)                                                                  \
     case BB:                                                                              \
-        return is_f32 ? launch_hla_t<float, BB>(T, N, D, r, ThatT, coeffT, st)            \
-                      : launch_hla_t<bf16_t, BB>(T, N, D, r, ThatT, coeffT, st);
+        return is_f32 ? launch_hla_t<float, BB>(T, N, D, r, basis, ThatT, coeffT, st)            \
+                      : launch_hla_t<bf16_t, BB>(T, N, D, r, basis, ThatT, coeffT, st);
     switch (B) {
         HLQ_HLA_CASE(16)
         HLQ_HLA_CASE(32)
@@ -63,7 +66,7 @@ __global__ __launch_bounds__(256) void k_hla_fill_u32(uint32_t *p, int n, uint32
     if (i < n) p[i] = value;
 }
 
-template <typename Tin, int B>
+template <typename Tin, int B, int BASIS>
 __global__ __launch_bounds__(256) void k_hla_absmax(const Tin *__restrict__ T, int64_t N, int D, int r,
                                                     uint32_t *__restrict__ amax_bits)
 {
@@ -86,7 +89,7 @@ __global__ __launch_bounds__(256) void k_hla_absmax(const Tin *__restrict__ T, i
             fwht_regs<B, CPL>(v + c);
 #pragma unroll
             for (int k = 0; k < B; ++k)
-                if (k < r) cmax[c] = fmaxf(cmax[c], fabsf(v[k * CPL + c]));
+                if (k < r) cmax[c] = fmaxf(cmax[c], fabsf(v[kept_row<B, BASIS>(k) * CPL + c]));
         }
     }
 #pragma unroll
@@ -99,7 +102,7 @@ __global__ __launch_bounds__(256) void k_hla_absmax(const Tin *__restrict__ T, i
     }
 }
 
-template <typename Tin, int B>
+template <typename Tin, int B, int BASIS>
 __global__ __launch_bounds__(256) void k_hla_quantize(const Tin *__restrict__ T, int64_t N, int D, int r,
                                                       const uint32_t *__restrict__ amax_bits, uint32_t k0,
                                                       uint32_t k1, int8_t *__restrict__ TqT, float *__restrict__ sT,
@@ -131,10 +134,10 @@ __global__ __launch_bounds__(256) void k_hla_quantize(const Tin *__restrict__ T,
             if (k < r) {
                 const uint32_t w = rand_word(cnt + (k >> 2), k0, k1);
                 *reinterpret_cast<uint32_t *>(TqT + o + k) =
-                    quant_pack4(v[(k + 0) * CPL + c], v[(k + 1) * CPL + c], v[(k + 2) * CPL + c], v[(k + 3) * CPL + c], inv, w);
+                    quant_pack4(v[kept_row<B, BASIS>(k + 0) * CPL + c], v[kept_row<B, BASIS>(k + 1) * CPL + c], v[kept_row<B, BASIS>(k + 2) * CPL + c], v[kept_row<B, BASIS>(k + 3) * CPL + c], inv, w);
                 if (coeffT)
                     *reinterpret_cast<float4 *>(coeffT + o + k) =
-                        make_float4(v[(k + 0) * CPL + c], v[(k + 1) * CPL + c], v[(k + 2) * CPL + c], v[(k + 3) * CPL + c]);
+                        make_float4(v[kept_row<B, BASIS>(k + 0) * CPL + c], v[kept_row<B, BASIS>(k + 1) * CPL + c], v[kept_row<B, BASIS>(k + 2) * CPL + c], v[kept_row<B, BASIS>(k + 3) * CPL + c]);
             }
         }
     }
@@ -142,7 +145,7 @@ __global__ __launch_bounds__(256) void k_hla_quantize(const Tin *__restrict__ T,
 
 size_t hla_quant_ws_bytes(int64_t D) { return (static_cast<size_t>(D) * 4 + 255) & ~static_cast<size_t>(255); }
 
-template <typename Tin, int B>
+template <typename Tin, int B, int BASIS>
 static hipError_t launch_hla_quant_t(const void *T, int64_t N, int D, int r, uint32_t k0, uint32_t k1, int8_t *TqT,
                                      float *sT, float *coeffT, void *ws, hipStream_t st)
 {
@@ -152,18 +155,21 @@ static hipError_t launch_hla_quant_t(const void *T, int64_t N, int D, int r, uin
     const Tin *t = static_cast<const Tin *>(T);
     dim3 grid((D + 64 * CPL - 1) / (64 * CPL), static_cast<unsigned>((nblk + 3) / 4));
     hipLaunchKernelGGL(k_hla_fill_u32, dim3((D + 255) / 256), dim3(256), 0, st, amax, D, 0u);
-    hipLaunchKernelGGL((k_hla_absmax<Tin, B>), grid, dim3(256), 0, st, t, N, D, r, amax);
-    hipLaunchKernelGGL((k_hla_quantize<Tin, B>), grid, dim3(256), 0, st, t, N, D, r, amax, k0, k1, TqT, sT, coeffT);
+    hipLaunchKernelGGL((k_hla_absmax<Tin, B, BASIS>), grid, dim3(256), 0, st, t, N, D, r, amax);
+    hipLaunchKernelGGL((k_hla_quantize<Tin, B, BASIS>), grid, dim3(256), 0, st, t, N, D, r, amax, k0, k1, TqT, sT, coeffT);
     return hipGetLastError();
 }
 
-hipError_t launch_hla_quant(const void *T, int64_t N, int D, int B, int r, bool is_f32, uint32_t k0, uint32_t k1,
-                            int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st)
+hipError_t launch_hla_quant(const void *T, int64_t N, int D, int B, int r, int basis, bool is_f32, uint32_t k0,
+                            uint32_t k1, int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st)
 {
-#define HLQ_HLAQ_CASE(BB)                                                                              \
-    case BB:                                                                                           \
-        return is_f32 ? launch_hla_quant_t<float, BB>(T, N, D, r, k0, k1, TqT, sT, coeffT, ws, st)     \
-                      : launch_hla_quant_t<bf16_t, BB>(T, N, D, r, k0, k1, TqT, sT, coeffT, ws, st);
+#define HLQ_HLAQ_CASE(BB)                                                                                  \
+    case BB:                                                                                               \
+        if (basis)                                                                                         \
+            return is_f32 ? launch_hla_quant_t<float, BB, 1>(T, N, D, r, k0, k1, TqT, sT, coeffT, ws, st)  \
+                          : launch_hla_quant_t<bf16_t, BB, 1>(T, N, D, r, k0, k1, TqT, sT, coeffT, ws, st); \
+        return is_f32 ? launch_hla_quant_t<float, BB, 0>(T, N, D, r, k0, k1, TqT, sT, coeffT, ws, st)      \
+                      : launch_hla_quant_t<bf16_t, BB, 0>(T, N, D, r, k0, k1, TqT, sT, coeffT, ws, st);
     switch (B) {
         HLQ_HLAQ_CASE(16)
         HLQ_HLAQ_CASE(32)

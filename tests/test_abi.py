@@ -101,6 +101,8 @@ def test_stage_entry_points_reject_bad_arguments_without_a_gpu():
     assert l.hlq_hla_project(FAKE, 250, 64, 16, 8, 0, FAKE, None, None) == 2
     assert l.hlq_hla_project(FAKE, 256, 64, 16, 5, 0, FAKE, None, None) == 4
     assert l.hlq_compress_act(FAKE, 256, 64, 16, 8, 0, None, None) == 1
+    assert l.hlq_hla_project_basis(FAKE, 256, 64, 16, 8, 2, 0, FAKE, None, None) == 4                       # unknown basis
+    assert l.hlq_hla_project_basis(FAKE, 250, 64, 16, 8, 1, 0, FAKE, None, None) == 2
     assert l.hlq_bf16_gemm_nt(FAKE, FAKE, 64, 64, 36, 1.0, 0, FAKE, None, 0, None) == 2                     # K % 8
     W256 = C.c_void_p(0x10000)
     assert l.hlq_hla_quantize(FAKE, 256, 64, 16, 2, 0, 2, 0, FAKE, FAKE, None, W256, 1 << 20, None) == 4   # r % 4
@@ -116,7 +118,7 @@ def test_mode_entry_point_rejects_bad_arguments_without_a_gpu():
     def call(X=FAKE, Xc=None, sXc=None, flags=0, N=256, r=8, wsb=1 << 30):
         return f(FAKE, X, Xc, sXc, FAKE, N, 256, 256, 16, r, 0, 0, flags, FAKE, FAKE, FAKE, wsb, None)
 
-    assert call(flags=8) == 2                                   # unknown flag
+    assert call(flags=64) == 2                                  # unknown flag
     assert call(flags=2, r=2) == 4                              # integer g_w path needs r % 4 == 0
     assert call(flags=2, N=16, r=8) == 2                        # compressed token axis % 16
     assert call(X=None, Xc=FAKE, sXc=None, flags=2) == 1        # int8 codes need their scales
