@@ -24,8 +24,13 @@ PEAK_I8_TOPS = 5000.0
 PEAK_BF16_TFLOPS = 2500.0
 
 
-def _event_time_us(fn, iters, torch):
-    """Average duration of fn() in microseconds, HIP events on the current (= launch) stream."""
+def _event_time_us(fn, iters, torch, warm=0):
+    """Average duration of fn() in microseconds, HIP events on the current (= launch) stream.
+    `warm` untimed calls first: the GPU's clocks need some 30 ms of load to settle after an idle
+    gap (a 130 us product measures 150 us in the first milliseconds), so every timed region is
+    preceded by enough of the same work."""
+    for _ in range(warm):
+        fn()
     start = torch.cuda.Event(enable_timing=True)
     stop = torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -71,8 +76,8 @@ def cpu_baseline(w, t, budget_tokens):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the CPU-oracle sample (0 = skip)")
     ap.add_argument("--no-modes", action="store_true",
@@ -112,7 +117,7 @@ def main():
         step()
     torch.cuda.synchronize()
     wall_us = (time.perf_counter() - t0) * 1e6 / args.steps
-    hlq_us = _event_time_us(step, args.steps, torch)
+    hlq_us = _event_time_us(step, args.steps, torch, warm=args.warmup // 2)
 
     # ---- the same path with the weight codes taken as cached (W quantised once per optimiser step) ----
     # ---- and kernel by kernel through the stage entry points, HIP events on the launch stream ----------
@@ -152,8 +157,8 @@ def main():
     # order and the thermal / cache state of the real path), "us_alone" = the same launch back to back.
     iters = max(10, args.steps // 2)
     names = list(stages)
-    for fn in stages.values():
-        for _ in range(3):
+    for _ in range(max(3, args.warmup // 4)):
+        for fn in stages.values():
             fn()
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(iters)]
     torch.cuda.synchronize()
@@ -167,7 +172,7 @@ def main():
               for k, name in enumerate(names)}
     kernels = {}
     for name, fn in stages.items():
-        alone = _event_time_us(fn, iters, torch)
+        alone = _event_time_us(fn, iters, torch, warm=max(3, args.warmup // 2))
         us = seq_us[name]
         kind, amount = work[name]
         if kind == "hbm":
@@ -188,16 +193,12 @@ def main():
         if need == 0 or need > ws.numel():
             continue
         fn = lambda: hlq.hlq_linear_backward_mode(G, X, None, None, W, N, I, O, B, r, w.seed, flags, dX, dW, ws)
-        for _ in range(3):
-            fn()
-        modes[label] = {"us": round(_event_time_us(fn, max(10, args.steps // 2), torch), 2)}
+        modes[label] = {"us": round(_event_time_us(fn, iters, torch, warm=max(3, args.warmup // 2)), 2)}
     # ---- the default path with the weight codes handed over (quantised once per optimiser step) ----
     assert hlq.hlq_weight_code_bits(O, 0) == qbits
     hlq.hlq_quantize_w(W, B, w.seed, WqT, sW, wws, None, qbits)
     cached = lambda: hlq.hlq_linear_backward_cached(G, X, None, None, WqT, sW, N, I, O, B, r, w.seed, 0, dX, dW, ws)
-    for _ in range(3):
-        cached()
-    cached_us = _event_time_us(cached, max(10, args.steps // 2), torch)
+    cached_us = _event_time_us(cached, iters, torch, warm=max(3, args.warmup // 2))
     step()   # leave dX / dW as the default path computes them
 
     # ---- dense bf16 backward on the same GPU (comparator, not part of the library) ----
@@ -207,16 +208,12 @@ def main():
 
     dXd = torch.empty_like(dX)
     dWd = torch.empty_like(dW)
-    for _ in range(5):
-        dense()
-    dense_us = _event_time_us(dense, args.steps, torch)
+    dense_us = _event_time_us(dense, args.steps, torch, warm=args.warmup)
 
     # ---- a plain copy of known size: the yardstick that scales the profiler's FETCH_SIZE / WRITE_SIZE ----
     calib_src = torch.empty(1 << 28, dtype=torch.uint8, device=dev)
     calib_dst = torch.empty_like(calib_src)
-    for _ in range(3):
-        calib_dst.copy_(calib_src)
-    copy_us = _event_time_us(lambda: calib_dst.copy_(calib_src), 10, torch)
+    copy_us = _event_time_us(lambda: calib_dst.copy_(calib_src), 20, torch, warm=10)
     del calib_src, calib_dst
 
     dom = "int8_gemm"
