@@ -55,4 +55,82 @@ __device__ __forceinline__ void hla_body(const Tin *__restrict__ T, int64_t N, i
     }
 }
 
+// ---- integer g_w list: pass 1 (column maxima of the kept coefficients) and pass 2 (int8 codes) ----
+template <typename Tin, int B, int BASIS>
+__device__ __forceinline__ void hla_absmax_body(const Tin *__restrict__ T, int64_t N, int D, int r,
+                                                uint32_t *__restrict__ amax_bits, int bx, int by)
+{
+    constexpr int CPL = 128 / B;
+    __shared__ float s_max[4][64 * CPL];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int col0 = (bx * 64 + lane) * CPL;
+    const int64_t nblk = N / B;
+    const int64_t blk = static_cast<int64_t>(by) * 4 + wave;
+    float cmax[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) cmax[c] = 0.0f;
+    if (col0 < D && blk < nblk) {
+        float v[B * CPL];
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+            Loader<Tin, CPL>::load(T + (blk * B + j) * static_cast<int64_t>(D) + col0, v + j * CPL);
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) {
+            fwht_regs<B, CPL>(v + c);
+#pragma unroll
+            for (int k = 0; k < B; ++k)
+                if (k < r) cmax[c] = fmaxf(cmax[c], fabsf(v[kept_row<B, BASIS>(k) * CPL + c]));
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) s_max[wave][lane * CPL + c] = cmax[c];
+    __syncthreads();
+    for (int idx = tid; idx < 64 * CPL; idx += 256) {
+        const float m = fmaxf(fmaxf(s_max[0][idx], s_max[1][idx]), fmaxf(s_max[2][idx], s_max[3][idx]));
+        const int col = bx * 64 * CPL + idx;
+        if (col < D && m > 0.0f) atomicMax(amax_bits + col, __float_as_uint(m));
+    }
+}
+
+template <typename Tin, int B, int BASIS>
+__device__ __forceinline__ void hla_quantize_body(const Tin *__restrict__ T, int64_t N, int D, int r,
+                                                  const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
+                                                  int8_t *__restrict__ TqT, float *__restrict__ sT,
+                                                  float *__restrict__ coeffT, int bx, int by)
+{
+    constexpr int CPL = 128 / B;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int col0 = (bx * 64 + lane) * CPL;
+    const int64_t nblk = N / B;
+    const int64_t Kc = nblk * r;
+    const int64_t blk = static_cast<int64_t>(by) * 4 + wave;
+    if (col0 >= D || blk >= nblk) return;
+
+    float v[B * CPL];
+#pragma unroll
+    for (int j = 0; j < B; ++j)
+        Loader<Tin, CPL>::load(T + (blk * B + j) * static_cast<int64_t>(D) + col0, v + j * CPL);
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        fwht_regs<B, CPL>(v + c);
+        const float a = __uint_as_float(amax_bits[col0 + c]);
+        const float inv = absmax_to_inv(a, 127.0f);
+        if (blk == 0) sT[col0 + c] = absmax_to_scale(a, 127.0f);
+        const int64_t o = static_cast<int64_t>(col0 + c) * Kc + blk * r;          // r % 4 == 0
+        const uint32_t cnt = static_cast<uint32_t>(col0 + c) * static_cast<uint32_t>(Kc >> 2) +
+                             static_cast<uint32_t>((blk * r) >> 2);
+#pragma unroll
+        for (int k = 0; k < B; k += 4) {
+            if (k < r) {
+                const uint32_t w = rand_word(cnt + (k >> 2), k0, k1);
+                *reinterpret_cast<uint32_t *>(TqT + o + k) =
+                    quant_pack4(v[kept_row<B, BASIS>(k + 0) * CPL + c], v[kept_row<B, BASIS>(k + 1) * CPL + c], v[kept_row<B, BASIS>(k + 2) * CPL + c], v[kept_row<B, BASIS>(k + 3) * CPL + c], inv, w);
+                if (coeffT)
+                    *reinterpret_cast<float4 *>(coeffT + o + k) =
+                        make_float4(v[kept_row<B, BASIS>(k + 0) * CPL + c], v[kept_row<B, BASIS>(k + 1) * CPL + c], v[kept_row<B, BASIS>(k + 2) * CPL + c], v[kept_row<B, BASIS>(k + 3) * CPL + c]);
+            }
+        }
+    }
+}
+
 }  // namespace hlq

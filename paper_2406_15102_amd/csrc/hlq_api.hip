@@ -87,11 +87,13 @@ Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_
     L.Wq = off;    off += up256(static_cast<size_t>(d_in) * d_out);
     L.sW = off;    off += up256(static_cast<size_t>(d_in) * 4);
     L.wws = off;   off += up256(hlq::quant_cols_ws_bytes(d_out, d_in));
+    // integer g_w list: column maxima of projected G (d_out words), then of projected X (d_in words),
+    // right behind those of the weight so that one fill zeroes all three
+    L.hws = off;   off += gwi ? up256(hlq::hla_quant_ws_bytes(d_out)) + up256(hlq::hla_quant_ws_bytes(d_in)) : 0;
     L.GhatT = off; off += up256(static_cast<size_t>(d_out) * Kc * esz);
     L.sGhat = off; off += gwi ? up256(static_cast<size_t>(d_out) * 4) : 0;
     L.XhatT = off; off += x_is_compressed ? 0 : up256(static_cast<size_t>(d_in) * Kc * esz);
     L.sXhat = off; off += (gwi && !x_is_compressed) ? up256(static_cast<size_t>(d_in) * 4) : 0;
-    L.hws = off;   off += gwi ? up256(hlq::hla_quant_ws_bytes(d_out > d_in ? d_out : d_in)) : 0;
     // split-K partial sums of whichever product wants them (the two products run one after the other)
     const size_t g1 = hlq::gemm_ws_bytes(0, static_cast<int>(N), static_cast<int>(d_in), static_cast<int>(d_out));
     const size_t g2 = hlq::gemm_ws_bytes(gwi ? 0 : 1, static_cast<int>(d_out), static_cast<int>(d_in), static_cast<int>(Kc));
@@ -406,8 +408,39 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     const float *sXh = sXc;
     // The transforms that depend on nothing share two launches when the shapes allow (k_front.hip);
     // the integer g_w list and very long rows of G keep one launch per stage.
-    const bool fused = !gwi && hlq::front_fusable(O, B);
+    const bool fusable = hlq::front_fusable(O, B);
+    const bool fused = !gwi && fusable;
+    const bool fused_q = gwi && fusable;
     const uint64_t kg = stream_key(seed, 0);
+    if (fused_q) {
+        uint32_t *amax_w = reinterpret_cast<uint32_t *>(ws + L.wws);
+        uint32_t *amax_g = reinterpret_cast<uint32_t *>(ws + L.hws);
+        uint32_t *amax_x = reinterpret_cast<uint32_t *>(ws + L.hws + up256(hlq::hla_quant_ws_bytes(O)));
+        const size_t zero_bytes = (L.hws - L.wws) + up256(hlq::hla_quant_ws_bytes(O)) + up256(hlq::hla_quant_ws_bytes(I));
+        const uint64_t k3 = stream_key(seed, 3), k2 = stream_key(seed, 2), kw = stream_key(seed, 1);
+        const hlq::FrontRows jr = hlq::front_rows(dX ? G : nullptr, N, O, B, static_cast<uint32_t>(kg),
+                                                  static_cast<uint32_t>(kg >> 32), qmax, Gq, sG);
+        const hlq::FrontFill jf{amax_w, static_cast<int>(zero_bytes / 4)};
+        const hlq::FrontHla none = hlq::front_hla(nullptr, N, O, B, r, nullptr);
+        const hlq::FrontAbsmax none_w = hlq::front_absmax(nullptr, O, I, B, nullptr);
+        if ((rc = launch_rc(hlq::launch_front(jr, none, jf, none, none_w, B, basis, f32, packed, st))) != HLQ_OK) return rc;
+        int8_t *xq = xc ? nullptr : reinterpret_cast<int8_t *>(ws + L.XhatT);
+        float *sx = xc ? nullptr : reinterpret_cast<float *>(ws + L.sXhat);
+        const hlq::FrontHlaQ jg = hlq::front_hlaq(dW ? G : nullptr, N, O, B, r, amax_g, static_cast<uint32_t>(k3),
+                                                  static_cast<uint32_t>(k3 >> 32), static_cast<int8_t *>(Gh), sGh);
+        const hlq::FrontHlaQ jx = hlq::front_hlaq(dW && !xc ? X : nullptr, N, I, B, r, amax_x, static_cast<uint32_t>(k2),
+                                                  static_cast<uint32_t>(k2 >> 32), xq, sx);
+        const bool wq = dX && !wc;
+        const hlq::FrontAbsmax jw = hlq::front_absmax(wq ? W : nullptr, O, I, B, amax_w);
+        const hlq::FrontColsQ jq = hlq::front_colsq(wq ? W : nullptr, O, I, B, amax_w, static_cast<uint32_t>(kw),
+                                                    static_cast<uint32_t>(kw >> 32), qmax, reinterpret_cast<int8_t *>(ws + L.Wq),
+                                                    reinterpret_cast<float *>(ws + L.sW));
+        if ((rc = launch_rc(hlq::launch_front_q(jg, jx, jw, jq, B, basis, f32, packed, st))) != HLQ_OK) return rc;
+        if (dW && !xc) {
+            Xh = xq;
+            sXh = sx;
+        }
+    }
     if (fused) {
         uint16_t *xh = xc ? nullptr : reinterpret_cast<uint16_t *>(ws + L.XhatT);
         const hlq::FrontRows jr = hlq::front_rows(dX ? G : nullptr, N, O, B, static_cast<uint32_t>(kg),
@@ -419,7 +452,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         if ((rc = launch_rc(hlq::launch_front(jr, jx, jf, jg, jw, B, basis, f32, packed, st))) != HLQ_OK) return rc;
         if (dW && !xc) Xh = xh;
     }
-    if (dX && !fused) {
+    if (dX && !fused && !fused_q) {
         // g_x stages 1-2: Q(G H)
         if ((rc = launch_rc(hlq::launch_quant_rows(G, N, O, B, f32, static_cast<uint32_t>(kg),
                                                    static_cast<uint32_t>(kg >> 32), qmax, packed, Gq, sG, nullptr, st))) != HLQ_OK)
@@ -434,7 +467,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
             Xh = xh;
         }
     }
-    if (dW && gwi) {
+    if (dW && gwi && !fused_q) {
         // g_w stages 3-4 and 1-2: HLA + int8 quantisation of G (stream 3) and of X (stream 2)
         const uint64_t k3 = stream_key(seed, 3), k2 = stream_key(seed, 2);
         if ((rc = launch_rc(hlq::launch_hla_quant(G, N, O, B, r, basis, f32, static_cast<uint32_t>(k3),
@@ -457,7 +490,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         const uint64_t kw = stream_key(seed, 1);
         int8_t *wq = reinterpret_cast<int8_t *>(ws + L.Wq);
         float *sw = reinterpret_cast<float *>(ws + L.sW);
-        if (wc)      // codes handed over by the caller
+        if (wc || fused_q)   // codes handed over by the caller, or made by the fused launches above
             rc = HLQ_OK;
         else if (fused)   // pass 1 ran in the second front launch
             rc = launch_rc(hlq::launch_quant_cols_pass2(W, O, I, B, f32, static_cast<uint32_t>(kw),

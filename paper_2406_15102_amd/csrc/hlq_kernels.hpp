@@ -52,6 +52,34 @@ struct FrontAbsmax { // pass 1 of K1T
     uint32_t *amax;
     int gx, gy;
 };
+struct FrontHlaQ {   // K3 + int8 quantisation of one tensor: pass 1 (amax) and pass 2 (codes) read the same fields
+    const void *T;
+    int64_t N;
+    int D, r;
+    uint32_t *amax;
+    uint32_t k0, k1;
+    int8_t *TqT;
+    float *sT;
+    int gx, gy;
+};
+struct FrontColsQ {  // pass 2 of K1T
+    const void *W;
+    int O, I;
+    const uint32_t *amax;
+    uint32_t k0, k1;
+    float qmax;
+    int8_t *WqT;
+    float *sW;
+    int gx, gy;
+};
+FrontHlaQ front_hlaq(const void *T, int64_t N, int D, int B, int r, uint32_t *amax, uint32_t k0, uint32_t k1, int8_t *TqT,
+                     float *sT);
+FrontColsQ front_colsq(const void *W, int O, int I, int B, const uint32_t *amax, uint32_t k0, uint32_t k1, float qmax,
+                       int8_t *WqT, float *sW);
+// The integer g_w list in three launches: (K1(G) | zeroing) through launch_front with empty K3 jobs,
+// then every pass 1 (maxima of projected G, projected X, transformed W), then every pass 2.
+hipError_t launch_front_q(const FrontHlaQ &jg, const FrontHlaQ &jx, const FrontAbsmax &jw, const FrontColsQ &jq, int B,
+                          int basis, bool is_f32, bool packed, hipStream_t st);
 bool front_fusable(int O, int B);
 FrontRows front_rows(const void *G, int64_t N, int O, int B, uint32_t k0, uint32_t k1, float qmax, int8_t *Gq, float *sG);
 FrontHla front_hla(const void *T, int64_t N, int D, int B, int r, uint16_t *out);

@@ -6,6 +6,10 @@
 //   front A   K1(G)  |  K3(X)  |  zeroing of the column maxima
 //   front B   K3(G)  |  column maxima of H^T W      (needs the zeroing; G is re-read while the
 //                                                    last-level cache still holds it)
+// and three launches carry the integer g_w list, whose projections are quantised in two passes too:
+//   front A   K1(G)  |  zeroing of all three sets of maxima
+//   front Q1  maxima of projected G  |  of projected X  |  of H^T W
+//   front Q2  int8 codes of projected G  |  of projected X  |  codes of the weight
 // A workgroup looks up its job from its index (jobs occupy consecutive index ranges, a job may be
 // empty) and runs the same device body as the stand-alone kernel of that stage.
 #include "hla_body.hpp"
@@ -44,6 +48,100 @@ __global__ __launch_bounds__(256) void k_front_b(FrontHla jg, FrontAbsmax jw)
     }
     b -= jg.gx * jg.gy;
     cols_absmax_body<Tin, B>(static_cast<const Tin *>(jw.W), jw.O, jw.I, jw.amax, b % jw.gx, b / jw.gx);
+}
+
+// integer g_w list, pass 1 of everything: maxima of the kept coefficients of G and of X, of H^T W
+template <typename Tin, int B, int BASIS>
+__global__ __launch_bounds__(256) void k_front_q1(FrontHlaQ jg, FrontHlaQ jx, FrontAbsmax jw)
+{
+    int b = blockIdx.x;
+    if (b < jg.gx * jg.gy) {
+        hla_absmax_body<Tin, B, BASIS>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.amax, b % jg.gx, b / jg.gx);
+        return;
+    }
+    b -= jg.gx * jg.gy;
+    if (b < jx.gx * jx.gy) {
+        hla_absmax_body<Tin, B, BASIS>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.amax, b % jx.gx, b / jx.gx);
+        return;
+    }
+    b -= jx.gx * jx.gy;
+    cols_absmax_body<Tin, B>(static_cast<const Tin *>(jw.W), jw.O, jw.I, jw.amax, b % jw.gx, b / jw.gx);
+}
+
+// pass 2 of everything: int8 codes of projected G and X, codes of the weight
+template <typename Tin, int B, int BASIS, bool PACKED>
+__global__ __launch_bounds__(256) void k_front_q2(FrontHlaQ jg, FrontHlaQ jx, FrontColsQ jq)
+{
+    int b = blockIdx.x;
+    if (b < jg.gx * jg.gy) {
+        hla_quantize_body<Tin, B, BASIS>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.amax, jg.k0, jg.k1, jg.TqT,
+                                         jg.sT, nullptr, b % jg.gx, b / jg.gx);
+        return;
+    }
+    b -= jg.gx * jg.gy;
+    if (b < jx.gx * jx.gy) {
+        hla_quantize_body<Tin, B, BASIS>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.amax, jx.k0, jx.k1, jx.TqT,
+                                         jx.sT, nullptr, b % jx.gx, b / jx.gx);
+        return;
+    }
+    b -= jx.gx * jx.gy;
+    cols_quantize_body<Tin, B, PACKED>(static_cast<const Tin *>(jq.W), jq.O, jq.I, jq.amax, jq.k0, jq.k1, jq.qmax, jq.WqT,
+                                       jq.sW, nullptr, b % jq.gx, b / jq.gx);
+}
+
+FrontHlaQ front_hlaq(const void *T, int64_t N, int D, int B, int r, uint32_t *amax, uint32_t k0, uint32_t k1, int8_t *TqT,
+                     float *sT)
+{
+    FrontHlaQ j{T, N, D, r, amax, k0, k1, TqT, sT, 0, 0};
+    if (!T) return j;
+    const int cpl = 128 / B;
+    j.gx = (D + 64 * cpl - 1) / (64 * cpl);
+    j.gy = static_cast<int>((N / B + 3) / 4);
+    return j;
+}
+
+FrontColsQ front_colsq(const void *W, int O, int I, int B, const uint32_t *amax, uint32_t k0, uint32_t k1, float qmax,
+                       int8_t *WqT, float *sW)
+{
+    FrontColsQ j{W, O, I, amax, k0, k1, qmax, WqT, sW, 0, 0};
+    if (!W) return j;
+    const int cpl = 128 / B;
+    j.gx = (I + 64 * cpl - 1) / (64 * cpl);
+    j.gy = (O + 4 * B - 1) / (4 * B);
+    return j;
+}
+
+template <typename Tin, int B, int BASIS>
+static hipError_t launch_front_q_t(const FrontHlaQ &jg, const FrontHlaQ &jx, const FrontAbsmax &jw, const FrontColsQ &jq,
+                                   bool packed, hipStream_t st)
+{
+    const int n1 = jg.gx * jg.gy + jx.gx * jx.gy + jw.gx * jw.gy;
+    if (n1 > 0) hipLaunchKernelGGL((k_front_q1<Tin, B, BASIS>), dim3(n1), dim3(256), 0, st, jg, jx, jw);
+    const int n2 = jg.gx * jg.gy + jx.gx * jx.gy + jq.gx * jq.gy;
+    if (n2 > 0) {
+        if (packed) hipLaunchKernelGGL((k_front_q2<Tin, B, BASIS, true>), dim3(n2), dim3(256), 0, st, jg, jx, jq);
+        else hipLaunchKernelGGL((k_front_q2<Tin, B, BASIS, false>), dim3(n2), dim3(256), 0, st, jg, jx, jq);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_front_q(const FrontHlaQ &jg, const FrontHlaQ &jx, const FrontAbsmax &jw, const FrontColsQ &jq, int B,
+                          int basis, bool is_f32, bool packed, hipStream_t st)
+{
+#define HLQ_FRONTQ_CASE(BB)                                                                     \
+    case BB:                                                                                    \
+        if (basis)                                                                              \
+            return is_f32 ? launch_front_q_t<float, BB, 1>(jg, jx, jw, jq, packed, st)          \
+                          : launch_front_q_t<bf16_t, BB, 1>(jg, jx, jw, jq, packed, st);        \
+        return is_f32 ? launch_front_q_t<float, BB, 0>(jg, jx, jw, jq, packed, st)              \
+                      : launch_front_q_t<bf16_t, BB, 0>(jg, jx, jw, jq, packed, st);
+    switch (B) {
+        HLQ_FRONTQ_CASE(16)
+        HLQ_FRONTQ_CASE(32)
+        HLQ_FRONTQ_CASE(64)
+    }
+#undef HLQ_FRONTQ_CASE
+    return hipErrorInvalidValue;
 }
 
 bool front_fusable(int O, int B)

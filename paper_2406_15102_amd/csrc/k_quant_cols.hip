@@ -33,57 +33,13 @@ __global__ __launch_bounds__(256) void k_cols_absmax(const Tin *__restrict__ W, 
     cols_absmax_body<Tin, B>(W, O, I, amax_bits, blockIdx.x, blockIdx.y);
 }
 
-// PACKED: the codes are written two to a byte (4-bit codes only), O/2 bytes per row of WqT.
 template <typename Tin, int B, bool PACKED>
 __global__ __launch_bounds__(256) void k_cols_quantize(const Tin *__restrict__ W, int O, int I,
                                                        const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
                                                        float qmax, int8_t *__restrict__ WqT, float *__restrict__ sW,
                                                        float *__restrict__ coeffT)
 {
-    constexpr int CPL = 128 / B;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int col0 = (blockIdx.x * 64 + lane) * CPL;
-    const int o0 = (blockIdx.y * 4 + wave) * B;
-    if (col0 >= I || o0 >= O) return;
-
-    float v[B * CPL];
-    load_row_block<Tin, B, CPL>(W + static_cast<int64_t>(o0) * I + col0, I, v);
-    float inv[CPL];
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-        const float a = __uint_as_float(amax_bits[col0 + c]);
-        inv[c] = absmax_to_inv(a, qmax);
-        if (o0 == 0) sW[col0 + c] = absmax_to_scale(a, qmax);
-    }
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-        fwht_regs<B, CPL>(v + c);
-        const int64_t orow = static_cast<int64_t>(col0 + c) * O + o0;
-        const uint32_t cnt = static_cast<uint32_t>(col0 + c) * static_cast<uint32_t>(O >> 2) +
-                             static_cast<uint32_t>(o0 >> 2);
-#pragma unroll
-        for (int d4 = 0; d4 < B / 16; ++d4) {
-            uint32_t out[4];
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const int j = (d4 * 4 + d) * 4;
-                const uint32_t w = rand_word(cnt + d4 * 4 + d, k0, k1);
-                out[d] = quant_pack4(v[(j + 0) * CPL + c], v[(j + 1) * CPL + c], v[(j + 2) * CPL + c],
-                                     v[(j + 3) * CPL + c], inv[c], w);
-            }
-            if (PACKED)
-                *reinterpret_cast<uint2 *>(WqT + orow / 2 + d4 * 8) =
-                    make_uint2(nibble_pack8(out[0], out[1]), nibble_pack8(out[2], out[3]));
-            else
-                *reinterpret_cast<uint4 *>(WqT + orow + d4 * 16) = make_uint4(out[0], out[1], out[2], out[3]);
-        }
-        if (coeffT) {
-#pragma unroll
-            for (int j = 0; j < B; j += 4)
-                *reinterpret_cast<float4 *>(coeffT + orow + j) =
-                    make_float4(v[j * CPL + c], v[(j + 1) * CPL + c], v[(j + 2) * CPL + c], v[(j + 3) * CPL + c]);
-        }
-    }
+    cols_quantize_body<Tin, B, PACKED>(W, O, I, amax_bits, k0, k1, qmax, WqT, sW, coeffT, blockIdx.x, blockIdx.y);
 }
 
 size_t quant_cols_ws_bytes(int64_t /*O*/, int64_t I)
