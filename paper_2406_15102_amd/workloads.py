@@ -54,6 +54,20 @@ WORKLOADS = {
 }
 
 
+# The twelve layer shapes (L, O, I) of the paper's latency table (Sec. 7, "Latency profiling
+# results"), at batch 64 as in its memory table: N = 64 L.  p01-p06 are EfficientFormer-L1 layers
+# (recipe of c2), p07-p12 ResNet-34 layers (recipe of c3).  The second ResNet shape is printed
+# "(256, 128, 152)"; it is read as I = 1152 = 3*3*128, the only 3x3 layer with 128 channels.
+_PAPER_LAYERS = [(196, 224, 896), (196, 896, 224), (196, 224, 864), (196, 864, 224), (784, 96, 432), (784, 96, 384),
+                 (1024, 64, 576), (256, 128, 1152), (256, 128, 64), (64, 256, 1152), (64, 256, 128), (16, 512, 2304)]
+for _k, (_L, _O, _I) in enumerate(_PAPER_LAYERS):
+    _name = "p%02d" % (_k + 1)
+    WORKLOADS[_name] = Workload(_name, 6 if _k < 6 else 7, 64 * _L, _I, _O, 16, 8, "bf16", 0,
+                                "%s layer (L, O, I) = (%d, %d, %d) of the paper's latency table, batch 64"
+                                % ("EfficientFormer-L1" if _k < 6 else "ResNet-34", _L, _O, _I))
+_RECIPE = {6: 2, 7: 3}   # value distributions: as c2 (outlier channels, per-token spread) / as c3 (post-ReLU)
+
+
 def scaled(w: Workload, N: int | None = None, d_in: int | None = None, d_out: int | None = None,
            **kw) -> Workload:
     """Same recipe at another size (for parity cases the oracle finishes in seconds)."""
@@ -68,31 +82,32 @@ def generate(w: Workload, want=("X", "W", "G")):
     """Return {"X": [N,d_in], "W": [d_out,d_in], "G": [N,d_out]} as CPU torch tensors of w.dtype."""
     out = {}
     base = 1000 * w.id
+    rid = _RECIPE.get(w.id, w.id)
     aux = np.random.Generator(np.random.PCG64(base + 3))
     if "X" in want:
         rng = np.random.Generator(np.random.PCG64(base + 0))
-        if w.id == 3:
+        if rid == 3:
             X = np.maximum(_normal(rng, (w.N, w.d_in), 1.0), np.float32(0))
-        elif w.id == 5:
+        elif rid == 5:
             X = rng.standard_t(4.0, size=(w.N, w.d_in)).astype(np.float32)
         else:
             X = _normal(rng, (w.N, w.d_in), 1.0)
-            if w.id in (2, 4):
-                frac, gain = (0.02, 20.0) if w.id == 2 else (0.005, 50.0)
+            if rid in (2, 4):
+                frac, gain = (0.02, 20.0) if rid == 2 else (0.005, 50.0)
                 n_out = max(1, int(round(frac * w.d_in)))
                 ch = aux.choice(w.d_in, size=n_out, replace=False)
                 X[:, ch] *= np.float32(gain)
         out["X"] = X
     if "W" in want:
         rng = np.random.Generator(np.random.PCG64(base + 1))
-        std = {1: 0.02, 2: 0.02, 3: float(np.sqrt(2.0 / w.d_in)), 4: 0.02, 5: 0.01}[w.id]
+        std = {1: 0.02, 2: 0.02, 3: float(np.sqrt(2.0 / w.d_in)), 4: 0.02, 5: 0.01}[rid]
         out["W"] = _normal(rng, (w.d_out, w.d_in), std)
     if "G" in want:
         rng = np.random.Generator(np.random.PCG64(base + 2))
-        std = {1: 1e-3, 2: 1e-3, 3: 1e-3, 4: 1e-4, 5: 1e-4}[w.id]
+        std = {1: 1e-3, 2: 1e-3, 3: 1e-3, 4: 1e-4, 5: 1e-4}[rid]
         G = _normal(rng, (w.N, w.d_out), std)
-        if w.id in (2, 4):
-            sigma = 0.5 if w.id == 2 else 1.0
+        if rid in (2, 4):
+            sigma = 0.5 if rid == 2 else 1.0
             G *= np.exp(np.float32(sigma) * rng.standard_normal((w.N, 1), dtype=np.float32))
         out["G"] = G
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32

@@ -91,3 +91,27 @@ def test_full_size_workload_sampled(name):
     ew = row_rel_err(dW[torch.from_numpy(orows).to(DEV)].float().cpu().numpy(), ref_dW, True)
     print("%s: dX err %.3e (%d rows)  dW err %.3e (%d rows)" % (name, ex, len(rows), ew, len(orows)))
     assert ex < TOL_OUT and ew < TOL_OUT
+
+
+PAPER_LAYERS = ["p%02d" % k for k in range(1, 13)]
+
+
+@pytest.mark.parametrize("name", PAPER_LAYERS)
+def test_paper_latency_table_layers_in_full(name):
+    """The twelve layer shapes of the paper's latency table at batch 64: small enough for the oracle
+    to compute the whole backward pass, odd enough (d_out = 64 ... 896, d_in = 64 ... 2304, up to
+    65536 tokens) to visit tile and split plans the large workloads do not."""
+    w = wl.WORKLOADS[name]
+    N, I, O, B, r = w.N, w.d_in, w.d_out, w.B, w.r
+    t = wl.generate(w)
+    G, X, W = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
+    dX = torch.empty((N, I), dtype=torch.bfloat16, device=DEV)
+    dW = torch.empty((O, I), dtype=torch.bfloat16, device=DEV)
+    ws = torch.empty(hlq.hlq_workspace_bytes(N, I, O, B, r), dtype=torch.uint8, device=DEV)
+    hlq.hlq_linear_backward_ex(G, X, None, W, N, I, O, B, r, w.seed, dX, dW, ws)
+    torch.cuda.synchronize()
+    ref = oracle.linear_backward_mode(wl.as_f32_numpy(t["G"]), wl.as_f32_numpy(t["X"]), wl.as_f32_numpy(t["W"]), B, r, w.seed)
+    ex = row_rel_err(dX.float().cpu().numpy(), ref["dX"], True)
+    ew = row_rel_err(dW.float().cpu().numpy(), ref["dW"], True)
+    print("%s: dX err %.3e  dW err %.3e" % (name, ex, ew))
+    assert ex < TOL_OUT and ew < TOL_OUT
