@@ -254,6 +254,44 @@ int hlqo_quantize_rows_q(const float *C, long rows, long K, uint64_t seed, uint3
     return 0;
 }
 
+/* The paper's own source of rounding randomness (Sec. 6.1): "the lower 11 bits of floating-point   */
+/* data" of the value being quantised stand in for the random number, at no generation cost:      */
+/*   m = low 11 bits of the binary32 pattern of x,   u = (m + 0.5)/2048,   q = floor(x*inv + u)   */
+/* Nothing else changes.  It is only as random as those bits are: for values that carry fewer    */
+/* than 24 significant bits (sums of a few bf16 numbers) they are mostly zero and the quantiser   */
+/* degenerates to rounding down.                                                                  */
+int8_t hlqo_quantize_one_mantissa(float x, float inv, int qmax)
+{
+    uint32_t bits;
+    memcpy(&bits, &x, 4);
+    float u = ((float)(bits & 0x7FFu) + 0.5f) * 0.00048828125f;   /* / 2048, exact */
+    float t = fmaf(x, inv, u);
+    int q = (int)floorf(t);
+    if (q > qmax) q = qmax;
+    if (q < -qmax) q = -qmax;
+    return (int8_t)q;
+}
+
+int hlqo_quantize_rows_mantissa(const float *C, long rows, long K, int qmax, int8_t *q /* [rows,K] */,
+                                float *scale /* [rows] */)
+{
+    if (qmax != 7 && qmax != 127) return -1;
+    const float fq = (float)qmax;
+#pragma omp parallel for schedule(static)
+    for (long i = 0; i < rows; ++i) {
+        const float *c = C + i * K;
+        float a = 0.0f;
+        for (long k = 0; k < K; ++k) {
+            float m = fabsf(c[k]);
+            if (m > a) a = m;
+        }
+        float inv = (a > 0.0f) ? fq / a : 0.0f;
+        scale[i] = a / fq;
+        for (long k = 0; k < K; ++k) q[i * K + k] = hlqo_quantize_one_mantissa(c[k], inv, qmax);
+    }
+    return 0;
+}
+
 int hlqo_quantize_rows_at(const float *C, long rows, long K, uint64_t seed, uint32_t tensor,
                           const long *row_ids, int8_t *q, float *scale)
 {

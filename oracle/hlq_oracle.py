@@ -23,7 +23,8 @@ __all__ = [
     "build", "num_threads", "hadamard", "coeff_f32", "coeff_f64", "transform_rows",
     "transform_cols", "stream_key", "rand_word", "rand_byte", "quantize_one", "quantize_rows",
     "int_gemm_nt", "dequant", "hla_f32", "hla_f64", "round_bf16", "gemm_nt_f64",
-    "linear_backward", "BASIS_NATURAL", "BASIS_SEQUENCY", "basis_rows",
+    "linear_backward", "BASIS_NATURAL", "BASIS_SEQUENCY", "basis_rows", "ROUND_COUNTER", "ROUND_MANTISSA",
+    "quantize_one_mantissa",
 ]
 
 
@@ -73,6 +74,9 @@ def _L():
         lib.hlqo_hla_basis_f32.argtypes = [f32p, C.c_long, C.c_long, C.c_int, C.c_int, C.c_int, f32p]
         lib.hlqo_hla_basis_f64.argtypes = [f32p, C.c_long, C.c_long, C.c_int, C.c_int, C.c_int, f64p]
         lib.hlqo_basis_rows.argtypes = [C.c_int, C.c_int, C.POINTER(C.c_int)]
+        lib.hlqo_quantize_one_mantissa.argtypes = [C.c_float, C.c_float, C.c_int]
+        lib.hlqo_quantize_one_mantissa.restype = C.c_int8
+        lib.hlqo_quantize_rows_mantissa.argtypes = [f32p, C.c_long, C.c_long, C.c_int, i8p, f32p]
         lib.hlqo_round_bf16.argtypes = [C.c_float]
         lib.hlqo_round_bf16.restype = C.c_float
         lib.hlqo_round_bf16_array.argtypes = [f32p, C.c_long, f32p]
@@ -163,8 +167,18 @@ def quantize_one(x: float, inv: float, byte: int, qmax: int = 7) -> int:
     return int(_L().hlqo_quantize_one_q(float(np.float32(x)), float(np.float32(inv)), byte, qmax))
 
 
-def quantize_rows(Cm, seed: int, tensor: int, row_ids=None, qmax: int = 7):
+ROUND_COUNTER, ROUND_MANTISSA = 0, 1
+
+
+def quantize_one_mantissa(x: float, inv: float, qmax: int = 7) -> int:
+    return int(_L().hlqo_quantize_one_mantissa(float(np.float32(x)), float(np.float32(inv)), qmax))
+
+
+def quantize_rows(Cm, seed: int, tensor: int, row_ids=None, qmax: int = 7, rounding: int = 0):
     """Stochastic absmax quantiser, one scale per row -> (codes int8, scales fp32).
+
+    rounding = ROUND_MANTISSA: the paper's pseudo-stochastic rounding from the low 11 mantissa bits
+    of each value (seed, tensor and row_ids then play no part).
 
     qmax = 7: the 4-bit codes of the g_x path; qmax = 127: int8 codes (g_w path, 8-bit warm-up).
     tensor selects the random stream: 0 G, 1 W (g_x product); 2 projected X, 3 projected G (g_w).
@@ -174,6 +188,10 @@ def quantize_rows(Cm, seed: int, tensor: int, row_ids=None, qmax: int = 7):
     rows, K = Cm.shape
     q = np.empty((rows, K), dtype=np.int8)
     s = np.empty(rows, dtype=np.float32)
+    if rounding == ROUND_MANTISSA:
+        _check(_L().hlqo_quantize_rows_mantissa(_p(Cm, C.c_float), rows, K, qmax, _p(q, C.c_int8), _p(s, C.c_float)),
+               "quantize_rows_mantissa")
+        return q, s
     ids = None
     if row_ids is not None:
         ids = np.ascontiguousarray(row_ids, dtype=np.int64)
@@ -284,7 +302,7 @@ def linear_backward(G, X, W, B: int, r: int, seed: int, want_dX: bool = True, wa
 
 
 def linear_backward_mode(G, X, W, B: int, r: int, seed: int, gx_bits: int = 4, gw_int8: bool = False,
-                         basis: int = 0):
+                         basis: int = 0, rounding: int = 0):
     """Both stage lists of Sec. 6.1 composed stage by stage, with the two options of the method:
 
     gx_bits = 8   the g_x codes use [-127, 127] (the int8 warm-up phase of Sec. 7) instead of 4 bits;
@@ -292,23 +310,25 @@ def linear_backward_mode(G, X, W, B: int, r: int, seed: int, gx_bits: int = 4, g
                   multiplied in integers (stage 5) and dequantised (stage 6), instead of being kept
                   in bf16;
     basis         which r rows of H the g_w list keeps: 0 the first r in natural order, 1 the r of
-                  lowest sequency.
+                  lowest sequency;
+    rounding      ROUND_COUNTER (seeded stream) or ROUND_MANTISSA (the paper's low-11-bit scheme), for
+                  every quantiser of both lists.
     Returns a dict with dX, dW (fp64) and every intermediate."""
     G, X, W = _f32(G), _f32(X), _f32(W)
     qx = 7 if gx_bits == 4 else 127
     assert gx_bits in (4, 8)
     out = {}
     # g_x: 1. FWH(g_o) on O  2. Q  3. FWH(w) on O  4. Q  5. integer product  6. dequantise
-    Gq, sG = quantize_rows(transform_rows(G, B), seed, TENSOR_G, qmax=qx)
-    Wq, sW = quantize_rows(transform_cols(W, B), seed, TENSOR_W, qmax=qx)
+    Gq, sG = quantize_rows(transform_rows(G, B), seed, TENSOR_G, qmax=qx, rounding=rounding)
+    Wq, sW = quantize_rows(transform_cols(W, B), seed, TENSOR_W, qmax=qx, rounding=rounding)
     acc = int_gemm_nt(Gq, Wq)
     out.update(Gq=Gq, sG=sG, Wq=Wq, sW=sW, acc=acc, dX=dequant(acc, sG, sW, B))
     # g_w: 1. HLA(x) on L  2. Q8  3. HLA(g_o^T) on L  4. Q8  5. integer product  6. dequantise
     xh = hla_f32(X, B, r, basis)
     gh = hla_f32(G, B, r, basis)
     if gw_int8:
-        Xq, sX = quantize_rows(xh, seed, TENSOR_XHAT, qmax=127)
-        Gq2, sG2 = quantize_rows(gh, seed, TENSOR_GHAT, qmax=127)
+        Xq, sX = quantize_rows(xh, seed, TENSOR_XHAT, qmax=127, rounding=rounding)
+        Gq2, sG2 = quantize_rows(gh, seed, TENSOR_GHAT, qmax=127, rounding=rounding)
         accw = int_gemm_nt(Gq2, Xq)
         out.update(XqT=Xq, sX=sX, GqT=Gq2, sGhat=sG2, accw=accw, dW=dequant(accw, sG2, sX, B))
     else:
