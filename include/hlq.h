@@ -116,6 +116,12 @@ int hlq_compress_act(const void *X, int64_t N, int64_t d_in, int B, int r, int d
                                    code 2b+1 in the high nibble, two's complement; rows of d_out/2 bytes;
                                    needs d_out % 32 == 0.  The operand format of hlq_int4_gemm_nt. */
 
+#define HLQ_BITS_ROUND_MANTISSA 0x200 /* OR into any of the above: round by the low 11 bits of each value's own
+                                        fp32 pattern, u = (bits + 0.5) / 2048 -- the pseudo-stochastic quantiser
+                                        the paper describes (Sec. 6.1) -- instead of the seeded stream (seed is
+                                        then ignored).  Only as random as those bits: on coefficients of bf16
+                                        inputs it mostly rounds down. */
+
 /*
  * Stages 1-2 of the g_x list: block Hadamard transform of every row of G along d_out, then
  * stochastic quantisation with one absmax scale per row.
@@ -188,6 +194,8 @@ int hlq_hla_project(const void *T, int64_t N, int64_t D, int B, int r, int dtype
  */
 #define HLQ_BASIS_NATURAL 0
 #define HLQ_BASIS_SEQUENCY 1
+#define HLQ_BASIS_ROUND_MANTISSA 0x200 /* hlq_hla_quantize_basis only, OR into the basis: rounding as
+                                          HLQ_BITS_ROUND_MANTISSA */
 int hlq_hla_project_basis(const void *T, int64_t N, int64_t D, int B, int r, int basis, int dtype, void *ThatT,
                           float *coeffT, void *stream);
 
@@ -207,6 +215,8 @@ int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64
                               (stages 2, 4), integer product (5), dequantisation (6) */
 #define HLQ_FLAG_GW_SEQUENCY 8 /* g_w list keeps the r lowest-sequency coefficients (HLQ_BASIS_SEQUENCY); a
                                  forward-time store handed over as Xc must have been made the same way */
+#define HLQ_FLAG_ROUND_MANTISSA 16 /* every quantiser of both lists rounds by the values' low 11 mantissa bits
+                                     (HLQ_BITS_ROUND_MANTISSA); one launch per stage */
 #define HLQ_FLAG_GX_UNPACKED 4 /* keep the 4-bit g_x codes one per int8 between the stages.  By default
                                   they are stored two to a byte whenever d_out % 32 == 0 (same codes, same
                                   dX bit for bit; half the traffic). */

@@ -19,6 +19,8 @@ HLQ_BF16, HLQ_F32 = 0, 1
 HLQ_OK = 0
 HLQ_FLAG_GX_8BIT, HLQ_FLAG_GW_INT8, HLQ_FLAG_GX_UNPACKED, HLQ_FLAG_GW_SEQUENCY = 1, 2, 4, 8
 HLQ_BASIS_NATURAL, HLQ_BASIS_SEQUENCY = 0, 1
+HLQ_BITS_ROUND_MANTISSA = HLQ_BASIS_ROUND_MANTISSA = 0x200
+HLQ_FLAG_ROUND_MANTISSA = 16
 HLQ_BITS_4, HLQ_BITS_8, HLQ_BITS_4_PACKED = 4, 8, 0x104
 
 _EXPORTS = {

@@ -92,7 +92,7 @@ __device__ __forceinline__ void hla_absmax_body(const Tin *__restrict__ T, int64
     }
 }
 
-template <typename Tin, int B, int BASIS>
+template <typename Tin, int B, int BASIS, bool MANT = false>
 __device__ __forceinline__ void hla_quantize_body(const Tin *__restrict__ T, int64_t N, int D, int r,
                                                   const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
                                                   int8_t *__restrict__ TqT, float *__restrict__ sT,
@@ -122,9 +122,10 @@ __device__ __forceinline__ void hla_quantize_body(const Tin *__restrict__ T, int
 #pragma unroll
         for (int k = 0; k < B; k += 4) {
             if (k < r) {
-                const uint32_t w = rand_word(cnt + (k >> 2), k0, k1);
                 *reinterpret_cast<uint32_t *>(TqT + o + k) =
-                    quant_pack4(v[kept_row<B, BASIS>(k + 0) * CPL + c], v[kept_row<B, BASIS>(k + 1) * CPL + c], v[kept_row<B, BASIS>(k + 2) * CPL + c], v[kept_row<B, BASIS>(k + 3) * CPL + c], inv, w);
+                    quant_pack4r<MANT>(v[kept_row<B, BASIS>(k + 0) * CPL + c], v[kept_row<B, BASIS>(k + 1) * CPL + c],
+                                       v[kept_row<B, BASIS>(k + 2) * CPL + c], v[kept_row<B, BASIS>(k + 3) * CPL + c], inv,
+                                       cnt + (k >> 2), k0, k1);
                 if (coeffT)
                     *reinterpret_cast<float4 *>(coeffT + o + k) =
                         make_float4(v[kept_row<B, BASIS>(k + 0) * CPL + c], v[kept_row<B, BASIS>(k + 1) * CPL + c], v[kept_row<B, BASIS>(k + 2) * CPL + c], v[kept_row<B, BASIS>(k + 3) * CPL + c]);

@@ -105,7 +105,7 @@ Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_
 
 int check_flags(int flags, int r, int64_t N, int B)
 {
-    if (flags & ~(HLQ_FLAG_GX_8BIT | HLQ_FLAG_GW_INT8 | HLQ_FLAG_GX_UNPACKED | HLQ_FLAG_GW_SEQUENCY)) return HLQ_ERR_SHAPE;
+    if (flags & ~(HLQ_FLAG_GX_8BIT | HLQ_FLAG_GW_INT8 | HLQ_FLAG_GX_UNPACKED | HLQ_FLAG_GW_SEQUENCY | HLQ_FLAG_ROUND_MANTISSA)) return HLQ_ERR_SHAPE;
     if (flags & HLQ_FLAG_GW_INT8) {
         if (r % 4 != 0) return HLQ_ERR_RANK;
         if ((N / B * r) % 16 != 0) return HLQ_ERR_SHAPE;
@@ -113,9 +113,15 @@ int check_flags(int flags, int r, int64_t N, int B)
     return HLQ_OK;
 }
 
-inline bool bits_ok(int bits) { return bits == HLQ_BITS_4 || bits == HLQ_BITS_8 || bits == HLQ_BITS_4_PACKED; }
-inline float bits_qmax(int bits) { return bits == HLQ_BITS_8 ? 127.0f : 7.0f; }
-inline bool bits_packed(int bits) { return bits == HLQ_BITS_4_PACKED; }
+inline bool bits_mant(int bits) { return (bits & HLQ_BITS_ROUND_MANTISSA) != 0; }
+inline int bits_base(int bits) { return bits & ~HLQ_BITS_ROUND_MANTISSA; }
+inline bool bits_ok(int bits)
+{
+    const int b = bits_base(bits);
+    return b == HLQ_BITS_4 || b == HLQ_BITS_8 || b == HLQ_BITS_4_PACKED;
+}
+inline float bits_qmax(int bits) { return bits_base(bits) == HLQ_BITS_8 ? 127.0f : 7.0f; }
+inline bool bits_packed(int bits) { return bits_base(bits) == HLQ_BITS_4_PACKED; }
 
 // Library-owned workspace, one per device, grown on demand.
 constexpr int kMaxDevices = 64;
@@ -197,7 +203,7 @@ int hlq_quantize_g(const void *G, int64_t N, int64_t d_out, int B, uint64_t seed
     const uint64_t key = stream_key(seed, 0);
     return launch_rc(hlq::launch_quant_rows(G, N, static_cast<int>(d_out), B, dtype == HLQ_F32,
                                             static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32),
-                                            bits_qmax(bits), bits_packed(bits), Gq, sG, coeff,
+                                            bits_qmax(bits), bits_packed(bits), bits_mant(bits), Gq, sG, coeff,
                                             static_cast<hipStream_t>(stream)));
 }
 
@@ -223,7 +229,7 @@ int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t s
     const uint64_t key = stream_key(seed, 1);
     return launch_rc(hlq::launch_quant_cols(W, static_cast<int>(d_out), static_cast<int>(d_in), B, dtype == HLQ_F32,
                                             static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32),
-                                            bits_qmax(bits), bits_packed(bits), WqT, sW, coeffT, workspace,
+                                            bits_qmax(bits), bits_packed(bits), bits_mant(bits), WqT, sW, coeffT, workspace,
                                             static_cast<hipStream_t>(stream)));
 }
 
@@ -330,6 +336,8 @@ int hlq_hla_quantize_basis(const void *T, int64_t N, int64_t D, int B, int r, in
 {
     int rc;
     if (!T || !TqT || !sT || !workspace) return HLQ_ERR_NULL;
+    const bool mant = (basis & HLQ_BASIS_ROUND_MANTISSA) != 0;
+    basis &= ~HLQ_BASIS_ROUND_MANTISSA;
     if (basis != HLQ_BASIS_NATURAL && basis != HLQ_BASIS_SEQUENCY) return HLQ_ERR_RANK;
     if ((rc = check_block(B)) != HLQ_OK) return rc;
     if ((rc = check_rank(B, r)) != HLQ_OK) return rc;
@@ -343,7 +351,7 @@ int hlq_hla_quantize_basis(const void *T, int64_t N, int64_t D, int B, int r, in
     if (!aligned(workspace, 256) || workspace_bytes < hlq::hla_quant_ws_bytes(D)) return HLQ_ERR_WORKSPACE;
     const uint64_t key = stream_key(seed, static_cast<uint32_t>(tensor));
     return launch_rc(hlq::launch_hla_quant(T, N, static_cast<int>(D), B, r, basis, dtype == HLQ_F32,
-                                           static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32), TqT, sT,
+                                           static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32), mant, TqT, sT,
                                            coeffT, workspace, static_cast<hipStream_t>(stream)));
 }
 
@@ -368,6 +376,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     // 4-bit codes travel two to a byte whenever their rows stay 16-byte aligned that way
     const bool packed = !(flags & (HLQ_FLAG_GX_8BIT | HLQ_FLAG_GX_UNPACKED)) && d_out % 32 == 0;
     const int basis = (flags & HLQ_FLAG_GW_SEQUENCY) ? HLQ_BASIS_SEQUENCY : HLQ_BASIS_NATURAL;
+    const bool mant = (flags & HLQ_FLAG_ROUND_MANTISSA) != 0;
     if (!G || (!dX && !dW)) return HLQ_ERR_NULL;
     if (dX && !W && !(Wc && sWc)) return HLQ_ERR_NULL;
     if (Wc && (!aligned(Wc, 16) || !aligned(sWc, 16))) return HLQ_ERR_SHAPE;
@@ -408,7 +417,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     const float *sXh = sXc;
     // The transforms that depend on nothing share two launches when the shapes allow (k_front.hip);
     // the integer g_w list and very long rows of G keep one launch per stage.
-    const bool fusable = hlq::front_fusable(O, B);
+    const bool fusable = hlq::front_fusable(O, B) && !mant;   // the fused launches carry the seeded rounding only
     const bool fused = !gwi && fusable;
     const bool fused_q = gwi && fusable;
     const uint64_t kg = stream_key(seed, 0);
@@ -455,7 +464,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     if (dX && !fused && !fused_q) {
         // g_x stages 1-2: Q(G H)
         if ((rc = launch_rc(hlq::launch_quant_rows(G, N, O, B, f32, static_cast<uint32_t>(kg),
-                                                   static_cast<uint32_t>(kg >> 32), qmax, packed, Gq, sG, nullptr, st))) != HLQ_OK)
+                                                   static_cast<uint32_t>(kg >> 32), qmax, packed, mant, Gq, sG, nullptr, st))) != HLQ_OK)
             return rc;
     }
     if (dW && !gwi && !fused) {
@@ -471,14 +480,14 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         // g_w stages 3-4 and 1-2: HLA + int8 quantisation of G (stream 3) and of X (stream 2)
         const uint64_t k3 = stream_key(seed, 3), k2 = stream_key(seed, 2);
         if ((rc = launch_rc(hlq::launch_hla_quant(G, N, O, B, r, basis, f32, static_cast<uint32_t>(k3),
-                                                  static_cast<uint32_t>(k3 >> 32), static_cast<int8_t *>(Gh), sGh,
+                                                  static_cast<uint32_t>(k3 >> 32), mant, static_cast<int8_t *>(Gh), sGh,
                                                   nullptr, ws + L.hws, st))) != HLQ_OK)
             return rc;
         if (!xc) {
             int8_t *xq = reinterpret_cast<int8_t *>(ws + L.XhatT);
             float *sx = reinterpret_cast<float *>(ws + L.sXhat);
             if ((rc = launch_rc(hlq::launch_hla_quant(X, N, I, B, r, basis, f32, static_cast<uint32_t>(k2),
-                                                      static_cast<uint32_t>(k2 >> 32), xq, sx, nullptr, ws + L.hws,
+                                                      static_cast<uint32_t>(k2 >> 32), mant, xq, sx, nullptr, ws + L.hws,
                                                       st))) != HLQ_OK)
                 return rc;
             Xh = xq;
@@ -494,11 +503,11 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
             rc = HLQ_OK;
         else if (fused)   // pass 1 ran in the second front launch
             rc = launch_rc(hlq::launch_quant_cols_pass2(W, O, I, B, f32, static_cast<uint32_t>(kw),
-                                                        static_cast<uint32_t>(kw >> 32), qmax, packed, wq, sw,
-                                                        ws + L.wws, st));
+                                                        static_cast<uint32_t>(kw >> 32), qmax, packed, false, wq, sw,
+                                                        nullptr, ws + L.wws, st));
         else
             rc = launch_rc(hlq::launch_quant_cols(W, O, I, B, f32, static_cast<uint32_t>(kw),
-                                                  static_cast<uint32_t>(kw >> 32), qmax, packed, wq, sw, nullptr,
+                                                  static_cast<uint32_t>(kw >> 32), qmax, packed, mant, wq, sw, nullptr,
                                                   ws + L.wws, st));
         if (rc != HLQ_OK) return rc;
         // g_x stages 5-6: integer product and dequantisation (1/B undoes H H^T = B I)
@@ -528,8 +537,9 @@ int hlq_linear_backward_mode(const void *G, const void *X, const void *Xc, const
 
 int hlq_weight_code_bits(int64_t d_out, int flags)
 {
-    if (flags & HLQ_FLAG_GX_8BIT) return HLQ_BITS_8;
-    return (!(flags & HLQ_FLAG_GX_UNPACKED) && d_out % 32 == 0) ? HLQ_BITS_4_PACKED : HLQ_BITS_4;
+    const int round = (flags & HLQ_FLAG_ROUND_MANTISSA) ? HLQ_BITS_ROUND_MANTISSA : 0;
+    if (flags & HLQ_FLAG_GX_8BIT) return HLQ_BITS_8 | round;
+    return ((!(flags & HLQ_FLAG_GX_UNPACKED) && d_out % 32 == 0) ? HLQ_BITS_4_PACKED : HLQ_BITS_4) | round;
 }
 
 int hlq_linear_backward_cached(const void *G, const void *X, const void *Xc, const float *sXc, const void *WqT,

@@ -184,6 +184,30 @@ __device__ __forceinline__ uint32_t quant_pack4(float x0, float x1, float x2, fl
     return lo | hi;
 }
 
+// The paper's pseudo-stochastic rounding (Sec. 6.1): the low 11 bits of the value's own binary32
+// pattern replace the random number, u = (m + 0.5) / 2048 (exact, one fma).  A sign flip of the
+// value (see butterfly_lanes_signed) leaves those bits alone.
+__device__ __forceinline__ int quant_code_mantissa(float x, float inv)
+{
+    const float m = static_cast<float>(__float_as_uint(x) & 0x7FFu);
+    const float u = __builtin_fmaf(m, 0.00048828125f, 0.000244140625f);
+    return floor_to_int(__builtin_fmaf(x, inv, u));
+}
+
+// Four codes packed into a dword, rounding by the seeded stream (word `counter` of the stream keyed
+// by k0, k1) or, with MANT, by the values' own low mantissa bits.
+template <bool MANT>
+__device__ __forceinline__ uint32_t quant_pack4r(float x0, float x1, float x2, float x3, float inv, uint32_t counter,
+                                                 uint32_t k0, uint32_t k1)
+{
+    if (!MANT) return quant_pack4(x0, x1, x2, x3, inv, rand_word(counter, k0, k1));
+    const uint32_t q0 = static_cast<uint32_t>(quant_code_mantissa(x0, inv));
+    const uint32_t q1 = static_cast<uint32_t>(quant_code_mantissa(x1, inv));
+    const uint32_t q2 = static_cast<uint32_t>(quant_code_mantissa(x2, inv));
+    const uint32_t q3 = static_cast<uint32_t>(quant_code_mantissa(x3, inv));
+    return __builtin_amdgcn_perm(q1, q0, 0x0c0c0400u) | __builtin_amdgcn_perm(q3, q2, 0x04000c0cu);
+}
+
 // Eight 4-bit codes from two dwords of int8 codes (as quant_pack4 makes them), two to a byte:
 // code 2b in the low nibble of byte b, code 2b+1 in the high nibble, two's complement.
 __device__ __forceinline__ uint32_t nibble_pack8(uint32_t lo, uint32_t hi)

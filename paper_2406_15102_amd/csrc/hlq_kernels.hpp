@@ -9,19 +9,22 @@ namespace hlq {
 
 // K1: rows of G -> codes + per-row scales (and optionally the fp32 coefficients).  `packed`
 // (4-bit codes only): two codes to a byte, O/2 bytes per row, instead of one int8 each.
+// `mant`: round by the low 11 mantissa bits of each value instead of the seeded stream (k0, k1 unused).
 hipError_t launch_quant_rows(const void *G, int64_t N, int O, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                             float qmax, bool packed, int8_t *Gq, float *sG, float *coeff, hipStream_t st);
+                             float qmax, bool packed, bool mant, int8_t *Gq, float *sG, float *coeff, hipStream_t st);
 
 // K1T: W [O, I] -> WqT [I, O] codes + per-in-feature scales.  `ws` holds the partial column
 // maxima and the reciprocal scales: quant_cols_ws_bytes(O, I) bytes.
 size_t quant_cols_ws_bytes(int64_t O, int64_t I);
 hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                             float qmax, bool packed, int8_t *WqT, float *sW, float *coeffT, void *ws, hipStream_t st);
+                             float qmax, bool packed, bool mant, int8_t *WqT, float *sW, float *coeffT, void *ws,
+                             hipStream_t st);
 
 // K1T split in its two passes, for callers that run pass 1 elsewhere (the fused front launches):
 // pass 2 alone, reading the column maxima pass 1 left in `ws`.
 hipError_t launch_quant_cols_pass2(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                                   float qmax, bool packed, int8_t *WqT, float *sW, const void *ws, hipStream_t st);
+                                   float qmax, bool packed, bool mant, int8_t *WqT, float *sW, float *coeffT,
+                                   const void *ws, hipStream_t st);
 
 // The independent transforms of one backward pass in two launches (k_front.hip).  A job with a
 // null tensor is empty.
@@ -97,7 +100,7 @@ hipError_t launch_hla(const void *T, int64_t N, int D, int B, int r, int basis, 
 // column maxima: hla_quant_ws_bytes(D) bytes.  Needs r % 4 == 0.
 size_t hla_quant_ws_bytes(int64_t D);
 hipError_t launch_hla_quant(const void *T, int64_t N, int D, int B, int r, int basis, bool is_f32, uint32_t k0,
-                            uint32_t k1, int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st);
+                            uint32_t k1, bool mant, int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st);
 
 // K2 / K4: C = alpha * sA (x) sB * (A . Bm^T).  kind 0: int8 operands, int32 accumulate;
 // kind 1: bf16 operands, fp32 accumulate.  K in elements.

@@ -73,20 +73,20 @@ __global__ __launch_bounds__(256) void k_hla_absmax(const Tin *__restrict__ T, i
     hla_absmax_body<Tin, B, BASIS>(T, N, D, r, amax_bits, blockIdx.x, blockIdx.y);
 }
 
-template <typename Tin, int B, int BASIS>
+template <typename Tin, int B, int BASIS, bool MANT>
 __global__ __launch_bounds__(256) void k_hla_quantize(const Tin *__restrict__ T, int64_t N, int D, int r,
                                                       const uint32_t *__restrict__ amax_bits, uint32_t k0,
                                                       uint32_t k1, int8_t *__restrict__ TqT, float *__restrict__ sT,
                                                       float *__restrict__ coeffT)
 {
-    hla_quantize_body<Tin, B, BASIS>(T, N, D, r, amax_bits, k0, k1, TqT, sT, coeffT, blockIdx.x, blockIdx.y);
+    hla_quantize_body<Tin, B, BASIS, MANT>(T, N, D, r, amax_bits, k0, k1, TqT, sT, coeffT, blockIdx.x, blockIdx.y);
 }
 
 size_t hla_quant_ws_bytes(int64_t D) { return (static_cast<size_t>(D) * 4 + 255) & ~static_cast<size_t>(255); }
 
 template <typename Tin, int B, int BASIS>
-static hipError_t launch_hla_quant_t(const void *T, int64_t N, int D, int r, uint32_t k0, uint32_t k1, int8_t *TqT,
-                                     float *sT, float *coeffT, void *ws, hipStream_t st)
+static hipError_t launch_hla_quant_t(const void *T, int64_t N, int D, int r, uint32_t k0, uint32_t k1, bool mant,
+                                     int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st)
 {
     constexpr int CPL = 128 / B;
     const int64_t nblk = N / B;
@@ -95,20 +95,23 @@ static hipError_t launch_hla_quant_t(const void *T, int64_t N, int D, int r, uin
     dim3 grid((D + 64 * CPL - 1) / (64 * CPL), static_cast<unsigned>((nblk + 3) / 4));
     hipLaunchKernelGGL(k_hla_fill_u32, dim3((D + 255) / 256), dim3(256), 0, st, amax, D, 0u);
     hipLaunchKernelGGL((k_hla_absmax<Tin, B, BASIS>), grid, dim3(256), 0, st, t, N, D, r, amax);
-    hipLaunchKernelGGL((k_hla_quantize<Tin, B, BASIS>), grid, dim3(256), 0, st, t, N, D, r, amax, k0, k1, TqT, sT, coeffT);
+    if (mant)
+        hipLaunchKernelGGL((k_hla_quantize<Tin, B, BASIS, true>), grid, dim3(256), 0, st, t, N, D, r, amax, k0, k1, TqT, sT, coeffT);
+    else
+        hipLaunchKernelGGL((k_hla_quantize<Tin, B, BASIS, false>), grid, dim3(256), 0, st, t, N, D, r, amax, k0, k1, TqT, sT, coeffT);
     return hipGetLastError();
 }
 
 hipError_t launch_hla_quant(const void *T, int64_t N, int D, int B, int r, int basis, bool is_f32, uint32_t k0,
-                            uint32_t k1, int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st)
+                            uint32_t k1, bool mant, int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st)
 {
 #define HLQ_HLAQ_CASE(BB)                                                                                  \
     case BB:                                                                                               \
         if (basis)                                                                                         \
-            return is_f32 ? launch_hla_quant_t<float, BB, 1>(T, N, D, r, k0, k1, TqT, sT, coeffT, ws, st)  \
-                          : launch_hla_quant_t<bf16_t, BB, 1>(T, N, D, r, k0, k1, TqT, sT, coeffT, ws, st); \
-        return is_f32 ? launch_hla_quant_t<float, BB, 0>(T, N, D, r, k0, k1, TqT, sT, coeffT, ws, st)      \
-                      : launch_hla_quant_t<bf16_t, BB, 0>(T, N, D, r, k0, k1, TqT, sT, coeffT, ws, st);
+            return is_f32 ? launch_hla_quant_t<float, BB, 1>(T, N, D, r, k0, k1, mant, TqT, sT, coeffT, ws, st)  \
+                          : launch_hla_quant_t<bf16_t, BB, 1>(T, N, D, r, k0, k1, mant, TqT, sT, coeffT, ws, st); \
+        return is_f32 ? launch_hla_quant_t<float, BB, 0>(T, N, D, r, k0, k1, mant, TqT, sT, coeffT, ws, st)      \
+                      : launch_hla_quant_t<bf16_t, BB, 0>(T, N, D, r, k0, k1, mant, TqT, sT, coeffT, ws, st);
     switch (B) {
         HLQ_HLAQ_CASE(16)
         HLQ_HLAQ_CASE(32)

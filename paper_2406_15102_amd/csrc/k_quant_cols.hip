@@ -33,13 +33,13 @@ __global__ __launch_bounds__(256) void k_cols_absmax(const Tin *__restrict__ W, 
     cols_absmax_body<Tin, B>(W, O, I, amax_bits, blockIdx.x, blockIdx.y);
 }
 
-template <typename Tin, int B, bool PACKED>
+template <typename Tin, int B, bool PACKED, bool MANT>
 __global__ __launch_bounds__(256) void k_cols_quantize(const Tin *__restrict__ W, int O, int I,
                                                        const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
                                                        float qmax, int8_t *__restrict__ WqT, float *__restrict__ sW,
                                                        float *__restrict__ coeffT)
 {
-    cols_quantize_body<Tin, B, PACKED>(W, O, I, amax_bits, k0, k1, qmax, WqT, sW, coeffT, blockIdx.x, blockIdx.y);
+    cols_quantize_body<Tin, B, PACKED, MANT>(W, O, I, amax_bits, k0, k1, qmax, WqT, sW, coeffT, blockIdx.x, blockIdx.y);
 }
 
 size_t quant_cols_ws_bytes(int64_t /*O*/, int64_t I)
@@ -49,44 +49,43 @@ size_t quant_cols_ws_bytes(int64_t /*O*/, int64_t I)
 }
 
 template <typename Tin, int B>
-static hipError_t launch_cols_t(const void *W, int O, int I, uint32_t k0, uint32_t k1, float qmax, bool packed, int8_t *WqT,
-                                float *sW, float *coeffT, void *ws, hipStream_t st)
+static hipError_t launch_cols_pass1_t(const void *W, int O, int I, void *ws, hipStream_t st)
 {
     constexpr int CPL = 128 / B;
     uint32_t *amax = static_cast<uint32_t *>(ws);
-    const Tin *w = static_cast<const Tin *>(W);
     dim3 grid((I + 64 * CPL - 1) / (64 * CPL), (O + 4 * B - 1) / (4 * B));
     hipLaunchKernelGGL(k_fill_u32, dim3((I + 255) / 256), dim3(256), 0, st, amax, I, 0u);
-    hipLaunchKernelGGL((k_cols_absmax<Tin, B>), grid, dim3(256), 0, st, w, O, I, amax);
-    if (packed)
-        hipLaunchKernelGGL((k_cols_quantize<Tin, B, true>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, coeffT);
-    else
-        hipLaunchKernelGGL((k_cols_quantize<Tin, B, false>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, coeffT);
+    hipLaunchKernelGGL((k_cols_absmax<Tin, B>), grid, dim3(256), 0, st, static_cast<const Tin *>(W), O, I, amax);
     return hipGetLastError();
 }
 
 template <typename Tin, int B>
 static hipError_t launch_cols_pass2_t(const void *W, int O, int I, uint32_t k0, uint32_t k1, float qmax, bool packed,
-                                      int8_t *WqT, float *sW, const void *ws, hipStream_t st)
+                                      bool mant, int8_t *WqT, float *sW, float *coeffT, const void *ws, hipStream_t st)
 {
     constexpr int CPL = 128 / B;
     const uint32_t *amax = static_cast<const uint32_t *>(ws);
     const Tin *w = static_cast<const Tin *>(W);
     dim3 grid((I + 64 * CPL - 1) / (64 * CPL), (O + 4 * B - 1) / (4 * B));
-    if (packed)
-        hipLaunchKernelGGL((k_cols_quantize<Tin, B, true>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, nullptr);
-    else
-        hipLaunchKernelGGL((k_cols_quantize<Tin, B, false>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, nullptr);
+#define HLQ_COLS2_LAUNCH(P, M) \
+    hipLaunchKernelGGL((k_cols_quantize<Tin, B, P, M>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, coeffT)
+    if (packed) {
+        if (mant) HLQ_COLS2_LAUNCH(true, true); else HLQ_COLS2_LAUNCH(true, false);
+    } else {
+        if (mant) HLQ_COLS2_LAUNCH(false, true); else HLQ_COLS2_LAUNCH(false, false);
+    }
+#undef HLQ_COLS2_LAUNCH
     return hipGetLastError();
 }
 
 hipError_t launch_quant_cols_pass2(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                                   float qmax, bool packed, int8_t *WqT, float *sW, const void *ws, hipStream_t st)
+                                   float qmax, bool packed, bool mant, int8_t *WqT, float *sW, float *coeffT,
+                                   const void *ws, hipStream_t st)
 {
-#define HLQ_COLS2_CASE(BB)                                                                                   \
-    case BB:                                                                                                 \
-        return is_f32 ? launch_cols_pass2_t<float, BB>(W, O, I, k0, k1, qmax, packed, WqT, sW, ws, st)       \
-                      : launch_cols_pass2_t<bf16_t, BB>(W, O, I, k0, k1, qmax, packed, WqT, sW, ws, st);
+#define HLQ_COLS2_CASE(BB)                                                                                               \
+    case BB:                                                                                                             \
+        return is_f32 ? launch_cols_pass2_t<float, BB>(W, O, I, k0, k1, qmax, packed, mant, WqT, sW, coeffT, ws, st)     \
+                      : launch_cols_pass2_t<bf16_t, BB>(W, O, I, k0, k1, qmax, packed, mant, WqT, sW, coeffT, ws, st);
     switch (B) {
         HLQ_COLS2_CASE(16)
         HLQ_COLS2_CASE(32)
@@ -97,19 +96,22 @@ hipError_t launch_quant_cols_pass2(const void *W, int O, int I, int B, bool is_f
 }
 
 hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
-                             float qmax, bool packed, int8_t *WqT, float *sW, float *coeffT, void *ws, hipStream_t st)
+                             float qmax, bool packed, bool mant, int8_t *WqT, float *sW, float *coeffT, void *ws,
+                             hipStream_t st)
 {
+    hipError_t e = hipErrorInvalidValue;
 #define HLQ_COLS_CASE(BB)                                                                            \
     case BB:                                                                                         \
-        return is_f32 ? launch_cols_t<float, BB>(W, O, I, k0, k1, qmax, packed, WqT, sW, coeffT, ws, st)           \
-                      : launch_cols_t<bf16_t, BB>(W, O, I, k0, k1, qmax, packed, WqT, sW, coeffT, ws, st);
+        e = is_f32 ? launch_cols_pass1_t<float, BB>(W, O, I, ws, st) : launch_cols_pass1_t<bf16_t, BB>(W, O, I, ws, st); \
+        break;
     switch (B) {
         HLQ_COLS_CASE(16)
         HLQ_COLS_CASE(32)
         HLQ_COLS_CASE(64)
     }
 #undef HLQ_COLS_CASE
-    return hipErrorInvalidValue;
+    if (e != hipSuccess) return e;
+    return launch_quant_cols_pass2(W, O, I, B, is_f32, k0, k1, qmax, packed, mant, WqT, sW, coeffT, ws, st);
 }
 
 }  // namespace hlq

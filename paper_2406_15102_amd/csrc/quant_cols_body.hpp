@@ -47,7 +47,7 @@ __device__ __forceinline__ void cols_absmax_body(const Tin *__restrict__ W, int 
 
 // pass 2: transform again, quantise against the column maxima, write the codes transposed.
 // PACKED: the codes are written two to a byte (4-bit codes only), O/2 bytes per row of WqT.
-template <typename Tin, int B, bool PACKED>
+template <typename Tin, int B, bool PACKED, bool MANT = false>
 __device__ __forceinline__ void cols_quantize_body(const Tin *__restrict__ W, int O, int I,
                                                    const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
                                                    float qmax, int8_t *__restrict__ WqT, float *__restrict__ sW,
@@ -80,9 +80,8 @@ __device__ __forceinline__ void cols_quantize_body(const Tin *__restrict__ W, in
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 const int j = (d4 * 4 + d) * 4;
-                const uint32_t w = rand_word(cnt + d4 * 4 + d, k0, k1);
-                out[d] = quant_pack4(v[(j + 0) * CPL + c], v[(j + 1) * CPL + c], v[(j + 2) * CPL + c],
-                                     v[(j + 3) * CPL + c], inv[c], w);
+                out[d] = quant_pack4r<MANT>(v[(j + 0) * CPL + c], v[(j + 1) * CPL + c], v[(j + 2) * CPL + c],
+                                            v[(j + 3) * CPL + c], inv[c], cnt + d4 * 4 + d, k0, k1);
             }
             if (PACKED)
                 *reinterpret_cast<uint2 *>(WqT + orow / 2 + d4 * 8) =

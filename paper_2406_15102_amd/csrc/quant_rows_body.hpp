@@ -8,7 +8,7 @@ namespace hlq {
 constexpr int K1_MAXC = 8;  // chunks of 8 elements per lane
 
 // PACKED: the codes are written two to a byte (4-bit codes only), O/2 bytes per row.
-template <typename Tin, int B, int BLOCK, bool PACKED>
+template <typename Tin, int B, int BLOCK, bool PACKED, bool MANT = false>
 __device__ __forceinline__ void quant_rows_body(const Tin *__restrict__ G, int64_t N, int O, int T, uint32_t k0,
                                                 uint32_t k1, float qmax, int8_t *__restrict__ Gq,
                                                 float *__restrict__ sG, float *__restrict__ coeff, int bx)
@@ -78,11 +78,9 @@ __device__ __forceinline__ void quant_rows_body(const Tin *__restrict__ G, int64
     for (int m = 0; m < K1_MAXC; ++m) {
         const int ci = g + m * T;
         if (ci < nch) {
-            const uint32_t w0 = rand_word(cbase + 2u * ci, k0, k1);
-            const uint32_t w1 = rand_word(cbase + 2u * ci + 1u, k0, k1);
             uint2 out;
-            out.x = quant_pack4(v[m][0], v[m][1], v[m][2], v[m][3], inv, w0);
-            out.y = quant_pack4(v[m][4], v[m][5], v[m][6], v[m][7], inv, w1);
+            out.x = quant_pack4r<MANT>(v[m][0], v[m][1], v[m][2], v[m][3], inv, cbase + 2u * ci, k0, k1);
+            out.y = quant_pack4r<MANT>(v[m][4], v[m][5], v[m][6], v[m][7], inv, cbase + 2u * ci + 1u, k0, k1);
             if (PACKED) *reinterpret_cast<uint32_t *>(qrow + static_cast<int64_t>(ci) * 4) = nibble_pack8(out.x, out.y);
             else *reinterpret_cast<uint2 *>(qrow + static_cast<int64_t>(ci) * 8) = out;
             if (coeff) {
