@@ -404,8 +404,8 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     const int Kc = static_cast<int>(N / B * r);
     const float invB = 1.0f / static_cast<float>(B);
 
-    // Launch order: everything that streams G first (the second reader then finds it in the
-    // last-level cache), then X, then the two passes over W back to back, then the two products.
+    // Launch order: the readers of G next to each other (the second one finds it in the last-level
+    // cache), the two passes over W back to back, then the two products.
     int8_t *Gq = reinterpret_cast<int8_t *>(ws + L.Gq);
     float *sG = reinterpret_cast<float *>(ws + L.sG);
     const bool wc = (Wc != nullptr);
@@ -415,8 +415,9 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     float *sGh = reinterpret_cast<float *>(ws + L.sGhat);
     const void *Xh = Xc;
     const float *sXh = sXc;
-    // The transforms that depend on nothing share two launches when the shapes allow (k_front.hip);
-    // the integer g_w list and very long rows of G keep one launch per stage.
+    // The transforms that depend on nothing share launches when the shapes allow (k_front.hip): two
+    // for the default path, three for the integer g_w list.  Very long rows of G and the
+    // mantissa-bit rounding keep one launch per stage.
     const bool fusable = hlq::front_fusable(O, B) && !mant;   // the fused launches carry the seeded rounding only
     const bool fused = !gwi && fusable;
     const bool fused_q = gwi && fusable;
