@@ -87,6 +87,7 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
         for (int j = 0; j < WN; ++j) acc[i][j] = Mma<KIND>::zero();
 
     u32x4 ra[PA], rb[PB];
+    bool keepN = true;                 // TAIL, spread schedule: the flag of the step being loaded
     bool keepA = true, keepB = true;   // TAIL: whether this thread's chunk of the step in ra / rb lies inside the row
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     // k steps of this workgroup: all of them, or the split's share [kbeg, kbeg + nk)
@@ -160,6 +161,29 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
         _Pragma("unroll") for (int i = 1; i < WM; ++i)                                                        \
             fa[BUF][i] = *reinterpret_cast<const u32x4 *>(ldsb + rdA[KS] + i * (32 * KCH * 16));              \
     }
+    // one fragment / one staging register at a time, for the schedule that spreads them out
+#define HLQ_READ_ONE(BUF, KS, Q)                                                                              \
+    {                                                                                                         \
+        if ((Q) == 0) fb[BUF][0] = *reinterpret_cast<const u32x4 *>(ldsb + rdB[KS]);                          \
+        else if ((Q) == 1) fa[BUF][0] = *reinterpret_cast<const u32x4 *>(ldsb + rdA[KS]);                     \
+        else if ((Q) < 1 + WN) fb[BUF][(Q) - 1] = *reinterpret_cast<const u32x4 *>(ldsb + rdB[KS] + ((Q) - 1) * (32 * KCH * 16)); \
+        else fa[BUF][(Q) - WN] = *reinterpret_cast<const u32x4 *>(ldsb + rdA[KS] + ((Q) - WN) * (32 * KCH * 16)); \
+    }
+#define HLQ_STORE_ONE(W_)                                                                                     \
+    {                                                                                                         \
+        if ((W_) < PA)                                                                                        \
+            *reinterpret_cast<u32x4 *>(ldsb + wr_off + (W_) * (RPP * KCH * 16)) = (!TAIL || keepA) ? ra[(W_) < PA ? (W_) : 0] : zero4; \
+        else                                                                                                  \
+            *reinterpret_cast<u32x4 *>(ldsb + wr_off + (BM * KCH * 16) + ((W_) - PA) * (RPP * KCH * 16)) =    \
+                (!TAIL || keepB) ? rb[(W_) >= PA ? (W_) - PA : 0] : zero4;                                    \
+    }
+#define HLQ_LOAD_ONE(W_, KT)                                                                                  \
+    {                                                                                                         \
+        HLQ_KOFS(KT)                                                                                          \
+        if ((W_) < PA) ra[(W_) < PA ? (W_) : 0] = __builtin_amdgcn_raw_buffer_load_b128(rsA, offa[(W_) < PA ? (W_) : 0] + kfix, kuni, 0); \
+        else rb[(W_) >= PA ? (W_) - PA : 0] = __builtin_amdgcn_raw_buffer_load_b128(rsB, offb[(W_) >= PA ? (W_) - PA : 0] + kfix, kuni, 0); \
+        keepN = kok;                                                                                          \
+    }
 #define HLQ_TOGGLE_STAGE()                                                                                    \
     {                                                                                                         \
         _Pragma("unroll") for (int ks = 0; ks < NS; ++ks) { rdA[ks] ^= STAGE_BYTES; rdB[ks] ^= STAGE_BYTES; } \
@@ -194,6 +218,8 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
         Mma<2>::expand(fb[0][0], pb[0], pb[1]);
     }
     constexpr int MPS = KIND == 2 ? 2 : 1;   // MFMAs per accumulator and sub-step
+    constexpr bool SPREAD = KIND != 2 && WM == 4 && WN == 4;   // schedule with the staging writes spread out
+    static_assert(!SPREAD || (PA == 8 && PB == 8), "the spread schedule publishes 8 + 8 staging registers");
 
     static_assert(NS == 4, "the staging schedule below is written for four sub-steps per step");
 
@@ -202,6 +228,47 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
 #pragma unroll
         for (int ks = 0; ks < NS; ++ks) {
             const int cur = ks & 1;
+            if constexpr (SPREAD) {
+                // LDS writes in consecutive MFMA slots hold the MFMA stream up (measured: ~17 cycles
+                // each), one write per two MFMAs costs nothing.  So the 16 staging writes of a step go
+                // out one per two MFMAs over the first three sub-steps (6 + 6 + 4), between the
+                // fragment reads, each followed one slot later by the global load that refills its
+                // register.  Memory instructions are written here in the order they are to issue: LDS
+                // accesses keep their program order.
+                const int WC = ks == 0 ? 6 : (ks == 1 ? 6 : (ks == 2 ? 4 : 0));   // writes of this sub-step
+                const int W0 = ks == 0 ? 0 : (ks == 1 ? 6 : 12);                   // first of them
+                if (ks == NS - 1) HLQ_TOGGLE_STAGE()
+#pragma unroll
+                for (int q = 0; q < WM * WN; ++q) {
+                    if (q < WM + WN) {
+                        if (ks < NS - 1) HLQ_READ_ONE(cur ^ 1, ks + 1, q)
+                        else HLQ_READ_ONE(cur ^ 1, 0, q)
+                    }
+                    if ((q & 1) && (q >> 1) < WC) HLQ_STORE_ONE(W0 + (q >> 1))
+                    if (!(q & 1) && q >= 2 && ((q - 2) >> 1) < WC) HLQ_LOAD_ONE(W0 + ((q - 2) >> 1), kt2)
+                }
+#pragma unroll
+                for (int i = 0; i < WM; ++i)
+#pragma unroll
+                    for (int j = 0; j < WN; ++j) acc[i][j] = Mma<KIND>::mma(fb[cur][j], fa[cur][i], acc[i][j]);
+#pragma unroll
+                for (int q = 0; q < WM * WN; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    if (q < WM + WN) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    if ((q & 1) && (q >> 1) < WC) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);
+                    if (!(q & 1) && q >= 2 && ((q - 2) >> 1) < WC) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                }
+                if (ks == NS - 2) {
+                    wr_off ^= STAGE_BYTES;
+                    keepA = keepB = keepN;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (ks == NS - 2) {
+                    lds_barrier();
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                continue;
+            }
             if (ks < NS - 1) {
                 HLQ_READ_FRAGS(cur ^ 1, ks + 1)
             } else {
@@ -291,6 +358,9 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
 #undef HLQ_STORE_LDS_B
 #undef HLQ_READ_FRAGS
 #undef HLQ_TOGGLE_STAGE
+#undef HLQ_READ_ONE
+#undef HLQ_STORE_ONE
+#undef HLQ_LOAD_ONE
 
     // ---- epilogue ----
     __syncthreads();   // all fragment reads are done: LDS is free for staging C
