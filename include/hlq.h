@@ -147,7 +147,8 @@ int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t s
 
 /*
  * Stages 5-6 of the g_x list: C[m, n] = alpha * sA[m] * sB[n] * sum_k A[m,k] * Bm[n,k], the sum
- * exact in int32 (int8 MFMA).  A [M, K] int8, Bm [Nn, K] int8, K % 16 == 0, Nn % 4 == 0.
+ * exact in int32 (int8 MFMA).  A [M, K] int8, Bm [Nn, K] int8 with |value| <= 127, K % 16 == 0,
+ * K <= 131072 (so that 127 * 127 * K fits int32), Nn % 4 == 0.
  *   out_dtype HLQ_BF16 / HLQ_F32 selects the type of C [M, Nn]; C may be NULL.
  *   acc: NULL or [M, Nn] int32 receiving the raw accumulators.  sA, sB may be NULL (= all ones).
  *   workspace: NULL, or device scratch (16-byte aligned) of hlq_gemm_workspace_bytes(0, M, Nn, K)
@@ -253,7 +254,7 @@ int hlq_compress_act_int8(const void *X, int64_t N, int64_t d_in, int B, int r, 
  *             Xc when dW is wanted.
  *   flags     any combination of HLQ_FLAG_*; 0 = hlq_linear_backward_ex.
  *   workspace >= hlq_workspace_bytes_mode(...) bytes, 256-aligned, or NULL for the library-owned one.
- * HLQ_FLAG_GW_INT8 additionally needs r % 4 == 0 (HLQ_ERR_RANK) and (N/B*r) % 16 == 0.
+ * HLQ_FLAG_GW_INT8 additionally needs r % 4 == 0 (HLQ_ERR_RANK), (N/B*r) % 16 == 0 and N/B*r <= 131072.
  */
 size_t hlq_workspace_bytes_mode(int64_t N, int64_t d_in, int64_t d_out, int B, int r, int x_is_compressed,
                                 int flags);

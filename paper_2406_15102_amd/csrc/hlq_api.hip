@@ -44,6 +44,10 @@ int check_hla_shape(int64_t N, int64_t D, int B, int r)
     return HLQ_OK;
 }
 
+// Longest reduction of the integer products: 127 * 127 * K (8-bit codes) and 256 * 49 * K (packed 4-bit
+// codes, accumulated times 256) must stay below 2^31.
+constexpr int64_t kMaxIntK = 131072;
+
 int check_gemm_shape(int64_t M, int64_t Nn, int64_t K, int kmult)
 {
     if (M <= 0 || Nn <= 0 || K <= 0 || K % kmult != 0 || Nn % 4 != 0) return HLQ_ERR_SHAPE;
@@ -236,6 +240,7 @@ int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t s
 size_t hlq_gemm_workspace_bytes(int kind, int64_t M, int64_t Nn, int64_t K)
 {
     if (kind < 0 || kind > 2 || check_gemm_shape(M, Nn, K, kind == 0 ? 16 : (kind == 1 ? 8 : 32)) != HLQ_OK) return 0;
+    if (kind != 1 && K > kMaxIntK) return 0;
     return hlq::gemm_ws_bytes(kind, static_cast<int>(M), static_cast<int>(Nn), static_cast<int>(K));
 }
 
@@ -247,6 +252,7 @@ int hlq_int8_gemm_nt(const int8_t *A, const int8_t *Bm, int64_t M, int64_t Nn, i
     if (!A || !Bm || (!C && !acc)) return HLQ_ERR_NULL;
     if ((rc = check_dtype(out_dtype)) != HLQ_OK) return rc;
     if ((rc = check_gemm_shape(M, Nn, K, 16)) != HLQ_OK) return rc;
+    if (K > kMaxIntK) return HLQ_ERR_SHAPE;
     if (!aligned(A, 16) || !aligned(Bm, 16) || (C && !aligned(C, 16)) || (acc && !aligned(acc, 16)) ||
         (sB && !aligned(sB, 16)))
         return HLQ_ERR_SHAPE;
@@ -264,7 +270,7 @@ int hlq_int4_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64
     if (!A || !Bm || (!C && !acc)) return HLQ_ERR_NULL;
     if ((rc = check_dtype(out_dtype)) != HLQ_OK) return rc;
     if ((rc = check_gemm_shape(M, Nn, K, 32)) != HLQ_OK) return rc;
-    if (K > 131072) return HLQ_ERR_SHAPE;   // 256 * 49 * K must fit the int32 accumulators
+    if (K > kMaxIntK) return HLQ_ERR_SHAPE;   // 256 * 49 * K must fit the int32 accumulators
     if (!aligned(A, 16) || !aligned(Bm, 16) || (C && !aligned(C, 16)) || (acc && !aligned(acc, 16)) ||
         (sB && !aligned(sB, 16)))
         return HLQ_ERR_SHAPE;
@@ -387,6 +393,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         return HLQ_ERR_SHAPE;
     if (gwi && static_cast<int64_t>(d_out > d_in ? d_out : d_in) * (N / B * r / 4) >= (int64_t(1) << 32))
         return HLQ_ERR_SHAPE;
+    if (gwi && N / B * r > kMaxIntK) return HLQ_ERR_SHAPE;   // int32 accumulators of the int8 dW product
 
     const bool xc = (Xc != nullptr);
     const Layout L = make_layout(N, d_in, d_out, B, r, xc, flags);

@@ -93,6 +93,7 @@ def test_stage_entry_points_reject_bad_arguments_without_a_gpu():
     assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 64, 40, None, None, 1.0, 1, FAKE, None, None, 0, None) == 2   # K % 16
     assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 62, 64, None, None, 1.0, 1, FAKE, None, None, 0, None) == 2   # Nn % 4
     assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 64, 64, None, None, 1.0, 1, None, None, None, 0, None) == 1
+    assert l.hlq_int8_gemm_nt(FAKE, FAKE, 64, 64, 131072 + 16, None, None, 1.0, 1, FAKE, None, None, 0, None) == 2   # int32 range
     assert l.hlq_quantize_g(FAKE, 16, 48, 16, 0, 0, 0x104, FAKE, FAKE, None, None) == 2     # packed rows: d_out % 32
     assert l.hlq_quantize_w(FAKE, 48, 256, 16, 0, 0, 0x104, FAKE, FAKE, None, FAKE, 1 << 20, None) == 2
     assert l.hlq_int4_gemm_nt(FAKE, FAKE, 64, 64, 48, None, None, 1.0, 1, FAKE, None, None, 0, None) == 2   # K % 32

@@ -72,6 +72,7 @@ def test_packed_rows_need_32_codes():
 GEMM_CASES = [
     (256, 256, 128, False), (300, 260, 256, False), (100, 36, 352, False), (260, 132, 96, False),
     (700, 520, 640, False), (384, 3072, 6272, True), (130, 516, 11008, True),
+    (72, 68, 131072, False), (72, 68, 131072, True),      # longest supported reduction: 256 * 49 * K still fits int32
 ]
 
 
