@@ -24,7 +24,7 @@ __all__ = [
     "transform_cols", "stream_key", "rand_word", "rand_byte", "quantize_one", "quantize_rows",
     "int_gemm_nt", "dequant", "hla_f32", "hla_f64", "round_bf16", "gemm_nt_f64",
     "linear_backward", "BASIS_NATURAL", "BASIS_SEQUENCY", "basis_rows", "ROUND_COUNTER", "ROUND_MANTISSA",
-    "quantize_one_mantissa",
+    "quantize_one_mantissa", "conv_out_size", "im2col", "col2im", "conv2d_backward",
 ]
 
 
@@ -334,4 +334,68 @@ def linear_backward_mode(G, X, W, B: int, r: int, seed: int, gx_bits: int = 4, g
     else:
         xh, gh = round_bf16(xh), round_bf16(gh)
         out.update(XhatT=xh, GhatT=gh, dW=gemm_nt_f64(gh, xh, 1.0 / B))
+    return out
+
+
+# ---- convolution layers: the same products with the spatial positions as the sequence (Sec. 3.1) ----
+# Tensors are channels-last: x [Nb, H, W, C], g [Nb, Ho, Wo, O], w [O, kh, kw, C].  Row t = (n, ho, wo)
+# of the column matrix holds the receptive field of output position (ho, wo) of sample n, its
+# columns ordered (ky, kx, c), which is the order of w's trailing axes; taps outside the image are 0.
+
+def conv_out_size(size: int, k: int, stride: int, pad: int, dil: int) -> int:
+    """Number of output positions along one spatial axis."""
+    return (size + 2 * pad - dil * (k - 1) - 1) // stride + 1
+
+
+def im2col(x, kh: int, kw: int, stride=(1, 1), pad=(0, 0), dil=(1, 1)) -> np.ndarray:
+    """x [Nb, H, W, C] -> column matrix [Nb*Ho*Wo, kh*kw*C] (same dtype), by the definition."""
+    x = np.asarray(x)
+    Nb, H, W, Cc = x.shape
+    Ho = conv_out_size(H, kh, stride[0], pad[0], dil[0])
+    Wo = conv_out_size(W, kw, stride[1], pad[1], dil[1])
+    cols = np.zeros((Nb, Ho, Wo, kh, kw, Cc), dtype=x.dtype)
+    for ky in range(kh):
+        for kx in range(kw):
+            for ho in range(Ho):
+                hi = ho * stride[0] - pad[0] + ky * dil[0]
+                if hi < 0 or hi >= H:
+                    continue
+                for wo in range(Wo):
+                    wi = wo * stride[1] - pad[1] + kx * dil[1]
+                    if 0 <= wi < W:
+                        cols[:, ho, wo, ky, kx, :] = x[:, hi, wi, :]
+    return cols.reshape(Nb * Ho * Wo, kh * kw * Cc)
+
+
+def col2im(cols, x_shape, kh: int, kw: int, stride=(1, 1), pad=(0, 0), dil=(1, 1)) -> np.ndarray:
+    """Adjoint of im2col: every entry of the column matrix is added to the pixel it was copied from
+    (fp64 sums) -> [Nb, H, W, C]."""
+    Nb, H, W, Cc = x_shape
+    Ho = conv_out_size(H, kh, stride[0], pad[0], dil[0])
+    Wo = conv_out_size(W, kw, stride[1], pad[1], dil[1])
+    cols = np.asarray(cols, dtype=np.float64).reshape(Nb, Ho, Wo, kh, kw, Cc)
+    dx = np.zeros((Nb, H, W, Cc), dtype=np.float64)
+    for ky in range(kh):
+        for kx in range(kw):
+            for ho in range(Ho):
+                hi = ho * stride[0] - pad[0] + ky * dil[0]
+                if hi < 0 or hi >= H:
+                    continue
+                for wo in range(Wo):
+                    wi = wo * stride[1] - pad[1] + kx * dil[1]
+                    if 0 <= wi < W:
+                        dx[:, hi, wi, :] += cols[:, ho, wo, ky, kx, :]
+    return dx
+
+
+def conv2d_backward(G4, X4, W4, B: int, r: int, seed: int, stride=(1, 1), pad=(0, 0), dil=(1, 1), **mode):
+    """HLQ backward pass of a convolution: column matrix of x, both stage lists of Sec. 6.1 on
+    (g [N, O], columns [N, kh*kw*C], w [O, kh*kw*C]) with N = Nb*Ho*Wo, then the column gradient
+    folded back onto the image.  Returns linear_backward_mode's dict plus dX_img, dW_k."""
+    G4, X4, W4 = _f32(G4), _f32(X4), _f32(W4)
+    O, kh, kw, Cc = W4.shape
+    out = linear_backward_mode(G4.reshape(-1, O), im2col(X4, kh, kw, stride, pad, dil), W4.reshape(O, -1),
+                               B, r, seed, **mode)
+    out["dX_img"] = col2im(out["dX"], X4.shape, kh, kw, stride, pad, dil)
+    out["dW_k"] = out["dW"].reshape(O, kh, kw, Cc)
     return out
