@@ -287,6 +287,55 @@ int hlq_linear_backward_cached(const void *G, const void *X, const void *Xc, con
  */
 int hlq_mfma_probe(int kind, int blocks, int iters, float *sink, void *stream);
 
+/* ---- convolution layers ------------------------------------------------------------------------ */
+
+/*
+ * Sec. 3.1: a convolution is optimised by the same technique with the spatial positions as the
+ * sequence (L = H.W): its backward pass is the linear layer's on the column matrix of the input.
+ * All tensors are channels-last, dense, device memory:
+ *   X [Nb, H, W, C],  G [Nb, Ho, Wo, O] (= [N, O] with N = Nb*Ho*Wo),  Wt [O, kh, kw, C] (= [O, I]
+ *   with I = kh*kw*C),  Ho = (H + 2 pad_h - dil_h (kh-1) - 1) / stride_h + 1, Wo likewise.
+ * The geometry is a host struct read during the call.
+ */
+typedef struct hlq_conv_geom {
+    int32_t Nb, H, W, C;                 /* input image batch */
+    int32_t O, kh, kw;                   /* filters */
+    int32_t stride_h, stride_w, pad_h, pad_w, dil_h, dil_w;
+} hlq_conv_geom;
+
+/* Output extent and the sizes of the equivalent linear layer; HLQ_ERR_SHAPE for a geometry with a
+ * non-positive field (sizes, strides, dilations < 1; pads < 0), an empty output, or N, I, W*C, Nb*H or a
+ * padded image axis (H + 2 pad_h + kh dil_h, same for W) of 2^31 or more.
+ * Any of the output pointers may be NULL. */
+int hlq_conv_sizes(const hlq_conv_geom *g, int64_t *Ho, int64_t *Wo, int64_t *N, int64_t *I);
+
+/*
+ * Column matrix: cols [N, I], row (n, ho, wo), column (ky, kx, c) -- the order of Wt's trailing
+ * axes -- holding X[n, ho stride_h - pad_h + ky dil_h, wo stride_w - pad_w + kx dil_w, c], or 0
+ * outside the image.  A pure copy in `dtype`.  X, cols 16-byte aligned.
+ */
+int hlq_im2col(const void *X, const hlq_conv_geom *g, int dtype, void *cols, void *stream);
+
+/*
+ * The adjoint: dX [Nb, H, W, C], each pixel the sum of the entries of cols [N, I] copied from it
+ * by hlq_im2col, added in fp32 in ascending (ky, kx) order and rounded once to `dtype`.  Every pixel
+ * is written (pixels no output position reads get 0).
+ */
+int hlq_col2im(const void *cols, const hlq_conv_geom *g, int dtype, void *dX, void *stream);
+
+/*
+ * Backward pass of the convolution: hlq_im2col(X), then hlq_linear_backward_mode on (G, cols, Wt)
+ * with the N, d_in = I, d_out = O above (same B, r, seed, flags, shape rules and status codes), then
+ * hlq_col2im of the column gradient.  dX [Nb, H, W, C] and dW [O, kh, kw, C] of `dtype`; either may
+ * be NULL.  A 1x1 kernel with unit stride and no padding is its own column matrix: no copy is made.
+ * The column gradient is held in `dtype` before it is folded.
+ *   workspace >= hlq_conv_workspace_bytes(...) bytes, 256-aligned; or NULL for the library-owned one.
+ */
+size_t hlq_conv_workspace_bytes(const hlq_conv_geom *g, int B, int r, int dtype, int flags);
+int hlq_conv2d_backward(const void *G, const void *X, const void *Wt, const hlq_conv_geom *g, int B, int r,
+                        uint64_t seed, int dtype, int flags, void *dX, void *dW, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

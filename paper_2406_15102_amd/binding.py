@@ -23,6 +23,16 @@ HLQ_BITS_ROUND_MANTISSA = HLQ_BASIS_ROUND_MANTISSA = 0x200
 HLQ_FLAG_ROUND_MANTISSA = 16
 HLQ_BITS_4, HLQ_BITS_8, HLQ_BITS_4_PACKED = 4, 8, 0x104
 
+
+
+class hlq_conv_geom(C.Structure):
+    """Geometry of a convolution layer, field for field the C struct of the same name."""
+    _fields_ = [(n, C.c_int32) for n in ("Nb", "H", "W", "C", "O", "kh", "kw", "stride_h", "stride_w", "pad_h",
+                                           "pad_w", "dil_h", "dil_w")]
+
+
+_GEOM_P = C.POINTER(hlq_conv_geom)
+
 _EXPORTS = {
     "hlq_status_str": (C.c_char_p, [C.c_int]),
     "hlq_version": (C.c_int, []),
@@ -63,6 +73,12 @@ _EXPORTS = {
     "hlq_bf16_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_float, C.c_int,
                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hlq_mfma_probe": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
+    "hlq_conv_sizes": (C.c_int, [_GEOM_P] + [C.POINTER(C.c_int64)] * 4),
+    "hlq_im2col": (C.c_int, [C.c_void_p, _GEOM_P, C.c_int, C.c_void_p, C.c_void_p]),
+    "hlq_col2im": (C.c_int, [C.c_void_p, _GEOM_P, C.c_int, C.c_void_p, C.c_void_p]),
+    "hlq_conv_workspace_bytes": (C.c_size_t, [_GEOM_P, C.c_int, C.c_int, C.c_int, C.c_int]),
+    "hlq_conv2d_backward": (C.c_int, [C.c_void_p] * 3 + [_GEOM_P, C.c_int, C.c_int, C.c_uint64, C.c_int, C.c_int]
+                            + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]),
 }
 
 _lib = None
@@ -290,3 +306,29 @@ def hlq_hla_quantize_basis(T, B, r, basis, seed, tensor, TqT, sT, workspace, coe
     _check(lib().hlq_hla_quantize_basis(_ptr(T), N, D, B, r, basis, seed, tensor, _dt(T), _ptr(TqT, torch.int8),
                                         _ptr(sT, torch.float32), _ptr(coeffT, torch.float32), _ptr(workspace),
                                         _nbytes(workspace), _stream()), "hlq_hla_quantize_basis")
+
+
+def hlq_conv_sizes(geom):
+    """-> (Ho, Wo, N, I) of the geometry."""
+    v = [C.c_int64() for _ in range(4)]
+    _check(lib().hlq_conv_sizes(C.byref(geom), *[C.byref(x) for x in v]), "hlq_conv_sizes")
+    return tuple(int(x.value) for x in v)
+
+
+def hlq_im2col(X, geom, cols):
+    _check(lib().hlq_im2col(_ptr(X), C.byref(geom), _dt(X), _ptr(cols, X.dtype), _stream()), "hlq_im2col")
+
+
+def hlq_col2im(cols, geom, dX):
+    _check(lib().hlq_col2im(_ptr(cols), C.byref(geom), _dt(cols), _ptr(dX, cols.dtype), _stream()), "hlq_col2im")
+
+
+def hlq_conv_workspace_bytes(geom, B, r, dtype, flags=0) -> int:
+    return int(lib().hlq_conv_workspace_bytes(C.byref(geom), B, r, dtype, flags))
+
+
+def hlq_conv2d_backward(G, X, Wt, geom, B, r, seed, flags, dX, dW, workspace=None):
+    """Channels-last G [Nb, Ho, Wo, O], X [Nb, H, W, C], Wt [O, kh, kw, C] -> dX, dW of the same layouts."""
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (_ptr(workspace), _nbytes(workspace))
+    _check(lib().hlq_conv2d_backward(_ptr(G), _ptr(X), _ptr(Wt), C.byref(geom), B, r, seed, _dt(G), flags, _ptr(dX),
+                                     _ptr(dW), ws_ptr, ws_bytes, _stream()), "hlq_conv2d_backward")

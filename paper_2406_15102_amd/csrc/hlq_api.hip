@@ -369,20 +369,16 @@ int hlq_compress_act_int8(const void *X, int64_t N, int64_t d_in, int B, int r, 
 
 // The whole path.  Either W (quantised here, every call) or its codes and scales as hlq_quantize_w
 // left them (Wc, sWc): the weight changes once per optimiser step, not once per micro-batch.
-static int backward_impl(const void *G, const void *X, const void *Xc, const float *sXc, const void *W, const void *Wc,
-                         const float *sWc, int64_t N, int64_t d_in, int64_t d_out, int B, int r, uint64_t seed, int dtype,
-                         int flags, void *dX, void *dW, void *workspace, size_t workspace_bytes, void *stream)
+// Everything backward_impl refuses, tested before the first launch.
+static int backward_check(const void *G, const void *X, const void *Xc, const float *sXc, const void *W, const void *Wc,
+                          const float *sWc, int64_t N, int64_t d_in, int64_t d_out, int B, int r, int dtype, int flags,
+                          const void *dX, const void *dW)
 {
     int rc;
     if ((rc = check_backward_shape(N, d_in, d_out, B, r)) != HLQ_OK) return rc;
     if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
     if ((rc = check_flags(flags, r, N, B)) != HLQ_OK) return rc;
     const bool gwi = (flags & HLQ_FLAG_GW_INT8) != 0;
-    const float qmax = (flags & HLQ_FLAG_GX_8BIT) ? 127.0f : 7.0f;
-    // 4-bit codes travel two to a byte whenever their rows stay 16-byte aligned that way
-    const bool packed = !(flags & (HLQ_FLAG_GX_8BIT | HLQ_FLAG_GX_UNPACKED)) && d_out % 32 == 0;
-    const int basis = (flags & HLQ_FLAG_GW_SEQUENCY) ? HLQ_BASIS_SEQUENCY : HLQ_BASIS_NATURAL;
-    const bool mant = (flags & HLQ_FLAG_ROUND_MANTISSA) != 0;
     if (!G || (!dX && !dW)) return HLQ_ERR_NULL;
     if (dX && !W && !(Wc && sWc)) return HLQ_ERR_NULL;
     if (Wc && (!aligned(Wc, 16) || !aligned(sWc, 16))) return HLQ_ERR_SHAPE;
@@ -394,6 +390,21 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     if (gwi && static_cast<int64_t>(d_out > d_in ? d_out : d_in) * (N / B * r / 4) >= (int64_t(1) << 32))
         return HLQ_ERR_SHAPE;
     if (gwi && N / B * r > kMaxIntK) return HLQ_ERR_SHAPE;   // int32 accumulators of the int8 dW product
+    return HLQ_OK;
+}
+
+static int backward_impl(const void *G, const void *X, const void *Xc, const float *sXc, const void *W, const void *Wc,
+                         const float *sWc, int64_t N, int64_t d_in, int64_t d_out, int B, int r, uint64_t seed, int dtype,
+                         int flags, void *dX, void *dW, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc;
+    if ((rc = backward_check(G, X, Xc, sXc, W, Wc, sWc, N, d_in, d_out, B, r, dtype, flags, dX, dW)) != HLQ_OK) return rc;
+    const bool gwi = (flags & HLQ_FLAG_GW_INT8) != 0;
+    const float qmax = (flags & HLQ_FLAG_GX_8BIT) ? 127.0f : 7.0f;
+    // 4-bit codes travel two to a byte whenever their rows stay 16-byte aligned that way
+    const bool packed = !(flags & (HLQ_FLAG_GX_8BIT | HLQ_FLAG_GX_UNPACKED)) && d_out % 32 == 0;
+    const int basis = (flags & HLQ_FLAG_GW_SEQUENCY) ? HLQ_BASIS_SEQUENCY : HLQ_BASIS_NATURAL;
+    const bool mant = (flags & HLQ_FLAG_ROUND_MANTISSA) != 0;
 
     const bool xc = (Xc != nullptr);
     const Layout L = make_layout(N, d_in, d_out, B, r, xc, flags);
@@ -573,6 +584,141 @@ int hlq_linear_backward(const void *G, const void *X, const void *W, int64_t N, 
 {
     if (!G || !X || !W || !dX || !dW) return HLQ_ERR_NULL;
     return hlq_linear_backward_ex(G, X, nullptr, W, N, d_in, d_out, B, r, seed, HLQ_BF16, dX, dW, nullptr, 0, stream);
+}
+
+// ---- convolution layers (Sec. 3.1) ---------------------------------------------------------------
+
+static int conv_shape(const hlq_conv_geom *g, hlq::ConvShape *out)
+{
+    if (!g) return HLQ_ERR_NULL;
+    if (g->Nb < 1 || g->H < 1 || g->W < 1 || g->C < 1 || g->O < 1 || g->kh < 1 || g->kw < 1 || g->stride_h < 1 ||
+        g->stride_w < 1 || g->dil_h < 1 || g->dil_w < 1 || g->pad_h < 0 || g->pad_w < 0)
+        return HLQ_ERR_SHAPE;
+    const int64_t eh = static_cast<int64_t>(g->H) + 2 * static_cast<int64_t>(g->pad_h) -
+                       static_cast<int64_t>(g->dil_h) * (g->kh - 1) - 1;
+    const int64_t ew = static_cast<int64_t>(g->W) + 2 * static_cast<int64_t>(g->pad_w) -
+                       static_cast<int64_t>(g->dil_w) * (g->kw - 1) - 1;
+    if (eh < 0 || ew < 0) return HLQ_ERR_SHAPE;
+    const int64_t Ho = eh / g->stride_h + 1, Wo = ew / g->stride_w + 1;
+    const int64_t N = g->Nb * Ho * Wo, I = static_cast<int64_t>(g->kh) * g->kw * g->C;
+    const int64_t limit = int64_t(1) << 31;
+    // the kernels index inside one row of either tensor, and one padded image axis, in 32 bits
+    if (N >= limit || I >= limit || static_cast<int64_t>(g->W) * g->C >= limit ||
+        static_cast<int64_t>(g->Nb) * g->H >= limit ||
+        static_cast<int64_t>(g->H) + 2 * static_cast<int64_t>(g->pad_h) + static_cast<int64_t>(g->kh) * g->dil_h >= limit ||
+        static_cast<int64_t>(g->W) + 2 * static_cast<int64_t>(g->pad_w) + static_cast<int64_t>(g->kw) * g->dil_w >= limit)
+        return HLQ_ERR_SHAPE;
+    hlq::ConvShape c{g->Nb, g->H, g->W, g->C, g->kh, g->kw, g->stride_h, g->stride_w, g->pad_h, g->pad_w,
+                     g->dil_h, g->dil_w, static_cast<int>(Ho), static_cast<int>(Wo), N};
+    if (out) *out = c;
+    return HLQ_OK;
+}
+
+static inline bool conv_is_pointwise(const hlq_conv_geom *g)
+{
+    return g->kh == 1 && g->kw == 1 && g->stride_h == 1 && g->stride_w == 1 && g->pad_h == 0 && g->pad_w == 0;
+}
+
+int hlq_conv_sizes(const hlq_conv_geom *g, int64_t *Ho, int64_t *Wo, int64_t *N, int64_t *I)
+{
+    hlq::ConvShape c;
+    const int rc = conv_shape(g, &c);
+    if (rc != HLQ_OK) return rc;
+    if (Ho) *Ho = c.Ho;
+    if (Wo) *Wo = c.Wo;
+    if (N) *N = c.N;
+    if (I) *I = static_cast<int64_t>(c.kh) * c.kw * c.C;
+    return HLQ_OK;
+}
+
+int hlq_im2col(const void *X, const hlq_conv_geom *g, int dtype, void *cols, void *stream)
+{
+    int rc;
+    hlq::ConvShape c;
+    if (!X || !cols) return HLQ_ERR_NULL;
+    if ((rc = conv_shape(g, &c)) != HLQ_OK) return rc;
+    if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if (!aligned(X, 16) || !aligned(cols, 16)) return HLQ_ERR_SHAPE;
+    return launch_rc(hlq::launch_im2col(X, c, dtype == HLQ_F32, cols, static_cast<hipStream_t>(stream)));
+}
+
+int hlq_col2im(const void *cols, const hlq_conv_geom *g, int dtype, void *dX, void *stream)
+{
+    int rc;
+    hlq::ConvShape c;
+    if (!cols || !dX) return HLQ_ERR_NULL;
+    if ((rc = conv_shape(g, &c)) != HLQ_OK) return rc;
+    if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if (!aligned(cols, 16) || !aligned(dX, 16)) return HLQ_ERR_SHAPE;
+    return launch_rc(hlq::launch_col2im(cols, c, dtype == HLQ_F32, dX, static_cast<hipStream_t>(stream)));
+}
+
+// workspace of the convolution pass: [column matrix | column gradient | the linear pass's own]
+struct ConvLayout {
+    size_t cols, dcols, inner, inner_bytes, total;
+};
+
+static ConvLayout conv_layout(const hlq::ConvShape &c, const hlq_conv_geom *g, int B, int r, int dtype, int flags)
+{
+    const int64_t I = static_cast<int64_t>(c.kh) * c.kw * c.C;
+    const size_t mat = conv_is_pointwise(g) ? 0 : up256(static_cast<size_t>(c.N) * I * (dtype == HLQ_F32 ? 4 : 2));
+    ConvLayout L;
+    L.cols = 0;
+    L.dcols = mat;
+    L.inner = 2 * mat;
+    L.inner_bytes = hlq_workspace_bytes_mode(c.N, I, g->O, B, r, 0, flags);
+    L.total = L.inner + L.inner_bytes;
+    return L;
+}
+
+size_t hlq_conv_workspace_bytes(const hlq_conv_geom *g, int B, int r, int dtype, int flags)
+{
+    hlq::ConvShape c;
+    if (conv_shape(g, &c) != HLQ_OK || check_dtype(dtype) != HLQ_OK) return 0;
+    const ConvLayout L = conv_layout(c, g, B, r, dtype, flags);
+    return L.inner_bytes == 0 ? 0 : L.total;
+}
+
+int hlq_conv2d_backward(const void *G, const void *X, const void *Wt, const hlq_conv_geom *g, int B, int r,
+                        uint64_t seed, int dtype, int flags, void *dX, void *dW, void *workspace,
+                        size_t workspace_bytes, void *stream)
+{
+    int rc;
+    hlq::ConvShape c;
+    if ((rc = conv_shape(g, &c)) != HLQ_OK) return rc;
+    if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    const int64_t I = static_cast<int64_t>(c.kh) * c.kw * c.C;
+    const bool pointwise = conv_is_pointwise(g);
+    // every refusal of the linear pass, before anything is launched (the column matrix stands in
+    // for X; its address inside the workspace is aligned by construction)
+    if ((rc = backward_check(G, dW ? X : nullptr, nullptr, nullptr, dX ? Wt : nullptr, nullptr, nullptr, c.N, I, g->O, B,
+                             r, dtype, flags, dX, dW)) != HLQ_OK)
+        return rc;
+    const ConvLayout L = conv_layout(c, g, B, r, dtype, flags);
+    char *ws = static_cast<char *>(workspace);
+    if (ws) {
+        if (!aligned(ws, 256) || workspace_bytes < L.total) return HLQ_ERR_WORKSPACE;
+    } else {
+        void *p = nullptr;
+        if ((rc = own_workspace(L.total, &p)) != HLQ_OK) return rc;
+        ws = static_cast<char *>(p);
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const bool f32 = dtype == HLQ_F32;
+    const void *xmat = X;
+    void *dxmat = dX;
+    if (!pointwise) {
+        if (dW) {
+            if ((rc = launch_rc(hlq::launch_im2col(X, c, f32, ws + L.cols, st))) != HLQ_OK) return rc;
+            xmat = ws + L.cols;
+        }
+        if (dX) dxmat = ws + L.dcols;
+    }
+    rc = backward_impl(G, dW ? xmat : nullptr, nullptr, nullptr, dX ? Wt : nullptr, nullptr, nullptr, c.N, I, g->O, B, r,
+                       seed, dtype, flags, dxmat, dW, ws + L.inner, L.inner_bytes, stream);
+    if (rc != HLQ_OK) return rc;
+    if (!pointwise && dX) return launch_rc(hlq::launch_col2im(dxmat, c, f32, dX, st));
+    return HLQ_OK;
 }
 
 }  // extern "C"

@@ -123,6 +123,16 @@ hipError_t launch_splitk_reduce(int kind, const GemmArgs &a, int splits, hipStre
 // (few output tiles, long reduction); 0 if the plan does not split.
 size_t gemm_ws_bytes(int kind, int M, int N, int K);
 
+// Convolution glue (k_conv.hip), channels-last tensors.  N = Nb * Ho * Wo rows of the column matrix.
+struct ConvShape {
+    int Nb, H, W, C, kh, kw, sh, sw, ph, pw, dh, dw, Ho, Wo;
+    int64_t N;
+};
+// x [Nb, H, W, C] -> cols [N, kh*kw*C], columns ordered (ky, kx, c), zero padding
+hipError_t launch_im2col(const void *X, const ConvShape &g, bool is_f32, void *cols, hipStream_t st);
+// cols [N, kh*kw*C] -> dx [Nb, H, W, C]: each pixel sums the entries copied from it (fp32, fixed order)
+hipError_t launch_col2im(const void *cols, const ConvShape &g, bool is_f32, void *dx, hipStream_t st);
+
 // Diagnostic: `blocks` workgroups of 4 wavefronts each run `iters` x 8 independent 32x32 MFMAs
 // (kind 0: i8, K = 32; kind 1: bf16, K = 16) from registers.
 hipError_t launch_mfma_probe(int kind, int blocks, int iters, float *sink, hipStream_t st);

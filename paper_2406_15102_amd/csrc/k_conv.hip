@@ -1,0 +1,151 @@
+// Convolution layers (arXiv 2406.15102, Sec. 3.1): a convolution is the linear layer's product
+// with the spatial positions as the sequence, so its backward pass is the same two stage lists on
+// the column matrix of the input.  This file holds the two pieces of glue around them, for
+// channels-last tensors:
+//   column matrix   x [Nb, H, W, C] -> cols [Nb*Ho*Wo, kh*kw*C]; row t = (n, ho, wo) is the receptive
+//                   field of output position (ho, wo), columns ordered (ky, kx, c) like the trailing
+//                   axes of a channels-last weight [O, kh, kw, C]; taps outside the image read 0;
+//   fold            its adjoint: pixel (n, h, w, c) of the image gradient is the sum of every
+//                   entry of the column gradient that was copied from it, added in fp32 in
+//                   ascending (ky, kx) order (deterministic), rounded once to the output type.
+// Both are plain HBM-bound data movement.  A wavefront owns one row of its output (one output
+// position's receptive field, or one image row), so the decomposition of the row index into
+// (n, y, x) is wave-uniform and each lane spends two integer divisions per 16 bytes moved;
+// lanes walk the row in 16-byte units (8 bf16 / 4 fp32 channels) when the channel count allows,
+// else element by element.
+#include "hlq_device.hpp"
+#include "hlq_kernels.hpp"
+
+namespace hlq {
+
+template <int VB> struct Unit;
+template <> struct Unit<16> { typedef uint4 type; };
+template <> struct Unit<4> { typedef uint32_t type; };
+template <> struct Unit<2> { typedef uint16_t type; };
+
+// Cu = channels in units of VB bytes
+template <int VB>
+__global__ __launch_bounds__(256) void k_im2col(const void *__restrict__ X, ConvShape g, int Cu, void *__restrict__ cols)
+{
+    typedef typename Unit<VB>::type U;
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (t >= g.N) return;
+    const int lane = threadIdx.x & 63;
+    const int wo = static_cast<int>(t % g.Wo);
+    const int64_t t2 = t / g.Wo;
+    const int ho = static_cast<int>(t2 % g.Ho);
+    const int64_t n = t2 / g.Ho;
+    const int h0 = ho * g.sh - g.ph, w0 = wo * g.sw - g.pw;
+    const U *x = static_cast<const U *>(X) + n * g.H * g.W * Cu;
+    const int row_units = g.kh * g.kw * Cu;
+    U *out = static_cast<U *>(cols) + t * row_units;
+    for (int v = lane; v < row_units; v += 64) {
+        const int tap = v / Cu, cu = v - tap * Cu;
+        const int ky = tap / g.kw, kx = tap - ky * g.kw;
+        const int hi = h0 + ky * g.dh, wi = w0 + kx * g.dw;
+        U val = {};
+        if (hi >= 0 && hi < g.H && wi >= 0 && wi < g.W) val = x[(static_cast<int64_t>(hi) * g.W + wi) * Cu + cu];
+        out[v] = val;
+    }
+}
+
+template <typename T> struct Chan;
+template <> struct Chan<bf16_t> {
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ void add(const bf16_t *p, float *s)
+    {
+        const uint4 q = *reinterpret_cast<const uint4 *>(p);
+        s[0] += bf16_lo(q.x); s[1] += bf16_hi(q.x); s[2] += bf16_lo(q.y); s[3] += bf16_hi(q.y);
+        s[4] += bf16_lo(q.z); s[5] += bf16_hi(q.z); s[6] += bf16_lo(q.w); s[7] += bf16_hi(q.w);
+    }
+    static __device__ __forceinline__ void store(bf16_t *p, const float *s)
+    {
+        uint4 q = {pack_bf16(s[0], s[1]), pack_bf16(s[2], s[3]), pack_bf16(s[4], s[5]), pack_bf16(s[6], s[7])};
+        *reinterpret_cast<uint4 *>(p) = q;
+    }
+    static __device__ __forceinline__ float load1(const bf16_t *p) { return bf16_lo(*p); }
+    static __device__ __forceinline__ void store1(bf16_t *p, float s) { *p = static_cast<bf16_t>(pack_bf16(s, 0.0f) & 0xFFFFu); }
+};
+template <> struct Chan<float> {
+    static constexpr int VEC = 4;
+    static __device__ __forceinline__ void add(const float *p, float *s)
+    {
+        const float4 q = *reinterpret_cast<const float4 *>(p);
+        s[0] += q.x; s[1] += q.y; s[2] += q.z; s[3] += q.w;
+    }
+    static __device__ __forceinline__ void store(float *p, const float *s)
+    {
+        *reinterpret_cast<float4 *>(p) = make_float4(s[0], s[1], s[2], s[3]);
+    }
+    static __device__ __forceinline__ float load1(const float *p) { return *p; }
+    static __device__ __forceinline__ void store1(float *p, float s) { *p = s; }
+};
+
+// VEC channels per lane step (Chan<T>::VEC, or 1); one wavefront per image row (n, h)
+template <typename T, bool VECTOR>
+__global__ __launch_bounds__(256) void k_col2im(const T *__restrict__ cols, ConvShape g, T *__restrict__ dx)
+{
+    constexpr int VEC = VECTOR ? Chan<T>::VEC : 1;
+    const int64_t rowi = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    if (rowi >= static_cast<int64_t>(g.Nb) * g.H) return;
+    const int lane = threadIdx.x & 63;
+    const int h = static_cast<int>(rowi % g.H);
+    const int64_t n = rowi / g.H;
+    const int Cv = g.C / VEC;
+    const int row_units = g.W * Cv;
+    const int64_t I = static_cast<int64_t>(g.kh) * g.kw * g.C;
+    for (int v = lane; v < row_units; v += 64) {
+        const int w = v / Cv, c = (v - w * Cv) * VEC;
+        float s[VEC];
+#pragma unroll
+        for (int k = 0; k < VEC; ++k) s[k] = 0.0f;
+        for (int ky = 0; ky < g.kh; ++ky) {
+            const int hn = h + g.ph - ky * g.dh;          // = ho * stride for the output row that read this pixel
+            if (hn < 0) break;                            // later taps only move further up
+            const int ho = hn / g.sh;
+            if (ho * g.sh != hn || ho >= g.Ho) continue;
+            for (int kx = 0; kx < g.kw; ++kx) {
+                const int wn = w + g.pw - kx * g.dw;
+                if (wn < 0) break;
+                const int wo = wn / g.sw;
+                if (wo * g.sw != wn || wo >= g.Wo) continue;
+                const int64_t t = (n * g.Ho + ho) * g.Wo + wo;
+                const T *p = cols + t * I + (ky * g.kw + kx) * g.C + c;
+                if (VECTOR) Chan<T>::add(p, s);
+                else s[0] += Chan<T>::load1(p);
+            }
+        }
+        T *o = dx + ((n * g.H + h) * g.W + w) * g.C + c;
+        if (VECTOR) Chan<T>::store(o, s);
+        else Chan<T>::store1(o, s[0]);
+    }
+}
+
+hipError_t launch_im2col(const void *X, const ConvShape &g, bool is_f32, void *cols, hipStream_t st)
+{
+    const int e = is_f32 ? 4 : 2;
+    const unsigned grid = static_cast<unsigned>((g.N + 3) / 4);
+    if ((g.C * e) % 16 == 0) hipLaunchKernelGGL(k_im2col<16>, dim3(grid), dim3(256), 0, st, X, g, g.C * e / 16, cols);
+    else if (is_f32) hipLaunchKernelGGL(k_im2col<4>, dim3(grid), dim3(256), 0, st, X, g, g.C, cols);
+    else hipLaunchKernelGGL(k_im2col<2>, dim3(grid), dim3(256), 0, st, X, g, g.C, cols);
+    return hipGetLastError();
+}
+
+hipError_t launch_col2im(const void *cols, const ConvShape &g, bool is_f32, void *dx, hipStream_t st)
+{
+    const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(g.Nb) * g.H + 3) / 4);
+    if (is_f32) {
+        const float *c = static_cast<const float *>(cols);
+        float *o = static_cast<float *>(dx);
+        if (g.C % 4 == 0) hipLaunchKernelGGL((k_col2im<float, true>), dim3(grid), dim3(256), 0, st, c, g, o);
+        else hipLaunchKernelGGL((k_col2im<float, false>), dim3(grid), dim3(256), 0, st, c, g, o);
+    } else {
+        const bf16_t *c = static_cast<const bf16_t *>(cols);
+        bf16_t *o = static_cast<bf16_t *>(dx);
+        if (g.C % 8 == 0) hipLaunchKernelGGL((k_col2im<bf16_t, true>), dim3(grid), dim3(256), 0, st, c, g, o);
+        else hipLaunchKernelGGL((k_col2im<bf16_t, false>), dim3(grid), dim3(256), 0, st, c, g, o);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace hlq

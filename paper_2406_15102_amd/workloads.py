@@ -114,6 +114,16 @@ def generate(w: Workload, want=("X", "W", "G")):
     return {k: torch.from_numpy(v).to(tdt) for k, v in out.items()}
 
 
+def generate_conv(Nb: int, H: int, W: int, C: int, O: int, kh: int, kw: int, Ho: int, Wo: int, dtype: str = "bf16"):
+    """Channels-last tensors of a convolution layer, value recipe of c3 (post-ReLU input,
+    Kaiming-normal filters, N(0, 1e-3) output gradient): {"X": [Nb,H,W,C], "W": [O,kh,kw,C],
+    "G": [Nb,Ho,Wo,O]}.  The output extent (Ho, Wo) is the caller's to compute."""
+    w = WORKLOADS["c3"]
+    x = generate(scaled(w, N=Nb * H * W, d_in=C, dtype=dtype), want=("X",))["X"].reshape(Nb, H, W, C)
+    t = generate(scaled(w, N=Nb * Ho * Wo, d_in=kh * kw * C, d_out=O, dtype=dtype), want=("W", "G"))
+    return {"X": x, "W": t["W"].reshape(O, kh, kw, C), "G": t["G"].reshape(Nb, Ho, Wo, O)}
+
+
 def as_f32_numpy(t: torch.Tensor) -> np.ndarray:
     """Widen (exactly) to fp32 numpy, the form the CPU oracle takes."""
     return t.detach().to("cpu", torch.float32).contiguous().numpy()

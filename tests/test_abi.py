@@ -152,3 +152,42 @@ def test_cached_weight_entry_point_without_a_gpu():
     assert call(WqT=None) == 1 and call(sW=None) == 1            # dX wanted: the codes and their scales are needed
     assert call(WqT=C.c_void_p(0x10004)) == 2                    # misaligned codes
     assert call(d_out=250) == 2 and call(B=20) == 3 and call(flags=64) == 2
+
+
+def test_convolution_entry_points_without_a_gpu():
+    l = hlq.lib()
+
+    def geom(**kw):
+        a = dict(Nb=4, H=8, W=8, C=16, O=32, kh=3, kw=3, stride_h=1, stride_w=1, pad_h=1, pad_w=1, dil_h=1, dil_w=1)
+        a.update(kw)
+        return hlq.hlq_conv_geom(**a)
+
+    assert hlq.hlq_conv_sizes(geom()) == (8, 8, 256, 144)
+    assert hlq.hlq_conv_sizes(geom(stride_h=2, stride_w=2)) == (4, 4, 64, 144)
+    assert hlq.hlq_conv_sizes(geom(H=7, W=9, kh=3, kw=2, stride_h=2, pad_h=0, dil_w=2)) == (3, 9, 108, 96)
+    assert hlq.hlq_conv_sizes(geom(kh=1, kw=1, pad_h=0, pad_w=0)) == (8, 8, 256, 16)
+    v = C.c_int64()
+    for bad in (geom(stride_h=0), geom(pad_w=-1), geom(dil_h=0), geom(C=0), geom(H=2, pad_h=0, kh=5), geom(Nb=0)):
+        assert l.hlq_conv_sizes(C.byref(bad), C.byref(v), None, None, None) == 2
+    assert l.hlq_conv_sizes(None, None, None, None, None) == 1
+    g = geom()
+    assert l.hlq_im2col(None, C.byref(g), 0, FAKE, None) == 1 and l.hlq_im2col(FAKE, C.byref(g), 7, FAKE, None) == 5
+    assert l.hlq_im2col(FAKE, C.byref(g), 0, C.c_void_p(0x10002), None) == 2
+    assert l.hlq_col2im(FAKE, C.byref(g), 0, None, None) == 1 and l.hlq_col2im(FAKE, None, 0, FAKE, None) == 1
+    f = l.hlq_conv2d_backward
+
+    def call(g, G=FAKE, X=FAKE, W=FAKE, B=16, r=8, flags=0, dX=FAKE, dW=FAKE, wsb=1 << 40):
+        return f(G, X, W, C.byref(g), B, r, 0, 0, flags, dX, dW, FAKE, wsb, None)
+
+    assert call(g, G=None) == 1 and call(g, dX=None, dW=None) == 1 and call(g, X=None) == 1 and call(g, W=None) == 1
+    assert call(g, B=20) == 3 and call(g, r=3) == 4 and call(g, flags=64) == 2
+    assert call(geom(O=40)) == 2                                 # d_out = O must be whole Hadamard blocks
+    assert call(geom(Nb=1, H=5, W=5)) == 2                       # N = 25 positions: not whole blocks of tokens
+    assert call(geom(C=3)) == 2                                  # I = 27: rows of the column matrix must be 16-byte multiples
+    assert call(g, wsb=1000) == 6
+    # workspace: two column matrices on top of the linear pass's own; none for a pointwise kernel
+    inner = hlq.hlq_workspace_bytes_mode(256, 144, 32, 16, 8, False, 0)
+    assert hlq.hlq_conv_workspace_bytes(g, 16, 8, 0) == inner + 2 * 256 * 144 * 2
+    p = geom(kh=1, kw=1, pad_h=0, pad_w=0)
+    assert hlq.hlq_conv_workspace_bytes(p, 16, 8, 0) == hlq.hlq_workspace_bytes_mode(256, 16, 32, 16, 8, False, 0)
+    assert hlq.hlq_conv_workspace_bytes(geom(O=40), 16, 8, 0) == 0
