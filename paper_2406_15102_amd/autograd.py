@@ -63,3 +63,84 @@ class HlqLinear(torch.nn.Module):
     def forward(self, x):
         self.calls += 1
         return HlqLinearFunction.apply(x, self.weight, self.B, self.r, self.seed + self.calls, self.flags)
+
+
+class HlqConv2dFunction(torch.autograd.Function):
+    """y = conv2d(x, w) with the HLQ backward pass (Sec. 3.1: the spatial positions are the sequence).
+
+    x [Nb, C, H, W] and w [O, C, kh, kw] in torch's channels_last memory format (other formats are
+    converted), bf16 or fp32 on the GPU, groups = 1, no bias.  Forward builds the column matrix of
+    x, keeps only its compressed form (as HlqLinearFunction does) and drops it; backward runs the
+    two stage lists on (g, compressed columns, w) and folds the column gradient onto the image.
+    Nb*Ho*Wo must be a multiple of B and kh*kw*C of 8.
+    """
+
+    @staticmethod
+    def forward(ctx, x, w, stride=(1, 1), padding=(0, 0), dilation=(1, 1), B=16, r=8, seed=0, flags=0):
+        Nb, Cc, H, W = x.shape
+        O, _, kh, kw = w.shape
+        x_l = x.permute(0, 2, 3, 1).contiguous()         # a view when x is channels_last
+        geom = hlq.hlq_conv_geom(Nb=Nb, H=H, W=W, C=Cc, O=O, kh=kh, kw=kw, stride_h=stride[0], stride_w=stride[1],
+                                 pad_h=padding[0], pad_w=padding[1], dil_h=dilation[0], dil_w=dilation[1])
+        Ho, Wo, N, I = hlq.hlq_conv_sizes(geom)
+        Kc = N // B * r
+        pointwise = (kh, kw, tuple(stride), tuple(padding)) == (1, 1, (1, 1), (0, 0))
+        cols = x_l.reshape(N, I) if pointwise else torch.empty((N, I), dtype=x.dtype, device=x.device)
+        if not pointwise:
+            hlq.hlq_im2col(x_l, geom, cols)
+        basis = hlq.HLQ_BASIS_SEQUENCY if flags & hlq.HLQ_FLAG_GW_SEQUENCY else hlq.HLQ_BASIS_NATURAL
+        if flags & hlq.HLQ_FLAG_GW_INT8:
+            xc = torch.empty((I, Kc), dtype=torch.int8, device=x.device)
+            sxc = torch.empty(I, dtype=torch.float32, device=x.device)
+            ws = torch.empty(hlq.hlq_hla_quantize_workspace_bytes(I), dtype=torch.uint8, device=x.device)
+            hlq.hlq_hla_quantize_basis(cols, B, r, basis, seed, 2, xc, sxc, ws)
+        else:
+            xc = torch.empty((I, Kc), dtype=torch.bfloat16, device=x.device)
+            sxc = None
+            hlq.hlq_hla_project_basis(cols, B, r, basis, xc)
+        ctx.save_for_backward(xc, sxc, w)
+        ctx.meta = (geom, (Nb, H, W, Cc), N, I, O, B, r, seed, flags, pointwise)
+        return torch.nn.functional.conv2d(x, w, None, stride, padding, dilation)
+
+    @staticmethod
+    def backward(ctx, gy):
+        xc, sxc, w = ctx.saved_tensors
+        geom, xshape, N, I, O, B, r, seed, flags, pointwise = ctx.meta
+        g2 = gy.permute(0, 2, 3, 1).contiguous().reshape(N, O)
+        w_l = w.permute(0, 2, 3, 1).contiguous().reshape(O, I)
+        need_dx, need_dw = ctx.needs_input_grad[0], ctx.needs_input_grad[1]
+        dcols = torch.empty((N, I), dtype=g2.dtype, device=g2.device) if need_dx else None
+        dW = torch.empty((O, I), dtype=g2.dtype, device=g2.device) if need_dw else None
+        dX = None
+        if need_dx or need_dw:
+            hlq.hlq_linear_backward_mode(g2, None, xc, sxc, w_l, N, I, O, B, r, seed, flags, dcols, dW)
+        if need_dx:
+            if pointwise:
+                dX = dcols.reshape(xshape)
+            else:
+                dX = torch.empty(xshape, dtype=g2.dtype, device=g2.device)
+                hlq.hlq_col2im(dcols, geom, dX)
+            dX = dX.permute(0, 3, 1, 2)                  # [Nb, C, H, W], channels_last strides
+        if need_dw:
+            dW = dW.reshape(O, geom.kh, geom.kw, geom.C).permute(0, 3, 1, 2)
+        return dX, dW, None, None, None, None, None, None, None
+
+
+class HlqConv2d(torch.nn.Module):
+    """Bias-free 2-D convolution trained with the HLQ backward pass; a fresh seed per call."""
+
+    def __init__(self, c_in, c_out, kernel_size, stride=1, padding=0, dilation=1, B=16, r=8, flags=0,
+                 dtype=torch.bfloat16, device="cuda", seed=0):
+        super().__init__()
+        pair = lambda v: (v, v) if isinstance(v, int) else tuple(v)   # noqa: E731
+        kh, kw = pair(kernel_size)
+        std = (2.0 / (c_in * kh * kw)) ** 0.5
+        w = torch.randn((c_out, c_in, kh, kw), dtype=torch.float32, device=device).mul_(std).to(dtype)
+        self.weight = torch.nn.Parameter(w.contiguous(memory_format=torch.channels_last))
+        self.stride, self.padding, self.dilation = pair(stride), pair(padding), pair(dilation)
+        self.B, self.r, self.flags, self.seed, self.calls = B, r, flags, seed, 0
+
+    def forward(self, x):
+        self.calls += 1
+        return HlqConv2dFunction.apply(x, self.weight, self.stride, self.padding, self.dilation, self.B, self.r,
+                                       self.seed + self.calls, self.flags)

@@ -39,3 +39,42 @@ def test_module_saves_the_compressed_activation():
     y.float().square().mean().backward()
     assert lin.weight.grad is not None and torch.isfinite(lin.weight.grad.float()).all()
     assert x.grad is not None and torch.isfinite(x.grad.float()).all()
+
+
+@pytest.mark.parametrize("flags,stride,ksize,pad", [(0, (1, 1), 3, (1, 1)), (hlq.HLQ_FLAG_GW_INT8, (2, 2), 3, (1, 1)),
+                                                    (0, (1, 1), 1, (0, 0))])
+def test_convolution_function_matches_direct_call(flags, stride, ksize, pad):
+    from paper_2406_15102_amd.autograd import HlqConv2dFunction
+    Nb, H, W, C, O = 8, 16, 16, 32, 64
+    geom = hlq.hlq_conv_geom(Nb=Nb, H=H, W=W, C=C, O=O, kh=ksize, kw=ksize, stride_h=stride[0], stride_w=stride[1],
+                             pad_h=pad[0], pad_w=pad[1], dil_h=1, dil_w=1)
+    Ho, Wo, N, I = hlq.hlq_conv_sizes(geom)
+    t = wl.generate_conv(Nb, H, W, C, O, ksize, ksize, Ho, Wo, "bf16")
+    G, X, Wt = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
+    x = X.permute(0, 3, 1, 2).detach().requires_grad_(True)          # NCHW shape over channels-last memory
+    w = Wt.permute(0, 3, 1, 2).detach().requires_grad_(True)
+    y = HlqConv2dFunction.apply(x, w, stride, pad, (1, 1), 16, 8, 3, flags)
+    assert y.shape == (Nb, O, Ho, Wo)
+    y.backward(G.permute(0, 3, 1, 2))
+    dX, dW = torch.empty_like(X), torch.empty_like(Wt)
+    hlq.hlq_conv2d_backward(G, X, Wt, geom, 16, 8, 3, flags, dX, dW)
+    torch.cuda.synchronize()
+    assert x.grad.shape == x.shape and w.grad.shape == w.shape
+    assert torch.equal(x.grad.permute(0, 2, 3, 1), dX) and torch.equal(w.grad.permute(0, 2, 3, 1), dW)
+
+
+def test_convolution_module_trains_a_step():
+    from paper_2406_15102_amd.autograd import HlqConv2d
+    conv = HlqConv2d(16, 32, 3, padding=1, device=DEV)
+    x = torch.randn((4, 16, 8, 8), dtype=torch.bfloat16, device=DEV).contiguous(memory_format=torch.channels_last)
+    x.requires_grad_(True)
+    y = conv(x)
+    ref = torch.nn.functional.conv2d(x.detach(), conv.weight.detach(), padding=1)
+    assert torch.equal(y, ref)
+    y.float().square().mean().backward()
+    gw = torch.autograd.grad(torch.nn.functional.conv2d(x.detach(), conv.weight, padding=1).float().square().mean(),
+                             conv.weight)[0]
+    # half of the token-axis coefficients are kept: the gradient correlates with the exact one
+    a, b = conv.weight.grad.float().flatten(), gw.float().flatten()
+    assert torch.isfinite(a).all() and float(torch.dot(a, b) / (a.norm() * b.norm())) > 0.3
+    assert x.grad is not None and x.grad.shape == x.shape and torch.isfinite(x.grad.float()).all()
