@@ -199,6 +199,29 @@ def main():
     hlq.hlq_quantize_w(W, B, w.seed, WqT, sW, wws, None, qbits)
     cached = lambda: hlq.hlq_linear_backward_cached(G, X, None, None, WqT, sW, N, I, O, B, r, w.seed, 0, dX, dW, ws)
     cached_us = _event_time_us(cached, iters, torch, warm=max(3, args.warmup // 2))
+    # ---- the same layer as a real convolution (channels-last image in, image gradient out) ----
+    conv = None
+    geo = wl.CONV_GEOMS.get(w.name)
+    if geo:
+        Nb, H, Wd, Cc, kh, kw, st, pd = geo
+        geom = hlq.hlq_conv_geom(Nb=Nb, H=H, W=Wd, C=Cc, O=O, kh=kh, kw=kw, stride_h=st, stride_w=st, pad_h=pd, pad_w=pd,
+                                 dil_h=1, dil_w=1)
+        Ho, Wo, Nc, Ic = hlq.hlq_conv_sizes(geom)
+        assert (Nc, Ic) == (N, I)
+        tc = wl.generate_conv(Nb, H, Wd, Cc, O, kh, kw, Ho, Wo, w.dtype)
+        Gc, Xc4, Wc4 = (tc[k].to(dev).contiguous() for k in ("G", "X", "W"))
+        dXi, dWk = torch.empty_like(Xc4), torch.empty_like(Wc4)
+        cws = torch.empty(hlq.hlq_conv_workspace_bytes(geom, B, r, hlq.binding._dt(Gc), 0), dtype=torch.uint8, device=dev)
+        colbuf = torch.empty((N, I), dtype=tdt, device=dev)
+        warm = max(3, args.warmup // 2)
+        conv = {
+            "geometry": {"Nb": Nb, "H": H, "W": Wd, "C": Cc, "O": O, "k": [kh, kw], "stride": st, "pad": pd},
+            "backward_us": round(_event_time_us(
+                lambda: hlq.hlq_conv2d_backward(Gc, Xc4, Wc4, geom, B, r, w.seed, 0, dXi, dWk, cws), iters, torch, warm), 2),
+            "im2col_us": round(_event_time_us(lambda: hlq.hlq_im2col(Xc4, geom, colbuf), iters, torch, warm), 2),
+            "col2im_us": round(_event_time_us(lambda: hlq.hlq_col2im(colbuf, geom, dXi), iters, torch, warm), 2),
+        }
+        del tc, Gc, Xc4, Wc4, dXi, dWk, cws, colbuf
     step()   # leave dX / dW as the default path computes them
 
     # ---- dense bf16 backward on the same GPU (comparator, not part of the library) ----
@@ -247,6 +270,7 @@ def main():
         "kernels": kernels,
         "modes_us": modes,
         "cached_weight_codes_us": round(cached_us, 2),
+        "as_convolution": conv,
         "copy_256MiB": {"us": round(copy_us, 2), "GB/s": round(2 * (1 << 28) / copy_us / 1e3, 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -8,11 +8,11 @@
 //   fold            its adjoint: pixel (n, h, w, c) of the image gradient is the sum of every
 //                   entry of the column gradient that was copied from it, added in fp32 in
 //                   ascending (ky, kx) order (deterministic), rounded once to the output type.
-// Both are plain HBM-bound data movement.  A wavefront owns one row of its output (one output
-// position's receptive field, or one image row), so the decomposition of the row index into
-// (n, y, x) is wave-uniform and each lane spends two integer divisions per 16 bytes moved;
-// lanes walk the row in 16-byte units (8 bf16 / 4 fp32 channels) when the channel count allows,
-// else element by element.
+// Both are plain HBM-bound data movement in 16-byte units (8 bf16 / 4 fp32 channels) when the channel
+// count allows, else element by element.  The column matrix gives a wavefront one row of its output
+// (one receptive field): the row index is decomposed once per wavefront and a lane spends two integer
+// divisions per unit.  The fold gives a lane one unit of the image and a wavefront 64 units of one
+// image row, so that even small feature maps make thousands of wavefronts.
 #include "hlq_device.hpp"
 #include "hlq_kernels.hpp"
 
@@ -81,44 +81,56 @@ template <> struct Chan<float> {
     static __device__ __forceinline__ void store1(float *p, float s) { *p = s; }
 };
 
-// VEC channels per lane step (Chan<T>::VEC, or 1); one wavefront per image row (n, h)
-template <typename T, bool VECTOR>
-__global__ __launch_bounds__(256) void k_col2im(const T *__restrict__ cols, ConvShape g, T *__restrict__ dx)
+// One lane per pixel and group of VEC channels (Chan<T>::VEC, or 1); a wavefront covers 64 such
+// units of one image row (n, h), so the row's decomposition and the vertical taps are wave-uniform.
+// KS > 0: kh = kw = KS known at compile time -- the tap loop unrolls and its loads are in flight
+// together.  A tap that no output position pairs with this pixel loads from row 0 of the column
+// matrix instead (always inside the tensor) and is not added.
+template <typename T, bool VECTOR, int KS>
+__global__ __launch_bounds__(256) void k_col2im(const T *__restrict__ cols, ConvShape g, int chunks, T *__restrict__ dx)
 {
     constexpr int VEC = VECTOR ? Chan<T>::VEC : 1;
-    const int64_t rowi = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int64_t wid = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    const int64_t rowi = wid / chunks;
     if (rowi >= static_cast<int64_t>(g.Nb) * g.H) return;
-    const int lane = threadIdx.x & 63;
+    const int chunk = static_cast<int>(wid - rowi * chunks);
     const int h = static_cast<int>(rowi % g.H);
     const int64_t n = rowi / g.H;
     const int Cv = g.C / VEC;
-    const int row_units = g.W * Cv;
-    const int64_t I = static_cast<int64_t>(g.kh) * g.kw * g.C;
-    for (int v = lane; v < row_units; v += 64) {
-        const int w = v / Cv, c = (v - w * Cv) * VEC;
-        float s[VEC];
+    const int v = chunk * 64 + (threadIdx.x & 63);
+    if (v >= g.W * Cv) return;
+    const int w = v / Cv, c = (v - w * Cv) * VEC;
+    const int KH = KS ? KS : g.kh, KW = KS ? KS : g.kw;
+    const int64_t I = static_cast<int64_t>(KH) * KW * g.C;
+    float s[VEC];
 #pragma unroll
-        for (int k = 0; k < VEC; ++k) s[k] = 0.0f;
-        for (int ky = 0; ky < g.kh; ++ky) {
-            const int hn = h + g.ph - ky * g.dh;          // = ho * stride for the output row that read this pixel
-            if (hn < 0) break;                            // later taps only move further up
-            const int ho = hn / g.sh;
-            if (ho * g.sh != hn || ho >= g.Ho) continue;
-            for (int kx = 0; kx < g.kw; ++kx) {
-                const int wn = w + g.pw - kx * g.dw;
-                if (wn < 0) break;
-                const int wo = wn / g.sw;
-                if (wo * g.sw != wn || wo >= g.Wo) continue;
-                const int64_t t = (n * g.Ho + ho) * g.Wo + wo;
-                const T *p = cols + t * I + (ky * g.kw + kx) * g.C + c;
-                if (VECTOR) Chan<T>::add(p, s);
-                else s[0] += Chan<T>::load1(p);
+    for (int k = 0; k < VEC; ++k) s[k] = 0.0f;
+#pragma unroll
+    for (int ky = 0; ky < KH; ++ky) {
+        const int hn = h + g.ph - ky * g.dh;              // = ho * stride for the output row that read this pixel
+        const int ho = g.sh == 1 ? hn : hn / g.sh;
+        const bool okh = hn >= 0 && ho * g.sh == hn && ho < g.Ho;
+#pragma unroll
+        for (int kx = 0; kx < KW; ++kx) {
+            const int wn = w + g.pw - kx * g.dw;
+            const int wo = g.sw == 1 ? wn : wn / g.sw;
+            const bool ok = okh && wn >= 0 && wo * g.sw == wn && wo < g.Wo;
+            const int64_t t = ok ? (n * g.Ho + ho) * g.Wo + wo : 0;
+            const T *p = cols + t * I + (ky * KW + kx) * g.C + c;
+            float a[VEC];
+#pragma unroll
+            for (int k = 0; k < VEC; ++k) a[k] = 0.0f;
+            if (VECTOR) Chan<T>::add(p, a);
+            else a[0] = Chan<T>::load1(p);
+            if (ok) {
+#pragma unroll
+                for (int k = 0; k < VEC; ++k) s[k] += a[k];
             }
         }
-        T *o = dx + ((n * g.H + h) * g.W + w) * g.C + c;
-        if (VECTOR) Chan<T>::store(o, s);
-        else Chan<T>::store1(o, s[0]);
     }
+    T *o = dx + ((n * g.H + h) * g.W + w) * g.C + c;
+    if (VECTOR) Chan<T>::store(o, s);
+    else Chan<T>::store1(o, s[0]);
 }
 
 hipError_t launch_im2col(const void *X, const ConvShape &g, bool is_f32, void *cols, hipStream_t st)
@@ -131,21 +143,30 @@ hipError_t launch_im2col(const void *X, const ConvShape &g, bool is_f32, void *c
     return hipGetLastError();
 }
 
-hipError_t launch_col2im(const void *cols, const ConvShape &g, bool is_f32, void *dx, hipStream_t st)
+template <typename T>
+static hipError_t launch_col2im_t(const void *cols, const ConvShape &g, void *dx, hipStream_t st)
 {
-    const unsigned grid = static_cast<unsigned>((static_cast<int64_t>(g.Nb) * g.H + 3) / 4);
-    if (is_f32) {
-        const float *c = static_cast<const float *>(cols);
-        float *o = static_cast<float *>(dx);
-        if (g.C % 4 == 0) hipLaunchKernelGGL((k_col2im<float, true>), dim3(grid), dim3(256), 0, st, c, g, o);
-        else hipLaunchKernelGGL((k_col2im<float, false>), dim3(grid), dim3(256), 0, st, c, g, o);
+    const T *c = static_cast<const T *>(cols);
+    T *o = static_cast<T *>(dx);
+    const bool vec = g.C % Chan<T>::VEC == 0;
+    const int chunks = (g.W * (vec ? g.C / Chan<T>::VEC : g.C) + 63) / 64;
+    const int64_t waves = static_cast<int64_t>(g.Nb) * g.H * chunks;
+    if (waves + 3 >= (int64_t(1) << 33)) return hipErrorInvalidValue;
+    const dim3 grid(static_cast<unsigned>((waves + 3) / 4));
+    const bool k3 = g.kh == 3 && g.kw == 3;
+    if (vec) {
+        if (k3) hipLaunchKernelGGL((k_col2im<T, true, 3>), grid, dim3(256), 0, st, c, g, chunks, o);
+        else hipLaunchKernelGGL((k_col2im<T, true, 0>), grid, dim3(256), 0, st, c, g, chunks, o);
     } else {
-        const bf16_t *c = static_cast<const bf16_t *>(cols);
-        bf16_t *o = static_cast<bf16_t *>(dx);
-        if (g.C % 8 == 0) hipLaunchKernelGGL((k_col2im<bf16_t, true>), dim3(grid), dim3(256), 0, st, c, g, o);
-        else hipLaunchKernelGGL((k_col2im<bf16_t, false>), dim3(grid), dim3(256), 0, st, c, g, o);
+        if (k3) hipLaunchKernelGGL((k_col2im<T, false, 3>), grid, dim3(256), 0, st, c, g, chunks, o);
+        else hipLaunchKernelGGL((k_col2im<T, false, 0>), grid, dim3(256), 0, st, c, g, chunks, o);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_col2im(const void *cols, const ConvShape &g, bool is_f32, void *dx, hipStream_t st)
+{
+    return is_f32 ? launch_col2im_t<float>(cols, g, dx, st) : launch_col2im_t<bf16_t>(cols, g, dx, st);
 }
 
 }  // namespace hlq

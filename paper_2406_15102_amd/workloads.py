@@ -68,6 +68,20 @@ for _k, (_L, _O, _I) in enumerate(_PAPER_LAYERS):
 _RECIPE = {6: 2, 7: 3}   # value distributions: as c2 (outlier channels, per-token spread) / as c3 (post-ReLU)
 
 
+# Convolution geometry behind the im2col-shaped workloads: (Nb, H, W, C, kh, kw, stride, pad), channels-last.
+# c3 is a 3x3 / 256-channel layer on 14x14 maps; the ResNet-34 rows of the latency table are read as
+# its 3x3 layers (I = 9 C) and its 1x1 stride-2 shortcut projections (I = C), at batch 64.
+CONV_GEOMS = {
+    "c3": (64, 14, 14, 256, 3, 3, 1, 1),
+    "p07": (64, 32, 32, 64, 3, 3, 1, 1),
+    "p08": (64, 16, 16, 128, 3, 3, 1, 1),
+    "p09": (64, 32, 32, 64, 1, 1, 2, 0),
+    "p10": (64, 16, 16, 128, 3, 3, 2, 1),
+    "p11": (64, 16, 16, 128, 1, 1, 2, 0),
+    "p12": (64, 8, 8, 256, 3, 3, 2, 1),
+}
+
+
 def scaled(w: Workload, N: int | None = None, d_in: int | None = None, d_out: int | None = None,
            **kw) -> Workload:
     """Same recipe at another size (for parity cases the oracle finishes in seconds)."""
