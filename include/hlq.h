@@ -324,11 +324,27 @@ int hlq_im2col(const void *X, const hlq_conv_geom *g, int dtype, void *cols, voi
 int hlq_col2im(const void *cols, const hlq_conv_geom *g, int dtype, void *dX, void *stream);
 
 /*
+ * ACBP for a convolution (Sec. 6.1, stage 1 -- and 2 -- of the g_w list at forward time): what
+ * hlq_hla_project_basis / hlq_hla_quantize_basis (tensor 2) give on hlq_im2col's result, computed
+ * straight from the image -- the column matrix is never stored.  XhatT [I, N/B*r] bf16, or XqT
+ * [I, N/B*r] int8 with sX [I]; coeffT as there.  Needs C % (128 / B) == 0 (HLQ_ERR_SHAPE otherwise:
+ * store the column matrix and compress that); the other rules and codes are those of the two
+ * functions named, with D = I.  The result feeds hlq_linear_backward_mode as Xc (and sXc).
+ */
+int hlq_conv_compress_act(const void *X, const hlq_conv_geom *g, int B, int r, int basis, int dtype, void *XhatT,
+                          float *coeffT, void *stream);
+int hlq_conv_compress_act_int8(const void *X, const hlq_conv_geom *g, int B, int r, int basis, uint64_t seed, int dtype,
+                               int8_t *XqT, float *sX, float *coeffT, void *workspace, size_t workspace_bytes,
+                               void *stream);
+
+/*
  * Backward pass of the convolution: hlq_im2col(X), then hlq_linear_backward_mode on (G, cols, Wt)
  * with the N, d_in = I, d_out = O above (same B, r, seed, flags, shape rules and status codes), then
  * hlq_col2im of the column gradient.  dX [Nb, H, W, C] and dW [O, kh, kw, C] of `dtype`; either may
- * be NULL.  A 1x1 kernel with unit stride and no padding is its own column matrix: no copy is made.
- * The column gradient is held in `dtype` before it is folded.
+ * be NULL.  A 1x1 kernel with unit stride and no padding is its own column matrix: no copy is made;
+ * with C % (128 / B) == 0 the g_w list projects straight from the image (hlq_conv_compress_act) and
+ * no column matrix is stored either -- same result bit for bit.  The column gradient is held in
+ * `dtype` before it is folded.
  *   workspace >= hlq_conv_workspace_bytes(...) bytes, 256-aligned; or NULL for the library-owned one.
  */
 size_t hlq_conv_workspace_bytes(const hlq_conv_geom *g, int B, int r, int dtype, int flags);

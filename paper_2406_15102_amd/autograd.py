@@ -69,8 +69,9 @@ class HlqConv2dFunction(torch.autograd.Function):
     """y = conv2d(x, w) with the HLQ backward pass (Sec. 3.1: the spatial positions are the sequence).
 
     x [Nb, C, H, W] and w [O, C, kh, kw] in torch's channels_last memory format (other formats are
-    converted), bf16 or fp32 on the GPU, groups = 1, no bias.  Forward builds the column matrix of
-    x, keeps only its compressed form (as HlqLinearFunction does) and drops it; backward runs the
+    converted), bf16 or fp32 on the GPU, groups = 1, no bias.  Forward keeps the compressed column
+    matrix of x (as HlqLinearFunction keeps the compressed x), projected straight from the image when
+    the channel count allows, else through a temporary column matrix; backward runs the
     two stage lists on (g, compressed columns, w) and folds the column gradient onto the image.
     Nb*Ho*Wo must be a multiple of B and kh*kw*C of 8.
     """
@@ -85,19 +86,27 @@ class HlqConv2dFunction(torch.autograd.Function):
         Ho, Wo, N, I = hlq.hlq_conv_sizes(geom)
         Kc = N // B * r
         pointwise = (kh, kw, tuple(stride), tuple(padding)) == (1, 1, (1, 1), (0, 0))
-        cols = x_l.reshape(N, I) if pointwise else torch.empty((N, I), dtype=x.dtype, device=x.device)
-        if not pointwise:
-            hlq.hlq_im2col(x_l, geom, cols)
+        from_image = not pointwise and Cc % (128 // B) == 0        # no column matrix is stored at all
         basis = hlq.HLQ_BASIS_SEQUENCY if flags & hlq.HLQ_FLAG_GW_SEQUENCY else hlq.HLQ_BASIS_NATURAL
+        if not from_image:
+            cols = x_l.reshape(N, I) if pointwise else torch.empty((N, I), dtype=x.dtype, device=x.device)
+            if not pointwise:
+                hlq.hlq_im2col(x_l, geom, cols)
         if flags & hlq.HLQ_FLAG_GW_INT8:
             xc = torch.empty((I, Kc), dtype=torch.int8, device=x.device)
             sxc = torch.empty(I, dtype=torch.float32, device=x.device)
             ws = torch.empty(hlq.hlq_hla_quantize_workspace_bytes(I), dtype=torch.uint8, device=x.device)
-            hlq.hlq_hla_quantize_basis(cols, B, r, basis, seed, 2, xc, sxc, ws)
+            if from_image:
+                hlq.hlq_conv_compress_act_int8(x_l, geom, B, r, basis, seed, xc, sxc, ws)
+            else:
+                hlq.hlq_hla_quantize_basis(cols, B, r, basis, seed, 2, xc, sxc, ws)
         else:
             xc = torch.empty((I, Kc), dtype=torch.bfloat16, device=x.device)
             sxc = None
-            hlq.hlq_hla_project_basis(cols, B, r, basis, xc)
+            if from_image:
+                hlq.hlq_conv_compress_act(x_l, geom, B, r, basis, xc)
+            else:
+                hlq.hlq_hla_project_basis(cols, B, r, basis, xc)
         ctx.save_for_backward(xc, sxc, w)
         ctx.meta = (geom, (Nb, H, W, Cc), N, I, O, B, r, seed, flags, pointwise)
         return torch.nn.functional.conv2d(x, w, None, stride, padding, dilation)

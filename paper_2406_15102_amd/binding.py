@@ -76,6 +76,10 @@ _EXPORTS = {
     "hlq_conv_sizes": (C.c_int, [_GEOM_P] + [C.POINTER(C.c_int64)] * 4),
     "hlq_im2col": (C.c_int, [C.c_void_p, _GEOM_P, C.c_int, C.c_void_p, C.c_void_p]),
     "hlq_col2im": (C.c_int, [C.c_void_p, _GEOM_P, C.c_int, C.c_void_p, C.c_void_p]),
+    "hlq_conv_compress_act": (C.c_int, [C.c_void_p, _GEOM_P, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                        C.c_void_p]),
+    "hlq_conv_compress_act_int8": (C.c_int, [C.c_void_p, _GEOM_P, C.c_int, C.c_int, C.c_int, C.c_uint64, C.c_int,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hlq_conv_workspace_bytes": (C.c_size_t, [_GEOM_P, C.c_int, C.c_int, C.c_int, C.c_int]),
     "hlq_conv2d_backward": (C.c_int, [C.c_void_p] * 3 + [_GEOM_P, C.c_int, C.c_int, C.c_uint64, C.c_int, C.c_int]
                             + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]),
@@ -321,6 +325,17 @@ def hlq_im2col(X, geom, cols):
 
 def hlq_col2im(cols, geom, dX):
     _check(lib().hlq_col2im(_ptr(cols), C.byref(geom), _dt(cols), _ptr(dX, cols.dtype), _stream()), "hlq_col2im")
+
+
+def hlq_conv_compress_act(X, geom, B, r, basis, XhatT, coeffT=None):
+    _check(lib().hlq_conv_compress_act(_ptr(X), C.byref(geom), B, r, basis, _dt(X), _ptr(XhatT, torch.bfloat16),
+                                       _ptr(coeffT, torch.float32), _stream()), "hlq_conv_compress_act")
+
+
+def hlq_conv_compress_act_int8(X, geom, B, r, basis, seed, XqT, sX, workspace, coeffT=None):
+    _check(lib().hlq_conv_compress_act_int8(_ptr(X), C.byref(geom), B, r, basis, seed, _dt(X), _ptr(XqT, torch.int8),
+                                            _ptr(sX, torch.float32), _ptr(coeffT, torch.float32), _ptr(workspace),
+                                            _nbytes(workspace), _stream()), "hlq_conv_compress_act_int8")
 
 
 def hlq_conv_workspace_bytes(geom, B, r, dtype, flags=0) -> int:

@@ -1,13 +1,65 @@
 // Device body of K3 (see k_hla.hip): workgroup (bx, by) of 256 threads projects token blocks
 // 4 by .. 4 by + 3 of the 64 * (128 / B) features starting at bx * 64 * (128 / B).
+//
+// Where the rows come from is a template argument: DenseRows reads a row-major [N, D] tensor;
+// ConvRows reads the column matrix of a channels-last image without it ever being stored
+// (arXiv 2406.15102, Sec. 3.1: the spatial positions of a convolution are the sequence) -- a lane's
+// 128 / B adjacent columns are channels of one filter tap, fixed for the lane, and the B consecutive
+// rows are consecutive output positions, stepped from one division per block.
 #pragma once
 #include "hlq_device.hpp"
+#include "hlq_kernels.hpp"
 
 namespace hlq {
 
-template <typename Tin, int B, int BASIS>
-__device__ __forceinline__ void hla_body(const Tin *__restrict__ T, int64_t N, int D, int r, bf16_t *__restrict__ ThatT,
-                                         float *__restrict__ coeffT, int bx, int by)
+template <typename Tin> struct DenseRows {
+    const Tin *T;
+    int64_t D;
+    template <int B, int CPL> __device__ __forceinline__ void load_block(int64_t row0, int col0, float *v) const
+    {
+#pragma unroll
+        for (int j = 0; j < B; ++j) Loader<Tin, CPL>::load(T + (row0 + j) * D + col0, v + j * CPL);
+    }
+};
+
+// needs C % CPL == 0 (a lane's columns stay inside one tap) and N < 2^31
+template <typename Tin> struct ConvRows {
+    const Tin *X;
+    ConvShape g;
+    template <int B, int CPL> __device__ __forceinline__ void load_block(int64_t row0, int col0, float *v) const
+    {
+        const int tap = col0 / g.C, c = col0 - tap * g.C;
+        const int ky = tap / g.kw, kx = tap - ky * g.kw;
+        const int dy = ky * g.dh - g.ph, dx = kx * g.dw - g.pw;
+        const uint32_t t = static_cast<uint32_t>(row0);
+        int wo = static_cast<int>(t % static_cast<uint32_t>(g.Wo));
+        const uint32_t t2 = t / static_cast<uint32_t>(g.Wo);
+        int ho = static_cast<int>(t2 % static_cast<uint32_t>(g.Ho));
+        int64_t n = t2 / static_cast<uint32_t>(g.Ho);
+#pragma unroll
+        for (int j = 0; j < B; ++j) {
+            const int hi = ho * g.sh + dy, wi = wo * g.sw + dx;
+            // a tap outside the image loads the nearest pixel instead (always a valid address, so the
+            // B loads carry no branch and stay in flight together) and is zeroed afterwards
+            const bool ok = hi >= 0 && hi < g.H && wi >= 0 && wi < g.W;
+            const int hc = min(max(hi, 0), g.H - 1), wc = min(max(wi, 0), g.W - 1);
+            Loader<Tin, CPL>::load(X + ((n * g.H + hc) * g.W + wc) * g.C + c, v + j * CPL);
+#pragma unroll
+            for (int k = 0; k < CPL; ++k) v[j * CPL + k] = ok ? v[j * CPL + k] : 0.0f;
+            if (++wo == g.Wo) {
+                wo = 0;
+                if (++ho == g.Ho) {
+                    ho = 0;
+                    ++n;
+                }
+            }
+        }
+    }
+};
+
+template <int B, int BASIS, typename Src>
+__device__ __forceinline__ void hla_body_src(const Src &src, int64_t N, int D, int r, bf16_t *__restrict__ ThatT,
+                                             float *__restrict__ coeffT, int bx, int by)
 {
     constexpr int CPL = 128 / B;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -18,9 +70,7 @@ __device__ __forceinline__ void hla_body(const Tin *__restrict__ T, int64_t N, i
     if (col0 >= D || blk >= nblk) return;
 
     float v[B * CPL];
-#pragma unroll
-    for (int j = 0; j < B; ++j)
-        Loader<Tin, CPL>::load(T + (blk * B + j) * static_cast<int64_t>(D) + col0, v + j * CPL);
+    src.template load_block<B, CPL>(blk * B, col0, v);
 #pragma unroll
     for (int c = 0; c < CPL; ++c) {
         fwht_regs<B, CPL>(v + c);
@@ -55,10 +105,17 @@ __device__ __forceinline__ void hla_body(const Tin *__restrict__ T, int64_t N, i
     }
 }
 
-// ---- integer g_w list: pass 1 (column maxima of the kept coefficients) and pass 2 (int8 codes) ----
 template <typename Tin, int B, int BASIS>
-__device__ __forceinline__ void hla_absmax_body(const Tin *__restrict__ T, int64_t N, int D, int r,
-                                                uint32_t *__restrict__ amax_bits, int bx, int by)
+__device__ __forceinline__ void hla_body(const Tin *__restrict__ T, int64_t N, int D, int r, bf16_t *__restrict__ ThatT,
+                                         float *__restrict__ coeffT, int bx, int by)
+{
+    hla_body_src<B, BASIS>(DenseRows<Tin>{T, D}, N, D, r, ThatT, coeffT, bx, by);
+}
+
+// ---- integer g_w list: pass 1 (column maxima of the kept coefficients) and pass 2 (int8 codes) ----
+template <int B, int BASIS, typename Src>
+__device__ __forceinline__ void hla_absmax_body_src(const Src &src, int64_t N, int D, int r,
+                                                    uint32_t *__restrict__ amax_bits, int bx, int by)
 {
     constexpr int CPL = 128 / B;
     __shared__ float s_max[4][64 * CPL];
@@ -71,9 +128,7 @@ __device__ __forceinline__ void hla_absmax_body(const Tin *__restrict__ T, int64
     for (int c = 0; c < CPL; ++c) cmax[c] = 0.0f;
     if (col0 < D && blk < nblk) {
         float v[B * CPL];
-#pragma unroll
-        for (int j = 0; j < B; ++j)
-            Loader<Tin, CPL>::load(T + (blk * B + j) * static_cast<int64_t>(D) + col0, v + j * CPL);
+        src.template load_block<B, CPL>(blk * B, col0, v);
 #pragma unroll
         for (int c = 0; c < CPL; ++c) {
             fwht_regs<B, CPL>(v + c);
@@ -92,11 +147,18 @@ __device__ __forceinline__ void hla_absmax_body(const Tin *__restrict__ T, int64
     }
 }
 
-template <typename Tin, int B, int BASIS, bool MANT = false>
-__device__ __forceinline__ void hla_quantize_body(const Tin *__restrict__ T, int64_t N, int D, int r,
-                                                  const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
-                                                  int8_t *__restrict__ TqT, float *__restrict__ sT,
-                                                  float *__restrict__ coeffT, int bx, int by)
+template <typename Tin, int B, int BASIS>
+__device__ __forceinline__ void hla_absmax_body(const Tin *__restrict__ T, int64_t N, int D, int r,
+                                                uint32_t *__restrict__ amax_bits, int bx, int by)
+{
+    hla_absmax_body_src<B, BASIS>(DenseRows<Tin>{T, D}, N, D, r, amax_bits, bx, by);
+}
+
+template <int B, int BASIS, bool MANT, typename Src>
+__device__ __forceinline__ void hla_quantize_body_src(const Src &src, int64_t N, int D, int r,
+                                                      const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
+                                                      int8_t *__restrict__ TqT, float *__restrict__ sT,
+                                                      float *__restrict__ coeffT, int bx, int by)
 {
     constexpr int CPL = 128 / B;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -107,9 +169,7 @@ __device__ __forceinline__ void hla_quantize_body(const Tin *__restrict__ T, int
     if (col0 >= D || blk >= nblk) return;
 
     float v[B * CPL];
-#pragma unroll
-    for (int j = 0; j < B; ++j)
-        Loader<Tin, CPL>::load(T + (blk * B + j) * static_cast<int64_t>(D) + col0, v + j * CPL);
+    src.template load_block<B, CPL>(blk * B, col0, v);
 #pragma unroll
     for (int c = 0; c < CPL; ++c) {
         fwht_regs<B, CPL>(v + c);
@@ -132,6 +192,15 @@ __device__ __forceinline__ void hla_quantize_body(const Tin *__restrict__ T, int
             }
         }
     }
+}
+
+template <typename Tin, int B, int BASIS, bool MANT = false>
+__device__ __forceinline__ void hla_quantize_body(const Tin *__restrict__ T, int64_t N, int D, int r,
+                                                  const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
+                                                  int8_t *__restrict__ TqT, float *__restrict__ sT,
+                                                  float *__restrict__ coeffT, int bx, int by)
+{
+    hla_quantize_body_src<B, BASIS, MANT>(DenseRows<Tin>{T, D}, N, D, r, amax_bits, k0, k1, TqT, sT, coeffT, bx, by);
 }
 
 }  // namespace hlq

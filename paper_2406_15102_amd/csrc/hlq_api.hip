@@ -406,7 +406,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     const int basis = (flags & HLQ_FLAG_GW_SEQUENCY) ? HLQ_BASIS_SEQUENCY : HLQ_BASIS_NATURAL;
     const bool mant = (flags & HLQ_FLAG_ROUND_MANTISSA) != 0;
 
-    const bool xc = (Xc != nullptr);
+    const bool xc = (Xc != nullptr) || !dW;   // no projection of X is held here: it was handed over, or dW is not wanted
     const Layout L = make_layout(N, d_in, d_out, B, r, xc, flags);
     char *ws = static_cast<char *>(workspace);
     if (ws) {
@@ -653,20 +653,80 @@ int hlq_col2im(const void *cols, const hlq_conv_geom *g, int dtype, void *dX, vo
     return launch_rc(hlq::launch_col2im(cols, c, dtype == HLQ_F32, dX, static_cast<hipStream_t>(stream)));
 }
 
-// workspace of the convolution pass: [column matrix | column gradient | the linear pass's own]
+static int conv_compress_check(const void *X, const hlq_conv_geom *g, hlq::ConvShape *c, int B, int r, int basis,
+                               int dtype)
+{
+    int rc;
+    if ((rc = conv_shape(g, c)) != HLQ_OK) return rc;
+    if (!X) return HLQ_ERR_NULL;
+    if (basis != HLQ_BASIS_NATURAL && basis != HLQ_BASIS_SEQUENCY) return HLQ_ERR_RANK;
+    if ((rc = check_block(B)) != HLQ_OK) return rc;
+    if ((rc = check_rank(B, r)) != HLQ_OK) return rc;
+    if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if ((rc = check_hla_shape(c->N, static_cast<int64_t>(c->kh) * c->kw * c->C, B, r)) != HLQ_OK) return rc;
+    if (!hlq::hla_conv_ok(*c, B) || !aligned(X, 16)) return HLQ_ERR_SHAPE;
+    return HLQ_OK;
+}
+
+int hlq_conv_compress_act(const void *X, const hlq_conv_geom *g, int B, int r, int basis, int dtype, void *XhatT,
+                          float *coeffT, void *stream)
+{
+    int rc;
+    hlq::ConvShape c;
+    if ((rc = conv_compress_check(X, g, &c, B, r, basis, dtype)) != HLQ_OK) return rc;
+    if (!XhatT) return HLQ_ERR_NULL;
+    if (!aligned(XhatT, 16) || (coeffT && !aligned(coeffT, 16))) return HLQ_ERR_SHAPE;
+    return launch_rc(hlq::launch_hla_conv(X, c, B, r, basis, dtype == HLQ_F32, static_cast<uint16_t *>(XhatT), coeffT,
+                                          static_cast<hipStream_t>(stream)));
+}
+
+int hlq_conv_compress_act_int8(const void *X, const hlq_conv_geom *g, int B, int r, int basis, uint64_t seed, int dtype,
+                               int8_t *XqT, float *sX, float *coeffT, void *workspace, size_t workspace_bytes,
+                               void *stream)
+{
+    int rc;
+    hlq::ConvShape c;
+    const bool mant = (basis & HLQ_BASIS_ROUND_MANTISSA) != 0;
+    basis &= ~HLQ_BASIS_ROUND_MANTISSA;
+    if ((rc = conv_compress_check(X, g, &c, B, r, basis, dtype)) != HLQ_OK) return rc;
+    if (!XqT || !sX || !workspace) return HLQ_ERR_NULL;
+    if (r % 4 != 0) return HLQ_ERR_RANK;
+    const int64_t D = static_cast<int64_t>(c.kh) * c.kw * c.C, Kc = c.N / B * r;
+    if (Kc % 16 != 0 || D * (Kc / 4) >= (int64_t(1) << 32)) return HLQ_ERR_SHAPE;
+    if (!aligned(XqT, 16) || (coeffT && !aligned(coeffT, 16))) return HLQ_ERR_SHAPE;
+    if (!aligned(workspace, 256) || workspace_bytes < hlq::hla_quant_ws_bytes(D)) return HLQ_ERR_WORKSPACE;
+    const uint64_t key = stream_key(seed, 2);
+    return launch_rc(hlq::launch_hla_quant_conv(X, c, B, r, basis, dtype == HLQ_F32, static_cast<uint32_t>(key),
+                                                static_cast<uint32_t>(key >> 32), mant, XqT, sX, coeffT, workspace,
+                                                static_cast<hipStream_t>(stream)));
+}
+
+// Workspace of the convolution pass: [x | sx | xws | column gradient | the linear pass's own].
+// `x` is the compressed column matrix (projected straight from the image) when the channel count
+// allows, else the column matrix itself; sx / xws its scales and column maxima (integer g_w list).
 struct ConvLayout {
-    size_t cols, dcols, inner, inner_bytes, total;
+    bool pointwise, implicit;
+    size_t x, sx, xws, xws_bytes, dcols, inner, inner_bytes, total;
 };
 
 static ConvLayout conv_layout(const hlq::ConvShape &c, const hlq_conv_geom *g, int B, int r, int dtype, int flags)
 {
     const int64_t I = static_cast<int64_t>(c.kh) * c.kw * c.C;
-    const size_t mat = conv_is_pointwise(g) ? 0 : up256(static_cast<size_t>(c.N) * I * (dtype == HLQ_F32 ? 4 : 2));
+    const size_t e = dtype == HLQ_F32 ? 4 : 2;
+    const bool gwi = (flags & HLQ_FLAG_GW_INT8) != 0;
     ConvLayout L;
-    L.cols = 0;
-    L.dcols = mat;
-    L.inner = 2 * mat;
-    L.inner_bytes = hlq_workspace_bytes_mode(c.N, I, g->O, B, r, 0, flags);
+    L.pointwise = conv_is_pointwise(g);
+    L.implicit = !L.pointwise && hlq::hla_conv_ok(c, B);
+    const size_t mat = L.pointwise ? 0 : up256(static_cast<size_t>(c.N) * I * e);
+    const size_t Kc = static_cast<size_t>(c.N / B * r);
+    size_t off = 0;
+    L.x = off;     off += L.implicit ? up256(static_cast<size_t>(I) * Kc * (gwi ? 1 : 2)) : mat;
+    L.sx = off;    off += (L.implicit && gwi) ? up256(static_cast<size_t>(I) * 4) : 0;
+    L.xws_bytes = (L.implicit && gwi) ? hlq::hla_quant_ws_bytes(I) : 0;
+    L.xws = off;   off += up256(L.xws_bytes);
+    L.dcols = off; off += mat;
+    L.inner = off;
+    L.inner_bytes = hlq_workspace_bytes_mode(c.N, I, g->O, B, r, L.implicit ? 1 : 0, flags);
     L.total = L.inner + L.inner_bytes;
     return L;
 }
@@ -674,7 +734,7 @@ static ConvLayout conv_layout(const hlq::ConvShape &c, const hlq_conv_geom *g, i
 size_t hlq_conv_workspace_bytes(const hlq_conv_geom *g, int B, int r, int dtype, int flags)
 {
     hlq::ConvShape c;
-    if (conv_shape(g, &c) != HLQ_OK || check_dtype(dtype) != HLQ_OK) return 0;
+    if (conv_shape(g, &c) != HLQ_OK || check_dtype(dtype) != HLQ_OK || check_block(B) != HLQ_OK) return 0;
     const ConvLayout L = conv_layout(c, g, B, r, dtype, flags);
     return L.inner_bytes == 0 ? 0 : L.total;
 }
@@ -688,9 +748,8 @@ int hlq_conv2d_backward(const void *G, const void *X, const void *Wt, const hlq_
     if ((rc = conv_shape(g, &c)) != HLQ_OK) return rc;
     if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
     const int64_t I = static_cast<int64_t>(c.kh) * c.kw * c.C;
-    const bool pointwise = conv_is_pointwise(g);
-    // every refusal of the linear pass, before anything is launched (the column matrix stands in
-    // for X; its address inside the workspace is aligned by construction)
+    // every refusal of the linear pass, before anything is launched (the image stands in for the
+    // column matrix; the buffers inside the workspace are aligned by construction)
     if ((rc = backward_check(G, dW ? X : nullptr, nullptr, nullptr, dX ? Wt : nullptr, nullptr, nullptr, c.N, I, g->O, B,
                              r, dtype, flags, dX, dW)) != HLQ_OK)
         return rc;
@@ -705,19 +764,38 @@ int hlq_conv2d_backward(const void *G, const void *X, const void *Wt, const hlq_
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool f32 = dtype == HLQ_F32;
-    const void *xmat = X;
+    const bool gwi = (flags & HLQ_FLAG_GW_INT8) != 0;
+    const void *xmat = X, *xc = nullptr;
+    const float *sxc = nullptr;
     void *dxmat = dX;
-    if (!pointwise) {
-        if (dW) {
-            if ((rc = launch_rc(hlq::launch_im2col(X, c, f32, ws + L.cols, st))) != HLQ_OK) return rc;
-            xmat = ws + L.cols;
+    if (!L.pointwise) {
+        if (dW && L.implicit) {
+            // stage 1 (and 2) of the g_w list straight from the image
+            const int basis = (flags & HLQ_FLAG_GW_SEQUENCY) ? HLQ_BASIS_SEQUENCY : HLQ_BASIS_NATURAL;
+            if (gwi) {
+                const uint64_t key = stream_key(seed, 2);
+                float *sx = reinterpret_cast<float *>(ws + L.sx);
+                rc = launch_rc(hlq::launch_hla_quant_conv(X, c, B, r, basis, f32, static_cast<uint32_t>(key),
+                                                          static_cast<uint32_t>(key >> 32),
+                                                          (flags & HLQ_FLAG_ROUND_MANTISSA) != 0,
+                                                          reinterpret_cast<int8_t *>(ws + L.x), sx, nullptr, ws + L.xws, st));
+                sxc = sx;
+            } else {
+                rc = launch_rc(hlq::launch_hla_conv(X, c, B, r, basis, f32, reinterpret_cast<uint16_t *>(ws + L.x), nullptr, st));
+            }
+            if (rc != HLQ_OK) return rc;
+            xmat = nullptr;
+            xc = ws + L.x;
+        } else if (dW) {
+            if ((rc = launch_rc(hlq::launch_im2col(X, c, f32, ws + L.x, st))) != HLQ_OK) return rc;
+            xmat = ws + L.x;
         }
         if (dX) dxmat = ws + L.dcols;
     }
-    rc = backward_impl(G, dW ? xmat : nullptr, nullptr, nullptr, dX ? Wt : nullptr, nullptr, nullptr, c.N, I, g->O, B, r,
-                       seed, dtype, flags, dxmat, dW, ws + L.inner, L.inner_bytes, stream);
+    rc = backward_impl(G, dW ? xmat : nullptr, dW ? xc : nullptr, dW ? sxc : nullptr, dX ? Wt : nullptr, nullptr, nullptr,
+                       c.N, I, g->O, B, r, seed, dtype, flags, dxmat, dW, ws + L.inner, L.inner_bytes, stream);
     if (rc != HLQ_OK) return rc;
-    if (!pointwise && dX) return launch_rc(hlq::launch_col2im(dxmat, c, f32, dX, st));
+    if (!L.pointwise && dX) return launch_rc(hlq::launch_col2im(dxmat, c, f32, dX, st));
     return HLQ_OK;
 }
 

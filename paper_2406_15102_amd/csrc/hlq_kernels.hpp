@@ -133,6 +133,15 @@ hipError_t launch_im2col(const void *X, const ConvShape &g, bool is_f32, void *c
 // cols [N, kh*kw*C] -> dx [Nb, H, W, C]: each pixel sums the entries copied from it (fp32, fixed order)
 hipError_t launch_col2im(const void *cols, const ConvShape &g, bool is_f32, void *dx, hipStream_t st);
 
+// K3 / K3q on the column matrix of X [Nb, H, W, C] without storing it: same outputs as launch_hla /
+// launch_hla_quant on launch_im2col's result, D = kh*kw*C.  Needs hla_conv_ok (C a multiple of the
+// 128 / B features a lane owns).
+bool hla_conv_ok(const ConvShape &g, int B);
+hipError_t launch_hla_conv(const void *X, const ConvShape &g, int B, int r, int basis, bool is_f32, uint16_t *ThatT,
+                           float *coeffT, hipStream_t st);
+hipError_t launch_hla_quant_conv(const void *X, const ConvShape &g, int B, int r, int basis, bool is_f32, uint32_t k0,
+                                 uint32_t k1, bool mant, int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st);
+
 // Diagnostic: `blocks` workgroups of 4 wavefronts each run `iters` x 8 independent 32x32 MFMAs
 // (kind 0: i8, K = 32; kind 1: bf16, K = 16) from registers.
 hipError_t launch_mfma_probe(int kind, int blocks, int iters, float *sink, hipStream_t st);

@@ -121,4 +121,100 @@ hipError_t launch_hla_quant(const void *T, int64_t N, int D, int B, int r, int b
     return hipErrorInvalidValue;
 }
 
+// ---- the same three kernels on the column matrix of a channels-last image (Sec. 3.1), read through
+// ---- ConvRows: the column matrix [N = Nb*Ho*Wo, D = kh*kw*C] is never stored ----------------------
+template <typename Tin, int B, int BASIS>
+__global__ __launch_bounds__(256) void k_hla_conv(const Tin *__restrict__ X, ConvShape g, int D, int r,
+                                                  bf16_t *__restrict__ ThatT, float *__restrict__ coeffT)
+{
+    hla_body_src<B, BASIS>(ConvRows<Tin>{X, g}, g.N, D, r, ThatT, coeffT, blockIdx.x, blockIdx.y);
+}
+
+template <typename Tin, int B, int BASIS>
+__global__ __launch_bounds__(256) void k_hla_absmax_conv(const Tin *__restrict__ X, ConvShape g, int D, int r,
+                                                         uint32_t *__restrict__ amax_bits)
+{
+    hla_absmax_body_src<B, BASIS>(ConvRows<Tin>{X, g}, g.N, D, r, amax_bits, blockIdx.x, blockIdx.y);
+}
+
+template <typename Tin, int B, int BASIS, bool MANT>
+__global__ __launch_bounds__(256) void k_hla_quantize_conv(const Tin *__restrict__ X, ConvShape g, int D, int r,
+                                                           const uint32_t *__restrict__ amax_bits, uint32_t k0,
+                                                           uint32_t k1, int8_t *__restrict__ TqT, float *__restrict__ sT,
+                                                           float *__restrict__ coeffT)
+{
+    hla_quantize_body_src<B, BASIS, MANT>(ConvRows<Tin>{X, g}, g.N, D, r, amax_bits, k0, k1, TqT, sT, coeffT, blockIdx.x,
+                                          blockIdx.y);
+}
+
+bool hla_conv_ok(const ConvShape &g, int B) { return g.C % (128 / B) == 0; }
+
+template <typename Tin, int B, int BASIS>
+static hipError_t launch_hla_conv_t(const void *X, const ConvShape &g, int r, bf16_t *ThatT, float *coeffT, hipStream_t st)
+{
+    constexpr int CPL = 128 / B;
+    const int D = g.kh * g.kw * g.C;
+    dim3 grid((D + 64 * CPL - 1) / (64 * CPL), static_cast<unsigned>((g.N / B + 3) / 4));
+    hipLaunchKernelGGL((k_hla_conv<Tin, B, BASIS>), grid, dim3(256), 0, st, static_cast<const Tin *>(X), g, D, r, ThatT, coeffT);
+    return hipGetLastError();
+}
+
+hipError_t launch_hla_conv(const void *X, const ConvShape &g, int B, int r, int basis, bool is_f32, uint16_t *ThatT,
+                           float *coeffT, hipStream_t st)
+{
+    if (!hla_conv_ok(g, B)) return hipErrorInvalidValue;
+#define HLQ_HLAC_CASE(BB)                                                                        \
+    case BB:                                                                                     \
+        if (basis)                                                                               \
+            return is_f32 ? launch_hla_conv_t<float, BB, 1>(X, g, r, ThatT, coeffT, st)          \
+                          : launch_hla_conv_t<bf16_t, BB, 1>(X, g, r, ThatT, coeffT, st);        \
+        return is_f32 ? launch_hla_conv_t<float, BB, 0>(X, g, r, ThatT, coeffT, st)              \
+                      : launch_hla_conv_t<bf16_t, BB, 0>(X, g, r, ThatT, coeffT, st);
+    switch (B) {
+        HLQ_HLAC_CASE(16)
+        HLQ_HLAC_CASE(32)
+        HLQ_HLAC_CASE(64)
+    }
+#undef HLQ_HLAC_CASE
+    return hipErrorInvalidValue;
+}
+
+template <typename Tin, int B, int BASIS>
+static hipError_t launch_hla_quant_conv_t(const void *X, const ConvShape &g, int r, uint32_t k0, uint32_t k1, bool mant,
+                                          int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st)
+{
+    constexpr int CPL = 128 / B;
+    const int D = g.kh * g.kw * g.C;
+    uint32_t *amax = static_cast<uint32_t *>(ws);
+    const Tin *x = static_cast<const Tin *>(X);
+    dim3 grid((D + 64 * CPL - 1) / (64 * CPL), static_cast<unsigned>((g.N / B + 3) / 4));
+    hipLaunchKernelGGL(k_hla_fill_u32, dim3((D + 255) / 256), dim3(256), 0, st, amax, D, 0u);
+    hipLaunchKernelGGL((k_hla_absmax_conv<Tin, B, BASIS>), grid, dim3(256), 0, st, x, g, D, r, amax);
+    if (mant)
+        hipLaunchKernelGGL((k_hla_quantize_conv<Tin, B, BASIS, true>), grid, dim3(256), 0, st, x, g, D, r, amax, k0, k1, TqT, sT, coeffT);
+    else
+        hipLaunchKernelGGL((k_hla_quantize_conv<Tin, B, BASIS, false>), grid, dim3(256), 0, st, x, g, D, r, amax, k0, k1, TqT, sT, coeffT);
+    return hipGetLastError();
+}
+
+hipError_t launch_hla_quant_conv(const void *X, const ConvShape &g, int B, int r, int basis, bool is_f32, uint32_t k0,
+                                 uint32_t k1, bool mant, int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st)
+{
+    if (!hla_conv_ok(g, B)) return hipErrorInvalidValue;
+#define HLQ_HLAQC_CASE(BB)                                                                                     \
+    case BB:                                                                                                   \
+        if (basis)                                                                                             \
+            return is_f32 ? launch_hla_quant_conv_t<float, BB, 1>(X, g, r, k0, k1, mant, TqT, sT, coeffT, ws, st)  \
+                          : launch_hla_quant_conv_t<bf16_t, BB, 1>(X, g, r, k0, k1, mant, TqT, sT, coeffT, ws, st); \
+        return is_f32 ? launch_hla_quant_conv_t<float, BB, 0>(X, g, r, k0, k1, mant, TqT, sT, coeffT, ws, st)      \
+                      : launch_hla_quant_conv_t<bf16_t, BB, 0>(X, g, r, k0, k1, mant, TqT, sT, coeffT, ws, st);
+    switch (B) {
+        HLQ_HLAQC_CASE(16)
+        HLQ_HLAQC_CASE(32)
+        HLQ_HLAQC_CASE(64)
+    }
+#undef HLQ_HLAQC_CASE
+    return hipErrorInvalidValue;
+}
+
 }  // namespace hlq

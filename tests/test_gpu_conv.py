@@ -140,3 +140,46 @@ def test_rejections_leave_outputs_untouched():
             hlq.hlq_conv2d_backward(G, X, Wt, _geom(g), a["B"], a["r"], 0, 0, dX, dW, a["workspace"])
     torch.cuda.synchronize()
     assert bool((dX == 7.0).all()) and bool((dW == 7.0).all())
+
+
+@pytest.mark.parametrize("g,B,r,basis", [(GEOMS[0], 16, 8, 0), (GEOMS[9], 16, 4, 1), (GEOMS[0], 16, 8, 1), (GEOMS[1], 32, 16, 0),
+                                         (GEOMS[9], 64, 32, 1), (GEOMS[4], 16, 8, 0), (GEOMS[8], 16, 2, 0),
+                                         (GEOMS[7], 32, 8, 0), (GEOMS[10], 32, 32, 0), (GEOMS[3], 16, 16, 1)])
+def test_compression_straight_from_the_image_equals_that_of_the_column_matrix(g, B, r, basis):
+    Nb, H, W, C, O, kh, kw, st, pd, dl, dtype = g
+    t, N, I = _tensors(g)
+    Kc = N // B * r
+    X = t["X"].to(DEV).contiguous()
+    geom = _geom(g)
+    cols = torch.empty((N, I), dtype=X.dtype, device=DEV)
+    hlq.hlq_im2col(X, geom, cols)
+    a, b = (torch.full((I, Kc), 3.0, dtype=torch.bfloat16, device=DEV) for _ in range(2))
+    ca, cb = (torch.full((I, Kc), 3.0, dtype=torch.float32, device=DEV) for _ in range(2))
+    hlq.hlq_hla_project_basis(cols, B, r, basis, a, ca)
+    hlq.hlq_conv_compress_act(X, geom, B, r, basis, b, cb)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b) and torch.equal(ca, cb)
+    # against the oracle's projection of its own column matrix
+    ref = oracle.hla_f32(oracle.im2col(wl.as_f32_numpy(t["X"]), kh, kw, st, pd, dl), B, r, basis)
+    scale = np.sqrt(B) * np.maximum(np.abs(ref).max(), 1e-30)
+    assert np.max(np.abs(cb.cpu().numpy() - ref)) <= 1e-5 * scale
+    if r % 4 == 0 and Kc % 16 == 0:
+        qa, qb = (torch.full((I, Kc), 3, dtype=torch.int8, device=DEV) for _ in range(2))
+        sa, sb = (torch.full((I,), 3.0, dtype=torch.float32, device=DEV) for _ in range(2))
+        ws = torch.empty(hlq.hlq_hla_quantize_workspace_bytes(I), dtype=torch.uint8, device=DEV)
+        hlq.hlq_hla_quantize_basis(cols, B, r, basis, 21, 2, qa, sa, ws)
+        hlq.hlq_conv_compress_act_int8(X, geom, B, r, basis, 21, qb, sb, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(qa, qb) and torch.equal(sa, sb)
+
+
+def test_image_path_refuses_channel_counts_that_split_a_lane():
+    g = GEOMS[5]                                                   # 4 channels, a lane owns 8 columns at B = 16
+    t, N, I = _tensors(g)
+    X = t["X"].to(DEV).contiguous()
+    out = torch.full((I, N // 16 * 8), 3.0, dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(hlq.HlqError):
+        hlq.hlq_conv_compress_act(X, _geom(g), 16, 8, 0, out)
+    hlq.hlq_conv_compress_act(X, _geom(g), 32, 16, 0, torch.empty((I, N // 32 * 16), dtype=torch.bfloat16, device=DEV))
+    torch.cuda.synchronize()
+    assert bool((out == 3.0).all())
