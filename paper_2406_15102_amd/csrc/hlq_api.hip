@@ -393,9 +393,12 @@ static int backward_check(const void *G, const void *X, const void *Xc, const fl
     return HLQ_OK;
 }
 
+// conv: NULL, or the geometry of a convolution; X is then its channels-last image and stands for
+// the column matrix [N, d_in], which the g_w list reads through the image (hla_conv_ok required).
 static int backward_impl(const void *G, const void *X, const void *Xc, const float *sXc, const void *W, const void *Wc,
                          const float *sWc, int64_t N, int64_t d_in, int64_t d_out, int B, int r, uint64_t seed, int dtype,
-                         int flags, void *dX, void *dW, void *workspace, size_t workspace_bytes, void *stream)
+                         int flags, void *dX, void *dW, void *workspace, size_t workspace_bytes, void *stream,
+                         const hlq::ConvShape *conv = nullptr)
 {
     int rc;
     if ((rc = backward_check(G, X, Xc, sXc, W, Wc, sWc, N, d_in, d_out, B, r, dtype, flags, dX, dW)) != HLQ_OK) return rc;
@@ -451,12 +454,20 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         const hlq::FrontFill jf{amax_w, static_cast<int>(zero_bytes / 4)};
         const hlq::FrontHla none = hlq::front_hla(nullptr, N, O, B, r, nullptr);
         const hlq::FrontAbsmax none_w = hlq::front_absmax(nullptr, O, I, B, nullptr);
-        if ((rc = launch_rc(hlq::launch_front(jr, none, jf, none, none_w, B, basis, f32, packed, st))) != HLQ_OK) return rc;
+        if ((rc = launch_rc(hlq::launch_front(jr, none, jf, none, none_w, nullptr, B, basis, f32, packed, st))) != HLQ_OK)
+            return rc;
         int8_t *xq = xc ? nullptr : reinterpret_cast<int8_t *>(ws + L.XhatT);
         float *sx = xc ? nullptr : reinterpret_cast<float *>(ws + L.sXhat);
+        if (conv && dW && !xc) {
+            // the image's projection keeps its own launches (it zeroes its maxima itself)
+            if ((rc = launch_rc(hlq::launch_hla_quant_conv(X, *conv, B, r, basis, f32, static_cast<uint32_t>(k2),
+                                                           static_cast<uint32_t>(k2 >> 32), mant, xq, sx, nullptr, amax_x,
+                                                           st))) != HLQ_OK)
+                return rc;
+        }
         const hlq::FrontHlaQ jg = hlq::front_hlaq(dW ? G : nullptr, N, O, B, r, amax_g, static_cast<uint32_t>(k3),
                                                   static_cast<uint32_t>(k3 >> 32), static_cast<int8_t *>(Gh), sGh);
-        const hlq::FrontHlaQ jx = hlq::front_hlaq(dW && !xc ? X : nullptr, N, I, B, r, amax_x, static_cast<uint32_t>(k2),
+        const hlq::FrontHlaQ jx = hlq::front_hlaq(dW && !xc && !conv ? X : nullptr, N, I, B, r, amax_x, static_cast<uint32_t>(k2),
                                                   static_cast<uint32_t>(k2 >> 32), xq, sx);
         const bool wq = dX && !wc;
         const hlq::FrontAbsmax jw = hlq::front_absmax(wq ? W : nullptr, O, I, B, amax_w);
@@ -477,7 +488,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         const hlq::FrontFill jf{reinterpret_cast<uint32_t *>(ws + L.wws), dX && !wc ? I : 0};
         const hlq::FrontHla jg = hlq::front_hla(dW ? G : nullptr, N, O, B, r, static_cast<uint16_t *>(Gh));
         const hlq::FrontAbsmax jw = hlq::front_absmax(dX && !wc ? W : nullptr, O, I, B, reinterpret_cast<uint32_t *>(ws + L.wws));
-        if ((rc = launch_rc(hlq::launch_front(jr, jx, jf, jg, jw, B, basis, f32, packed, st))) != HLQ_OK) return rc;
+        if ((rc = launch_rc(hlq::launch_front(jr, jx, jf, jg, jw, conv, B, basis, f32, packed, st))) != HLQ_OK) return rc;
         if (dW && !xc) Xh = xh;
     }
     if (dX && !fused && !fused_q) {
@@ -491,7 +502,9 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         if ((rc = launch_rc(hlq::launch_hla(G, N, O, B, r, basis, f32, static_cast<uint16_t *>(Gh), nullptr, st))) != HLQ_OK) return rc;
         if (!xc) {
             uint16_t *xh = reinterpret_cast<uint16_t *>(ws + L.XhatT);
-            if ((rc = launch_rc(hlq::launch_hla(X, N, I, B, r, basis, f32, xh, nullptr, st))) != HLQ_OK) return rc;
+            rc = launch_rc(conv ? hlq::launch_hla_conv(X, *conv, B, r, basis, f32, xh, nullptr, st)
+                                : hlq::launch_hla(X, N, I, B, r, basis, f32, xh, nullptr, st));
+            if (rc != HLQ_OK) return rc;
             Xh = xh;
         }
     }
@@ -505,10 +518,13 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         if (!xc) {
             int8_t *xq = reinterpret_cast<int8_t *>(ws + L.XhatT);
             float *sx = reinterpret_cast<float *>(ws + L.sXhat);
-            if ((rc = launch_rc(hlq::launch_hla_quant(X, N, I, B, r, basis, f32, static_cast<uint32_t>(k2),
-                                                      static_cast<uint32_t>(k2 >> 32), mant, xq, sx, nullptr, ws + L.hws,
-                                                      st))) != HLQ_OK)
-                return rc;
+            rc = launch_rc(conv ? hlq::launch_hla_quant_conv(X, *conv, B, r, basis, f32, static_cast<uint32_t>(k2),
+                                                             static_cast<uint32_t>(k2 >> 32), mant, xq, sx, nullptr,
+                                                             ws + L.hws, st)
+                                : hlq::launch_hla_quant(X, N, I, B, r, basis, f32, static_cast<uint32_t>(k2),
+                                                        static_cast<uint32_t>(k2 >> 32), mant, xq, sx, nullptr, ws + L.hws,
+                                                        st));
+            if (rc != HLQ_OK) return rc;
             Xh = xq;
             sXh = sx;
         }
@@ -701,32 +717,24 @@ int hlq_conv_compress_act_int8(const void *X, const hlq_conv_geom *g, int B, int
                                                 static_cast<hipStream_t>(stream)));
 }
 
-// Workspace of the convolution pass: [x | sx | xws | column gradient | the linear pass's own].
-// `x` is the compressed column matrix (projected straight from the image) when the channel count
-// allows, else the column matrix itself; sx / xws its scales and column maxima (integer g_w list).
+// Workspace of the convolution pass: [column matrix | column gradient | the linear pass's own].
+// The column matrix is stored only when the g_w list cannot read it through the image.
 struct ConvLayout {
     bool pointwise, implicit;
-    size_t x, sx, xws, xws_bytes, dcols, inner, inner_bytes, total;
+    size_t cols, dcols, inner, inner_bytes, total;
 };
 
 static ConvLayout conv_layout(const hlq::ConvShape &c, const hlq_conv_geom *g, int B, int r, int dtype, int flags)
 {
     const int64_t I = static_cast<int64_t>(c.kh) * c.kw * c.C;
-    const size_t e = dtype == HLQ_F32 ? 4 : 2;
-    const bool gwi = (flags & HLQ_FLAG_GW_INT8) != 0;
     ConvLayout L;
     L.pointwise = conv_is_pointwise(g);
     L.implicit = !L.pointwise && hlq::hla_conv_ok(c, B);
-    const size_t mat = L.pointwise ? 0 : up256(static_cast<size_t>(c.N) * I * e);
-    const size_t Kc = static_cast<size_t>(c.N / B * r);
-    size_t off = 0;
-    L.x = off;     off += L.implicit ? up256(static_cast<size_t>(I) * Kc * (gwi ? 1 : 2)) : mat;
-    L.sx = off;    off += (L.implicit && gwi) ? up256(static_cast<size_t>(I) * 4) : 0;
-    L.xws_bytes = (L.implicit && gwi) ? hlq::hla_quant_ws_bytes(I) : 0;
-    L.xws = off;   off += up256(L.xws_bytes);
-    L.dcols = off; off += mat;
-    L.inner = off;
-    L.inner_bytes = hlq_workspace_bytes_mode(c.N, I, g->O, B, r, L.implicit ? 1 : 0, flags);
+    const size_t mat = L.pointwise ? 0 : up256(static_cast<size_t>(c.N) * I * (dtype == HLQ_F32 ? 4 : 2));
+    L.cols = 0;
+    L.dcols = L.implicit ? 0 : mat;
+    L.inner = L.dcols + mat;
+    L.inner_bytes = hlq_workspace_bytes_mode(c.N, I, g->O, B, r, 0, flags);
     L.total = L.inner + L.inner_bytes;
     return L;
 }
@@ -764,36 +772,17 @@ int hlq_conv2d_backward(const void *G, const void *X, const void *Wt, const hlq_
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     const bool f32 = dtype == HLQ_F32;
-    const bool gwi = (flags & HLQ_FLAG_GW_INT8) != 0;
-    const void *xmat = X, *xc = nullptr;
-    const float *sxc = nullptr;
+    const void *xmat = X;
     void *dxmat = dX;
     if (!L.pointwise) {
-        if (dW && L.implicit) {
-            // stage 1 (and 2) of the g_w list straight from the image
-            const int basis = (flags & HLQ_FLAG_GW_SEQUENCY) ? HLQ_BASIS_SEQUENCY : HLQ_BASIS_NATURAL;
-            if (gwi) {
-                const uint64_t key = stream_key(seed, 2);
-                float *sx = reinterpret_cast<float *>(ws + L.sx);
-                rc = launch_rc(hlq::launch_hla_quant_conv(X, c, B, r, basis, f32, static_cast<uint32_t>(key),
-                                                          static_cast<uint32_t>(key >> 32),
-                                                          (flags & HLQ_FLAG_ROUND_MANTISSA) != 0,
-                                                          reinterpret_cast<int8_t *>(ws + L.x), sx, nullptr, ws + L.xws, st));
-                sxc = sx;
-            } else {
-                rc = launch_rc(hlq::launch_hla_conv(X, c, B, r, basis, f32, reinterpret_cast<uint16_t *>(ws + L.x), nullptr, st));
-            }
-            if (rc != HLQ_OK) return rc;
-            xmat = nullptr;
-            xc = ws + L.x;
-        } else if (dW) {
-            if ((rc = launch_rc(hlq::launch_im2col(X, c, f32, ws + L.x, st))) != HLQ_OK) return rc;
-            xmat = ws + L.x;
+        if (dW && !L.implicit) {
+            if ((rc = launch_rc(hlq::launch_im2col(X, c, f32, ws + L.cols, st))) != HLQ_OK) return rc;
+            xmat = ws + L.cols;
         }
         if (dX) dxmat = ws + L.dcols;
     }
-    rc = backward_impl(G, dW ? xmat : nullptr, dW ? xc : nullptr, dW ? sxc : nullptr, dX ? Wt : nullptr, nullptr, nullptr,
-                       c.N, I, g->O, B, r, seed, dtype, flags, dxmat, dW, ws + L.inner, L.inner_bytes, stream);
+    rc = backward_impl(G, dW ? xmat : nullptr, nullptr, nullptr, dX ? Wt : nullptr, nullptr, nullptr, c.N, I, g->O, B, r,
+                       seed, dtype, flags, dxmat, dW, ws + L.inner, L.inner_bytes, stream, L.implicit ? &c : nullptr);
     if (rc != HLQ_OK) return rc;
     if (!L.pointwise && dX) return launch_rc(hlq::launch_col2im(dxmat, c, f32, dX, st));
     return HLQ_OK;

@@ -26,6 +26,12 @@ hipError_t launch_quant_cols_pass2(const void *W, int O, int I, int B, bool is_f
                                    float qmax, bool packed, bool mant, int8_t *WqT, float *sW, float *coeffT,
                                    const void *ws, hipStream_t st);
 
+// Geometry of a convolution over channels-last tensors.  N = Nb * Ho * Wo rows of the column matrix.
+struct ConvShape {
+    int Nb, H, W, C, kh, kw, sh, sw, ph, pw, dh, dw, Ho, Wo;
+    int64_t N;
+};
+
 // The independent transforms of one backward pass in two launches (k_front.hip).  A job with a
 // null tensor is empty.
 struct FrontRows {   // K1 on G, 256-thread variant
@@ -44,6 +50,10 @@ struct FrontHla {    // K3 on one tensor
     int D, r;
     uint16_t *out;
     int gx, gy;
+};
+struct FrontConv {   // on: the K3(X) job of front A reads the column matrix of an image (jx.T = the image)
+    ConvShape g;
+    int on;
 };
 struct FrontFill {   // n words at p := 0
     uint32_t *p;
@@ -87,8 +97,10 @@ bool front_fusable(int O, int B);
 FrontRows front_rows(const void *G, int64_t N, int O, int B, uint32_t k0, uint32_t k1, float qmax, int8_t *Gq, float *sG);
 FrontHla front_hla(const void *T, int64_t N, int D, int B, int r, uint16_t *out);
 FrontAbsmax front_absmax(const void *W, int O, int I, int B, uint32_t *amax);
+// conv: NULL, or the geometry whose column matrix jx.T (an image) stands for; needs hla_conv_ok.
 hipError_t launch_front(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
-                        const FrontAbsmax &jw, int B, int basis, bool is_f32, bool packed, hipStream_t st);
+                        const FrontAbsmax &jw, const ConvShape *conv, int B, int basis, bool is_f32, bool packed,
+                        hipStream_t st);
 
 // K3: token-axis Hadamard low-rank projection, T [N, D] -> ThatT [D, N/B*r] bf16.
 // basis: which r rows of the order-B matrix are kept, 0 = rows 0..r-1, 1 = the r of lowest sequency.
@@ -123,11 +135,7 @@ hipError_t launch_splitk_reduce(int kind, const GemmArgs &a, int splits, hipStre
 // (few output tiles, long reduction); 0 if the plan does not split.
 size_t gemm_ws_bytes(int kind, int M, int N, int K);
 
-// Convolution glue (k_conv.hip), channels-last tensors.  N = Nb * Ho * Wo rows of the column matrix.
-struct ConvShape {
-    int Nb, H, W, C, kh, kw, sh, sw, ph, pw, dh, dw, Ho, Wo;
-    int64_t N;
-};
+// Convolution glue (k_conv.hip), channels-last tensors.
 // x [Nb, H, W, C] -> cols [N, kh*kw*C], columns ordered (ky, kx, c), zero padding
 hipError_t launch_im2col(const void *X, const ConvShape &g, bool is_f32, void *cols, hipStream_t st);
 // cols [N, kh*kw*C] -> dx [Nb, H, W, C]: each pixel sums the entries copied from it (fp32, fixed order)

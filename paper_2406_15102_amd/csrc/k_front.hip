@@ -3,7 +3,8 @@
 // list (column maxima of H^T W) do not depend on one another (arXiv 2406.15102, Sec. 6.1), and each
 // costs a few tens of microseconds, of which four to five are the fixed price of a launch that
 // waits for its predecessor to drain.  Two launches carry them instead of six:
-//   front A   K1(G)  |  K3(X)  |  zeroing of the column maxima
+//   front A   K1(G)  |  K3(X)  |  zeroing of the column maxima      (X a matrix, or the image of a
+//                                                                    convolution read as its column matrix)
 //   front B   K3(G)  |  column maxima of H^T W      (needs the zeroing; G is re-read while the
 //                                                    last-level cache still holds it)
 // and three launches carry the integer g_w list, whose projections are quantised in two passes too:
@@ -19,8 +20,11 @@
 
 namespace hlq {
 
-template <typename Tin, int B, bool PACKED, int BASIS>
-__global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, FrontFill jf)
+// CONV: X is a channels-last image and K3 reads its column matrix through ConvRows.  A kernel of
+// its own: the extra address arithmetic would cost the matrix variant registers, and with them a
+// wavefront of occupancy at B = 32.
+template <typename Tin, int B, bool PACKED, int BASIS, bool CONV>
+__global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, FrontFill jf, FrontConv jc)
 {
     int b = blockIdx.x;
     if (b < jr.blocks) {
@@ -30,7 +34,11 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
     }
     b -= jr.blocks;
     if (b < jx.gx * jx.gy) {
-        hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, b % jx.gx, b / jx.gx);
+        if (CONV)
+            hla_body_src<B, BASIS>(ConvRows<Tin>{static_cast<const Tin *>(jx.T), jc.g}, jx.N, jx.D, jx.r, jx.out, nullptr,
+                                   b % jx.gx, b / jx.gx);
+        else
+            hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, b % jx.gx, b / jx.gx);
         return;
     }
     b -= jx.gx * jx.gy;
@@ -182,12 +190,17 @@ FrontAbsmax front_absmax(const void *W, int O, int I, int B, uint32_t *amax)
 
 template <typename Tin, int B, int BASIS>
 static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
-                                 const FrontAbsmax &jw, bool packed, hipStream_t st)
+                                 const FrontAbsmax &jw, const FrontConv &jc, bool packed, hipStream_t st)
 {
     const int na = jr.blocks + jx.gx * jx.gy + (jf.n + 255) / 256;
     if (na > 0) {
-        if (packed) hipLaunchKernelGGL((k_front_a<Tin, B, true, BASIS>), dim3(na), dim3(256), 0, st, jr, jx, jf);
-        else hipLaunchKernelGGL((k_front_a<Tin, B, false, BASIS>), dim3(na), dim3(256), 0, st, jr, jx, jf);
+#define HLQ_FRONT_A(P, CV) hipLaunchKernelGGL((k_front_a<Tin, B, P, BASIS, CV>), dim3(na), dim3(256), 0, st, jr, jx, jf, jc)
+        if (jc.on) {
+            if (packed) HLQ_FRONT_A(true, true); else HLQ_FRONT_A(false, true);
+        } else {
+            if (packed) HLQ_FRONT_A(true, false); else HLQ_FRONT_A(false, false);
+        }
+#undef HLQ_FRONT_A
     }
     const int nb = jg.gx * jg.gy + jw.gx * jw.gy;
     if (nb > 0) hipLaunchKernelGGL((k_front_b<Tin, B, BASIS>), dim3(nb), dim3(256), 0, st, jg, jw);
@@ -195,15 +208,22 @@ static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const 
 }
 
 hipError_t launch_front(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
-                        const FrontAbsmax &jw, int B, int basis, bool is_f32, bool packed, hipStream_t st)
+                        const FrontAbsmax &jw, const ConvShape *conv, int B, int basis, bool is_f32, bool packed,
+                        hipStream_t st)
 {
+    FrontConv jc{};
+    if (conv) {
+        if (!hla_conv_ok(*conv, B)) return hipErrorInvalidValue;
+        jc.g = *conv;
+        jc.on = 1;
+    }
 #define HLQ_FRONT_CASE(BB)                                                                      \
     case BB:                                                                                    \
         if (basis)                                                                              \
-            return is_f32 ? launch_front_t<float, BB, 1>(jr, jx, jf, jg, jw, packed, st)        \
-                          : launch_front_t<bf16_t, BB, 1>(jr, jx, jf, jg, jw, packed, st);      \
-        return is_f32 ? launch_front_t<float, BB, 0>(jr, jx, jf, jg, jw, packed, st)            \
-                      : launch_front_t<bf16_t, BB, 0>(jr, jx, jf, jg, jw, packed, st);
+            return is_f32 ? launch_front_t<float, BB, 1>(jr, jx, jf, jg, jw, jc, packed, st)        \
+                          : launch_front_t<bf16_t, BB, 1>(jr, jx, jf, jg, jw, jc, packed, st);      \
+        return is_f32 ? launch_front_t<float, BB, 0>(jr, jx, jf, jg, jw, jc, packed, st)            \
+                      : launch_front_t<bf16_t, BB, 0>(jr, jx, jf, jg, jw, jc, packed, st);
     switch (B) {
         HLQ_FRONT_CASE(16)
         HLQ_FRONT_CASE(32)

@@ -185,11 +185,10 @@ def test_convolution_entry_points_without_a_gpu():
     assert call(geom(Nb=1, H=5, W=5)) == 2                       # N = 25 positions: not whole blocks of tokens
     assert call(geom(C=3)) == 2                                  # I = 27: rows of the column matrix must be 16-byte multiples
     assert call(g, wsb=1000) == 6
-    # workspace: the compressed column matrix and the column gradient on top of the linear pass's own
-    # (which then holds no projection of X); the column matrix itself when the channels do not
-    # divide among the lanes; nothing extra for a pointwise kernel
-    inner = hlq.hlq_workspace_bytes_mode(256, 144, 32, 16, 8, True, 0)
-    assert hlq.hlq_conv_workspace_bytes(g, 16, 8, 0) == inner + 144 * 128 * 2 + 256 * 144 * 2
+    # workspace: the column gradient on top of the linear pass's own; the column matrix too when the
+    # channels do not divide among the lanes; nothing extra for a pointwise kernel
+    inner = hlq.hlq_workspace_bytes_mode(256, 144, 32, 16, 8, False, 0)
+    assert hlq.hlq_conv_workspace_bytes(g, 16, 8, 0) == inner + 256 * 144 * 2
     g4 = geom(C=4, kh=2, kw=2, pad_h=0, pad_w=0, stride_h=2, stride_w=2)          # N = 64, I = 16
     assert hlq.hlq_conv_workspace_bytes(g4, 16, 8, 0) == hlq.hlq_workspace_bytes_mode(64, 16, 32, 16, 8, False, 0) + 2 * 64 * 16 * 2
     assert l.hlq_conv_compress_act(FAKE, C.byref(g4), 16, 8, 0, 0, FAKE, None, None) == 2      # 4 channels, 8 per lane
