@@ -115,3 +115,28 @@ def test_paper_latency_table_layers_in_full(name):
     ew = row_rel_err(dW.float().cpu().numpy(), ref["dW"], True)
     print("%s: dX err %.3e  dW err %.3e" % (name, ex, ew))
     assert ex < TOL_OUT and ew < TOL_OUT
+
+
+@pytest.mark.parametrize("name", sorted(wl.CONV_GEOMS))
+def test_convolution_layers_in_full(name):
+    """The ResNet-shaped workloads as real convolutions (channels-last image in, image gradient out),
+    in the configuration bench.py times them, against the oracle's whole pass."""
+    w = wl.WORKLOADS[name]
+    Nb, H, Wd, C, kh, kw, st, pd = wl.CONV_GEOMS[name]
+    O, B, r = w.d_out, w.B, w.r
+    geom = hlq.hlq_conv_geom(Nb=Nb, H=H, W=Wd, C=C, O=O, kh=kh, kw=kw, stride_h=st, stride_w=st, pad_h=pd, pad_w=pd,
+                             dil_h=1, dil_w=1)
+    Ho, Wo, N, I = hlq.hlq_conv_sizes(geom)
+    assert (N, I) == (w.N, w.d_in)
+    t = wl.generate_conv(Nb, H, Wd, C, O, kh, kw, Ho, Wo, w.dtype)
+    G, X, Wt = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
+    dX, dW = torch.empty_like(X), torch.empty_like(Wt)
+    ws = torch.empty(hlq.hlq_conv_workspace_bytes(geom, B, r, hlq.HLQ_BF16, 0), dtype=torch.uint8, device=DEV)
+    hlq.hlq_conv2d_backward(G, X, Wt, geom, B, r, w.seed, 0, dX, dW, ws)
+    torch.cuda.synchronize()
+    ref = oracle.conv2d_backward(wl.as_f32_numpy(t["G"]), wl.as_f32_numpy(t["X"]), wl.as_f32_numpy(t["W"]), B, r, w.seed,
+                                 stride=(st, st), pad=(pd, pd))
+    ex = row_rel_err(dX.float().cpu().numpy().reshape(-1, C), ref["dX_img"].reshape(-1, C), True)
+    ew = row_rel_err(dW.float().cpu().numpy().reshape(O, I), ref["dW_k"].reshape(O, I), True)
+    print("%s as a convolution: dX err %.3e  dW err %.3e" % (name, ex, ew))
+    assert ex < TOL_OUT and ew < TOL_OUT
