@@ -194,6 +194,10 @@ def main():
             continue
         fn = lambda: hlq.hlq_linear_backward_mode(G, X, None, None, W, N, I, O, B, r, w.seed, flags, dX, dW, ws)
         modes[label] = {"us": round(_event_time_us(fn, iters, torch, warm=max(3, args.warmup // 2)), 2)}
+    # ---- the default path with one launch per matrix product (by default the two share a launch) ----
+    sep = lambda: hlq.hlq_linear_backward_mode(G, X, None, None, W, N, I, O, B, r, w.seed, hlq.HLQ_FLAG_SEPARATE_PRODUCTS,
+                                               dX, dW, ws)
+    separate_us = _event_time_us(sep, iters, torch, warm=max(3, args.warmup // 2))
     # ---- the default path with the weight codes handed over (quantised once per optimiser step) ----
     assert hlq.hlq_weight_code_bits(O, 0) == qbits
     hlq.hlq_quantize_w(W, B, w.seed, WqT, sW, wws, None, qbits)
@@ -299,6 +303,7 @@ def main():
         "kernels": kernels,
         "modes_us": modes,
         "cached_weight_codes_us": round(cached_us, 2),
+        "separate_products_us": round(separate_us, 2),
         "as_convolution": conv,
         "copy_256MiB": {"us": round(copy_us, 2), "GB/s": round(2 * (1 << 28) / copy_us / 1e3, 1)},
         "roofline": roofline,

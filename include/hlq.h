@@ -218,6 +218,10 @@ int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64
                                  forward-time store handed over as Xc must have been made the same way */
 #define HLQ_FLAG_ROUND_MANTISSA 16 /* every quantiser of both lists rounds by the values' low 11 mantissa bits
                                      (HLQ_BITS_ROUND_MANTISSA); one launch per stage */
+#define HLQ_FLAG_SEPARATE_PRODUCTS 32 /* one launch per matrix product.  By default the two products of the
+                                        default lists share a launch (they are independent, and neither fills
+                                        the chip for most layers); dX is the same bit for bit either way, dW
+                                        up to the summation order of its k splits. */
 #define HLQ_FLAG_GX_UNPACKED 4 /* keep the 4-bit g_x codes one per int8 between the stages.  By default
                                   they are stored two to a byte whenever d_out % 32 == 0 (same codes, same
                                   dX bit for bit; half the traffic). */

@@ -5,7 +5,7 @@
 from . import workloads  # noqa: F401
 from .binding import (  # noqa: F401
     HLQ_BF16, HLQ_F32, HLQ_BITS_4, HLQ_BITS_4_PACKED, HLQ_BITS_8, HLQ_FLAG_GW_INT8, HLQ_FLAG_GX_8BIT,
-    HLQ_FLAG_GX_UNPACKED, HLQ_FLAG_ROUND_MANTISSA, HLQ_BITS_ROUND_MANTISSA, HLQ_BASIS_ROUND_MANTISSA, HLQ_FLAG_GW_SEQUENCY, HLQ_BASIS_NATURAL, HLQ_BASIS_SEQUENCY, hlq_hla_project_basis,
+    HLQ_FLAG_GX_UNPACKED, HLQ_FLAG_ROUND_MANTISSA, HLQ_FLAG_SEPARATE_PRODUCTS, HLQ_BITS_ROUND_MANTISSA, HLQ_BASIS_ROUND_MANTISSA, HLQ_FLAG_GW_SEQUENCY, HLQ_BASIS_NATURAL, HLQ_BASIS_SEQUENCY, hlq_hla_project_basis,
     hlq_hla_quantize_basis, HlqError, hlq_compress_act_int8, hlq_hla_quantize,
     hlq_hla_quantize_workspace_bytes, hlq_gemm_workspace_bytes, hlq_linear_backward_mode, hlq_linear_backward_cached, hlq_weight_code_bits, hlq_workspace_bytes_mode, exported_symbols, hlq_bf16_gemm_nt, hlq_compress_act, hlq_hla_project,
     hlq_int8_gemm_nt, hlq_int4_gemm_nt, hlq_linear_backward, hlq_mfma_probe, hlq_linear_backward_ex, hlq_quantize_g, hlq_quantize_w,

@@ -21,6 +21,7 @@ HLQ_FLAG_GX_8BIT, HLQ_FLAG_GW_INT8, HLQ_FLAG_GX_UNPACKED, HLQ_FLAG_GW_SEQUENCY =
 HLQ_BASIS_NATURAL, HLQ_BASIS_SEQUENCY = 0, 1
 HLQ_BITS_ROUND_MANTISSA = HLQ_BASIS_ROUND_MANTISSA = 0x200
 HLQ_FLAG_ROUND_MANTISSA = 16
+HLQ_FLAG_SEPARATE_PRODUCTS = 32
 HLQ_BITS_4, HLQ_BITS_8, HLQ_BITS_4_PACKED = 4, 8, 0x104
 
 

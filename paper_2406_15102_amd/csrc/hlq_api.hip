@@ -102,6 +102,14 @@ Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_
     const size_t g1 = hlq::gemm_ws_bytes(0, static_cast<int>(N), static_cast<int>(d_in), static_cast<int>(d_out));
     const size_t g2 = hlq::gemm_ws_bytes(gwi ? 0 : 1, static_cast<int>(d_out), static_cast<int>(d_in), static_cast<int>(Kc));
     L.gws_bytes = g1 > g2 ? g1 : g2;
+    if (!gwi && !(flags & (HLQ_FLAG_GX_8BIT | HLQ_FLAG_GX_UNPACKED | HLQ_FLAG_SEPARATE_PRODUCTS)) && d_out % 32 == 0) {
+        // the two products in one launch plan the g_w product's k split for the pair
+        hlq::GemmArgs ax{}, aw{};
+        ax.M = static_cast<int>(N), ax.N = static_cast<int>(d_in), ax.K = static_cast<int>(d_out);
+        aw.M = static_cast<int>(d_out), aw.N = static_cast<int>(d_in), aw.K = static_cast<int>(Kc);
+        const size_t gp = hlq::gemm_pair_ws_bytes(2, ax, 1, aw, size_t(256) << 20);
+        if (gp > L.gws_bytes) L.gws_bytes = gp;
+    }
     L.gws = off;   off += up256(L.gws_bytes);
     L.total = off;
     return L;
@@ -109,7 +117,8 @@ Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_
 
 int check_flags(int flags, int r, int64_t N, int B)
 {
-    if (flags & ~(HLQ_FLAG_GX_8BIT | HLQ_FLAG_GW_INT8 | HLQ_FLAG_GX_UNPACKED | HLQ_FLAG_GW_SEQUENCY | HLQ_FLAG_ROUND_MANTISSA)) return HLQ_ERR_SHAPE;
+    if (flags & ~(HLQ_FLAG_GX_8BIT | HLQ_FLAG_GW_INT8 | HLQ_FLAG_GX_UNPACKED | HLQ_FLAG_GW_SEQUENCY | HLQ_FLAG_ROUND_MANTISSA |
+                  HLQ_FLAG_SEPARATE_PRODUCTS)) return HLQ_ERR_SHAPE;
     if (flags & HLQ_FLAG_GW_INT8) {
         if (r % 4 != 0) return HLQ_ERR_RANK;
         if ((N / B * r) % 16 != 0) return HLQ_ERR_SHAPE;
@@ -545,20 +554,18 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
                                                   static_cast<uint32_t>(kw >> 32), qmax, packed, mant, wq, sw, nullptr,
                                                   ws + L.wws, st));
         if (rc != HLQ_OK) return rc;
-        // g_x stages 5-6: integer product and dequantisation (1/B undoes H H^T = B I)
-        hlq::GemmArgs a{Gq, Wq, static_cast<int>(N), I, O, sG, sW, invB, dX, f32, nullptr, ws + L.gws, L.gws_bytes};
-        if ((rc = launch_rc(hlq::launch_gemm_nt(packed ? 2 : 0, a, st))) != HLQ_OK) return rc;
     }
-    if (dW) {
-        // g_w stage 5 (and 6): product over the compressed token axis
-        if (gwi) {
-            hlq::GemmArgs a{Gh, Xh, O, I, Kc, sGh, sXh, invB, dW, f32, nullptr, ws + L.gws, L.gws_bytes};
-            if ((rc = launch_rc(hlq::launch_gemm_nt(0, a, st))) != HLQ_OK) return rc;
-        } else {
-            hlq::GemmArgs a{Gh, Xh, O, I, Kc, nullptr, nullptr, invB, dW, f32, nullptr, ws + L.gws, L.gws_bytes};
-            if ((rc = launch_rc(hlq::launch_gemm_nt(1, a, st))) != HLQ_OK) return rc;
-        }
-    }
+    // The products: g_x stages 5-6 (integer product and dequantisation; 1/B undoes H H^T = B I) and
+    // g_w stage 5 (and 6) over the compressed token axis.  Independent of each other: one launch
+    // carries both when that combination of kernels is built (k_gemm_pair.hip).
+    hlq::GemmArgs ax{Gq, Wq, static_cast<int>(N), I, O, sG, sW, invB, dX, f32, nullptr, ws + L.gws, L.gws_bytes};
+    hlq::GemmArgs aw{Gh, Xh, O, I, Kc, gwi ? sGh : nullptr, gwi ? sXh : nullptr, invB, dW, f32, nullptr, ws + L.gws,
+                     L.gws_bytes};
+    const int kx = packed ? 2 : 0, kw_ = gwi ? 0 : 1;
+    if (dX && dW && !(flags & HLQ_FLAG_SEPARATE_PRODUCTS) && hlq::gemm_pair_available(kx, ax, kw_, aw))
+        return launch_rc(hlq::launch_gemm_pair(kx, ax, kw_, aw, st));
+    if (dX && (rc = launch_rc(hlq::launch_gemm_nt(kx, ax, st))) != HLQ_OK) return rc;
+    if (dW && (rc = launch_rc(hlq::launch_gemm_nt(kw_, aw, st))) != HLQ_OK) return rc;
     return HLQ_OK;
 }
 

@@ -131,6 +131,15 @@ struct GemmArgs {
 };
 hipError_t launch_gemm_nt(int kind, const GemmArgs &a, hipStream_t st);
 hipError_t launch_splitk_reduce(int kind, const GemmArgs &a, int splits, hipStream_t st);
+// K2 | K4 in one launch (k_gemm_pair.hip): product `a` of kind 2 and product `b` of kind 1, both
+// with a scaled output of the same dtype.  Only b's k may be split (b.ws).  gemm_pair_available
+// says whether the combination is built; the results are those of two launch_gemm_nt calls up to
+// the summation order of b's k splits.
+bool gemm_pair_available(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b);
+hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, hipStream_t st);
+// split-k scratch (b.ws) that the pair's plan would use if it may have up to `cap` bytes; only the
+// shapes and kinds of a and b are read
+size_t gemm_pair_ws_bytes(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, size_t cap);
 // Scratch that lets launch_gemm_nt split k whenever that is the faster plan for this shape
 // (few output tiles, long reduction); 0 if the plan does not split.
 size_t gemm_ws_bytes(int kind, int M, int N, int K);

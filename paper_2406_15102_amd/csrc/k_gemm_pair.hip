@@ -1,0 +1,195 @@
+// K2 | K4 in one launch.  The two products of a backward pass (arXiv 2406.15102, Sec. 6.1: stage 5
+// of the g_x list and stage 5 of the g_w list) do not depend on each other, and for all but the
+// largest layers neither fills the chip by itself: 150 tiles of 256 x 256 at the ViT MLP, a
+// handful at a ResNet layer, against 256 compute units.  Launched together, the tiles of one fill
+// the compute units the other leaves idle, the tail of one overlaps the start of the other, and
+// one launch latency goes away.  A workgroup runs the tile body of gemm_body.hpp of whichever
+// product its index falls in (first the g_x product's tiles, padded to a multiple of 8 so that the
+// second product's tiles keep their XCD assignment, then the g_w product's).  The tile sizes and
+// the k split of the g_w product are planned for the pair, not for each product alone.
+//
+// Instantiated for the default lists: packed 4-bit codes (kind 2) with bf16 or fp32 output for
+// g_x; bf16 operands (kind 1) with direct output or split-k partials for g_w.  Other combinations
+// keep one launch per product.
+#include "gemm_body.hpp"
+#include "gemm_plan.hpp"
+
+namespace hlq {
+
+template <int KIND_, int W_, bool TAIL_, int OUT_> struct TileCfg {
+    static constexpr int KIND = KIND_, W = W_, OUT = OUT_;
+    static constexpr bool TAIL = TAIL_;
+};
+
+template <class CA, class CB>
+__global__ __launch_bounds__(256) void k_gemm_pair(GemmDev ga, GemmDev gb, int nA, int nA_pad)
+{
+    const int b = static_cast<int>(blockIdx.x);
+    if (b < nA_pad) {
+        if (b < nA) gemm_tile<CA::KIND, CA::W, CA::W, 8, CA::TAIL, CA::OUT>(ga, b);
+    } else {
+        gemm_tile<CB::KIND, CB::W, CB::W, 8, CB::TAIL, CB::OUT>(gb, b - nA_pad);
+    }
+}
+
+// Plan of the pair: tile size of either product and the k split of the g_w product, by a model of
+// how the launch unfolds (microseconds; constants fitted to a sweep of every plan over eleven layer
+// shapes on MI355X).  A tile of nk steps (128 B of k) takes nk * step + fixed.  A 256-tile owns a
+// compute unit.  128-tiles share one in twos only if both products use them (the launch has one LDS
+// size, the larger) and there are more of them than compute units; they step faster alone.
+// Workgroups are dispatched in index order, g_x product first, each to the first free slot: after
+// the g_x tiles' full rounds, the slots of its last, partial round free up one tile later than the
+// rest, and the g_w tiles -- all equal -- finish at the first instant by which enough of them fit.
+struct PairPlan {
+    bool bigA, bigB;
+    int splitsB;
+};
+
+namespace {
+constexpr double kStepBig = 1.3, kPackedScale = 1.8, kStepSmallAlone = 0.6, kStepSmallShared = 1.1;
+constexpr double kFixedBig = 12.0, kFixedSmall = 6.5;
+constexpr int kSplitChoices[] = {1, 2, 3, 4, 6, 8, 12, 16};
+
+struct TileClass {
+    double step, fixed;
+    int slots;   // tiles in flight on the chip
+};
+TileClass tile_class(bool big, bool mixed, double n)
+{
+    if (big) return {kStepBig, kFixedBig, 256};
+    if (mixed || n <= 256.0) return {kStepSmallAlone, kFixedSmall, 256};
+    return {kStepSmallShared, kFixedSmall, 512};
+}
+
+// nA tiles of tA on mA slots, then nB tiles of tB on mB slots (the same silicon, possibly cut finer)
+double pair_makespan(double nA, double tA, int mA, double nB, double tB, int mB)
+{
+    const double qA = __builtin_floor(nA / mA), rA = nA - qA * mA;
+    const double T1 = qA * tA, T2 = rA > 0 ? T1 + tA : T1;
+    const double g2 = __builtin_round(rA / mA * mB), g1 = mB - g2;      // slots free at T2 / at T1
+    // candidate finishing times: T1 + k tB and T2 + k tB; the first with enough capacity
+    double best = 1e30;
+    for (int grp = 0; grp < 2; ++grp) {
+        const double base = grp ? T2 : T1;
+        const double gs = grp ? g2 : g1;
+        if (gs <= 0) continue;
+        // smallest k with g1 floor((T - T1)/tB) + g2 floor((T - T2)/tB) >= nB at T = base + k tB
+        double lo = grp ? 0 : 1, hi = __builtin_ceil(nB / gs) + 1;
+        while (lo < hi) {
+            const double k = __builtin_floor((lo + hi) / 2), T = base + k * tB;
+            const double c1 = g1 * __builtin_fmax(0.0, __builtin_floor((T - T1) / tB + 1e-9));
+            const double c2 = g2 * __builtin_fmax(0.0, __builtin_floor((T - T2) / tB + 1e-9));
+            if (c1 + c2 >= nB) hi = k; else lo = k + 1;
+        }
+        const double T = base + lo * tB;
+        if (T < best) best = T;
+    }
+    return best > T2 ? best : T2;
+}
+}  // namespace
+
+static PairPlan plan_pair(const GemmArgs &a, int kindA, const GemmArgs &b, int kindB, size_t ws_bytes)
+{
+    const int nkA = (row_bytes(kindA, a.K) + 127) / 128, nkB = (row_bytes(kindB, b.K) + 127) / 128;
+    const double scaleA = kindA == 2 ? kPackedScale : 1.0, scaleB = kindB == 2 ? kPackedScale : 1.0;
+    const double mnB = static_cast<double>(b.M) * b.N;
+    PairPlan best{true, true, 1};
+    double best_t = 1e30;
+    for (int bigA = 1; bigA >= 0; --bigA) {
+        for (int bigB = 1; bigB >= 0; --bigB) {
+            const bool mixed = bigA != bigB;
+            const int ta = bigA ? 256 : 128, tb = bigB ? 256 : 128;
+            const double nA = static_cast<double>((a.M + ta - 1) / ta) * ((a.N + ta - 1) / ta);
+            const double nB1 = static_cast<double>((b.M + tb - 1) / tb) * ((b.N + tb - 1) / tb);
+            const TileClass ca = tile_class(bigA != 0, mixed, nA);
+            const double tA = nkA * scaleA * ca.step + ca.fixed;
+            for (int S : kSplitChoices) {
+                if (S > 1 && (S > nkB || S * mnB * 4.0 > static_cast<double>(ws_bytes))) break;
+                const TileClass cb = tile_class(bigB != 0, mixed, nB1 * S);
+                const double tB = __builtin_ceil(static_cast<double>(nkB) / S) * scaleB * cb.step + cb.fixed;
+                double t = pair_makespan(nA, tA, ca.slots, nB1 * S, tB, cb.slots);
+                if (S > 1) t += 2.0 * S * mnB * 4.0 / 8.0e6 + 3.0;     // partials out and back, one more launch
+                if (t < best_t) {
+                    best_t = t;
+                    best = PairPlan{bigA != 0, bigB != 0, S};
+                }
+            }
+        }
+    }
+    return best;
+}
+
+// split-k scratch the pair's plan asks for when it may have up to `cap` bytes
+size_t gemm_pair_ws_bytes(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, size_t cap)
+{
+    const PairPlan p = plan_pair(a, kindA, b, kindB, cap);
+    return p.splitsB > 1 ? static_cast<size_t>(p.splitsB) * b.M * b.N * 4 : 0;
+}
+
+template <class CA, class CB>
+static hipError_t launch_pair_tt(const GemmDev &ga, const GemmDev &gb, hipStream_t st)
+{
+    constexpr size_t la = gemm_lds_bytes(CA::W, CA::W, 8), lb = gemm_lds_bytes(CB::W, CB::W, 8);
+    constexpr size_t lds_bytes = la > lb ? la : lb;
+    static bool attr_set = false;     // idempotent; racing callers set the same value
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_pair<CA, CB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int nA = ga.tiles_m * ga.tiles_n * ga.splits, nB = gb.tiles_m * gb.tiles_n * gb.splits;
+    const int nA_pad = (nA + 7) & ~7;
+    hipLaunchKernelGGL((k_gemm_pair<CA, CB>), dim3(nA_pad + nB), dim3(256), lds_bytes, st, ga, gb, nA, nA_pad);
+    return hipGetLastError();
+}
+
+// the g_w product writes the dtype the g_x product writes (CA::OUT), or its split-k partials
+template <class CA, int WB, bool TAILB>
+static hipError_t launch_pair_b(const GemmDev &ga, const GemmDev &gb, int outB, hipStream_t st)
+{
+    if (outB == 3) return launch_pair_tt<CA, TileCfg<1, WB, TAILB, 3>>(ga, gb, st);
+    return launch_pair_tt<CA, TileCfg<1, WB, TAILB, CA::OUT>>(ga, gb, st);
+}
+
+template <class CA>
+static hipError_t launch_pair_a(const GemmDev &ga, const GemmDev &gb, bool bigB, bool tailB, int outB, hipStream_t st)
+{
+    if (bigB) return tailB ? launch_pair_b<CA, 4, true>(ga, gb, outB, st) : launch_pair_b<CA, 4, false>(ga, gb, outB, st);
+    return tailB ? launch_pair_b<CA, 2, true>(ga, gb, outB, st) : launch_pair_b<CA, 2, false>(ga, gb, outB, st);
+}
+
+template <int WA, bool TAILA>
+static hipError_t launch_pair_o(const GemmDev &ga, const GemmDev &gb, bool f32, bool bigB, bool tailB, int outB,
+                                hipStream_t st)
+{
+    return f32 ? launch_pair_a<TileCfg<2, WA, TAILA, 1>>(ga, gb, bigB, tailB, outB, st)
+               : launch_pair_a<TileCfg<2, WA, TAILA, 0>>(ga, gb, bigB, tailB, outB, st);
+}
+
+bool gemm_pair_available(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b)
+{
+    return kindA == 2 && kindB == 1 && a.C && b.C && !a.acc && !b.acc && a.c_is_f32 == b.c_is_f32;
+}
+
+hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, hipStream_t st)
+{
+    if (!gemm_pair_available(kindA, a, kindB, b)) return hipErrorInvalidValue;
+    const bool can_split = b.ws != nullptr && (reinterpret_cast<uintptr_t>(b.ws) & 15) == 0;
+    const PairPlan p = plan_pair(a, kindA, b, kindB, can_split ? b.ws_bytes : 0);
+    const GemmDev ga = gemm_dev(kindA, a, p.bigA ? 256 : 128, p.bigA ? 256 : 128, 1);
+    const GemmDev gb = gemm_dev(kindB, b, p.bigB ? 256 : 128, p.bigB ? 256 : 128, p.splitsB);
+    const bool tailA = ga.Kb % 128 != 0, tailB = gb.Kb % 128 != 0;
+    const int outB = p.splitsB > 1 ? 3 : (b.c_is_f32 ? 1 : 0);
+    hipError_t e;
+    if (p.bigA)
+        e = tailA ? launch_pair_o<4, true>(ga, gb, a.c_is_f32, p.bigB, tailB, outB, st)
+                  : launch_pair_o<4, false>(ga, gb, a.c_is_f32, p.bigB, tailB, outB, st);
+    else
+        e = tailA ? launch_pair_o<2, true>(ga, gb, a.c_is_f32, p.bigB, tailB, outB, st)
+                  : launch_pair_o<2, false>(ga, gb, a.c_is_f32, p.bigB, tailB, outB, st);
+    if (e != hipSuccess || p.splitsB == 1) return e;
+    return launch_splitk_reduce(1, b, p.splitsB, st);
+}
+
+}  // namespace hlq

@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2406_15102_amd as hlq
 from paper_2406_15102_amd import workloads as wl
-from test_gpu_parity import TOL_OUT, dev, rand_tensor, row_rel_err
+from test_gpu_parity import same_up_to_split_order, TOL_OUT, dev, rand_tensor, row_rel_err
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -86,7 +86,10 @@ def test_backward_sequency_matches_oracle(w, extra):
     if not extra:
         XhT = torch.empty((I, N // B * r), dtype=torch.bfloat16, device=DEV)
         hlq.hlq_hla_project_basis(X, B, r, SEQ, XhT)
-        dW2 = torch.empty_like(dW)
+        dX2, dW2 = torch.empty_like(dX), torch.empty_like(dW)
+        hlq.hlq_linear_backward_mode(G, None, XhT, None, W, N, I, O, B, r, w.seed, flags, dX2, dW2, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(dW, dW2) and torch.equal(dX, dX2)
         hlq.hlq_linear_backward_mode(G, None, XhT, None, W, N, I, O, B, r, w.seed, flags, None, dW2, ws)
         torch.cuda.synchronize()
-        assert torch.equal(dW, dW2)
+        assert same_up_to_split_order(dW2, dW)     # dW alone may split its reduction differently

@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2406_15102_amd as hlq
 from paper_2406_15102_amd import workloads as wl
-from test_gpu_parity import TOL_OUT, row_rel_err
+from test_gpu_parity import TOL_OUT, row_rel_err, same_up_to_split_order
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -105,13 +105,13 @@ def test_convolution_backward_matches_oracle(g, flags):
     ex = row_rel_err(wl.as_f32_numpy(dX).reshape(-1, cols_x), ref["dX_img"].reshape(-1, cols_x), bf)
     ew = row_rel_err(wl.as_f32_numpy(dW).reshape(O, I), ref["dW_k"].reshape(O, I), bf)
     assert ex < TOL_OUT and ew < TOL_OUT, (ex, ew)
-    # each output alone: the same bits, and the library-owned workspace
+    # each output alone: the same dX bits, dW up to the order of its k splits; the library-owned workspace
     dX1 = torch.full_like(X, 3.0)
     dW1 = torch.full_like(Wt, 3.0)
     hlq.hlq_conv2d_backward(G, X, Wt, geom, B, r, seed, flags, dX1, None, ws)
     hlq.hlq_conv2d_backward(G, X, Wt, geom, B, r, seed, flags, None, dW1)
     torch.cuda.synchronize()
-    assert torch.equal(dX1, dX) and torch.equal(dW1, dW)
+    assert torch.equal(dX1, dX) and same_up_to_split_order(dW1, dW)
 
 
 def test_pointwise_convolution_is_the_linear_layer():

@@ -1,0 +1,66 @@
+"""The two matrix products in one launch against one launch each: dX must not change by a bit (same
+tiles, same reduction order), dW only by the order in which its k splits are summed; both against
+the oracle.  Shapes visit both tile sizes of either product, ragged k steps and split reductions."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2406_15102_amd as hlq
+from paper_2406_15102_amd import workloads as wl
+from test_gpu_parity import TOL_OUT, row_rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+CASES = [
+    # N, d_in, d_out, B, r, dtype
+    (1024, 264, 512, 16, 8, "bf16"),
+    (4096, 768, 3072, 16, 8, "bf16"),      # both products under-fill the chip alone
+    (12544, 576, 64, 16, 8, "bf16"),       # ragged k step of the g_x product, long split reduction of g_w
+    (2048, 1152, 128, 16, 8, "bf16"),
+    (512, 96, 224, 32, 16, "bf16"),        # d_out % 32 == 0 but ragged everywhere
+    (256, 256, 256, 16, 8, "f32"),
+    (1536, 200, 320, 64, 16, "f32"),
+    (8192, 2048, 1024, 32, 4, "bf16"),
+]
+
+
+@pytest.mark.parametrize("N,d_in,d_out,B,r,dtype", CASES)
+def test_paired_products_equal_separate_ones(N, d_in, d_out, B, r, dtype):
+    w = wl.scaled(wl.WORKLOADS["c2"], N=N, d_in=d_in, d_out=d_out, B=B, r=r, dtype=dtype)
+    t = wl.generate(w)
+    G, X, W = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
+    ws = torch.empty(hlq.hlq_workspace_bytes_mode(N, d_in, d_out, B, r, False, 0), dtype=torch.uint8, device=DEV)
+    out = {}
+    for flags in (0, hlq.HLQ_FLAG_SEPARATE_PRODUCTS):
+        dX = torch.full((N, d_in), 7.0, dtype=G.dtype, device=DEV)
+        dW = torch.full((d_out, d_in), 7.0, dtype=G.dtype, device=DEV)
+        print("pair case", N, d_in, d_out, B, r, dtype, "flags", flags, flush=True)
+        hlq.hlq_linear_backward_mode(G, X, None, None, W, N, d_in, d_out, B, r, 3, flags, dX, dW, ws)
+        torch.cuda.synchronize()
+        out[flags] = (dX, dW)
+    assert torch.equal(out[0][0], out[hlq.HLQ_FLAG_SEPARATE_PRODUCTS][0])
+    a, b = out[0][1].float(), out[hlq.HLQ_FLAG_SEPARATE_PRODUCTS][1].float()
+    scale = float(b.abs().max())
+    assert float((a - b).abs().max()) <= (2.0 ** -7 if dtype == "bf16" else 1e-5) * scale
+    ref = oracle.linear_backward_mode(wl.as_f32_numpy(t["G"]), wl.as_f32_numpy(t["X"]), wl.as_f32_numpy(t["W"]), B, r, 3)
+    bf = dtype == "bf16"
+    for dX, dW in out.values():
+        assert row_rel_err(dX.float().cpu().numpy(), ref["dX"], bf) < TOL_OUT
+        assert row_rel_err(dW.float().cpu().numpy(), ref["dW"], bf) < TOL_OUT
+
+
+def test_one_output_alone_takes_the_single_launches():
+    N, d_in, d_out, B, r = 1024, 264, 512, 16, 8
+    w = wl.scaled(wl.WORKLOADS["c2"], N=N, d_in=d_in, d_out=d_out, B=B, r=r)
+    t = wl.generate(w)
+    G, X, W = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
+    dX, dW = (torch.empty((N, d_in), dtype=G.dtype, device=DEV), torch.empty((d_out, d_in), dtype=G.dtype, device=DEV))
+    hlq.hlq_linear_backward_mode(G, X, None, None, W, N, d_in, d_out, B, r, 3, 0, dX, dW)
+    dX1, dW1 = torch.empty_like(dX), torch.empty_like(dW)
+    hlq.hlq_linear_backward_mode(G, X, None, None, W, N, d_in, d_out, B, r, 3, 0, dX1, None)
+    hlq.hlq_linear_backward_mode(G, X, None, None, W, N, d_in, d_out, B, r, 3, 0, None, dW1)
+    torch.cuda.synchronize()
+    assert torch.equal(dX, dX1)
+    assert float((dW.float() - dW1.float()).abs().max()) <= 2.0 ** -7 * float(dW1.float().abs().max())

@@ -18,6 +18,15 @@ DEV = "cuda:0"
 TOL_OUT = 2e-2
 
 
+def same_up_to_split_order(a, b):
+    """dW of one configuration against dW of another whose product split its reduction differently
+    (the two products in one launch, or one launch each): the partial sums are the same fp32
+    numbers added in another order, so the results agree to a few fp32 roundings of the largest
+    term -- far inside one bf16 step of the largest entry."""
+    a, b = a.float(), b.float()
+    return float((a - b).abs().max()) <= 2.0 ** -7 * float(b.abs().max())
+
+
 def row_rel_err(got, ref, bf16_out=False):
     """max over rows n of |delta[n,:]|_inf / (|ref[n,:]|_2 / sqrt(cols)).
 
