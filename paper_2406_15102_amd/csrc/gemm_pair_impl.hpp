@@ -1,0 +1,90 @@
+// K2 | K4 in one launch.  The two products of a backward pass (arXiv 2406.15102, Sec. 6.1: stage 5
+// of the g_x list and stage 5 of the g_w list) do not depend on each other, and for all but the
+// largest layers neither fills the chip by itself: 150 tiles of 256 x 256 at the ViT MLP, a
+// handful at a ResNet layer, against 256 compute units.  Launched together, the tiles of one fill
+// the compute units the other leaves idle, the tail of one overlaps the start of the other, and
+// one launch latency goes away.  A workgroup runs the tile body of gemm_body.hpp of whichever
+// product its index falls in (first the g_x product's tiles, padded to a multiple of 8 so that the
+// second product's tiles keep their XCD assignment, then the g_w product's).  The tile sizes and
+// the k split of the g_w product are planned for the pair, not for each product alone.
+//
+// One translation unit per pair of operand kinds (k_gemm_pair_*.hip instantiate launch_pair_kinds
+// below: 64 kernels each -- two tile sizes and whole or ragged k steps per product, bf16 or fp32
+// output, direct output or split-k partials for the g_w product); k_gemm_pair.hip plans and dispatches.
+#pragma once
+#include "gemm_body.hpp"
+#include "gemm_plan.hpp"
+
+namespace hlq {
+
+template <int KIND_, int W_, bool TAIL_, int OUT_> struct TileCfg {
+    static constexpr int KIND = KIND_, W = W_, OUT = OUT_;
+    static constexpr bool TAIL = TAIL_;
+};
+
+template <class CA, class CB>
+__global__ __launch_bounds__(256) void k_gemm_pair(GemmDev ga, GemmDev gb, int nA, int nA_pad)
+{
+    const int b = static_cast<int>(blockIdx.x);
+    if (b < nA_pad) {
+        if (b < nA) gemm_tile<CA::KIND, CA::W, CA::W, 8, CA::TAIL, CA::OUT>(ga, b);
+    } else {
+        gemm_tile<CB::KIND, CB::W, CB::W, 8, CB::TAIL, CB::OUT>(gb, b - nA_pad);
+    }
+}
+
+template <class CA, class CB>
+static hipError_t launch_pair_tt(const GemmDev &ga, const GemmDev &gb, hipStream_t st)
+{
+    constexpr size_t la = gemm_lds_bytes(CA::W, CA::W, 8), lb = gemm_lds_bytes(CB::W, CB::W, 8);
+    constexpr size_t lds_bytes = la > lb ? la : lb;
+    static bool attr_set = false;     // idempotent; racing callers set the same value
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_pair<CA, CB>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    const int nA = ga.tiles_m * ga.tiles_n * ga.splits, nB = gb.tiles_m * gb.tiles_n * gb.splits;
+    const int nA_pad = (nA + 7) & ~7;
+    hipLaunchKernelGGL((k_gemm_pair<CA, CB>), dim3(nA_pad + nB), dim3(256), lds_bytes, st, ga, gb, nA, nA_pad);
+    return hipGetLastError();
+}
+
+// the g_w product writes the dtype the g_x product writes (CA::OUT), or its split-k partials
+template <class CA, int KB, int WB, bool TAILB>
+static hipError_t launch_pair_b(const GemmDev &ga, const GemmDev &gb, int outB, hipStream_t st)
+{
+    if (outB == 3) return launch_pair_tt<CA, TileCfg<KB, WB, TAILB, 3>>(ga, gb, st);
+    return launch_pair_tt<CA, TileCfg<KB, WB, TAILB, CA::OUT>>(ga, gb, st);
+}
+
+template <class CA, int KB>
+static hipError_t launch_pair_a(const GemmDev &ga, const GemmDev &gb, bool bigB, bool tailB, int outB, hipStream_t st)
+{
+    if (bigB) return tailB ? launch_pair_b<CA, KB, 4, true>(ga, gb, outB, st) : launch_pair_b<CA, KB, 4, false>(ga, gb, outB, st);
+    return tailB ? launch_pair_b<CA, KB, 2, true>(ga, gb, outB, st) : launch_pair_b<CA, KB, 2, false>(ga, gb, outB, st);
+}
+
+template <int KA, int KB, int WA, bool TAILA>
+static hipError_t launch_pair_o(const GemmDev &ga, const GemmDev &gb, bool f32, bool bigB, bool tailB, int outB,
+                                hipStream_t st)
+{
+    return f32 ? launch_pair_a<TileCfg<KA, WA, TAILA, 1>, KB>(ga, gb, bigB, tailB, outB, st)
+               : launch_pair_a<TileCfg<KA, WA, TAILA, 0>, KB>(ga, gb, bigB, tailB, outB, st);
+}
+
+// every kernel of one pair of kinds; the plan comes from the caller
+template <int KA, int KB>
+static hipError_t launch_pair_kinds(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB,
+                                    hipStream_t st)
+{
+    const bool tailA = ga.Kb % 128 != 0, tailB = gb.Kb % 128 != 0;
+    if (bigA)
+        return tailA ? launch_pair_o<KA, KB, 4, true>(ga, gb, f32, bigB, tailB, outB, st)
+                     : launch_pair_o<KA, KB, 4, false>(ga, gb, f32, bigB, tailB, outB, st);
+    return tailA ? launch_pair_o<KA, KB, 2, true>(ga, gb, f32, bigB, tailB, outB, st)
+                 : launch_pair_o<KA, KB, 2, false>(ga, gb, f32, bigB, tailB, outB, st);
+}
+
+}  // namespace hlq

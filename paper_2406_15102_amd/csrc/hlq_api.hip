@@ -102,12 +102,13 @@ Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_
     const size_t g1 = hlq::gemm_ws_bytes(0, static_cast<int>(N), static_cast<int>(d_in), static_cast<int>(d_out));
     const size_t g2 = hlq::gemm_ws_bytes(gwi ? 0 : 1, static_cast<int>(d_out), static_cast<int>(d_in), static_cast<int>(Kc));
     L.gws_bytes = g1 > g2 ? g1 : g2;
-    if (!gwi && !(flags & (HLQ_FLAG_GX_8BIT | HLQ_FLAG_GX_UNPACKED | HLQ_FLAG_SEPARATE_PRODUCTS)) && d_out % 32 == 0) {
+    if (!(flags & HLQ_FLAG_SEPARATE_PRODUCTS)) {
         // the two products in one launch plan the g_w product's k split for the pair
+        const bool packed = !(flags & (HLQ_FLAG_GX_8BIT | HLQ_FLAG_GX_UNPACKED)) && d_out % 32 == 0;
         hlq::GemmArgs ax{}, aw{};
         ax.M = static_cast<int>(N), ax.N = static_cast<int>(d_in), ax.K = static_cast<int>(d_out);
         aw.M = static_cast<int>(d_out), aw.N = static_cast<int>(d_in), aw.K = static_cast<int>(Kc);
-        const size_t gp = hlq::gemm_pair_ws_bytes(2, ax, 1, aw, size_t(256) << 20);
+        const size_t gp = hlq::gemm_pair_ws_bytes(packed ? 2 : 0, ax, gwi ? 0 : 1, aw, size_t(256) << 20);
         if (gp > L.gws_bytes) L.gws_bytes = gp;
     }
     L.gws = off;   off += up256(L.gws_bytes);

@@ -1,36 +1,15 @@
-// K2 | K4 in one launch.  The two products of a backward pass (arXiv 2406.15102, Sec. 6.1: stage 5
-// of the g_x list and stage 5 of the g_w list) do not depend on each other, and for all but the
-// largest layers neither fills the chip by itself: 150 tiles of 256 x 256 at the ViT MLP, a
-// handful at a ResNet layer, against 256 compute units.  Launched together, the tiles of one fill
-// the compute units the other leaves idle, the tail of one overlaps the start of the other, and
-// one launch latency goes away.  A workgroup runs the tile body of gemm_body.hpp of whichever
-// product its index falls in (first the g_x product's tiles, padded to a multiple of 8 so that the
-// second product's tiles keep their XCD assignment, then the g_w product's).  The tile sizes and
-// the k split of the g_w product are planned for the pair, not for each product alone.
-//
-// Instantiated for the default lists: packed 4-bit codes (kind 2) with bf16 or fp32 output for
-// g_x; bf16 operands (kind 1) with direct output or split-k partials for g_w.  Other combinations
-// keep one launch per product.
-#include "gemm_body.hpp"
+// K2 | K4 in one launch: the plan and the dispatch over the operand kinds.  The kernels live in
+// gemm_pair_impl.hpp, instantiated by k_gemm_pair_KK.hip for KK = (kind of the g_x product, kind of
+// the g_w product): 21 the default lists (packed 4-bit codes, bf16 projections), 20 with the integer
+// g_w list, 01 / 00 the same with one int8 per g_x code (8-bit warm-up, unpacked storage).
 #include "gemm_plan.hpp"
 
 namespace hlq {
 
-template <int KIND_, int W_, bool TAIL_, int OUT_> struct TileCfg {
-    static constexpr int KIND = KIND_, W = W_, OUT = OUT_;
-    static constexpr bool TAIL = TAIL_;
-};
-
-template <class CA, class CB>
-__global__ __launch_bounds__(256) void k_gemm_pair(GemmDev ga, GemmDev gb, int nA, int nA_pad)
-{
-    const int b = static_cast<int>(blockIdx.x);
-    if (b < nA_pad) {
-        if (b < nA) gemm_tile<CA::KIND, CA::W, CA::W, 8, CA::TAIL, CA::OUT>(ga, b);
-    } else {
-        gemm_tile<CB::KIND, CB::W, CB::W, 8, CB::TAIL, CB::OUT>(gb, b - nA_pad);
-    }
-}
+hipError_t launch_pair_21(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, hipStream_t st);
+hipError_t launch_pair_20(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, hipStream_t st);
+hipError_t launch_pair_01(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, hipStream_t st);
+hipError_t launch_pair_00(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, hipStream_t st);
 
 // Plan of the pair: tile size of either product and the k split of the g_w product, by a model of
 // how the launch unfolds (microseconds; constants fitted to a sweep of every plan over eleven layer
@@ -126,50 +105,10 @@ size_t gemm_pair_ws_bytes(int kindA, const GemmArgs &a, int kindB, const GemmArg
     return p.splitsB > 1 ? static_cast<size_t>(p.splitsB) * b.M * b.N * 4 : 0;
 }
 
-template <class CA, class CB>
-static hipError_t launch_pair_tt(const GemmDev &ga, const GemmDev &gb, hipStream_t st)
-{
-    constexpr size_t la = gemm_lds_bytes(CA::W, CA::W, 8), lb = gemm_lds_bytes(CB::W, CB::W, 8);
-    constexpr size_t lds_bytes = la > lb ? la : lb;
-    static bool attr_set = false;     // idempotent; racing callers set the same value
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_pair<CA, CB>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds_bytes));
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    const int nA = ga.tiles_m * ga.tiles_n * ga.splits, nB = gb.tiles_m * gb.tiles_n * gb.splits;
-    const int nA_pad = (nA + 7) & ~7;
-    hipLaunchKernelGGL((k_gemm_pair<CA, CB>), dim3(nA_pad + nB), dim3(256), lds_bytes, st, ga, gb, nA, nA_pad);
-    return hipGetLastError();
-}
-
-// the g_w product writes the dtype the g_x product writes (CA::OUT), or its split-k partials
-template <class CA, int WB, bool TAILB>
-static hipError_t launch_pair_b(const GemmDev &ga, const GemmDev &gb, int outB, hipStream_t st)
-{
-    if (outB == 3) return launch_pair_tt<CA, TileCfg<1, WB, TAILB, 3>>(ga, gb, st);
-    return launch_pair_tt<CA, TileCfg<1, WB, TAILB, CA::OUT>>(ga, gb, st);
-}
-
-template <class CA>
-static hipError_t launch_pair_a(const GemmDev &ga, const GemmDev &gb, bool bigB, bool tailB, int outB, hipStream_t st)
-{
-    if (bigB) return tailB ? launch_pair_b<CA, 4, true>(ga, gb, outB, st) : launch_pair_b<CA, 4, false>(ga, gb, outB, st);
-    return tailB ? launch_pair_b<CA, 2, true>(ga, gb, outB, st) : launch_pair_b<CA, 2, false>(ga, gb, outB, st);
-}
-
-template <int WA, bool TAILA>
-static hipError_t launch_pair_o(const GemmDev &ga, const GemmDev &gb, bool f32, bool bigB, bool tailB, int outB,
-                                hipStream_t st)
-{
-    return f32 ? launch_pair_a<TileCfg<2, WA, TAILA, 1>>(ga, gb, bigB, tailB, outB, st)
-               : launch_pair_a<TileCfg<2, WA, TAILA, 0>>(ga, gb, bigB, tailB, outB, st);
-}
-
 bool gemm_pair_available(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b)
 {
-    return kindA == 2 && kindB == 1 && a.C && b.C && !a.acc && !b.acc && a.c_is_f32 == b.c_is_f32;
+    return (kindA == 2 || kindA == 0) && (kindB == 1 || kindB == 0) && a.C && b.C && !a.acc && !b.acc &&
+           a.c_is_f32 == b.c_is_f32;
 }
 
 hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, hipStream_t st)
@@ -179,17 +118,16 @@ hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmA
     const PairPlan p = plan_pair(a, kindA, b, kindB, can_split ? b.ws_bytes : 0);
     const GemmDev ga = gemm_dev(kindA, a, p.bigA ? 256 : 128, p.bigA ? 256 : 128, 1);
     const GemmDev gb = gemm_dev(kindB, b, p.bigB ? 256 : 128, p.bigB ? 256 : 128, p.splitsB);
-    const bool tailA = ga.Kb % 128 != 0, tailB = gb.Kb % 128 != 0;
     const int outB = p.splitsB > 1 ? 3 : (b.c_is_f32 ? 1 : 0);
     hipError_t e;
-    if (p.bigA)
-        e = tailA ? launch_pair_o<4, true>(ga, gb, a.c_is_f32, p.bigB, tailB, outB, st)
-                  : launch_pair_o<4, false>(ga, gb, a.c_is_f32, p.bigB, tailB, outB, st);
+    if (kindA == 2)
+        e = kindB == 1 ? launch_pair_21(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, st)
+                       : launch_pair_20(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, st);
     else
-        e = tailA ? launch_pair_o<2, true>(ga, gb, a.c_is_f32, p.bigB, tailB, outB, st)
-                  : launch_pair_o<2, false>(ga, gb, a.c_is_f32, p.bigB, tailB, outB, st);
+        e = kindB == 1 ? launch_pair_01(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, st)
+                       : launch_pair_00(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, st);
     if (e != hipSuccess || p.splitsB == 1) return e;
-    return launch_splitk_reduce(1, b, p.splitsB, st);
+    return launch_splitk_reduce(kindB == 1 ? 1 : 0, b, p.splitsB, st);
 }
 
 }  // namespace hlq

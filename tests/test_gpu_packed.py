@@ -132,9 +132,10 @@ def test_backward_packed_equals_unpacked(w):
         out.append((dX, dW))
     # dX: the same bits however the codes are stored and however the products are launched
     assert all(torch.equal(out[0][0], o[0]) for o in out[1:])
-    # dW does not depend on the code storage; with one launch per product it is the same launch
-    assert torch.equal(out[2][1], out[3][1]) and torch.equal(out[1][1], out[2][1])
-    assert same_up_to_split_order(out[0][1], out[2][1])
+    # dW does not depend on the code storage: with one launch per product it is the same launch; sharing
+    # a launch with a differently stored g_x product may only change how its reduction is split
+    assert torch.equal(out[2][1], out[3][1])
+    assert same_up_to_split_order(out[0][1], out[2][1]) and same_up_to_split_order(out[1][1], out[2][1])
 
 
 @pytest.mark.parametrize("flags", [0, hlq.HLQ_FLAG_GX_UNPACKED, hlq.HLQ_FLAG_GX_8BIT, hlq.HLQ_FLAG_GW_INT8])

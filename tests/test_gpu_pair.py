@@ -26,25 +26,37 @@ CASES = [
 ]
 
 
+MODES = [0, hlq.HLQ_FLAG_GW_INT8, hlq.HLQ_FLAG_GX_8BIT, hlq.HLQ_FLAG_GX_UNPACKED | hlq.HLQ_FLAG_GW_INT8]
+
+
+@pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("N,d_in,d_out,B,r,dtype", CASES)
-def test_paired_products_equal_separate_ones(N, d_in, d_out, B, r, dtype):
+def test_paired_products_equal_separate_ones(N, d_in, d_out, B, r, dtype, mode):
     w = wl.scaled(wl.WORKLOADS["c2"], N=N, d_in=d_in, d_out=d_out, B=B, r=r, dtype=dtype)
     t = wl.generate(w)
     G, X, W = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
-    ws = torch.empty(hlq.hlq_workspace_bytes_mode(N, d_in, d_out, B, r, False, 0), dtype=torch.uint8, device=DEV)
+    if mode & hlq.HLQ_FLAG_GW_INT8 and (N // B * r) % 16:
+        pytest.skip("the integer g_w list needs whole 16-byte rows of codes")
+    ws = torch.empty(hlq.hlq_workspace_bytes_mode(N, d_in, d_out, B, r, False, mode), dtype=torch.uint8, device=DEV)
+    SEP = mode | hlq.HLQ_FLAG_SEPARATE_PRODUCTS
     out = {}
-    for flags in (0, hlq.HLQ_FLAG_SEPARATE_PRODUCTS):
+    for flags in (mode, SEP):
         dX = torch.full((N, d_in), 7.0, dtype=G.dtype, device=DEV)
         dW = torch.full((d_out, d_in), 7.0, dtype=G.dtype, device=DEV)
         print("pair case", N, d_in, d_out, B, r, dtype, "flags", flags, flush=True)
         hlq.hlq_linear_backward_mode(G, X, None, None, W, N, d_in, d_out, B, r, 3, flags, dX, dW, ws)
         torch.cuda.synchronize()
         out[flags] = (dX, dW)
-    assert torch.equal(out[0][0], out[hlq.HLQ_FLAG_SEPARATE_PRODUCTS][0])
-    a, b = out[0][1].float(), out[hlq.HLQ_FLAG_SEPARATE_PRODUCTS][1].float()
-    scale = float(b.abs().max())
-    assert float((a - b).abs().max()) <= (2.0 ** -7 if dtype == "bf16" else 1e-5) * scale
-    ref = oracle.linear_backward_mode(wl.as_f32_numpy(t["G"]), wl.as_f32_numpy(t["X"]), wl.as_f32_numpy(t["W"]), B, r, 3)
+    assert torch.equal(out[mode][0], out[SEP][0])
+    if mode & hlq.HLQ_FLAG_GW_INT8:
+        assert torch.equal(out[mode][1], out[SEP][1])      # integer partial sums: exact in any order
+    else:
+        a, b = out[mode][1].float(), out[SEP][1].float()
+        scale = float(b.abs().max())
+        assert float((a - b).abs().max()) <= (2.0 ** -7 if dtype == "bf16" else 1e-5) * scale
+    ref = oracle.linear_backward_mode(wl.as_f32_numpy(t["G"]), wl.as_f32_numpy(t["X"]), wl.as_f32_numpy(t["W"]), B, r, 3,
+                                      gx_bits=8 if mode & hlq.HLQ_FLAG_GX_8BIT else 4,
+                                      gw_int8=bool(mode & hlq.HLQ_FLAG_GW_INT8))
     bf = dtype == "bf16"
     for dX, dW in out.values():
         assert row_rel_err(dX.float().cpu().numpy(), ref["dX"], bf) < TOL_OUT
