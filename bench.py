@@ -134,6 +134,7 @@ def main():
     gws = torch.empty(max(16, hlq.hlq_gemm_workspace_bytes(2 if packed else 0, N, I, O),
                           hlq.hlq_gemm_workspace_bytes(1, O, I, Kc)),
                       dtype=torch.uint8, device=dev)   # split-K scratch, as the whole path has it
+    pws = torch.empty(max(16, hlq.hlq_backward_products_workspace_bytes(N, I, O, Kc, qbits)), dtype=torch.uint8, device=dev)
     stages = {   # in the launch order of the whole path
         "quantize_g": lambda: hlq.hlq_quantize_g(G, B, w.seed, Gq, sG, None, qbits),
         "hla_g": lambda: hlq.hlq_hla_project(G, B, r, GhT),
@@ -142,6 +143,8 @@ def main():
         "int8_gemm": lambda: (hlq.hlq_int4_gemm_nt if packed else hlq.hlq_int8_gemm_nt)(
             Gq, WqT, sG, sW, 1.0 / B, dX, None, gws),
         "bf16_gemm": lambda: hlq.hlq_bf16_gemm_nt(GhT, XhT, 1.0 / B, dW, gws),
+        # what the whole path launches instead of the two above: both products in one launch
+        "products": lambda: hlq.hlq_backward_products(Gq, sG, WqT, sW, qbits, GhT, None, XhT, None, B, dX, dW, pws),
     }
     e = 2 if w.dtype == "bf16" else 4
     cbytes = 0.5 if packed else 1.0          # bytes per stored code
@@ -152,6 +155,9 @@ def main():
         "hla_g": ("hbm", N * O * e + 2 * Kc * O),
         "hla_x": ("hbm", N * I * e + 2 * Kc * I),
         "bf16_gemm": ("mfma_bf16", 2.0 * O * I * Kc),
+        # two dtypes in one launch: the work is counted in int8-equivalent operations, a bf16 flop as two
+        # (the ratio of the two MFMA peaks), so that frac = time at the two peaks / time taken
+        "products": ("mfma_mixed", 2.0 * N * I * O + 2.0 * (2.0 * O * I * Kc)),
     }
     # Two timings per kernel: "us" = inside the whole sequence (events between the stage calls, the
     # order and the thermal / cache state of the real path), "us_alone" = the same launch back to back.
@@ -177,7 +183,7 @@ def main():
         kind, amount = work[name]
         if kind == "hbm":
             ach, peak, unit = amount / us / 1e3, PEAK_HBM_GBS, "GB/s"
-        elif kind == "mfma_i8":
+        elif kind in ("mfma_i8", "mfma_mixed"):
             ach, peak, unit = amount / us / 1e6, PEAK_I8_TOPS, "TFLOP/s"
         else:
             ach, peak, unit = amount / us / 1e6, PEAK_BF16_TFLOPS, "TFLOP/s"
@@ -271,7 +277,7 @@ def main():
     copy_us = _event_time_us(lambda: calib_dst.copy_(calib_src), 20, torch, warm=10)
     del calib_src, calib_dst
 
-    dom = "int8_gemm"
+    dom = "products"
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
@@ -279,10 +285,13 @@ def main():
             traffic = json.load(open(tpath)).get(args.workload, {}).get(dom)
         except Exception:
             traffic = None
-    roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["achieved"], "peak": PEAK_I8_TOPS,
-                "unit": "TFLOP/s", "frac": kernels[dom]["frac"], "traffic": traffic,
-                "note": "int8 MFMA ops (2*N*d_in*d_out per launch) over the HIP-event average of %s launches, "
-                        "each timed inside the stage sequence of the path" % iters}
+    roofline = {"kernel": "products (k_gemm_pair: int8 dX product | bf16 dW product in one launch)", "bound": "mfma",
+                "achieved": kernels[dom]["achieved"], "peak": PEAK_I8_TOPS, "unit": "TFLOP/s", "frac": kernels[dom]["frac"],
+                "traffic": traffic,
+                "note": "int8-equivalent ops per launch (2*N*d_in*d_out int8 ops + 2 x 2*d_out*d_in*Kc bf16 flops: a bf16 "
+                        "flop counts as two, the ratio of the MFMA peaks, so frac = time at the two datasheet peaks / time "
+                        "taken) over the HIP-event average of %s launches, each timed inside the stage sequence of the "
+                        "path; the products alone: kernels.int8_gemm, kernels.bf16_gemm" % iters}
 
     cpu = None
     if args.cpu_tokens > 0:

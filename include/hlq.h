@@ -291,6 +291,26 @@ int hlq_linear_backward_cached(const void *G, const void *X, const void *Xc, con
  */
 int hlq_mfma_probe(int kind, int blocks, int iters, float *sink, void *stream);
 
+/*
+ * Stages 5-6 of the g_x list and stage 5 (and 6) of the g_w list in ONE launch -- what the whole
+ * path runs after its transforms.  The two products are independent and for most layers neither
+ * fills the chip: tiles of one take the compute units the other leaves idle.
+ *   Gq [N, d_out] / WqT [d_in, d_out] codes as hlq_quantize_g / _w store them for `gx_bits`
+ *   (HLQ_BITS_4, HLQ_BITS_8 or HLQ_BITS_4_PACKED, no rounding bit), with sG [N], sW [d_in];
+ *   GhatT [d_out, Kc] / XhatT [d_in, Kc]: bf16 projections (sGhat = sXhat = NULL), or int8 codes with
+ *   their scales sGhat [d_out], sXhat [d_in] (the integer g_w list);
+ *   dX [N, d_in] = Gq . WqT^T * sG (x) sW / B,  dW [d_out, d_in] = GhatT . XhatT^T (* scales) / B, of `dtype`.
+ *   workspace: NULL, or >= hlq_backward_products_workspace_bytes(...) bytes of device scratch
+ *   (16-byte aligned) that lets the g_w product split its reduction.
+ * Shape rules of the two products (hlq_int8_gemm_nt / hlq_int4_gemm_nt / hlq_bf16_gemm_nt) apply.
+ * dX equals the single product's bit for bit; dW up to the summation order of the k splits.
+ */
+size_t hlq_backward_products_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int64_t Kc, int gx_bits, int gw_int8);
+int hlq_backward_products(const void *Gq, const float *sG, const void *WqT, const float *sW, int gx_bits,
+                          const void *GhatT, const float *sGhat, const void *XhatT, const float *sXhat, int64_t N,
+                          int64_t d_in, int64_t d_out, int64_t Kc, int B, int dtype, void *dX, void *dW, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
 /* ---- convolution layers ------------------------------------------------------------------------ */
 
 /*

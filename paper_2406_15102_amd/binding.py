@@ -74,6 +74,9 @@ _EXPORTS = {
     "hlq_bf16_gemm_nt": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_float, C.c_int,
                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hlq_mfma_probe": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
+    "hlq_backward_products_workspace_bytes": (C.c_size_t, [C.c_int64] * 4 + [C.c_int, C.c_int]),
+    "hlq_backward_products": (C.c_int, [C.c_void_p] * 4 + [C.c_int] + [C.c_void_p] * 4 + [C.c_int64] * 4
+                              + [C.c_int, C.c_int] + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]),
     "hlq_conv_sizes": (C.c_int, [_GEOM_P] + [C.POINTER(C.c_int64)] * 4),
     "hlq_im2col": (C.c_int, [C.c_void_p, _GEOM_P, C.c_int, C.c_void_p, C.c_void_p]),
     "hlq_col2im": (C.c_int, [C.c_void_p, _GEOM_P, C.c_int, C.c_void_p, C.c_void_p]),
@@ -348,3 +351,18 @@ def hlq_conv2d_backward(G, X, Wt, geom, B, r, seed, flags, dX, dW, workspace=Non
     ws_ptr, ws_bytes = (None, 0) if workspace is None else (_ptr(workspace), _nbytes(workspace))
     _check(lib().hlq_conv2d_backward(_ptr(G), _ptr(X), _ptr(Wt), C.byref(geom), B, r, seed, _dt(G), flags, _ptr(dX),
                                      _ptr(dW), ws_ptr, ws_bytes, _stream()), "hlq_conv2d_backward")
+
+
+def hlq_backward_products_workspace_bytes(N, d_in, d_out, Kc, gx_bits, gw_int8=False) -> int:
+    return int(lib().hlq_backward_products_workspace_bytes(N, d_in, d_out, Kc, gx_bits, int(bool(gw_int8))))
+
+
+def hlq_backward_products(Gq, sG, WqT, sW, gx_bits, GhatT, sGhat, XhatT, sXhat, B, dX, dW, workspace=None):
+    """Both matrix products of the pass in one launch, from the stored codes and projections."""
+    N, d_in = dX.shape
+    d_out, Kc = GhatT.shape
+    ws_ptr, ws_bytes = (None, 0) if workspace is None else (_ptr(workspace), _nbytes(workspace))
+    _check(lib().hlq_backward_products(_codes_ptr(Gq), _ptr(sG, torch.float32), _codes_ptr(WqT), _ptr(sW, torch.float32),
+                                       gx_bits, _ptr(GhatT), _ptr(sGhat, torch.float32), _ptr(XhatT),
+                                       _ptr(sXhat, torch.float32), N, d_in, d_out, Kc, B, _dt(dX), _ptr(dX), _ptr(dW),
+                                       ws_ptr, ws_bytes, _stream()), "hlq_backward_products")

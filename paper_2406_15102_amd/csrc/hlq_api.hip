@@ -290,6 +290,60 @@ int hlq_int4_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64
     return launch_rc(hlq::launch_gemm_nt(2, a, static_cast<hipStream_t>(stream)));
 }
 
+// kinds of the two products from the storage of their operands
+static int products_kinds(int gx_bits, bool gw_int8, int *kx, int *kw)
+{
+    if (gx_bits != HLQ_BITS_4 && gx_bits != HLQ_BITS_8 && gx_bits != HLQ_BITS_4_PACKED) return HLQ_ERR_SHAPE;
+    *kx = gx_bits == HLQ_BITS_4_PACKED ? 2 : 0;
+    *kw = gw_int8 ? 0 : 1;
+    return HLQ_OK;
+}
+
+static int products_check(int64_t N, int64_t d_in, int64_t d_out, int64_t Kc, int kx, int kw)
+{
+    int rc;
+    if ((rc = check_gemm_shape(N, d_in, d_out, kx == 2 ? 32 : 16)) != HLQ_OK) return rc;
+    if ((rc = check_gemm_shape(d_out, d_in, Kc, kw == 0 ? 16 : 8)) != HLQ_OK) return rc;
+    if (d_out > kMaxIntK || (kw == 0 && Kc > kMaxIntK)) return HLQ_ERR_SHAPE;
+    return HLQ_OK;
+}
+
+size_t hlq_backward_products_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int64_t Kc, int gx_bits, int gw_int8)
+{
+    int kx, kw;
+    if (products_kinds(gx_bits, gw_int8 != 0, &kx, &kw) != HLQ_OK || products_check(N, d_in, d_out, Kc, kx, kw) != HLQ_OK)
+        return 0;
+    hlq::GemmArgs ax{}, aw{};
+    ax.M = static_cast<int>(N), ax.N = static_cast<int>(d_in), ax.K = static_cast<int>(d_out);
+    aw.M = static_cast<int>(d_out), aw.N = static_cast<int>(d_in), aw.K = static_cast<int>(Kc);
+    return hlq::gemm_pair_ws_bytes(kx, ax, kw, aw, size_t(256) << 20);
+}
+
+int hlq_backward_products(const void *Gq, const float *sG, const void *WqT, const float *sW, int gx_bits,
+                          const void *GhatT, const float *sGhat, const void *XhatT, const float *sXhat, int64_t N,
+                          int64_t d_in, int64_t d_out, int64_t Kc, int B, int dtype, void *dX, void *dW, void *workspace,
+                          size_t workspace_bytes, void *stream)
+{
+    int rc, kx, kw;
+    if (!Gq || !sG || !WqT || !sW || !GhatT || !XhatT || !dX || !dW) return HLQ_ERR_NULL;
+    if ((sGhat == nullptr) != (sXhat == nullptr)) return HLQ_ERR_NULL;      // both int8 with scales, or both bf16
+    if ((rc = check_block(B)) != HLQ_OK) return rc;
+    if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if ((rc = products_kinds(gx_bits, sGhat != nullptr, &kx, &kw)) != HLQ_OK) return rc;
+    if ((rc = products_check(N, d_in, d_out, Kc, kx, kw)) != HLQ_OK) return rc;
+    if (!aligned(Gq, 16) || !aligned(WqT, 16) || !aligned(sW, 16) || !aligned(GhatT, 16) || !aligned(XhatT, 16) ||
+        (sXhat && !aligned(sXhat, 16)) || !aligned(dX, 16) || !aligned(dW, 16))
+        return HLQ_ERR_SHAPE;
+    if (workspace && !aligned(workspace, 16)) return HLQ_ERR_WORKSPACE;
+    const float invB = 1.0f / static_cast<float>(B);
+    const bool f32 = dtype == HLQ_F32;
+    hlq::GemmArgs ax{Gq, WqT, static_cast<int>(N), static_cast<int>(d_in), static_cast<int>(d_out), sG, sW, invB, dX, f32,
+                     nullptr, nullptr, 0};
+    hlq::GemmArgs aw{GhatT, XhatT, static_cast<int>(d_out), static_cast<int>(d_in), static_cast<int>(Kc), sGhat, sXhat,
+                     invB, dW, f32, nullptr, workspace, workspace_bytes};
+    return launch_rc(hlq::launch_gemm_pair(kx, ax, kw, aw, static_cast<hipStream_t>(stream)));
+}
+
 int hlq_hla_project(const void *T, int64_t N, int64_t D, int B, int r, int dtype, void *ThatT, float *coeffT,
                     void *stream)
 {

@@ -200,3 +200,21 @@ def test_convolution_entry_points_without_a_gpu():
     p = geom(kh=1, kw=1, pad_h=0, pad_w=0)
     assert hlq.hlq_conv_workspace_bytes(p, 16, 8, 0) == hlq.hlq_workspace_bytes_mode(256, 16, 32, 16, 8, False, 0)
     assert hlq.hlq_conv_workspace_bytes(geom(O=40), 16, 8, 0) == 0
+
+
+def test_products_entry_point_without_a_gpu():
+    l = hlq.lib()
+    f = l.hlq_backward_products
+
+    def call(Gq=FAKE, sG=FAKE, WqT=FAKE, sW=FAKE, bits=0x104, Gh=FAKE, sGh=None, Xh=FAKE, sXh=None, N=256, I=256, O=256,
+             Kc=128, B=16, dt=0, dX=FAKE, dW=FAKE):
+        return f(Gq, sG, WqT, sW, bits, Gh, sGh, Xh, sXh, N, I, O, Kc, B, dt, dX, dW, None, 0, None)
+
+    assert call(Gq=None) == 1 and call(dW=None) == 1 and call(sGh=FAKE) == 1      # int8 projections come with both scales
+    assert call(bits=5) == 2 and call(bits=0x304) == 2                             # storage, without a rounding bit
+    assert call(O=48) == 2                                                         # packed codes need d_out % 32 == 0
+    assert call(B=20) == 3 and call(dt=9) == 5
+    assert call(Kc=12) == 2 and call(sGh=FAKE, sXh=FAKE, Kc=24) == 2               # 16-byte rows of either operand kind
+    assert hlq.hlq_backward_products_workspace_bytes(12608, 768, 3072, 6304, 0x104) > 0
+    assert hlq.hlq_backward_products_workspace_bytes(4096, 4096, 11008, 2048, 0x104) == 0
+    assert hlq.hlq_backward_products_workspace_bytes(4096, 4096, 11008, 2048, 7) == 0

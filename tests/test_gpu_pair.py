@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2406_15102_amd as hlq
 from paper_2406_15102_amd import workloads as wl
-from test_gpu_parity import TOL_OUT, row_rel_err
+from test_gpu_parity import TOL_OUT, row_rel_err, same_up_to_split_order
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -76,3 +76,44 @@ def test_one_output_alone_takes_the_single_launches():
     torch.cuda.synchronize()
     assert torch.equal(dX, dX1)
     assert float((dW.float() - dW1.float()).abs().max()) <= 2.0 ** -7 * float(dW1.float().abs().max())
+
+
+@pytest.mark.parametrize("gw_int8", [False, True])
+@pytest.mark.parametrize("N,d_in,d_out,B,r,dtype", [CASES[0], CASES[1], CASES[5]])
+def test_products_entry_point_equals_the_whole_path(N, d_in, d_out, B, r, dtype, gw_int8):
+    """Stage entry points up to the stored codes and projections, then both products through
+    hlq_backward_products: what the whole path computes."""
+    w = wl.scaled(wl.WORKLOADS["c2"], N=N, d_in=d_in, d_out=d_out, B=B, r=r, dtype=dtype)
+    t = wl.generate(w)
+    G, X, W = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
+    Kc, seed = N // B * r, 3
+    flags = hlq.HLQ_FLAG_GW_INT8 if gw_int8 else 0
+    dX0 = torch.empty((N, d_in), dtype=G.dtype, device=DEV)
+    dW0 = torch.empty((d_out, d_in), dtype=G.dtype, device=DEV)
+    hlq.hlq_linear_backward_mode(G, X, None, None, W, N, d_in, d_out, B, r, seed, flags, dX0, dW0)
+    bits = hlq.hlq_weight_code_bits(d_out, flags)
+    cb = d_out // 2 if bits == hlq.HLQ_BITS_4_PACKED else d_out
+    Gq = torch.empty((N, cb), dtype=torch.uint8, device=DEV)
+    WqT = torch.empty((d_in, cb), dtype=torch.uint8, device=DEV)
+    sG, sW = torch.empty(N, dtype=torch.float32, device=DEV), torch.empty(d_in, dtype=torch.float32, device=DEV)
+    wws = torch.empty(hlq.hlq_quantize_w_workspace_bytes(d_out, d_in), dtype=torch.uint8, device=DEV)
+    hlq.hlq_quantize_g(G, B, seed, Gq, sG, None, bits)
+    hlq.hlq_quantize_w(W, B, seed, WqT, sW, wws, None, bits)
+    if gw_int8:
+        Gh, Xh = (torch.empty((d, Kc), dtype=torch.int8, device=DEV) for d in (d_out, d_in))
+        sGh, sXh = (torch.empty(d, dtype=torch.float32, device=DEV) for d in (d_out, d_in))
+        hws = torch.empty(hlq.hlq_hla_quantize_workspace_bytes(max(d_in, d_out)), dtype=torch.uint8, device=DEV)
+        hlq.hlq_hla_quantize(G, B, r, seed, 3, Gh, sGh, hws)
+        hlq.hlq_hla_quantize(X, B, r, seed, 2, Xh, sXh, hws)
+    else:
+        Gh, Xh = (torch.empty((d, Kc), dtype=torch.bfloat16, device=DEV) for d in (d_out, d_in))
+        sGh = sXh = None
+        hlq.hlq_hla_project(G, B, r, Gh)
+        hlq.hlq_hla_project(X, B, r, Xh)
+    pws = torch.empty(max(16, hlq.hlq_backward_products_workspace_bytes(N, d_in, d_out, Kc, bits, gw_int8)),
+                      dtype=torch.uint8, device=DEV)
+    dX1, dW1 = torch.full_like(dX0, 7.0), torch.full_like(dW0, 7.0)
+    hlq.hlq_backward_products(Gq, sG, WqT, sW, bits, Gh, sGh, Xh, sXh, B, dX1, dW1, pws)
+    torch.cuda.synchronize()
+    assert torch.equal(dX0, dX1)
+    assert torch.equal(dW0, dW1) if gw_int8 else same_up_to_split_order(dW1, dW0)
