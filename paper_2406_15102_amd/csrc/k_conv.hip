@@ -105,12 +105,11 @@ __global__ __launch_bounds__(256) void k_col2im(const T *__restrict__ cols, Conv
     float s[VEC];
 #pragma unroll
     for (int k = 0; k < VEC; ++k) s[k] = 0.0f;
-#pragma unroll
+    // constant trip counts (KS > 0) unroll by themselves; the general case stays a loop
     for (int ky = 0; ky < KH; ++ky) {
         const int hn = h + g.ph - ky * g.dh;              // = ho * stride for the output row that read this pixel
         const int ho = g.sh == 1 ? hn : hn / g.sh;
         const bool okh = hn >= 0 && ho * g.sh == hn && ho < g.Ho;
-#pragma unroll
         for (int kx = 0; kx < KW; ++kx) {
             const int wn = w + g.pw - kx * g.dw;
             const int wo = g.sw == 1 ? wn : wn / g.sw;
