@@ -341,7 +341,11 @@ int hlq_backward_products(const void *Gq, const float *sG, const void *WqT, cons
                      nullptr, nullptr, 0};
     hlq::GemmArgs aw{GhatT, XhatT, static_cast<int>(d_out), static_cast<int>(d_in), static_cast<int>(Kc), sGhat, sXhat,
                      invB, dW, f32, nullptr, workspace, workspace_bytes};
-    return launch_rc(hlq::launch_gemm_pair(kx, ax, kw, aw, static_cast<hipStream_t>(stream)));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hlq::gemm_pair_available(kx, ax, kw, aw)) return launch_rc(hlq::launch_gemm_pair(kx, ax, kw, aw, st));
+    // a grid too large for one launch: one launch per product
+    if ((rc = launch_rc(hlq::launch_gemm_nt(kx, ax, st))) != HLQ_OK) return rc;
+    return launch_rc(hlq::launch_gemm_nt(kw, aw, st));
 }
 
 int hlq_hla_project(const void *T, int64_t N, int64_t D, int B, int r, int dtype, void *ThatT, float *coeffT,

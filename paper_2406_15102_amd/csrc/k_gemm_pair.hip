@@ -107,8 +107,11 @@ size_t gemm_pair_ws_bytes(int kindA, const GemmArgs &a, int kindB, const GemmArg
 
 bool gemm_pair_available(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b)
 {
+    // the grid of the launch (128-tiles of both products, the second split 16 ways) must fit 31 bits with room
+    const int64_t blocks = static_cast<int64_t>((a.M + 127) / 128) * ((a.N + 127) / 128) +
+                           16 * static_cast<int64_t>((b.M + 127) / 128) * ((b.N + 127) / 128);
     return (kindA == 2 || kindA == 0) && (kindB == 1 || kindB == 0) && a.C && b.C && !a.acc && !b.acc &&
-           a.c_is_f32 == b.c_is_f32;
+           a.c_is_f32 == b.c_is_f32 && blocks < (int64_t(1) << 30);
 }
 
 hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, hipStream_t st)
