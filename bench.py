@@ -200,6 +200,16 @@ def main():
             continue
         fn = lambda: hlq.hlq_linear_backward_mode(G, X, None, None, W, N, I, O, B, r, w.seed, flags, dX, dW, ws)
         modes[label] = {"us": round(_event_time_us(fn, iters, torch, warm=max(3, args.warmup // 2)), 2)}
+    # ---- activation compressed at forward time (ACBP): the store, and the backward pass that consumes it ----
+    hlq.hlq_compress_act(X, B, r, XhT)
+    acbp = {
+        "compress_act_us": round(_event_time_us(lambda: hlq.hlq_compress_act(X, B, r, XhT), iters, torch,
+                                                warm=max(3, args.warmup // 2)), 2),
+        "backward_from_store_us": round(_event_time_us(
+            lambda: hlq.hlq_linear_backward_ex(G, None, XhT, W, N, I, O, B, r, w.seed, dX, dW, ws), iters, torch,
+            warm=max(3, args.warmup // 2)), 2),
+        "stored_bytes": XhT.numel() * 2, "x_bytes": X.numel() * X.element_size(),
+    }
     # ---- the default path with one launch per matrix product (by default the two share a launch) ----
     sep = lambda: hlq.hlq_linear_backward_mode(G, X, None, None, W, N, I, O, B, r, w.seed, hlq.HLQ_FLAG_SEPARATE_PRODUCTS,
                                                dX, dW, ws)
@@ -313,6 +323,7 @@ def main():
         "modes_us": modes,
         "cached_weight_codes_us": round(cached_us, 2),
         "separate_products_us": round(separate_us, 2),
+        "forward_time_store": acbp,
         "as_convolution": conv,
         "copy_256MiB": {"us": round(copy_us, 2), "GB/s": round(2 * (1 << 28) / copy_us / 1e3, 1)},
         "roofline": roofline,

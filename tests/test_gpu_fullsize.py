@@ -85,6 +85,13 @@ def test_full_size_workload_sampled(name):
     XhT = torch.empty((I, Kc), dtype=torch.bfloat16, device=DEV)
     hlq.hlq_compress_act(X, B, r, XhT)
     assert np.array_equal(XhT.float().cpu().numpy().view(np.uint32), xh.view(np.uint32))   # ACBP store, in full
+    # the backward pass that consumes the store (how the 70B-shaped workload is meant to run): same bits
+    ws = torch.empty(hlq.hlq_workspace_bytes(N, I, O, B, r, True), dtype=torch.uint8, device=DEV)
+    dX2, dW2 = torch.empty_like(dX), torch.empty_like(dW)
+    hlq.hlq_linear_backward_ex(G, None, XhT, W, N, I, O, B, r, w.seed, dX2, dW2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dX2, dX) and torch.equal(dW2, dW)
+    del ws, dX2, dW2
     orows = _sample(O, 12, [0, 1, 127, 128, 255, 256, O - 257, O - 1], seed=2)
     gh = oracle.round_bf16(oracle.hla_f32(np.ascontiguousarray(Gn[:, orows]), B, r))
     ref_dW = oracle.gemm_nt_f64(gh, xh, 1.0 / B)
