@@ -90,7 +90,7 @@ Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_
     L.sG = off;    off += up256(static_cast<size_t>(N) * 4);
     L.Wq = off;    off += up256(static_cast<size_t>(d_in) * d_out);
     L.sW = off;    off += up256(static_cast<size_t>(d_in) * 4);
-    L.wws = off;   off += up256(hlq::quant_cols_ws_bytes(d_out, d_in));
+    L.wws = off;   off += up256(hlq::quant_cols_table_bytes(d_out, d_in, B));
     // integer g_w list: column maxima of projected G (d_out words), then of projected X (d_in words),
     // right behind those of the weight so that one fill zeroes all three
     L.hws = off;   off += gwi ? up256(hlq::hla_quant_ws_bytes(d_out)) + up256(hlq::hla_quant_ws_bytes(d_in)) : 0;
@@ -548,15 +548,25 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
             sXh = sx;
         }
     }
+    // the table of per-row-block maxima of H^T W, when pass 1 rides in the one-launch front
+    int w_parts = 1;
     if (fused) {
         uint16_t *xh = xc ? nullptr : reinterpret_cast<uint16_t *>(ws + L.XhatT);
         const hlq::FrontRows jr = hlq::front_rows(dX ? G : nullptr, N, O, B, static_cast<uint32_t>(kg),
                                                   static_cast<uint32_t>(kg >> 32), qmax, Gq, sG);
         const hlq::FrontHla jx = hlq::front_hla(dW && !xc ? X : nullptr, N, I, B, r, xh);
-        const hlq::FrontFill jf{reinterpret_cast<uint32_t *>(ws + L.wws), dX && !wc ? I : 0};
         const hlq::FrontHla jg = hlq::front_hla(dW ? G : nullptr, N, O, B, r, static_cast<uint16_t *>(Gh));
-        const hlq::FrontAbsmax jw = hlq::front_absmax(dX && !wc ? W : nullptr, O, I, B, reinterpret_cast<uint32_t *>(ws + L.wws));
-        if ((rc = launch_rc(hlq::launch_front(jr, jx, jf, jg, jw, conv, B, basis, f32, packed, st))) != HLQ_OK) return rc;
+        hlq::FrontAbsmax jw = hlq::front_absmax(dX && !wc ? W : nullptr, O, I, B, reinterpret_cast<uint32_t *>(ws + L.wws));
+        if (hlq::quant_cols_row_blocks(O, B) <= hlq::kFrontOneLaunchMaxParts) {
+            // few row blocks of W: everything in one launch, the maxima per row block
+            jw.partial = 1;
+            w_parts = jw.W ? jw.gy : 1;
+            rc = launch_rc(hlq::launch_front_one(jr, jx, jg, jw, conv, B, basis, f32, packed, st));
+        } else {
+            const hlq::FrontFill jf{reinterpret_cast<uint32_t *>(ws + L.wws), dX && !wc ? I : 0};
+            rc = launch_rc(hlq::launch_front(jr, jx, jf, jg, jw, conv, B, basis, f32, packed, st));
+        }
+        if (rc != HLQ_OK) return rc;
         if (dW && !xc) Xh = xh;
     }
     if (dX && !fused && !fused_q) {
@@ -607,7 +617,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         else if (fused)   // pass 1 ran in the second front launch
             rc = launch_rc(hlq::launch_quant_cols_pass2(W, O, I, B, f32, static_cast<uint32_t>(kw),
                                                         static_cast<uint32_t>(kw >> 32), qmax, packed, false, wq, sw,
-                                                        nullptr, ws + L.wws, st));
+                                                        nullptr, ws + L.wws, w_parts, st));
         else
             rc = launch_rc(hlq::launch_quant_cols(W, O, I, B, f32, static_cast<uint32_t>(kw),
                                                   static_cast<uint32_t>(kw >> 32), qmax, packed, mant, wq, sw, nullptr,

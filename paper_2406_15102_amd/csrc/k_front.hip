@@ -7,6 +7,7 @@
 //                                                                    convolution read as its column matrix)
 //   front B   K3(G)  |  column maxima of H^T W      (needs the zeroing; G is re-read while the
 //                                                    last-level cache still holds it)
+// or ONE, when the weight has few row blocks (k_front_one below): the maxima stay per row block.
 // and three launches carry the integer g_w list, whose projections are quantised in two passes too:
 //   front A   K1(G)  |  zeroing of all three sets of maxima
 //   front Q1  maxima of projected G  |  of projected X  |  of H^T W
@@ -44,6 +45,35 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
     b -= jx.gx * jx.gy;
     const int i = b * 256 + threadIdx.x;
     if (i < jf.n) jf.p[i] = 0u;
+}
+
+// The whole front in one launch, for weights with few row blocks: pass 1 of K1T leaves its maxima per
+// row block (no zeroing, hence no launch before it) and pass 2 reduces the few rows of that table.
+template <typename Tin, int B, bool PACKED, int BASIS, bool CONV>
+__global__ __launch_bounds__(256) void k_front_one(FrontRows jr, FrontHla jx, FrontHla jg, FrontAbsmax jw, FrontConv jc)
+{
+    int b = blockIdx.x;
+    if (b < jr.blocks) {
+        quant_rows_body<Tin, B, 256, PACKED>(static_cast<const Tin *>(jr.G), jr.N, jr.O, jr.T, jr.k0, jr.k1, jr.qmax, jr.Gq,
+                                             jr.sG, nullptr, b);
+        return;
+    }
+    b -= jr.blocks;
+    if (b < jx.gx * jx.gy) {
+        if (CONV)
+            hla_body_src<B, BASIS>(ConvRows<Tin>{static_cast<const Tin *>(jx.T), jc.g}, jx.N, jx.D, jx.r, jx.out, nullptr,
+                                   b % jx.gx, b / jx.gx);
+        else
+            hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, b % jx.gx, b / jx.gx);
+        return;
+    }
+    b -= jx.gx * jx.gy;
+    if (b < jg.gx * jg.gy) {
+        hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.out, nullptr, b % jg.gx, b / jg.gx);
+        return;
+    }
+    b -= jg.gx * jg.gy;
+    cols_absmax_body<Tin, B>(static_cast<const Tin *>(jw.W), jw.O, jw.I, jw.amax, b % jw.gx, b / jw.gx, true);
 }
 
 template <typename Tin, int B, int BASIS>
@@ -180,7 +210,7 @@ FrontHla front_hla(const void *T, int64_t N, int D, int B, int r, uint16_t *out)
 
 FrontAbsmax front_absmax(const void *W, int O, int I, int B, uint32_t *amax)
 {
-    FrontAbsmax j{W, O, I, amax, 0, 0};
+    FrontAbsmax j{W, O, I, amax, 0, 0, 0};
     if (!W) return j;
     const int cpl = 128 / B;
     j.gx = (I + 64 * cpl - 1) / (64 * cpl);
@@ -205,6 +235,48 @@ static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const 
     const int nb = jg.gx * jg.gy + jw.gx * jw.gy;
     if (nb > 0) hipLaunchKernelGGL((k_front_b<Tin, B, BASIS>), dim3(nb), dim3(256), 0, st, jg, jw);
     return hipGetLastError();
+}
+
+template <typename Tin, int B, int BASIS>
+static hipError_t launch_front_one_t(const FrontRows &jr, const FrontHla &jx, const FrontHla &jg, const FrontAbsmax &jw,
+                                     const FrontConv &jc, bool packed, hipStream_t st)
+{
+    const int n = jr.blocks + jx.gx * jx.gy + jg.gx * jg.gy + jw.gx * jw.gy;
+    if (n == 0) return hipSuccess;
+#define HLQ_FRONT_ONE(P, CV) hipLaunchKernelGGL((k_front_one<Tin, B, P, BASIS, CV>), dim3(n), dim3(256), 0, st, jr, jx, jg, jw, jc)
+    if (jc.on) {
+        if (packed) HLQ_FRONT_ONE(true, true); else HLQ_FRONT_ONE(false, true);
+    } else {
+        if (packed) HLQ_FRONT_ONE(true, false); else HLQ_FRONT_ONE(false, false);
+    }
+#undef HLQ_FRONT_ONE
+    return hipGetLastError();
+}
+
+hipError_t launch_front_one(const FrontRows &jr, const FrontHla &jx, const FrontHla &jg, const FrontAbsmax &jw,
+                            const ConvShape *conv, int B, int basis, bool is_f32, bool packed, hipStream_t st)
+{
+    FrontConv jc{};
+    if (conv) {
+        if (!hla_conv_ok(*conv, B)) return hipErrorInvalidValue;
+        jc.g = *conv;
+        jc.on = 1;
+    }
+    if (jw.W && (!jw.partial || jw.gy > kFrontOneLaunchMaxParts)) return hipErrorInvalidValue;
+#define HLQ_FRONT1_CASE(BB)                                                                     \
+    case BB:                                                                                    \
+        if (basis)                                                                              \
+            return is_f32 ? launch_front_one_t<float, BB, 1>(jr, jx, jg, jw, jc, packed, st)    \
+                          : launch_front_one_t<bf16_t, BB, 1>(jr, jx, jg, jw, jc, packed, st);  \
+        return is_f32 ? launch_front_one_t<float, BB, 0>(jr, jx, jg, jw, jc, packed, st)        \
+                      : launch_front_one_t<bf16_t, BB, 0>(jr, jx, jg, jw, jc, packed, st);
+    switch (B) {
+        HLQ_FRONT1_CASE(16)
+        HLQ_FRONT1_CASE(32)
+        HLQ_FRONT1_CASE(64)
+    }
+#undef HLQ_FRONT1_CASE
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_front(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
