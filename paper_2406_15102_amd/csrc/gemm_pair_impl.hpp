@@ -4,8 +4,8 @@
 // handful at a ResNet layer, against 256 compute units.  Launched together, the tiles of one fill
 // the compute units the other leaves idle, the tail of one overlaps the start of the other, and
 // one launch latency goes away.  A workgroup runs the tile body of gemm_body.hpp of whichever
-// product its index falls in (first the g_x product's tiles, padded to a multiple of 8 so that the
-// second product's tiles keep their XCD assignment, then the g_w product's).  The tile sizes and
+// product its index falls in (first the tiles of the product with the longer tiles, padded to a
+// multiple of 8 so that the other product's tiles keep their XCD assignment, then the other's).  The tile sizes and
 // the k split of the g_w product are planned for the pair, not for each product alone.
 //
 // One translation unit per pair of operand kinds (k_gemm_pair_*.hip instantiate launch_pair_kinds
@@ -22,19 +22,21 @@ template <int KIND_, int W_, bool TAIL_, int OUT_> struct TileCfg {
     static constexpr bool TAIL = TAIL_;
 };
 
+// n0 workgroups of the product that goes first (padded to n0_pad), then the other's; b_first: the
+// g_w product goes first (the plan puts the product with the longer tiles first).
 template <class CA, class CB>
-__global__ __launch_bounds__(256) void k_gemm_pair(GemmDev ga, GemmDev gb, int nA, int nA_pad)
+__global__ __launch_bounds__(256) void k_gemm_pair(GemmDev ga, GemmDev gb, int n0, int n0_pad, int b_first)
 {
     const int b = static_cast<int>(blockIdx.x);
-    if (b < nA_pad) {
-        if (b < nA) gemm_tile<CA::KIND, CA::W, CA::W, 8, CA::TAIL, CA::OUT>(ga, b);
-    } else {
-        gemm_tile<CB::KIND, CB::W, CB::W, 8, CB::TAIL, CB::OUT>(gb, b - nA_pad);
-    }
+    const bool in_first = b < n0_pad;
+    if (in_first && b >= n0) return;                    // padding
+    const int idx = in_first ? b : b - n0_pad;
+    if (in_first != (b_first != 0)) gemm_tile<CA::KIND, CA::W, CA::W, 8, CA::TAIL, CA::OUT>(ga, idx);
+    else gemm_tile<CB::KIND, CB::W, CB::W, 8, CB::TAIL, CB::OUT>(gb, idx);
 }
 
 template <class CA, class CB>
-static hipError_t launch_pair_tt(const GemmDev &ga, const GemmDev &gb, hipStream_t st)
+static hipError_t launch_pair_tt(const GemmDev &ga, const GemmDev &gb, bool b_first, hipStream_t st)
 {
     constexpr size_t la = gemm_lds_bytes(CA::W, CA::W, 8), lb = gemm_lds_bytes(CB::W, CB::W, 8);
     constexpr size_t lds_bytes = la > lb ? la : lb;
@@ -46,45 +48,48 @@ static hipError_t launch_pair_tt(const GemmDev &ga, const GemmDev &gb, hipStream
         attr_set = true;
     }
     const int nA = ga.tiles_m * ga.tiles_n * ga.splits, nB = gb.tiles_m * gb.tiles_n * gb.splits;
-    const int nA_pad = (nA + 7) & ~7;
-    hipLaunchKernelGGL((k_gemm_pair<CA, CB>), dim3(nA_pad + nB), dim3(256), lds_bytes, st, ga, gb, nA, nA_pad);
+    const int n0 = b_first ? nB : nA, n1 = b_first ? nA : nB;
+    const int n0_pad = (n0 + 7) & ~7;
+    hipLaunchKernelGGL((k_gemm_pair<CA, CB>), dim3(n0_pad + n1), dim3(256), lds_bytes, st, ga, gb, n0, n0_pad,
+                       b_first ? 1 : 0);
     return hipGetLastError();
 }
 
 // the g_w product writes the dtype the g_x product writes (CA::OUT), or its split-k partials
 template <class CA, int KB, int WB, bool TAILB>
-static hipError_t launch_pair_b(const GemmDev &ga, const GemmDev &gb, int outB, hipStream_t st)
+static hipError_t launch_pair_b(const GemmDev &ga, const GemmDev &gb, int outB, bool b_first, hipStream_t st)
 {
-    if (outB == 3) return launch_pair_tt<CA, TileCfg<KB, WB, TAILB, 3>>(ga, gb, st);
-    return launch_pair_tt<CA, TileCfg<KB, WB, TAILB, CA::OUT>>(ga, gb, st);
+    if (outB == 3) return launch_pair_tt<CA, TileCfg<KB, WB, TAILB, 3>>(ga, gb, b_first, st);
+    return launch_pair_tt<CA, TileCfg<KB, WB, TAILB, CA::OUT>>(ga, gb, b_first, st);
 }
 
 template <class CA, int KB>
-static hipError_t launch_pair_a(const GemmDev &ga, const GemmDev &gb, bool bigB, bool tailB, int outB, hipStream_t st)
+static hipError_t launch_pair_a(const GemmDev &ga, const GemmDev &gb, bool bigB, bool tailB, int outB, bool b_first,
+                                hipStream_t st)
 {
-    if (bigB) return tailB ? launch_pair_b<CA, KB, 4, true>(ga, gb, outB, st) : launch_pair_b<CA, KB, 4, false>(ga, gb, outB, st);
-    return tailB ? launch_pair_b<CA, KB, 2, true>(ga, gb, outB, st) : launch_pair_b<CA, KB, 2, false>(ga, gb, outB, st);
+    if (bigB) return tailB ? launch_pair_b<CA, KB, 4, true>(ga, gb, outB, b_first, st) : launch_pair_b<CA, KB, 4, false>(ga, gb, outB, b_first, st);
+    return tailB ? launch_pair_b<CA, KB, 2, true>(ga, gb, outB, b_first, st) : launch_pair_b<CA, KB, 2, false>(ga, gb, outB, b_first, st);
 }
 
 template <int KA, int KB, int WA, bool TAILA>
 static hipError_t launch_pair_o(const GemmDev &ga, const GemmDev &gb, bool f32, bool bigB, bool tailB, int outB,
-                                hipStream_t st)
+                                bool b_first, hipStream_t st)
 {
-    return f32 ? launch_pair_a<TileCfg<KA, WA, TAILA, 1>, KB>(ga, gb, bigB, tailB, outB, st)
-               : launch_pair_a<TileCfg<KA, WA, TAILA, 0>, KB>(ga, gb, bigB, tailB, outB, st);
+    return f32 ? launch_pair_a<TileCfg<KA, WA, TAILA, 1>, KB>(ga, gb, bigB, tailB, outB, b_first, st)
+               : launch_pair_a<TileCfg<KA, WA, TAILA, 0>, KB>(ga, gb, bigB, tailB, outB, b_first, st);
 }
 
 // every kernel of one pair of kinds; the plan comes from the caller
 template <int KA, int KB>
 static hipError_t launch_pair_kinds(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB,
-                                    hipStream_t st)
+                                    bool b_first, hipStream_t st)
 {
     const bool tailA = ga.Kb % 128 != 0, tailB = gb.Kb % 128 != 0;
     if (bigA)
-        return tailA ? launch_pair_o<KA, KB, 4, true>(ga, gb, f32, bigB, tailB, outB, st)
-                     : launch_pair_o<KA, KB, 4, false>(ga, gb, f32, bigB, tailB, outB, st);
-    return tailA ? launch_pair_o<KA, KB, 2, true>(ga, gb, f32, bigB, tailB, outB, st)
-                 : launch_pair_o<KA, KB, 2, false>(ga, gb, f32, bigB, tailB, outB, st);
+        return tailA ? launch_pair_o<KA, KB, 4, true>(ga, gb, f32, bigB, tailB, outB, b_first, st)
+                     : launch_pair_o<KA, KB, 4, false>(ga, gb, f32, bigB, tailB, outB, b_first, st);
+    return tailA ? launch_pair_o<KA, KB, 2, true>(ga, gb, f32, bigB, tailB, outB, b_first, st)
+                 : launch_pair_o<KA, KB, 2, false>(ga, gb, f32, bigB, tailB, outB, b_first, st);
 }
 
 }  // namespace hlq

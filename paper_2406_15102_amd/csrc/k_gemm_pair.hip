@@ -6,22 +6,28 @@
 
 namespace hlq {
 
-hipError_t launch_pair_21(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, hipStream_t st);
-hipError_t launch_pair_20(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, hipStream_t st);
-hipError_t launch_pair_01(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, hipStream_t st);
-hipError_t launch_pair_00(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, hipStream_t st);
+hipError_t launch_pair_21(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, bool b_first,
+                          hipStream_t st);
+hipError_t launch_pair_20(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, bool b_first,
+                          hipStream_t st);
+hipError_t launch_pair_01(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, bool b_first,
+                          hipStream_t st);
+hipError_t launch_pair_00(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, bool b_first,
+                          hipStream_t st);
 
 // Plan of the pair: tile size of either product and the k split of the g_w product, by a model of
 // how the launch unfolds (microseconds; constants fitted to a sweep of every plan over eleven layer
 // shapes on MI355X).  A tile of nk steps (128 B of k) takes nk * step + fixed.  A 256-tile owns a
 // compute unit.  128-tiles share one in twos only if both products use them (the launch has one LDS
 // size, the larger) and there are more of them than compute units; they step faster alone.
-// Workgroups are dispatched in index order, g_x product first, each to the first free slot: after
-// the g_x tiles' full rounds, the slots of its last, partial round free up one tile later than the
-// rest, and the g_w tiles -- all equal -- finish at the first instant by which enough of them fit.
+// Workgroups are dispatched in index order, the product with the longer tiles first, each to the first
+// free slot: after the first product's full rounds, the slots of its last, partial round free up one
+// tile later than the rest, and the other product's tiles -- all equal -- finish at the first instant
+// by which enough of them fit.
 struct PairPlan {
     bool bigA, bigB;
     int splitsB;
+    bool b_first;    // the g_w product's tiles are dispatched first
 };
 
 namespace {
@@ -72,7 +78,7 @@ static PairPlan plan_pair(const GemmArgs &a, int kindA, const GemmArgs &b, int k
     const int nkA = (row_bytes(kindA, a.K) + 127) / 128, nkB = (row_bytes(kindB, b.K) + 127) / 128;
     const double scaleA = kindA == 2 ? kPackedScale : 1.0, scaleB = kindB == 2 ? kPackedScale : 1.0;
     const double mnB = static_cast<double>(b.M) * b.N;
-    PairPlan best{true, true, 1};
+    PairPlan best{true, true, 1, false};
     double best_t = 1e30;
     for (int bigA = 1; bigA >= 0; --bigA) {
         for (int bigB = 1; bigB >= 0; --bigB) {
@@ -86,11 +92,14 @@ static PairPlan plan_pair(const GemmArgs &a, int kindA, const GemmArgs &b, int k
                 if (S > 1 && (S > nkB || S * mnB * 4.0 > static_cast<double>(ws_bytes))) break;
                 const TileClass cb = tile_class(bigB != 0, mixed, nB1 * S);
                 const double tB = __builtin_ceil(static_cast<double>(nkB) / S) * scaleB * cb.step + cb.fixed;
-                double t = pair_makespan(nA, tA, ca.slots, nB1 * S, tB, cb.slots);
+                // the product with the longer tiles goes first: its tiles are the ones that must not start late
+                const bool b_first = tB > tA;
+                double t = b_first ? pair_makespan(nB1 * S, tB, cb.slots, nA, tA, ca.slots)
+                                   : pair_makespan(nA, tA, ca.slots, nB1 * S, tB, cb.slots);
                 if (S > 1) t += 2.0 * S * mnB * 4.0 / 8.0e6 + 3.0;     // partials out and back, one more launch
                 if (t < best_t) {
                     best_t = t;
-                    best = PairPlan{bigA != 0, bigB != 0, S};
+                    best = PairPlan{bigA != 0, bigB != 0, S, b_first};
                 }
             }
         }
@@ -124,11 +133,11 @@ hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmA
     const int outB = p.splitsB > 1 ? 3 : (b.c_is_f32 ? 1 : 0);
     hipError_t e;
     if (kindA == 2)
-        e = kindB == 1 ? launch_pair_21(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, st)
-                       : launch_pair_20(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, st);
+        e = kindB == 1 ? launch_pair_21(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st)
+                       : launch_pair_20(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st);
     else
-        e = kindB == 1 ? launch_pair_01(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, st)
-                       : launch_pair_00(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, st);
+        e = kindB == 1 ? launch_pair_01(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st)
+                       : launch_pair_00(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st);
     if (e != hipSuccess || p.splitsB == 1) return e;
     return launch_splitk_reduce(kindB == 1 ? 1 : 0, b, p.splitsB, st);
 }
