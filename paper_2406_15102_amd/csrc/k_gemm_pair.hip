@@ -16,12 +16,12 @@ hipError_t launch_pair_00(const GemmDev &ga, const GemmDev &gb, bool bigA, bool 
                           hipStream_t st);
 
 // Plan of the pair: tile size of either product and the k split of the g_w product, by a model of
-// how the launch unfolds (microseconds; constants fitted to a sweep of every plan over eleven layer
-// shapes on MI355X).  A tile of nk steps (128 B of k) takes nk * step + fixed.  A 256-tile owns a
+// how the launch unfolds (microseconds; constants fitted to a sweep of every plan, either dispatch
+// order, over thirteen layer shapes on MI355X).  A tile of nk steps (128 B of k) takes nk * step + fixed.  A 256-tile owns a
 // compute unit.  128-tiles share one in twos only if both products use them (the launch has one LDS
 // size, the larger) and there are more of them than compute units; they step faster alone.
-// Workgroups are dispatched in index order, the product with the longer tiles first, each to the first
-// free slot: after the first product's full rounds, the slots of its last, partial round free up one
+// Workgroups are dispatched in index order, one product's tiles then the other's (both orders are
+// priced), each to the first free slot: after the first product's full rounds, the slots of its last, partial round free up one
 // tile later than the rest, and the other product's tiles -- all equal -- finish at the first instant
 // by which enough of them fit.
 struct PairPlan {
@@ -31,8 +31,8 @@ struct PairPlan {
 };
 
 namespace {
-constexpr double kStepBig = 1.3, kPackedScale = 1.8, kStepSmallAlone = 0.6, kStepSmallShared = 1.1;
-constexpr double kFixedBig = 12.0, kFixedSmall = 6.5;
+constexpr double kStepBig = 1.3, kPackedScale = 1.8, kStepSmallAlone = 0.6, kStepSmallShared = 0.9;
+constexpr double kFixedBig = 16.0, kFixedSmall = 6.5;
 constexpr int kSplitChoices[] = {1, 2, 3, 4, 6, 8, 12, 16};
 
 struct TileClass {
@@ -92,10 +92,11 @@ static PairPlan plan_pair(const GemmArgs &a, int kindA, const GemmArgs &b, int k
                 if (S > 1 && (S > nkB || S * mnB * 4.0 > static_cast<double>(ws_bytes))) break;
                 const TileClass cb = tile_class(bigB != 0, mixed, nB1 * S);
                 const double tB = __builtin_ceil(static_cast<double>(nkB) / S) * scaleB * cb.step + cb.fixed;
-                // the product with the longer tiles goes first: its tiles are the ones that must not start late
-                const bool b_first = tB > tA;
-                double t = b_first ? pair_makespan(nB1 * S, tB, cb.slots, nA, tA, ca.slots)
-                                   : pair_makespan(nA, tA, ca.slots, nB1 * S, tB, cb.slots);
+                // either product may go first: usually the one with the longer tiles, which must not start late
+                const double tab = pair_makespan(nA, tA, ca.slots, nB1 * S, tB, cb.slots);
+                const double tba = pair_makespan(nB1 * S, tB, cb.slots, nA, tA, ca.slots);
+                const bool b_first = tba < tab;
+                double t = b_first ? tba : tab;
                 if (S > 1) t += 2.0 * S * mnB * 4.0 / 8.0e6 + 3.0;     // partials out and back, one more launch
                 if (t < best_t) {
                     best_t = t;
