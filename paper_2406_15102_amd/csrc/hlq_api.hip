@@ -557,8 +557,9 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         const hlq::FrontHla jx = hlq::front_hla(dW && !xc ? X : nullptr, N, I, B, r, xh);
         const hlq::FrontHla jg = hlq::front_hla(dW ? G : nullptr, N, O, B, r, static_cast<uint16_t *>(Gh));
         hlq::FrontAbsmax jw = hlq::front_absmax(dX && !wc ? W : nullptr, O, I, B, reinterpret_cast<uint32_t *>(ws + L.wws));
-        if (hlq::quant_cols_row_blocks(O, B) <= hlq::kFrontOneLaunchMaxParts) {
-            // few row blocks of W: everything in one launch, the maxima per row block
+        if (!jw.W || hlq::quant_cols_row_blocks(O, B) <= hlq::kFrontOneLaunchMaxParts) {
+            // no pass over W here (codes handed over, or dX not wanted), or few row blocks of W:
+            // everything in one launch, the maxima per row block
             jw.partial = 1;
             w_parts = jw.W ? jw.gy : 1;
             rc = launch_rc(hlq::launch_front_one(jr, jx, jg, jw, conv, B, basis, f32, packed, st));
