@@ -79,12 +79,13 @@ def _oracle_pass(t, g, B, r, seed, flags):
     return oracle.conv2d_backward(
         wl.as_f32_numpy(t["G"]), wl.as_f32_numpy(t["X"]), wl.as_f32_numpy(t["W"]), B, r, seed, stride=st, pad=pd, dil=dl,
         gx_bits=8 if flags & hlq.HLQ_FLAG_GX_8BIT else 4, gw_int8=bool(flags & hlq.HLQ_FLAG_GW_INT8),
-        basis=1 if flags & hlq.HLQ_FLAG_GW_SEQUENCY else 0)
+        basis=1 if flags & hlq.HLQ_FLAG_GW_SEQUENCY else 0, rounding=1 if flags & hlq.HLQ_FLAG_ROUND_MANTISSA else 0)
 
 
 @pytest.mark.parametrize("g,flags", [(g, 0) for g in GEOMS] + [
     (GEOMS[1], hlq.HLQ_FLAG_GW_INT8), (GEOMS[4], hlq.HLQ_FLAG_GX_8BIT | hlq.HLQ_FLAG_GW_SEQUENCY),
-    (GEOMS[9], hlq.HLQ_FLAG_GW_INT8 | hlq.HLQ_FLAG_GX_UNPACKED)])
+    (GEOMS[9], hlq.HLQ_FLAG_GW_INT8 | hlq.HLQ_FLAG_GX_UNPACKED), (GEOMS[10], hlq.HLQ_FLAG_ROUND_MANTISSA),
+    (GEOMS[1], hlq.HLQ_FLAG_ROUND_MANTISSA | hlq.HLQ_FLAG_GW_INT8), (GEOMS[0], hlq.HLQ_FLAG_SEPARATE_PRODUCTS)])
 def test_convolution_backward_matches_oracle(g, flags):
     Nb, H, W, C, O, kh, kw, st, pd, dl, dtype = g
     B, r, seed = 16, 8, 5
