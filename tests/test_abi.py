@@ -215,6 +215,6 @@ def test_products_entry_point_without_a_gpu():
     assert call(O=48) == 2                                                         # packed codes need d_out % 32 == 0
     assert call(B=20) == 3 and call(dt=9) == 5
     assert call(Kc=12) == 2 and call(sGh=FAKE, sXh=FAKE, Kc=24) == 2               # 16-byte rows of either operand kind
-    assert hlq.hlq_backward_products_workspace_bytes(12608, 768, 3072, 6304, 0x104) > 0
+    assert hlq.hlq_backward_products_workspace_bytes(50176, 432, 96, 25088, 0x104) > 0    # few tiles, long reduction
     assert hlq.hlq_backward_products_workspace_bytes(4096, 4096, 11008, 2048, 0x104) == 0
     assert hlq.hlq_backward_products_workspace_bytes(4096, 4096, 11008, 2048, 7) == 0
