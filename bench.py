@@ -119,6 +119,17 @@ def main():
     wall_us = (time.perf_counter() - t0) * 1e6 / args.steps
     hlq_us = _event_time_us(step, args.steps, torch, warm=args.warmup // 2)
 
+    # ---- median and minimum of single steps (an event pair per step) ----
+    n_stat = min(args.steps, 100)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_stat)]
+    for a_, b_ in pairs:
+        a_.record()
+        step()
+        b_.record()
+    torch.cuda.synchronize()
+    per_step = sorted(a_.elapsed_time(b_) * 1000.0 for a_, b_ in pairs)
+    step_stats = {"median_us": round(per_step[len(per_step) // 2], 2), "min_us": round(per_step[0], 2), "steps": n_stat}
+
     # ---- the same path with the weight codes taken as cached (W quantised once per optimiser step) ----
     # ---- and kernel by kernel through the stage entry points, HIP events on the launch stream ----------
     packed = O % 32 == 0          # the whole path stores the 4-bit codes two to a byte then
@@ -281,6 +292,19 @@ def main():
     del sets, dense_out
     step()
 
+    # ---- the MFMA rate the chip sustains at its running clock: a register-resident loop of independent MFMAs,
+    # ---- one workgroup of four wavefronts per compute unit (the products' own occupancy) ----
+    sink = torch.zeros(1, dtype=torch.float32, device=dev)
+    n_cu = torch.cuda.get_device_properties(0).multi_processor_count
+    probe_iters = 20000
+    sustained = {}
+    for kind, label, ops in ((0, "int8_TOPS", 65536.0), (1, "bf16_TFLOPS", 32768.0)):
+        us = _event_time_us(lambda: hlq.hlq_mfma_probe(kind, n_cu, probe_iters, sink), 10, torch, warm=10)
+        sustained[label] = round(n_cu * 4 * probe_iters * 8 * ops / us / 1e6, 1)
+    # the pair's work priced at the sustained rates instead of the datasheet peaks
+    pair_ideal_us = 2.0 * N * I * O / sustained["int8_TOPS"] / 1e6 + 2.0 * O * I * Kc / sustained["bf16_TFLOPS"] / 1e6
+    sustained["products_frac_of_sustained"] = round(pair_ideal_us / kernels["products"]["us"], 4)
+
     # ---- a plain copy of known size: the yardstick that scales the profiler's FETCH_SIZE / WRITE_SIZE ----
     calib_src = torch.empty(1 << 28, dtype=torch.uint8, device=dev)
     calib_dst = torch.empty_like(calib_src)
@@ -316,6 +340,7 @@ def main():
                    "io_dtype": w.dtype, "includes": "W quantisation counted every step",
                    "code_storage": "4-bit, two per byte" if packed else "int8"},
         "wall_us_per_step": round(wall_us, 2),
+        "single_step": step_stats,
         "dense_bf16_backward_us": round(dense_us, 2),
         "speedup_vs_dense_bf16": round(dense_us / hlq_us, 3),
         "rotated_inputs": rotated,
@@ -325,6 +350,7 @@ def main():
         "separate_products_us": round(separate_us, 2),
         "forward_time_store": acbp,
         "as_convolution": conv,
+        "mfma_sustained": sustained,
         "copy_256MiB": {"us": round(copy_us, 2), "GB/s": round(2 * (1 << 28) / copy_us / 1e3, 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,

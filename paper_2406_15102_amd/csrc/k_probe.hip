@@ -16,13 +16,23 @@ __global__ __launch_bounds__(256) void k_mfma_probe(int iters, float *sink)
 {
     const int lane = threadIdx.x;
     if (KIND == 0) {
-        v4i a = {lane, lane + 1, lane + 2, lane + 3}, b = {lane * 3, lane * 5, lane * 7, lane * 11};
+        // a different pseudo-random operand pair for each of the eight MFMAs in flight, so that
+        // consecutive MFMAs toggle the multipliers as real data does (constant operands draw less
+        // power and clock higher than any product can)
+        v4i a[8], b[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                a[i][e] = static_cast<int>(0x9E3779B9u * static_cast<unsigned>(lane * 37 + i * 11 + e + 1));
+                b[i][e] = static_cast<int>(0x85EBCA6Bu * static_cast<unsigned>(lane * 53 + i * 7 + e + 3));
+            }
         v16i acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = v16i{0};
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+            for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[i], acc[i], 0, 0, 0);
         }
         int s = 0;
 #pragma unroll
@@ -47,15 +57,23 @@ __global__ __launch_bounds__(256) void k_mfma_probe(int iters, float *sink)
         for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][15];
         if (s == 12345.678f) sink[0] = s;
     } else {
-        v8bf a, b;
+        // as above: eight different operand pairs, values of mixed sign and magnitude in (-2, 2)
+        v8bf a[8], b[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { a[e] = static_cast<__bf16>(1.0f + lane * 0.001f); b[e] = static_cast<__bf16>(0.5f); }
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const unsigned ha = 0x9E3779B9u * static_cast<unsigned>(lane * 37 + i * 11 + e + 1);
+                const unsigned hb = 0x85EBCA6Bu * static_cast<unsigned>(lane * 53 + i * 7 + e + 3);
+                a[i][e] = static_cast<__bf16>((static_cast<int>(ha >> 8) - (1 << 23)) * (1.0f / (1 << 22)));
+                b[i][e] = static_cast<__bf16>((static_cast<int>(hb >> 8) - (1 << 23)) * (1.0f / (1 << 22)));
+            }
         v16f acc[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) acc[i] = v16f{0.0f};
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+            for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[i], acc[i], 0, 0, 0);
         }
         float s = 0.0f;
 #pragma unroll
