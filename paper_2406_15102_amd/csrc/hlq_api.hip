@@ -505,8 +505,9 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     const void *Xh = Xc;
     const float *sXh = sXc;
     // The transforms that depend on nothing share launches when the shapes allow (k_front.hip): two
-    // for the default path, three for the integer g_w list.  Very long rows of G and the
-    // mantissa-bit rounding keep one launch per stage.
+    // for the default path (one when the weight has few row blocks or is not transformed here),
+    // three for the integer g_w list.  Very long rows of G and the mantissa-bit rounding keep one
+    // launch per stage.
     const bool fusable = hlq::front_fusable(O, B) && !mant;   // the fused launches carry the seeded rounding only
     const bool fused = !gwi && fusable;
     const bool fused_q = gwi && fusable;
@@ -631,11 +632,11 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     hlq::GemmArgs ax{Gq, Wq, static_cast<int>(N), I, O, sG, sW, invB, dX, f32, nullptr, ws + L.gws, L.gws_bytes};
     hlq::GemmArgs aw{Gh, Xh, O, I, Kc, gwi ? sGh : nullptr, gwi ? sXh : nullptr, invB, dW, f32, nullptr, ws + L.gws,
                      L.gws_bytes};
-    const int kx = packed ? 2 : 0, kw_ = gwi ? 0 : 1;
-    if (dX && dW && !(flags & HLQ_FLAG_SEPARATE_PRODUCTS) && hlq::gemm_pair_available(kx, ax, kw_, aw))
-        return launch_rc(hlq::launch_gemm_pair(kx, ax, kw_, aw, st));
-    if (dX && (rc = launch_rc(hlq::launch_gemm_nt(kx, ax, st))) != HLQ_OK) return rc;
-    if (dW && (rc = launch_rc(hlq::launch_gemm_nt(kw_, aw, st))) != HLQ_OK) return rc;
+    const int kind_x = packed ? 2 : 0, kind_w = gwi ? 0 : 1;
+    if (dX && dW && !(flags & HLQ_FLAG_SEPARATE_PRODUCTS) && hlq::gemm_pair_available(kind_x, ax, kind_w, aw))
+        return launch_rc(hlq::launch_gemm_pair(kind_x, ax, kind_w, aw, st));
+    if (dX && (rc = launch_rc(hlq::launch_gemm_nt(kind_x, ax, st))) != HLQ_OK) return rc;
+    if (dW && (rc = launch_rc(hlq::launch_gemm_nt(kind_w, aw, st))) != HLQ_OK) return rc;
     return HLQ_OK;
 }
 
