@@ -90,7 +90,7 @@ Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_
     L.sG = off;    off += up256(static_cast<size_t>(N) * 4);
     L.Wq = off;    off += up256(static_cast<size_t>(d_in) * d_out);
     L.sW = off;    off += up256(static_cast<size_t>(d_in) * 4);
-    L.wws = off;   off += up256(hlq::quant_cols_table_bytes(d_out, d_in, B));
+    L.wws = off;   off += up256(hlq::quant_cols_ws_bytes(d_out, d_in));
     // integer g_w list: column maxima of projected G (d_out words), then of projected X (d_in words),
     // right behind those of the weight so that one fill zeroes all three
     L.hws = off;   off += gwi ? up256(hlq::hla_quant_ws_bytes(d_out)) + up256(hlq::hla_quant_ws_bytes(d_in)) : 0;
@@ -505,8 +505,8 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     const void *Xh = Xc;
     const float *sXh = sXc;
     // The transforms that depend on nothing share launches when the shapes allow (k_front.hip): two
-    // for the default path (one when the weight has few row blocks or is not transformed here),
-    // three for the integer g_w list.  Very long rows of G and the mantissa-bit rounding keep one
+    // and pass 2 over the weight for the default path (one in all when the weight has few rows or
+    // is not transformed here), three for the integer g_w list.  Very long rows of G and the mantissa-bit rounding keep one
     // launch per stage.
     const bool fusable = hlq::front_fusable(O, B) && !mant;   // the fused launches carry the seeded rounding only
     const bool fused = !gwi && fusable;
@@ -549,23 +549,28 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
             sXh = sx;
         }
     }
-    // the table of per-row-block maxima of H^T W, when pass 1 rides in the one-launch front
-    int w_parts = 1;
+    // g_x stages 3-4, Q(H^T W) transposed: where the codes go, and whether the front launch made them
+    const uint64_t kw = stream_key(seed, 1);
+    int8_t *const wq = reinterpret_cast<int8_t *>(ws + L.Wq);
+    float *const sw = reinterpret_cast<float *>(ws + L.sW);
+    bool w_done = wc || fused_q || !dX;   // handed over by the caller, made by the fused launches above, or not needed
     if (fused) {
         uint16_t *xh = xc ? nullptr : reinterpret_cast<uint16_t *>(ws + L.XhatT);
         const hlq::FrontRows jr = hlq::front_rows(dX ? G : nullptr, N, O, B, static_cast<uint32_t>(kg),
                                                   static_cast<uint32_t>(kg >> 32), qmax, Gq, sG);
         const hlq::FrontHla jx = hlq::front_hla(dW && !xc ? X : nullptr, N, I, B, r, xh);
         const hlq::FrontHla jg = hlq::front_hla(dW ? G : nullptr, N, O, B, r, static_cast<uint16_t *>(Gh));
-        hlq::FrontAbsmax jw = hlq::front_absmax(dX && !wc ? W : nullptr, O, I, B, reinterpret_cast<uint32_t *>(ws + L.wws));
-        if (!jw.W || hlq::quant_cols_row_blocks(O, B) <= hlq::kFrontOneLaunchMaxParts) {
-            // no pass over W here (codes handed over, or dX not wanted), or few row blocks of W:
-            // everything in one launch, the maxima per row block
-            jw.partial = 1;
-            w_parts = jw.W ? jw.gy : 1;
-            rc = launch_rc(hlq::launch_front_one(jr, jx, jg, jw, conv, B, basis, f32, packed, st));
+        if (w_done || hlq::cols_full_ok(O, I, B, f32)) {
+            // no pass over W here, or a weight of few rows, which one workgroup per strip of columns
+            // quantises completely: everything independent in one launch
+            const hlq::FrontColsQ jq = hlq::front_cols_full(w_done ? nullptr : W, O, I, B, static_cast<uint32_t>(kw),
+                                                            static_cast<uint32_t>(kw >> 32), qmax, wq, sw);
+            rc = launch_rc(hlq::launch_front_one(jr, jx, jg, jq, conv, B, basis, f32, packed, st));
+            w_done = true;
         } else {
-            const hlq::FrontFill jf{reinterpret_cast<uint32_t *>(ws + L.wws), dX && !wc ? I : 0};
+            // pass 1 over W rides in the second launch, behind the zeroing of its maxima in the first
+            const hlq::FrontAbsmax jw = hlq::front_absmax(W, O, I, B, reinterpret_cast<uint32_t *>(ws + L.wws));
+            const hlq::FrontFill jf{reinterpret_cast<uint32_t *>(ws + L.wws), I};
             rc = launch_rc(hlq::launch_front(jr, jx, jf, jg, jw, conv, B, basis, f32, packed, st));
         }
         if (rc != HLQ_OK) return rc;
@@ -609,17 +614,11 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
             sXh = sx;
         }
     }
-    if (dX) {
-        // g_x stages 3-4: Q(H^T W), transposed
-        const uint64_t kw = stream_key(seed, 1);
-        int8_t *wq = reinterpret_cast<int8_t *>(ws + L.Wq);
-        float *sw = reinterpret_cast<float *>(ws + L.sW);
-        if (wc || fused_q)   // codes handed over by the caller, or made by the fused launches above
-            rc = HLQ_OK;
-        else if (fused)   // pass 1 ran in the second front launch
+    if (!w_done) {
+        if (fused)   // pass 1 ran in the second front launch
             rc = launch_rc(hlq::launch_quant_cols_pass2(W, O, I, B, f32, static_cast<uint32_t>(kw),
                                                         static_cast<uint32_t>(kw >> 32), qmax, packed, false, wq, sw,
-                                                        nullptr, ws + L.wws, w_parts, st));
+                                                        nullptr, ws + L.wws, st));
         else
             rc = launch_rc(hlq::launch_quant_cols(W, O, I, B, f32, static_cast<uint32_t>(kw),
                                                   static_cast<uint32_t>(kw >> 32), qmax, packed, mant, wq, sw, nullptr,

@@ -22,16 +22,15 @@ hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, ui
 
 // K1T split in its two passes, for callers that run pass 1 elsewhere (the fused front launches):
 // pass 2 alone, reading the column maxima pass 1 left in `ws`.
-// parts: rows of the table of maxima in ws ([parts][I]); 1 after the atomic pass 1.
 hipError_t launch_quant_cols_pass2(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
                                    float qmax, bool packed, bool mant, int8_t *WqT, float *sW, float *coeffT,
-                                   const void *ws, int parts, hipStream_t st);
-// Row blocks of pass 1 (= rows of a table of partial maxima), and the largest count for which the
-// whole front goes out as one launch (launch_front_one below).
-int quant_cols_row_blocks(int O, int B);
-// bytes of the maxima of the whole path: the table when the one-launch front applies, else one row
-size_t quant_cols_table_bytes(int64_t O, int64_t I, int B);
-constexpr int kFrontOneLaunchMaxParts = 8;
+                                   const void *ws, hipStream_t st);
+// The weights that one workgroup per strip of columns quantises completely, both passes, inside the
+// one-launch front (launch_front_one below): at most 64 row blocks (O / B; 64 groups of four lanes
+// take one each) and small enough to be found in the cache by the second pass.
+constexpr int kColsFullMaxRowBlocks = 64;
+constexpr int64_t kColsFullMaxBytes = 4 << 20;
+bool cols_full_ok(int O, int I, int B, bool is_f32);
 
 // Geometry of a convolution over channels-last tensors.  N = Nb * Ho * Wo rows of the column matrix.
 struct ConvShape {
@@ -71,7 +70,6 @@ struct FrontAbsmax { // pass 1 of K1T
     int O, I;
     uint32_t *amax;
     int gx, gy;
-    int partial;     // 1: each workgroup stores its maxima as row `by` of amax [gy][I] (no zeroing, no atomics)
 };
 struct FrontHlaQ {   // K3 + int8 quantisation of one tensor: pass 1 (amax) and pass 2 (codes) read the same fields
     const void *T;
@@ -105,9 +103,12 @@ bool front_fusable(int O, int B);
 FrontRows front_rows(const void *G, int64_t N, int O, int B, uint32_t k0, uint32_t k1, float qmax, int8_t *Gq, float *sG);
 FrontHla front_hla(const void *T, int64_t N, int D, int B, int r, uint16_t *out);
 FrontAbsmax front_absmax(const void *W, int O, int I, int B, uint32_t *amax);
-// K1(G) | K3(X) | K3(G) | pass 1 of K1T in ONE launch: jw.partial must be set (maxima per row block,
-// jw.gy <= kFrontOneLaunchMaxParts rows in jw.amax), so that nothing has to be zeroed beforehand.
-hipError_t launch_front_one(const FrontRows &jr, const FrontHla &jx, const FrontHla &jg, const FrontAbsmax &jw,
+// all of K1T for a weight that passes cols_full_ok: one workgroup per strip of columns (gy carries the
+// strip's width as a shift)
+FrontColsQ front_cols_full(const void *W, int O, int I, int B, uint32_t k0, uint32_t k1, float qmax, int8_t *WqT, float *sW);
+// K1(G) | K3(X) | K3(G) | all of K1T in ONE launch (jq from front_cols_full, or without a weight):
+// nothing has to be zeroed beforehand and no launch for pass 2 follows.
+hipError_t launch_front_one(const FrontRows &jr, const FrontHla &jx, const FrontHla &jg, const FrontColsQ &jq,
                             const ConvShape *conv, int B, int basis, bool is_f32, bool packed, hipStream_t st);
 // conv: NULL, or the geometry whose column matrix jx.T (an image) stands for; needs hla_conv_ok.
 hipError_t launch_front(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,

@@ -47,12 +47,19 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
     if (i < jf.n) jf.p[i] = 0u;
 }
 
-// The whole front in one launch, for weights with few row blocks: pass 1 of K1T leaves its maxima per
-// row block (no zeroing, hence no launch before it) and pass 2 reduces the few rows of that table.
+// The whole front in one launch, for weights of few rows: a workgroup per strip of columns runs both
+// passes of K1T (cols_full_body), so neither a zeroing launch before it nor a launch for pass 2 is needed.
+// (three wavefronts per SIMD asked for below B = 64, which the other jobs had before the strip quantiser
+// joined them: left alone, the register allocator spends all 256 registers on it)
 template <typename Tin, int B, bool PACKED, int BASIS, bool CONV>
-__global__ __launch_bounds__(256) void k_front_one(FrontRows jr, FrontHla jx, FrontHla jg, FrontAbsmax jw, FrontConv jc)
+__global__ __launch_bounds__(256, B == 64 ? 2 : 3) void k_front_one(FrontRows jr, FrontHla jx, FrontHla jg, FrontColsQ jq, FrontConv jc)
 {
     int b = blockIdx.x;
+    if (b < jq.gx) {       // first: these workgroups pass over their strip twice
+        cols_full_body<Tin, B, PACKED>(static_cast<const Tin *>(jq.W), jq.O, jq.I, jq.k0, jq.k1, jq.qmax, jq.WqT, jq.sW, b, jq.gy);
+        return;
+    }
+    b -= jq.gx;
     if (b < jr.blocks) {
         quant_rows_body<Tin, B, 256, PACKED>(static_cast<const Tin *>(jr.G), jr.N, jr.O, jr.T, jr.k0, jr.k1, jr.qmax, jr.Gq,
                                              jr.sG, nullptr, b);
@@ -68,12 +75,7 @@ __global__ __launch_bounds__(256) void k_front_one(FrontRows jr, FrontHla jx, Fr
         return;
     }
     b -= jx.gx * jx.gy;
-    if (b < jg.gx * jg.gy) {
-        hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.out, nullptr, b % jg.gx, b / jg.gx);
-        return;
-    }
-    b -= jg.gx * jg.gy;
-    cols_absmax_body<Tin, B>(static_cast<const Tin *>(jw.W), jw.O, jw.I, jw.amax, b % jw.gx, b / jw.gx, true);
+    hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.out, nullptr, b % jg.gx, b / jg.gx);
 }
 
 template <typename Tin, int B, int BASIS>
@@ -210,11 +212,29 @@ FrontHla front_hla(const void *T, int64_t N, int D, int B, int r, uint16_t *out)
 
 FrontAbsmax front_absmax(const void *W, int O, int I, int B, uint32_t *amax)
 {
-    FrontAbsmax j{W, O, I, amax, 0, 0, 0};
+    FrontAbsmax j{W, O, I, amax, 0, 0};
     if (!W) return j;
     const int cpl = 128 / B;
     j.gx = (I + 64 * cpl - 1) / (64 * cpl);
     j.gy = (O + 4 * B - 1) / (4 * B);
+    return j;
+}
+
+bool cols_full_ok(int O, int I, int B, bool is_f32)
+{
+    return O / B <= kColsFullMaxRowBlocks && static_cast<int64_t>(O) * I * (is_f32 ? 4 : 2) <= kColsFullMaxBytes;
+}
+
+FrontColsQ front_cols_full(const void *W, int O, int I, int B, uint32_t k0, uint32_t k1, float qmax, int8_t *WqT, float *sW)
+{
+    FrontColsQ j{W, O, I, nullptr, k0, k1, qmax, WqT, sW, 0, 0};
+    if (!W) return j;
+    // as many groups of lanes as there are row blocks, so that a pass is one round: 16, 32 or 64
+    const int nrb = O / B;
+    const int lg = nrb <= 16 ? 4 : (nrb <= 32 ? 3 : 2);
+    const int strip = (128 / B) << lg;
+    j.gx = (I + strip - 1) / strip;
+    j.gy = lg;
     return j;
 }
 
@@ -238,12 +258,12 @@ static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const 
 }
 
 template <typename Tin, int B, int BASIS>
-static hipError_t launch_front_one_t(const FrontRows &jr, const FrontHla &jx, const FrontHla &jg, const FrontAbsmax &jw,
+static hipError_t launch_front_one_t(const FrontRows &jr, const FrontHla &jx, const FrontHla &jg, const FrontColsQ &jq,
                                      const FrontConv &jc, bool packed, hipStream_t st)
 {
-    const int n = jr.blocks + jx.gx * jx.gy + jg.gx * jg.gy + jw.gx * jw.gy;
+    const int n = jq.gx + jr.blocks + jx.gx * jx.gy + jg.gx * jg.gy;
     if (n == 0) return hipSuccess;
-#define HLQ_FRONT_ONE(P, CV) hipLaunchKernelGGL((k_front_one<Tin, B, P, BASIS, CV>), dim3(n), dim3(256), 0, st, jr, jx, jg, jw, jc)
+#define HLQ_FRONT_ONE(P, CV) hipLaunchKernelGGL((k_front_one<Tin, B, P, BASIS, CV>), dim3(n), dim3(256), 0, st, jr, jx, jg, jq, jc)
     if (jc.on) {
         if (packed) HLQ_FRONT_ONE(true, true); else HLQ_FRONT_ONE(false, true);
     } else {
@@ -253,7 +273,7 @@ static hipError_t launch_front_one_t(const FrontRows &jr, const FrontHla &jx, co
     return hipGetLastError();
 }
 
-hipError_t launch_front_one(const FrontRows &jr, const FrontHla &jx, const FrontHla &jg, const FrontAbsmax &jw,
+hipError_t launch_front_one(const FrontRows &jr, const FrontHla &jx, const FrontHla &jg, const FrontColsQ &jq,
                             const ConvShape *conv, int B, int basis, bool is_f32, bool packed, hipStream_t st)
 {
     FrontConv jc{};
@@ -262,14 +282,14 @@ hipError_t launch_front_one(const FrontRows &jr, const FrontHla &jx, const Front
         jc.g = *conv;
         jc.on = 1;
     }
-    if (jw.W && (!jw.partial || jw.gy > kFrontOneLaunchMaxParts)) return hipErrorInvalidValue;
+    if (jq.W && (jq.O / B > kColsFullMaxRowBlocks || jq.gy < 2 || jq.gy > 4)) return hipErrorInvalidValue;
 #define HLQ_FRONT1_CASE(BB)                                                                     \
     case BB:                                                                                    \
         if (basis)                                                                              \
-            return is_f32 ? launch_front_one_t<float, BB, 1>(jr, jx, jg, jw, jc, packed, st)    \
-                          : launch_front_one_t<bf16_t, BB, 1>(jr, jx, jg, jw, jc, packed, st);  \
-        return is_f32 ? launch_front_one_t<float, BB, 0>(jr, jx, jg, jw, jc, packed, st)        \
-                      : launch_front_one_t<bf16_t, BB, 0>(jr, jx, jg, jw, jc, packed, st);
+            return is_f32 ? launch_front_one_t<float, BB, 1>(jr, jx, jg, jq, jc, packed, st)    \
+                          : launch_front_one_t<bf16_t, BB, 1>(jr, jx, jg, jq, jc, packed, st);  \
+        return is_f32 ? launch_front_one_t<float, BB, 0>(jr, jx, jg, jq, jc, packed, st)        \
+                      : launch_front_one_t<bf16_t, BB, 0>(jr, jx, jg, jq, jc, packed, st);
     switch (B) {
         HLQ_FRONT1_CASE(16)
         HLQ_FRONT1_CASE(32)

@@ -37,26 +37,15 @@ template <typename Tin, int B, bool PACKED, bool MANT>
 __global__ __launch_bounds__(256) void k_cols_quantize(const Tin *__restrict__ W, int O, int I,
                                                        const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
                                                        float qmax, int8_t *__restrict__ WqT, float *__restrict__ sW,
-                                                       float *__restrict__ coeffT, int parts)
+                                                       float *__restrict__ coeffT)
 {
-    cols_quantize_body<Tin, B, PACKED, MANT>(W, O, I, amax_bits, k0, k1, qmax, WqT, sW, coeffT, blockIdx.x, blockIdx.y,
-                                             parts);
+    cols_quantize_body<Tin, B, PACKED, MANT>(W, O, I, amax_bits, k0, k1, qmax, WqT, sW, coeffT, blockIdx.x, blockIdx.y);
 }
-
-int quant_cols_row_blocks(int O, int B) { return (O + 4 * B - 1) / (4 * B); }
 
 size_t quant_cols_ws_bytes(int64_t /*O*/, int64_t I)
 {
     // amax bit patterns, one uint32 per in-feature
     return (static_cast<size_t>(I) * 4 + 255) & ~static_cast<size_t>(255);
-}
-
-size_t quant_cols_table_bytes(int64_t O, int64_t I, int B)
-{
-    // the same per row block of pass 1, when there are few enough of those for the one-launch front
-    const int rb = quant_cols_row_blocks(static_cast<int>(O), B);
-    const size_t rows = rb <= kFrontOneLaunchMaxParts ? rb : 1;
-    return (static_cast<size_t>(I) * rows * 4 + 255) & ~static_cast<size_t>(255);
 }
 
 template <typename Tin, int B>
@@ -72,15 +61,14 @@ static hipError_t launch_cols_pass1_t(const void *W, int O, int I, void *ws, hip
 
 template <typename Tin, int B>
 static hipError_t launch_cols_pass2_t(const void *W, int O, int I, uint32_t k0, uint32_t k1, float qmax, bool packed,
-                                      bool mant, int8_t *WqT, float *sW, float *coeffT, const void *ws, int parts,
-                                      hipStream_t st)
+                                      bool mant, int8_t *WqT, float *sW, float *coeffT, const void *ws, hipStream_t st)
 {
     constexpr int CPL = 128 / B;
     const uint32_t *amax = static_cast<const uint32_t *>(ws);
     const Tin *w = static_cast<const Tin *>(W);
     dim3 grid((I + 64 * CPL - 1) / (64 * CPL), (O + 4 * B - 1) / (4 * B));
 #define HLQ_COLS2_LAUNCH(P, M) \
-    hipLaunchKernelGGL((k_cols_quantize<Tin, B, P, M>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, coeffT, parts)
+    hipLaunchKernelGGL((k_cols_quantize<Tin, B, P, M>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, coeffT)
     if (packed) {
         if (mant) HLQ_COLS2_LAUNCH(true, true); else HLQ_COLS2_LAUNCH(true, false);
     } else {
@@ -92,12 +80,12 @@ static hipError_t launch_cols_pass2_t(const void *W, int O, int I, uint32_t k0, 
 
 hipError_t launch_quant_cols_pass2(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
                                    float qmax, bool packed, bool mant, int8_t *WqT, float *sW, float *coeffT,
-                                   const void *ws, int parts, hipStream_t st)
+                                   const void *ws, hipStream_t st)
 {
 #define HLQ_COLS2_CASE(BB)                                                                                               \
     case BB:                                                                                                             \
-        return is_f32 ? launch_cols_pass2_t<float, BB>(W, O, I, k0, k1, qmax, packed, mant, WqT, sW, coeffT, ws, parts, st)     \
-                      : launch_cols_pass2_t<bf16_t, BB>(W, O, I, k0, k1, qmax, packed, mant, WqT, sW, coeffT, ws, parts, st);
+        return is_f32 ? launch_cols_pass2_t<float, BB>(W, O, I, k0, k1, qmax, packed, mant, WqT, sW, coeffT, ws, st)     \
+                      : launch_cols_pass2_t<bf16_t, BB>(W, O, I, k0, k1, qmax, packed, mant, WqT, sW, coeffT, ws, st);
     switch (B) {
         HLQ_COLS2_CASE(16)
         HLQ_COLS2_CASE(32)
@@ -123,7 +111,7 @@ hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, ui
     }
 #undef HLQ_COLS_CASE
     if (e != hipSuccess) return e;
-    return launch_quant_cols_pass2(W, O, I, B, is_f32, k0, k1, qmax, packed, mant, WqT, sW, coeffT, ws, 1, st);
+    return launch_quant_cols_pass2(W, O, I, B, is_f32, k0, k1, qmax, packed, mant, WqT, sW, coeffT, ws, st);
 }
 
 }  // namespace hlq

@@ -12,12 +12,12 @@ __device__ __forceinline__ void load_row_block(const Tin *base, int64_t pitch, f
     for (int j = 0; j < B; ++j) Loader<Tin, CPL>::load(base + j * pitch, v + j * CPL);
 }
 
-// `partial`: instead of merging into one maximum per column with an atomic (which needs the
-// maxima zeroed by an earlier launch), the workgroup stores its own maxima as row `by` of a
-// [row blocks of 4 B][I] table that pass 2 reduces; nothing needs zeroing then.
+// pass 1: one row block per wavefront; the four wavefronts' maxima meet in LDS and are merged
+// into one maximum per column with an atomic on the bit patterns (non-negative floats order like
+// their bit patterns), so the maxima must have been zeroed by an earlier launch.
 template <typename Tin, int B>
 __device__ __forceinline__ void cols_absmax_body(const Tin *__restrict__ W, int O, int I, uint32_t *__restrict__ amax_bits,
-                                                 int bx, int by, bool partial = false)
+                                                 int bx, int by)
 {
     constexpr int CPL = 128 / B;
     __shared__ float s_max[4][64 * CPL];
@@ -44,50 +44,21 @@ __device__ __forceinline__ void cols_absmax_body(const Tin *__restrict__ W, int 
     for (int idx = tid; idx < 64 * CPL; idx += 256) {
         const float m = fmaxf(fmaxf(s_max[0][idx], s_max[1][idx]), fmaxf(s_max[2][idx], s_max[3][idx]));
         const int col = bx * 64 * CPL + idx;
-        if (col >= I) continue;
-        if (partial) amax_bits[static_cast<int64_t>(by) * I + col] = __float_as_uint(m);
-        else if (m > 0.0f) atomicMax(amax_bits + col, __float_as_uint(m));
+        if (col < I && m > 0.0f) atomicMax(amax_bits + col, __float_as_uint(m));
     }
 }
 
-// pass 2: transform again, quantise against the column maxima, write the codes transposed.
+// One row block (B rows from o0) of CPL columns from col0: transform again, quantise against the
+// reciprocal scales `inv` of those columns, write the codes transposed.
 // PACKED: the codes are written two to a byte (4-bit codes only), O/2 bytes per row of WqT.
-// `parts`: rows of the table of maxima ([parts][I]; 1 = the merged maxima of the atomic pass 1).
-template <typename Tin, int B, bool PACKED, bool MANT = false>
-__device__ __forceinline__ void cols_quantize_body(const Tin *__restrict__ W, int O, int I,
-                                                   const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
-                                                   float qmax, int8_t *__restrict__ WqT, float *__restrict__ sW,
-                                                   float *__restrict__ coeffT, int bx, int by, int parts = 1)
+template <typename Tin, int B, bool PACKED, bool MANT>
+__device__ __forceinline__ void cols_quantize_block(const Tin *__restrict__ W, int O, int I, const float *inv, uint32_t k0,
+                                                    uint32_t k1, int8_t *__restrict__ WqT, float *__restrict__ coeffT,
+                                                    int col0, int o0)
 {
     constexpr int CPL = 128 / B;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int col0 = (bx * 64 + lane) * CPL;
-    const int o0 = (by * 4 + wave) * B;
-    if (col0 >= I || o0 >= O) return;
-
     float v[B * CPL];
     load_row_block<Tin, B, CPL>(W + static_cast<int64_t>(o0) * I + col0, I, v);
-    // column maxima: CPL adjacent words per table row, read as vectors; non-negative floats order
-    // like their bit patterns
-    uint32_t abits[CPL];
-    {
-        typedef uint32_t uvec __attribute__((ext_vector_type(CPL)));
-        uvec m = *reinterpret_cast<const uvec *>(amax_bits + col0);
-        for (int p = 1; p < parts; ++p) {
-            const uvec q = *reinterpret_cast<const uvec *>(amax_bits + static_cast<int64_t>(p) * I + col0);
-#pragma unroll
-            for (int c = 0; c < CPL; ++c) m[c] = max(m[c], q[c]);
-        }
-#pragma unroll
-        for (int c = 0; c < CPL; ++c) abits[c] = m[c];
-    }
-    float inv[CPL];
-#pragma unroll
-    for (int c = 0; c < CPL; ++c) {
-        const float a = __uint_as_float(abits[c]);
-        inv[c] = absmax_to_inv(a, qmax);
-        if (o0 == 0) sW[col0 + c] = absmax_to_scale(a, qmax);
-    }
 #pragma unroll
     for (int c = 0; c < CPL; ++c) {
         fwht_regs<B, CPL>(v + c);
@@ -116,6 +87,78 @@ __device__ __forceinline__ void cols_quantize_body(const Tin *__restrict__ W, in
                     make_float4(v[j * CPL + c], v[(j + 1) * CPL + c], v[(j + 2) * CPL + c], v[(j + 3) * CPL + c]);
         }
     }
+}
+
+// pass 2: one row block per wavefront against the column maxima that pass 1 merged.
+template <typename Tin, int B, bool PACKED, bool MANT = false>
+__device__ __forceinline__ void cols_quantize_body(const Tin *__restrict__ W, int O, int I,
+                                                   const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
+                                                   float qmax, int8_t *__restrict__ WqT, float *__restrict__ sW,
+                                                   float *__restrict__ coeffT, int bx, int by)
+{
+    constexpr int CPL = 128 / B;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int col0 = (bx * 64 + lane) * CPL;
+    const int o0 = (by * 4 + wave) * B;
+    if (col0 >= I || o0 >= O) return;
+    float inv[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        const float a = __uint_as_float(amax_bits[col0 + c]);
+        inv[c] = absmax_to_inv(a, qmax);
+        if (o0 == 0) sW[col0 + c] = absmax_to_scale(a, qmax);
+    }
+    cols_quantize_block<Tin, B, PACKED, MANT>(W, O, I, inv, k0, k1, WqT, coeffT, col0, o0);
+}
+
+// Both passes by one workgroup, for a weight of few rows: the workgroup owns a strip of LG * CPL
+// columns over all of O (LG = 1 << lg lanes side by side: 16, 8 or 4), its 256 / LG groups of
+// lanes take a row block each per round, the maxima meet in LDS, and the second pass finds the
+// rows in the cache.  No other workgroup is waited for, so this can ride in a launch with anything.
+template <typename Tin, int B, bool PACKED>
+__device__ __forceinline__ void cols_full_body(const Tin *__restrict__ W, int O, int I, uint32_t k0, uint32_t k1, float qmax,
+                                               int8_t *__restrict__ WqT, float *__restrict__ sW, int bx, int lg)
+{
+    constexpr int CPL = 128 / B;
+    __shared__ float s_strip[256 * CPL];      // [group][lane of the group][column of the lane]
+    const int tid = threadIdx.x, grp = tid >> lg, sub = tid & ((1 << lg) - 1), groups = 256 >> lg;
+    const int col0 = ((bx << lg) + sub) * CPL;
+    const int nrb = O / B;
+    float cmax[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) cmax[c] = 0.0f;
+    if (col0 < I) {
+#pragma nounroll
+        for (int rb = grp; rb < nrb; rb += groups) {
+            float v[B * CPL];
+            load_row_block<Tin, B, CPL>(W + static_cast<int64_t>(rb) * B * I + col0, I, v);
+#pragma unroll
+            for (int c = 0; c < CPL; ++c) {
+                fwht_regs<B, CPL>(v + c);
+#pragma unroll
+                for (int j = 0; j < B; ++j) cmax[c] = fmaxf(cmax[c], fabsf(v[j * CPL + c]));
+            }
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) s_strip[tid * CPL + c] = cmax[c];
+    __syncthreads();
+    if (col0 >= I) return;
+    // a few groups at a time: all of them in flight would cost CPL registers each
+#pragma unroll 2
+    for (int g = 0; g < groups; ++g) {
+#pragma unroll
+        for (int c = 0; c < CPL; ++c) cmax[c] = fmaxf(cmax[c], s_strip[((g << lg) + sub) * CPL + c]);
+    }
+    float inv[CPL];
+#pragma unroll
+    for (int c = 0; c < CPL; ++c) {
+        inv[c] = absmax_to_inv(cmax[c], qmax);
+        if (grp == 0) sW[col0 + c] = absmax_to_scale(cmax[c], qmax);
+    }
+#pragma nounroll
+    for (int rb = grp; rb < nrb; rb += groups)
+        cols_quantize_block<Tin, B, PACKED, false>(W, O, I, inv, k0, k1, WqT, nullptr, col0, rb * B);
 }
 
 }  // namespace hlq
