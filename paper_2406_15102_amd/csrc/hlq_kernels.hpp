@@ -26,10 +26,11 @@ hipError_t launch_quant_cols_pass2(const void *W, int O, int I, int B, bool is_f
                                    float qmax, bool packed, bool mant, int8_t *WqT, float *sW, float *coeffT,
                                    const void *ws, hipStream_t st);
 // The weights that one workgroup per strip of columns quantises completely, both passes, inside the
-// one-launch front (launch_front_one below): at most 64 row blocks (O / B; 64 groups of four lanes
-// take one each) and small enough to be found in the cache by the second pass.
-constexpr int kColsFullMaxRowBlocks = 64;
-constexpr int64_t kColsFullMaxBytes = 4 << 20;
+// one-launch front (launch_front_one below): at most 256 row blocks (O / B; 64 groups of four lanes
+// take one each per round, so four rounds a pass) and small enough for the second pass to find
+// them in the cache.  Measured: a gain up to these sizes, none at 13-20 MB, a loss beyond.
+constexpr int kColsFullMaxRowBlocks = 256;
+constexpr int64_t kColsFullMaxBytes = 8 << 20;
 bool cols_full_ok(int O, int I, int B, bool is_f32);
 
 // Geometry of a convolution over channels-last tensors.  N = Nb * Ho * Wo rows of the column matrix.

@@ -229,7 +229,7 @@ FrontColsQ front_cols_full(const void *W, int O, int I, int B, uint32_t k0, uint
 {
     FrontColsQ j{W, O, I, nullptr, k0, k1, qmax, WqT, sW, 0, 0};
     if (!W) return j;
-    // as many groups of lanes as there are row blocks, so that a pass is one round: 16, 32 or 64
+    // as many groups of lanes as there are row blocks, so that a pass is one round where it can be: 16, 32 or 64
     const int nrb = O / B;
     const int lg = nrb <= 16 ? 4 : (nrb <= 32 ? 3 : 2);
     const int strip = (128 / B) << lg;

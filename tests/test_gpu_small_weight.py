@@ -2,8 +2,8 @@
 workgroup per strip of columns.  The codes must be those of the stand-alone stage (two passes, many
 workgroups), which the bit-exact parity tests pin to the oracle: the path given those codes returns
 the same bits as the path that makes its own.  Shapes cover the three strip widths (up to 16, 32, 64
-row blocks), ragged last strips, every block order, both dtypes, both code storages, and weights just
-past either limit, which take the other route."""
+row blocks a round), several rounds, ragged last strips and rounds, every block order, both dtypes,
+both code storages, and weights just past either limit, which take the other route."""
 import numpy as np
 import pytest
 import torch
@@ -23,13 +23,16 @@ CASES = [
     (256, 264, 272, 16, 4, "f32"),      # 17: strips of 8 lanes
     (512, 200, 512, 16, 8, "bf16"),     # 32
     (256, 136, 528, 16, 8, "bf16"),     # 33: strips of 4 lanes
-    (256, 104, 1024, 16, 8, "f32"),     # 64: the limit
-    (256, 104, 1040, 16, 8, "bf16"),    # 65: past it
+    (256, 104, 1024, 16, 8, "f32"),     # 64: one full round
+    (256, 104, 1040, 16, 8, "bf16"),    # 65: a second round of one
+    (256, 40, 2080, 16, 8, "bf16"),     # 130: three rounds
+    (128, 72, 4096, 16, 8, "f32"),      # 256: the limit
+    (128, 72, 4112, 16, 8, "bf16"),     # 257: past it
     (256, 520, 1024, 32, 8, "bf16"),    # B = 32, 32 row blocks
     (256, 40, 2048, 32, 16, "f32"),     # B = 32, 64 row blocks
     (256, 264, 1024, 64, 32, "bf16"),   # B = 64, 16 row blocks
     (128, 72, 4096, 64, 8, "bf16"),     # B = 64, 64 row blocks
-    (128, 4104, 512, 16, 8, "bf16"),    # 4.2 MB: past the size limit
+    (128, 8200, 512, 16, 8, "bf16"),    # 8.4 MB: past the size limit
 ]
 
 
