@@ -466,8 +466,9 @@ static int backward_check(const void *G, const void *X, const void *Xc, const fl
 static int backward_impl(const void *G, const void *X, const void *Xc, const float *sXc, const void *W, const void *Wc,
                          const float *sWc, int64_t N, int64_t d_in, int64_t d_out, int B, int r, uint64_t seed, int dtype,
                          int flags, void *dX, void *dW, void *workspace, size_t workspace_bytes, void *stream,
-                         const hlq::ConvShape *conv = nullptr)
+                         const hlq::ConvShape *conv = nullptr, hlq::SplitReduce *defer = nullptr)
 {
+    if (defer) defer->blocks = 0;
     int rc;
     if ((rc = backward_check(G, X, Xc, sXc, W, Wc, sWc, N, d_in, d_out, B, r, dtype, flags, dX, dW)) != HLQ_OK) return rc;
     const bool gwi = (flags & HLQ_FLAG_GW_INT8) != 0;
@@ -633,7 +634,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
                      L.gws_bytes};
     const int kind_x = packed ? 2 : 0, kind_w = gwi ? 0 : 1;
     if (dX && dW && !(flags & HLQ_FLAG_SEPARATE_PRODUCTS) && hlq::gemm_pair_available(kind_x, ax, kind_w, aw))
-        return launch_rc(hlq::launch_gemm_pair(kind_x, ax, kind_w, aw, st));
+        return launch_rc(hlq::launch_gemm_pair(kind_x, ax, kind_w, aw, st, defer));
     if (dX && (rc = launch_rc(hlq::launch_gemm_nt(kind_x, ax, st))) != HLQ_OK) return rc;
     if (dW && (rc = launch_rc(hlq::launch_gemm_nt(kind_w, aw, st))) != HLQ_OK) return rc;
     return HLQ_OK;
@@ -858,10 +859,14 @@ int hlq_conv2d_backward(const void *G, const void *X, const void *Wt, const hlq_
         }
         if (dX) dxmat = ws + L.dcols;
     }
+    const bool fold = !L.pointwise && dX;
+    hlq::SplitReduce red{};
     rc = backward_impl(G, dW ? xmat : nullptr, nullptr, nullptr, dX ? Wt : nullptr, nullptr, nullptr, c.N, I, g->O, B, r,
-                       seed, dtype, flags, dxmat, dW, ws + L.inner, L.inner_bytes, stream, L.implicit ? &c : nullptr);
+                       seed, dtype, flags, dxmat, dW, ws + L.inner, L.inner_bytes, stream, L.implicit ? &c : nullptr,
+                       fold ? &red : nullptr);
     if (rc != HLQ_OK) return rc;
-    if (!L.pointwise && dX) return launch_rc(hlq::launch_col2im(dxmat, c, f32, dX, st));
+    // the fold, and in the same launch the reduction that the weight gradient's product left to do, if any
+    if (fold) return launch_rc(hlq::launch_col2im(dxmat, c, f32, dX, st, &red));
     return HLQ_OK;
 }
 

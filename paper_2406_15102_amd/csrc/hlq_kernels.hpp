@@ -145,12 +145,26 @@ struct GemmArgs {
 };
 hipError_t launch_gemm_nt(int kind, const GemmArgs &a, hipStream_t st);
 hipError_t launch_splitk_reduce(int kind, const GemmArgs &a, int splits, hipStream_t st);
+// The same reduction as a job description, for a later launch of the caller's that carries it
+// beside its own work (the fold of a convolution): `blocks` workgroups of 256 threads, 0 = none.
+struct SplitReduce {
+    const int32_t *partial;
+    int splits, M, N;
+    const float *sA, *sB;
+    float alpha;
+    void *C;
+    int kind, c_is_f32;
+    int blocks;
+};
+SplitReduce splitk_reduce_job_of(int kind, const GemmArgs &a, int splits);
 // K2 | K4 in one launch (k_gemm_pair.hip): product `a` of kind 2 and product `b` of kind 1, both
 // with a scaled output of the same dtype.  Only b's k may be split (b.ws).  gemm_pair_available
 // says whether the combination is built; the results are those of two launch_gemm_nt calls up to
 // the summation order of b's k splits.
 bool gemm_pair_available(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b);
-hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, hipStream_t st);
+// defer: if not null and b's k is split, the reduction is not launched but described there (blocks > 0).
+hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, hipStream_t st,
+                            SplitReduce *defer = nullptr);
 // split-k scratch (b.ws) that the pair's plan would use if it may have up to `cap` bytes; only the
 // shapes and kinds of a and b are read
 size_t gemm_pair_ws_bytes(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, size_t cap);
@@ -162,7 +176,9 @@ size_t gemm_ws_bytes(int kind, int M, int N, int K);
 // x [Nb, H, W, C] -> cols [N, kh*kw*C], columns ordered (ky, kx, c), zero padding
 hipError_t launch_im2col(const void *X, const ConvShape &g, bool is_f32, void *cols, hipStream_t st);
 // cols [N, kh*kw*C] -> dx [Nb, H, W, C]: each pixel sums the entries copied from it (fp32, fixed order)
-hipError_t launch_col2im(const void *cols, const ConvShape &g, bool is_f32, void *dx, hipStream_t st);
+// red: NULL, or a split-K reduction (independent of the fold) that the first red->blocks workgroups run
+hipError_t launch_col2im(const void *cols, const ConvShape &g, bool is_f32, void *dx, hipStream_t st,
+                         const SplitReduce *red = nullptr);
 
 // K3 / K3q on the column matrix of X [Nb, H, W, C] without storing it: same outputs as launch_hla /
 // launch_hla_quant on launch_im2col's result, D = kh*kw*C.  Needs hla_conv_ok (C a multiple of the

@@ -15,6 +15,7 @@
 // image row, so that even small feature maps make thousands of wavefronts.
 #include "hlq_device.hpp"
 #include "hlq_kernels.hpp"
+#include "reduce_body.hpp"
 
 namespace hlq {
 
@@ -87,10 +88,16 @@ template <> struct Chan<float> {
 // together.  A tap that no output position pairs with this pixel loads from row 0 of the column
 // matrix instead (always inside the tensor) and is not added.
 template <typename T, bool VECTOR, int KS>
-__global__ __launch_bounds__(256) void k_col2im(const T *__restrict__ cols, ConvShape g, int chunks, T *__restrict__ dx)
+__global__ __launch_bounds__(256) void k_col2im(const T *__restrict__ cols, ConvShape g, int chunks, T *__restrict__ dx,
+                                                SplitReduce red)
 {
     constexpr int VEC = VECTOR ? Chan<T>::VEC : 1;
-    const int64_t wid = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
+    // a side job that shares the launch: the split-K reduction of the weight gradient's product
+    if (blockIdx.x < static_cast<unsigned>(red.blocks)) {
+        splitk_reduce_job(red, blockIdx.x);
+        return;
+    }
+    const int64_t wid = static_cast<int64_t>(blockIdx.x - red.blocks) * 4 + (threadIdx.x >> 6);
     const int64_t rowi = wid / chunks;
     if (rowi >= static_cast<int64_t>(g.Nb) * g.H) return;
     const int chunk = static_cast<int>(wid - rowi * chunks);
@@ -143,29 +150,31 @@ hipError_t launch_im2col(const void *X, const ConvShape &g, bool is_f32, void *c
 }
 
 template <typename T>
-static hipError_t launch_col2im_t(const void *cols, const ConvShape &g, void *dx, hipStream_t st)
+static hipError_t launch_col2im_t(const void *cols, const ConvShape &g, void *dx, hipStream_t st, const SplitReduce &red)
 {
     const T *c = static_cast<const T *>(cols);
     T *o = static_cast<T *>(dx);
     const bool vec = g.C % Chan<T>::VEC == 0;
     const int chunks = (g.W * (vec ? g.C / Chan<T>::VEC : g.C) + 63) / 64;
     const int64_t waves = static_cast<int64_t>(g.Nb) * g.H * chunks;
-    if (waves + 3 >= (int64_t(1) << 33)) return hipErrorInvalidValue;
-    const dim3 grid(static_cast<unsigned>((waves + 3) / 4));
+    if (waves + 3 >= (int64_t(1) << 33) || red.blocks < 0 || red.blocks > (1 << 28)) return hipErrorInvalidValue;
+    const dim3 grid(static_cast<unsigned>((waves + 3) / 4 + red.blocks));
     const bool k3 = g.kh == 3 && g.kw == 3;
     if (vec) {
-        if (k3) hipLaunchKernelGGL((k_col2im<T, true, 3>), grid, dim3(256), 0, st, c, g, chunks, o);
-        else hipLaunchKernelGGL((k_col2im<T, true, 0>), grid, dim3(256), 0, st, c, g, chunks, o);
+        if (k3) hipLaunchKernelGGL((k_col2im<T, true, 3>), grid, dim3(256), 0, st, c, g, chunks, o, red);
+        else hipLaunchKernelGGL((k_col2im<T, true, 0>), grid, dim3(256), 0, st, c, g, chunks, o, red);
     } else {
-        if (k3) hipLaunchKernelGGL((k_col2im<T, false, 3>), grid, dim3(256), 0, st, c, g, chunks, o);
-        else hipLaunchKernelGGL((k_col2im<T, false, 0>), grid, dim3(256), 0, st, c, g, chunks, o);
+        if (k3) hipLaunchKernelGGL((k_col2im<T, false, 3>), grid, dim3(256), 0, st, c, g, chunks, o, red);
+        else hipLaunchKernelGGL((k_col2im<T, false, 0>), grid, dim3(256), 0, st, c, g, chunks, o, red);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_col2im(const void *cols, const ConvShape &g, bool is_f32, void *dx, hipStream_t st)
+hipError_t launch_col2im(const void *cols, const ConvShape &g, bool is_f32, void *dx, hipStream_t st, const SplitReduce *red)
 {
-    return is_f32 ? launch_col2im_t<float>(cols, g, dx, st) : launch_col2im_t<bf16_t>(cols, g, dx, st);
+    const SplitReduce none{};
+    const SplitReduce &job = red ? *red : none;
+    return is_f32 ? launch_col2im_t<float>(cols, g, dx, st, job) : launch_col2im_t<bf16_t>(cols, g, dx, st, job);
 }
 
 }  // namespace hlq

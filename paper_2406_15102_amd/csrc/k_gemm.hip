@@ -3,6 +3,7 @@
 // plan (tile size, k splits) and the host-side dispatch over the template arguments.
 #include "gemm_body.hpp"
 #include "gemm_plan.hpp"
+#include "reduce_body.hpp"
 
 namespace hlq {
 
@@ -12,37 +13,13 @@ __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
     gemm_tile<KIND, WM, WN, KCH, TAIL, OUT>(g, static_cast<int>(blockIdx.x));
 }
 
-// ---- split-K: sum of the partial accumulators, then the same scaling as the direct epilogue -------
-// Partials are summed in split order (integers exactly, floats in a fixed order): deterministic.
+// ---- split-K: the reduction of the partial accumulators as a kernel of its own (reduce_body.hpp) ----
 template <int KIND, bool F32>
 __global__ __launch_bounds__(256) void k_splitk_reduce(const int32_t *__restrict__ partial, int splits, int M, int N,
                                                        const float *__restrict__ sA, const float *__restrict__ sB,
                                                        float alpha, void *__restrict__ C)
 {
-    const int64_t e = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * 4;
-    const int64_t total = static_cast<int64_t>(M) * N;
-    if (e >= total) return;
-    const int m = static_cast<int>(e / N), n = static_cast<int>(e % N);
-    f32x4 o;
-    if (KIND == 0) {
-        v4i sum = {0, 0, 0, 0};
-        for (int z = 0; z < splits; ++z) sum += *reinterpret_cast<const v4i *>(partial + z * total + e);
-        const float sa = sA ? sA[m] : 1.0f;
-        f32x4 cs = {alpha, alpha, alpha, alpha};
-        if (sB) cs = *reinterpret_cast<const f32x4 *>(sB + n) * alpha;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) o[k] = static_cast<float>(sum[k]) * (sa * cs[k]);
-    } else {
-        f32x4 sum = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (int z = 0; z < splits; ++z) sum += *reinterpret_cast<const f32x4 *>(partial + z * total + e);
-        o = sum * alpha;
-    }
-    if (F32) {
-        *reinterpret_cast<f32x4 *>(static_cast<float *>(C) + e) = o;
-    } else {
-        u32x2 p = {pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
-        *reinterpret_cast<u32x2 *>(static_cast<bf16_t *>(C) + e) = p;
-    }
+    splitk_reduce_body<KIND, F32>(partial, splits, M, N, sA, sB, alpha, C, blockIdx.x);
 }
 
 // `nk` = k steps of the product (128 B of k per operand row);
@@ -79,6 +56,13 @@ size_t gemm_ws_bytes(int kind, int M, int N, int K)
 {
     const GemmPlan p = plan_for(kind, M, N, K, ~static_cast<size_t>(0), true);
     return p.splits > 1 ? static_cast<size_t>(p.splits) * M * N * 4 : 0;
+}
+
+SplitReduce splitk_reduce_job_of(int kind, const GemmArgs &a, int splits)
+{
+    const int64_t quads = (static_cast<int64_t>(a.M) * a.N + 3) / 4;
+    return SplitReduce{static_cast<const int32_t *>(a.ws), splits, a.M, a.N, a.sA, a.sB, a.alpha, a.C, kind, a.c_is_f32 ? 1 : 0,
+                       static_cast<int>((quads + 255) / 256)};
 }
 
 // kind 0: int32 partials (the two integer products), kind 1: fp32 partials

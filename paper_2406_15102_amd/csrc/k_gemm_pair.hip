@@ -124,8 +124,9 @@ bool gemm_pair_available(int kindA, const GemmArgs &a, int kindB, const GemmArgs
            a.c_is_f32 == b.c_is_f32 && blocks < (int64_t(1) << 30);
 }
 
-hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, hipStream_t st)
+hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, hipStream_t st, SplitReduce *defer)
 {
+    if (defer) defer->blocks = 0;
     if (!gemm_pair_available(kindA, a, kindB, b)) return hipErrorInvalidValue;
     const bool can_split = b.ws != nullptr && (reinterpret_cast<uintptr_t>(b.ws) & 15) == 0;
     const PairPlan p = plan_pair(a, kindA, b, kindB, can_split ? b.ws_bytes : 0);
@@ -140,6 +141,10 @@ hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmA
         e = kindB == 1 ? launch_pair_01(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st)
                        : launch_pair_00(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st);
     if (e != hipSuccess || p.splitsB == 1) return e;
+    if (defer) {
+        *defer = splitk_reduce_job_of(kindB == 1 ? 1 : 0, b, p.splitsB);
+        return hipSuccess;
+    }
     return launch_splitk_reduce(kindB == 1 ? 1 : 0, b, p.splitsB, st);
 }
 
