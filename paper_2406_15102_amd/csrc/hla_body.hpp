@@ -57,6 +57,16 @@ template <typename Tin> struct ConvRows {
     }
 };
 
+// Workgroup l of a K3 job -> (column strip bx, group of four token blocks by): grp consecutive by of
+// one strip on one XCD (l mod 8), one after the other.  by may come out past the last group: the
+// bodies return for those.
+__device__ __forceinline__ void hla_job_map(int l, int gx, int grp, int &bx, int &by)
+{
+    const int t = l >> 3, u = (l & 7) + 8 * (t / grp);
+    bx = u % gx;
+    by = grp * (u / gx) + t % grp;
+}
+
 template <int B, int BASIS, typename Src>
 __device__ __forceinline__ void hla_body_src(const Src &src, int64_t N, int D, int r, bf16_t *__restrict__ ThatT,
                                              float *__restrict__ coeffT, int bx, int by)

@@ -56,8 +56,21 @@ struct FrontHla {    // K3 on one tensor
     int64_t N;
     int D, r;
     uint16_t *out;
-    int gx, gy;
+    int gx, gy;      // column strips, groups of four token blocks
+    int grp, nb;     // hla_job_map's grouping and the workgroups it needs (>= gx * gy)
 };
+// Order of the workgroups of a K3 job.  A workgroup writes 8 r bytes of each of its output rows and
+// the workgroup of the next `by` the 8 r bytes after them; workgroups go round-robin to the eight
+// XCDs (index mod 8), each with its own L2.  hla_job_map (hla_body.hpp) keeps `grp` consecutive
+// `by` of one strip on one XCD, back to back, so that their pieces meet in that L2 and leave it as
+// whole 128-byte lines (measured, cold inputs: G of 4096 x 11008, 22 strips, 51.6 -> 42.5 us; no change
+// where the strips are a multiple of 8, which gives the same placement by itself).
+inline int hla_job_grp(int r) { return r >= 8 ? 2 : (r == 4 ? 4 : 8); }
+inline int hla_job_blocks(int gx, int gy, int grp)
+{
+    const int units = gx * ((gy + grp - 1) / grp);
+    return 8 * grp * ((units + 7) / 8);
+}
 struct FrontConv {   // on: the K3(X) job of front A reads the column matrix of an image (jx.T = the image)
     ConvShape g;
     int on;

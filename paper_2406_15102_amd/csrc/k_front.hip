@@ -34,15 +34,16 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
         return;
     }
     b -= jr.blocks;
-    if (b < jx.gx * jx.gy) {
+    if (b < jx.nb) {
+        int bx, by;
+        hla_job_map(b, jx.gx, jx.grp, bx, by);
         if (CONV)
-            hla_body_src<B, BASIS>(ConvRows<Tin>{static_cast<const Tin *>(jx.T), jc.g}, jx.N, jx.D, jx.r, jx.out, nullptr,
-                                   b % jx.gx, b / jx.gx);
+            hla_body_src<B, BASIS>(ConvRows<Tin>{static_cast<const Tin *>(jx.T), jc.g}, jx.N, jx.D, jx.r, jx.out, nullptr, bx, by);
         else
-            hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, b % jx.gx, b / jx.gx);
+            hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, bx, by);
         return;
     }
-    b -= jx.gx * jx.gy;
+    b -= jx.nb;
     const int i = b * 256 + threadIdx.x;
     if (i < jf.n) jf.p[i] = 0u;
 }
@@ -66,27 +67,32 @@ __global__ __launch_bounds__(256, B == 64 ? 2 : 3) void k_front_one(FrontRows jr
         return;
     }
     b -= jr.blocks;
-    if (b < jx.gx * jx.gy) {
+    if (b < jx.nb) {
+        int bx, by;
+        hla_job_map(b, jx.gx, jx.grp, bx, by);
         if (CONV)
-            hla_body_src<B, BASIS>(ConvRows<Tin>{static_cast<const Tin *>(jx.T), jc.g}, jx.N, jx.D, jx.r, jx.out, nullptr,
-                                   b % jx.gx, b / jx.gx);
+            hla_body_src<B, BASIS>(ConvRows<Tin>{static_cast<const Tin *>(jx.T), jc.g}, jx.N, jx.D, jx.r, jx.out, nullptr, bx, by);
         else
-            hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, b % jx.gx, b / jx.gx);
+            hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, bx, by);
         return;
     }
-    b -= jx.gx * jx.gy;
-    hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.out, nullptr, b % jg.gx, b / jg.gx);
+    b -= jx.nb;
+    int bx, by;
+    hla_job_map(b, jg.gx, jg.grp, bx, by);
+    hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.out, nullptr, bx, by);
 }
 
 template <typename Tin, int B, int BASIS>
 __global__ __launch_bounds__(256) void k_front_b(FrontHla jg, FrontAbsmax jw)
 {
     int b = blockIdx.x;
-    if (b < jg.gx * jg.gy) {
-        hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.out, nullptr, b % jg.gx, b / jg.gx);
+    if (b < jg.nb) {
+        int bx, by;
+        hla_job_map(b, jg.gx, jg.grp, bx, by);
+        hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.out, nullptr, bx, by);
         return;
     }
-    b -= jg.gx * jg.gy;
+    b -= jg.nb;
     cols_absmax_body<Tin, B>(static_cast<const Tin *>(jw.W), jw.O, jw.I, jw.amax, b % jw.gx, b / jw.gx);
 }
 
@@ -202,11 +208,13 @@ FrontRows front_rows(const void *G, int64_t N, int O, int B, uint32_t k0, uint32
 
 FrontHla front_hla(const void *T, int64_t N, int D, int B, int r, uint16_t *out)
 {
-    FrontHla j{T, N, D, r, out, 0, 0};
+    FrontHla j{T, N, D, r, out, 0, 0, 1, 0};
     if (!T) return j;
     const int cpl = 128 / B;
     j.gx = (D + 64 * cpl - 1) / (64 * cpl);
     j.gy = static_cast<int>((N / B + 3) / 4);
+    j.grp = hla_job_grp(r);
+    j.nb = hla_job_blocks(j.gx, j.gy, j.grp);
     return j;
 }
 
@@ -242,7 +250,7 @@ template <typename Tin, int B, int BASIS>
 static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
                                  const FrontAbsmax &jw, const FrontConv &jc, bool packed, hipStream_t st)
 {
-    const int na = jr.blocks + jx.gx * jx.gy + (jf.n + 255) / 256;
+    const int na = jr.blocks + jx.nb + (jf.n + 255) / 256;
     if (na > 0) {
 #define HLQ_FRONT_A(P, CV) hipLaunchKernelGGL((k_front_a<Tin, B, P, BASIS, CV>), dim3(na), dim3(256), 0, st, jr, jx, jf, jc)
         if (jc.on) {
@@ -252,7 +260,7 @@ static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const 
         }
 #undef HLQ_FRONT_A
     }
-    const int nb = jg.gx * jg.gy + jw.gx * jw.gy;
+    const int nb = jg.nb + jw.gx * jw.gy;
     if (nb > 0) hipLaunchKernelGGL((k_front_b<Tin, B, BASIS>), dim3(nb), dim3(256), 0, st, jg, jw);
     return hipGetLastError();
 }
@@ -261,7 +269,7 @@ template <typename Tin, int B, int BASIS>
 static hipError_t launch_front_one_t(const FrontRows &jr, const FrontHla &jx, const FrontHla &jg, const FrontColsQ &jq,
                                      const FrontConv &jc, bool packed, hipStream_t st)
 {
-    const int n = jq.gx + jr.blocks + jx.gx * jx.gy + jg.gx * jg.gy;
+    const int n = jq.gx + jr.blocks + jx.nb + jg.nb;
     if (n == 0) return hipSuccess;
 #define HLQ_FRONT_ONE(P, CV) hipLaunchKernelGGL((k_front_one<Tin, B, P, BASIS, CV>), dim3(n), dim3(256), 0, st, jr, jx, jg, jq, jc)
     if (jc.on) {

@@ -18,9 +18,11 @@ namespace hlq {
 
 template <typename Tin, int B, int BASIS>
 __global__ __launch_bounds__(256) void k_hla(const Tin *__restrict__ T, int64_t N, int D, int r,
-                                             bf16_t *__restrict__ ThatT, float *__restrict__ coeffT)
+                                             bf16_t *__restrict__ ThatT, float *__restrict__ coeffT, int gx, int grp)
 {
-    hla_body<Tin, B, BASIS>(T, N, D, r, ThatT, coeffT, blockIdx.x, blockIdx.y);
+    int bx, by;
+    hla_job_map(static_cast<int>(blockIdx.x), gx, grp, bx, by);
+    hla_body<Tin, B, BASIS>(T, N, D, r, ThatT, coeffT, bx, by);
 }
 
 template <typename Tin, int B>
@@ -28,11 +30,13 @@ static hipError_t launch_hla_t(const void *T, int64_t N, int D, int r, int basis
 {
     constexpr int CPL = 128 / B;
     const int64_t nblk = N / B;
-    dim3 grid((D + 64 * CPL - 1) / (64 * CPL), static_cast<unsigned>((nblk + 3) / 4));
+    const int gx = (D + 64 * CPL - 1) / (64 * CPL), gy = static_cast<int>((nblk + 3) / 4);
+    const int grp = hla_job_grp(r);
+    const dim3 grid(hla_job_blocks(gx, gy, grp));
     if (basis)
-        hipLaunchKernelGGL((k_hla<Tin, B, 1>), grid, dim3(256), 0, st, static_cast<const Tin *>(T), N, D, r, ThatT, coeffT);
+        hipLaunchKernelGGL((k_hla<Tin, B, 1>), grid, dim3(256), 0, st, static_cast<const Tin *>(T), N, D, r, ThatT, coeffT, gx, grp);
     else
-        hipLaunchKernelGGL((k_hla<Tin, B, 0>), grid, dim3(256), 0, st, static_cast<const Tin *>(T), N, D, r, ThatT, coeffT);
+        hipLaunchKernelGGL((k_hla<Tin, B, 0>), grid, dim3(256), 0, st, static_cast<const Tin *>(T), N, D, r, ThatT, coeffT, gx, grp);
     return hipGetLastError();
 }
 
