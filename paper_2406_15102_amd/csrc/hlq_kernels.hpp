@@ -56,16 +56,23 @@ struct FrontHla {    // K3 on one tensor
     int64_t N;
     int D, r;
     uint16_t *out;
-    int gx, gy;      // column strips, groups of four token blocks
+    int gx, gy;      // column strips, groups of kHlaBlocks token blocks
     int grp, nb;     // hla_job_map's grouping and the workgroups it needs (>= gx * gy)
 };
-// Order of the workgroups of a K3 job.  A workgroup writes 8 r bytes of each of its output rows and
-// the workgroup of the next `by` the 8 r bytes after them; workgroups go round-robin to the eight
-// XCDs (index mod 8), each with its own L2.  hla_job_map (hla_body.hpp) keeps `grp` consecutive
-// `by` of one strip on one XCD, back to back, so that their pieces meet in that L2 and leave it as
-// whole 128-byte lines (measured, cold inputs: G of 4096 x 11008, 22 strips, 51.6 -> 42.5 us; no change
-// where the strips are a multiple of 8, which gives the same placement by itself).
-inline int hla_job_grp(int r) { return r >= 8 ? 2 : (r == 4 ? 4 : 8); }
+// Shape of a K3 workgroup: kHlaLanes lanes side by side (each CPL = 128/B columns: 256 B of a row
+// of bf16) times 256/kHlaLanes token blocks, so that both the reads (runs of 256 B) and the writes
+// (r coefficients of 16 consecutive token blocks: 32 r bytes of an output row) come in long runs.
+// Measured on cold inputs against 64 lanes x 4 token blocks (1 KB reads, 8 r byte writes), us:
+// X of 65536 x 576: 54.8 -> 25.1, G of 4096 x 11008: 41.7 -> 34.2, G of 12608 x 3072: 36.5 -> 27.5.
+constexpr int kHlaLanes = 16, kHlaBlocks = 256 / kHlaLanes;
+inline int hla_grid_x(int D, int B) { return (D + kHlaLanes * (128 / B) - 1) / (kHlaLanes * (128 / B)); }
+inline int hla_grid_y(int64_t N, int B) { return static_cast<int>((N / B + kHlaBlocks - 1) / kHlaBlocks); }
+// Order of the workgroups of a K3 job.  A workgroup writes 32 r bytes of each of its output rows and
+// the workgroup of the next `by` the 32 r bytes after them; workgroups go round-robin to the eight
+// XCDs (index mod 8), each with its own L2.  Where 32 r bytes are less than a 128-byte line,
+// hla_job_map (hla_body.hpp) keeps the `grp` consecutive `by` that complete a line on one XCD, back
+// to back, so that their pieces meet in that L2 and leave it as whole lines.
+inline int hla_job_grp(int r) { return r >= 4 ? 1 : (r == 2 ? 2 : 4); }
 inline int hla_job_blocks(int gx, int gy, int grp)
 {
     const int units = gx * ((gy + grp - 1) / grp);

@@ -210,9 +210,8 @@ FrontHla front_hla(const void *T, int64_t N, int D, int B, int r, uint16_t *out)
 {
     FrontHla j{T, N, D, r, out, 0, 0, 1, 0};
     if (!T) return j;
-    const int cpl = 128 / B;
-    j.gx = (D + 64 * cpl - 1) / (64 * cpl);
-    j.gy = static_cast<int>((N / B + 3) / 4);
+    j.gx = hla_grid_x(D, B);
+    j.gy = hla_grid_y(N, B);
     j.grp = hla_job_grp(r);
     j.nb = hla_job_blocks(j.gx, j.gy, j.grp);
     return j;

@@ -30,7 +30,7 @@ static hipError_t launch_hla_t(const void *T, int64_t N, int D, int r, int basis
 {
     constexpr int CPL = 128 / B;
     const int64_t nblk = N / B;
-    const int gx = (D + 64 * CPL - 1) / (64 * CPL), gy = static_cast<int>((nblk + 3) / 4);
+    const int gx = hla_grid_x(D, B), gy = hla_grid_y(N, B);
     const int grp = hla_job_grp(r);
     const dim3 grid(hla_job_blocks(gx, gy, grp));
     if (basis)
@@ -158,7 +158,7 @@ static hipError_t launch_hla_conv_t(const void *X, const ConvShape &g, int r, bf
 {
     constexpr int CPL = 128 / B;
     const int D = g.kh * g.kw * g.C;
-    dim3 grid((D + 64 * CPL - 1) / (64 * CPL), static_cast<unsigned>((g.N / B + 3) / 4));
+    dim3 grid(hla_grid_x(D, B), hla_grid_y(g.N, B));
     hipLaunchKernelGGL((k_hla_conv<Tin, B, BASIS>), grid, dim3(256), 0, st, static_cast<const Tin *>(X), g, D, r, ThatT, coeffT);
     return hipGetLastError();
 }
