@@ -57,7 +57,7 @@ template <typename Tin> struct ConvRows {
     }
 };
 
-// Workgroup l of a K3 job -> (column strip bx, group of kHlaBlocks token blocks by): grp consecutive by of
+// Workgroup l of a K3 job -> (column strip bx, group of 256/B token blocks by): grp consecutive by of
 // one strip on one XCD (l mod 8), one after the other.  by may come out past the last group: the
 // bodies return for those.
 __device__ __forceinline__ void hla_job_map(int l, int gx, int grp, int &bx, int &by)
@@ -72,11 +72,12 @@ __device__ __forceinline__ void hla_body_src(const Src &src, int64_t N, int D, i
                                              float *__restrict__ coeffT, int bx, int by)
 {
     constexpr int CPL = 128 / B;
+    constexpr int L = hla_lanes(B), NB = hla_blocks(B);
     const int tid = threadIdx.x;
-    const int col0 = (bx * kHlaLanes + (tid & (kHlaLanes - 1))) * CPL;
+    const int col0 = (bx * L + tid % L) * CPL;
     const int64_t nblk = N / B;
     const int64_t Kc = nblk * r;
-    const int64_t blk = static_cast<int64_t>(by) * kHlaBlocks + tid / kHlaLanes;
+    const int64_t blk = static_cast<int64_t>(by) * NB + tid / L;
     if (col0 >= D || blk >= nblk) return;
 
     float v[B * CPL];

@@ -20,6 +20,12 @@ hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, ui
                              float qmax, bool packed, bool mant, int8_t *WqT, float *sW, float *coeffT, void *ws,
                              hipStream_t st);
 
+// Shape of a workgroup of K1T's two passes, as for K3: B lanes side by side (runs of 256 B of a row
+// of bf16) times 256/B row blocks, whose codes are neighbours in a row of the transposed output
+// (runs of 256 bytes, 128 packed).
+inline int cols_grid_x(int I, int B) { return (I + 127) / 128; }
+inline int cols_grid_y(int O, int B) { return (O + 255) / 256; }       // 256/B row blocks of B rows
+
 // K1T split in its two passes, for callers that run pass 1 elsewhere (the fused front launches):
 // pass 2 alone, reading the column maxima pass 1 left in `ws`.
 hipError_t launch_quant_cols_pass2(const void *W, int O, int I, int B, bool is_f32, uint32_t k0, uint32_t k1,
@@ -56,23 +62,29 @@ struct FrontHla {    // K3 on one tensor
     int64_t N;
     int D, r;
     uint16_t *out;
-    int gx, gy;      // column strips, groups of kHlaBlocks token blocks
+    int gx, gy;      // column strips of 128, groups of 256/B token blocks
     int grp, nb;     // hla_job_map's grouping and the workgroups it needs (>= gx * gy)
 };
-// Shape of a K3 workgroup: kHlaLanes lanes side by side (each CPL = 128/B columns: 256 B of a row
-// of bf16) times 256/kHlaLanes token blocks, so that both the reads (runs of 256 B) and the writes
-// (r coefficients of 16 consecutive token blocks: 32 r bytes of an output row) come in long runs.
-// Measured on cold inputs against 64 lanes x 4 token blocks (1 KB reads, 8 r byte writes), us:
-// X of 65536 x 576: 54.8 -> 25.1, G of 4096 x 11008: 41.7 -> 34.2, G of 12608 x 3072: 36.5 -> 27.5.
-constexpr int kHlaLanes = 16, kHlaBlocks = 256 / kHlaLanes;
-inline int hla_grid_x(int D, int B) { return (D + kHlaLanes * (128 / B) - 1) / (kHlaLanes * (128 / B)); }
-inline int hla_grid_y(int64_t N, int B) { return static_cast<int>((N / B + kHlaBlocks - 1) / kHlaBlocks); }
-// Order of the workgroups of a K3 job.  A workgroup writes 32 r bytes of each of its output rows and
-// the workgroup of the next `by` the 32 r bytes after them; workgroups go round-robin to the eight
-// XCDs (index mod 8), each with its own L2.  Where 32 r bytes are less than a 128-byte line,
-// hla_job_map (hla_body.hpp) keeps the `grp` consecutive `by` that complete a line on one XCD, back
-// to back, so that their pieces meet in that L2 and leave it as whole lines.
-inline int hla_job_grp(int r) { return r >= 4 ? 1 : (r == 2 ? 2 : 4); }
+// Shape of a K3 workgroup: B lanes side by side (each CPL = 128/B columns: 256 B of a row of bf16
+// whatever B) times 256/B token blocks, so that both the reads (runs of 256 B) and the writes
+// (r coefficients of 256/B consecutive token blocks: 512 r/B bytes of an output row) come in long
+// runs.  Measured at B = 16 on cold inputs against 64 lanes x 4 token blocks (1 KB reads, 8 r byte
+// writes), us: X of 65536 x 576: 54.8 -> 25.1, G of 4096 x 11008: 41.7 -> 34.2, G of 12608 x 3072:
+// 36.5 -> 27.5.  (16 lanes at B = 64 would read runs of 64 B: the whole pass 424 -> 451 us.)
+constexpr int hla_lanes(int B) { return B; }
+constexpr int hla_blocks(int B) { return 256 / B; }
+inline int hla_grid_x(int D, int B) { return (D + 127) / 128; }      // B lanes x 128/B columns = 128 columns
+inline int hla_grid_y(int64_t N, int B) { return static_cast<int>((N / B + hla_blocks(B) - 1) / hla_blocks(B)); }
+// Order of the workgroups of a K3 job.  A workgroup writes 512 r/B bytes of each of its output rows
+// and the workgroup of the next `by` the bytes after them; workgroups go round-robin to the eight
+// XCDs (index mod 8), each with its own L2.  Where that is less than a 128-byte line, hla_job_map
+// (hla_body.hpp) keeps the `grp` consecutive `by` that complete a line on one XCD, back to back, so
+// that their pieces meet in that L2 and leave it as whole lines.
+inline int hla_job_grp(int B, int r)
+{
+    const int bytes = 512 * r / B;
+    return bytes >= 128 ? 1 : (bytes >= 64 ? 2 : (bytes >= 32 ? 4 : 8));
+}
 inline int hla_job_blocks(int gx, int gy, int grp)
 {
     const int units = gx * ((gy + grp - 1) / grp);

@@ -151,9 +151,8 @@ FrontColsQ front_colsq(const void *W, int O, int I, int B, const uint32_t *amax,
 {
     FrontColsQ j{W, O, I, amax, k0, k1, qmax, WqT, sW, 0, 0};
     if (!W) return j;
-    const int cpl = 128 / B;
-    j.gx = (I + 64 * cpl - 1) / (64 * cpl);
-    j.gy = (O + 4 * B - 1) / (4 * B);
+    j.gx = cols_grid_x(I, B);
+    j.gy = cols_grid_y(O, B);
     return j;
 }
 
@@ -212,7 +211,7 @@ FrontHla front_hla(const void *T, int64_t N, int D, int B, int r, uint16_t *out)
     if (!T) return j;
     j.gx = hla_grid_x(D, B);
     j.gy = hla_grid_y(N, B);
-    j.grp = hla_job_grp(r);
+    j.grp = hla_job_grp(B, r);
     j.nb = hla_job_blocks(j.gx, j.gy, j.grp);
     return j;
 }
@@ -221,9 +220,8 @@ FrontAbsmax front_absmax(const void *W, int O, int I, int B, uint32_t *amax)
 {
     FrontAbsmax j{W, O, I, amax, 0, 0};
     if (!W) return j;
-    const int cpl = 128 / B;
-    j.gx = (I + 64 * cpl - 1) / (64 * cpl);
-    j.gy = (O + 4 * B - 1) / (4 * B);
+    j.gx = cols_grid_x(I, B);
+    j.gy = cols_grid_y(O, B);
     return j;
 }
 

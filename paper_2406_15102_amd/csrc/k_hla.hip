@@ -31,7 +31,7 @@ static hipError_t launch_hla_t(const void *T, int64_t N, int D, int r, int basis
     constexpr int CPL = 128 / B;
     const int64_t nblk = N / B;
     const int gx = hla_grid_x(D, B), gy = hla_grid_y(N, B);
-    const int grp = hla_job_grp(r);
+    const int grp = hla_job_grp(B, r);
     const dim3 grid(hla_job_blocks(gx, gy, grp));
     if (basis)
         hipLaunchKernelGGL((k_hla<Tin, B, 1>), grid, dim3(256), 0, st, static_cast<const Tin *>(T), N, D, r, ThatT, coeffT, gx, grp);

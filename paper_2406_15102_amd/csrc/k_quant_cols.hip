@@ -3,18 +3,18 @@
 // stochastic quantisation (Sec. 5.1) with one absmax scale per in-feature (= per column of W,
 // = per row of the transposed, reduction-contiguous output WqT [d_in, d_out]).
 //
-// A lane owns CPL = 128/B adjacent columns and B consecutive rows: B fully coalesced row loads
-// (16 B per lane for bf16) put whole Hadamard blocks in its registers, so the transform needs no
-// lane exchange.  A wavefront is one (B rows) x (64*CPL columns) unit of work and a workgroup four
-// consecutive row blocks, which makes thousands of independent workgroups even for one layer.
+// A lane owns CPL = 128/B adjacent columns and B consecutive rows: B row loads (16 B per lane for
+// bf16) put whole Hadamard blocks in its registers, so the transform needs no lane exchange.  A
+// workgroup is B lanes side by side (runs of 256 B of a row) times 256/B consecutive row blocks,
+// whose codes are neighbours in a row of the transposed output (runs of 256 bytes, 128 packed):
+// thousands of independent workgroups even for one layer, and long runs both ways.
 // The column absmax spans all of d_out, hence two passes over W (the second mostly served by the
 // last-level cache when W fits there):
 //   zero    amax[d_in] = 0
 //   pass 1  transform, per-column max over the workgroup's rows (LDS), one atomic max per column
 //           and workgroup.  max() is order-independent and the values are non-negative floats,
 //           whose bit patterns order like unsigned integers: the result is deterministic.
-//   pass 2  transform again, quantise, write B codes per column and wavefront (contiguous in
-//           d_out; the four wavefronts of a workgroup complete 4*B contiguous bytes per column).
+//   pass 2  transform again, quantise, write B codes per column and row block.
 #include "quant_cols_body.hpp"
 #include "hlq_kernels.hpp"
 
@@ -53,7 +53,7 @@ static hipError_t launch_cols_pass1_t(const void *W, int O, int I, void *ws, hip
 {
     constexpr int CPL = 128 / B;
     uint32_t *amax = static_cast<uint32_t *>(ws);
-    dim3 grid((I + 64 * CPL - 1) / (64 * CPL), (O + 4 * B - 1) / (4 * B));
+    dim3 grid(cols_grid_x(I, B), cols_grid_y(O, B));
     hipLaunchKernelGGL(k_fill_u32, dim3((I + 255) / 256), dim3(256), 0, st, amax, I, 0u);
     hipLaunchKernelGGL((k_cols_absmax<Tin, B>), grid, dim3(256), 0, st, static_cast<const Tin *>(W), O, I, amax);
     return hipGetLastError();
@@ -66,7 +66,7 @@ static hipError_t launch_cols_pass2_t(const void *W, int O, int I, uint32_t k0, 
     constexpr int CPL = 128 / B;
     const uint32_t *amax = static_cast<const uint32_t *>(ws);
     const Tin *w = static_cast<const Tin *>(W);
-    dim3 grid((I + 64 * CPL - 1) / (64 * CPL), (O + 4 * B - 1) / (4 * B));
+    dim3 grid(cols_grid_x(I, B), cols_grid_y(O, B));
 #define HLQ_COLS2_LAUNCH(P, M) \
     hipLaunchKernelGGL((k_cols_quantize<Tin, B, P, M>), grid, dim3(256), 0, st, w, O, I, amax, k0, k1, qmax, WqT, sW, coeffT)
     if (packed) {

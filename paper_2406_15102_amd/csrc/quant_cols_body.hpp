@@ -2,6 +2,7 @@
 // pass 1, the column maxima of the transformed weight.
 #pragma once
 #include "hlq_device.hpp"
+#include "hlq_kernels.hpp"
 
 namespace hlq {
 
@@ -12,18 +13,18 @@ __device__ __forceinline__ void load_row_block(const Tin *base, int64_t pitch, f
     for (int j = 0; j < B; ++j) Loader<Tin, CPL>::load(base + j * pitch, v + j * CPL);
 }
 
-// pass 1: one row block per wavefront; the four wavefronts' maxima meet in LDS and are merged
+// pass 1: a row block per group of B lanes (256 / B groups); the groups' maxima meet in LDS and are merged
 // into one maximum per column with an atomic on the bit patterns (non-negative floats order like
 // their bit patterns), so the maxima must have been zeroed by an earlier launch.
 template <typename Tin, int B>
 __device__ __forceinline__ void cols_absmax_body(const Tin *__restrict__ W, int O, int I, uint32_t *__restrict__ amax_bits,
                                                  int bx, int by)
 {
-    constexpr int CPL = 128 / B;
-    __shared__ float s_max[4][64 * CPL];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int col0 = (bx * 64 + lane) * CPL;
-    const int o0 = (by * 4 + wave) * B;
+    constexpr int CPL = 128 / B, L = B, NB = 256 / B;     // lanes side by side, row blocks
+    __shared__ float s_max[NB][L * CPL];
+    const int tid = threadIdx.x, grp = tid / L, sub = tid % L;
+    const int col0 = (bx * L + sub) * CPL;
+    const int o0 = (by * NB + grp) * B;
     float cmax[CPL];
 #pragma unroll
     for (int c = 0; c < CPL; ++c) cmax[c] = 0.0f;
@@ -39,11 +40,13 @@ __device__ __forceinline__ void cols_absmax_body(const Tin *__restrict__ W, int 
         }
     }
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) s_max[wave][lane * CPL + c] = cmax[c];
+    for (int c = 0; c < CPL; ++c) s_max[grp][sub * CPL + c] = cmax[c];
     __syncthreads();
-    for (int idx = tid; idx < 64 * CPL; idx += 256) {
-        const float m = fmaxf(fmaxf(s_max[0][idx], s_max[1][idx]), fmaxf(s_max[2][idx], s_max[3][idx]));
-        const int col = bx * 64 * CPL + idx;
+    for (int idx = tid; idx < L * CPL; idx += 256) {
+        float m = s_max[0][idx];
+#pragma unroll
+        for (int g = 1; g < NB; ++g) m = fmaxf(m, s_max[g][idx]);
+        const int col = bx * L * CPL + idx;
         if (col < I && m > 0.0f) atomicMax(amax_bits + col, __float_as_uint(m));
     }
 }
@@ -89,7 +92,7 @@ __device__ __forceinline__ void cols_quantize_block(const Tin *__restrict__ W, i
     }
 }
 
-// pass 2: one row block per wavefront against the column maxima that pass 1 merged.
+// pass 2: a row block per group of B lanes against the column maxima that pass 1 merged.
 template <typename Tin, int B, bool PACKED, bool MANT = false>
 __device__ __forceinline__ void cols_quantize_body(const Tin *__restrict__ W, int O, int I,
                                                    const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
@@ -97,9 +100,10 @@ __device__ __forceinline__ void cols_quantize_body(const Tin *__restrict__ W, in
                                                    float *__restrict__ coeffT, int bx, int by)
 {
     constexpr int CPL = 128 / B;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int col0 = (bx * 64 + lane) * CPL;
-    const int o0 = (by * 4 + wave) * B;
+    constexpr int L = B, NB = 256 / B;
+    const int tid = threadIdx.x;
+    const int col0 = (bx * L + tid % L) * CPL;
+    const int o0 = (by * NB + tid / L) * B;
     if (col0 >= I || o0 >= O) return;
     float inv[CPL];
 #pragma unroll
