@@ -32,7 +32,9 @@
  *   r a power of two, 1 <= r <= B                   HLQ_ERR_RANK
  *   N > 0, N % B == 0; d_out > 0, d_out % B == 0, d_out <= 65536;
  *   d_in > 0, d_in % 8 == 0; (N / B * r) % 8 == 0;
- *   N * d_out / 4 < 2^32 and d_in * d_out / 4 < 2^32 (random-stream counters)     HLQ_ERR_SHAPE
+ *   N * d_out / 4 < 2^32 and d_in * d_out / 4 < 2^32 (random-stream counters);
+ *   N / B <= 262140 and ceil(D / 128) * ceil(N / (4 B)) < 2^30 for D = d_in and D = d_out
+ *   (workgroups of one launch of the token-axis transform)                        HLQ_ERR_SHAPE
  */
 #ifndef HLQ_H_
 #define HLQ_H_

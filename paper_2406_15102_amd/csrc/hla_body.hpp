@@ -128,12 +128,12 @@ template <int B, int BASIS, typename Src>
 __device__ __forceinline__ void hla_absmax_body_src(const Src &src, int64_t N, int D, int r,
                                                     uint32_t *__restrict__ amax_bits, int bx, int by)
 {
-    constexpr int CPL = 128 / B;
-    __shared__ float s_max[4][64 * CPL];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int col0 = (bx * 64 + lane) * CPL;
+    constexpr int CPL = 128 / B, L = hla_lanes(B), NB = hla_blocks(B);
+    __shared__ float s_max[NB][L * CPL];
+    const int tid = threadIdx.x, grp = tid / L, sub = tid % L;
+    const int col0 = (bx * L + sub) * CPL;
     const int64_t nblk = N / B;
-    const int64_t blk = static_cast<int64_t>(by) * 4 + wave;
+    const int64_t blk = static_cast<int64_t>(by) * NB + grp;
     float cmax[CPL];
 #pragma unroll
     for (int c = 0; c < CPL; ++c) cmax[c] = 0.0f;
@@ -149,11 +149,13 @@ __device__ __forceinline__ void hla_absmax_body_src(const Src &src, int64_t N, i
         }
     }
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) s_max[wave][lane * CPL + c] = cmax[c];
+    for (int c = 0; c < CPL; ++c) s_max[grp][sub * CPL + c] = cmax[c];
     __syncthreads();
-    for (int idx = tid; idx < 64 * CPL; idx += 256) {
-        const float m = fmaxf(fmaxf(s_max[0][idx], s_max[1][idx]), fmaxf(s_max[2][idx], s_max[3][idx]));
-        const int col = bx * 64 * CPL + idx;
+    for (int idx = tid; idx < L * CPL; idx += 256) {
+        float m = s_max[0][idx];
+#pragma unroll
+        for (int g = 1; g < NB; ++g) m = fmaxf(m, s_max[g][idx]);
+        const int col = bx * L * CPL + idx;
         if (col < D && m > 0.0f) atomicMax(amax_bits + col, __float_as_uint(m));
     }
 }
@@ -171,12 +173,12 @@ __device__ __forceinline__ void hla_quantize_body_src(const Src &src, int64_t N,
                                                       int8_t *__restrict__ TqT, float *__restrict__ sT,
                                                       float *__restrict__ coeffT, int bx, int by)
 {
-    constexpr int CPL = 128 / B;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int col0 = (bx * 64 + lane) * CPL;
+    constexpr int CPL = 128 / B, L = hla_lanes(B), NB = hla_blocks(B);
+    const int tid = threadIdx.x;
+    const int col0 = (bx * L + tid % L) * CPL;
     const int64_t nblk = N / B;
     const int64_t Kc = nblk * r;
-    const int64_t blk = static_cast<int64_t>(by) * 4 + wave;
+    const int64_t blk = static_cast<int64_t>(by) * NB + tid / L;
     if (col0 >= D || blk >= nblk) return;
 
     float v[B * CPL];

@@ -41,6 +41,7 @@ int check_hla_shape(int64_t N, int64_t D, int B, int r)
     const int64_t Kc = N / B * r;
     if (Kc % 8 != 0 || Kc > (int64_t(1) << 30)) return HLQ_ERR_SHAPE;
     if ((N / B + 3) / 4 > 65535) return HLQ_ERR_SHAPE;   // token-block groups are the grid's y axis
+    if ((D + 127) / 128 * ((N / B + 3) / 4) >= (int64_t(1) << 30)) return HLQ_ERR_SHAPE;   // workgroups of one launch
     return HLQ_OK;
 }
 

@@ -140,9 +140,8 @@ FrontHlaQ front_hlaq(const void *T, int64_t N, int D, int B, int r, uint32_t *am
 {
     FrontHlaQ j{T, N, D, r, amax, k0, k1, TqT, sT, 0, 0};
     if (!T) return j;
-    const int cpl = 128 / B;
-    j.gx = (D + 64 * cpl - 1) / (64 * cpl);
-    j.gy = static_cast<int>((N / B + 3) / 4);
+    j.gx = hla_grid_x(D, B);
+    j.gy = hla_grid_y(N, B);
     return j;
 }
 

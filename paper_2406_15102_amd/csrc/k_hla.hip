@@ -96,7 +96,7 @@ static hipError_t launch_hla_quant_t(const void *T, int64_t N, int D, int r, uin
     const int64_t nblk = N / B;
     uint32_t *amax = static_cast<uint32_t *>(ws);
     const Tin *t = static_cast<const Tin *>(T);
-    dim3 grid((D + 64 * CPL - 1) / (64 * CPL), static_cast<unsigned>((nblk + 3) / 4));
+    dim3 grid(hla_grid_x(D, B), hla_grid_y(N, B));
     hipLaunchKernelGGL(k_hla_fill_u32, dim3((D + 255) / 256), dim3(256), 0, st, amax, D, 0u);
     hipLaunchKernelGGL((k_hla_absmax<Tin, B, BASIS>), grid, dim3(256), 0, st, t, N, D, r, amax);
     if (mant)
@@ -191,7 +191,7 @@ static hipError_t launch_hla_quant_conv_t(const void *X, const ConvShape &g, int
     const int D = g.kh * g.kw * g.C;
     uint32_t *amax = static_cast<uint32_t *>(ws);
     const Tin *x = static_cast<const Tin *>(X);
-    dim3 grid((D + 64 * CPL - 1) / (64 * CPL), static_cast<unsigned>((g.N / B + 3) / 4));
+    dim3 grid(hla_grid_x(D, B), hla_grid_y(g.N, B));
     hipLaunchKernelGGL(k_hla_fill_u32, dim3((D + 255) / 256), dim3(256), 0, st, amax, D, 0u);
     hipLaunchKernelGGL((k_hla_absmax_conv<Tin, B, BASIS>), grid, dim3(256), 0, st, x, g, D, r, amax);
     if (mant)
