@@ -209,15 +209,49 @@ __device__ __forceinline__ void gemm_tile(const GemmDev &g, const int bid)
     HLQ_STORE_LDS_A()
     HLQ_STORE_LDS_B()
     wr_off ^= STAGE_BYTES;
-    HLQ_LOAD_GLOBAL_A(nk > 1 ? 1 : 0)
-    HLQ_LOAD_GLOBAL_B(nk > 1 ? 1 : 0)
+    const bool one_step = nk == 1;
+    if (!one_step) {
+        HLQ_LOAD_GLOBAL_A(1)
+        HLQ_LOAD_GLOBAL_B(1)
+    }
     lds_barrier();
-    HLQ_READ_FRAGS(0, 0)
     u32x4 ea[2][WM][2], pb[2];    // packed codes: expanded A operands and first B operand of the coming sub-step
-    if constexpr (KIND == 2) {
+    if (one_step) {
+        // A reduction of one step (the 4-bit codes of up to 256 out-features, a finely split k):
+        // there is no pipeline to keep full.  The sub-steps that hold data are multiplied straight
+        // from stage 0 (the rest of a ragged step is zeros), nothing is staged or loaded again.
+        const int bytes = g.Kb - kbeg * (KCH * 16);
+        const int nsub = bytes >= KCH * 16 ? NS : (bytes + 31) / 32;
 #pragma unroll
-        for (int i = 0; i < WM; ++i) Mma<2>::expand(fa[0][i], ea[0][i][0], ea[0][i][1]);
-        Mma<2>::expand(fb[0][0], pb[0], pb[1]);
+        for (int ks = 0; ks < NS; ++ks) {
+            if (ks < nsub) {
+                HLQ_READ_FRAGS(0, ks)
+                if constexpr (KIND == 2) {
+#pragma unroll
+                    for (int i = 0; i < WM; ++i) Mma<2>::expand(fa[0][i], ea[0][i][0], ea[0][i][1]);
+#pragma unroll
+                    for (int j = 0; j < WN; ++j) {
+                        Mma<2>::expand(fb[0][j], pb[0], pb[1]);
+#pragma unroll
+                        for (int i = 0; i < WM; ++i) acc[i][j] = Mma<2>::mma(pb[0], ea[0][i][0], acc[i][j]);
+#pragma unroll
+                        for (int i = 0; i < WM; ++i) acc[i][j] = Mma<2>::mma(pb[1], ea[0][i][1], acc[i][j]);
+                    }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < WM; ++i)
+#pragma unroll
+                        for (int j = 0; j < WN; ++j) acc[i][j] = Mma<KIND>::mma(fb[0][j], fa[0][i], acc[i][j]);
+                }
+            }
+        }
+    } else {
+        HLQ_READ_FRAGS(0, 0)
+        if constexpr (KIND == 2) {
+#pragma unroll
+            for (int i = 0; i < WM; ++i) Mma<2>::expand(fa[0][i], ea[0][i][0], ea[0][i][1]);
+            Mma<2>::expand(fb[0][0], pb[0], pb[1]);
+        }
     }
     constexpr int MPS = KIND == 2 ? 2 : 1;   // MFMAs per accumulator and sub-step
     constexpr bool SPREAD = KIND != 2 && WM == 4 && WN == 4;   // schedule with the staging writes spread out
@@ -225,7 +259,7 @@ __device__ __forceinline__ void gemm_tile(const GemmDev &g, const int bid)
 
     static_assert(NS == 4, "the staging schedule below is written for four sub-steps per step");
 
-    for (int kt = 0; kt < nk; ++kt) {
+    for (int kt = 0; kt < (one_step ? 0 : nk); ++kt) {
         const int kt2 = kt + 2 < nk ? kt + 2 : nk - 1;
 #pragma unroll
         for (int ks = 0; ks < NS; ++ks) {
