@@ -33,6 +33,7 @@ struct PairPlan {
 namespace {
 constexpr double kStepBig = 1.3, kPackedScale = 1.8, kStepSmallAlone = 0.6, kStepSmallShared = 0.9;
 constexpr double kFixedBig = 16.0, kFixedSmall = 6.5;
+constexpr double kOneStepSaves = 2.0;    // a tile of one step skips the pipeline (gemm_body.hpp)
 constexpr int kSplitChoices[] = {1, 2, 3, 4, 6, 8, 12, 16};
 
 struct TileClass {
@@ -87,11 +88,12 @@ static PairPlan plan_pair(const GemmArgs &a, int kindA, const GemmArgs &b, int k
             const double nA = static_cast<double>((a.M + ta - 1) / ta) * ((a.N + ta - 1) / ta);
             const double nB1 = static_cast<double>((b.M + tb - 1) / tb) * ((b.N + tb - 1) / tb);
             const TileClass ca = tile_class(bigA != 0, mixed, nA);
-            const double tA = nkA * scaleA * ca.step + ca.fixed;
+            const double tA = nkA * scaleA * ca.step + ca.fixed - (nkA == 1 ? kOneStepSaves : 0.0);
             for (int S : kSplitChoices) {
                 if (S > 1 && (S > nkB || S * mnB * 4.0 > static_cast<double>(ws_bytes))) break;
                 const TileClass cb = tile_class(bigB != 0, mixed, nB1 * S);
-                const double tB = __builtin_ceil(static_cast<double>(nkB) / S) * scaleB * cb.step + cb.fixed;
+                const double stepsB = __builtin_ceil(static_cast<double>(nkB) / S);
+                const double tB = stepsB * scaleB * cb.step + cb.fixed - (stepsB == 1.0 ? kOneStepSaves : 0.0);
                 // either product may go first: usually the one with the longer tiles, which must not start late
                 const double tab = pair_makespan(nA, tA, ca.slots, nB1 * S, tB, cb.slots);
                 const double tba = pair_makespan(nB1 * S, tB, cb.slots, nA, tA, ca.slots);
