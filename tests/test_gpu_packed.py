@@ -73,6 +73,7 @@ GEMM_CASES = [
     (256, 256, 128, False), (300, 260, 256, False), (100, 36, 352, False), (260, 132, 96, False),
     (700, 520, 640, False), (384, 3072, 6272, True), (130, 516, 11008, True),
     (72, 68, 131072, False), (72, 68, 131072, True),      # longest supported reduction: 256 * 49 * K still fits int32
+    (300, 260, 64, False), (515, 200, 160, False), (260, 388, 256, False), (4096, 4096, 96, False),   # one k step
 ]
 
 

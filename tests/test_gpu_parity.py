@@ -160,6 +160,8 @@ GEMM_I8_CASES = [
     (130, 132, 592),        # K = 9*64 + 16: ragged last k step
     (64, 8, 16),            # tiny
     (515, 1028, 11008),     # the LLaMA reduction length, 5 x 9 tiles
+    (300, 260, 32), (515, 200, 48), (256, 384, 96), (1000, 136, 128),   # one k step: whole, ragged, every sub-step count
+    (4096, 4096, 64),       # one k step on 256-tiles
 ]
 
 
@@ -255,7 +257,9 @@ def test_hla_project(N, D, B, r, dtype):
 # --------------------------------------------------------------------------------------------
 # K4: bf16 MFMA product
 # --------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("M,Nn,K", [(256, 256, 128), (300, 260, 104), (1030, 520, 6304), (64, 8, 8), (768, 264, 6272)])
+@pytest.mark.parametrize("M,Nn,K", [(256, 256, 128), (300, 260, 104), (1030, 520, 6304), (64, 8, 8), (768, 264, 6272),
+                                    (300, 260, 16), (515, 200, 40), (260, 384, 64),      # one k step, whole and ragged
+                                    (136, 264, 2048)])                                  # split until one step is left
 def test_bf16_gemm(M, Nn, K):
     A = rand_tensor((M, K), torch.bfloat16, seed=M + K)
     Bm = rand_tensor((Nn, K), torch.bfloat16, seed=Nn + K + 1)
