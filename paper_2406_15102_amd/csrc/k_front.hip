@@ -236,7 +236,7 @@ FrontColsQ front_cols_full(const void *W, int O, int I, int B, uint32_t k0, uint
     // as many groups of lanes as there are row blocks, so that a pass is one round where it can be: 16, 32 or 64
     const int nrb = O / B;
     const int lg = nrb <= 16 ? 4 : (nrb <= 32 ? 3 : 2);
-    const int strip = (128 / B) << lg;
+    const int strip = (B == 16 ? ColsFull<16>::CW : (B == 32 ? ColsFull<32>::CW : ColsFull<64>::CW)) << lg;
     j.gx = (I + strip - 1) / strip;
     j.gy = lg;
     return j;

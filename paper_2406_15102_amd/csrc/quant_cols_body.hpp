@@ -51,15 +51,14 @@ __device__ __forceinline__ void cols_absmax_body(const Tin *__restrict__ W, int 
     }
 }
 
-// One row block (B rows from o0) of CPL columns from col0: transform again, quantise against the
+// One row block (B rows from o0) of CPL columns (a lane's share) from col0: transform again, quantise against the
 // reciprocal scales `inv` of those columns, write the codes transposed.
 // PACKED: the codes are written two to a byte (4-bit codes only), O/2 bytes per row of WqT.
-template <typename Tin, int B, bool PACKED, bool MANT>
+template <typename Tin, int B, bool PACKED, bool MANT, int CPL = 128 / B>
 __device__ __forceinline__ void cols_quantize_block(const Tin *__restrict__ W, int O, int I, const float *inv, uint32_t k0,
                                                     uint32_t k1, int8_t *__restrict__ WqT, float *__restrict__ coeffT,
                                                     int col0, int o0)
 {
-    constexpr int CPL = 128 / B;
     float v[B * CPL];
     load_row_block<Tin, B, CPL>(W + static_cast<int64_t>(o0) * I + col0, I, v);
 #pragma unroll
@@ -115,54 +114,60 @@ __device__ __forceinline__ void cols_quantize_body(const Tin *__restrict__ W, in
     cols_quantize_block<Tin, B, PACKED, MANT>(W, O, I, inv, k0, k1, WqT, coeffT, col0, o0);
 }
 
-// Both passes by one workgroup, for a weight of few rows: the workgroup owns a strip of LG * CPL
-// columns over all of O (LG = 1 << lg lanes side by side: 16, 8 or 4), its 256 / LG groups of
-// lanes take a row block each per round, the maxima meet in LDS, and the second pass finds the
-// rows in the cache.  No other workgroup is waited for, so this can ride in a launch with anything.
+// Both passes by one workgroup, for a small weight: the workgroup owns a strip of LG * CW columns
+// over all of O (LG = 1 << lg lanes side by side: 16, 8 or 4; CW columns a lane, fewer than the
+// 128/B of the two-pass kernels so that a lane's chain of loads, transform and quantisation is
+// short: this job's latency is what the launch around it can end on), its 256 / LG groups of lanes
+// take a row block each per round, the maxima meet in LDS, and the second pass finds the rows in
+// the cache.  No other workgroup is waited for, so this can ride in a launch with anything.
+template <int B> struct ColsFull {
+    static constexpr int CW = B == 16 ? 4 : 2;      // columns a lane: 64 (B = 16, 32) or 128 values
+};
+
 template <typename Tin, int B, bool PACKED>
 __device__ __forceinline__ void cols_full_body(const Tin *__restrict__ W, int O, int I, uint32_t k0, uint32_t k1, float qmax,
                                                int8_t *__restrict__ WqT, float *__restrict__ sW, int bx, int lg)
 {
-    constexpr int CPL = 128 / B;
-    __shared__ float s_strip[256 * CPL];      // [group][lane of the group][column of the lane]
+    constexpr int CW = ColsFull<B>::CW;
+    __shared__ float s_strip[256 * CW];       // [group][lane of the group][column of the lane]
     const int tid = threadIdx.x, grp = tid >> lg, sub = tid & ((1 << lg) - 1), groups = 256 >> lg;
-    const int col0 = ((bx << lg) + sub) * CPL;
+    const int col0 = ((bx << lg) + sub) * CW;
     const int nrb = O / B;
-    float cmax[CPL];
+    float cmax[CW];
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) cmax[c] = 0.0f;
+    for (int c = 0; c < CW; ++c) cmax[c] = 0.0f;
     if (col0 < I) {
 #pragma nounroll
         for (int rb = grp; rb < nrb; rb += groups) {
-            float v[B * CPL];
-            load_row_block<Tin, B, CPL>(W + static_cast<int64_t>(rb) * B * I + col0, I, v);
+            float v[B * CW];
+            load_row_block<Tin, B, CW>(W + static_cast<int64_t>(rb) * B * I + col0, I, v);
 #pragma unroll
-            for (int c = 0; c < CPL; ++c) {
-                fwht_regs<B, CPL>(v + c);
+            for (int c = 0; c < CW; ++c) {
+                fwht_regs<B, CW>(v + c);
 #pragma unroll
-                for (int j = 0; j < B; ++j) cmax[c] = fmaxf(cmax[c], fabsf(v[j * CPL + c]));
+                for (int j = 0; j < B; ++j) cmax[c] = fmaxf(cmax[c], fabsf(v[j * CW + c]));
             }
         }
     }
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) s_strip[tid * CPL + c] = cmax[c];
+    for (int c = 0; c < CW; ++c) s_strip[tid * CW + c] = cmax[c];
     __syncthreads();
     if (col0 >= I) return;
-    // a few groups at a time: all of them in flight would cost CPL registers each
-#pragma unroll 2
+    // a few groups at a time: all of them in flight would cost CW registers each
+#pragma unroll 4
     for (int g = 0; g < groups; ++g) {
 #pragma unroll
-        for (int c = 0; c < CPL; ++c) cmax[c] = fmaxf(cmax[c], s_strip[((g << lg) + sub) * CPL + c]);
+        for (int c = 0; c < CW; ++c) cmax[c] = fmaxf(cmax[c], s_strip[((g << lg) + sub) * CW + c]);
     }
-    float inv[CPL];
+    float inv[CW];
 #pragma unroll
-    for (int c = 0; c < CPL; ++c) {
+    for (int c = 0; c < CW; ++c) {
         inv[c] = absmax_to_inv(cmax[c], qmax);
         if (grp == 0) sW[col0 + c] = absmax_to_scale(cmax[c], qmax);
     }
 #pragma nounroll
     for (int rb = grp; rb < nrb; rb += groups)
-        cols_quantize_block<Tin, B, PACKED, false>(W, O, I, inv, k0, k1, WqT, nullptr, col0, rb * B);
+        cols_quantize_block<Tin, B, PACKED, false, CW>(W, O, I, inv, k0, k1, WqT, nullptr, col0, rb * B);
 }
 
 }  // namespace hlq
