@@ -233,9 +233,10 @@ FrontColsQ front_cols_full(const void *W, int O, int I, int B, uint32_t k0, uint
 {
     FrontColsQ j{W, O, I, nullptr, k0, k1, qmax, WqT, sW, 0, 0};
     if (!W) return j;
-    // as many groups of lanes as there are row blocks, so that a pass is one round where it can be: 16, 32 or 64
+    // as many groups of lanes as there are row blocks, so that a pass is one round where it can be: 16, 32 or
+    // 64; beyond 64 row blocks there are several rounds anyway and the longer runs of 32 groups measure better
     const int nrb = O / B;
-    const int lg = nrb <= 16 ? 4 : (nrb <= 32 ? 3 : 2);
+    const int lg = nrb <= 16 ? 4 : (nrb <= 32 ? 3 : (nrb <= 64 ? 2 : 3));
     const int strip = (B == 16 ? ColsFull<16>::CW : (B == 32 ? ColsFull<32>::CW : ColsFull<64>::CW)) << lg;
     j.gx = (I + strip - 1) / strip;
     j.gy = lg;
