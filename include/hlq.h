@@ -73,15 +73,32 @@ int hlq_version(void);
 size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r, int x_is_compressed);
 
 /*
+ * Registers caller-owned device memory as the scratch of every call on the CURRENT device that is
+ * given no workspace of its own (hlq_linear_backward, and the entry points below when their
+ * `workspace` is NULL): the layer of Sec. 3.1, Eq. 1 then runs through the plain signature without
+ * the library ever allocating, freeing or synchronising.
+ *   dev_ptr  256-byte aligned device memory that stays valid until it is replaced or withdrawn;
+ *            NULL (bytes ignored) withdraws the registration and returns to the library-owned scratch.
+ *   bytes    its size; size it with hlq_workspace_bytes / hlq_workspace_bytes_mode /
+ *            hlq_conv_workspace_bytes for the largest problem that will be run.
+ * HLQ_ERR_WORKSPACE for a misaligned pointer or bytes == 0 with a non-NULL pointer (the previous
+ * registration stays).  The memory is not touched by this call.  Host-side only: no GPU work.
+ */
+int hlq_set_workspace(void *dev_ptr, size_t bytes);
+
+/*
  * The whole backward pass of one layer for bf16 tensors (both stage lists of Sec. 6.1):
  *   dX [N, d_in]     = dequant( Q4(G H) . Q4(H^T W) )        stages 1-6 of the g_x list
  *   dW [d_out, d_in] = (1/B) . HLA_r(G)^T . HLA_r(X)          stages 1, 3, 5 of the g_w list
  * `seed` selects the stochastic-rounding stream (same seed -> same bits).
- * Scratch memory is owned by the library: it is allocated with hipMalloc on the first call on a
- * device and again only when a later call needs more (such a call synchronises that allocation;
- * it must not run under stream capture).  Use hlq_linear_backward_ex with a caller workspace for
- * a call that never allocates.  Calls that share the library workspace must not overlap on one
- * device.
+ * Scratch memory: the workspace registered with hlq_set_workspace for the current device, if any --
+ * the call then allocates nothing, frees nothing and never synchronises, and returns
+ * HLQ_ERR_WORKSPACE (nothing enqueued) when hlq_workspace_bytes(...) exceeds what was registered.
+ * With nothing registered the library owns the scratch: allocated with hipMalloc on the first call
+ * on a device and again only when a later call needs more (such a call synchronises the device and
+ * frees the old buffer: outside any hot path, never under stream capture).
+ * Calls that share a workspace -- registered or library-owned -- must not overlap on one device,
+ * whether from two streams or two host threads.
  */
 int hlq_linear_backward(const void *G, const void *X, const void *W, int64_t N, int64_t d_in,
                         int64_t d_out, int B, int r, uint64_t seed, void *dX, void *dW, void *stream);
@@ -93,7 +110,7 @@ int hlq_linear_backward(const void *G, const void *X, const void *W, int64_t N, 
  *   dX, dW either may be NULL to skip that half (X/XhatT may then be NULL when dW is NULL, and
  *          W may be NULL when dX is NULL).
  *   workspace  device memory of at least hlq_workspace_bytes(...) bytes, 256-byte aligned, or
- *          NULL to use the library-owned workspace described above.
+ *          NULL to use the registered or library-owned workspace described above.
  */
 int hlq_linear_backward_ex(const void *G, const void *X, const void *XhatT, const void *W, int64_t N,
                            int64_t d_in, int64_t d_out, int B, int r, uint64_t seed, int dtype,

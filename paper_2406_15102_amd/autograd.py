@@ -6,9 +6,37 @@ runs in the HIP kernels behind ``binding``.  Nothing here is needed by the libra
 """
 from __future__ import annotations
 
+import itertools
+
 import torch
 
 from . import binding as hlq
+
+_layer_ids = itertools.count(1)
+
+
+def _layer_seed(seed: int) -> int:
+    """A rounding stream of its own for every layer object: the caller's seed plus the layer's
+    number times an odd 64-bit constant (layers built in the same order get the same streams)."""
+    return (int(seed) + next(_layer_ids) * 0x9E3779B97F4A7C15) & 0x7FFFFFFFFFFFFFFF
+
+
+def _backward_workspace(N, d_in, d_out, B, r, flags, device):
+    """Scratch of one backward pass as a torch tensor: the caching allocator orders its reuse on the
+    stream, and the library call then allocates, frees and synchronises nothing."""
+    need = hlq.hlq_workspace_bytes_mode(N, d_in, d_out, B, r, True, flags)
+    if need == 0:
+        raise ValueError("shape (N=%d, d_in=%d, d_out=%d, B=%d, r=%d, flags=%d) is outside the library's rules"
+                         % (N, d_in, d_out, B, r, flags))
+    return torch.empty(need, dtype=torch.uint8, device=device)
+
+
+def _as_grad_dtype(w, dtype):
+    """The weight in the element type of the incoming gradient (autocast hands a bf16 gradient to an
+    fp32 parameter); the library reads every tensor of a call in one element type."""
+    if dtype not in (torch.bfloat16, torch.float32):
+        raise TypeError("gradient dtype must be bfloat16 or float32, got %s" % dtype)
+    return w if w.dtype == dtype else w.to(dtype)
 
 
 class HlqLinearFunction(torch.autograd.Function):
@@ -48,7 +76,11 @@ class HlqLinearFunction(torch.autograd.Function):
         dX = torch.empty((N, d_in), dtype=g2.dtype, device=g2.device) if need_dx else None
         dW = torch.empty((d_out, d_in), dtype=g2.dtype, device=g2.device) if need_dw else None
         if need_dx or need_dw:
-            hlq.hlq_linear_backward_mode(g2, None, xc, sxc, w.contiguous(), N, d_in, d_out, B, r, seed, flags, dX, dW)
+            ws = _backward_workspace(N, d_in, d_out, B, r, flags, g2.device)
+            hlq.hlq_linear_backward_mode(g2, None, xc, sxc, _as_grad_dtype(w, g2.dtype).contiguous(), N, d_in, d_out,
+                                         B, r, seed, flags, dX, dW, ws)
+        if need_dw and dW.dtype != w.dtype:
+            dW = dW.to(w.dtype)
         return (dX.reshape(xshape) if need_dx else None), dW, None, None, None, None
 
 
@@ -58,7 +90,7 @@ class HlqLinear(torch.nn.Module):
     def __init__(self, d_in, d_out, B=16, r=8, flags=0, dtype=torch.bfloat16, device="cuda", seed=0):
         super().__init__()
         self.weight = torch.nn.Parameter(torch.randn((d_out, d_in), dtype=torch.float32, device=device).mul_(0.02).to(dtype))
-        self.B, self.r, self.flags, self.seed, self.calls = B, r, flags, seed, 0
+        self.B, self.r, self.flags, self.seed, self.calls = B, r, flags, _layer_seed(seed), 0
 
     def forward(self, x):
         self.calls += 1
@@ -116,13 +148,14 @@ class HlqConv2dFunction(torch.autograd.Function):
         xc, sxc, w = ctx.saved_tensors
         geom, xshape, N, I, O, B, r, seed, flags, pointwise = ctx.meta
         g2 = gy.permute(0, 2, 3, 1).contiguous().reshape(N, O)
-        w_l = w.permute(0, 2, 3, 1).contiguous().reshape(O, I)
+        w_l = _as_grad_dtype(w, g2.dtype).permute(0, 2, 3, 1).contiguous().reshape(O, I)
         need_dx, need_dw = ctx.needs_input_grad[0], ctx.needs_input_grad[1]
         dcols = torch.empty((N, I), dtype=g2.dtype, device=g2.device) if need_dx else None
         dW = torch.empty((O, I), dtype=g2.dtype, device=g2.device) if need_dw else None
         dX = None
         if need_dx or need_dw:
-            hlq.hlq_linear_backward_mode(g2, None, xc, sxc, w_l, N, I, O, B, r, seed, flags, dcols, dW)
+            ws = _backward_workspace(N, I, O, B, r, flags, g2.device)
+            hlq.hlq_linear_backward_mode(g2, None, xc, sxc, w_l, N, I, O, B, r, seed, flags, dcols, dW, ws)
         if need_dx:
             if pointwise:
                 dX = dcols.reshape(xshape)
@@ -132,6 +165,8 @@ class HlqConv2dFunction(torch.autograd.Function):
             dX = dX.permute(0, 3, 1, 2)                  # [Nb, C, H, W], channels_last strides
         if need_dw:
             dW = dW.reshape(O, geom.kh, geom.kw, geom.C).permute(0, 3, 1, 2)
+            if dW.dtype != w.dtype:
+                dW = dW.to(w.dtype)
         return dX, dW, None, None, None, None, None, None, None
 
 
@@ -147,7 +182,7 @@ class HlqConv2d(torch.nn.Module):
         w = torch.randn((c_out, c_in, kh, kw), dtype=torch.float32, device=device).mul_(std).to(dtype)
         self.weight = torch.nn.Parameter(w.contiguous(memory_format=torch.channels_last))
         self.stride, self.padding, self.dilation = pair(stride), pair(padding), pair(dilation)
-        self.B, self.r, self.flags, self.seed, self.calls = B, r, flags, seed, 0
+        self.B, self.r, self.flags, self.seed, self.calls = B, r, flags, _layer_seed(seed), 0
 
     def forward(self, x):
         self.calls += 1

@@ -38,6 +38,7 @@ _EXPORTS = {
     "hlq_status_str": (C.c_char_p, [C.c_int]),
     "hlq_version": (C.c_int, []),
     "hlq_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int]),
+    "hlq_set_workspace": (C.c_int, [C.c_void_p, C.c_size_t]),
     "hlq_linear_backward": (C.c_int, [C.c_void_p] * 3 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64]
                             + [C.c_void_p] * 3),
     "hlq_linear_backward_ex": (C.c_int, [C.c_void_p] * 4 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64, C.c_int]
@@ -140,6 +141,39 @@ def _ptr(t, dtype=None):
     return C.c_void_p(t.data_ptr())
 
 
+def _expect(name, t, shape, dtype):
+    """Refuse a tensor whose element type or element count is not what the C call will read or
+    write: the library sees only a pointer and would run past the end (or read bf16 bits as fp32)."""
+    if t is None:
+        return
+    if t.dtype != dtype:
+        raise TypeError("%s must be %s like the gradient, got %s" % (name, dtype, t.dtype))
+    n = 1
+    for d in shape:
+        n *= int(d)
+    if t.numel() != n:
+        raise ValueError("%s must hold %s = %d elements, has %d" % (name, "x".join(str(int(d)) for d in shape), n, t.numel()))
+
+
+def _expect_backward(G, X, W, dX, dW, N, d_in, d_out):
+    dt = G.dtype
+    _expect("G", G, (N, d_out), dt)
+    _expect("X", X, (N, d_in), dt)
+    _expect("W", W, (d_out, d_in), dt)
+    _expect("dX", dX, (N, d_in), dt)
+    _expect("dW", dW, (d_out, d_in), dt)
+
+
+def _expect_store(Xc, sXc, d_in, Kc, flags):
+    if Xc is None:
+        return
+    if flags & HLQ_FLAG_GW_INT8:
+        _expect("Xc", Xc, (d_in, Kc), torch.int8)
+        _expect("sXc", sXc, (d_in,), torch.float32)
+    else:
+        _expect("Xc", Xc, (d_in, Kc), torch.bfloat16)
+
+
 def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -161,8 +195,17 @@ def hlq_workspace_bytes(N, d_in, d_out, B, r, x_is_compressed=False) -> int:
     return int(lib().hlq_workspace_bytes(N, d_in, d_out, B, r, int(bool(x_is_compressed))))
 
 
+def hlq_set_workspace(workspace):
+    """Register `workspace` (a uint8 CUDA tensor the caller keeps alive) as the scratch of every call
+    on the current device that passes none; None withdraws it."""
+    if workspace is None:
+        _check(lib().hlq_set_workspace(None, 0), "hlq_set_workspace")
+    else:
+        _check(lib().hlq_set_workspace(_ptr(workspace), _nbytes(workspace)), "hlq_set_workspace")
+
+
 def hlq_linear_backward(G, X, W, B, r, seed, dX, dW):
-    """dX, dW <- HLQ backward of one bf16 layer (library-owned workspace)."""
+    """dX, dW <- HLQ backward of one bf16 layer (registered or library-owned workspace)."""
     N, d_out = G.shape
     d_in = W.shape[1]
     for t in (G, X, W, dX, dW):
@@ -175,6 +218,8 @@ def hlq_linear_backward(G, X, W, B, r, seed, dX, dW):
 def hlq_linear_backward_ex(G, X, XhatT, W, N, d_in, d_out, B, r, seed, dX, dW, workspace=None):
     """Full-option call; any of X / XhatT / W / dX / dW may be None as hlq.h allows."""
     dt = _dt(G)
+    _expect_backward(G, X, W, dX, dW, N, d_in, d_out)
+    _expect_store(XhatT, None, d_in, N // B * r, 0)
     ws_ptr, ws_bytes = (None, 0) if workspace is None else (_ptr(workspace), workspace.numel() * workspace.element_size())
     _check(lib().hlq_linear_backward_ex(_ptr(G), _ptr(X), _ptr(XhatT), _ptr(W), N, d_in, d_out, B, r, seed, dt,
                                         _ptr(dX), _ptr(dW), ws_ptr, ws_bytes, _stream()), "hlq_linear_backward_ex")
@@ -284,6 +329,8 @@ def hlq_workspace_bytes_mode(N, d_in, d_out, B, r, x_is_compressed=False, flags=
 
 def hlq_linear_backward_mode(G, X, Xc, sXc, W, N, d_in, d_out, B, r, seed, flags, dX, dW, workspace=None):
     """hlq_linear_backward_ex with HLQ_FLAG_GX_8BIT / HLQ_FLAG_GW_INT8."""
+    _expect_backward(G, X, W, dX, dW, N, d_in, d_out)
+    _expect_store(Xc, sXc, d_in, N // B * r, flags)
     ws_ptr, ws_bytes = (None, 0) if workspace is None else (_ptr(workspace), _nbytes(workspace))
     _check(lib().hlq_linear_backward_mode(_ptr(G), _ptr(X), _ptr(Xc), _ptr(sXc, torch.float32), _ptr(W), N, d_in,
                                           d_out, B, r, seed, _dt(G), flags, _ptr(dX), _ptr(dW), ws_ptr, ws_bytes,
@@ -296,6 +343,8 @@ def hlq_weight_code_bits(d_out, flags) -> int:
 
 def hlq_linear_backward_cached(G, X, Xc, sXc, WqT, sW, N, d_in, d_out, B, r, seed, flags, dX, dW, workspace=None):
     """hlq_linear_backward_mode with the weight codes of hlq_quantize_w handed over."""
+    _expect_backward(G, X, None, dX, dW, N, d_in, d_out)
+    _expect_store(Xc, sXc, d_in, N // B * r, flags)
     ws_ptr, ws_bytes = (None, 0) if workspace is None else (_ptr(workspace), _nbytes(workspace))
     _check(lib().hlq_linear_backward_cached(_ptr(G), _ptr(X), _ptr(Xc), _ptr(sXc, torch.float32), _ptr(WqT),
                                             _ptr(sW, torch.float32), N, d_in, d_out, B, r, seed, _dt(G), flags,

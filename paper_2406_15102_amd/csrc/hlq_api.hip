@@ -138,17 +138,39 @@ inline bool bits_ok(int bits)
 inline float bits_qmax(int bits) { return bits_base(bits) == HLQ_BITS_8 ? 127.0f : 7.0f; }
 inline bool bits_packed(int bits) { return bits_base(bits) == HLQ_BITS_4_PACKED; }
 
-// Library-owned workspace, one per device, grown on demand.
+// Workspace of the calls that pass none: per device, either the memory the caller registered with
+// hlq_set_workspace (never allocated, freed or synchronised here), or a library-owned buffer grown on
+// demand.
 constexpr int kMaxDevices = 64;
 std::mutex g_ws_mutex;
 void *g_ws_ptr[kMaxDevices] = {nullptr};
 size_t g_ws_bytes[kMaxDevices] = {0};
+void *g_user_ws_ptr[kMaxDevices] = {nullptr};
+size_t g_user_ws_bytes[kMaxDevices] = {0};
+
+// the device the calling thread has current; 0 where no device can be asked (argument checks on a
+// machine without a GPU must still come out with their status)
+int current_device()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return dev;
+}
 
 int own_workspace(size_t bytes, void **out)
 {
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HLQ_ERR_WORKSPACE;
+    const int dev = current_device();
+    if (dev < 0 || dev >= kMaxDevices) return HLQ_ERR_WORKSPACE;
     std::lock_guard<std::mutex> lock(g_ws_mutex);
+    if (g_user_ws_ptr[dev]) {
+        // registered by the caller: use it or refuse; nothing is allocated, freed or waited for
+        if (g_user_ws_bytes[dev] < bytes) return HLQ_ERR_WORKSPACE;
+        *out = g_user_ws_ptr[dev];
+        return HLQ_OK;
+    }
     if (g_ws_bytes[dev] < bytes) {
         if (g_ws_ptr[dev]) {
             // earlier calls may still be running on the old buffer
@@ -190,7 +212,18 @@ const char *hlq_status_str(int status)
     return "HLQ: unknown status";
 }
 
-int hlq_version(void) { return 100; }
+int hlq_version(void) { return 200; }
+
+int hlq_set_workspace(void *dev_ptr, size_t bytes)
+{
+    if (dev_ptr && (!aligned(dev_ptr, 256) || bytes == 0)) return HLQ_ERR_WORKSPACE;
+    const int dev = current_device();
+    if (dev < 0 || dev >= kMaxDevices) return HLQ_ERR_WORKSPACE;
+    std::lock_guard<std::mutex> lock(g_ws_mutex);
+    g_user_ws_ptr[dev] = dev_ptr;
+    g_user_ws_bytes[dev] = dev_ptr ? bytes : 0;
+    return HLQ_OK;
+}
 
 size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r, int x_is_compressed)
 {

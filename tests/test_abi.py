@@ -218,3 +218,37 @@ def test_products_entry_point_without_a_gpu():
     assert hlq.hlq_backward_products_workspace_bytes(50176, 432, 96, 25088, 0x104) > 0    # few tiles, long reduction
     assert hlq.hlq_backward_products_workspace_bytes(4096, 4096, 11008, 2048, 0x104) == 0
     assert hlq.hlq_backward_products_workspace_bytes(4096, 4096, 11008, 2048, 7) == 0
+
+
+def test_set_workspace_rejects_and_bounds_the_plain_call_without_a_gpu():
+    """A registered workspace is used or refused, never replaced by an allocation: with one that is
+    too small the plain 12-argument call comes back with HLQ_ERR_WORKSPACE before anything is launched."""
+    sw = hlq.lib().hlq_set_workspace
+    try:
+        assert sw(C.c_void_p(0x10010), 1 << 20) == 6            # not 256-byte aligned
+        assert sw(FAKE, 0) == 6                                 # a pointer without a size
+        assert sw(FAKE, 1000) == 0
+        assert _bw() == 6                                       # 1000 bytes cannot hold this layer's scratch
+        f = hlq.lib().hlq_linear_backward_ex                    # the same through a NULL workspace argument
+        assert f(FAKE, FAKE, None, FAKE, 256, 256, 256, 16, 8, 0, 0, FAKE, FAKE, None, 0, None) == 6
+        assert _bw(B=8) == 3                                    # argument checks still come first
+    finally:
+        assert sw(None, 0) == 0                                 # withdrawn: back to the library-owned scratch
+
+
+def test_binding_refuses_mismatched_tensors():
+    """The binding checks element type and element count of every tensor against the gradient's: an
+    fp32 weight beside a bf16 gradient, or a tensor shorter than the stated sizes, must not reach
+    the library (which sees only pointers)."""
+    import torch
+    g = torch.empty((32, 64), dtype=torch.bfloat16)
+    x = torch.empty((32, 16), dtype=torch.bfloat16)
+    w32 = torch.empty((64, 16), dtype=torch.float32)
+    with pytest.raises(TypeError):
+        binding._expect_backward(g, x, w32, None, None, 32, 16, 64)
+    w = torch.empty((64, 8), dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        binding._expect_backward(g, x, w, None, None, 32, 16, 64)
+    with pytest.raises(TypeError):
+        binding._expect_store(torch.empty((16, 16), dtype=torch.bfloat16), None, 16, 16, binding.HLQ_FLAG_GW_INT8)
+    binding._expect_backward(g, x, torch.empty((64, 16), dtype=torch.bfloat16), None, None, 32, 16, 64)

@@ -78,3 +78,36 @@ def test_convolution_module_trains_a_step():
     a, b = conv.weight.grad.float().flatten(), gw.float().flatten()
     assert torch.isfinite(a).all() and float(torch.dot(a, b) / (a.norm() * b.norm())) > 0.3
     assert x.grad is not None and x.grad.shape == x.shape and torch.isfinite(x.grad.float()).all()
+
+
+def test_fp32_weight_with_bf16_gradient_is_cast_not_misread():
+    """Under autocast the gradient arrives in bf16 while the parameter is fp32: the wrapper hands the
+    library a bf16 copy of the weight (it reads every tensor of a call in one element type) and
+    returns the weight gradient in the parameter's type."""
+    w_ = wl.scaled(wl.WORKLOADS["c2"], N=512, d_in=264, d_out=256)
+    t = wl.generate(w_)
+    G, X, W = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
+    N, I, O, B, r = w_.N, w_.d_in, w_.d_out, w_.B, w_.r
+    w32 = W.float().clone()                               # exactly the bf16 values, held in fp32
+
+    xc = torch.empty((I, N // B * r), dtype=torch.bfloat16, device=DEV)
+    hlq.hlq_compress_act(X, B, r, xc)
+    ctx = type("Ctx", (), {})()
+    ctx.saved_tensors = (xc, None, w32)
+    ctx.meta = (X.shape, N, I, O, B, r, 11, 0)
+    ctx.needs_input_grad = (True, True, False, False, False, False)
+    dx, dw = HlqLinearFunction.backward(ctx, G)[:2]
+    dX = torch.empty((N, I), dtype=torch.bfloat16, device=DEV)
+    dW = torch.empty((O, I), dtype=torch.bfloat16, device=DEV)
+    hlq.hlq_linear_backward_mode(G, X, None, None, W, N, I, O, B, r, 11, 0, dX, dW)
+    torch.cuda.synchronize()
+    assert dw.dtype == torch.float32 and torch.equal(dw, dW.float())
+    assert torch.equal(dx, dX)
+    with pytest.raises(TypeError):
+        hlq.hlq_linear_backward_mode(G, X, None, None, W.float(), N, I, O, B, r, 11, 0, dX, dW)
+
+
+def test_layers_draw_different_rounding_streams():
+    a = HlqLinear(64, 64, device=DEV)
+    b = HlqLinear(64, 64, device=DEV)
+    assert a.seed != b.seed

@@ -76,7 +76,7 @@ def test_full_size_workload_sampled(name):
     acc = oracle.int_gemm_nt(gq_s, ref_Wq)
     assert np.max(np.abs(acc)) <= 49 * O
     ref_dX = oracle.dequant(acc, sg_s, ref_sW, B)
-    ex = row_rel_err(dX[torch.from_numpy(rows).to(DEV)].float().cpu().numpy(), ref_dX, True)
+    ex = row_rel_err(dX[torch.from_numpy(rows).to(DEV)].float().cpu().numpy(), ref_dX, True, label=name + " dX")
     del ref_Gq, ref_Wq
 
     # ---- dW on sampled out-feature rows ----
@@ -95,7 +95,7 @@ def test_full_size_workload_sampled(name):
     orows = _sample(O, 12, [0, 1, 127, 128, 255, 256, O - 257, O - 1], seed=2)
     gh = oracle.round_bf16(oracle.hla_f32(np.ascontiguousarray(Gn[:, orows]), B, r))
     ref_dW = oracle.gemm_nt_f64(gh, xh, 1.0 / B)
-    ew = row_rel_err(dW[torch.from_numpy(orows).to(DEV)].float().cpu().numpy(), ref_dW, True)
+    ew = row_rel_err(dW[torch.from_numpy(orows).to(DEV)].float().cpu().numpy(), ref_dW, True, label=name + " dW")
     print("%s: dX err %.3e (%d rows)  dW err %.3e (%d rows)" % (name, ex, len(rows), ew, len(orows)))
     assert ex < TOL_OUT and ew < TOL_OUT
 
