@@ -73,6 +73,17 @@ int hlq_version(void);
 size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r, int x_is_compressed);
 
 /*
+ * Process-wide switches, for measurements (every setting computes the same results).
+ *   HLQ_OPT_PERSISTENT_PRODUCTS  1 (default): layers whose matrix products (Sec. 6.1, g_x stages 5-6
+ *       and g_w stage 5) come to at least four 256 x 256 tiles per compute unit run them as one
+ *       persistent launch, a workgroup per compute unit walking a fixed list of tiles and loading
+ *       across tile boundaries;  0: always one workgroup per tile.
+ * Unknown option: HLQ_ERR_SHAPE.  Not synchronised with calls running on other host threads.
+ */
+#define HLQ_OPT_PERSISTENT_PRODUCTS 1
+int hlq_set_option(int option, int value);
+
+/*
  * Registers caller-owned device memory as the scratch of every call on the CURRENT device that is
  * given no workspace of its own (hlq_linear_backward, and the entry points below when their
  * `workspace` is NULL): the layer of Sec. 3.1, Eq. 1 then runs through the plain signature without
@@ -303,9 +314,12 @@ int hlq_linear_backward_cached(const void *G, const void *X, const void *Xc, con
 
 /*
  * Diagnostic, not part of the backward pass: `blocks` workgroups of four wavefronts each issue
- * iters * 8 independent 32x32 MFMAs from registers (kind 0: int8, K = 32, 65536 ops each;
- * kind 1: bf16, K = 16, 32768 flops each).  Timing it gives the MFMA rate the chip sustains at
- * its running clock, the practical ceiling for the two matrix products of Sec. 6.1.
+ * iters * 8 independent MFMAs from registers (kind 0: int8 32x32x32 on random bytes, 65536 ops each;
+ * kind 1: bf16 32x32x16, 32768 flops each; 2, 3, 4: fp8, fp6, fp4 32x32x64; 5: bf16 16x16x32, 16384
+ * flops each; 6: int8 16x16x64, 32768 ops each; 7, 8: int8 32x32x32 on 4-bit codes times 16 -- what
+ * the packed-code product feeds -- and on the codes as small integers).  Timing it gives the MFMA
+ * rate the chip sustains at its running clock for that shape and operand pattern, the practical
+ * ceiling for the two matrix products of Sec. 6.1; kind outside 0..8: HLQ_ERR_SHAPE.
  * sink: one device float (never written in practice; keeps the loop alive).
  */
 int hlq_mfma_probe(int kind, int blocks, int iters, float *sink, void *stream);

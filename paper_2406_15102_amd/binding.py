@@ -39,6 +39,7 @@ _EXPORTS = {
     "hlq_version": (C.c_int, []),
     "hlq_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int]),
     "hlq_set_workspace": (C.c_int, [C.c_void_p, C.c_size_t]),
+    "hlq_set_option": (C.c_int, [C.c_int, C.c_int]),
     "hlq_linear_backward": (C.c_int, [C.c_void_p] * 3 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64]
                             + [C.c_void_p] * 3),
     "hlq_linear_backward_ex": (C.c_int, [C.c_void_p] * 4 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64, C.c_int]
@@ -193,6 +194,13 @@ def hlq_status_str(status: int) -> str:
 
 def hlq_workspace_bytes(N, d_in, d_out, B, r, x_is_compressed=False) -> int:
     return int(lib().hlq_workspace_bytes(N, d_in, d_out, B, r, int(bool(x_is_compressed))))
+
+
+HLQ_OPT_PERSISTENT_PRODUCTS = 1
+
+
+def hlq_set_option(option, value):
+    _check(lib().hlq_set_option(int(option), int(value)), "hlq_set_option")
 
 
 def hlq_set_workspace(workspace):

@@ -214,6 +214,13 @@ const char *hlq_status_str(int status)
 
 int hlq_version(void) { return 200; }
 
+int hlq_set_option(int option, int value)
+{
+    if (option != HLQ_OPT_PERSISTENT_PRODUCTS) return HLQ_ERR_SHAPE;
+    hlq::gemm_stream_enable(value != 0);
+    return HLQ_OK;
+}
+
 int hlq_set_workspace(void *dev_ptr, size_t bytes)
 {
     if (dev_ptr && (!aligned(dev_ptr, 256) || bytes == 0)) return HLQ_ERR_WORKSPACE;
@@ -425,7 +432,7 @@ int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64
 int hlq_mfma_probe(int kind, int blocks, int iters, float *sink, void *stream)
 {
     if (!sink) return HLQ_ERR_NULL;
-    if (kind < 0 || kind > 4 || blocks <= 0 || blocks > (1 << 20) || iters <= 0) return HLQ_ERR_SHAPE;
+    if (kind < 0 || kind > 8 || blocks <= 0 || blocks > (1 << 20) || iters <= 0) return HLQ_ERR_SHAPE;
     return launch_rc(hlq::launch_mfma_probe(kind, blocks, iters, sink, static_cast<hipStream_t>(stream)));
 }
 

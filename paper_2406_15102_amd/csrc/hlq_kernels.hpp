@@ -197,6 +197,14 @@ bool gemm_pair_available(int kindA, const GemmArgs &a, int kindB, const GemmArgs
 // defer: if not null and b's k is split, the reduction is not launched but described there (blocks > 0).
 hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, hipStream_t st,
                             SplitReduce *defer = nullptr);
+// The products as ONE persistent launch (k_gemm_stream.hip): a workgroup per compute unit walks a
+// fixed list of 256 x 256 tiles of `a`, then of `b` (NULL: one product only), loading across tile
+// boundaries.  Same bits as launch_gemm_nt without a k split.  gemm_stream_wanted: the shapes allow it
+// (bf16 output, whole k steps, at least four tiles per compute unit in all) and it has not been
+// switched off; callers ask it after their plan has chosen 256-tiles and no k split.
+bool gemm_stream_wanted(int kindA, const GemmArgs &a, int kindB, const GemmArgs *b);
+hipError_t launch_gemm_stream(int kindA, const GemmArgs &a, int kindB, const GemmArgs *b, hipStream_t st);
+void gemm_stream_enable(bool on);
 // split-k scratch (b.ws) that the pair's plan would use if it may have up to `cap` bytes; only the
 // shapes and kinds of a and b are read
 size_t gemm_pair_ws_bytes(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, size_t cap);

@@ -126,6 +126,7 @@ hipError_t launch_gemm_nt(int kind, const GemmArgs &a, hipStream_t st)
 {
     const bool can_split = a.ws != nullptr && a.C != nullptr && (reinterpret_cast<uintptr_t>(a.ws) & 15) == 0;
     const GemmPlan p = plan_for(kind, a.M, a.N, a.K, a.ws_bytes, can_split);
+    if (p.big && p.splits == 1 && gemm_stream_wanted(kind, a, 0, nullptr)) return launch_gemm_stream(kind, a, 0, nullptr, st);
     if (kind == 0) return p.big ? launch_t<0, 4, 4, 8>(a, p.splits, st) : launch_t<0, 2, 2, 8>(a, p.splits, st);
     if (kind == 2) return p.big ? launch_t<2, 4, 4, 8>(a, p.splits, st) : launch_t<2, 2, 2, 8>(a, p.splits, st);
     return p.big ? launch_t<1, 4, 4, 8>(a, p.splits, st) : launch_t<1, 2, 2, 8>(a, p.splits, st);

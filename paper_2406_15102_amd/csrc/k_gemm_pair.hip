@@ -132,6 +132,8 @@ hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmA
     if (!gemm_pair_available(kindA, a, kindB, b)) return hipErrorInvalidValue;
     const bool can_split = b.ws != nullptr && (reinterpret_cast<uintptr_t>(b.ws) & 15) == 0;
     const PairPlan p = plan_pair(a, kindA, b, kindB, can_split ? b.ws_bytes : 0);
+    if (p.bigA && p.bigB && p.splitsB == 1 && gemm_stream_wanted(kindA, a, kindB, &b))
+        return launch_gemm_stream(kindA, a, kindB, &b, st);
     const GemmDev ga = gemm_dev(kindA, a, p.bigA ? 256 : 128, p.bigA ? 256 : 128, 1);
     const GemmDev gb = gemm_dev(kindB, b, p.bigB ? 256 : 128, p.bigB ? 256 : 128, p.splitsB);
     const int outB = p.splitsB > 1 ? 3 : (b.c_is_f32 ? 1 : 0);
