@@ -176,6 +176,19 @@ int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t s
                    void *stream);
 
 /*
+ * hlq_quantize_w for callers that cannot allocate device memory and have no scratch to hand over:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and results (WqT, sW bit for bit) minus coeffT and the workspace: the column maxima
+ * live in a 256 KiB array inside the library's code object (one copy per GPU, kept until the
+ * process ends).  Nothing is allocated or freed, by this call or by anything it calls.
+ *   d_in <= 65536 (the array's size); beyond that HLQ_ERR_WORKSPACE, nothing enqueued.
+ * Every call on a GPU uses that GPU's one array (zeroed by a fill kernel at the start of each call):
+ * calls that overlap on one GPU -- two streams, two threads -- race; keep them on one stream.
+ */
+int hlq_quantize_w_static(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t seed, int dtype, int bits,
+                          int8_t *WqT, float *sW, void *stream);
+
+/*
  * Stages 5-6 of the g_x list: C[m, n] = alpha * sA[m] * sB[n] * sum_k A[m,k] * Bm[n,k], the sum
  * exact in int32 (int8 MFMA).  A [M, K] int8, Bm [Nn, K] int8 with |value| <= 127, K % 16 == 0,
  * K <= 131072 (so that 127 * 127 * K fits int32), Nn % 4 == 0.

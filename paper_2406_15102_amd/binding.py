@@ -40,6 +40,8 @@ _EXPORTS = {
     "hlq_workspace_bytes": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int]),
     "hlq_set_workspace": (C.c_int, [C.c_void_p, C.c_size_t]),
     "hlq_set_option": (C.c_int, [C.c_int, C.c_int]),
+    "hlq_quantize_w_static": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_uint64, C.c_int, C.c_int, C.c_void_p,
+                                        C.c_void_p, C.c_void_p]),
     "hlq_linear_backward": (C.c_int, [C.c_void_p] * 3 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64]
                             + [C.c_void_p] * 3),
     "hlq_linear_backward_ex": (C.c_int, [C.c_void_p] * 4 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64, C.c_int]
@@ -260,6 +262,13 @@ def hlq_quantize_w(W, B, seed, WqT, sW, workspace, coeffT=None, bits=4):
     _check(lib().hlq_quantize_w(_ptr(W), d_out, d_in, B, seed, _dt(W), bits, _codes_ptr(WqT), _ptr(sW, torch.float32),
                                 _ptr(coeffT, torch.float32), _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream()), "hlq_quantize_w")
+
+
+def hlq_quantize_w_static(W, B, seed, WqT, sW, bits=4):
+    """hlq_quantize_w on the library's static scratch (no workspace, nothing allocated)."""
+    d_out, d_in = W.shape
+    _check(lib().hlq_quantize_w_static(_ptr(W), d_out, d_in, B, seed, _dt(W), bits, _codes_ptr(WqT),
+                                       _ptr(sW, torch.float32), _stream()), "hlq_quantize_w_static")
 
 
 def _ws(workspace):

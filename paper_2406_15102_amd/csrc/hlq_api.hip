@@ -288,6 +288,31 @@ int hlq_quantize_w(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t s
                                             static_cast<hipStream_t>(stream)));
 }
 
+int hlq_quantize_w_static(const void *W, int64_t d_out, int64_t d_in, int B, uint64_t seed, int dtype, int bits,
+                          int8_t *WqT, float *sW, void *stream)
+{
+    int rc;
+    if (!W || !WqT || !sW) return HLQ_ERR_NULL;
+    if ((rc = check_block(B)) != HLQ_OK) return rc;
+    if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if (!bits_ok(bits)) return HLQ_ERR_DTYPE;
+    if (d_in <= 0 || d_in % 8 != 0) return HLQ_ERR_SHAPE;
+    if ((rc = check_quant_shape(d_in, d_out, B)) != HLQ_OK) return rc;
+    if (bits_packed(bits) && d_out % 32 != 0) return HLQ_ERR_SHAPE;
+    if (!aligned(W, 16) || !aligned(WqT, 16)) return HLQ_ERR_SHAPE;
+    if (d_in > hlq::kQuantColsStaticMaxI) return HLQ_ERR_WORKSPACE;   // beyond the library's static scratch
+    void *ws = nullptr;
+    if (hlq::quant_cols_static_scratch(&ws) != hipSuccess) {
+        (void)hipGetLastError();
+        return HLQ_ERR_WORKSPACE;
+    }
+    const uint64_t key = stream_key(seed, 1);
+    return launch_rc(hlq::launch_quant_cols(W, static_cast<int>(d_out), static_cast<int>(d_in), B, dtype == HLQ_F32,
+                                            static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32),
+                                            bits_qmax(bits), bits_packed(bits), bits_mant(bits), WqT, sW, nullptr, ws,
+                                            static_cast<hipStream_t>(stream)));
+}
+
 size_t hlq_gemm_workspace_bytes(int kind, int64_t M, int64_t Nn, int64_t K)
 {
     if (kind < 0 || kind > 2 || check_gemm_shape(M, Nn, K, kind == 0 ? 16 : (kind == 1 ? 8 : 32)) != HLQ_OK) return 0;

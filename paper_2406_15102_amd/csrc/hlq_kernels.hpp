@@ -20,6 +20,12 @@ hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, ui
                              float qmax, bool packed, bool mant, int8_t *WqT, float *sW, float *coeffT, void *ws,
                              hipStream_t st);
 
+// The same scratch as a file-scope device array inside the library (k_quant_cols.hip), for callers that
+// cannot allocate: room for the column maxima of a weight with up to kQuantColsStaticMaxI in-features
+// (256 KiB per GPU).  Returns the array's address on the current device (asked for once per device).
+constexpr int kQuantColsStaticMaxI = 65536;
+hipError_t quant_cols_static_scratch(void **ptr);
+
 // Shape of a workgroup of K1T's two passes, as for K3: B lanes side by side (runs of 256 B of a row
 // of bf16) times 256/B row blocks, whose codes are neighbours in a row of the transposed output
 // (runs of 256 bytes, 128 packed).

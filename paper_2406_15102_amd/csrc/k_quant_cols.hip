@@ -18,6 +18,8 @@
 #include "quant_cols_body.hpp"
 #include "hlq_kernels.hpp"
 
+#include <mutex>
+
 namespace hlq {
 
 __global__ __launch_bounds__(256) void k_fill_u32(uint32_t *p, int n, uint32_t value)
@@ -112,6 +114,32 @@ hipError_t launch_quant_cols(const void *W, int O, int I, int B, bool is_f32, ui
 #undef HLQ_COLS_CASE
     if (e != hipSuccess) return e;
     return launch_quant_cols_pass2(W, O, I, B, is_f32, k0, k1, qmax, packed, mant, WqT, sW, coeffT, ws, st);
+}
+
+// ---- scratch for callers that cannot allocate -------------------------------------------------
+// The column maxima of launch_quant_cols in device memory that belongs to the code object: one
+// copy per GPU the library runs on, held until the process ends.  On the host the array's name is
+// only a handle: its device address is asked for once per device and kept.
+static __device__ __align__(256) __attribute__((used)) uint32_t scratch[kQuantColsStaticMaxI];
+
+hipError_t quant_cols_static_scratch(void **ptr)
+{
+    static std::mutex mtx;
+    static void *addr[64] = {nullptr};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mtx);
+    if (!addr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        addr[dev] = p;
+    }
+    *ptr = addr[dev];
+    return hipSuccess;
 }
 
 }  // namespace hlq

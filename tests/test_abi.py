@@ -236,6 +236,18 @@ def test_set_workspace_rejects_and_bounds_the_plain_call_without_a_gpu():
         assert sw(None, 0) == 0                                 # withdrawn: back to the library-owned scratch
 
 
+def test_static_scratch_entry_point_rejects_bad_arguments_without_a_gpu():
+    f = hlq.lib().hlq_quantize_w_static
+
+    def call(W=FAKE, d_out=256, d_in=256, B=16, dt=0, bits=4, WqT=FAKE, sW=FAKE):
+        return f(W, d_out, d_in, B, 0, dt, bits, WqT, sW, None)
+
+    assert call(W=None) == 1 and call(WqT=None) == 1 and call(sW=None) == 1
+    assert call(B=8) == 3 and call(dt=5) == 5 and call(bits=3) == 5
+    assert call(d_in=100) == 2 and call(d_out=250) == 2
+    assert call(d_in=65536 + 8, d_out=64) == 6                  # beyond the static array: refused, not allocated
+
+
 def test_binding_refuses_mismatched_tensors():
     """The binding checks element type and element count of every tensor against the gradient's: an
     fp32 weight beside a bf16 gradient, or a tensor shorter than the stated sizes, must not reach
