@@ -100,6 +100,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="c4")
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the CPU-oracle sample (0 = skip)")
+    ap.add_argument("--only-path", action="store_true",
+                    help="time the whole path only and print a short JSON line (what a counter profile wants to see)")
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=0|1",
+                    help="library switch for A/B runs: persistent=0|1 (persistent matrix products), "
+                         "shared_g=0|1 (K1 and K3 share one read of G)")
     ap.add_argument("--no-modes", action="store_true",
                     help="skip the extra whole-path timings of the method's options (keeps a profile to the default path)")
     args = ap.parse_args()
@@ -114,6 +119,10 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     hlq.lib()  # fail loudly if the HIP library is missing
+    for item in args.option:
+        name, _, val = item.partition("=")
+        key = {"persistent": hlq.HLQ_OPT_PERSISTENT_PRODUCTS, "shared_g": hlq.HLQ_OPT_SHARED_G_READ}[name]
+        hlq.hlq_set_option(key, int(val))
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = wl.WORKLOADS[args.workload]
@@ -139,6 +148,11 @@ def main():
     torch.cuda.synchronize()
     wall_us = (time.perf_counter() - t0) * 1e6 / args.steps
     hlq_us = _event_time_us(step, args.steps, torch, warm=args.warmup // 2)
+    if args.only_path:
+        print(json.dumps({"metric": "hlq_backward_dX_dW_latency", "value": round(hlq_us, 2), "unit": "us",
+                          "workload": w.name, "steps": args.steps, "warmup": args.warmup, "options": args.option,
+                          "wall_us_per_step": round(wall_us, 2)}))
+        return
 
     # ---- median and minimum of single steps (an event pair per step) ----
     n_stat = min(args.steps, 100)

@@ -78,9 +78,15 @@ size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r,
  *       and g_w stage 5) come to at least four 256 x 256 tiles per compute unit run them as one
  *       persistent launch, a workgroup per compute unit walking a fixed list of tiles and loading
  *       across tile boundaries;  0: always one workgroup per tile.
+ *   HLQ_OPT_SHARED_G_READ  1: for a large G, the workgroups that quantise a group of 64 rows of
+ *       G (g_x stages 1-2) and those that project the same rows along the tokens (g_w stage 3) are
+ *       dispatched next to one another on one XCD, so that the second reader finds the rows in that
+ *       XCD's L2 and G comes from memory once (half the fetched bytes of that launch, but measured slower: the
+ *       launch is not bound by bytes);  0 (default): each stage's workgroups keep their own index range.
  * Unknown option: HLQ_ERR_SHAPE.  Not synchronised with calls running on other host threads.
  */
 #define HLQ_OPT_PERSISTENT_PRODUCTS 1
+#define HLQ_OPT_SHARED_G_READ 2
 int hlq_set_option(int option, int value);
 
 /*

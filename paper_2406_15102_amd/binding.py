@@ -199,6 +199,7 @@ def hlq_workspace_bytes(N, d_in, d_out, B, r, x_is_compressed=False) -> int:
 
 
 HLQ_OPT_PERSISTENT_PRODUCTS = 1
+HLQ_OPT_SHARED_G_READ = 2
 
 
 def hlq_set_option(option, value):

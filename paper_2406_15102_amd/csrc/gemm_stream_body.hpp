@@ -184,8 +184,8 @@ __device__ __forceinline__ void gemm_stream_product(const GemmDev &g, const int 
     {                                                                                                         \
         int lm0, ln0;                                                                                         \
         HLQ_TILE_OF(T, lm0, ln0)                                                                              \
-        ldA = g.A + static_cast<int64_t>(lm0) * g.Kb;                                                         \
-        ldB = g.Bm + static_cast<int64_t>(ln0) * g.Kb;                                                        \
+        ldA = g.A + static_cast<int64_t>(lm0) * g.Kb;                                            \
+        ldB = g.Bm + static_cast<int64_t>(ln0) * g.Kb;                                           \
         _Pragma("unroll") for (int i = 0; i < PA; ++i) {                                                      \
             const int row = lr + RPP * i;                                                                     \
             offa[i] = static_cast<uint32_t>(lm0 + row < g.M ? row : 0) * static_cast<uint32_t>(g.Kb) + lc * 16u; \

@@ -67,12 +67,16 @@ __device__ __forceinline__ void hla_job_map(int l, int gx, int grp, int &bx, int
     by = grp * (u / gx) + t % grp;
 }
 
-template <int B, int BASIS, typename Src>
+// LM: lanes side by side as a multiple of hla_lanes(B) -- 1 for the stand-alone shape (B lanes x 256/B token
+// blocks), 4 for the workgroups that share their rows of G with K1 in the last-level-cache-free front
+// launch (4 B lanes = 512 columns x 64/B token blocks = 64 rows).
+template <int B, int BASIS, typename Src, int LM = 1>
 __device__ __forceinline__ void hla_body_src(const Src &src, int64_t N, int D, int r, bf16_t *__restrict__ ThatT,
                                              float *__restrict__ coeffT, int bx, int by)
 {
     constexpr int CPL = 128 / B;
-    constexpr int L = hla_lanes(B), NB = hla_blocks(B);
+    constexpr int L = hla_lanes(B) * LM, NB = 256 / L;
+    static_assert(NB >= 1 && L * NB == 256, "a K3 workgroup is 256 lanes");
     const int tid = threadIdx.x;
     const int col0 = (bx * L + tid % L) * CPL;
     const int64_t nblk = N / B;
@@ -116,11 +120,11 @@ __device__ __forceinline__ void hla_body_src(const Src &src, int64_t N, int D, i
     }
 }
 
-template <typename Tin, int B, int BASIS>
+template <typename Tin, int B, int BASIS, int LM = 1>
 __device__ __forceinline__ void hla_body(const Tin *__restrict__ T, int64_t N, int D, int r, bf16_t *__restrict__ ThatT,
                                          float *__restrict__ coeffT, int bx, int by)
 {
-    hla_body_src<B, BASIS>(DenseRows<Tin>{T, D}, N, D, r, ThatT, coeffT, bx, by);
+    hla_body_src<B, BASIS, DenseRows<Tin>, LM>(DenseRows<Tin>{T, D}, N, D, r, ThatT, coeffT, bx, by);
 }
 
 // ---- integer g_w list: pass 1 (column maxima of the kept coefficients) and pass 2 (int8 codes) ----

@@ -96,6 +96,19 @@ inline int hla_job_blocks(int gx, int gy, int grp)
     const int units = gx * ((gy + grp - 1) / grp);
     return 8 * grp * ((units + 7) / 8);
 }
+// K1(G) and K3(G) of one launch sharing ONE read of G from memory: rows of G go through in groups of
+// 64; the workgroups of a group -- its K1 rows, then its K3 strips of 512 columns -- sit next to one
+// another in the index sequence of ONE XCD (index mod 8), so that whichever of the two readers of a row
+// comes second finds it in that XCD's L2.  `pair` consecutive groups (the ones whose K3 output pieces
+// complete a 128-byte line) go to the same XCD back to back.  on == 0: the jobs keep their own ranges.
+struct FrontShare {
+    int on;
+    int nk1;      // K1 workgroups per group of 64 rows
+    int gx;       // K3 workgroups per group (strips of 512 columns)
+    int pair;     // groups per unit handed to an XCD
+    int units;    // units in all
+    int blocks;   // workgroups of the two jobs together: 8 * ceil(units / 8) * pair * (nk1 + gx)
+};
 struct FrontConv {   // on: the K3(X) job of front A reads the column matrix of an image (jx.T = the image)
     ConvShape g;
     int on;
@@ -153,6 +166,9 @@ hipError_t launch_front_one(const FrontRows &jr, const FrontHla &jx, const Front
 hipError_t launch_front(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
                         const FrontAbsmax &jw, const ConvShape *conv, int B, int basis, bool is_f32, bool packed,
                         hipStream_t st);
+// whether launch_front lets K1 (jr) and its first K3 job (jx) share the read of their tensor; switch for A/B
+FrontShare front_share(const FrontRows &jr, const FrontHla &jx, int B, bool is_f32);
+void front_share_enable(bool on);
 
 // K3: token-axis Hadamard low-rank projection, T [N, D] -> ThatT [D, N/B*r] bf16.
 // basis: which r rows of the order-B matrix are kept, 0 = rows 0..r-1, 1 = the r of lowest sequency.

@@ -19,15 +19,41 @@
 #include "quant_cols_body.hpp"
 #include "quant_rows_body.hpp"
 
+#include <atomic>
+
 namespace hlq {
 
 // CONV: X is a channels-last image and K3 reads its column matrix through ConvRows.  A kernel of
 // its own: the extra address arithmetic would cost the matrix variant registers, and with them a
 // wavefront of occupancy at B = 32.
 template <typename Tin, int B, bool PACKED, int BASIS, bool CONV>
-__global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, FrontFill jf, FrontConv jc)
+__global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, FrontFill jf, FrontConv jc, FrontShare js)
 {
     int b = blockIdx.x;
+    if (!CONV && js.on) {
+        // K1 and K3 read the same tensor: both readers of a group of 64 rows on one XCD, one after the other
+        if (b < js.blocks) {
+            const int per = js.nk1 + js.gx;
+            const int xcd = b & 7, q = b >> 3;
+            const int unit = (q / (js.pair * per)) * 8 + xcd;
+            const int u = q % (js.pair * per);
+            const int grp = unit * js.pair + u / per, v = u % per;
+            if (unit >= js.units) return;
+            if (v < js.nk1) {
+                const int blk = grp * js.nk1 + v;
+                if (blk < jr.blocks)
+                    quant_rows_body<Tin, B, 256, PACKED>(static_cast<const Tin *>(jr.G), jr.N, jr.O, jr.T, jr.k0, jr.k1, jr.qmax,
+                                                         jr.Gq, jr.sG, nullptr, blk);
+            } else {
+                hla_body<Tin, B, BASIS, 4>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, v - js.nk1, grp);
+            }
+            return;
+        }
+        b -= js.blocks;
+        const int i = b * 256 + threadIdx.x;
+        if (i < jf.n) jf.p[i] = 0u;
+        return;
+    }
     if (b < jr.blocks) {
         quant_rows_body<Tin, B, 256, PACKED>(static_cast<const Tin *>(jr.G), jr.N, jr.O, jr.T, jr.k0, jr.k1, jr.qmax, jr.Gq,
                                              jr.sG, nullptr, b);
@@ -243,13 +269,51 @@ FrontColsQ front_cols_full(const void *W, int O, int I, int B, uint32_t k0, uint
     return j;
 }
 
+namespace {
+// Off by default.  Measured at 4096 x 4096 x 11008 (rocprofv3, 212 launches each way): with the shared
+// read the launch fetches 97 MB instead of 181 MB from beyond the L2s -- G comes in once -- and takes
+// 62.4 us instead of 52.7: the launch is bound by the quantiser's arithmetic and by latency, not by
+// bytes (its second read of G is served by the last-level cache), and the narrower K3 workgroups of
+// the shared form write shorter runs.
+std::atomic<int> g_share_enabled{0};
+}
+void front_share_enable(bool on) { g_share_enabled.store(on ? 1 : 0); }
+
+FrontShare front_share(const FrontRows &jr, const FrontHla &jx, int B, bool is_f32)
+{
+    FrontShare s{};
+    if (!g_share_enabled.load() || !jr.G || jr.G != jx.T || jr.N != jx.N || jr.O != jx.D) return s;
+    constexpr int RG = 64;                              // rows of a group: 64 / B token blocks of K3
+    const int rows_per_k1 = 256 / jr.T;                 // T = 256: one row per workgroup
+    if (RG % rows_per_k1 != 0) return s;
+    // Only where it pays: a group's rows (and what is written for them) must sit in one XCD's L2
+    // together (4 MB), and the tensor must be large enough for its second read to cost real time.
+    const int64_t row_bytes = static_cast<int64_t>(jr.O) * (is_f32 ? 4 : 2);
+    if (row_bytes * RG > (int64_t(2) << 20) || row_bytes * jr.N < (int64_t(16) << 20)) return s;
+    const int64_t groups = (jr.N + RG - 1) / RG;
+    int pair = B / jx.r;                                // K3 writes 128 r / B bytes per column and group
+    if (pair < 1) pair = 1;
+    if (pair > 8) pair = 8;
+    const int64_t units = (groups + pair - 1) / pair;
+    s.nk1 = RG / rows_per_k1;
+    s.gx = (jr.O + 511) / 512;
+    s.pair = pair;
+    const int64_t blocks = 8 * ((units + 7) / 8) * pair * (s.nk1 + s.gx);
+    if (blocks >= (int64_t(1) << 30)) return FrontShare{};
+    s.units = static_cast<int>(units);
+    s.blocks = static_cast<int>(blocks);
+    s.on = 1;
+    return s;
+}
+
 template <typename Tin, int B, int BASIS>
 static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const FrontFill &jf, const FrontHla &jg,
                                  const FrontAbsmax &jw, const FrontConv &jc, bool packed, hipStream_t st)
 {
-    const int na = jr.blocks + jx.nb + (jf.n + 255) / 256;
+    const FrontShare js = jc.on ? FrontShare{} : front_share(jr, jx, B, sizeof(Tin) == 4);
+    const int na = (js.on ? js.blocks : jr.blocks + jx.nb) + (jf.n + 255) / 256;
     if (na > 0) {
-#define HLQ_FRONT_A(P, CV) hipLaunchKernelGGL((k_front_a<Tin, B, P, BASIS, CV>), dim3(na), dim3(256), 0, st, jr, jx, jf, jc)
+#define HLQ_FRONT_A(P, CV) hipLaunchKernelGGL((k_front_a<Tin, B, P, BASIS, CV>), dim3(na), dim3(256), 0, st, jr, jx, jf, jc, js)
         if (jc.on) {
             if (packed) HLQ_FRONT_A(true, true); else HLQ_FRONT_A(false, true);
         } else {
