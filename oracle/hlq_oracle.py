@@ -24,7 +24,7 @@ __all__ = [
     "transform_cols", "stream_key", "rand_word", "rand_byte", "quantize_one", "quantize_rows",
     "int_gemm_nt", "dequant", "hla_f32", "hla_f64", "round_bf16", "gemm_nt_f64",
     "linear_backward", "BASIS_NATURAL", "BASIS_SEQUENCY", "basis_rows", "ROUND_COUNTER", "ROUND_MANTISSA",
-    "quantize_one_mantissa", "conv_out_size", "im2col", "col2im", "conv2d_backward",
+    "quantize_one_mantissa", "conv_out_size", "im2col", "col2im", "conv2d_backward", "pack_nibbles",
 ]
 
 
@@ -301,8 +301,19 @@ def linear_backward(G, X, W, B: int, r: int, seed: int, want_dX: bool = True, wa
     return out
 
 
+def pack_nibbles(q) -> np.ndarray:
+    """4-bit codes [rows, K] in [-7, 7] (K even) -> [rows, K/2] bytes, two codes to a byte: code 2b in
+    the low nibble of byte b, code 2b+1 in the high nibble, each as a 4-bit two's-complement number --
+    the storage format of the paper's int4 operands and of its int4 activation store (Sec. 6.1)."""
+    q = np.asarray(q).astype(np.int16)
+    assert q.ndim == 2 and q.shape[1] % 2 == 0 and np.max(np.abs(q), initial=0) <= 7
+    lo = q[:, 0::2] & 0xF
+    hi = q[:, 1::2] & 0xF
+    return (lo | (hi << 4)).astype(np.uint8)
+
+
 def linear_backward_mode(G, X, W, B: int, r: int, seed: int, gx_bits: int = 4, gw_int8: bool = False,
-                         basis: int = 0, rounding: int = 0):
+                         basis: int = 0, rounding: int = 0, xhat_bits: int = 8):
     """Both stage lists of Sec. 6.1 composed stage by stage, with the two options of the method:
 
     gx_bits = 8   the g_x codes use [-127, 127] (the int8 warm-up phase of Sec. 7) instead of 4 bits;
@@ -313,6 +324,10 @@ def linear_backward_mode(G, X, W, B: int, r: int, seed: int, gx_bits: int = 4, g
                   lowest sequency;
     rounding      ROUND_COUNTER (seeded stream) or ROUND_MANTISSA (the paper's low-11-bit scheme), for
                   every quantiser of both lists.
+    xhat_bits     with gw_int8: 8, or 4 -- the projected x is quantised to [-7, 7] instead of [-127, 127]
+                  (same stream, same per-feature absmax scale), the form in which Sec. 6.1's activation
+                  compression keeps it between the passes ("int4"); the projected g_o stays int8 and
+                  the product is the same integer product.
     Returns a dict with dX, dW (fp64) and every intermediate."""
     G, X, W = _f32(G), _f32(X), _f32(W)
     qx = 7 if gx_bits == 4 else 127
@@ -326,8 +341,9 @@ def linear_backward_mode(G, X, W, B: int, r: int, seed: int, gx_bits: int = 4, g
     # g_w: 1. HLA(x) on L  2. Q8  3. HLA(g_o^T) on L  4. Q8  5. integer product  6. dequantise
     xh = hla_f32(X, B, r, basis)
     gh = hla_f32(G, B, r, basis)
+    assert xhat_bits in (4, 8) and (gw_int8 or xhat_bits == 8)
     if gw_int8:
-        Xq, sX = quantize_rows(xh, seed, TENSOR_XHAT, qmax=127, rounding=rounding)
+        Xq, sX = quantize_rows(xh, seed, TENSOR_XHAT, qmax=127 if xhat_bits == 8 else 7, rounding=rounding)
         Gq2, sG2 = quantize_rows(gh, seed, TENSOR_GHAT, qmax=127, rounding=rounding)
         accw = int_gemm_nt(Gq2, Xq)
         out.update(XqT=Xq, sX=sX, GqT=Gq2, sGhat=sG2, accw=accw, dW=dequant(accw, sG2, sX, B))

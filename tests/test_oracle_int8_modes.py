@@ -100,3 +100,59 @@ def test_eight_bit_gx_is_closer_to_the_dense_product():
         e8 += np.mean((o8["dX"] - ref) ** 2)
         assert np.max(np.abs(o8["acc"])) <= 127 * 127 * 64
     assert e8 < e4 / 50
+
+
+def test_pack_nibbles_layout():
+    """Two codes to a byte: code 2b low nibble, code 2b+1 high nibble, 4-bit two's complement --
+    checked against arithmetic done by hand, and by unpacking with sign extension."""
+    q = np.array([[1, -1, 7, -7, 0, 3, -4, 5]], dtype=np.int8)
+    p = oracle.pack_nibbles(q)
+    assert p.dtype == np.uint8 and p.shape == (1, 4)
+    assert p.tolist() == [[0x01 | (0xF << 4), 0x07 | (0x9 << 4), 0x00 | (0x3 << 4), 0xC | (0x5 << 4)]]
+    rng = np.random.default_rng(0)
+    q = rng.integers(-7, 8, size=(5, 64)).astype(np.int8)
+    p = oracle.pack_nibbles(q).astype(np.int16)
+    lo = ((p & 0xF) ^ 8) - 8                      # sign-extend a nibble
+    hi = (((p >> 4) & 0xF) ^ 8) - 8
+    back = np.stack([lo, hi], axis=2).reshape(5, 64)
+    assert np.array_equal(back, q)
+    with pytest.raises(AssertionError):
+        oracle.pack_nibbles(np.array([[8, 0]], dtype=np.int8))
+
+
+def test_int4_activation_store_is_the_same_quantiser_at_qmax_7():
+    """Sec. 6.1 keeps the compressed activation as 4-bit integers between the passes: the stage-2
+    quantiser with codes in [-7, 7].  Same projection, same stream, same absmax per feature; only the
+    grid is coarser, the product stays the integer product, and the estimate stays unbiased."""
+    G, X, W = _problem(N=64, I=16, O=32)
+    B, r = 16, 8
+    o4 = oracle.linear_backward_mode(G, X, W, B, r, 2, gw_int8=True, xhat_bits=4)
+    o8 = oracle.linear_backward_mode(G, X, W, B, r, 2, gw_int8=True, xhat_bits=8)
+    xh = oracle.hla_f32(X, B, r)
+    Xq, sX = oracle.quantize_rows(xh, 2, oracle.TENSOR_XHAT, qmax=7)
+    assert np.array_equal(o4["XqT"], Xq) and np.array_equal(o4["sX"], sX)
+    a = np.max(np.abs(xh), axis=1)
+    assert np.array_equal(sX, (a / np.float32(7.0)).astype(np.float32))
+    assert np.max(np.abs(Xq.astype(np.int32))) == 7 and np.all(np.max(np.abs(Xq.astype(np.int32)), axis=1) == 7)
+    assert np.all(np.abs(Xq.astype(np.float64) * sX[:, None] - xh) < sX[:, None] * (1 + 1e-6))
+    # the other operand and the whole g_x list do not change
+    assert np.array_equal(o4["GqT"], o8["GqT"]) and np.array_equal(o4["dX"], o8["dX"])
+    assert np.array_equal(o4["accw"], o4["GqT"].astype(np.int64) @ Xq.astype(np.int64).T)
+    # dequantisation: acc * sGhat[o] * sX[i] / B, recomputed here in fp64 from the parts
+    want = o4["accw"].astype(np.float64) * o4["sGhat"].astype(np.float64)[:, None] * sX.astype(np.float64)[None, :] / B
+    assert np.allclose(o4["dW"], want, rtol=1e-6, atol=0)
+    # unbiased: the seed average converges to the product of the exact projections, from further away
+    # than with 8-bit codes
+    exact = oracle.hla_f64(G, B, r) @ oracle.hla_f64(X, B, r).T / B
+    scale = np.sqrt(np.mean(exact ** 2))
+    errs = []
+    for S in (1, 16, 256):
+        m = np.zeros_like(exact)
+        for seed in range(S):
+            m += oracle.linear_backward_mode(G, X, W, B, r, seed, gw_int8=True, xhat_bits=4)["dW"]
+        errs.append(np.sqrt(np.mean((m / S - exact) ** 2)) / scale)
+    e8 = np.sqrt(np.mean((o8["dW"] - exact) ** 2)) / scale
+    assert e8 < errs[0] < 0.6
+    assert errs[1] < errs[0] / 2.5 and errs[2] < errs[1] / 2.5
+    with pytest.raises(AssertionError):
+        oracle.linear_backward_mode(G, X, W, B, r, 0, gw_int8=False, xhat_bits=4)
