@@ -301,10 +301,25 @@ int hlq_compress_act_int8(const void *X, int64_t N, int64_t d_in, int B, int r, 
                           int8_t *XqT, float *sX, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * ACBP with the 4-bit store the paper names (Sec. 6.1: the compressed activation is kept as int4, an
+ * eighth of an fp32 feature map before the r/B reduction): stage 2 of the g_w list with codes in
+ * [-7, 7] -- same projection, same random stream (tensor 2) and counters, same per-feature absmax
+ * as hlq_compress_act_int8, scale sX = absmax / 7 -- stored two to a byte in the layout of
+ * HLQ_BITS_4_PACKED:  Xq4T [d_in, N/B*r/2] bytes, sX [d_in] fp32: an eighth (r = B/2) of X's bf16
+ * footprint.  Needs r % 8 == 0 (HLQ_ERR_RANK) and (N/B*r) % 32 == 0 (HLQ_ERR_SHAPE); workspace as
+ * for hlq_compress_act_int8.  The backward pass takes it as Xc with HLQ_FLAG_GW_INT8 | HLQ_FLAG_XC_INT4:
+ * the codes are widened to int8 (a pass over the store, into the workspace) and multiplied with the
+ * int8 codes of the projected gradient; dW = acc * sGhat[o] * sX[i] / B as in the int8 list.
+ */
+#define HLQ_FLAG_XC_INT4 64 /* Xc holds 4-bit codes two to a byte (hlq_compress_act_int4); needs HLQ_FLAG_GW_INT8 and Xc */
+int hlq_compress_act_int4(const void *X, int64_t N, int64_t d_in, int B, int r, uint64_t seed, int dtype,
+                          uint8_t *Xq4T, float *sX, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * hlq_linear_backward_ex with the options above.
  *   Xc, sXc   X compressed at forward time, or NULL: bf16 XhatT (sXc NULL) without
- *             HLQ_FLAG_GW_INT8; int8 XqT with its scales sXc [d_in] with it.  Exactly one of X and
- *             Xc when dW is wanted.
+ *             HLQ_FLAG_GW_INT8; int8 XqT with its scales sXc [d_in] with it (4-bit Xq4T with
+ *             HLQ_FLAG_XC_INT4 as well).  Exactly one of X and Xc when dW is wanted.
  *   flags     any combination of HLQ_FLAG_*; 0 = hlq_linear_backward_ex.
  *   workspace >= hlq_workspace_bytes_mode(...) bytes, 256-aligned, or NULL for the library-owned one.
  * HLQ_FLAG_GW_INT8 additionally needs r % 4 == 0 (HLQ_ERR_RANK), (N/B*r) % 16 == 0 and N/B*r <= 131072.

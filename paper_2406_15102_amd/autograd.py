@@ -44,7 +44,8 @@ class HlqLinearFunction(torch.autograd.Function):
 
     x [..., d_in] and w [d_out, d_in] in bf16 or fp32 on the GPU.  Forward stores the compressed
     activation (the first r of every B token-axis Hadamard coefficients, bf16, or int8 codes with
-    ``flags & HLQ_FLAG_GW_INT8``) instead of x.  Backward returns dX = Q(G H) Q(H^T W) / B and
+    ``flags & HLQ_FLAG_GW_INT8``, or 4-bit codes with ``HLQ_FLAG_GW_INT8 | HLQ_FLAG_XC_INT4``: natural
+    basis only) instead of x.  Backward returns dX = Q(G H) Q(H^T W) / B and
     dW = HLA(G)^T HLA(X) / B.  The number of tokens must be a multiple of B.
     """
 
@@ -54,7 +55,12 @@ class HlqLinearFunction(torch.autograd.Function):
         N, d_in = x2.shape
         Kc = N // B * r
         basis = hlq.HLQ_BASIS_SEQUENCY if flags & hlq.HLQ_FLAG_GW_SEQUENCY else hlq.HLQ_BASIS_NATURAL
-        if flags & hlq.HLQ_FLAG_GW_INT8:
+        if flags & hlq.HLQ_FLAG_XC_INT4:        # the paper's int4 store: 4-bit codes, two to a byte
+            xc = torch.empty((d_in, Kc // 2), dtype=torch.uint8, device=x.device)
+            sxc = torch.empty(d_in, dtype=torch.float32, device=x.device)
+            ws = torch.empty(hlq.hlq_hla_quantize_workspace_bytes(d_in), dtype=torch.uint8, device=x.device)
+            hlq.hlq_compress_act_int4(x2, B, r, seed, xc, sxc, ws)
+        elif flags & hlq.HLQ_FLAG_GW_INT8:
             xc = torch.empty((d_in, Kc), dtype=torch.int8, device=x.device)
             sxc = torch.empty(d_in, dtype=torch.float32, device=x.device)
             ws = torch.empty(hlq.hlq_hla_quantize_workspace_bytes(d_in), dtype=torch.uint8, device=x.device)

@@ -22,6 +22,7 @@ HLQ_BASIS_NATURAL, HLQ_BASIS_SEQUENCY = 0, 1
 HLQ_BITS_ROUND_MANTISSA = HLQ_BASIS_ROUND_MANTISSA = 0x200
 HLQ_FLAG_ROUND_MANTISSA = 16
 HLQ_FLAG_SEPARATE_PRODUCTS = 32
+HLQ_FLAG_XC_INT4 = 64
 HLQ_BITS_4, HLQ_BITS_8, HLQ_BITS_4_PACKED = 4, 8, 0x104
 
 
@@ -57,6 +58,8 @@ _EXPORTS = {
     "hlq_hla_quantize": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_uint64, C.c_int, C.c_int,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hlq_compress_act_int8": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_uint64, C.c_int,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "hlq_compress_act_int4": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_uint64, C.c_int,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hlq_workspace_bytes_mode": (C.c_size_t, [C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int]),
     "hlq_linear_backward_mode": (C.c_int, [C.c_void_p] * 5 + [C.c_int64] * 3 + [C.c_int, C.c_int, C.c_uint64, C.c_int,
@@ -170,7 +173,10 @@ def _expect_backward(G, X, W, dX, dW, N, d_in, d_out):
 def _expect_store(Xc, sXc, d_in, Kc, flags):
     if Xc is None:
         return
-    if flags & HLQ_FLAG_GW_INT8:
+    if flags & HLQ_FLAG_XC_INT4:
+        _expect("Xc", Xc, (d_in, Kc // 2), torch.uint8)
+        _expect("sXc", sXc, (d_in,), torch.float32)
+    elif flags & HLQ_FLAG_GW_INT8:
         _expect("Xc", Xc, (d_in, Kc), torch.int8)
         _expect("sXc", sXc, (d_in,), torch.float32)
     else:
@@ -339,6 +345,13 @@ def hlq_compress_act_int8(X, B, r, seed, XqT, sX, workspace):
     _check(lib().hlq_compress_act_int8(_ptr(X), N, d_in, B, r, seed, _dt(X), _ptr(XqT, torch.int8),
                                        _ptr(sX, torch.float32), _ptr(workspace), _nbytes(workspace), _stream()),
            "hlq_compress_act_int8")
+
+
+def hlq_compress_act_int4(X, B, r, seed, Xq4T, sX, workspace):
+    N, d_in = X.shape
+    _check(lib().hlq_compress_act_int4(_ptr(X), N, d_in, B, r, seed, _dt(X), _ptr(Xq4T, torch.uint8),
+                                       _ptr(sX, torch.float32), _ptr(workspace), _nbytes(workspace), _stream()),
+           "hlq_compress_act_int4")
 
 
 def hlq_workspace_bytes_mode(N, d_in, d_out, B, r, x_is_compressed=False, flags=0) -> int:

@@ -171,7 +171,10 @@ __device__ __forceinline__ void hla_absmax_body(const Tin *__restrict__ T, int64
     hla_absmax_body_src<B, BASIS>(DenseRows<Tin>{T, D}, N, D, r, amax_bits, bx, by);
 }
 
-template <int B, int BASIS, bool MANT, typename Src>
+// P4: codes in [-7, 7] stored two to a byte (TqT then has Kc/2 bytes per feature; needs r % 8 == 0) -- the
+// 4-bit form in which the compressed activation is kept between the passes (Sec. 6.1) -- instead of
+// codes in [-127, 127], one int8 each.  Same stream, same counters, same maxima either way.
+template <int B, int BASIS, bool MANT, typename Src, bool P4 = false>
 __device__ __forceinline__ void hla_quantize_body_src(const Src &src, int64_t N, int D, int r,
                                                       const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
                                                       int8_t *__restrict__ TqT, float *__restrict__ sT,
@@ -190,12 +193,34 @@ __device__ __forceinline__ void hla_quantize_body_src(const Src &src, int64_t N,
 #pragma unroll
     for (int c = 0; c < CPL; ++c) {
         fwht_regs<B, CPL>(v + c);
+        constexpr float QMAX = P4 ? 7.0f : 127.0f;
         const float a = __uint_as_float(amax_bits[col0 + c]);
-        const float inv = absmax_to_inv(a, 127.0f);
-        if (blk == 0) sT[col0 + c] = absmax_to_scale(a, 127.0f);
+        const float inv = absmax_to_inv(a, QMAX);
+        if (blk == 0) sT[col0 + c] = absmax_to_scale(a, QMAX);
         const int64_t o = static_cast<int64_t>(col0 + c) * Kc + blk * r;          // r % 4 == 0
         const uint32_t cnt = static_cast<uint32_t>(col0 + c) * static_cast<uint32_t>(Kc >> 2) +
                              static_cast<uint32_t>((blk * r) >> 2);
+        if constexpr (P4) {
+#pragma unroll
+            for (int k = 0; k < B; k += 8) {
+                if (k < r) {
+                    const uint32_t lo =
+                        quant_pack4r<MANT>(v[kept_row<B, BASIS>(k + 0) * CPL + c], v[kept_row<B, BASIS>(k + 1) * CPL + c],
+                                           v[kept_row<B, BASIS>(k + 2) * CPL + c], v[kept_row<B, BASIS>(k + 3) * CPL + c], inv,
+                                           cnt + (k >> 2), k0, k1);
+                    const uint32_t hi =
+                        quant_pack4r<MANT>(v[kept_row<B, BASIS>(k + 4) * CPL + c], v[kept_row<B, BASIS>(k + 5) * CPL + c],
+                                           v[kept_row<B, BASIS>(k + 6) * CPL + c], v[kept_row<B, BASIS>(k + 7) * CPL + c], inv,
+                                           cnt + (k >> 2) + 1u, k0, k1);
+                    *reinterpret_cast<uint32_t *>(TqT + ((o + k) >> 1)) = nibble_pack8(lo, hi);
+                    if (coeffT) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) coeffT[o + k + e] = v[kept_row<B, BASIS>(k + e) * CPL + c];
+                    }
+                }
+            }
+            continue;
+        }
 #pragma unroll
         for (int k = 0; k < B; k += 4) {
             if (k < r) {
@@ -211,13 +236,14 @@ __device__ __forceinline__ void hla_quantize_body_src(const Src &src, int64_t N,
     }
 }
 
-template <typename Tin, int B, int BASIS, bool MANT = false>
+template <typename Tin, int B, int BASIS, bool MANT = false, bool P4 = false>
 __device__ __forceinline__ void hla_quantize_body(const Tin *__restrict__ T, int64_t N, int D, int r,
                                                   const uint32_t *__restrict__ amax_bits, uint32_t k0, uint32_t k1,
                                                   int8_t *__restrict__ TqT, float *__restrict__ sT,
                                                   float *__restrict__ coeffT, int bx, int by)
 {
-    hla_quantize_body_src<B, BASIS, MANT>(DenseRows<Tin>{T, D}, N, D, r, amax_bits, k0, k1, TqT, sT, coeffT, bx, by);
+    hla_quantize_body_src<B, BASIS, MANT, DenseRows<Tin>, P4>(DenseRows<Tin>{T, D}, N, D, r, amax_bits, k0, k1, TqT, sT, coeffT,
+                                                             bx, by);
 }
 
 }  // namespace hlq

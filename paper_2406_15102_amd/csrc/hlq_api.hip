@@ -97,7 +97,9 @@ Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_
     L.hws = off;   off += gwi ? up256(hlq::hla_quant_ws_bytes(d_out)) + up256(hlq::hla_quant_ws_bytes(d_in)) : 0;
     L.GhatT = off; off += up256(static_cast<size_t>(d_out) * Kc * esz);
     L.sGhat = off; off += gwi ? up256(static_cast<size_t>(d_out) * 4) : 0;
-    L.XhatT = off; off += x_is_compressed ? 0 : up256(static_cast<size_t>(d_in) * Kc * esz);
+    // X projected here, or the int8 codes unpacked from a 4-bit store that was handed over
+    const bool x_unpack = x_is_compressed && (flags & HLQ_FLAG_XC_INT4);
+    L.XhatT = off; off += (x_is_compressed && !x_unpack) ? 0 : up256(static_cast<size_t>(d_in) * Kc * esz);
     L.sXhat = off; off += (gwi && !x_is_compressed) ? up256(static_cast<size_t>(d_in) * 4) : 0;
     // split-K partial sums of whichever product wants them (the two products run one after the other)
     const size_t g1 = hlq::gemm_ws_bytes(0, static_cast<int>(N), static_cast<int>(d_in), static_cast<int>(d_out));
@@ -120,10 +122,16 @@ Layout make_layout(int64_t N, int64_t d_in, int64_t d_out, int B, int r, bool x_
 int check_flags(int flags, int r, int64_t N, int B)
 {
     if (flags & ~(HLQ_FLAG_GX_8BIT | HLQ_FLAG_GW_INT8 | HLQ_FLAG_GX_UNPACKED | HLQ_FLAG_GW_SEQUENCY | HLQ_FLAG_ROUND_MANTISSA |
-                  HLQ_FLAG_SEPARATE_PRODUCTS)) return HLQ_ERR_SHAPE;
+                  HLQ_FLAG_SEPARATE_PRODUCTS | HLQ_FLAG_XC_INT4)) return HLQ_ERR_SHAPE;
     if (flags & HLQ_FLAG_GW_INT8) {
         if (r % 4 != 0) return HLQ_ERR_RANK;
         if ((N / B * r) % 16 != 0) return HLQ_ERR_SHAPE;
+    }
+    if (flags & HLQ_FLAG_XC_INT4) {
+        // the 4-bit store belongs to the integer g_w list; its rows are whole 16-byte pieces of packed codes
+        if (!(flags & HLQ_FLAG_GW_INT8)) return HLQ_ERR_SHAPE;
+        if (r % 8 != 0) return HLQ_ERR_RANK;
+        if ((N / B * r) % 32 != 0) return HLQ_ERR_SHAPE;
     }
     return HLQ_OK;
 }
@@ -502,6 +510,27 @@ int hlq_compress_act_int8(const void *X, int64_t N, int64_t d_in, int B, int r, 
     return hlq_hla_quantize(X, N, d_in, B, r, seed, 2, dtype, XqT, sX, nullptr, workspace, workspace_bytes, stream);
 }
 
+int hlq_compress_act_int4(const void *X, int64_t N, int64_t d_in, int B, int r, uint64_t seed, int dtype, uint8_t *Xq4T,
+                          float *sX, void *workspace, size_t workspace_bytes, void *stream)
+{
+    int rc;
+    if (!X || !Xq4T || !sX || !workspace) return HLQ_ERR_NULL;
+    if ((rc = check_block(B)) != HLQ_OK) return rc;
+    if ((rc = check_rank(B, r)) != HLQ_OK) return rc;
+    if (r % 8 != 0) return HLQ_ERR_RANK;
+    if ((rc = check_dtype(dtype)) != HLQ_OK) return rc;
+    if ((rc = check_hla_shape(N, d_in, B, r)) != HLQ_OK) return rc;
+    const int64_t Kc = N / B * r;
+    if (Kc % 32 != 0 || d_in * (Kc / 4) >= (int64_t(1) << 32)) return HLQ_ERR_SHAPE;
+    if (!aligned(X, 16) || !aligned(Xq4T, 16)) return HLQ_ERR_SHAPE;
+    if (!aligned(workspace, 256) || workspace_bytes < hlq::hla_quant_ws_bytes(d_in)) return HLQ_ERR_WORKSPACE;
+    const uint64_t key = stream_key(seed, 2);
+    return launch_rc(hlq::launch_hla_quant(X, N, static_cast<int>(d_in), B, r, HLQ_BASIS_NATURAL, dtype == HLQ_F32,
+                                           static_cast<uint32_t>(key), static_cast<uint32_t>(key >> 32), false,
+                                           reinterpret_cast<int8_t *>(Xq4T), sX, nullptr, workspace,
+                                           static_cast<hipStream_t>(stream), true));
+}
+
 // The whole path.  Either W (quantised here, every call) or its codes and scales as hlq_quantize_w
 // left them (Wc, sWc): the weight changes once per optimiser step, not once per micro-batch.
 // Everything backward_impl refuses, tested before the first launch.
@@ -519,6 +548,7 @@ static int backward_check(const void *G, const void *X, const void *Xc, const fl
     if (Wc && (!aligned(Wc, 16) || !aligned(sWc, 16))) return HLQ_ERR_SHAPE;
     if (dW && ((X == nullptr) == (Xc == nullptr))) return HLQ_ERR_NULL;   // exactly one of the two
     if (dW && Xc && (gwi != (sXc != nullptr))) return HLQ_ERR_NULL;       // int8 codes come with their scales
+    if ((flags & HLQ_FLAG_XC_INT4) && dW && !Xc) return HLQ_ERR_NULL;     // the flag describes a store that is handed over
     if (!aligned(G, 16) || (X && !aligned(X, 16)) || (Xc && !aligned(Xc, 16)) || (sXc && !aligned(sXc, 16)) ||
         (W && !aligned(W, 16)) || (dX && !aligned(dX, 16)) || (dW && !aligned(dW, 16)))
         return HLQ_ERR_SHAPE;
@@ -572,6 +602,12 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
     float *sGh = reinterpret_cast<float *>(ws + L.sGhat);
     const void *Xh = Xc;
     const float *sXh = sXc;
+    if (dW && Xc && (flags & HLQ_FLAG_XC_INT4)) {
+        // the activation was kept as 4-bit codes (Sec. 6.1): widen them to the int8 operand of the product
+        int8_t *xu = reinterpret_cast<int8_t *>(ws + L.XhatT);
+        if ((rc = launch_rc(hlq::launch_unpack_nibbles(Xc, xu, static_cast<int64_t>(d_in) * Kc / 2, st))) != HLQ_OK) return rc;
+        Xh = xu;
+    }
     // The transforms that depend on nothing share launches when the shapes allow (k_front.hip): two
     // and pass 2 over the weight for the default path (one in all when the weight has few rows or
     // is not transformed here), three for the integer g_w list.  Very long rows of G and the mantissa-bit rounding keep one

@@ -179,8 +179,12 @@ hipError_t launch_hla(const void *T, int64_t N, int D, int B, int r, int basis, 
 // 1-2 / 3-4 of the g_w list): T [N, D] -> TqT [D, N/B*r] int8 + sT [D].  `ws` holds D words of
 // column maxima: hla_quant_ws_bytes(D) bytes.  Needs r % 4 == 0.
 size_t hla_quant_ws_bytes(int64_t D);
+// p4: codes in [-7, 7] stored two to a byte (TqT [D, N/B*r/2] bytes; needs r % 8 == 0; seeded rounding only)
 hipError_t launch_hla_quant(const void *T, int64_t N, int D, int B, int r, int basis, bool is_f32, uint32_t k0,
-                            uint32_t k1, bool mant, int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st);
+                            uint32_t k1, bool mant, int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st,
+                            bool p4 = false);
+// 4-bit codes two to a byte -> one int8 each; bytes_in a multiple of 16, both pointers 16-byte aligned
+hipError_t launch_unpack_nibbles(const void *in, int8_t *out, int64_t bytes_in, hipStream_t st);
 
 // K2 / K4: C = alpha * sA (x) sB * (A . Bm^T).  kind 0: int8 operands, int32 accumulate;
 // kind 1: bf16 operands, fp32 accumulate.  K in elements.

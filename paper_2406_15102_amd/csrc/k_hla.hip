@@ -77,20 +77,55 @@ __global__ __launch_bounds__(256) void k_hla_absmax(const Tin *__restrict__ T, i
     hla_absmax_body<Tin, B, BASIS>(T, N, D, r, amax_bits, blockIdx.x, blockIdx.y);
 }
 
-template <typename Tin, int B, int BASIS, bool MANT>
+template <typename Tin, int B, int BASIS, bool MANT, bool P4 = false>
 __global__ __launch_bounds__(256) void k_hla_quantize(const Tin *__restrict__ T, int64_t N, int D, int r,
                                                       const uint32_t *__restrict__ amax_bits, uint32_t k0,
                                                       uint32_t k1, int8_t *__restrict__ TqT, float *__restrict__ sT,
                                                       float *__restrict__ coeffT)
 {
-    hla_quantize_body<Tin, B, BASIS, MANT>(T, N, D, r, amax_bits, k0, k1, TqT, sT, coeffT, blockIdx.x, blockIdx.y);
+    hla_quantize_body<Tin, B, BASIS, MANT, P4>(T, N, D, r, amax_bits, k0, k1, TqT, sT, coeffT, blockIdx.x, blockIdx.y);
+}
+
+// 4-bit codes two to a byte (code 2b low nibble, code 2b+1 high nibble, two's complement) -> one int8
+// each: what the integer g_w product multiplies when the activation was stored as int4 (Sec. 6.1).
+// A lane turns 16 bytes into 32.
+__global__ __launch_bounds__(256) void k_unpack_nibbles(const uint4 *__restrict__ in, uint4 *__restrict__ out, int64_t n16)
+{
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+    if (i >= n16) return;
+    const uint4 x = in[i];
+    const uint32_t w[4] = {x.x, x.y, x.z, x.w};
+    uint32_t o[8];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t lo = w[d] & 0x0F0F0F0Fu, hi = (w[d] >> 4) & 0x0F0F0F0Fu;
+        // bytes (lo0, hi0, lo1, hi1) and (lo2, hi2, lo3, hi3): v_perm selectors 0-3 = second operand, 4-7 = first
+        uint32_t a = __builtin_amdgcn_perm(hi, lo, 0x05010400u);
+        uint32_t b = __builtin_amdgcn_perm(hi, lo, 0x07030602u);
+        // sign-extend every byte's nibble: a set bit 3 fills the upper half of its byte
+        a |= ((a >> 3) & 0x01010101u) * 0xF0u;
+        b |= ((b >> 3) & 0x01010101u) * 0xF0u;
+        o[2 * d] = a;
+        o[2 * d + 1] = b;
+    }
+    out[2 * i] = make_uint4(o[0], o[1], o[2], o[3]);
+    out[2 * i + 1] = make_uint4(o[4], o[5], o[6], o[7]);
+}
+
+hipError_t launch_unpack_nibbles(const void *in, int8_t *out, int64_t bytes_in, hipStream_t st)
+{
+    const int64_t n16 = bytes_in / 16;
+    if (n16 <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_unpack_nibbles, dim3(static_cast<unsigned>((n16 + 255) / 256)), dim3(256), 0, st,
+                       static_cast<const uint4 *>(in), reinterpret_cast<uint4 *>(out), n16);
+    return hipGetLastError();
 }
 
 size_t hla_quant_ws_bytes(int64_t D) { return (static_cast<size_t>(D) * 4 + 255) & ~static_cast<size_t>(255); }
 
 template <typename Tin, int B, int BASIS>
 static hipError_t launch_hla_quant_t(const void *T, int64_t N, int D, int r, uint32_t k0, uint32_t k1, bool mant,
-                                     int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st)
+                                     int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st, bool p4 = false)
 {
     constexpr int CPL = 128 / B;
     const int64_t nblk = N / B;
@@ -99,7 +134,9 @@ static hipError_t launch_hla_quant_t(const void *T, int64_t N, int D, int r, uin
     dim3 grid(hla_grid_x(D, B), hla_grid_y(N, B));
     hipLaunchKernelGGL(k_hla_fill_u32, dim3((D + 255) / 256), dim3(256), 0, st, amax, D, 0u);
     hipLaunchKernelGGL((k_hla_absmax<Tin, B, BASIS>), grid, dim3(256), 0, st, t, N, D, r, amax);
-    if (mant)
+    if (p4)   // the 4-bit store rounds by the seeded stream only
+        hipLaunchKernelGGL((k_hla_quantize<Tin, B, BASIS, false, true>), grid, dim3(256), 0, st, t, N, D, r, amax, k0, k1, TqT, sT, coeffT);
+    else if (mant)
         hipLaunchKernelGGL((k_hla_quantize<Tin, B, BASIS, true>), grid, dim3(256), 0, st, t, N, D, r, amax, k0, k1, TqT, sT, coeffT);
     else
         hipLaunchKernelGGL((k_hla_quantize<Tin, B, BASIS, false>), grid, dim3(256), 0, st, t, N, D, r, amax, k0, k1, TqT, sT, coeffT);
@@ -107,15 +144,15 @@ static hipError_t launch_hla_quant_t(const void *T, int64_t N, int D, int r, uin
 }
 
 hipError_t launch_hla_quant(const void *T, int64_t N, int D, int B, int r, int basis, bool is_f32, uint32_t k0,
-                            uint32_t k1, bool mant, int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st)
+                            uint32_t k1, bool mant, int8_t *TqT, float *sT, float *coeffT, void *ws, hipStream_t st, bool p4)
 {
 #define HLQ_HLAQ_CASE(BB)                                                                                  \
     case BB:                                                                                               \
         if (basis)                                                                                         \
-            return is_f32 ? launch_hla_quant_t<float, BB, 1>(T, N, D, r, k0, k1, mant, TqT, sT, coeffT, ws, st)  \
-                          : launch_hla_quant_t<bf16_t, BB, 1>(T, N, D, r, k0, k1, mant, TqT, sT, coeffT, ws, st); \
-        return is_f32 ? launch_hla_quant_t<float, BB, 0>(T, N, D, r, k0, k1, mant, TqT, sT, coeffT, ws, st)      \
-                      : launch_hla_quant_t<bf16_t, BB, 0>(T, N, D, r, k0, k1, mant, TqT, sT, coeffT, ws, st);
+            return is_f32 ? launch_hla_quant_t<float, BB, 1>(T, N, D, r, k0, k1, mant, TqT, sT, coeffT, ws, st, p4)  \
+                          : launch_hla_quant_t<bf16_t, BB, 1>(T, N, D, r, k0, k1, mant, TqT, sT, coeffT, ws, st, p4); \
+        return is_f32 ? launch_hla_quant_t<float, BB, 0>(T, N, D, r, k0, k1, mant, TqT, sT, coeffT, ws, st, p4)      \
+                      : launch_hla_quant_t<bf16_t, BB, 0>(T, N, D, r, k0, k1, mant, TqT, sT, coeffT, ws, st, p4);
     switch (B) {
         HLQ_HLAQ_CASE(16)
         HLQ_HLAQ_CASE(32)
