@@ -78,7 +78,7 @@ size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r,
  *       and g_w stage 5) come to at least four 256 x 256 tiles per compute unit run them as one
  *       persistent launch, a workgroup per compute unit walking a fixed list of tiles and loading
  *       across tile boundaries;  0: always one workgroup per tile.
- *   HLQ_OPT_SHARED_G_READ  1: for a large G, the workgroups that quantise a group of 64 rows of
+ *   HLQ_OPT_SHARED_G_READ  1: for a large G, the workgroups that quantise a group of 128 rows of
  *       G (g_x stages 1-2) and those that project the same rows along the tokens (g_w stage 3) are
  *       dispatched next to one another on one XCD, so that the second reader finds the rows in that
  *       XCD's L2 and G comes from memory once (half the fetched bytes of that launch, but measured slower: the
@@ -373,6 +373,19 @@ int hlq_mfma_probe(int kind, int blocks, int iters, float *sink, void *stream);
  * dX equals the single product's bit for bit; dW up to the summation order of the k splits.
  */
 size_t hlq_backward_products_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int64_t Kc, int gx_bits, int gw_int8);
+/*
+ * How hlq_backward_products would lay the two products out for bf16 outputs, given `workspace_bytes` of
+ * split-k scratch -- host arithmetic only, nothing is launched (the plan is a cost model fitted to
+ * measurements; this entry point lets a test pin its choices):
+ *   plan[0], plan[1]  tile edge (256 or 128) of the g_x and of the g_w product
+ *   plan[2]           k splits of the g_w product
+ *   plan[3]           1 if the g_w product's tiles are dispatched first
+ *   plan[4]           1 if the persistent form takes the launch (needs a visible GPU: its grid is the
+ *                     number of compute units; 0 without one)
+ * Status codes as for hlq_backward_products_workspace_bytes's shape rules; plan NULL: HLQ_ERR_NULL.
+ */
+int hlq_backward_products_plan(int64_t N, int64_t d_in, int64_t d_out, int64_t Kc, int gx_bits, int gw_int8,
+                               size_t workspace_bytes, int *plan);
 int hlq_backward_products(const void *Gq, const float *sG, const void *WqT, const float *sW, int gx_bits,
                           const void *GhatT, const float *sGhat, const void *XhatT, const float *sXhat, int64_t N,
                           int64_t d_in, int64_t d_out, int64_t Kc, int B, int dtype, void *dX, void *dW, void *workspace,

@@ -82,6 +82,7 @@ _EXPORTS = {
                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "hlq_mfma_probe": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]),
     "hlq_backward_products_workspace_bytes": (C.c_size_t, [C.c_int64] * 4 + [C.c_int, C.c_int]),
+    "hlq_backward_products_plan": (C.c_int, [C.c_int64] * 4 + [C.c_int, C.c_int, C.c_size_t, C.POINTER(C.c_int)]),
     "hlq_backward_products": (C.c_int, [C.c_void_p] * 4 + [C.c_int] + [C.c_void_p] * 4 + [C.c_int64] * 4
                               + [C.c_int, C.c_int] + [C.c_void_p] * 3 + [C.c_size_t, C.c_void_p]),
     "hlq_conv_sizes": (C.c_int, [_GEOM_P] + [C.POINTER(C.c_int64)] * 4),
@@ -435,6 +436,14 @@ def hlq_conv2d_backward(G, X, Wt, geom, B, r, seed, flags, dX, dW, workspace=Non
 
 def hlq_backward_products_workspace_bytes(N, d_in, d_out, Kc, gx_bits, gw_int8=False) -> int:
     return int(lib().hlq_backward_products_workspace_bytes(N, d_in, d_out, Kc, gx_bits, int(bool(gw_int8))))
+
+
+def hlq_backward_products_plan(N, d_in, d_out, Kc, gx_bits, gw_int8=False, workspace_bytes=1 << 28):
+    """-> (tile_x, tile_w, splits_w, w_first, persistent): the layout hlq_backward_products would choose."""
+    plan = (C.c_int * 5)()
+    _check(lib().hlq_backward_products_plan(N, d_in, d_out, Kc, gx_bits, int(bool(gw_int8)), workspace_bytes, plan),
+           "hlq_backward_products_plan")
+    return tuple(int(v) for v in plan)
 
 
 def hlq_backward_products(Gq, sG, WqT, sW, gx_bits, GhatT, sGhat, XhatT, sXhat, B, dX, dW, workspace=None):

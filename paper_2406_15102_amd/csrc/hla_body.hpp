@@ -68,8 +68,8 @@ __device__ __forceinline__ void hla_job_map(int l, int gx, int grp, int &bx, int
 }
 
 // LM: lanes side by side as a multiple of hla_lanes(B) -- 1 for the stand-alone shape (B lanes x 256/B token
-// blocks), 4 for the workgroups that share their rows of G with K1 in the last-level-cache-free front
-// launch (4 B lanes = 512 columns x 64/B token blocks = 64 rows).
+// blocks), 2 for the workgroups that share their rows of G with K1 through one XCD's L2
+// (2 B lanes = 256 columns x 128/B token blocks = 128 rows).
 template <int B, int BASIS, typename Src, int LM = 1>
 __device__ __forceinline__ void hla_body_src(const Src &src, int64_t N, int D, int r, bf16_t *__restrict__ ThatT,
                                              float *__restrict__ coeffT, int bx, int by)

@@ -394,6 +394,22 @@ size_t hlq_backward_products_workspace_bytes(int64_t N, int64_t d_in, int64_t d_
     return hlq::gemm_pair_ws_bytes(kx, ax, kw, aw, size_t(256) << 20);
 }
 
+int hlq_backward_products_plan(int64_t N, int64_t d_in, int64_t d_out, int64_t Kc, int gx_bits, int gw_int8,
+                               size_t workspace_bytes, int *plan)
+{
+    int rc, kx, kw;
+    if (!plan) return HLQ_ERR_NULL;
+    if ((rc = products_kinds(gx_bits, gw_int8 != 0, &kx, &kw)) != HLQ_OK) return rc;
+    if ((rc = products_check(N, d_in, d_out, Kc, kx, kw)) != HLQ_OK) return rc;
+    hlq::GemmArgs ax{}, aw{};
+    ax.M = static_cast<int>(N), ax.N = static_cast<int>(d_in), ax.K = static_cast<int>(d_out);
+    aw.M = static_cast<int>(d_out), aw.N = static_cast<int>(d_in), aw.K = static_cast<int>(Kc);
+    // non-null outputs: the persistent form is only chosen for products that write C
+    ax.C = aw.C = plan;
+    hlq::gemm_pair_describe(kx, ax, kw, aw, workspace_bytes, plan);
+    return HLQ_OK;
+}
+
 int hlq_backward_products(const void *Gq, const float *sG, const void *WqT, const float *sW, int gx_bits,
                           const void *GhatT, const float *sGhat, const void *XhatT, const float *sXhat, int64_t N,
                           int64_t d_in, int64_t d_out, int64_t Kc, int B, int dtype, void *dX, void *dW, void *workspace,

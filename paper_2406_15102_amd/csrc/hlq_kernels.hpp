@@ -97,14 +97,14 @@ inline int hla_job_blocks(int gx, int gy, int grp)
     return 8 * grp * ((units + 7) / 8);
 }
 // K1(G) and K3(G) of one launch sharing ONE read of G from memory: rows of G go through in groups of
-// 64; the workgroups of a group -- its K1 rows, then its K3 strips of 512 columns -- sit next to one
+// 128; the workgroups of a group -- its K1 rows, then its K3 strips of 256 columns -- sit next to one
 // another in the index sequence of ONE XCD (index mod 8), so that whichever of the two readers of a row
 // comes second finds it in that XCD's L2.  `pair` consecutive groups (the ones whose K3 output pieces
 // complete a 128-byte line) go to the same XCD back to back.  on == 0: the jobs keep their own ranges.
 struct FrontShare {
     int on;
-    int nk1;      // K1 workgroups per group of 64 rows
-    int gx;       // K3 workgroups per group (strips of 512 columns)
+    int nk1;      // K1 workgroups per group of 128 rows
+    int gx;       // K3 workgroups per group (strips of 256 columns)
     int pair;     // groups per unit handed to an XCD
     int units;    // units in all
     int blocks;   // workgroups of the two jobs together: 8 * ceil(units / 8) * pair * (nk1 + gx)
@@ -231,6 +231,10 @@ hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmA
 bool gemm_stream_wanted(int kindA, const GemmArgs &a, int kindB, const GemmArgs *b);
 hipError_t launch_gemm_stream(int kindA, const GemmArgs &a, int kindB, const GemmArgs *b, hipStream_t st);
 void gemm_stream_enable(bool on);
+// What launch_gemm_pair would do with these shapes and this much split-k scratch, without doing it:
+// plan[0], plan[1] = tile edge (256 or 128) of a's and b's product, plan[2] = k splits of b,
+// plan[3] = 1 if b's tiles are dispatched first, plan[4] = 1 if the persistent form takes the launch.
+void gemm_pair_describe(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, size_t ws_bytes, int plan[5]);
 // split-k scratch (b.ws) that the pair's plan would use if it may have up to `cap` bytes; only the
 // shapes and kinds of a and b are read
 size_t gemm_pair_ws_bytes(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, size_t cap);

@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
 {
     int b = blockIdx.x;
     if (!CONV && js.on) {
-        // K1 and K3 read the same tensor: both readers of a group of 64 rows on one XCD, one after the other
+        // K1 and K3 read the same tensor: both readers of a group of 128 rows on one XCD, one after the other
         if (b < js.blocks) {
             const int per = js.nk1 + js.gx;
             const int xcd = b & 7, q = b >> 3;
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
                     quant_rows_body<Tin, B, 256, PACKED>(static_cast<const Tin *>(jr.G), jr.N, jr.O, jr.T, jr.k0, jr.k1, jr.qmax,
                                                          jr.Gq, jr.sG, nullptr, blk);
             } else {
-                hla_body<Tin, B, BASIS, 4>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, v - js.nk1, grp);
+                hla_body<Tin, B, BASIS, 2>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, v - js.nk1, grp);
             }
             return;
         }
@@ -283,20 +283,20 @@ FrontShare front_share(const FrontRows &jr, const FrontHla &jx, int B, bool is_f
 {
     FrontShare s{};
     if (!g_share_enabled.load() || !jr.G || jr.G != jx.T || jr.N != jx.N || jr.O != jx.D) return s;
-    constexpr int RG = 64;                              // rows of a group: 64 / B token blocks of K3
+    constexpr int RG = 128;                             // rows of a group: 128 / B token blocks of K3
     const int rows_per_k1 = 256 / jr.T;                 // T = 256: one row per workgroup
     if (RG % rows_per_k1 != 0) return s;
     // Only where it pays: a group's rows (and what is written for them) must sit in one XCD's L2
     // together (4 MB), and the tensor must be large enough for its second read to cost real time.
     const int64_t row_bytes = static_cast<int64_t>(jr.O) * (is_f32 ? 4 : 2);
-    if (row_bytes * RG > (int64_t(2) << 20) || row_bytes * jr.N < (int64_t(16) << 20)) return s;
+    if (row_bytes * RG > (int64_t(3) << 20) || row_bytes * jr.N < (int64_t(16) << 20)) return s;
     const int64_t groups = (jr.N + RG - 1) / RG;
-    int pair = B / jx.r;                                // K3 writes 128 r / B bytes per column and group
+    int pair = B / (2 * jx.r);                          // K3 writes 256 r / B bytes per column and group
     if (pair < 1) pair = 1;
     if (pair > 8) pair = 8;
     const int64_t units = (groups + pair - 1) / pair;
     s.nk1 = RG / rows_per_k1;
-    s.gx = (jr.O + 511) / 512;
+    s.gx = (jr.O + 255) / 256;
     s.pair = pair;
     const int64_t blocks = 8 * ((units + 7) / 8) * pair * (s.nk1 + s.gx);
     if (blocks >= (int64_t(1) << 30)) return FrontShare{};

@@ -117,6 +117,16 @@ size_t gemm_pair_ws_bytes(int kindA, const GemmArgs &a, int kindB, const GemmArg
     return p.splitsB > 1 ? static_cast<size_t>(p.splitsB) * b.M * b.N * 4 : 0;
 }
 
+void gemm_pair_describe(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b, size_t ws_bytes, int plan[5])
+{
+    const PairPlan p = plan_pair(a, kindA, b, kindB, ws_bytes);
+    plan[0] = p.bigA ? 256 : 128;
+    plan[1] = p.bigB ? 256 : 128;
+    plan[2] = p.splitsB;
+    plan[3] = p.b_first ? 1 : 0;
+    plan[4] = (p.bigA && p.bigB && p.splitsB == 1 && gemm_stream_wanted(kindA, a, kindB, &b)) ? 1 : 0;
+}
+
 bool gemm_pair_available(int kindA, const GemmArgs &a, int kindB, const GemmArgs &b)
 {
     // the grid of the launch (128-tiles of both products, the second split 16 ways) must fit 31 bits with room
