@@ -57,7 +57,8 @@ __global__ __launch_bounds__(256) void k_mfma_probe(int iters, float *sink)
         for (int i = 0; i < 8; ++i) acc[i] = v4f{0.0f};
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i], b[i], acc[i], 0, 0, 0);
+            for (int i = 0; i < 8; ++i)   // written out: the builtin's accumulator tuples get copied around every iteration
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i]) : "v"(a[i]), "v"(b[i]));
         }
         float s = 0.0f;
 #pragma unroll
@@ -96,7 +97,8 @@ __global__ __launch_bounds__(256) void k_mfma_probe(int iters, float *sink)
             for (int i = 0; i < 8; ++i) acc[i] = v4i32{0};
             for (int it = 0; it < iters; ++it) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[i], b[i], acc[i], 0, 0, 0);
+                for (int i = 0; i < 8; ++i)
+                    asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(acc[i]) : "v"(a[i]), "v"(b[i]));
             }
             int s = 0;
 #pragma unroll
