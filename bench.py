@@ -104,7 +104,7 @@ def main():
                     help="time the whole path only and print a short JSON line (what a counter profile wants to see)")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=0|1",
                     help="library switch for A/B runs: persistent=0|1 (persistent matrix products), "
-                         "shared_g=0|1 (K1 and K3 share one read of G)")
+                         "shared_g=0|1 (K1 and K3 share one read of G), direct_lds=0|1 (operands of the products straight into LDS)")
     ap.add_argument("--no-modes", action="store_true",
                     help="skip the extra whole-path timings of the method's options (keeps a profile to the default path)")
     args = ap.parse_args()
@@ -121,7 +121,8 @@ def main():
     hlq.lib()  # fail loudly if the HIP library is missing
     for item in args.option:
         name, _, val = item.partition("=")
-        key = {"persistent": hlq.HLQ_OPT_PERSISTENT_PRODUCTS, "shared_g": hlq.HLQ_OPT_SHARED_G_READ}[name]
+        key = {"persistent": hlq.HLQ_OPT_PERSISTENT_PRODUCTS, "shared_g": hlq.HLQ_OPT_SHARED_G_READ,
+               "direct_lds": hlq.HLQ_OPT_DIRECT_TO_LDS}[name]
         hlq.hlq_set_option(key, int(val))
     dev = "cuda:0"
     torch.cuda.set_device(0)

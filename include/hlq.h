@@ -74,19 +74,24 @@ size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r,
 
 /*
  * Process-wide switches, for measurements (every setting computes the same results).
- *   HLQ_OPT_PERSISTENT_PRODUCTS  1 (default): layers whose matrix products (Sec. 6.1, g_x stages 5-6
- *       and g_w stage 5) come to at least four 256 x 256 tiles per compute unit run them as one
- *       persistent launch, a workgroup per compute unit walking a fixed list of tiles and loading
- *       across tile boundaries;  0: always one workgroup per tile.
+ *   HLQ_OPT_PERSISTENT_PRODUCTS  1: layers whose matrix products (Sec. 6.1, g_x stages 5-6 and g_w
+ *       stage 5) come to at least four 256 x 256 tiles per compute unit run them as one persistent
+ *       launch, a workgroup per compute unit walking a fixed list of tiles and loading across tile
+ *       boundaries (operands staged through registers);  0 (default): always one workgroup per tile.
  *   HLQ_OPT_SHARED_G_READ  1: for a large G, the workgroups that quantise a group of 128 rows of
  *       G (g_x stages 1-2) and those that project the same rows along the tokens (g_w stage 3) are
  *       dispatched next to one another on one XCD, so that the second reader finds the rows in that
- *       XCD's L2 and G comes from memory once (half the fetched bytes of that launch, but measured slower: the
- *       launch is not bound by bytes);  0 (default): each stage's workgroups keep their own index range.
+ *       XCD's L2 and G comes from memory once (measured at N = 4096, d_out = 11008: 98.5 MB fetched
+ *       instead of 180.6 MB, 51.5 instead of 53.0 us -- the launch is not bound by those bytes);
+ *       0 (default): each stage's workgroups keep their own index range.
+ *   HLQ_OPT_DIRECT_TO_LDS  1 (default): 256 x 256 tiles of the matrix products whose operand rows are
+ *       whole 128-byte steps (at least four per workgroup) load their operands from global memory
+ *       straight into LDS;  0: every tile stages them through registers.
  * Unknown option: HLQ_ERR_SHAPE.  Not synchronised with calls running on other host threads.
  */
 #define HLQ_OPT_PERSISTENT_PRODUCTS 1
 #define HLQ_OPT_SHARED_G_READ 2
+#define HLQ_OPT_DIRECT_TO_LDS 3
 int hlq_set_option(int option, int value);
 
 /*

@@ -207,6 +207,7 @@ def hlq_workspace_bytes(N, d_in, d_out, B, r, x_is_compressed=False) -> int:
 
 HLQ_OPT_PERSISTENT_PRODUCTS = 1
 HLQ_OPT_SHARED_G_READ = 2
+HLQ_OPT_DIRECT_TO_LDS = 3
 
 
 def hlq_set_option(option, value):

@@ -9,18 +9,30 @@
 // the k split of the g_w product are planned for the pair, not for each product alone.
 //
 // One translation unit per pair of operand kinds (k_gemm_pair_*.hip instantiate launch_pair_kinds
-// below: 64 kernels each -- two tile sizes and whole or ragged k steps per product, bf16 or fp32
+// below: 100 kernels each -- two tile sizes and whole or ragged k steps per product, the 256-tile also with
+// its operands loaded straight into LDS, bf16 or fp32
 // output, direct output or split-k partials for the g_w product); k_gemm_pair.hip plans and dispatches.
 #pragma once
 #include "gemm_body.hpp"
+#include "gemm_dl_body.hpp"
 #include "gemm_plan.hpp"
 
 namespace hlq {
 
-template <int KIND_, int W_, bool TAIL_, int OUT_> struct TileCfg {
-    static constexpr int KIND = KIND_, W = W_, OUT = OUT_;
-    static constexpr bool TAIL = TAIL_;
+// MODE: 0 = rows of whole 128-byte steps, 1 = a ragged last step, 2 = whole steps loaded straight into
+// LDS (gemm_dl_body.hpp; 256-tiles only)
+template <int KIND_, int W_, int MODE_, int OUT_> struct TileCfg {
+    static constexpr int KIND = KIND_, W = W_, OUT = OUT_, MODE = MODE_;
+    static constexpr size_t LDS = MODE_ == 2 ? kGemmDlLdsBytes : gemm_lds_bytes(W_, W_, 8);
+    static_assert(MODE_ != 2 || W_ == 4, "the direct-to-LDS body is written for 256 x 256 tiles");
 };
+
+template <class C>
+__device__ __forceinline__ void pair_tile(const GemmDev &g, int idx)
+{
+    if constexpr (C::MODE == 2) gemm_tile_dl<C::KIND, C::OUT>(g, idx);
+    else gemm_tile<C::KIND, C::W, C::W, 8, C::MODE == 1, C::OUT>(g, idx);
+}
 
 // n0 workgroups of the product that goes first (padded to n0_pad), then the other's; b_first: the
 // g_w product goes first (the plan puts the product with the longer tiles first).
@@ -31,15 +43,14 @@ __global__ __launch_bounds__(256) void k_gemm_pair(GemmDev ga, GemmDev gb, int n
     const bool in_first = b < n0_pad;
     if (in_first && b >= n0) return;                    // padding
     const int idx = in_first ? b : b - n0_pad;
-    if (in_first != (b_first != 0)) gemm_tile<CA::KIND, CA::W, CA::W, 8, CA::TAIL, CA::OUT>(ga, idx);
-    else gemm_tile<CB::KIND, CB::W, CB::W, 8, CB::TAIL, CB::OUT>(gb, idx);
+    if (in_first != (b_first != 0)) pair_tile<CA>(ga, idx);
+    else pair_tile<CB>(gb, idx);
 }
 
 template <class CA, class CB>
 static hipError_t launch_pair_tt(const GemmDev &ga, const GemmDev &gb, bool b_first, hipStream_t st)
 {
-    constexpr size_t la = gemm_lds_bytes(CA::W, CA::W, 8), lb = gemm_lds_bytes(CB::W, CB::W, 8);
-    constexpr size_t lds_bytes = la > lb ? la : lb;
+    constexpr size_t lds_bytes = CA::LDS > CB::LDS ? CA::LDS : CB::LDS;
     static bool attr_set = false;     // idempotent; racing callers set the same value
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_pair<CA, CB>),
@@ -56,27 +67,30 @@ static hipError_t launch_pair_tt(const GemmDev &ga, const GemmDev &gb, bool b_fi
 }
 
 // the g_w product writes the dtype the g_x product writes (CA::OUT), or its split-k partials
-template <class CA, int KB, int WB, bool TAILB>
+template <class CA, int KB, int WB, int MODEB>
 static hipError_t launch_pair_b(const GemmDev &ga, const GemmDev &gb, int outB, bool b_first, hipStream_t st)
 {
-    if (outB == 3) return launch_pair_tt<CA, TileCfg<KB, WB, TAILB, 3>>(ga, gb, b_first, st);
-    return launch_pair_tt<CA, TileCfg<KB, WB, TAILB, CA::OUT>>(ga, gb, b_first, st);
+    if (outB == 3) return launch_pair_tt<CA, TileCfg<KB, WB, MODEB, 3>>(ga, gb, b_first, st);
+    return launch_pair_tt<CA, TileCfg<KB, WB, MODEB, CA::OUT>>(ga, gb, b_first, st);
 }
 
 template <class CA, int KB>
-static hipError_t launch_pair_a(const GemmDev &ga, const GemmDev &gb, bool bigB, bool tailB, int outB, bool b_first,
+static hipError_t launch_pair_a(const GemmDev &ga, const GemmDev &gb, bool bigB, int modeB, int outB, bool b_first,
                                 hipStream_t st)
 {
-    if (bigB) return tailB ? launch_pair_b<CA, KB, 4, true>(ga, gb, outB, b_first, st) : launch_pair_b<CA, KB, 4, false>(ga, gb, outB, b_first, st);
-    return tailB ? launch_pair_b<CA, KB, 2, true>(ga, gb, outB, b_first, st) : launch_pair_b<CA, KB, 2, false>(ga, gb, outB, b_first, st);
+    if (bigB) {
+        if (modeB == 2) return launch_pair_b<CA, KB, 4, 2>(ga, gb, outB, b_first, st);
+        return modeB ? launch_pair_b<CA, KB, 4, 1>(ga, gb, outB, b_first, st) : launch_pair_b<CA, KB, 4, 0>(ga, gb, outB, b_first, st);
+    }
+    return modeB ? launch_pair_b<CA, KB, 2, 1>(ga, gb, outB, b_first, st) : launch_pair_b<CA, KB, 2, 0>(ga, gb, outB, b_first, st);
 }
 
-template <int KA, int KB, int WA, bool TAILA>
-static hipError_t launch_pair_o(const GemmDev &ga, const GemmDev &gb, bool f32, bool bigB, bool tailB, int outB,
+template <int KA, int KB, int WA, int MODEA>
+static hipError_t launch_pair_o(const GemmDev &ga, const GemmDev &gb, bool f32, bool bigB, int modeB, int outB,
                                 bool b_first, hipStream_t st)
 {
-    return f32 ? launch_pair_a<TileCfg<KA, WA, TAILA, 1>, KB>(ga, gb, bigB, tailB, outB, b_first, st)
-               : launch_pair_a<TileCfg<KA, WA, TAILA, 0>, KB>(ga, gb, bigB, tailB, outB, b_first, st);
+    return f32 ? launch_pair_a<TileCfg<KA, WA, MODEA, 1>, KB>(ga, gb, bigB, modeB, outB, b_first, st)
+               : launch_pair_a<TileCfg<KA, WA, MODEA, 0>, KB>(ga, gb, bigB, modeB, outB, b_first, st);
 }
 
 // every kernel of one pair of kinds; the plan comes from the caller
@@ -84,12 +98,15 @@ template <int KA, int KB>
 static hipError_t launch_pair_kinds(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB,
                                     bool b_first, hipStream_t st)
 {
-    const bool tailA = ga.Kb % 128 != 0, tailB = gb.Kb % 128 != 0;
-    if (bigA)
-        return tailA ? launch_pair_o<KA, KB, 4, true>(ga, gb, f32, bigB, tailB, outB, b_first, st)
-                     : launch_pair_o<KA, KB, 4, false>(ga, gb, f32, bigB, tailB, outB, b_first, st);
-    return tailA ? launch_pair_o<KA, KB, 2, true>(ga, gb, f32, bigB, tailB, outB, b_first, st)
-                 : launch_pair_o<KA, KB, 2, false>(ga, gb, f32, bigB, tailB, outB, b_first, st);
+    const int modeA = ga.Kb % 128 != 0 ? 1 : (bigA && gemm_dl_ok(ga.Kb, ga.splits) ? 2 : 0);
+    const int modeB = gb.Kb % 128 != 0 ? 1 : (bigB && gemm_dl_ok(gb.Kb, gb.splits) ? 2 : 0);
+    if (bigA) {
+        if (modeA == 2) return launch_pair_o<KA, KB, 4, 2>(ga, gb, f32, bigB, modeB, outB, b_first, st);
+        return modeA ? launch_pair_o<KA, KB, 4, 1>(ga, gb, f32, bigB, modeB, outB, b_first, st)
+                     : launch_pair_o<KA, KB, 4, 0>(ga, gb, f32, bigB, modeB, outB, b_first, st);
+    }
+    return modeA ? launch_pair_o<KA, KB, 2, 1>(ga, gb, f32, bigB, modeB, outB, b_first, st)
+                 : launch_pair_o<KA, KB, 2, 0>(ga, gb, f32, bigB, modeB, outB, b_first, st);
 }
 
 }  // namespace hlq

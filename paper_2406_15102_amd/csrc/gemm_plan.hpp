@@ -22,6 +22,11 @@ struct GemmPlan {
 GemmPlan plan_gemm(int M, int N, int nk, double scale, size_t ws_bytes, bool allow_split);
 GemmPlan plan_for(int kind, int M, int N, int K, size_t ws_bytes, bool allow_split);
 
+// whether a 256-tiled product with rows of Kb bytes, its k split `splits` ways, takes the kernel that
+// loads its operands straight into LDS (gemm_dl_body.hpp)
+bool gemm_dl_ok(int Kb, int splits);
+void gemm_dl_enable(bool on);
+
 // kernel argument block of one product tiled BM x BN, k split `splits` ways
 static inline GemmDev gemm_dev(int kind, const GemmArgs &a, int BM, int BN, int splits)
 {

@@ -226,6 +226,7 @@ int hlq_set_option(int option, int value)
 {
     if (option == HLQ_OPT_PERSISTENT_PRODUCTS) hlq::gemm_stream_enable(value != 0);
     else if (option == HLQ_OPT_SHARED_G_READ) hlq::front_share_enable(value != 0);
+    else if (option == HLQ_OPT_DIRECT_TO_LDS) hlq::gemm_dl_enable(value != 0);
     else return HLQ_ERR_SHAPE;
     return HLQ_OK;
 }

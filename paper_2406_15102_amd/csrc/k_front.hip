@@ -271,10 +271,11 @@ FrontColsQ front_cols_full(const void *W, int O, int I, int B, uint32_t k0, uint
 
 namespace {
 // Off by default.  Measured at 4096 x 4096 x 11008 (rocprofv3, 212 launches each way): with the shared
-// read the launch fetches 97 MB instead of 181 MB from beyond the L2s -- G comes in once -- and takes
-// 62.4 us instead of 52.7: the launch is bound by the quantiser's arithmetic and by latency, not by
-// bytes (its second read of G is served by the last-level cache), and the narrower K3 workgroups of
-// the shared form write shorter runs.
+// read the launch fetches 98.5 MB instead of 180.6 MB from beyond the L2s -- G comes in once -- and
+// takes 51.5 us instead of 53.0, the whole pass the same either way: the launch is bound by the
+// quantiser's arithmetic and by latency, not by those bytes (its second read of G is served by the
+// last-level cache).  A first form with groups of 64 rows and narrower K3 workgroups, whose write
+// runs were shorter, took 62.4 us.
 std::atomic<int> g_share_enabled{0};
 }
 void front_share_enable(bool on) { g_share_enabled.store(on ? 1 : 0); }

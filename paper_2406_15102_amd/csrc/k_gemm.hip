@@ -2,10 +2,28 @@
 // launch per product: the kernel around the tile body of gemm_body.hpp, the split-K reduction, the
 // plan (tile size, k splits) and the host-side dispatch over the template arguments.
 #include "gemm_body.hpp"
+#include "gemm_dl_body.hpp"
 #include "gemm_plan.hpp"
 #include "reduce_body.hpp"
 
+#include <atomic>
+
 namespace hlq {
+
+// operands straight into LDS (gemm_dl_body.hpp) wherever the shape allows; switched off for A/B runs
+static std::atomic<int> g_dl_enabled{1};
+void gemm_dl_enable(bool on) { g_dl_enabled.store(on ? 1 : 0); }
+bool gemm_dl_ok(int Kb, int splits)
+{
+    // whole 128-byte steps, and enough of them per workgroup to fill the ring's pipeline
+    return g_dl_enabled.load() != 0 && Kb % 128 == 0 && (Kb / 128) / splits >= 4;
+}
+
+template <int KIND, int OUT>
+__global__ __launch_bounds__(256) void k_gemm_dl(GemmDev g)
+{
+    gemm_tile_dl<KIND, OUT>(g, static_cast<int>(blockIdx.x));
+}
 
 template <int KIND, int WM, int WN, int KCH, bool TAIL, int OUT>
 __global__ __launch_bounds__(256) void k_gemm_nt(GemmDev g)
@@ -98,10 +116,26 @@ static hipError_t launch_tt(const GemmArgs &a, int splits, hipStream_t st)
     return hipGetLastError();
 }
 
+template <int KIND, int OUT>
+static hipError_t launch_dl(const GemmArgs &a, int splits, hipStream_t st)
+{
+    const GemmDev g = gemm_dev(KIND, a, 256, 256, splits);
+    static bool attr_set = false;     // idempotent; racing callers set the same value
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_dl<KIND, OUT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kGemmDlLdsBytes));
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_gemm_dl<KIND, OUT>), dim3(g.tiles_m * g.tiles_n * splits), dim3(256), kGemmDlLdsBytes, st, g);
+    return hipGetLastError();
+}
+
 template <int KIND, int WM, int WN, int KCH, int OUT>
 static hipError_t launch_o(const GemmArgs &a, int splits, hipStream_t st)
 {
     const int Kb = row_bytes(KIND, a.K);
+    if (WM == 4 && WN == 4 && gemm_dl_ok(Kb, splits)) return launch_dl<KIND, OUT>(a, splits, st);
     return (Kb % (KCH * 16) == 0) ? launch_tt<KIND, WM, WN, KCH, false, OUT>(a, splits, st)
                                   : launch_tt<KIND, WM, WN, KCH, true, OUT>(a, splits, st);
 }

@@ -19,7 +19,11 @@ __global__ __launch_bounds__(256) void k_gemm_stream(GemmDev ga, GemmDev gb)
 }
 
 namespace {
-std::atomic<int> g_stream_enabled{1};
+// Off by default: the tile-per-workgroup kernels that load their operands straight into LDS
+// (gemm_dl_body.hpp) are ahead of this form wherever it applies -- 8192 x 28672 x 8192, both products,
+// same session: 2150 us one workgroup per tile through registers, 2143 persistent, 2075 straight into
+// LDS -- and the ring of that body leaves no LDS for an epilogue that overlaps the next tile's loads.
+std::atomic<int> g_stream_enabled{0};
 
 // compute units of the current device, rounded down to a multiple of 8 (one workgroup each; the
 // tile lists are cut per XCD); 0 if unknown
@@ -81,7 +85,7 @@ bool gemm_stream_wanted(int kindA, const GemmArgs &a, int kindB, const GemmArgs 
     // Measured on MI355X against one workgroup per tile (same session, alternating): at 3.7 tiles per
     // compute unit (4096 x 4096 x 11008) the two forms take the same time within 1 %, either way;
     // at 28 tiles per compute unit (8192 x 28672 x 8192) the persistent form is 0.8 % (both products)
-    // to 1.8 % (the g_x product alone) faster.  It is used from four tiles per compute unit on.
+    // to 1.8 % (the g_x product alone) faster.  When switched on it is used from four tiles per compute unit on.
     return tiles256(a) + (b ? tiles256(*b) : 0) >= 4 * grid;
 }
 

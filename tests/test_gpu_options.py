@@ -1,7 +1,7 @@
 """The library's measurement switches (hlq_set_option) change how the work is laid out on the chip,
 never what is computed: with either setting the whole path must give the same bits.  (That the
-persistent form of the products is right against the oracle is checked by the full-size 70B-shaped
-workloads, which take it by default.)"""
+direct-to-LDS form of the products is right against the oracle is checked by the full-size
+workloads, which take it by default; the persistent form is compared with it here.)"""
 import pytest
 import torch
 
@@ -34,7 +34,7 @@ def test_persistent_products_same_bits(B, r, flags):
         hlq.hlq_set_option(hlq.HLQ_OPT_PERSISTENT_PRODUCTS, 1)
         dX1, dW1 = _run(w, G, X, W, flags=flags)
     finally:
-        hlq.hlq_set_option(hlq.HLQ_OPT_PERSISTENT_PRODUCTS, 1)
+        hlq.hlq_set_option(hlq.HLQ_OPT_PERSISTENT_PRODUCTS, 0)
     assert torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
     assert float(dX1.float().abs().max()) > 0 and float(dW1.float().abs().max()) > 0
 
@@ -50,7 +50,7 @@ def test_persistent_products_ragged_edges_same_bits():
         hlq.hlq_set_option(hlq.HLQ_OPT_PERSISTENT_PRODUCTS, 1)
         dX1, dW1 = _run(w, G, X, W)
     finally:
-        hlq.hlq_set_option(hlq.HLQ_OPT_PERSISTENT_PRODUCTS, 1)
+        hlq.hlq_set_option(hlq.HLQ_OPT_PERSISTENT_PRODUCTS, 0)
     assert torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
 
 
@@ -69,6 +69,66 @@ def test_shared_read_of_g_same_bits(B, r, N):
     finally:
         hlq.hlq_set_option(hlq.HLQ_OPT_SHARED_G_READ, 0)
     assert torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
+
+
+@pytest.mark.parametrize("N,d_in,d_out,B,r,flags", [
+    (4096, 4096, 2048, 16, 8, 0),                                   # both products on 256-tiles, whole steps
+    (4096 - 64, 4096 - 104, 2048, 32, 16, 0),                       # tiles that hang over the edges
+    (4096, 4096, 2048, 16, 8, hlq.HLQ_FLAG_GW_INT8),                # integer g_w list: int8 operands for both
+    (4096, 4096, 2048, 16, 8, hlq.HLQ_FLAG_GX_UNPACKED),            # one int8 per code for the g_x product
+    (1024, 1024, 8192, 16, 8, 0),                                   # few tiles, long reduction for the g_x product
+])
+def test_direct_to_lds_same_bits(N, d_in, d_out, B, r, flags):
+    w = wl.scaled(wl.WORKLOADS["c4"], N=N, d_in=d_in, d_out=d_out, B=B, r=r)
+    t = wl.generate(w)
+    G, X, W = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
+    try:
+        hlq.hlq_set_option(hlq.HLQ_OPT_DIRECT_TO_LDS, 0)
+        dX0, dW0 = _run(w, G, X, W, flags=flags)
+        hlq.hlq_set_option(hlq.HLQ_OPT_DIRECT_TO_LDS, 1)
+        dX1, dW1 = _run(w, G, X, W, flags=flags)
+    finally:
+        hlq.hlq_set_option(hlq.HLQ_OPT_DIRECT_TO_LDS, 1)
+    assert torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
+    assert float(dX1.float().abs().max()) > 0 and float(dW1.float().abs().max()) > 0
+
+
+@pytest.mark.parametrize("kind", ["int8", "int4", "bf16"])
+@pytest.mark.parametrize("M,Nn,K,f32", [(4096, 4096, 1024, False), (4096 - 40, 4096 - 24, 2048, True),
+                                         (512, 768, 32768, False)])
+def test_direct_to_lds_products_same_bits(kind, M, Nn, K, f32):
+    """The stage entry points of the products, operands through registers against straight into LDS:
+    256-tiles with whole steps, ragged tile edges with fp32 output, a long reduction that is split."""
+    gen = torch.Generator(device="cpu").manual_seed(M + K)
+    out = torch.float32 if f32 else torch.bfloat16
+    ws = torch.zeros(64 << 20, dtype=torch.uint8, device=DEV)
+    if kind == "bf16":
+        A = torch.randn((M, K), generator=gen).to(torch.bfloat16).to(DEV)
+        Bm = torch.randn((Nn, K), generator=gen).to(torch.bfloat16).to(DEV)
+        run = lambda C: hlq.hlq_bf16_gemm_nt(A, Bm, 1.0 / 16, C, ws)
+    else:
+        A = torch.randint(-7, 8, (M, K), generator=gen, dtype=torch.int8)
+        Bm = torch.randint(-7, 8, (Nn, K), generator=gen, dtype=torch.int8)
+        sA, sB = torch.rand(M, generator=gen).to(DEV), torch.rand(Nn, generator=gen).to(DEV)
+        if kind == "int4":
+            pack = lambda q: ((q[:, 0::2] & 15) | ((q[:, 1::2] & 15) << 4)).to(torch.uint8)
+            A4, B4 = pack(A.to(torch.int16)).to(DEV), pack(Bm.to(torch.int16)).to(DEV)
+            run = lambda C: hlq.hlq_int4_gemm_nt(A4, B4, sA, sB, 1.0 / 16, C, None, ws)
+        else:
+            Ad, Bd = A.to(DEV), Bm.to(DEV)
+            run = lambda C: hlq.hlq_int8_gemm_nt(Ad, Bd, sA, sB, 1.0 / 16, C, None, ws)
+    C0 = torch.zeros((M, Nn), dtype=out, device=DEV)
+    C1 = torch.zeros((M, Nn), dtype=out, device=DEV)
+    try:
+        hlq.hlq_set_option(hlq.HLQ_OPT_DIRECT_TO_LDS, 0)
+        run(C0)
+        hlq.hlq_set_option(hlq.HLQ_OPT_DIRECT_TO_LDS, 1)
+        run(C1)
+        torch.cuda.synchronize()
+    finally:
+        hlq.hlq_set_option(hlq.HLQ_OPT_DIRECT_TO_LDS, 1)
+    assert torch.equal(C0, C1)
+    assert float(C1.float().abs().max()) > 0
 
 
 def test_unknown_option_is_refused():
