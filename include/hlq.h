@@ -356,9 +356,10 @@ int hlq_linear_backward_cached(const void *G, const void *X, const void *Xc, con
  * iters * 8 independent MFMAs from registers (kind 0: int8 32x32x32 on random bytes, 65536 ops each;
  * kind 1: bf16 32x32x16, 32768 flops each; 2, 3, 4: fp8, fp6, fp4 32x32x64; 5: bf16 16x16x32, 16384
  * flops each; 6: int8 16x16x64, 32768 ops each; 7, 8: int8 32x32x32 on 4-bit codes times 16 -- what
- * the packed-code product feeds -- and on the codes as small integers).  Timing it gives the MFMA
+ * the packed-code product feeds -- and on the codes as small integers; 9: int8 16x16x64 on the codes
+ * times 16).  Timing it gives the MFMA
  * rate the chip sustains at its running clock for that shape and operand pattern, the practical
- * ceiling for the two matrix products of Sec. 6.1; kind outside 0..8: HLQ_ERR_SHAPE.
+ * ceiling for the two matrix products of Sec. 6.1; kind outside 0..9: HLQ_ERR_SHAPE.
  * sink: one device float (never written in practice; keeps the loop alive).
  */
 int hlq_mfma_probe(int kind, int blocks, int iters, float *sink, void *stream);

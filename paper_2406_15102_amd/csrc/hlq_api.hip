@@ -483,7 +483,7 @@ int hlq_bf16_gemm_nt(const void *A, const void *Bm, int64_t M, int64_t Nn, int64
 int hlq_mfma_probe(int kind, int blocks, int iters, float *sink, void *stream)
 {
     if (!sink) return HLQ_ERR_NULL;
-    if (kind < 0 || kind > 8 || blocks <= 0 || blocks > (1 << 20) || iters <= 0) return HLQ_ERR_SHAPE;
+    if (kind < 0 || kind > 9 || blocks <= 0 || blocks > (1 << 20) || iters <= 0) return HLQ_ERR_SHAPE;
     return launch_rc(hlq::launch_mfma_probe(kind, blocks, iters, sink, static_cast<hipStream_t>(stream)));
 }
 

@@ -64,10 +64,10 @@ __global__ __launch_bounds__(256) void k_mfma_probe(int iters, float *sink)
 #pragma unroll
         for (int i = 0; i < 8; ++i) s += acc[i][0] + acc[i][3];
         if (s == 12345.678f) sink[0] = s;
-    } else if (KIND == 6 || KIND == 7 || KIND == 8) {
+    } else if (KIND == 6 || KIND == 7 || KIND == 8 || KIND == 9) {
         // int8 operands as the g_x product has them: 4-bit codes in [-7, 7], KIND 7 times 16 (a nibble
         // in the high half of its byte, what the packed-code kernel feeds), KIND 8 as plain small
-        // integers; KIND 6: random bytes on the 16x16x64 shape
+        // integers; KIND 6: random bytes on the 16x16x64 shape, KIND 9: the codes times 16 on that shape
         typedef int v4i32 __attribute__((ext_vector_type(4)));
         v4i a[8], b[8];
 #pragma unroll
@@ -77,13 +77,14 @@ __global__ __launch_bounds__(256) void k_mfma_probe(int iters, float *sink)
                 unsigned ha = 0x9E3779B9u * static_cast<unsigned>(lane * 37 + i * 11 + e + 1);
                 unsigned hb = 0x85EBCA6Bu * static_cast<unsigned>(lane * 53 + i * 7 + e + 3);
                 if (KIND != 6) {
+                    constexpr bool HI = KIND == 7 || KIND == 9;
                     unsigned wa = 0, wb = 0;
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const int ca = static_cast<int>((ha >> (8 * q)) & 0xFF) % 15 - 7;
                         const int cb = static_cast<int>((hb >> (8 * q)) & 0xFF) % 15 - 7;
-                        wa |= (static_cast<unsigned>(KIND == 7 ? ca * 16 : ca) & 0xFFu) << (8 * q);
-                        wb |= (static_cast<unsigned>(KIND == 7 ? cb * 16 : cb) & 0xFFu) << (8 * q);
+                        wa |= (static_cast<unsigned>(HI ? ca * 16 : ca) & 0xFFu) << (8 * q);
+                        wb |= (static_cast<unsigned>(HI ? cb * 16 : cb) & 0xFFu) << (8 * q);
                     }
                     ha = wa;
                     hb = wb;
@@ -91,7 +92,7 @@ __global__ __launch_bounds__(256) void k_mfma_probe(int iters, float *sink)
                 a[i][e] = static_cast<int>(ha);
                 b[i][e] = static_cast<int>(hb);
             }
-        if (KIND == 6) {
+        if (KIND == 6 || KIND == 9) {
             v4i32 acc[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc[i] = v4i32{0};
@@ -172,6 +173,7 @@ hipError_t launch_mfma_probe(int kind, int blocks, int iters, float *sink, hipSt
         case 5: hipLaunchKernelGGL(k_mfma_probe<5>, dim3(blocks), dim3(256), 0, st, iters, sink); break;
         case 6: hipLaunchKernelGGL(k_mfma_probe<6>, dim3(blocks), dim3(256), 0, st, iters, sink); break;
         case 7: hipLaunchKernelGGL(k_mfma_probe<7>, dim3(blocks), dim3(256), 0, st, iters, sink); break;
+        case 9: hipLaunchKernelGGL(k_mfma_probe<9>, dim3(blocks), dim3(256), 0, st, iters, sink); break;
         default: hipLaunchKernelGGL(k_mfma_probe<8>, dim3(blocks), dim3(256), 0, st, iters, sink); break;
     }
     return hipGetLastError();
