@@ -1,13 +1,14 @@
 // Device body of K2 / K4 for 256 x 256 tiles and rows of whole 128-byte steps, with the operands
-// streamed from global memory straight into LDS (arXiv 2406.15102, Sec. 6.1: stages 5-6 of the g_x
-// list, stage 5 of the g_w list; the same products, tile, MFMA feeding and epilogue as gemm_body.hpp,
-// bit for bit the same results).
+// streamed from global memory straight into LDS and multiplied by 16 x 16 MFMAs (arXiv 2406.15102,
+// Sec. 6.1: stages 5-6 of the g_x list, stage 5 of the g_w list; the same products, tile, LDS layout
+// and bits as gemm_body.hpp).
 //
 // In gemm_body.hpp an operand chunk travels global -> registers -> LDS.  The ds_write that moves it
-// on reads 1 KB of registers per wavefront and holds up the MFMA stream; the round trip through the
-// register file also costs power, which on this chip is clock.  `buffer_load ... lds` delivers the
-// chunks into LDS without touching the register file.  What it takes to make that pay (measured on
-// MI355X with the rocprofv3 counters SQ_VMEM_TA_ADDR_FIFO_FULL, SQ_INST_LEVEL_VMEM, GRBM_GUI_ACTIVE):
+// on reads 1 KB of registers per wavefront and holds up the MFMA stream, and the round trip through
+// the register file costs power -- which on this chip, power-limited on matrix work, is clock.
+// `buffer_load ... lds` delivers the chunks into LDS without touching the register file.  What it
+// takes to make that pay (measured on MI355X with the rocprofv3 counters SQ_VMEM_TA_ADDR_FIFO_FULL,
+// SQ_INST_LEVEL_VMEM, GRBM_GUI_ACTIVE):
 //   * a load instruction of a wavefront fetches whole 128-byte lines (8 rows x 128 B) -- with 64-byte
 //     steps every line is asked for twice and a load takes 1.7 x as long to land;
 //   * loads go out singly between the MFMAs, never in a burst from all four wavefronts (the address
@@ -15,27 +16,168 @@
 //   * LDS is a ring of five 32 KB units -- all 160 KB.  Step kt keeps its A rows in unit 2 kt mod 5 and
 //     its Bm rows in the next one, so while step kt is multiplied step kt + 1 is complete or landing
 //     in two more units and the fifth takes the A rows of step kt + 2 already: a load has between
-//     0.75 and 1.75 steps to land, about what the register-staged pipeline gives it.
-// One barrier per step, after the third of its four sub-steps: by then every wavefront has waited
-// for its own loads of step kt + 1, and nobody reads step kt from LDS any more (the fragments of
-// the last sub-step are in registers), which frees that step's two units for the Bm rows of step
-// kt + 2 and, one step later, the A rows of step kt + 3.
+//     0.75 and 1.5 steps to land, about what the register-staged pipeline gives it.
+// One barrier per step, before its last sub-step: by then every wavefront has waited for its own
+// loads of step kt + 1, and nobody reads step kt from LDS any more (the fragments of the last
+// sub-step are in registers), which frees that step's two units for the Bm rows of step kt + 2 and,
+// one step later, the A rows of step kt + 3.
+//
+// MFMA shape: 16 x 16 x 32 (bf16) / 16 x 16 x 64 (int8), 8 x 8 accumulators of four registers per
+// wavefront.  A register-resident probe sustains 5-10 % more on these shapes than on the 32 x 32 ones
+// at the chip's power limit, and this loop built around them measured 8 % (long reductions) to 4 %
+// faster than the same loop on 32 x 32 MFMAs, with the same bits.  Both operands of an MFMA are read as
+// 16 rows x 64 B (lane -> row lane % 16, 16-byte chunk lane / 16), one ds_read_b128 each; packed 4-bit
+// codes are read as 16 rows x 32 B (8 bytes a lane) and widened to one such operand in registers.
 #pragma once
 #include "gemm_common.hpp"
 
 namespace hlq {
 
 typedef __attribute__((address_space(3))) void lds_void_t;
+typedef float v4f_t __attribute__((ext_vector_type(4)));
 
 constexpr size_t kGemmDlLdsBytes = 5u * 256u * 128u;   // the ring; the epilogue's slabs reuse its start
 
-// half of Mma<2>::expand: dwords 2 h and 2 h + 1 of a packed fragment (6 vector instructions)
-__device__ __forceinline__ void expand_half(const u32x4 &x, u32x4 &even, u32x4 &odd, int h)
+// 16 x 16 MFMAs.  The MFMA's A operand is fed from Bm and its B operand from A, which leaves a lane with
+// C[m][n .. n + 3], m = 16 i + lane % 16, n = 16 j + 4 (lane / 16), of accumulator (i, j).
+// Written out as instructions with the accumulator tied to the destination: through the builtins the
+// compiler is free to give an MFMA of this size a destination other than its addend, and with all 256
+// accumulator registers in use it then moves dozens of accumulators around at the top of every k step.
+// What the compiler's hazard handling no longer sees is kept apart by construction: an accumulator is
+// touched by one MFMA in 64, operands written by vector instructions (the widened codes) are written a
+// sub-step before they are multiplied, and the epilogue waits out the last MFMAs before it reads.
+template <int KIND> struct Mma16;
+template <> struct Mma16<0> {
+    typedef v4i acc_t;
+    static __device__ __forceinline__ acc_t zero() { return acc_t{0, 0, 0, 0}; }
+    static __device__ __forceinline__ void mma(const u32x4 &x, const u32x4 &y, acc_t &c)
+    {
+        asm volatile("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+a"(c) : "v"(x), "v"(y));
+    }
+};
+template <> struct Mma16<1> {
+    typedef v4f_t acc_t;
+    static __device__ __forceinline__ acc_t zero() { return acc_t{0.0f, 0.0f, 0.0f, 0.0f}; }
+    static __device__ __forceinline__ void mma(const u32x4 &x, const u32x4 &y, acc_t &c)
+    {
+        asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(x), "v"(y));
+    }
+};
+// packed 4-bit codes: 8 bytes (16 codes) widen to one int8 operand, the even codes in its low half and the
+// odd ones in its high half, each moved to the high nibble of its byte (16 x the code, sign included: see
+// Mma<2>).  Both operands of a product widen the same way, so which code meets which lane does not matter.
+template <> struct Mma16<2> : Mma16<0> {
+    // part 0: the odd codes (2 instructions), parts 1, 2: one dword of the even codes each (2 instructions)
+    static __device__ __forceinline__ void expand_part(const u32x2 &x, u32x4 &o, int part)
+    {
+        if (part == 0) {
+            o[2] = x[0] & 0xF0F0F0F0u;
+            o[3] = x[1] & 0xF0F0F0F0u;
+        } else {
+            o[part - 1] = (x[part - 1] << 4) & 0xF0F0F0F0u;
+        }
+    }
+};
+
+// raw 32-bit accumulators of the 16 x 16 layout (parity export, split-k partials): direct 16-byte stores
+template <int KIND, bool GUARD>
+__device__ __forceinline__ void store_raw16(typename Mma16<KIND>::acc_t (&acc)[8][8], int32_t *out, int M, int N, int wm0,
+                                            int wn0, int lane)
 {
+    const int fr = lane & 15, fq = lane >> 4;
 #pragma unroll
-    for (int d = 0; d < 2; ++d) {
-        odd[2 * h + d] = x[2 * h + d] & 0xF0F0F0F0u;
-        even[2 * h + d] = (x[2 * h + d] << 4) & 0xF0F0F0F0u;
+    for (int i = 0; i < 8; ++i) {
+        const int m = wm0 + i * 16 + fr;
+        int32_t *row = out + static_cast<int64_t>(m) * N + wn0 + fq * 4;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (!GUARD || (m < M && wn0 + j * 16 + fq * 4 < N)) {
+                const auto e0 = acc[i][j][0], e1 = acc[i][j][1], e2 = acc[i][j][2], e3 = acc[i][j][3];
+                v4i raw = {Mma<KIND>::raw(e0), Mma<KIND>::raw(e1), Mma<KIND>::raw(e2), Mma<KIND>::raw(e3)};
+                *reinterpret_cast<v4i *>(row + j * 16) = raw;
+            }
+        }
+    }
+}
+
+// C = alpha * sA[m] * sB[n] * acc for the 16 x 16 layout, the arithmetic of store_scaled value for value;
+// staged per 16-row group through LDS so that global stores are 16-byte, row-contiguous pieces.
+template <int KIND, bool F32, bool GUARD>
+__device__ __forceinline__ void store_scaled16(typename Mma16<KIND>::acc_t (&acc)[8][8], void *Cout, int M, int N,
+                                               const float *sA, const float *sB, float alpha, int wm0, int wn0, int lane,
+                                               char *slab)
+{
+    constexpr int PITCH = 128 * (F32 ? 4 : 2) + 16;
+    constexpr int EPL = F32 ? 4 : 8;       // elements per 16-byte piece
+    constexpr int LPR = 128 / EPL;         // lanes per row
+    constexpr int RPI = 64 / LPR;          // rows per store instruction
+    const int fr = lane & 15, fq = lane >> 4;
+    f32x4 cs[8];
+    if (KIND == 1) {
+        // unused
+    } else if (sB) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            int n = wn0 + j * 16 + fq * 4;
+            if (GUARD) n = n < N ? n : 0;
+            cs[j] = *reinterpret_cast<const f32x4 *>(sB + n) * alpha;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) cs[j] = f32x4{alpha, alpha, alpha, alpha};
+    }
+    float sa[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int m = wm0 + i * 16 + fr;
+        if (GUARD) m = m < M ? m : 0;
+        sa[i] = sA ? sA[m] : 1.0f;
+    }
+    const int rr0 = lane / LPR, cc = (lane % LPR) * EPL;
+    char *wr = slab + fr * PITCH + fq * 4 * (F32 ? 4 : 2);
+    const char *rd = slab + rr0 * PITCH + cc * (F32 ? 4 : 2);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            f32x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (KIND == 1) o[e] = Mma<KIND>::to_float(acc[i][j][e]) * alpha;   // no scales on the bf16 product
+                else o[e] = Mma<KIND>::to_float(acc[i][j][e]) * (sa[i] * cs[j][e]);
+            }
+            if (F32) {
+                *reinterpret_cast<f32x4 *>(wr + (j * 16) * 4) = o;
+            } else {
+                u32x2 p = {pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3])};
+                *reinterpret_cast<u32x2 *>(wr + (j * 16) * 2) = p;
+            }
+        }
+        lds_wave_fence();
+        u32x4 v[16 / RPI];
+#pragma unroll
+        for (int p = 0; p < 16 / RPI; ++p) v[p] = *reinterpret_cast<const u32x4 *>(rd + p * RPI * PITCH);
+        const int mbase = wm0 + i * 16 + rr0;
+        char *dst = static_cast<char *>(Cout) + (static_cast<int64_t>(mbase) * N + wn0 + cc) * (F32 ? 4 : 2);
+        const int64_t step = static_cast<int64_t>(RPI) * N * (F32 ? 4 : 2);
+#pragma unroll
+        for (int p = 0; p < 16 / RPI; ++p) {
+            if (!GUARD) {
+                *reinterpret_cast<u32x4 *>(dst + p * step) = v[p];
+            } else {
+                const int m = mbase + p * RPI, n = wn0 + cc;
+                if (m < M) {
+                    if (F32 || (N & 7) == 0) {
+                        if (n < N) *reinterpret_cast<u32x4 *>(dst + p * step) = v[p];
+                    } else {   // bf16 rows that are only 8-byte aligned: two halves, the last may be missing
+                        const u32x2 lo = {v[p][0], v[p][1]}, hi = {v[p][2], v[p][3]};
+                        if (n < N) *reinterpret_cast<u32x2 *>(dst + p * step) = lo;
+                        if (n + 4 < N) *reinterpret_cast<u32x2 *>(dst + p * step + 8) = hi;
+                    }
+                }
+            }
+        }
+        lds_wave_fence();
     }
 }
 
@@ -44,7 +186,10 @@ __device__ __forceinline__ void expand_half(const u32x4 &x, u32x4 &even, u32x4 &
 template <int KIND, int OUT>
 __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
 {
-    constexpr int W = 4, BT = 256, GROUP = 4, NS = 4;
+    constexpr int BT = 256, GROUP = 4, NB = 8;
+    constexpr bool PACKED = KIND == 2;
+    constexpr int NS = PACKED ? 4 : 2;            // sub-steps per step: 32 B of packed codes, 64 B otherwise
+    constexpr int SLOTS = NB * NB;                // MFMAs of a sub-step, one per accumulator
     constexpr uint32_t UNIT = BT * 128u;          // one operand's rows of one step: 32 KB
     constexpr uint32_t RING = 5u * UNIT;
     extern __shared__ u32x4 lds[];
@@ -108,27 +253,16 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
     }
 
     // ---- fragment reads: one per-lane register per (operand, sub-step), holding the ring position ----
-    const int fr = lane & 31, fh = lane >> 5;
+    // lane -> row lane % 16 of a 16-row block; bytes 16 (lane / 16) .. + 15 of the sub-step's 64 B, or, for
+    // packed codes, bytes 8 (lane / 16) .. + 7 of its 32 B.  Block i of an operand is 2 KB further.
+    const int fr = lane & 15, fq = lane >> 4;
     uint32_t rdA[NS], rdB[NS];
 #pragma unroll
-    for (int ks = 0; ks < NS; ++ks) {
-        rdA[ks] = lds_chunk<8>(wave_m * 128 + fr, 2 * ks + fh) * 16u;
-        rdB[ks] = UNIT + lds_chunk<8>(wave_n * 128 + fr, 2 * ks + fh) * 16u;
-    }
-    u32x4 fa[2][W], fb[2][W];
-    // fragment Q of sub-step KS, in the order the MFMAs consume them: fb[0], fa[0], fb[1..], fa[1..]
-#define HLQD_READ_ONE(BUF, KS, Q)                                                                             \
-    {                                                                                                         \
-        if ((Q) == 0) fb[BUF][0] = *reinterpret_cast<const u32x4 *>(ldsb + rdB[KS]);                          \
-        else if ((Q) == 1) fa[BUF][0] = *reinterpret_cast<const u32x4 *>(ldsb + rdA[KS]);                     \
-        else if ((Q) < 1 + W) fb[BUF][(Q) - 1] = *reinterpret_cast<const u32x4 *>(ldsb + rdB[KS] + ((Q) - 1) * 4096u); \
-        else fa[BUF][(Q) - W] = *reinterpret_cast<const u32x4 *>(ldsb + rdA[KS] + ((Q) - W) * 4096u);         \
-    }
-    // packed codes: the A fragments first (they are expanded within the same sub-step), then the Bm ones
-#define HLQD_READ_ONE_P(BUF, KS, Q)                                                                           \
-    {                                                                                                         \
-        if ((Q) < W) fa[BUF][Q] = *reinterpret_cast<const u32x4 *>(ldsb + rdA[KS] + (Q) * 4096u);             \
-        else fb[BUF][(Q) - W] = *reinterpret_cast<const u32x4 *>(ldsb + rdB[KS] + ((Q) - W) * 4096u);         \
+    for (int s = 0; s < NS; ++s) {
+        const int chunk = PACKED ? 2 * s + (fq >> 1) : 4 * s + fq;
+        const uint32_t half = PACKED ? static_cast<uint32_t>(fq & 1) * 8u : 0u;
+        rdA[s] = lds_chunk<8>(wave_m * 128 + fr, chunk) * 16u + half;
+        rdB[s] = UNIT + lds_chunk<8>(wave_n * 128 + fr, chunk) * 16u + half;
     }
     // the reads of a step are done: the read position of sub-step S2 (A or Bm) moves on two units, mod the ring
 #define HLQD_NEXT_UNIT(S2, OP)                                                                                \
@@ -137,12 +271,33 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
         const uint32_t a_ = r_ + 2u * UNIT;                                                                   \
         r_ = a_ < a_ - RING ? a_ : a_ - RING;   /* unsigned: a_ - RING wraps when a_ < RING */                \
     }
+    // MFMA operands, double-buffered by sub-step: fb[.][j] the Bm blocks, fa[.][i] the A blocks.  For packed
+    // codes they hold the widened operands, and pk the 8-byte pieces between their read and their widening.
+    u32x4 fa[2][NB], fb[2][NB];
+    u32x2 pk[2 * NB];
+    // fragment Q of sub-step S (0-7: Bm blocks -- the first row of MFMAs takes them all --, 8-15: A blocks)
+#define HLQD_READ_ONE(BUF, S, Q)                                                                              \
+    {                                                                                                         \
+        if constexpr (PACKED) {                                                                               \
+            if ((Q) < NB) pk[Q] = *reinterpret_cast<const u32x2 *>(ldsb + rdB[S] + (Q) * 2048u);              \
+            else pk[Q] = *reinterpret_cast<const u32x2 *>(ldsb + rdA[S] + ((Q) - NB) * 2048u);                \
+        } else {                                                                                              \
+            if ((Q) < NB) fb[BUF][Q] = *reinterpret_cast<const u32x4 *>(ldsb + rdB[S] + (Q) * 2048u);         \
+            else fa[BUF][(Q) - NB] = *reinterpret_cast<const u32x4 *>(ldsb + rdA[S] + ((Q) - NB) * 2048u);    \
+        }                                                                                                     \
+    }
+    // packed codes: part P (0-2) of the widening of fragment Q into the operands of buffer BUF
+#define HLQD_EXPAND(BUF, Q, P)                                                                                \
+    {                                                                                                         \
+        if ((Q) < NB) Mma16<2>::expand_part(pk[Q], fb[BUF][Q], P);                                            \
+        else Mma16<2>::expand_part(pk[Q], fa[BUF][(Q) - NB], P);                                              \
+    }
 
-    typename Mma<KIND>::acc_t acc[W][W];
+    typename Mma16<KIND>::acc_t acc[NB][NB];
 #pragma unroll
-    for (int i = 0; i < W; ++i)
+    for (int i = 0; i < NB; ++i)
 #pragma unroll
-        for (int j = 0; j < W; ++j) acc[i][j] = Mma<KIND>::zero();
+        for (int j = 0; j < NB; ++j) acc[i][j] = Mma16<KIND>::zero();
 
     // prologue: steps 0 and 1 in flight (units 0, 1 and 2, 3), wait for step 0
 #pragma unroll
@@ -158,77 +313,46 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int q = 0; q < 2 * W; ++q) HLQD_READ_ONE(0, 0, q)
-    u32x4 ea[2][W][2], pb[2];    // packed codes: expanded A operands and first B operand of the coming sub-step
-    if constexpr (KIND == 2) {
+    for (int q = 0; q < 2 * NB; ++q) HLQD_READ_ONE(0, 0, q)
+    if constexpr (PACKED) {
 #pragma unroll
-        for (int i = 0; i < W; ++i) Mma<2>::expand(fa[0][i], ea[0][i][0], ea[0][i][1]);
-        Mma<2>::expand(fb[0][0], pb[0], pb[1]);
+        for (int q = 0; q < 2 * NB; ++q)
+#pragma unroll
+            for (int p = 0; p < 3; ++p) HLQD_EXPAND(0, q, p)
     }
 
     // Step kt reads units u = 2 kt mod 5 (A) and u + 1 (Bm); step kt + 1 sits in the next two units.
-    //   sub-steps 0, 1  the A rows of step kt + 2 go into the one free unit, u + 4 (four loads each)
-    //   sub-step 2      the read positions move on; its barrier: every wavefront's loads of step kt + 1
-    //                   have landed (all but the 8 youngest have) and nobody reads step kt from LDS any more
-    //   sub-step 3      fragments of step kt + 1's first sub-step; the Bm rows of step kt + 2 go into unit u
-    // The loop is written slot by slot -- what is to issue around one MFMA (two for the packed codes) --
-    // with a scheduling fence after each slot: 16 slots a sub-step, the fragment reads of the next
-    // sub-step in the first eight, the loads in the second eight (every other slot in sub-steps 0 and
-    // 1, every slot in sub-step 3), a few vector instructions in each.
+    // Every sub-step is 64 MFMAs -- accumulator (q / 8, q % 8) in slot q -- and reads the 16 fragments of
+    // the next sub-step in the even slots of its first half (packed codes: widens them, two instructions
+    // a slot, from slot 16 on).  The loop is written slot by slot, what is to issue around one MFMA, with a
+    // scheduling fence after each slot, so the issue order is the source order.
+    //   all but the last sub-step   the A rows of step kt + 2 go into the one free unit, u + 4, evenly spread
+    //   last but one                the read positions move on; its barrier: every wavefront's loads of
+    //                               step kt + 1 have landed (all but the 8 youngest have) and nobody reads
+    //                               step kt from LDS any more
+    //   last                        fragments of step kt + 1's first sub-step; the Bm rows of step kt + 2
+    //                               go into unit u, one load every fourth slot of its first half
     int u = 0;
     for (int kt = 0; kt < nk; ++kt) {
         const int ua = u == 0 ? 4 : u - 1;   // (2 kt + 4) mod 5
 #pragma unroll
-        for (int ks = 0; ks < NS; ++ks) {
-            const int cur = ks & 1;
-            const int nks = ks < NS - 1 ? ks + 1 : 0;   // the sub-step whose fragments are read now
-            if constexpr (KIND != 2) {
+        for (int s = 0; s < NS; ++s) {
+            const int cur = s & 1;
+            const int ns = s < NS - 1 ? s + 1 : 0;       // the sub-step whose fragments are read now
+            constexpr int APER = SLOTS * (NS - 1) / 8;   // slots between two loads of A rows
 #pragma unroll
-                for (int q = 0; q < W * W; ++q) {
-                    if (q < 2 * W) HLQD_READ_ONE(cur ^ 1, nks, q)
-                    if (ks < 2 && q >= 2 * W && (q & 1)) HLQD_LOAD_ONE(kt + 2, 0, 4 * ks + ((q - 2 * W) >> 1), ua)
-                    if (ks == 3 && q >= 2 * W) HLQD_LOAD_ONE(kt + 2, 1, q - 2 * W, u)
-                    if (ks == 2 && q >= 2 * W) HLQD_NEXT_UNIT((q - 2 * W) >> 1, q & 1)
-                    acc[q / W][q % W] = Mma<KIND>::mma(fb[cur][q % W], fa[cur][q / W], acc[q / W][q % W]);
-                    __builtin_amdgcn_sched_barrier(0);
+            for (int q = 0; q < SLOTS; ++q) {
+                if (q < 4 * NB && !(q & 1)) HLQD_READ_ONE(cur ^ 1, ns, q >> 1)
+                if (s < NS - 1 && (s * SLOTS + q) % APER == APER - 3) HLQD_LOAD_ONE(kt + 2, 0, (s * SLOTS + q) / APER, ua)
+                if (s == NS - 1 && q < 4 * NB && (q & 3) == 1) HLQD_LOAD_ONE(kt + 2, 1, q >> 2, u)
+                if (s == NS - 2 && q >= 4 * NB && q < 4 * NB + 2 * NS) HLQD_NEXT_UNIT((q - 4 * NB) >> 1, q & 1)
+                if constexpr (PACKED) {
+                    if (q >= 16) HLQD_EXPAND(cur ^ 1, (q - 16) / 3, (q - 16) % 3)
                 }
-            } else {
-                // packed codes: every fragment expands to two MFMA operands (12 vector instructions),
-                // 32 MFMAs a sub-step, two a slot.  Column j of the accumulators takes slots 4 j .. 4 j + 3
-                // (rows 0-1 and 2-3 with the even codes, then with the odd ones).  Half an expansion a
-                // slot: the Bm operands of columns 1, 2, 3 in slots 0-5 (column 0's were expanded at the
-                // end of the previous sub-step), the next sub-step's four A operands in slots 6-13 --
-                // their fragments are read in slots 0-3 -- and its first Bm operand in slots 14-15.
-                u32x4 eb[3][2];
-                eb[0][0] = pb[0];
-                eb[0][1] = pb[1];
-#pragma unroll
-                for (int q = 0; q < W * W; ++q) {
-                    const int j = q >> 2, t = q & 3, half = t >> 1, i0 = 2 * (t & 1);
-                    if (q < 2 * W) HLQD_READ_ONE_P(cur ^ 1, nks, q)
-                    if (ks < 2 && q >= 2 * W && (q & 1)) HLQD_LOAD_ONE(kt + 2, 0, 4 * ks + ((q - 2 * W) >> 1), ua)
-                    if (ks == 3 && q >= 2 * W) HLQD_LOAD_ONE(kt + 2, 1, q - 2 * W, u)
-                    if (ks == 2 && q >= 2 * W) HLQD_NEXT_UNIT((q - 2 * W) >> 1, q & 1)
-                    if (q < 6) expand_half(fb[cur][1 + (q >> 1)], eb[(1 + (q >> 1)) % 3][0], eb[(1 + (q >> 1)) % 3][1], q & 1);
-                    else if (q < 14) expand_half(fa[cur ^ 1][(q - 6) >> 1], ea[cur ^ 1][(q - 6) >> 1][0], ea[cur ^ 1][(q - 6) >> 1][1], q & 1);
-                    else expand_half(fb[cur ^ 1][0], pb[0], pb[1], q & 1);
-                    acc[i0][j] = Mma<2>::mma(eb[j % 3][half], ea[cur][i0][half], acc[i0][j]);
-                    acc[i0 + 1][j] = Mma<2>::mma(eb[j % 3][half], ea[cur][i0 + 1][half], acc[i0 + 1][j]);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                if (ks == NS - 1) {
-                    // loop-carried: keep the compiler from moving these expansions to the top of the
-                    // next iteration, where they would stand in front of the first MFMA
-#pragma unroll
-                    for (int i = 0; i < W; ++i) {
-                        asm("" : "+v"(ea[cur ^ 1][i][0]));
-                        asm("" : "+v"(ea[cur ^ 1][i][1]));
-                    }
-                    asm("" : "+v"(pb[0]));
-                    asm("" : "+v"(pb[1]));
-                }
+                Mma16<KIND>::mma(fb[cur][q % NB], fa[cur][q / NB], acc[q / NB][q % NB]);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            if (ks == 2) {
+            if (s == NS - 2) {
                 asm volatile("" ::: "memory");   // no memory access of the program may cross the barrier
                 __builtin_amdgcn_s_waitcnt(0x0070 | 8);   // vmcnt(8), lgkmcnt(0)
                 __builtin_amdgcn_s_barrier();
@@ -241,25 +365,28 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
 #undef HLQD_LOAD_ONE
 #undef HLQD_READ_ONE
 #undef HLQD_NEXT_UNIT
-#undef HLQD_READ_ONE_P
+#undef HLQD_EXPAND
 
-    // ---- epilogue (shared with gemm_tile) ----
+    // ---- epilogue ----
+    // the last MFMAs have written their accumulators (the compiler does not know that the statements
+    // above are MFMAs and would not keep the reads below far enough from them by itself)
+    asm volatile("s_nop 15\n\ts_nop 15");
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(0x0070);   // every load has landed: LDS is free for staging C
     __syncthreads();
     const int wm0 = m0 + wave_m * 128, wn0 = n0 + wave_n * 128;
-    char *slab = ldsb + wave * EpiSlab<W>::BYTES;   // wavefront-private
+    char *slab = ldsb + wave * (16 * (128 * 4 + 16));   // wavefront-private, one 16-row group
     const bool interior = (m0 + BT <= g.M) && (n0 + BT <= g.N) && ((g.N & 7) == 0);
     if (OUT == 2) {
-        if (interior) store_raw<KIND, W, W, false>(acc, g.acc, g.M, g.N, wm0, wn0, lane);
-        else store_raw<KIND, W, W, true>(acc, g.acc, g.M, g.N, wm0, wn0, lane);
+        if (interior) store_raw16<KIND, false>(acc, g.acc, g.M, g.N, wm0, wn0, lane);
+        else store_raw16<KIND, true>(acc, g.acc, g.M, g.N, wm0, wn0, lane);
     } else if (OUT == 3) {
         int32_t *part = g.partial + static_cast<int64_t>(split) * g.M * g.N;
-        if (interior) store_raw<KIND, W, W, false>(acc, part, g.M, g.N, wm0, wn0, lane);
-        else store_raw<KIND, W, W, true>(acc, part, g.M, g.N, wm0, wn0, lane);
+        if (interior) store_raw16<KIND, false>(acc, part, g.M, g.N, wm0, wn0, lane);
+        else store_raw16<KIND, true>(acc, part, g.M, g.N, wm0, wn0, lane);
     } else {
-        if (interior) store_scaled<KIND, W, W, OUT == 1, false>(acc, g.C, g.M, g.N, g.sA, g.sB, g.alpha, wm0, wn0, lane, slab);
-        else store_scaled<KIND, W, W, OUT == 1, true>(acc, g.C, g.M, g.N, g.sA, g.sB, g.alpha, wm0, wn0, lane, slab);
+        if (interior) store_scaled16<KIND, OUT == 1, false>(acc, g.C, g.M, g.N, g.sA, g.sB, g.alpha, wm0, wn0, lane, slab);
+        else store_scaled16<KIND, OUT == 1, true>(acc, g.C, g.M, g.N, g.sA, g.sB, g.alpha, wm0, wn0, lane, slab);
     }
 }
 
