@@ -23,6 +23,9 @@ FLAGS = [
     # packed-fp32 instructions are not to be generated on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    # the k loops of the matrix products are written to be unrolled in full (a step of 256 MFMAs with
+    # everything that issues between them); the default size limit for `#pragma unroll` is below that
+    "-mllvm", "-pragma-unroll-threshold=1000000",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

@@ -323,9 +323,9 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
 
     // Step kt reads units u = 2 kt mod 5 (A) and u + 1 (Bm); step kt + 1 sits in the next two units.
     // Every sub-step is 64 MFMAs -- accumulator (q / 8, q % 8) in slot q -- and reads the 16 fragments of
-    // the next sub-step in the even slots of its first half (packed codes: widens them, two instructions
-    // a slot, from slot 16 on).  The loop is written slot by slot, what is to issue around one MFMA, with a
-    // scheduling fence after each slot, so the issue order is the source order.
+    // the next sub-step in the even slots of its first half (packed codes: see below).  The loop is written
+    // slot by slot, what is to issue around one MFMA, with a scheduling fence after each slot, so the issue
+    // order is the source order.
     //   all but the last sub-step   the A rows of step kt + 2 go into the one free unit, u + 4, evenly spread
     //   last but one                the read positions move on; its barrier: every wavefront's loads of
     //                               step kt + 1 have landed (all but the 8 youngest have) and nobody reads
@@ -339,18 +339,46 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
         for (int s = 0; s < NS; ++s) {
             const int cur = s & 1;
             const int ns = s < NS - 1 ? s + 1 : 0;       // the sub-step whose fragments are read now
-            constexpr int APER = SLOTS * (NS - 1) / 8;   // slots between two loads of A rows
+            if constexpr (!PACKED) {
+                constexpr int APER = SLOTS * (NS - 1) / 8;   // slots between two loads of A rows
 #pragma unroll
-            for (int q = 0; q < SLOTS; ++q) {
-                if (q < 4 * NB && !(q & 1)) HLQD_READ_ONE(cur ^ 1, ns, q >> 1)
-                if (s < NS - 1 && (s * SLOTS + q) % APER == APER - 3) HLQD_LOAD_ONE(kt + 2, 0, (s * SLOTS + q) / APER, ua)
-                if (s == NS - 1 && q < 4 * NB && (q & 3) == 1) HLQD_LOAD_ONE(kt + 2, 1, q >> 2, u)
-                if (s == NS - 2 && q >= 4 * NB && q < 4 * NB + 2 * NS) HLQD_NEXT_UNIT((q - 4 * NB) >> 1, q & 1)
-                if constexpr (PACKED) {
-                    if (q >= 16) HLQD_EXPAND(cur ^ 1, (q - 16) / 3, (q - 16) % 3)
+                for (int q = 0; q < SLOTS; ++q) {
+                    if (q < 4 * NB && !(q & 1)) HLQD_READ_ONE(cur ^ 1, ns, q >> 1)
+                    if (s < NS - 1 && (s * SLOTS + q) % APER == APER - 3) HLQD_LOAD_ONE(kt + 2, 0, (s * SLOTS + q) / APER, ua)
+                    if (s == NS - 1 && q < 4 * NB && (q & 3) == 1) HLQD_LOAD_ONE(kt + 2, 1, q >> 2, u)
+                    if (s == NS - 2 && q >= 4 * NB && q < 4 * NB + 2 * NS) HLQD_NEXT_UNIT((q - 4 * NB) >> 1, q & 1)
+                    Mma16<KIND>::mma(fb[cur][q % NB], fa[cur][q / NB], acc[q / NB][q % NB]);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                Mma16<KIND>::mma(fb[cur][q % NB], fa[cur][q / NB], acc[q / NB][q % NB]);
-                __builtin_amdgcn_sched_barrier(0);
+            } else {
+                // packed codes: a slot has room for the MFMA and 12 more cycles of issue -- two fragment reads,
+                // or one part of a widening (two instructions), or a load.  Slots 0-7 read the 16 fragments,
+                // slots 12, 18, ..., 54 are kept for the loads (three of the A rows in sub-steps 0 and 1, two in
+                // sub-step 2, the eight of the Bm rows in sub-step 3; read positions move on in those that stay
+                // free: the one just used, and in sub-step 0 also the one that sub-step 3 will use), and the 48
+                // parts of the widening take the other slots from 8 on.
+#pragma unroll
+                for (int q = 0; q < SLOTS; ++q) {
+                    const bool lslot = q >= 12 && q <= 54 && (q - 12) % 6 == 0;
+                    const int li = (q - 12) / 6;                       // which of the eight load slots
+                    if (q < NB) {
+                        HLQD_READ_ONE(cur ^ 1, ns, 2 * q)
+                        HLQD_READ_ONE(cur ^ 1, ns, 2 * q + 1)
+                    }
+                    if (lslot) {
+                        if (s < 2 && li % 3 == 1) HLQD_LOAD_ONE(kt + 2, 0, 3 * s + li / 3, ua)
+                        if (s == 2 && (li == 1 || li == 4)) HLQD_LOAD_ONE(kt + 2, 0, 6 + li / 3, ua)
+                        if (s == 3) HLQD_LOAD_ONE(kt + 2, 1, li, u)
+                        if (s < 3 && (li == 3 || li == 6)) HLQD_NEXT_UNIT(ns, li == 6)
+                        if (s == 0 && (li == 0 || li == 2)) HLQD_NEXT_UNIT(0, li == 2)
+                    }
+                    if (q >= 8 && !lslot) {
+                        const int e = q - 8 - (q > 12 ? (q < 54 ? (q - 12 + 5) / 6 : 8) : 0);   // rank among the widening slots
+                        HLQD_EXPAND(cur ^ 1, e / 3, e % 3)
+                    }
+                    Mma16<KIND>::mma(fb[cur][q % NB], fa[cur][q / NB], acc[q / NB][q % NB]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             if (s == NS - 2) {
                 asm volatile("" ::: "memory");   // no memory access of the program may cross the barrier
