@@ -319,6 +319,14 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
         for (int q = 0; q < 2 * NB; ++q)
 #pragma unroll
             for (int p = 0; p < 3; ++p) HLQD_EXPAND(0, q, p)
+        // an MFMA may not read a register within two instructions of the vector instruction that wrote it;
+        // inside the loop a sub-step lies between the two, here nothing does
+#pragma unroll
+        for (int q = 0; q < NB; ++q) {
+            asm volatile("" ::"v"(fb[0][q]));   // computed before this point ...
+            asm volatile("" ::"v"(fa[0][q]));
+        }
+        asm volatile("s_nop 1");                // ... and two instructions ahead of the first MFMA
     }
 
     // Step kt reads units u = 2 kt mod 5 (A) and u + 1 (Bm); step kt + 1 sits in the next two units.
