@@ -24,32 +24,43 @@ PEAK_I8_TOPS = 5000.0
 PEAK_BF16_TFLOPS = 2500.0
 
 
-WARM_MS = 60.0   # load that precedes every timed region, whatever --warmup says
+WARM_MS = 60.0        # load that precedes every timed region, whatever --warmup says
+DENSE_WARM_MS = 400.0  # the dense comparator (hipBLASLt) keeps getting faster for some 0.3 s of calls: 712 us after 60 ms
+                       # of them, 684 after 400 ms on one box; the speed-up is quoted against the settled figure
 
 
-def _warm(fn, torch, calls=0):
+def _warm(fn, torch, calls=0, warm_ms=WARM_MS):
     """Run fn() back to back for at least WARM_MS of GPU time (and at least `calls` times): after an
     idle gap the GPU needs some 30 ms of load before its clocks settle (a 130 us product measures
     150 us in the first milliseconds), so no timed region may depend on how few warm-up steps the
     caller asked for.  Batches double, so the last one alone is about half of the load."""
     start = torch.cuda.Event(enable_timing=True)
     stop = torch.cuda.Event(enable_timing=True)
-    gpu_ms, done, batch = 0.0, 0, max(8, int(calls))
-    while gpu_ms < WARM_MS or done < calls:
+    gpu_ms, done, batch, per_call = 0.0, 0, max(8, int(calls)), 0.0
+    while gpu_ms < warm_ms or done < calls:
         start.record()
         for _ in range(batch):
             fn()
         stop.record()
         stop.synchronize()
-        gpu_ms += start.elapsed_time(stop)
+        per_call = start.elapsed_time(stop) / batch
+        gpu_ms += per_call * batch
         done += batch
         batch = min(8192, batch * 2)
+    return per_call                      # milliseconds per call in the last batch
 
 
-def _event_time_us(fn, iters, torch, warm=0):
+MIN_TIMED_MS = 40.0   # auxiliary figures: a timed region this long at least, however few --steps
+
+
+def _event_time_us(fn, iters, torch, warm=0, min_ms=MIN_TIMED_MS, warm_ms=WARM_MS):
     """Average duration of fn() in microseconds, HIP events on the current (= launch) stream, after
-    _warm (at least `warm` calls and WARM_MS of the same work)."""
-    _warm(fn, torch, warm)
+    _warm (at least `warm` calls and WARM_MS of the same work).  `iters` is raised so that the timed
+    region lasts min_ms: averages over a few milliseconds swing by several per cent with the clocks.
+    (The headline figure passes min_ms = 0 and times exactly --steps steps.)"""
+    per_call = _warm(fn, torch, warm, warm_ms)
+    if min_ms > 0 and per_call > 0:
+        iters = max(iters, int(min_ms / per_call) + 1)
     start = torch.cuda.Event(enable_timing=True)
     stop = torch.cuda.Event(enable_timing=True)
     for _ in range(8):                   # the events follow load, not the idle gap of the synchronisation
@@ -148,7 +159,7 @@ def main():
         step()
     torch.cuda.synchronize()
     wall_us = (time.perf_counter() - t0) * 1e6 / args.steps
-    hlq_us = _event_time_us(step, args.steps, torch, warm=args.warmup // 2)
+    hlq_us = _event_time_us(step, args.steps, torch, warm=args.warmup // 2, min_ms=0)   # exactly --steps steps
     if args.only_path:
         print(json.dumps({"metric": "hlq_backward_dX_dW_latency", "value": round(hlq_us, 2), "unit": "us",
                           "workload": w.name, "steps": args.steps, "warmup": args.warmup, "options": args.option,
@@ -216,7 +227,9 @@ def main():
         for fn in stages.values():
             fn()
 
-    _warm(all_stages, torch, 3)
+    seq_ms = _warm(all_stages, torch, 3)
+    if seq_ms > 0:                       # the sequence, too, is timed over MIN_TIMED_MS at least
+        iters = max(iters, min(400, int(MIN_TIMED_MS / seq_ms) + 1))
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(iters)]
     all_stages()
     for it in range(iters):
@@ -302,7 +315,7 @@ def main():
 
     dXd = torch.empty_like(dX)
     dWd = torch.empty_like(dW)
-    dense_us = _event_time_us(dense, args.steps, torch, warm=args.warmup)
+    dense_us = _event_time_us(dense, args.steps, torch, warm=args.warmup, warm_ms=DENSE_WARM_MS)
 
     # ---- cold inputs: the loop above re-reads the same tensors, which the 256 MB last-level cache keeps when
     # ---- the layer is small; here every step takes the next of several input / output sets (>= 1 GB in all) ----
