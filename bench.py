@@ -113,9 +113,10 @@ def main():
     ap.add_argument("--cpu-tokens", type=int, default=4096, help="tokens of the CPU-oracle sample (0 = skip)")
     ap.add_argument("--only-path", action="store_true",
                     help="time the whole path only and print a short JSON line (what a counter profile wants to see)")
-    ap.add_argument("--option", action="append", default=[], metavar="NAME=0|1",
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="library switch for A/B runs: persistent=0|1 (persistent matrix products), "
-                         "shared_g=0|1 (K1 and K3 share one read of G), direct_lds=0|1 (operands of the products straight into LDS)")
+                         "shared_g=0|1 (K1 and K3 share one read of G), direct_lds=0|1 (operands of the products straight into LDS), "
+                         "plan_tile=0|128|256 and plan_splits=0..16 (override the plan of the products; 0 = the cost model)")
     ap.add_argument("--no-modes", action="store_true",
                     help="skip the extra whole-path timings of the method's options (keeps a profile to the default path)")
     args = ap.parse_args()
@@ -133,7 +134,8 @@ def main():
     for item in args.option:
         name, _, val = item.partition("=")
         key = {"persistent": hlq.HLQ_OPT_PERSISTENT_PRODUCTS, "shared_g": hlq.HLQ_OPT_SHARED_G_READ,
-               "direct_lds": hlq.HLQ_OPT_DIRECT_TO_LDS}[name]
+               "direct_lds": hlq.HLQ_OPT_DIRECT_TO_LDS, "plan_tile": hlq.HLQ_OPT_PLAN_TILE,
+               "plan_splits": hlq.HLQ_OPT_PLAN_SPLITS}[name]
         hlq.hlq_set_option(key, int(val))
     dev = "cuda:0"
     torch.cuda.set_device(0)

@@ -73,7 +73,8 @@ int hlq_version(void);
 size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r, int x_is_compressed);
 
 /*
- * Process-wide switches, for measurements (every setting computes the same results).
+ * Process-wide switches, for measurements (every setting computes the same results; see PLAN_SPLITS for
+ * the one qualification).
  *   HLQ_OPT_PERSISTENT_PRODUCTS  1: layers whose matrix products (Sec. 6.1, g_x stages 5-6 and g_w
  *       stage 5) come to at least four 256 x 256 tiles per compute unit run them as one persistent
  *       launch, a workgroup per compute unit walking a fixed list of tiles and loading across tile
@@ -87,11 +88,20 @@ size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r,
  *   HLQ_OPT_DIRECT_TO_LDS  1 (default): 256 x 256 tiles of the matrix products whose operand rows are
  *       whole 128-byte steps (at least four per workgroup) load their operands from global memory
  *       straight into LDS;  0: every tile stages them through registers.
- * Unknown option: HLQ_ERR_SHAPE.  Not synchronised with calls running on other host threads.
+ *   HLQ_OPT_PLAN_TILE  0 (default): a cost model picks 128 x 128 or 256 x 256 tiles for each matrix product;
+ *       128 or 256: every product takes that tile.
+ *   HLQ_OPT_PLAN_SPLITS  0 (default): the model picks the k split of a product with few output tiles (of
+ *       the g_w product when the two share a launch);  1..16: that split, cut down to the steps of the
+ *       reduction and to the split-k scratch at hand.  The workspace sizes are computed under the same
+ *       setting, so set it before asking for them.  A different split sums the bf16 product in a
+ *       different order: dW then agrees to rounding, not bit for bit; everything else stays bit-equal.
+ * Unknown option or value: HLQ_ERR_SHAPE.  Not synchronised with calls running on other host threads.
  */
 #define HLQ_OPT_PERSISTENT_PRODUCTS 1
 #define HLQ_OPT_SHARED_G_READ 2
 #define HLQ_OPT_DIRECT_TO_LDS 3
+#define HLQ_OPT_PLAN_TILE 4
+#define HLQ_OPT_PLAN_SPLITS 5
 int hlq_set_option(int option, int value);
 
 /*

@@ -208,6 +208,8 @@ def hlq_workspace_bytes(N, d_in, d_out, B, r, x_is_compressed=False) -> int:
 HLQ_OPT_PERSISTENT_PRODUCTS = 1
 HLQ_OPT_SHARED_G_READ = 2
 HLQ_OPT_DIRECT_TO_LDS = 3
+HLQ_OPT_PLAN_TILE = 4
+HLQ_OPT_PLAN_SPLITS = 5
 
 
 def hlq_set_option(option, value):

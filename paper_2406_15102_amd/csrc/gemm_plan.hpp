@@ -22,6 +22,13 @@ struct GemmPlan {
 GemmPlan plan_gemm(int M, int N, int nk, double scale, size_t ws_bytes, bool allow_split);
 GemmPlan plan_for(int kind, int M, int N, int K, size_t ws_bytes, bool allow_split);
 
+// measurement overrides of the plans (hlq_set_option): tile = 0 (the model decides), 128 or 256 for every
+// product; splits = 0 (the model decides) or the k split of a single product / of the g_w product of a
+// pair, cut down to what the reduction and the scratch allow.  A negative argument leaves that setting.
+void gemm_plan_force(int tile, int splits);
+int gemm_plan_forced_tile();
+int gemm_plan_forced_splits(int nk, double mn, size_t ws_bytes, bool allow_split);
+
 // whether a 256-tiled product with rows of Kb bytes, its k split `splits` ways, takes the kernel that
 // loads its operands straight into LDS (gemm_dl_body.hpp)
 bool gemm_dl_ok(int Kb, int splits);

@@ -64,10 +64,34 @@ GemmPlan plan_gemm(int M, int N, int nk, double scale, size_t ws_bytes, bool all
     return best;
 }
 
+// plan overrides for measurements (hlq_set_option): 0 = the cost model decides
+static std::atomic<int> g_plan_tile{0}, g_plan_splits{0};
+void gemm_plan_force(int tile, int splits)
+{
+    if (tile >= 0) g_plan_tile.store(tile);
+    if (splits >= 0) g_plan_splits.store(splits);
+}
+int gemm_plan_forced_tile() { return g_plan_tile.load(); }
+// the forced k split, cut down to what the reduction (nk steps) and the scratch (bytes for M x N partials) allow
+int gemm_plan_forced_splits(int nk, double mn, size_t ws_bytes, bool allow_split)
+{
+    int S = g_plan_splits.load();
+    if (S <= 0) return 0;
+    if (!allow_split) return 1;
+    if (S > 16) S = 16;
+    if (S > nk) S = nk;
+    while (S > 1 && static_cast<double>(S) * mn * 4.0 > static_cast<double>(ws_bytes)) --S;
+    return S < 1 ? 1 : S;
+}
+
 GemmPlan plan_for(int kind, int M, int N, int K, size_t ws_bytes, bool allow_split)
 {
     // a step of the packed product carries twice the MFMAs of a byte-operand step
-    return plan_gemm(M, N, (row_bytes(kind, K) + 127) / 128, kind == 2 ? P4_STEP_SCALE : 1.0, ws_bytes, allow_split);
+    const int nk = (row_bytes(kind, K) + 127) / 128;
+    GemmPlan p = plan_gemm(M, N, nk, kind == 2 ? P4_STEP_SCALE : 1.0, ws_bytes, allow_split);
+    if (const int t = gemm_plan_forced_tile()) p.big = t == 256;
+    if (const int S = gemm_plan_forced_splits(nk, static_cast<double>(M) * N, ws_bytes, allow_split)) p.splits = S;
+    return p;
 }
 
 size_t gemm_ws_bytes(int kind, int M, int N, int K)

@@ -107,6 +107,8 @@ static PairPlan plan_pair(const GemmArgs &a, int kindA, const GemmArgs &b, int k
             }
         }
     }
+    if (const int t = gemm_plan_forced_tile()) best.bigA = best.bigB = t == 256;
+    if (const int S = gemm_plan_forced_splits(nkB, mnB, ws_bytes, ws_bytes > 0)) best.splitsB = S;
     return best;
 }
 

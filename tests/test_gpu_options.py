@@ -131,7 +131,39 @@ def test_direct_to_lds_products_same_bits(kind, M, Nn, K, f32):
     assert float(C1.float().abs().max()) > 0
 
 
+@pytest.mark.parametrize("tile,splits", [(256, 1), (256, 2), (256, 3), (128, 1), (128, 4)])
+def test_forced_plans_agree(tile, splits):
+    """Every plan of the products computes the same pass: dX bit for bit, dW to the rounding of a
+    different summation order; with the plan held fixed, operands through registers and straight
+    into LDS give the same bits (this is what reaches the split-k form of the straight-into-LDS body)."""
+    w = wl.scaled(wl.WORKLOADS["c4"], N=2048, d_in=1024 + 24, d_out=2048, B=16, r=8)   # whole k steps for both products, ragged tile edges
+    t = wl.generate(w)
+    G, X, W = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
+    dX_auto, dW_auto = _run(w, G, X, W)
+    try:
+        hlq.hlq_set_option(hlq.HLQ_OPT_PLAN_TILE, tile)
+        hlq.hlq_set_option(hlq.HLQ_OPT_PLAN_SPLITS, splits)
+        Kc = w.N // w.B * w.r
+        plan = hlq.hlq_backward_products_plan(w.N, w.d_in, w.d_out, Kc, hlq.HLQ_BITS_4_PACKED, False, 1 << 28)
+        assert plan[:3] == (tile, tile, splits)
+        dX1, dW1 = _run(w, G, X, W)
+        hlq.hlq_set_option(hlq.HLQ_OPT_DIRECT_TO_LDS, 0)
+        dX0, dW0 = _run(w, G, X, W)
+    finally:
+        hlq.hlq_set_option(hlq.HLQ_OPT_DIRECT_TO_LDS, 1)
+        hlq.hlq_set_option(hlq.HLQ_OPT_PLAN_TILE, 0)
+        hlq.hlq_set_option(hlq.HLQ_OPT_PLAN_SPLITS, 0)
+    assert torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
+    assert torch.equal(dX1, dX_auto)
+    d = (dW1.float() - dW_auto.float()).abs()
+    assert float((d / (dW_auto.float().abs() + 1e-6)).median()) < 1e-2 and float(d.max()) <= 2 ** -6 * float(dW_auto.float().abs().max())
+
+
 def test_unknown_option_is_refused():
     with pytest.raises(hlq.HlqError) as ei:
         hlq.hlq_set_option(99, 1)
     assert ei.value.status == 2
+    with pytest.raises(hlq.HlqError):
+        hlq.hlq_set_option(hlq.HLQ_OPT_PLAN_TILE, 192)
+    with pytest.raises(hlq.HlqError):
+        hlq.hlq_set_option(hlq.HLQ_OPT_PLAN_SPLITS, 17)
