@@ -116,6 +116,7 @@ def main():
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="library switch for A/B runs: persistent=0|1 (persistent matrix products), "
                          "shared_g=0|1 (K1 and K3 share one read of G), direct_lds=0|1 (operands of the products straight into LDS), "
+                         "tail_tiles=0|1 (192-row tiles for a product's last partial round), "
                          "plan_tile=0|128|256 and plan_splits=0..16 (override the plan of the products; 0 = the cost model)")
     ap.add_argument("--no-modes", action="store_true",
                     help="skip the extra whole-path timings of the method's options (keeps a profile to the default path)")
@@ -135,7 +136,7 @@ def main():
         name, _, val = item.partition("=")
         key = {"persistent": hlq.HLQ_OPT_PERSISTENT_PRODUCTS, "shared_g": hlq.HLQ_OPT_SHARED_G_READ,
                "direct_lds": hlq.HLQ_OPT_DIRECT_TO_LDS, "plan_tile": hlq.HLQ_OPT_PLAN_TILE,
-               "plan_splits": hlq.HLQ_OPT_PLAN_SPLITS}[name]
+               "plan_splits": hlq.HLQ_OPT_PLAN_SPLITS, "tail_tiles": hlq.HLQ_OPT_TAIL_TILES}[name]
         hlq.hlq_set_option(key, int(val))
     dev = "cuda:0"
     torch.cuda.set_device(0)

@@ -88,6 +88,10 @@ size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r,
  *   HLQ_OPT_DIRECT_TO_LDS  1 (default): 256 x 256 tiles of the matrix products whose operand rows are
  *       whole 128-byte steps (at least four per workgroup) load their operands from global memory
  *       straight into LDS;  0: every tile stages them through registers.
+ *   HLQ_OPT_TAIL_TILES  1 (default): a product on 256 x 256 tiles that loads straight into LDS and would
+ *       leave most compute units idle in its last round hands its last rows to tiles of 192 x 256, which
+ *       shortens that round by a quarter (the g_w product when it closes the launch of both products, or a
+ *       product launched alone; not the packed codes);  0: 256 x 256 tiles throughout.
  *   HLQ_OPT_PLAN_TILE  0 (default): a cost model picks 128 x 128 or 256 x 256 tiles for each matrix product;
  *       128 or 256: every product takes that tile.
  *   HLQ_OPT_PLAN_SPLITS  0 (default): the model picks the k split of a product with few output tiles (of
@@ -102,6 +106,7 @@ size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r,
 #define HLQ_OPT_DIRECT_TO_LDS 3
 #define HLQ_OPT_PLAN_TILE 4
 #define HLQ_OPT_PLAN_SPLITS 5
+#define HLQ_OPT_TAIL_TILES 6
 int hlq_set_option(int option, int value);
 
 /*

@@ -1,4 +1,4 @@
-// Device body of K2 / K4 for 256 x 256 tiles and rows of whole 128-byte steps, with the operands
+// Device body of K2 / K4 for 256 x 256 (or 192 x 256) tiles and rows of whole 128-byte steps, with the operands
 // streamed from global memory straight into LDS and multiplied by 16 x 16 MFMAs (arXiv 2406.15102,
 // Sec. 6.1: stages 5-6 of the g_x list, stage 5 of the g_w list; the same products, tile, LDS layout
 // and bits as gemm_body.hpp).
@@ -28,6 +28,11 @@
 // faster than the same loop on 32 x 32 MFMAs, with the same bits.  Both operands of an MFMA are read as
 // 16 rows x 64 B (lane -> row lane % 16, 16-byte chunk lane / 16), one ds_read_b128 each; packed 4-bit
 // codes are read as 16 rows x 32 B (8 bytes a lane) and widened to one such operand in registers.
+//
+// A second tile shape, 192 rows x 256 columns (6 x 8 accumulators per wavefront, three quarters of the
+// work), serves the last rows of a product whose 256-row tiles would leave most compute units idle in
+// their last round: 11008 x 4096 is 688 tiles of 256 x 256, 2.69 rounds on 256 compute units; with the
+// last 2816 rows in 192-row tiles it is 512 + 240 tiles, two rounds and one of three-quarter tiles.
 #pragma once
 #include "gemm_common.hpp"
 
@@ -80,13 +85,13 @@ template <> struct Mma16<2> : Mma16<0> {
 };
 
 // raw 32-bit accumulators of the 16 x 16 layout (parity export, split-k partials): direct 16-byte stores
-template <int KIND, bool GUARD>
-__device__ __forceinline__ void store_raw16(typename Mma16<KIND>::acc_t (&acc)[8][8], int32_t *out, int M, int N, int wm0,
+template <int KIND, int NBM, bool GUARD>
+__device__ __forceinline__ void store_raw16(typename Mma16<KIND>::acc_t (&acc)[NBM][8], int32_t *out, int M, int N, int wm0,
                                             int wn0, int lane)
 {
     const int fr = lane & 15, fq = lane >> 4;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < NBM; ++i) {
         const int m = wm0 + i * 16 + fr;
         int32_t *row = out + static_cast<int64_t>(m) * N + wn0 + fq * 4;
 #pragma unroll
@@ -102,8 +107,8 @@ __device__ __forceinline__ void store_raw16(typename Mma16<KIND>::acc_t (&acc)[8
 
 // C = alpha * sA[m] * sB[n] * acc for the 16 x 16 layout, the arithmetic of store_scaled value for value;
 // staged per 16-row group through LDS so that global stores are 16-byte, row-contiguous pieces.
-template <int KIND, bool F32, bool GUARD>
-__device__ __forceinline__ void store_scaled16(typename Mma16<KIND>::acc_t (&acc)[8][8], void *Cout, int M, int N,
+template <int KIND, int NBM, bool F32, bool GUARD>
+__device__ __forceinline__ void store_scaled16(typename Mma16<KIND>::acc_t (&acc)[NBM][8], void *Cout, int M, int N,
                                                const float *sA, const float *sB, float alpha, int wm0, int wn0, int lane,
                                                char *slab)
 {
@@ -126,9 +131,9 @@ __device__ __forceinline__ void store_scaled16(typename Mma16<KIND>::acc_t (&acc
 #pragma unroll
         for (int j = 0; j < 8; ++j) cs[j] = f32x4{alpha, alpha, alpha, alpha};
     }
-    float sa[8];
+    float sa[NBM];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < NBM; ++i) {
         int m = wm0 + i * 16 + fr;
         if (GUARD) m = m < M ? m : 0;
         sa[i] = sA ? sA[m] : 1.0f;
@@ -137,7 +142,7 @@ __device__ __forceinline__ void store_scaled16(typename Mma16<KIND>::acc_t (&acc
     char *wr = slab + fr * PITCH + fq * 4 * (F32 ? 4 : 2);
     const char *rd = slab + rr0 * PITCH + cc * (F32 ? 4 : 2);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < NBM; ++i) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             f32x4 o;
@@ -182,14 +187,17 @@ __device__ __forceinline__ void store_scaled16(typename Mma16<KIND>::acc_t (&acc
 }
 
 // OUT as in gemm_tile; `bid`: index of the workgroup among those of this product.
-// Requires g.Kb % 128 == 0 and tiles of 256 x 256 (g.tiles_m, g.tiles_n counted in such tiles).
-template <int KIND, int OUT>
+// Requires g.Kb % 128 == 0 and tiles of 32 NBM rows x 256 columns, NBM = 8 or 6 (g.tiles_m, g.tiles_n counted
+// in such tiles; the 192-row tile is not written for packed codes).
+template <int KIND, int NBM, int OUT>
 __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
 {
-    constexpr int BT = 256, GROUP = 4, NB = 8;
+    constexpr int BT = 256, BTM = 32 * NBM, GROUP = 4, NB = 8;
     constexpr bool PACKED = KIND == 2;
+    static_assert(NBM == 8 || (NBM == 6 && !PACKED), "tiles of 256 x 256, or 192 x 256 for byte and bf16 operands");
     constexpr int NS = PACKED ? 4 : 2;            // sub-steps per step: 32 B of packed codes, 64 B otherwise
-    constexpr int SLOTS = NB * NB;                // MFMAs of a sub-step, one per accumulator
+    constexpr int SLOTS = NBM * NB;               // MFMAs of a sub-step, one per accumulator
+    constexpr int NR = NBM + NB;                  // fragments of a sub-step
     constexpr uint32_t UNIT = BT * 128u;          // one operand's rows of one step: 32 KB
     constexpr uint32_t RING = 5u * UNIT;
     extern __shared__ u32x4 lds[];
@@ -215,9 +223,10 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
         tm = first_m + within % gsz;
         tn = within / gsz;
     }
-    const int m0 = tm * BT, n0 = tn * BT;
+    const int m0 = tm * BTM, n0 = tn * BT;
 
     // ---- loads: instruction j of this wavefront fills rows 8 (4 j + wave) .. + 7 of an operand ----
+    // (NBM instructions for the A rows, 8 for the Bm rows)
     // 1 KB of LDS in lane order: lane -> row lane / 8 of the block, position lane % 8 of the row, which
     // in the swizzled layout (lds_chunk<8>) holds chunk position ^ (row & 7) ^ (row >> 3 & 1) of that
     // row.  Rows past the end of an operand are redirected to the tile's first row (never stored).
@@ -225,14 +234,14 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
     const char *baseB = g.Bm + static_cast<int64_t>(n0) * g.Kb;
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(baseA), 0, 0x7FFFFFFF, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsB = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(baseB), 0, 0x7FFFFFFF, 0x00020000);
-    uint32_t offa[8], offb[8];
+    uint32_t offa[NBM], offb[8];
     {
         const int rb = lane >> 3, slot = lane & 7;
         const uint32_t c16 = static_cast<uint32_t>(slot ^ rb ^ (wave & 1)) * 16u;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int row = 8 * (4 * j + wave) + rb;
-            offa[j] = static_cast<uint32_t>(m0 + row < g.M ? row : 0) * static_cast<uint32_t>(g.Kb) + c16;
+            if (j < NBM) offa[j < NBM ? j : 0] = static_cast<uint32_t>(m0 + row < g.M ? row : 0) * static_cast<uint32_t>(g.Kb) + c16;
             offb[j] = static_cast<uint32_t>(n0 + row < g.N ? row : 0) * static_cast<uint32_t>(g.Kb) + c16;
         }
     }
@@ -261,7 +270,7 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
     for (int s = 0; s < NS; ++s) {
         const int chunk = PACKED ? 2 * s + (fq >> 1) : 4 * s + fq;
         const uint32_t half = PACKED ? static_cast<uint32_t>(fq & 1) * 8u : 0u;
-        rdA[s] = lds_chunk<8>(wave_m * 128 + fr, chunk) * 16u + half;
+        rdA[s] = lds_chunk<8>(wave_m * (16 * NBM) + fr, chunk) * 16u + half;
         rdB[s] = UNIT + lds_chunk<8>(wave_n * 128 + fr, chunk) * 16u + half;
     }
     // the reads of a step are done: the read position of sub-step S2 (A or Bm) moves on two units, mod the ring
@@ -273,8 +282,8 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
     }
     // MFMA operands, double-buffered by sub-step: fb[.][j] the Bm blocks, fa[.][i] the A blocks.  For packed
     // codes they hold the widened operands, and pk the 8-byte pieces between their read and their widening.
-    u32x4 fa[2][NB], fb[2][NB];
-    u32x2 pk[2 * NB];
+    u32x4 fa[2][NBM], fb[2][NB];
+    u32x2 pk[NR];
     // fragment Q of sub-step S (0-7: Bm blocks -- the first row of MFMAs takes them all --, 8-15: A blocks)
 #define HLQD_READ_ONE(BUF, S, Q)                                                                              \
     {                                                                                                         \
@@ -293,30 +302,30 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
         else Mma16<2>::expand_part(pk[Q], fa[BUF][(Q) - NB], P);                                              \
     }
 
-    typename Mma16<KIND>::acc_t acc[NB][NB];
+    typename Mma16<KIND>::acc_t acc[NBM][NB];
 #pragma unroll
-    for (int i = 0; i < NB; ++i)
+    for (int i = 0; i < NBM; ++i)
 #pragma unroll
         for (int j = 0; j < NB; ++j) acc[i][j] = Mma16<KIND>::zero();
 
     // prologue: steps 0 and 1 in flight (units 0, 1 and 2, 3), wait for step 0
 #pragma unroll
-    for (int j = 0; j < 8; ++j) HLQD_LOAD_ONE(0, 0, j, 0)
+    for (int j = 0; j < NBM; ++j) HLQD_LOAD_ONE(0, 0, j, 0)
 #pragma unroll
     for (int j = 0; j < 8; ++j) HLQD_LOAD_ONE(0, 1, j, 1)
 #pragma unroll
-    for (int j = 0; j < 8; ++j) HLQD_LOAD_ONE(1, 0, j, 2)
+    for (int j = 0; j < NBM; ++j) HLQD_LOAD_ONE(1, 0, j, 2)
 #pragma unroll
     for (int j = 0; j < 8; ++j) HLQD_LOAD_ONE(1, 1, j, 3)
     asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0x0070 | (16 & 15) | ((16 >> 4) << 14));   // vmcnt(16): step 0 has landed
+    __builtin_amdgcn_s_waitcnt(0x0070 | (NR & 15) | ((NR >> 4) << 14));   // vmcnt(NR): step 0 has landed
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
 #pragma unroll
-    for (int q = 0; q < 2 * NB; ++q) HLQD_READ_ONE(0, 0, q)
+    for (int q = 0; q < NR; ++q) HLQD_READ_ONE(0, 0, q)
     if constexpr (PACKED) {
 #pragma unroll
-        for (int q = 0; q < 2 * NB; ++q)
+        for (int q = 0; q < NR; ++q)
 #pragma unroll
             for (int p = 0; p < 3; ++p) HLQD_EXPAND(0, q, p)
         // an MFMA may not read a register within two instructions of the vector instruction that wrote it;
@@ -348,10 +357,10 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
             const int cur = s & 1;
             const int ns = s < NS - 1 ? s + 1 : 0;       // the sub-step whose fragments are read now
             if constexpr (!PACKED) {
-                constexpr int APER = SLOTS * (NS - 1) / 8;   // slots between two loads of A rows
+                constexpr int APER = SLOTS * (NS - 1) / NBM;   // slots between two loads of A rows
 #pragma unroll
                 for (int q = 0; q < SLOTS; ++q) {
-                    if (q < 4 * NB && !(q & 1)) HLQD_READ_ONE(cur ^ 1, ns, q >> 1)
+                    if (q < 2 * NR && !(q & 1)) HLQD_READ_ONE(cur ^ 1, ns, q >> 1)
                     if (s < NS - 1 && (s * SLOTS + q) % APER == APER - 3) HLQD_LOAD_ONE(kt + 2, 0, (s * SLOTS + q) / APER, ua)
                     if (s == NS - 1 && q < 4 * NB && (q & 3) == 1) HLQD_LOAD_ONE(kt + 2, 1, q >> 2, u)
                     if (s == NS - 2 && q >= 4 * NB && q < 4 * NB + 2 * NS) HLQD_NEXT_UNIT((q - 4 * NB) >> 1, q & 1)
@@ -390,7 +399,7 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
             }
             if (s == NS - 2) {
                 asm volatile("" ::: "memory");   // no memory access of the program may cross the barrier
-                __builtin_amdgcn_s_waitcnt(0x0070 | 8);   // vmcnt(8), lgkmcnt(0)
+                __builtin_amdgcn_s_waitcnt(0x0070 | NBM);   // vmcnt(NBM): all but the A rows of step kt + 2; lgkmcnt(0)
                 __builtin_amdgcn_s_barrier();
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_sched_barrier(0);
@@ -410,19 +419,19 @@ __device__ __forceinline__ void gemm_tile_dl(const GemmDev &g, const int bid)
     asm volatile("" ::: "memory");
     __builtin_amdgcn_s_waitcnt(0x0070);   // every load has landed: LDS is free for staging C
     __syncthreads();
-    const int wm0 = m0 + wave_m * 128, wn0 = n0 + wave_n * 128;
+    const int wm0 = m0 + wave_m * (16 * NBM), wn0 = n0 + wave_n * 128;
     char *slab = ldsb + wave * (16 * (128 * 4 + 16));   // wavefront-private, one 16-row group
-    const bool interior = (m0 + BT <= g.M) && (n0 + BT <= g.N) && ((g.N & 7) == 0);
+    const bool interior = (m0 + BTM <= g.M) && (n0 + BT <= g.N) && ((g.N & 7) == 0);
     if (OUT == 2) {
-        if (interior) store_raw16<KIND, false>(acc, g.acc, g.M, g.N, wm0, wn0, lane);
-        else store_raw16<KIND, true>(acc, g.acc, g.M, g.N, wm0, wn0, lane);
+        if (interior) store_raw16<KIND, NBM, false>(acc, g.acc, g.M, g.N, wm0, wn0, lane);
+        else store_raw16<KIND, NBM, true>(acc, g.acc, g.M, g.N, wm0, wn0, lane);
     } else if (OUT == 3) {
         int32_t *part = g.partial + static_cast<int64_t>(split) * g.M * g.N;
-        if (interior) store_raw16<KIND, false>(acc, part, g.M, g.N, wm0, wn0, lane);
-        else store_raw16<KIND, true>(acc, part, g.M, g.N, wm0, wn0, lane);
+        if (interior) store_raw16<KIND, NBM, false>(acc, part, g.M, g.N, wm0, wn0, lane);
+        else store_raw16<KIND, NBM, true>(acc, part, g.M, g.N, wm0, wn0, lane);
     } else {
-        if (interior) store_scaled16<KIND, OUT == 1, false>(acc, g.C, g.M, g.N, g.sA, g.sB, g.alpha, wm0, wn0, lane, slab);
-        else store_scaled16<KIND, OUT == 1, true>(acc, g.C, g.M, g.N, g.sA, g.sB, g.alpha, wm0, wn0, lane, slab);
+        if (interior) store_scaled16<KIND, NBM, OUT == 1, false>(acc, g.C, g.M, g.N, g.sA, g.sB, g.alpha, wm0, wn0, lane, slab);
+        else store_scaled16<KIND, NBM, OUT == 1, true>(acc, g.C, g.M, g.N, g.sA, g.sB, g.alpha, wm0, wn0, lane, slab);
     }
 }
 

@@ -34,6 +34,31 @@ int gemm_plan_forced_splits(int nk, double mn, size_t ws_bytes, bool allow_split
 bool gemm_dl_ok(int Kb, int splits);
 void gemm_dl_enable(bool on);
 
+// Rows at the end of a product of M x N in 256 x 256 tiles that are better served by 192-row tiles
+// (gemm_dl_body.hpp), 0 = none: when `before` tiles of the same launch are dispatched ahead of it and its
+// last round on `slots` compute units would be partly empty, the row tiles that reach into that round --
+// and as many more as it takes for the rest to fit the full rounds -- are cut into 192-row tiles if those
+// then fit one round: the last round shrinks to three quarters.  Switched off by gemm_tail_enable(false).
+void gemm_tail_enable(bool on);
+bool gemm_tail_enabled();
+static inline int gemm_tail_rows(int M, int N, int before, int slots = 256)
+{
+    if (!gemm_tail_enabled()) return 0;
+    const int tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256;
+    const int64_t total = static_cast<int64_t>(before) + static_cast<int64_t>(tiles_m) * tiles_n;
+    const int rem = static_cast<int>(total % slots);
+    if (rem == 0 || total < slots) return 0;               // whole rounds, or less than one
+    const int64_t cap = total - rem;                          // what the full rounds hold
+    const int rt = (rem + tiles_n - 1) / tiles_n;             // row tiles that reach into the last round
+    if (rt > tiles_m) return 0;
+    const int main_rows = (tiles_m - rt) * 256;
+    const int tail_rows = M - main_rows;
+    const int64_t main_tiles = static_cast<int64_t>(tiles_m - rt) * tiles_n;
+    const int64_t tail_tiles = static_cast<int64_t>((tail_rows + 191) / 192) * tiles_n;
+    if (before + main_tiles + tail_tiles > cap + slots) return 0;   // the 192-row tiles would start another round
+    return tail_rows;
+}
+
 // kernel argument block of one product tiled BM x BN, k split `splits` ways
 static inline GemmDev gemm_dev(int kind, const GemmArgs &a, int BM, int BN, int splits)
 {
@@ -54,6 +79,23 @@ static inline GemmDev gemm_dev(int kind, const GemmArgs &a, int BM, int BN, int 
     g.splits = splits;
     g.partial = static_cast<int32_t *>(a.ws);
     return g;
+}
+
+// the last `tail_rows` rows of the product `g` (tiled 256 x 256, no k split, output C) as a product of
+// its own in tiles of 192 x 256; `g` is cut back to the rows before them
+static inline GemmDev gemm_dev_cut_tail(GemmDev &g, int tail_rows)
+{
+    GemmDev t = g;
+    const int main_rows = g.M - tail_rows;
+    const int64_t esz = g.c_is_f32 ? 4 : 2;
+    t.A = g.A + static_cast<int64_t>(main_rows) * g.Kb;
+    t.M = tail_rows;
+    t.sA = g.sA ? g.sA + main_rows : nullptr;
+    t.C = static_cast<char *>(g.C) + static_cast<int64_t>(main_rows) * g.N * esz;
+    t.tiles_m = (tail_rows + 191) / 192;
+    g.M = main_rows;
+    g.tiles_m = main_rows / 256;
+    return t;
 }
 
 // dynamic LDS of a workgroup: two operand stages, or the four epilogue slabs if those are larger

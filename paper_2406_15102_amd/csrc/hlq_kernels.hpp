@@ -232,6 +232,7 @@ bool gemm_stream_wanted(int kindA, const GemmArgs &a, int kindB, const GemmArgs 
 hipError_t launch_gemm_stream(int kindA, const GemmArgs &a, int kindB, const GemmArgs *b, hipStream_t st);
 void gemm_stream_enable(bool on);
 void gemm_dl_enable(bool on);   // operands of 256-tiles straight into LDS where the shape allows (default on)
+void gemm_tail_enable(bool on);   // 192-row tiles for the last rows of a product whose last round would be partly empty (default on)
 void gemm_plan_force(int tile, int splits);   // measurement overrides of the plans, see gemm_plan.hpp
 // What launch_gemm_pair would do with these shapes and this much split-k scratch, without doing it:
 // plan[0], plan[1] = tile edge (256 or 128) of a's and b's product, plan[2] = k splits of b,

@@ -19,10 +19,19 @@ bool gemm_dl_ok(int Kb, int splits)
     return g_dl_enabled.load() != 0 && Kb % 128 == 0 && (Kb / 128) / splits >= 4;
 }
 
+// `gt`: the product's last rows in 192-row tiles (gt.tiles_m = 0: none), dispatched behind the n_main
+// workgroups of the 256-row tiles
 template <int KIND, int OUT>
-__global__ __launch_bounds__(256) void k_gemm_dl(GemmDev g)
+__global__ __launch_bounds__(256) void k_gemm_dl(GemmDev g, GemmDev gt, int n_main)
 {
-    gemm_tile_dl<KIND, OUT>(g, static_cast<int>(blockIdx.x));
+    const int b = static_cast<int>(blockIdx.x);
+    if constexpr (KIND != 2 && OUT != 2 && OUT != 3) {
+        if (b >= n_main) {
+            gemm_tile_dl<KIND, 6, OUT>(gt, b - n_main);
+            return;
+        }
+    }
+    gemm_tile_dl<KIND, 8, OUT>(g, b);
 }
 
 template <int KIND, int WM, int WN, int KCH, bool TAIL, int OUT>
@@ -63,6 +72,11 @@ GemmPlan plan_gemm(int M, int N, int nk, double scale, size_t ws_bytes, bool all
     }
     return best;
 }
+
+// the last rows of a product in 192-row tiles where that saves a quarter of its last round (gemm_plan.hpp)
+static std::atomic<int> g_tail_enabled{1};
+void gemm_tail_enable(bool on) { g_tail_enabled.store(on ? 1 : 0); }
+bool gemm_tail_enabled() { return g_tail_enabled.load() != 0; }
 
 // plan overrides for measurements (hlq_set_option): 0 = the cost model decides
 static std::atomic<int> g_plan_tile{0}, g_plan_splits{0};
@@ -143,7 +157,13 @@ static hipError_t launch_tt(const GemmArgs &a, int splits, hipStream_t st)
 template <int KIND, int OUT>
 static hipError_t launch_dl(const GemmArgs &a, int splits, hipStream_t st)
 {
-    const GemmDev g = gemm_dev(KIND, a, 256, 256, splits);
+    GemmDev g = gemm_dev(KIND, a, 256, 256, splits);
+    GemmDev gt = g;
+    gt.tiles_m = 0;
+    if (KIND != 2 && (OUT == 0 || OUT == 1) && splits == 1) {
+        const int tail_rows = gemm_tail_rows(a.M, a.N, 0);
+        if (tail_rows > 0) gt = gemm_dev_cut_tail(g, tail_rows);
+    }
     static bool attr_set = false;     // idempotent; racing callers set the same value
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm_dl<KIND, OUT>),
@@ -151,7 +171,8 @@ static hipError_t launch_dl(const GemmArgs &a, int splits, hipStream_t st)
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_gemm_dl<KIND, OUT>), dim3(g.tiles_m * g.tiles_n * splits), dim3(256), kGemmDlLdsBytes, st, g);
+    const int n_main = g.tiles_m * g.tiles_n * splits, n_tail = gt.tiles_m * gt.tiles_n;
+    hipLaunchKernelGGL((k_gemm_dl<KIND, OUT>), dim3(n_main + n_tail), dim3(256), kGemmDlLdsBytes, st, g, gt, n_main);
     return hipGetLastError();
 }
 

@@ -6,14 +6,14 @@
 
 namespace hlq {
 
-hipError_t launch_pair_21(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, bool b_first,
-                          hipStream_t st);
-hipError_t launch_pair_20(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, bool b_first,
-                          hipStream_t st);
-hipError_t launch_pair_01(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, bool b_first,
-                          hipStream_t st);
-hipError_t launch_pair_00(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, bool b_first,
-                          hipStream_t st);
+hipError_t launch_pair_21(const GemmDev &ga, const GemmDev &gb, const GemmDev &gbt, bool bigA, bool f32, bool bigB, int outB,
+                          bool b_first, hipStream_t st);
+hipError_t launch_pair_20(const GemmDev &ga, const GemmDev &gb, const GemmDev &gbt, bool bigA, bool f32, bool bigB, int outB,
+                          bool b_first, hipStream_t st);
+hipError_t launch_pair_01(const GemmDev &ga, const GemmDev &gb, const GemmDev &gbt, bool bigA, bool f32, bool bigB, int outB,
+                          bool b_first, hipStream_t st);
+hipError_t launch_pair_00(const GemmDev &ga, const GemmDev &gb, const GemmDev &gbt, bool bigA, bool f32, bool bigB, int outB,
+                          bool b_first, hipStream_t st);
 
 // Plan of the pair: tile size of either product and the k split of the g_w product, by a model of
 // how the launch unfolds (microseconds; constants fitted to a sweep of every plan, either dispatch
@@ -147,15 +147,23 @@ hipError_t launch_gemm_pair(int kindA, const GemmArgs &a, int kindB, const GemmA
     if (p.bigA && p.bigB && p.splitsB == 1 && gemm_stream_wanted(kindA, a, kindB, &b))
         return launch_gemm_stream(kindA, a, kindB, &b, st);
     const GemmDev ga = gemm_dev(kindA, a, p.bigA ? 256 : 128, p.bigA ? 256 : 128, 1);
-    const GemmDev gb = gemm_dev(kindB, b, p.bigB ? 256 : 128, p.bigB ? 256 : 128, p.splitsB);
+    GemmDev gb = gemm_dev(kindB, b, p.bigB ? 256 : 128, p.bigB ? 256 : 128, p.splitsB);
     const int outB = p.splitsB > 1 ? 3 : (b.c_is_f32 ? 1 : 0);
+    // the g_w product's last rows in 192-row tiles when it closes the launch on 256-tiles that load straight
+    // into LDS and its last round would be partly empty (gemm_plan.hpp)
+    GemmDev gbt = gb;
+    gbt.tiles_m = 0;
+    if (p.bigA && p.bigB && p.splitsB == 1 && !p.b_first && kindB != 2 && gemm_dl_ok(gb.Kb, 1)) {
+        const int tail_rows = gemm_tail_rows(b.M, b.N, ga.tiles_m * ga.tiles_n);
+        if (tail_rows > 0) gbt = gemm_dev_cut_tail(gb, tail_rows);
+    }
     hipError_t e;
     if (kindA == 2)
-        e = kindB == 1 ? launch_pair_21(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st)
-                       : launch_pair_20(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st);
+        e = kindB == 1 ? launch_pair_21(ga, gb, gbt, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st)
+                       : launch_pair_20(ga, gb, gbt, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st);
     else
-        e = kindB == 1 ? launch_pair_01(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st)
-                       : launch_pair_00(ga, gb, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st);
+        e = kindB == 1 ? launch_pair_01(ga, gb, gbt, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st)
+                       : launch_pair_00(ga, gb, gbt, p.bigA, a.c_is_f32, p.bigB, outB, p.b_first, st);
     if (e != hipSuccess || p.splitsB == 1) return e;
     if (defer) {
         *defer = splitk_reduce_job_of(kindB == 1 ? 1 : 0, b, p.splitsB);

@@ -3,10 +3,10 @@
 
 namespace hlq {
 
-hipError_t launch_pair_20(const GemmDev &ga, const GemmDev &gb, bool bigA, bool f32, bool bigB, int outB, bool b_first,
-                          hipStream_t st)
+hipError_t launch_pair_20(const GemmDev &ga, const GemmDev &gb, const GemmDev &gbt, bool bigA, bool f32, bool bigB, int outB,
+                          bool b_first, hipStream_t st)
 {
-    return launch_pair_kinds<2, 0>(ga, gb, bigA, f32, bigB, outB, b_first, st);
+    return launch_pair_kinds<2, 0>(ga, gb, gbt, bigA, f32, bigB, outB, b_first, st);
 }
 
 }  // namespace hlq

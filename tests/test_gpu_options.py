@@ -159,6 +159,59 @@ def test_forced_plans_agree(tile, splits):
     assert float((d / (dW_auto.float().abs() + 1e-6)).median()) < 1e-2 and float(d.max()) <= 2 ** -6 * float(dW_auto.float().abs().max())
 
 
+@pytest.mark.parametrize("N,d_in,d_out", [(1024, 4096, 4352), (1024, 4096 - 24, 4352 - 32), (2048, 2048, 8192 + 256)])
+def test_tail_tiles_same_bits(N, d_in, d_out):
+    """The last rows of the g_w product in 192-row tiles (taken when its last round on 256-row tiles
+    would be partly empty) against 256-row tiles throughout: the same bits.  256-tiles are forced so
+    that the small g_x product does not move the plan to 128-tiles."""
+    w = wl.scaled(wl.WORKLOADS["c4"], N=N, d_in=d_in, d_out=d_out, B=16, r=8)
+    t = wl.generate(w)
+    G, X, W = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
+    try:
+        hlq.hlq_set_option(hlq.HLQ_OPT_PLAN_TILE, 256)
+        hlq.hlq_set_option(hlq.HLQ_OPT_PLAN_SPLITS, 1)
+        hlq.hlq_set_option(hlq.HLQ_OPT_TAIL_TILES, 0)
+        dX0, dW0 = _run(w, G, X, W)
+        hlq.hlq_set_option(hlq.HLQ_OPT_TAIL_TILES, 1)
+        dX1, dW1 = _run(w, G, X, W)
+    finally:
+        hlq.hlq_set_option(hlq.HLQ_OPT_TAIL_TILES, 1)
+        hlq.hlq_set_option(hlq.HLQ_OPT_PLAN_TILE, 0)
+        hlq.hlq_set_option(hlq.HLQ_OPT_PLAN_SPLITS, 0)
+    assert torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
+    assert float(dW1.float().abs().max()) > 0
+
+
+@pytest.mark.parametrize("kind", ["int8", "bf16"])
+@pytest.mark.parametrize("M,Nn,K,f32", [(4352, 4096, 512, False), (4352 - 40, 4096 - 24, 1024, True), (8192 + 300, 2048, 512, False)])
+def test_tail_tiles_products_same_bits(kind, M, Nn, K, f32):
+    """A product launched alone: 272 (or 272 ragged, or 264) tiles of 256 x 256 leave a last round of a few
+    tiles, which the 192-row tiles take over."""
+    gen = torch.Generator(device="cpu").manual_seed(M + K)
+    out = torch.float32 if f32 else torch.bfloat16
+    if kind == "bf16":
+        A = torch.randn((M, K), generator=gen).to(torch.bfloat16).to(DEV)
+        Bm = torch.randn((Nn, K), generator=gen).to(torch.bfloat16).to(DEV)
+        run = lambda C: hlq.hlq_bf16_gemm_nt(A, Bm, 1.0 / 16, C, None)
+    else:
+        A = torch.randint(-127, 128, (M, K), generator=gen, dtype=torch.int8).to(DEV)
+        Bm = torch.randint(-127, 128, (Nn, K), generator=gen, dtype=torch.int8).to(DEV)
+        sA, sB = torch.rand(M, generator=gen).to(DEV), torch.rand(Nn, generator=gen).to(DEV)
+        run = lambda C: hlq.hlq_int8_gemm_nt(A, Bm, sA, sB, 1.0 / 16, C, None, None)
+    C0 = torch.zeros((M, Nn), dtype=out, device=DEV)
+    C1 = torch.zeros((M, Nn), dtype=out, device=DEV)
+    try:
+        hlq.hlq_set_option(hlq.HLQ_OPT_TAIL_TILES, 0)
+        run(C0)
+        hlq.hlq_set_option(hlq.HLQ_OPT_TAIL_TILES, 1)
+        run(C1)
+        torch.cuda.synchronize()
+    finally:
+        hlq.hlq_set_option(hlq.HLQ_OPT_TAIL_TILES, 1)
+    assert torch.equal(C0, C1)
+    assert float(C1.float().abs().max()) > 0
+
+
 def test_unknown_option_is_refused():
     with pytest.raises(hlq.HlqError) as ei:
         hlq.hlq_set_option(99, 1)
