@@ -3,10 +3,11 @@
 // list (column maxima of H^T W) do not depend on one another (arXiv 2406.15102, Sec. 6.1), and each
 // costs a few tens of microseconds, of which four to five are the fixed price of a launch that
 // waits for its predecessor to drain.  Two launches carry them instead of six:
-//   front A   K1(G)  |  K3(X)  |  zeroing of the column maxima      (X a matrix, or the image of a
-//                                                                    convolution read as its column matrix)
-//   front B   K3(G)  |  column maxima of H^T W      (needs the zeroing; G is re-read while the
-//                                                    last-level cache still holds it)
+//   front A   K1(G)  |  K3(G)  |  zeroing of the column maxima      (both readers of G together: the second
+//                                                                    finds it in the caches)
+//   front B   K3(X)  |  column maxima of H^T W                       (needs the zeroing)
+// (a convolution swaps the two projections: K3 of the image, read as its column matrix, exists for the first
+// launch only)
 // or ONE, when the weight has few row blocks (k_front_one below): the maxima stay per row block.
 // and three launches carry the integer g_w list, whose projections are quantised in two passes too:
 //   front A   K1(G)  |  zeroing of all three sets of maxima
