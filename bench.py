@@ -117,6 +117,7 @@ def main():
                     help="library switch for A/B runs: persistent=0|1 (persistent matrix products), "
                          "shared_g=0|1 (K1 and K3 share one read of G), direct_lds=0|1 (operands of the products straight into LDS), "
                          "tail_tiles=0|1 (192-row tiles for a product's last partial round), "
+                         "interleave=0|1 (row quantiser and projection of G in turns within their launch), "
                          "plan_tile=0|128|256 and plan_splits=0..16 (override the plan of the products; 0 = the cost model)")
     ap.add_argument("--no-modes", action="store_true",
                     help="skip the extra whole-path timings of the method's options (keeps a profile to the default path)")
@@ -136,7 +137,8 @@ def main():
         name, _, val = item.partition("=")
         key = {"persistent": hlq.HLQ_OPT_PERSISTENT_PRODUCTS, "shared_g": hlq.HLQ_OPT_SHARED_G_READ,
                "direct_lds": hlq.HLQ_OPT_DIRECT_TO_LDS, "plan_tile": hlq.HLQ_OPT_PLAN_TILE,
-               "plan_splits": hlq.HLQ_OPT_PLAN_SPLITS, "tail_tiles": hlq.HLQ_OPT_TAIL_TILES}[name]
+               "plan_splits": hlq.HLQ_OPT_PLAN_SPLITS, "tail_tiles": hlq.HLQ_OPT_TAIL_TILES,
+               "interleave": hlq.HLQ_OPT_FRONT_INTERLEAVE}[name]
         hlq.hlq_set_option(key, int(val))
     dev = "cuda:0"
     torch.cuda.set_device(0)

@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     hlq_quantize_w_workspace_bytes, hlq_status_str, hlq_version, hlq_workspace_bytes, lib,
     hlq_conv_geom, hlq_conv_sizes, hlq_im2col, hlq_col2im, hlq_conv_workspace_bytes, hlq_conv2d_backward,
     hlq_conv_compress_act, hlq_conv_compress_act_int8, hlq_backward_products, hlq_backward_products_workspace_bytes,
-    hlq_set_workspace, hlq_quantize_w_static, hlq_compress_act_int4, HLQ_FLAG_XC_INT4, hlq_backward_products_plan, hlq_set_option, HLQ_OPT_PERSISTENT_PRODUCTS, HLQ_OPT_SHARED_G_READ, HLQ_OPT_DIRECT_TO_LDS, HLQ_OPT_PLAN_TILE, HLQ_OPT_PLAN_SPLITS, HLQ_OPT_TAIL_TILES,
+    hlq_set_workspace, hlq_quantize_w_static, hlq_compress_act_int4, HLQ_FLAG_XC_INT4, hlq_backward_products_plan, hlq_set_option, HLQ_OPT_PERSISTENT_PRODUCTS, HLQ_OPT_SHARED_G_READ, HLQ_OPT_DIRECT_TO_LDS, HLQ_OPT_PLAN_TILE, HLQ_OPT_PLAN_SPLITS, HLQ_OPT_TAIL_TILES, HLQ_OPT_FRONT_INTERLEAVE,
 )

@@ -211,6 +211,7 @@ HLQ_OPT_DIRECT_TO_LDS = 3
 HLQ_OPT_PLAN_TILE = 4
 HLQ_OPT_PLAN_SPLITS = 5
 HLQ_OPT_TAIL_TILES = 6
+HLQ_OPT_FRONT_INTERLEAVE = 7
 
 
 def hlq_set_option(option, value):

@@ -228,6 +228,7 @@ int hlq_set_option(int option, int value)
     else if (option == HLQ_OPT_SHARED_G_READ) hlq::front_share_enable(value != 0);
     else if (option == HLQ_OPT_DIRECT_TO_LDS) hlq::gemm_dl_enable(value != 0);
     else if (option == HLQ_OPT_TAIL_TILES) hlq::gemm_tail_enable(value != 0);
+    else if (option == HLQ_OPT_FRONT_INTERLEAVE) hlq::front_mix_enable(value != 0);
     else if (option == HLQ_OPT_PLAN_TILE && (value == 0 || value == 128 || value == 256)) hlq::gemm_plan_force(value, -1);
     else if (option == HLQ_OPT_PLAN_SPLITS && value >= 0 && value <= 16) hlq::gemm_plan_force(-1, value);
     else return HLQ_ERR_SHAPE;

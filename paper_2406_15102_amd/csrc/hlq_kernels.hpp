@@ -109,6 +109,13 @@ struct FrontShare {
     int units;    // units in all
     int blocks;   // workgroups of the two jobs together: 8 * ceil(units / 8) * pair * (nk1 + gx)
 };
+// The two jobs of the first launch in turns along the index sequence: `gran * q` workgroups of the row
+// quantiser, then `gran` of the projection, `cyc` times over, then what is left of either.  The quantiser is
+// bound by its arithmetic and the projection by memory: side by side on a compute unit they take less than
+// one after the other.  gran == 0: each job keeps its own range of indices.
+struct FrontMix {
+    int gran, q, cyc;
+};
 struct FrontConv {   // on: the K3(X) job of front A reads the column matrix of an image (jx.T = the image)
     ConvShape g;
     int on;
@@ -169,6 +176,7 @@ hipError_t launch_front(const FrontRows &jr, const FrontHla &jx, const FrontFill
 // whether launch_front lets K1 (jr) and its first K3 job (jx) share the read of their tensor; switch for A/B
 FrontShare front_share(const FrontRows &jr, const FrontHla &jx, int B, bool is_f32);
 void front_share_enable(bool on);
+void front_mix_enable(bool on);
 
 // K3: token-axis Hadamard low-rank projection, T [N, D] -> ThatT [D, N/B*r] bf16.
 // basis: which r rows of the order-B matrix are kept, 0 = rows 0..r-1, 1 = the r of lowest sequency.

@@ -28,7 +28,8 @@ namespace hlq {
 // its own: the extra address arithmetic would cost the matrix variant registers, and with them a
 // wavefront of occupancy at B = 32.
 template <typename Tin, int B, bool PACKED, int BASIS, bool CONV>
-__global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, FrontFill jf, FrontConv jc, FrontShare js)
+__global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, FrontFill jf, FrontConv jc, FrontShare js,
+                                                 FrontMix jm)
 {
     int b = blockIdx.x;
     if (!CONV && js.on) {
@@ -53,6 +54,33 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
         b -= js.blocks;
         const int i = b * 256 + threadIdx.x;
         if (i < jf.n) jf.p[i] = 0u;
+        return;
+    }
+    if (!CONV && jm.gran) {
+        const int per = jm.gran * (jm.q + 1);
+        int k1 = -1, k3 = -1;
+        if (b < jm.cyc * per) {
+            const int turn = b / per, pos = b % per;
+            if (pos < jm.gran * jm.q) k1 = turn * jm.gran * jm.q + pos;
+            else k3 = turn * jm.gran + pos - jm.gran * jm.q;
+        } else {
+            b -= jm.cyc * per;
+            const int k1_left = jr.blocks - jm.cyc * jm.gran * jm.q, k3_left = jx.nb - jm.cyc * jm.gran;
+            if (b < k1_left) k1 = jm.cyc * jm.gran * jm.q + b;
+            else if (b - k1_left < k3_left) k3 = jm.cyc * jm.gran + b - k1_left;
+            else b -= k1_left + k3_left;
+        }
+        if (k1 >= 0) {
+            quant_rows_body<Tin, B, 256, PACKED>(static_cast<const Tin *>(jr.G), jr.N, jr.O, jr.T, jr.k0, jr.k1, jr.qmax, jr.Gq,
+                                                 jr.sG, nullptr, k1);
+        } else if (k3 >= 0) {
+            int bx, by;
+            hla_job_map(k3, jx.gx, jx.grp, bx, by);
+            hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, bx, by);
+        } else {
+            const int i = b * 256 + threadIdx.x;
+            if (i < jf.n) jf.p[i] = 0u;
+        }
         return;
     }
     if (b < jr.blocks) {
@@ -281,6 +309,28 @@ std::atomic<int> g_share_enabled{0};
 }
 void front_share_enable(bool on) { g_share_enabled.store(on ? 1 : 0); }
 
+namespace {
+// On by default.  Whole pass at 4096 x 4096 x 11008, alternating runs on one box: 371.9 us with each job in its
+// own range, 364-367 with turns of 8 to 128 workgroups of the projection (32 the best by a microsecond);
+// 8192 x 28672 x 8192 and the small layers do not move.
+std::atomic<int> g_mix_enabled{1};
+constexpr int kMixGran = 32;     // a multiple of 8: hla_job_map counts on index mod 8 being the XCD
+}
+void front_mix_enable(bool on) { g_mix_enabled.store(on ? 1 : 0); }
+
+FrontMix front_mix(const FrontRows &jr, const FrontHla &jx)
+{
+    FrontMix m{0, 0, 0};
+    if (!g_mix_enabled.load() || !jr.G || !jx.T || jr.blocks < kMixGran || jx.nb < kMixGran) return m;
+    m.gran = kMixGran;
+    m.q = (jr.blocks + jx.nb / 2) / jx.nb;     // workgroups of the quantiser per workgroup of the projection
+    if (m.q < 1) m.q = 1;
+    const int c1 = jr.blocks / (m.gran * m.q), c3 = jx.nb / m.gran;
+    m.cyc = c1 < c3 ? c1 : c3;
+    if (m.cyc == 0) m.gran = 0;
+    return m;
+}
+
 FrontShare front_share(const FrontRows &jr, const FrontHla &jx, int B, bool is_f32)
 {
     FrontShare s{};
@@ -313,9 +363,10 @@ static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const 
                                  const FrontAbsmax &jw, const FrontConv &jc, bool packed, hipStream_t st)
 {
     const FrontShare js = jc.on ? FrontShare{} : front_share(jr, jx, B, sizeof(Tin) == 4);
+    const FrontMix jm = (jc.on || js.on) ? FrontMix{0, 0, 0} : front_mix(jr, jx);
     const int na = (js.on ? js.blocks : jr.blocks + jx.nb) + (jf.n + 255) / 256;
     if (na > 0) {
-#define HLQ_FRONT_A(P, CV) hipLaunchKernelGGL((k_front_a<Tin, B, P, BASIS, CV>), dim3(na), dim3(256), 0, st, jr, jx, jf, jc, js)
+#define HLQ_FRONT_A(P, CV) hipLaunchKernelGGL((k_front_a<Tin, B, P, BASIS, CV>), dim3(na), dim3(256), 0, st, jr, jx, jf, jc, js, jm)
         if (jc.on) {
             if (packed) HLQ_FRONT_A(true, true); else HLQ_FRONT_A(false, true);
         } else {

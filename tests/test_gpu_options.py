@@ -71,6 +71,30 @@ def test_shared_read_of_g_same_bits(B, r, N):
     assert torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
 
 
+@pytest.mark.parametrize("B,r,N,d_out", [
+    (16, 8, 2048, 8192),          # whole turns of both jobs
+    (32, 8, 2048 + 32, 8192),     # workgroups of the quantiser left over after the last turn
+    (64, 64, 2048, 8192),
+    (16, 2, 2048 + 128, 8192),
+    (16, 8, 1008, 11008),         # rows of 5.4 chunks a lane, projection workgroups left over
+    (16, 4, 4096, 2048),          # short rows: several per workgroup of the quantiser
+])
+def test_front_interleave_same_bits(B, r, N, d_out):
+    # the row quantiser's and the projection's workgroups in turns, or one job after the other
+    w = wl.scaled(wl.WORKLOADS["c4"], N=N, d_in=4104, d_out=d_out, B=B, r=r)
+    t = wl.generate(w)
+    G, X, W = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
+    try:
+        hlq.hlq_set_option(hlq.HLQ_OPT_FRONT_INTERLEAVE, 0)
+        dX0, dW0 = _run(w, G, X, W)
+        hlq.hlq_set_option(hlq.HLQ_OPT_FRONT_INTERLEAVE, 1)
+        dX1, dW1 = _run(w, G, X, W)
+    finally:
+        hlq.hlq_set_option(hlq.HLQ_OPT_FRONT_INTERLEAVE, 1)
+    assert torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
+    assert float(dX1.float().abs().max()) > 0 and float(dW1.float().abs().max()) > 0
+
+
 @pytest.mark.parametrize("N,d_in,d_out,B,r,flags", [
     (4096, 4096, 2048, 16, 8, 0),                                   # both products on 256-tiles, whole steps
     (4096 - 64, 4096 - 104, 2048, 32, 16, 0),                       # tiles that hang over the edges
