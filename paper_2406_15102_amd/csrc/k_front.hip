@@ -3,11 +3,11 @@
 // list (column maxima of H^T W) do not depend on one another (arXiv 2406.15102, Sec. 6.1), and each
 // costs a few tens of microseconds, of which four to five are the fixed price of a launch that
 // waits for its predecessor to drain.  Two launches carry them instead of six:
-//   front A   K1(G)  |  K3(G)  |  zeroing of the column maxima      (both readers of G together: the second
-//                                                                    finds it in the caches)
-//   front B   K3(X)  |  column maxima of H^T W                       (needs the zeroing)
-// (a convolution swaps the two projections: K3 of the image, read as its column matrix, exists for the first
-// launch only)
+//   front A   K1(G)  |  K3(G)  |  K3(X)  |  zeroing of the column maxima    (workgroups of the quantiser and of
+//                                                                           the projections in turns)
+//   front B   column maxima of H^T W                                        (needs the zeroing)
+// (with HLQ_OPT_FRONT_INTERLEAVE off, each job keeps its own index range and K3(X) rides in front B; a
+// convolution has K3 of the image, read as its column matrix, in front A and K3(G) in front B)
 // or ONE, when the weight has few row blocks (k_front_one below): the maxima stay per row block.
 // and three launches carry the integer g_w list, whose projections are quantised in two passes too:
 //   front A   K1(G)  |  zeroing of all three sets of maxima
@@ -29,7 +29,7 @@ namespace hlq {
 // wavefront of occupancy at B = 32.
 template <typename Tin, int B, bool PACKED, int BASIS, bool CONV>
 __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, FrontFill jf, FrontConv jc, FrontShare js,
-                                                 FrontMix jm)
+                                                 FrontMix jm, FrontHla jy)
 {
     int b = blockIdx.x;
     if (!CONV && js.on) {
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
             else k3 = turn * jm.gran + pos - jm.gran * jm.q;
         } else {
             b -= jm.cyc * per;
-            const int k1_left = jr.blocks - jm.cyc * jm.gran * jm.q, k3_left = jx.nb - jm.cyc * jm.gran;
+            const int k1_left = jr.blocks - jm.cyc * jm.gran * jm.q, k3_left = jx.nb + jy.nb - jm.cyc * jm.gran;
             if (b < k1_left) k1 = jm.cyc * jm.gran * jm.q + b;
             else if (b - k1_left < k3_left) k3 = jm.cyc * jm.gran + b - k1_left;
             else b -= k1_left + k3_left;
@@ -73,10 +73,14 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
         if (k1 >= 0) {
             quant_rows_body<Tin, B, 256, PACKED>(static_cast<const Tin *>(jr.G), jr.N, jr.O, jr.T, jr.k0, jr.k1, jr.qmax, jr.Gq,
                                                  jr.sG, nullptr, k1);
-        } else if (k3 >= 0) {
+        } else if (k3 >= 0 && k3 < jx.nb) {
             int bx, by;
             hla_job_map(k3, jx.gx, jx.grp, bx, by);
             hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jx.T), jx.N, jx.D, jx.r, jx.out, nullptr, bx, by);
+        } else if (k3 >= 0) {
+            int bx, by;
+            hla_job_map(k3 - jx.nb, jy.gx, jy.grp, bx, by);
+            hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jy.T), jy.N, jy.D, jy.r, jy.out, nullptr, bx, by);
         } else {
             const int i = b * 256 + threadIdx.x;
             if (i < jf.n) jf.p[i] = 0u;
@@ -318,14 +322,15 @@ constexpr int kMixGran = 32;     // a multiple of 8: hla_job_map counts on index
 }
 void front_mix_enable(bool on) { g_mix_enabled.store(on ? 1 : 0); }
 
-FrontMix front_mix(const FrontRows &jr, const FrontHla &jx)
+FrontMix front_mix(const FrontRows &jr, const FrontHla &jx, int more)
 {
     FrontMix m{0, 0, 0};
     if (!g_mix_enabled.load() || !jr.G || !jx.T || jr.blocks < kMixGran || jx.nb < kMixGran) return m;
+    const int nb = jx.nb + more;
     m.gran = kMixGran;
-    m.q = (jr.blocks + jx.nb / 2) / jx.nb;     // workgroups of the quantiser per workgroup of the projection
+    m.q = (jr.blocks + nb / 2) / nb;     // workgroups of the quantiser per workgroup of the projections
     if (m.q < 1) m.q = 1;
-    const int c1 = jr.blocks / (m.gran * m.q), c3 = jx.nb / m.gran;
+    const int c1 = jr.blocks / (m.gran * m.q), c3 = nb / m.gran;
     m.cyc = c1 < c3 ? c1 : c3;
     if (m.cyc == 0) m.gran = 0;
     return m;
@@ -363,10 +368,23 @@ static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const 
                                  const FrontAbsmax &jw, const FrontConv &jc, bool packed, hipStream_t st)
 {
     const FrontShare js = jc.on ? FrontShare{} : front_share(jr, jx, B, sizeof(Tin) == 4);
-    const FrontMix jm = (jc.on || js.on) ? FrontMix{0, 0, 0} : front_mix(jr, jx);
-    const int na = (js.on ? js.blocks : jr.blocks + jx.nb) + (jf.n + 255) / 256;
+    // In turns, the first launch takes both projections (the second is left with the pass over W): the row
+    // quantiser's arithmetic then has all the memory-bound work there is to run beside.
+    FrontMix jm = (jc.on || js.on) ? FrontMix{0, 0, 0} : front_mix(jr, jx, 0);
+    const FrontHla none = front_hla(nullptr, 0, 0, B, 1, nullptr);
+    bool both = false;
+    if (jm.gran && jg.T) {
+        const FrontMix m2 = front_mix(jr, jx, jg.nb);
+        if (m2.gran) {
+            jm = m2;
+            both = true;
+        }
+    }
+    const FrontHla &jy = both ? jg : none;        // second projection of the first launch
+    const FrontHla &jb = both ? none : jg;        // projection of the second launch
+    const int na = (js.on ? js.blocks : jr.blocks + jx.nb + jy.nb) + (jf.n + 255) / 256;
     if (na > 0) {
-#define HLQ_FRONT_A(P, CV) hipLaunchKernelGGL((k_front_a<Tin, B, P, BASIS, CV>), dim3(na), dim3(256), 0, st, jr, jx, jf, jc, js, jm)
+#define HLQ_FRONT_A(P, CV) hipLaunchKernelGGL((k_front_a<Tin, B, P, BASIS, CV>), dim3(na), dim3(256), 0, st, jr, jx, jf, jc, js, jm, jy)
         if (jc.on) {
             if (packed) HLQ_FRONT_A(true, true); else HLQ_FRONT_A(false, true);
         } else {
@@ -374,8 +392,8 @@ static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const 
         }
 #undef HLQ_FRONT_A
     }
-    const int nb = jg.nb + jw.gx * jw.gy;
-    if (nb > 0) hipLaunchKernelGGL((k_front_b<Tin, B, BASIS>), dim3(nb), dim3(256), 0, st, jg, jw);
+    const int nb = jb.nb + jw.gx * jw.gy;
+    if (nb > 0) hipLaunchKernelGGL((k_front_b<Tin, B, BASIS>), dim3(nb), dim3(256), 0, st, jb, jw);
     return hipGetLastError();
 }
 
