@@ -685,9 +685,15 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
                                                   static_cast<uint32_t>(kg >> 32), qmax, Gq, sG);
         const hlq::FrontHla jx = hlq::front_hla(dW && !xc ? X : nullptr, N, I, B, r, xh);
         const hlq::FrontHla jg = hlq::front_hla(dW ? G : nullptr, N, O, B, r, static_cast<uint16_t *>(Gh));
-        if (w_done || hlq::cols_full_ok(O, I, B, f32)) {
-            // no pass over W here, or a weight of few rows, which one workgroup per strip of columns
-            // quantises completely: everything independent in one launch
+        if (w_done && !conv && hlq::front_mix_enabled()) {
+            // no pass over W here: the front launch alone (its second launch has nothing to do), with the
+            // quantiser's and the projections' workgroups in turns
+            const hlq::FrontAbsmax none_w = hlq::front_absmax(nullptr, O, I, B, nullptr);
+            const hlq::FrontFill no_fill{nullptr, 0};
+            rc = launch_rc(hlq::launch_front(jr, jg, no_fill, jx, none_w, nullptr, B, basis, f32, packed, st));
+        } else if (w_done || hlq::cols_full_ok(O, I, B, f32)) {
+            // no pass over W here (a convolution, or the turns switched off), or a weight of few rows, which one
+            // workgroup per strip of columns quantises completely: everything independent in one launch
             const hlq::FrontColsQ jq = hlq::front_cols_full(w_done ? nullptr : W, O, I, B, static_cast<uint32_t>(kw),
                                                             static_cast<uint32_t>(kw >> 32), qmax, wq, sw);
             rc = launch_rc(hlq::launch_front_one(jr, jx, jg, jq, conv, B, basis, f32, packed, st));
@@ -696,10 +702,9 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
             // pass 1 over W rides in the second launch, behind the zeroing of its maxima in the first
             const hlq::FrontAbsmax jw = hlq::front_absmax(W, O, I, B, reinterpret_cast<uint32_t *>(ws + L.wws));
             const hlq::FrontFill jf{reinterpret_cast<uint32_t *>(ws + L.wws), I};
-            // The first launch takes K1(G) and one K3, the second the other K3 and pass 1.  Both readers
-            // of G together (the second finds it in the cache; K1 is bound by arithmetic, K3 by memory)
-            // measured 1.5 % off the whole pass at 4096 x 4096 x 11008; the projection straight from an
-            // image exists for the first launch only, so a convolution keeps K3(X) there.
+            // The first launch takes K1(G) and K3(G) -- and, unless HLQ_OPT_FRONT_INTERLEAVE is off, K3(X) too,
+            // see launch_front_t --, the second what is left and pass 1.  The projection straight from an
+            // image exists for the first launch only, so a convolution has K3(X) there and K3(G) in the second.
             if (conv) rc = launch_rc(hlq::launch_front(jr, jx, jf, jg, jw, conv, B, basis, f32, packed, st));
             else rc = launch_rc(hlq::launch_front(jr, jg, jf, jx, jw, nullptr, B, basis, f32, packed, st));
         }

@@ -177,6 +177,7 @@ hipError_t launch_front(const FrontRows &jr, const FrontHla &jx, const FrontFill
 FrontShare front_share(const FrontRows &jr, const FrontHla &jx, int B, bool is_f32);
 void front_share_enable(bool on);
 void front_mix_enable(bool on);
+bool front_mix_enabled();
 
 // K3: token-axis Hadamard low-rank projection, T [N, D] -> ThatT [D, N/B*r] bf16.
 // basis: which r rows of the order-B matrix are kept, 0 = rows 0..r-1, 1 = the r of lowest sequency.

@@ -103,6 +103,13 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
         return;
     }
     b -= jx.nb;
+    if (b < jy.nb) {
+        int bx, by;
+        hla_job_map(b, jy.gx, jy.grp, bx, by);
+        hla_body<Tin, B, BASIS>(static_cast<const Tin *>(jy.T), jy.N, jy.D, jy.r, jy.out, nullptr, bx, by);
+        return;
+    }
+    b -= jy.nb;
     const int i = b * 256 + threadIdx.x;
     if (i < jf.n) jf.p[i] = 0u;
 }
@@ -321,6 +328,7 @@ std::atomic<int> g_mix_enabled{1};
 constexpr int kMixGran = 32;     // a multiple of 8: hla_job_map counts on index mod 8 being the XCD
 }
 void front_mix_enable(bool on) { g_mix_enabled.store(on ? 1 : 0); }
+bool front_mix_enabled() { return g_mix_enabled.load() != 0; }
 
 FrontMix front_mix(const FrontRows &jr, const FrontHla &jx, int more)
 {
@@ -368,18 +376,12 @@ static hipError_t launch_front_t(const FrontRows &jr, const FrontHla &jx, const 
                                  const FrontAbsmax &jw, const FrontConv &jc, bool packed, hipStream_t st)
 {
     const FrontShare js = jc.on ? FrontShare{} : front_share(jr, jx, B, sizeof(Tin) == 4);
-    // In turns, the first launch takes both projections (the second is left with the pass over W): the row
-    // quantiser's arithmetic then has all the memory-bound work there is to run beside.
-    FrontMix jm = (jc.on || js.on) ? FrontMix{0, 0, 0} : front_mix(jr, jx, 0);
+    // Unless that is switched off, the first launch takes both projections (the second is left with the pass
+    // over W, if there is one) and hands out its workgroups in turns: the row quantiser's arithmetic then has
+    // all the memory-bound work there is to run beside.
     const FrontHla none = front_hla(nullptr, 0, 0, B, 1, nullptr);
-    bool both = false;
-    if (jm.gran && jg.T) {
-        const FrontMix m2 = front_mix(jr, jx, jg.nb);
-        if (m2.gran) {
-            jm = m2;
-            both = true;
-        }
-    }
+    const bool both = g_mix_enabled.load() && !jc.on && !js.on && jg.T;
+    const FrontMix jm = (jc.on || js.on) ? FrontMix{0, 0, 0} : front_mix(jr, jx, both ? jg.nb : 0);
     const FrontHla &jy = both ? jg : none;        // second projection of the first launch
     const FrontHla &jb = both ? none : jg;        // projection of the second launch
     const int na = (js.on ? js.blocks : jr.blocks + jx.nb + jy.nb) + (jf.n + 255) / 256;
