@@ -24,6 +24,25 @@
 
 namespace hlq {
 
+// Workgroup b of the n1 + n3 that two kinds of job share, handed out in turns (FrontMix): k1 >= 0, the index
+// among the first kind, or k3 >= 0, among the second; both < 0 past the end, with b counted from there.
+__device__ __forceinline__ void front_turns(const FrontMix &jm, int &b, int n1, int n3, int &k1, int &k3)
+{
+    const int per = jm.gran * (jm.q + 1);
+    k1 = k3 = -1;
+    if (b < jm.cyc * per) {
+        const int turn = b / per, pos = b % per;
+        if (pos < jm.gran * jm.q) k1 = turn * jm.gran * jm.q + pos;
+        else k3 = turn * jm.gran + pos - jm.gran * jm.q;
+        return;
+    }
+    b -= jm.cyc * per;
+    const int k1_left = n1 - jm.cyc * jm.gran * jm.q, k3_left = n3 - jm.cyc * jm.gran;
+    if (b < k1_left) k1 = jm.cyc * jm.gran * jm.q + b;
+    else if (b - k1_left < k3_left) k3 = jm.cyc * jm.gran + b - k1_left;
+    else b -= k1_left + k3_left;
+}
+
 // CONV: X is a channels-last image and K3 reads its column matrix through ConvRows.  A kernel of
 // its own: the extra address arithmetic would cost the matrix variant registers, and with them a
 // wavefront of occupancy at B = 32.
@@ -57,19 +76,8 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
         return;
     }
     if (!CONV && jm.gran) {
-        const int per = jm.gran * (jm.q + 1);
-        int k1 = -1, k3 = -1;
-        if (b < jm.cyc * per) {
-            const int turn = b / per, pos = b % per;
-            if (pos < jm.gran * jm.q) k1 = turn * jm.gran * jm.q + pos;
-            else k3 = turn * jm.gran + pos - jm.gran * jm.q;
-        } else {
-            b -= jm.cyc * per;
-            const int k1_left = jr.blocks - jm.cyc * jm.gran * jm.q, k3_left = jx.nb + jy.nb - jm.cyc * jm.gran;
-            if (b < k1_left) k1 = jm.cyc * jm.gran * jm.q + b;
-            else if (b - k1_left < k3_left) k3 = jm.cyc * jm.gran + b - k1_left;
-            else b -= k1_left + k3_left;
-        }
+        int k1, k3;
+        front_turns(jm, b, jr.blocks, jx.nb + jy.nb, k1, k3);
         if (k1 >= 0) {
             quant_rows_body<Tin, B, 256, PACKED>(static_cast<const Tin *>(jr.G), jr.N, jr.O, jr.T, jr.k0, jr.k1, jr.qmax, jr.Gq,
                                                  jr.sG, nullptr, k1);
@@ -119,7 +127,8 @@ __global__ __launch_bounds__(256) void k_front_a(FrontRows jr, FrontHla jx, Fron
 // (three wavefronts per SIMD asked for below B = 64, which the other jobs had before the strip quantiser
 // joined them: left alone, the register allocator spends all 256 registers on it)
 template <typename Tin, int B, bool PACKED, int BASIS, bool CONV>
-__global__ __launch_bounds__(256, B == 64 ? 2 : 3) void k_front_one(FrontRows jr, FrontHla jx, FrontHla jg, FrontColsQ jq, FrontConv jc)
+__global__ __launch_bounds__(256, B == 64 ? 2 : 3) void k_front_one(FrontRows jr, FrontHla jx, FrontHla jg, FrontColsQ jq, FrontConv jc,
+                                                                    FrontMix jm)
 {
     int b = blockIdx.x;
     if (b < jq.gx) {       // first: these workgroups pass over their strip twice
@@ -127,6 +136,13 @@ __global__ __launch_bounds__(256, B == 64 ? 2 : 3) void k_front_one(FrontRows jr
         return;
     }
     b -= jq.gx;
+    if (jm.gran) {
+        // the row quantiser's workgroups and the projections' in turns: b becomes an index in the ranges below
+        int k1, k3;
+        front_turns(jm, b, jr.blocks, jx.nb + jg.nb, k1, k3);
+        if (k1 < 0 && k3 < 0) return;
+        b = k1 >= 0 ? k1 : jr.blocks + k3;
+    }
     if (b < jr.blocks) {
         quant_rows_body<Tin, B, 256, PACKED>(static_cast<const Tin *>(jr.G), jr.N, jr.O, jr.T, jr.k0, jr.k1, jr.qmax, jr.Gq,
                                              jr.sG, nullptr, b);
@@ -330,18 +346,24 @@ constexpr int kMixGran = 32;     // a multiple of 8: hla_job_map counts on index
 void front_mix_enable(bool on) { g_mix_enabled.store(on ? 1 : 0); }
 bool front_mix_enabled() { return g_mix_enabled.load() != 0; }
 
-FrontMix front_mix(const FrontRows &jr, const FrontHla &jx, int more)
+// turns for n1 workgroups of the quantiser and n3 of the projections; gran == 0 if either has too few
+FrontMix front_mix_of(int n1, int n3)
 {
     FrontMix m{0, 0, 0};
-    if (!g_mix_enabled.load() || !jr.G || !jx.T || jr.blocks < kMixGran || jx.nb < kMixGran) return m;
-    const int nb = jx.nb + more;
+    if (!g_mix_enabled.load() || n1 < kMixGran || n3 < kMixGran) return m;
     m.gran = kMixGran;
-    m.q = (jr.blocks + nb / 2) / nb;     // workgroups of the quantiser per workgroup of the projections
+    m.q = (n1 + n3 / 2) / n3;     // workgroups of the quantiser per workgroup of the projections
     if (m.q < 1) m.q = 1;
-    const int c1 = jr.blocks / (m.gran * m.q), c3 = nb / m.gran;
+    const int c1 = n1 / (m.gran * m.q), c3 = n3 / m.gran;
     m.cyc = c1 < c3 ? c1 : c3;
     if (m.cyc == 0) m.gran = 0;
     return m;
+}
+
+FrontMix front_mix(const FrontRows &jr, const FrontHla &jx, int more)
+{
+    if (!jr.G || !jx.T) return FrontMix{0, 0, 0};
+    return front_mix_of(jr.blocks, jx.nb + more);
 }
 
 FrontShare front_share(const FrontRows &jr, const FrontHla &jx, int B, bool is_f32)
@@ -405,7 +427,9 @@ static hipError_t launch_front_one_t(const FrontRows &jr, const FrontHla &jx, co
 {
     const int n = jq.gx + jr.blocks + jx.nb + jg.nb;
     if (n == 0) return hipSuccess;
-#define HLQ_FRONT_ONE(P, CV) hipLaunchKernelGGL((k_front_one<Tin, B, P, BASIS, CV>), dim3(n), dim3(256), 0, st, jr, jx, jg, jq, jc)
+    // (layers whose quantiser has fewer than a thousand workgroups lose a little by it: 29.3 -> 30.0 us at 12544 x 896 x 224)
+    const FrontMix jm = (jr.G && jr.blocks >= 1024) ? front_mix_of(jr.blocks, jx.nb + jg.nb) : FrontMix{0, 0, 0};
+#define HLQ_FRONT_ONE(P, CV) hipLaunchKernelGGL((k_front_one<Tin, B, P, BASIS, CV>), dim3(n), dim3(256), 0, st, jr, jx, jg, jq, jc, jm)
     if (jc.on) {
         if (packed) HLQ_FRONT_ONE(true, true); else HLQ_FRONT_ONE(false, true);
     } else {

@@ -71,17 +71,19 @@ def test_shared_read_of_g_same_bits(B, r, N):
     assert torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
 
 
-@pytest.mark.parametrize("B,r,N,d_out", [
-    (16, 8, 2048, 8192),          # whole turns of both jobs
-    (32, 8, 2048 + 32, 8192),     # workgroups of the quantiser left over after the last turn
-    (64, 64, 2048, 8192),
-    (16, 2, 2048 + 128, 8192),
-    (16, 8, 1008, 11008),         # rows of 5.4 chunks a lane, projection workgroups left over
-    (16, 4, 4096, 2048),          # short rows: several per workgroup of the quantiser
+@pytest.mark.parametrize("B,r,N,d_out,d_in", [
+    (16, 8, 2048, 8192, 4104),          # whole turns of both jobs
+    (32, 8, 2048 + 32, 8192, 4104),     # workgroups of the quantiser left over after the last turn
+    (64, 64, 2048, 8192, 4104),
+    (16, 2, 2048 + 128, 8192, 4104),
+    (16, 8, 1008, 11008, 4104),         # rows of 5.4 chunks a lane, projection workgroups left over
+    (16, 4, 4096, 2048, 4104),          # short rows: several per workgroup of the quantiser
+    (16, 8, 8192 + 16, 1024, 520),      # a small weight: everything in one launch, strips of W first
+    (32, 16, 16384, 512, 264),
 ])
-def test_front_interleave_same_bits(B, r, N, d_out):
-    # the row quantiser's and the projection's workgroups in turns, or one job after the other
-    w = wl.scaled(wl.WORKLOADS["c4"], N=N, d_in=4104, d_out=d_out, B=B, r=r)
+def test_front_interleave_same_bits(B, r, N, d_out, d_in):
+    # the row quantiser's and the projections' workgroups in turns, or one job after the other
+    w = wl.scaled(wl.WORKLOADS["c4"], N=N, d_in=d_in, d_out=d_out, B=B, r=r)
     t = wl.generate(w)
     G, X, W = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
     try:
