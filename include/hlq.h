@@ -92,10 +92,12 @@ size_t hlq_workspace_bytes(int64_t N, int64_t d_in, int64_t d_out, int B, int r,
  *       leave most compute units idle in its last round hands its last rows to tiles of 192 x 256, which
  *       shortens that round by a quarter (the g_w product when it closes the launch of both products, or a
  *       product launched alone; not the packed codes);  0: 256 x 256 tiles throughout.
- *   HLQ_OPT_FRONT_INTERLEAVE  1 (default): in the launch that carries the row quantiser of G and the
- *       token-axis projection of G, workgroups of the two take turns along the index sequence (the
- *       quantiser is bound by arithmetic, the projection by memory: side by side they take less);
- *       0: all of the quantiser's workgroups first.
+ *   HLQ_OPT_FRONT_INTERLEAVE  1 (default): the row quantiser of G shares a launch with all the
+ *       memory-bound transforms that do not wait for anything -- both token-axis projections, or, on the
+ *       integer g_w list, the passes that take the maxima -- and the workgroups of the two kinds take
+ *       turns along the index sequence (the quantiser is bound by arithmetic: side by side they take
+ *       less);  0: the former composition -- the quantiser's workgroups first, then one projection, the
+ *       other in the second launch (integer g_w list: the quantiser with the zeroing, before the passes).
  *   HLQ_OPT_PLAN_TILE  0 (default): a cost model picks 128 x 128 or 256 x 256 tiles for each matrix product;
  *       128 or 256: every product takes that tile.
  *   HLQ_OPT_PLAN_SPLITS  0 (default): the model picks the k split of a product with few output tiles (of

@@ -648,7 +648,10 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         const hlq::FrontFill jf{amax_w, static_cast<int>(zero_bytes / 4)};
         const hlq::FrontHla none = hlq::front_hla(nullptr, N, O, B, r, nullptr);
         const hlq::FrontAbsmax none_w = hlq::front_absmax(nullptr, O, I, B, nullptr);
-        if ((rc = launch_rc(hlq::launch_front(jr, none, jf, none, none_w, nullptr, B, basis, f32, packed, st))) != HLQ_OK)
+        // the zeroing first; the row quantiser with it, or -- in turns -- beside the three passes that only read
+        const bool k1_later = hlq::front_mix_enabled();
+        const hlq::FrontRows no_rows = hlq::front_rows(nullptr, N, O, B, 0, 0, qmax, nullptr, nullptr);
+        if ((rc = launch_rc(hlq::launch_front(k1_later ? no_rows : jr, none, jf, none, none_w, nullptr, B, basis, f32, packed, st))) != HLQ_OK)
             return rc;
         int8_t *xq = xc ? nullptr : reinterpret_cast<int8_t *>(ws + L.XhatT);
         float *sx = xc ? nullptr : reinterpret_cast<float *>(ws + L.sXhat);
@@ -668,7 +671,7 @@ static int backward_impl(const void *G, const void *X, const void *Xc, const flo
         const hlq::FrontColsQ jq = hlq::front_colsq(wq ? W : nullptr, O, I, B, amax_w, static_cast<uint32_t>(kw),
                                                     static_cast<uint32_t>(kw >> 32), qmax, reinterpret_cast<int8_t *>(ws + L.Wq),
                                                     reinterpret_cast<float *>(ws + L.sW));
-        if ((rc = launch_rc(hlq::launch_front_q(jg, jx, jw, jq, B, basis, f32, packed, st))) != HLQ_OK) return rc;
+        if ((rc = launch_rc(hlq::launch_front_q(jg, jx, jw, jq, k1_later ? jr : no_rows, B, basis, f32, packed, st))) != HLQ_OK) return rc;
         if (dW && !xc) {
             Xh = xq;
             sXh = sx;

@@ -155,9 +155,10 @@ FrontHlaQ front_hlaq(const void *T, int64_t N, int D, int B, int r, uint32_t *am
 FrontColsQ front_colsq(const void *W, int O, int I, int B, const uint32_t *amax, uint32_t k0, uint32_t k1, float qmax,
                        int8_t *WqT, float *sW);
 // The integer g_w list in three launches: (K1(G) | zeroing) through launch_front with empty K3 jobs,
-// then every pass 1 (maxima of projected G, projected X, transformed W), then every pass 2.
-hipError_t launch_front_q(const FrontHlaQ &jg, const FrontHlaQ &jx, const FrontAbsmax &jw, const FrontColsQ &jq, int B,
-                          int basis, bool is_f32, bool packed, hipStream_t st);
+// then every pass 1 (maxima of projected G, projected X, transformed W), then every pass 2.  `jr`, if it is
+// not empty, is K1(G) riding in the second launch instead, its workgroups in turns with the passes 1.
+hipError_t launch_front_q(const FrontHlaQ &jg, const FrontHlaQ &jx, const FrontAbsmax &jw, const FrontColsQ &jq,
+                          const FrontRows &jr, int B, int basis, bool is_f32, bool packed, hipStream_t st);
 bool front_fusable(int O, int B);
 FrontRows front_rows(const void *G, int64_t N, int O, int B, uint32_t k0, uint32_t k1, float qmax, int8_t *Gq, float *sG);
 FrontHla front_hla(const void *T, int64_t N, int D, int B, int r, uint16_t *out);

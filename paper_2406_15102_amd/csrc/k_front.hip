@@ -24,6 +24,8 @@
 
 namespace hlq {
 
+FrontMix front_mix_of(int n1, int n3);
+
 // Workgroup b of the n1 + n3 that two kinds of job share, handed out in turns (FrontMix): k1 >= 0, the index
 // among the first kind, or k3 >= 0, among the second; both < 0 past the end, with b counted from there.
 __device__ __forceinline__ void front_turns(const FrontMix &jm, int &b, int n1, int n3, int &k1, int &k3)
@@ -179,10 +181,30 @@ __global__ __launch_bounds__(256) void k_front_b(FrontHla jg, FrontAbsmax jw)
 }
 
 // integer g_w list, pass 1 of everything: maxima of the kept coefficients of G and of X, of H^T W
-template <typename Tin, int B, int BASIS>
-__global__ __launch_bounds__(256) void k_front_q1(FrontHlaQ jg, FrontHlaQ jx, FrontAbsmax jw)
+// With jr (the row quantiser of G, which waits for nothing) riding along, in turns: its arithmetic beside three
+// passes that only read.
+template <typename Tin, int B, int BASIS, bool PACKED>
+__global__ __launch_bounds__(256) void k_front_q1(FrontHlaQ jg, FrontHlaQ jx, FrontAbsmax jw, FrontRows jr, FrontMix jm)
 {
     int b = blockIdx.x;
+    if (jr.blocks > 0) {
+        int k1 = -1, k3 = -1;
+        const int n3 = jg.gx * jg.gy + jx.gx * jx.gy + jw.gx * jw.gy;
+        if (jm.gran) {
+            front_turns(jm, b, jr.blocks, n3, k1, k3);
+        } else if (b < jr.blocks) {
+            k1 = b;
+        } else {
+            k3 = b - jr.blocks;
+        }
+        if (k1 >= 0) {
+            quant_rows_body<Tin, B, 256, PACKED>(static_cast<const Tin *>(jr.G), jr.N, jr.O, jr.T, jr.k0, jr.k1, jr.qmax, jr.Gq,
+                                                 jr.sG, nullptr, k1);
+            return;
+        }
+        if (k3 < 0) return;
+        b = k3;
+    }
     if (b < jg.gx * jg.gy) {
         hla_absmax_body<Tin, B, BASIS>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.amax, b % jg.gx, b / jg.gx);
         return;
@@ -239,10 +261,15 @@ FrontColsQ front_colsq(const void *W, int O, int I, int B, const uint32_t *amax,
 
 template <typename Tin, int B, int BASIS>
 static hipError_t launch_front_q_t(const FrontHlaQ &jg, const FrontHlaQ &jx, const FrontAbsmax &jw, const FrontColsQ &jq,
-                                   bool packed, hipStream_t st)
+                                   const FrontRows &jr, bool packed, hipStream_t st)
 {
-    const int n1 = jg.gx * jg.gy + jx.gx * jx.gy + jw.gx * jw.gy;
-    if (n1 > 0) hipLaunchKernelGGL((k_front_q1<Tin, B, BASIS>), dim3(n1), dim3(256), 0, st, jg, jx, jw);
+    const int n3 = jg.gx * jg.gy + jx.gx * jx.gy + jw.gx * jw.gy;
+    const int n1 = n3 + jr.blocks;
+    const FrontMix jm = jr.blocks > 0 ? front_mix_of(jr.blocks, n3) : FrontMix{0, 0, 0};
+    if (n1 > 0) {
+        if (packed) hipLaunchKernelGGL((k_front_q1<Tin, B, BASIS, true>), dim3(n1), dim3(256), 0, st, jg, jx, jw, jr, jm);
+        else hipLaunchKernelGGL((k_front_q1<Tin, B, BASIS, false>), dim3(n1), dim3(256), 0, st, jg, jx, jw, jr, jm);
+    }
     const int n2 = jg.gx * jg.gy + jx.gx * jx.gy + jq.gx * jq.gy;
     if (n2 > 0) {
         if (packed) hipLaunchKernelGGL((k_front_q2<Tin, B, BASIS, true>), dim3(n2), dim3(256), 0, st, jg, jx, jq);
@@ -251,16 +278,16 @@ static hipError_t launch_front_q_t(const FrontHlaQ &jg, const FrontHlaQ &jx, con
     return hipGetLastError();
 }
 
-hipError_t launch_front_q(const FrontHlaQ &jg, const FrontHlaQ &jx, const FrontAbsmax &jw, const FrontColsQ &jq, int B,
-                          int basis, bool is_f32, bool packed, hipStream_t st)
+hipError_t launch_front_q(const FrontHlaQ &jg, const FrontHlaQ &jx, const FrontAbsmax &jw, const FrontColsQ &jq,
+                          const FrontRows &jr, int B, int basis, bool is_f32, bool packed, hipStream_t st)
 {
 #define HLQ_FRONTQ_CASE(BB)                                                                     \
     case BB:                                                                                    \
         if (basis)                                                                              \
-            return is_f32 ? launch_front_q_t<float, BB, 1>(jg, jx, jw, jq, packed, st)          \
-                          : launch_front_q_t<bf16_t, BB, 1>(jg, jx, jw, jq, packed, st);        \
-        return is_f32 ? launch_front_q_t<float, BB, 0>(jg, jx, jw, jq, packed, st)              \
-                      : launch_front_q_t<bf16_t, BB, 0>(jg, jx, jw, jq, packed, st);
+            return is_f32 ? launch_front_q_t<float, BB, 1>(jg, jx, jw, jq, jr, packed, st)          \
+                          : launch_front_q_t<bf16_t, BB, 1>(jg, jx, jw, jq, jr, packed, st);        \
+        return is_f32 ? launch_front_q_t<float, BB, 0>(jg, jx, jw, jq, jr, packed, st)              \
+                      : launch_front_q_t<bf16_t, BB, 0>(jg, jx, jw, jq, jr, packed, st);
     switch (B) {
         HLQ_FRONTQ_CASE(16)
         HLQ_FRONTQ_CASE(32)

@@ -97,6 +97,23 @@ def test_front_interleave_same_bits(B, r, N, d_out, d_in):
     assert float(dX1.float().abs().max()) > 0 and float(dW1.float().abs().max()) > 0
 
 
+@pytest.mark.parametrize("B,r,N,d_out,d_in", [(16, 8, 2048, 8192, 4104), (32, 8, 2048 + 32, 4096, 1032), (16, 4, 4096, 2048, 4104)])
+def test_front_interleave_integer_gw_same_bits(B, r, N, d_out, d_in):
+    # integer g_w list: the row quantiser beside the passes that take the maxima, or in the launch before them
+    w = wl.scaled(wl.WORKLOADS["c4"], N=N, d_in=d_in, d_out=d_out, B=B, r=r)
+    t = wl.generate(w)
+    G, X, W = (t[k].to(DEV).contiguous() for k in ("G", "X", "W"))
+    try:
+        hlq.hlq_set_option(hlq.HLQ_OPT_FRONT_INTERLEAVE, 0)
+        dX0, dW0 = _run(w, G, X, W, flags=hlq.HLQ_FLAG_GW_INT8)
+        hlq.hlq_set_option(hlq.HLQ_OPT_FRONT_INTERLEAVE, 1)
+        dX1, dW1 = _run(w, G, X, W, flags=hlq.HLQ_FLAG_GW_INT8)
+    finally:
+        hlq.hlq_set_option(hlq.HLQ_OPT_FRONT_INTERLEAVE, 1)
+    assert torch.equal(dX0, dX1) and torch.equal(dW0, dW1)
+    assert float(dX1.float().abs().max()) > 0 and float(dW1.float().abs().max()) > 0
+
+
 @pytest.mark.parametrize("N,d_in,d_out,B,r,flags", [
     (4096, 4096, 2048, 16, 8, 0),                                   # both products on 256-tiles, whole steps
     (4096 - 64, 4096 - 104, 2048, 32, 16, 0),                       # tiles that hang over the edges
