@@ -97,7 +97,7 @@ def test_front_interleave_same_bits(B, r, N, d_out, d_in):
     assert float(dX1.float().abs().max()) > 0 and float(dW1.float().abs().max()) > 0
 
 
-@pytest.mark.parametrize("B,r,N,d_out,d_in", [(16, 8, 2048, 8192, 4104), (32, 8, 2048 + 32, 4096, 1032), (16, 4, 4096, 2048, 4104)])
+@pytest.mark.parametrize("B,r,N,d_out,d_in", [(16, 8, 2048, 8192, 4104), (32, 8, 2048 + 64, 4096, 1032), (16, 4, 4096, 2048, 4104)])
 def test_front_interleave_integer_gw_same_bits(B, r, N, d_out, d_in):
     # integer g_w list: the row quantiser beside the passes that take the maxima, or in the launch before them
     w = wl.scaled(wl.WORKLOADS["c4"], N=N, d_in=d_in, d_out=d_out, B=B, r=r)
