@@ -222,7 +222,10 @@ __global__ __launch_bounds__(256) void k_front_q1(FrontHlaQ jg, FrontHlaQ jx, Fr
 template <typename Tin, int B, int BASIS, bool PACKED>
 __global__ __launch_bounds__(256) void k_front_q2(FrontHlaQ jg, FrontHlaQ jx, FrontColsQ jq)
 {
-    int b = blockIdx.x;
+    // backwards through the jobs and through each of them (reverse_same_xcd): what the passes that took the maxima
+    // read last is what the last-level cache still holds
+    const int64_t bytes = (jg.T ? jg.N * jg.D : 0) + (jx.T ? jx.N * jx.D : 0) + (jq.W ? static_cast<int64_t>(jq.O) * jq.I : 0);
+    int b = reverse_same_xcd(blockIdx.x, gridDim.x, bytes * static_cast<int64_t>(sizeof(Tin)));
     if (b < jg.gx * jg.gy) {
         hla_quantize_body<Tin, B, BASIS>(static_cast<const Tin *>(jg.T), jg.N, jg.D, jg.r, jg.amax, jg.k0, jg.k1, jg.TqT,
                                          jg.sT, nullptr, b % jg.gx, b / jg.gx);

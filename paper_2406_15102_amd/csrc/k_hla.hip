@@ -83,7 +83,10 @@ __global__ __launch_bounds__(256) void k_hla_quantize(const Tin *__restrict__ T,
                                                       uint32_t k1, int8_t *__restrict__ TqT, float *__restrict__ sT,
                                                       float *__restrict__ coeffT)
 {
-    hla_quantize_body<Tin, B, BASIS, MANT, P4>(T, N, D, r, amax_bits, k0, k1, TqT, sT, coeffT, blockIdx.x, blockIdx.y);
+    // backwards (reverse_same_xcd): what the pass that took the maxima read last is what the last-level cache still holds
+    const int lin = reverse_same_xcd(blockIdx.x + blockIdx.y * gridDim.x, gridDim.x * gridDim.y,
+                                     N * D * static_cast<int64_t>(sizeof(Tin)));
+    hla_quantize_body<Tin, B, BASIS, MANT, P4>(T, N, D, r, amax_bits, k0, k1, TqT, sT, coeffT, lin % gridDim.x, lin / gridDim.x);
 }
 
 // 4-bit codes two to a byte (code 2b low nibble, code 2b+1 high nibble, two's complement) -> one int8
@@ -184,8 +187,10 @@ __global__ __launch_bounds__(256) void k_hla_quantize_conv(const Tin *__restrict
                                                            uint32_t k1, int8_t *__restrict__ TqT, float *__restrict__ sT,
                                                            float *__restrict__ coeffT)
 {
-    hla_quantize_body_src<B, BASIS, MANT>(ConvRows<Tin>{X, g}, g.N, D, r, amax_bits, k0, k1, TqT, sT, coeffT, blockIdx.x,
-                                          blockIdx.y);
+    const int lin = reverse_same_xcd(blockIdx.x + blockIdx.y * gridDim.x, gridDim.x * gridDim.y,   // backwards, as above
+                                     g.N * D * static_cast<int64_t>(sizeof(Tin)));
+    hla_quantize_body_src<B, BASIS, MANT>(ConvRows<Tin>{X, g}, g.N, D, r, amax_bits, k0, k1, TqT, sT, coeffT, lin % gridDim.x,
+                                          lin / gridDim.x);
 }
 
 bool hla_conv_ok(const ConvShape &g, int B) { return g.C % (128 / B) == 0; }

@@ -41,7 +41,10 @@ __global__ __launch_bounds__(256) void k_cols_quantize(const Tin *__restrict__ W
                                                        float qmax, int8_t *__restrict__ WqT, float *__restrict__ sW,
                                                        float *__restrict__ coeffT)
 {
-    cols_quantize_body<Tin, B, PACKED, MANT>(W, O, I, amax_bits, k0, k1, qmax, WqT, sW, coeffT, blockIdx.x, blockIdx.y);
+    // backwards (reverse_same_xcd): what pass 1 read last is what the last-level cache still holds
+    const int lin = reverse_same_xcd(blockIdx.x + blockIdx.y * gridDim.x, gridDim.x * gridDim.y,
+                                     static_cast<int64_t>(O) * I * static_cast<int64_t>(sizeof(Tin)));
+    cols_quantize_body<Tin, B, PACKED, MANT>(W, O, I, amax_bits, k0, k1, qmax, WqT, sW, coeffT, lin % gridDim.x, lin / gridDim.x);
 }
 
 size_t quant_cols_ws_bytes(int64_t /*O*/, int64_t I)
