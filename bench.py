@@ -258,6 +258,12 @@ def main():
             ach, peak, unit = amount / us / 1e6, PEAK_BF16_TFLOPS, "TFLOP/s"
         kernels[name] = {"us": round(us, 2), "us_alone": round(alone, 2), "bound": kind, "achieved": round(ach, 1),
                          "peak": peak, "unit": unit, "frac": round(ach / peak, 4)}
+        if name == "quantize_w":
+            # the column quantiser needs the maxima over all of d_out before it can round: W is read twice
+            # (the FETCH_SIZE counter shows both reads); `frac` above prices the one-pass bytes, this the bytes moved
+            moved = O * I * (2 * e + cbytes) + 8 * I
+            kernels[name]["moved_bytes"] = int(moved)
+            kernels[name]["frac_of_moved_bytes"] = round(moved / us / 1e3 / PEAK_HBM_GBS, 4)
 
     # ---- the method's options, whole path (extra figures; `value` stays the default path) ----
     modes = {}
